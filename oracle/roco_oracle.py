@@ -1,0 +1,291 @@
+"""Plain float64 NumPy oracle for RoCo (arxiv 2402.06262).  TEST INFRASTRUCTURE ONLY.
+
+This file is the slow, obviously-correct statement of what the HIP library must
+compute.  It is used by the tests, the smoke check and the CPU-baseline leg of
+the benchmark, and by nothing in the product path.  It shares no code with the
+HIP path and imports nothing from it.
+
+RoCo is a heuristic applied step by step, not a shortcut to a closed-form
+result, so the oracle is the algorithm itself, in the paper's order and
+notation, on one *unit* (one attention head of one sequence of one layer; the
+paper's Fig. 1 caption: every head evicts at its own positions):
+
+* scaled dot-product attention per head, causal                 (section 2.1, eq. 1)
+* a fixed buffer of at most B tokens per head, evict when full  (section 3,
+  "Key-Value Constrained Inference"; section 4, first paragraph)
+* importance = mean attention score, MAS = Acc / Count          (section 4.3, "Results")
+* eviction scope from the standard deviation
+      Std(x) = sqrt(Acc2(x)/Count(x) - (Acc(x)/Count(x))^2)
+  of the attention probabilities a token has received: the tokens with the
+  largest Std are kept out of the scope, and the token with the lowest MAS
+  inside the scope is removed                                    (section 4.3, Std paragraph)
+* Acc, Acc2 (the paper's Acc^square) and Count are three B-sized arrays per
+  head                                                           (same paragraph; section 5.3 "Overhead")
+* prefill eviction frees many tokens in one eviction step        (section 5.3 "Overhead", block-wise
+  evict-and-encode; appendix B)
+
+Readings taken where the paper is silent (each is listed in the design doc):
+
+* `scope` = s = the number of tokens *inside* the eviction scope, i.e. the s
+  occupied slots of smallest variance; the paper's r (number of protected
+  top-Std tokens) is n - s.
+* Ranking uses the population variance max(0, Acc2/Count - MAS^2); the square
+  root is monotone and is not taken.
+* One eviction step that frees E > 1 tokens is E token-wise RoCo evictions
+  with the statistics frozen.  `select_evictions_literal` is that loop;
+  `select_evictions` is its closed form (the E lowest-MAS tokens among the
+  s + E - 1 lowest-variance tokens); the tests check they agree.
+* A token's own query counts among the queries that attended it, so the key at
+  position j of an L-token prompt has Count = L - j.
+* Evict first, then append: the victim is chosen from the statistics of the
+  previous steps, the new key/value overwrite its slot, and attention runs over
+  at most B entries.
+* Ties (equal variance at the scope boundary, equal MAS) go to the lowest slot
+  index; before compaction slot index equals position.
+* After prefill compaction the retained tokens are stored in ascending position.
+* An optional recency bias adds `recency_bias` to the scaled logit when
+  0 <= qpos - kpos < recency_window (workload 5 only; not from the paper).
+
+PARITY PINS (tests/test_oracle_*.py): softmax rows sum to one; the cache never
+exceeds B; B >= length reproduces dense causal attention written
+independently; incremental statistics equal a brute-force recount from the
+logged attention rows; two closed forms (uniform attention -> harmonic numbers;
+one-dimensional log-weights -> exact rationals) including a hand-worked 6-token
+example; closed-form selection equals the literal loop; slot-permutation
+invariance of a decode step.
+PARITY UNPINNED by the paper itself: the readings listed above (the paper prints
+no numeric example of RoCo); they are pinned only by internal consistency.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List, Optional, Tuple
+
+import numpy as np
+
+F64 = np.float64
+
+
+# ---------------------------------------------------------------------------
+# attention (section 2.1, eq. 1) with the causal mask (section 2.1, "Key-Value Cache")
+# ---------------------------------------------------------------------------
+
+def _recency(qpos: np.ndarray, kpos: np.ndarray, window: int, bias: float) -> np.ndarray:
+    """bias * 1[0 <= qpos - kpos < window], broadcast qpos[:,None] against kpos[None,:]."""
+    if window <= 0 or bias == 0.0:
+        return np.zeros((qpos.shape[0], kpos.shape[0]), dtype=F64)
+    diff = qpos[:, None] - kpos[None, :]
+    return np.where((diff >= 0) & (diff < window), F64(bias), F64(0.0))
+
+
+def causal_probability_rows(Q, K, length: int, scale: float, recency_window: int = 0,
+                            recency_bias: float = 0.0, row_block: int = 512):
+    """Yield (i0, P) with P[i - i0, j] = softmax_j(scale q_i.k_j + bias), j <= i < length.
+
+    Entries with j > i are exactly zero.  Evaluated a block of query rows at a
+    time only to bound memory; the values are those of the definition.
+    """
+    Q = np.asarray(Q, dtype=F64)[:length]
+    K = np.asarray(K, dtype=F64)[:length]
+    kpos = np.arange(length)
+    for i0 in range(0, length, row_block):
+        i1 = min(length, i0 + row_block)
+        qpos = np.arange(i0, i1)
+        S = (Q[i0:i1] @ K[:i1].T) * F64(scale)
+        S = S + _recency(qpos, kpos[:i1], recency_window, recency_bias)
+        visible = kpos[None, :i1] <= qpos[:, None]
+        S = np.where(visible, S, -np.inf)
+        S = S - S.max(axis=1, keepdims=True)
+        P = np.exp(S)
+        P = P / P.sum(axis=1, keepdims=True)
+        yield i0, P
+
+
+@dataclass
+class PrefillStats:
+    acc: np.ndarray  # [length]  sum over queries i >= j of P[i, j]
+    acc2: np.ndarray  # [length] sum over queries i >= j of P[i, j]^2
+    count: np.ndarray  # [length] number of queries that attended key j = length - j
+    out: Optional[np.ndarray]  # [length, d] attention output, if requested
+
+
+def prefill_statistics(Q, K, V, length: int, scale: float, recency_window: int = 0,
+                       recency_bias: float = 0.0, want_out: bool = False,
+                       row_block: int = 512) -> PrefillStats:
+    """Column statistics of the causal attention matrix (section 4.3: Acc, Acc^square, Count)."""
+    acc = np.zeros(length, dtype=F64)
+    acc2 = np.zeros(length, dtype=F64)
+    count = np.zeros(length, dtype=F64)
+    Vd = np.asarray(V, dtype=F64)[:length]
+    out = np.zeros((length, Vd.shape[1]), dtype=F64) if want_out else None
+    for i0, P in causal_probability_rows(Q, K, length, scale, recency_window,
+                                         recency_bias, row_block):
+        i1 = i0 + P.shape[0]
+        acc[:i1] += P.sum(axis=0)
+        acc2[:i1] += (P * P).sum(axis=0)
+        count[:i1] += (np.arange(i1)[None, :] <= np.arange(i0, i1)[:, None]).sum(axis=0)
+        if want_out:
+            out[i0:i1] = P @ Vd[:i1]
+    return PrefillStats(acc, acc2, count, out)
+
+
+# ---------------------------------------------------------------------------
+# importance and robustness measures (section 4.3)
+# ---------------------------------------------------------------------------
+
+def mean_attention_score(acc, count):
+    """MAS = Acc / Count."""
+    return np.asarray(acc, dtype=F64) / np.asarray(count, dtype=F64)
+
+
+def attention_variance(acc, acc2, count):
+    """Std(x)^2 = Acc2/Count - (Acc/Count)^2, clamped at zero."""
+    acc, acc2, count = (np.asarray(a, dtype=F64) for a in (acc, acc2, count))
+    mas = acc / count
+    return np.maximum(F64(0.0), acc2 / count - mas * mas)
+
+
+def k_smallest(values: np.ndarray, k: int) -> np.ndarray:
+    """Indices of the k smallest values; equal values are taken in index order."""
+    order = np.argsort(np.asarray(values, dtype=F64), kind="stable")
+    return np.sort(order[:k])
+
+
+def select_victim(mas: np.ndarray, var: np.ndarray, scope: int) -> int:
+    """One RoCo eviction: scope = the `scope` lowest-variance tokens, victim = lowest MAS in it."""
+    inside = k_smallest(var, scope)
+    return int(inside[np.argmin(mas[inside])])  # argmin returns the first (lowest index) minimum
+
+
+def select_evictions_literal(mas: np.ndarray, var: np.ndarray, scope: int, n_evict: int) -> np.ndarray:
+    """E token-wise evictions with frozen statistics, one at a time (the literal reading)."""
+    alive = np.ones(mas.shape[0], dtype=bool)
+    victims: List[int] = []
+    for _ in range(n_evict):
+        idx = np.flatnonzero(alive)
+        v = idx[select_victim(mas[idx], var[idx], min(scope, idx.shape[0]))]
+        victims.append(int(v))
+        alive[v] = False
+    return np.sort(np.array(victims, dtype=np.int64))
+
+
+def select_evictions(mas: np.ndarray, var: np.ndarray, scope: int, n_evict: int) -> np.ndarray:
+    """Closed form of the loop above: the E lowest-MAS among the s+E-1 lowest-variance tokens."""
+    if n_evict <= 0:
+        return np.zeros(0, dtype=np.int64)
+    eligible = k_smallest(var, min(mas.shape[0], scope + n_evict - 1))
+    return np.sort(eligible[k_smallest(mas[eligible], n_evict)])
+
+
+# ---------------------------------------------------------------------------
+# the two calls of the boundary
+# ---------------------------------------------------------------------------
+
+@dataclass
+class CacheState:
+    """Budgeted per-head cache: at most `budget` slots (section 3: n <= B at every step)."""
+
+    K: np.ndarray  # [budget, d] float64
+    V: np.ndarray  # [budget, d]
+    acc: np.ndarray  # [budget]
+    acc2: np.ndarray  # [budget]
+    count: np.ndarray  # [budget]
+    pos: np.ndarray  # [budget] int64 original position, -1 for an empty slot
+    n_used: int
+
+    @property
+    def budget(self) -> int:
+        return self.K.shape[0]
+
+    def copy(self) -> "CacheState":
+        return CacheState(self.K.copy(), self.V.copy(), self.acc.copy(), self.acc2.copy(),
+                          self.count.copy(), self.pos.copy(), self.n_used)
+
+
+@dataclass
+class PrefillResult:
+    cache: CacheState
+    out: Optional[np.ndarray]  # [length, d] or None
+    full: PrefillStats  # statistics of all prompt tokens before eviction
+    evicted: np.ndarray  # sorted positions removed
+    retained: np.ndarray  # sorted positions kept
+
+
+def prefill_compress(Q, K, V, length: int, budget: int, scope: int, scale: float,
+                     recency_window: int = 0, recency_bias: float = 0.0,
+                     want_out: bool = False, row_block: int = 512,
+                     force_retained: Optional[np.ndarray] = None) -> PrefillResult:
+    """Encode a prompt and compress its cache to `budget` tokens in one eviction step.
+
+    `force_retained` replaces the oracle's own retained set (used by the parity
+    harness after a declared tie, never by the pins).
+    """
+    full = prefill_statistics(Q, K, V, length, scale, recency_window, recency_bias,
+                              want_out, row_block)
+    n_evict = max(0, length - budget)
+    mas = mean_attention_score(full.acc, full.count)
+    var = attention_variance(full.acc, full.acc2, full.count)
+    evicted = select_evictions(mas, var, scope, n_evict)
+    keep = np.ones(length, dtype=bool)
+    keep[evicted] = False
+    retained = np.flatnonzero(keep)
+    if force_retained is not None:
+        retained = np.sort(np.asarray(force_retained, dtype=np.int64))
+        keep[:] = False
+        keep[retained] = True
+        evicted = np.flatnonzero(~keep)
+    n = retained.shape[0]
+    assert n == min(length, budget)
+    d = np.asarray(K).shape[1]
+    cache = CacheState(np.zeros((budget, d), F64), np.zeros((budget, d), F64),
+                       np.zeros(budget, F64), np.zeros(budget, F64), np.zeros(budget, F64),
+                       np.full(budget, -1, dtype=np.int64), n)
+    cache.K[:n] = np.asarray(K, dtype=F64)[retained]
+    cache.V[:n] = np.asarray(V, dtype=F64)[retained]
+    cache.acc[:n] = full.acc[retained]
+    cache.acc2[:n] = full.acc2[retained]
+    cache.count[:n] = full.count[retained]
+    cache.pos[:n] = retained
+    return PrefillResult(cache, full.out, full, evicted, retained)
+
+
+@dataclass
+class DecodeResult:
+    out: np.ndarray  # [d]
+    probs: np.ndarray  # [n_used] attention probabilities over the occupied slots
+    evicted_slot: int  # -1 when nothing was evicted
+    evicted_pos: int
+    written_slot: int
+    mas: Optional[np.ndarray]  # statistics the decision was taken on (None if no eviction)
+    var: Optional[np.ndarray]
+
+
+def decode_step(state: CacheState, q, k_new, v_new, qpos: int, scope: int, scale: float,
+                recency_window: int = 0, recency_bias: float = 0.0,
+                force_victim: Optional[int] = None) -> DecodeResult:
+    """One auto-regressive step on a budgeted cache, in place: evict, append, attend, update."""
+    B = state.budget
+    mas = var = None
+    if state.n_used == B:
+        mas = mean_attention_score(state.acc, state.count)
+        var = attention_variance(state.acc, state.acc2, state.count)
+        slot = select_victim(mas, var, scope) if force_victim is None else int(force_victim)
+        evicted_slot, evicted_pos = slot, int(state.pos[slot])
+    else:
+        slot = state.n_used
+        state.n_used += 1
+        evicted_slot, evicted_pos = -1, -1
+    state.K[slot] = np.asarray(k_new, dtype=F64)
+    state.V[slot] = np.asarray(v_new, dtype=F64)
+    state.pos[slot] = qpos
+    state.acc[slot] = state.acc2[slot] = state.count[slot] = 0.0
+    n = state.n_used
+    z = (state.K[:n] @ np.asarray(q, dtype=F64)) * F64(scale)
+    z = z + _recency(np.array([qpos]), state.pos[:n], recency_window, recency_bias)[0]
+    p = np.exp(z - z.max())
+    p = p / p.sum()
+    out = p @ state.V[:n]
+    state.acc[:n] += p
+    state.acc2[:n] += p * p
+    state.count[:n] += 1.0
+    return DecodeResult(out, p, evicted_slot, evicted_pos, slot, mas, var)

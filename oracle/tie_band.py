@@ -1,0 +1,76 @@
+"""Tie-band check for eviction decisions.  TEST INFRASTRUCTURE ONLY.
+
+The HIP path keeps Acc, Acc2 and Count in fp32 and the oracle keeps them in
+float64, so the two may order two tokens differently when the oracle's own gap
+between them is below what fp32 statistics can resolve.  The matching rule is:
+index sets must be identical unless the oracle's own score gap lies inside the
+tolerance band
+
+    MAS:       |gap| <= rel * MAS
+    variance:  |gap| <= rel * (Acc2/Count + MAS^2)
+
+(the variance band is stated on the two terms that cancel in
+Acc2/Count - MAS^2, section 4.3 of the paper, because the difference itself can
+be arbitrarily smaller than either).
+
+`admissible_eviction` answers, for an eviction set G that differs from the
+oracle's: is there an assignment of the in-band tokens to the two sides of the
+variance threshold, and an ordering of in-band MAS values, under which RoCo's
+rule evicts exactly G?  If so the case is a *declared tie*; the harness counts
+it and lets the oracle adopt G so later steps stay comparable.  If not, the HIP
+path is wrong.
+"""
+from __future__ import annotations
+
+from typing import Iterable, Tuple
+
+import numpy as np
+
+F64 = np.float64
+
+
+def bands(acc, acc2, count, rel: float = 1e-3) -> Tuple[np.ndarray, np.ndarray]:
+    """(eps_mas, eps_var) per token."""
+    acc, acc2, count = (np.asarray(a, dtype=F64) for a in (acc, acc2, count))
+    mas = acc / count
+    return rel * np.abs(mas), rel * (acc2 / count + mas * mas)
+
+
+def admissible_eviction(mas, var, eps_mas, eps_var, scope: int, n_evict: int,
+                        evicted: Iterable[int]) -> Tuple[bool, str]:
+    """Can RoCo's rule, with in-band comparisons decided either way, evict exactly `evicted`?"""
+    mas, var = np.asarray(mas, dtype=F64), np.asarray(var, dtype=F64)
+    n = mas.shape[0]
+    G = np.array(sorted(int(g) for g in evicted), dtype=np.int64)
+    if G.shape[0] != n_evict or np.unique(G).shape[0] != n_evict:
+        return False, "wrong number of evicted tokens"
+    if n_evict == 0:
+        return True, "nothing to evict"
+    if G.min() < 0 or G.max() >= n:
+        return False, "evicted index out of range"
+    m = min(n, scope + n_evict - 1)
+    order = np.argsort(var, kind="stable")
+    t = order[m - 1]
+    if m == n:
+        border = np.zeros(n, dtype=bool)
+        inside = np.ones(n, dtype=bool)
+    else:
+        border = np.abs(var - var[t]) <= eps_var + eps_var[t]
+        inside = (var < var[t]) & ~border  # in the scope whatever the in-band order is
+    outside = ~inside & ~border
+    in_G = np.zeros(n, dtype=bool)
+    in_G[G] = True
+    if np.any(outside & in_G):
+        return False, "an evicted token lies clearly outside the variance scope"
+    # every scope member that survives must not have a clearly lower MAS than an evicted one
+    thr = np.max(mas[G] - eps_mas[G])
+    survives_ok = mas + eps_mas >= thr
+    if np.any(inside & ~in_G & ~survives_ok):
+        return False, "a token clearly inside the scope with clearly lower MAS was kept"
+    fixed = int(np.count_nonzero(inside | (border & in_G)))
+    if fixed > m:
+        return False, "more in-band tokens evicted than the scope can hold"
+    fill = int(np.count_nonzero(border & ~in_G & survives_ok))
+    if fixed + fill < m:
+        return False, "scope cannot be completed without a token of clearly lower MAS"
+    return True, "declared tie"

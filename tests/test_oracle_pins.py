@@ -1,0 +1,366 @@
+"""Pins for the CPU oracle: what the paper and the mathematics fix, independent of the oracle's code.
+
+Every expected value here comes from a closed form, an exact rational computation, a brute-force
+recount, or a textbook routine written separately -- never from the oracle itself.
+"""
+import itertools
+import math
+import os
+from fractions import Fraction as Fr
+
+import numpy as np
+import pytest
+
+from oracle import roco_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "six_token_example.txt")
+
+
+def load_golden():
+    rec = {}
+    with open(GOLDEN) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, *vals = line.split()
+            rec[key] = [Fr(v) for v in vals]
+    return rec
+
+
+def dense_causal_attention(Q, K, V, scale):
+    """Textbook dense causal attention (section 2.1 eq. 1), written independently of the oracle."""
+    L = Q.shape[0]
+    S = np.einsum("id,jd->ij", Q, K) * scale
+    S[np.triu_indices(L, 1)] = -np.inf
+    E = np.exp(S - S.max(1)[:, None])
+    P = E / E.sum(1)[:, None]
+    return P, P @ V
+
+
+def rand_unit(rng, T, d):
+    return rng.standard_normal((T, d)), rng.standard_normal((T, d)), rng.standard_normal((T, d))
+
+
+# ---------------------------------------------------------------------------- invariants
+
+def test_rows_sum_to_one_and_are_causal():
+    rng = np.random.default_rng(1)
+    Q, K, _ = rand_unit(rng, 70, 8)
+    seen = 0
+    for i0, P in orc.causal_probability_rows(Q, K, 70, 0.35, row_block=16):
+        assert np.allclose(P.sum(1), 1.0, atol=1e-12)
+        for r in range(P.shape[0]):
+            assert np.all(P[r, i0 + r + 1:] == 0.0)
+            assert np.all(P[r, : i0 + r + 1] > 0.0)
+        seen += P.shape[0]
+    assert seen == 70
+
+
+def test_row_block_size_does_not_change_values():
+    rng = np.random.default_rng(2)
+    Q, K, V = rand_unit(rng, 45, 4)
+    a = orc.prefill_statistics(Q, K, V, 45, 0.5, want_out=True, row_block=7)
+    b = orc.prefill_statistics(Q, K, V, 45, 0.5, want_out=True, row_block=512)
+    for x, y in ((a.acc, b.acc), (a.acc2, b.acc2), (a.count, b.count), (a.out, b.out)):
+        assert np.allclose(x, y, rtol=1e-13, atol=1e-15)
+
+
+def test_prefill_matches_independent_dense_attention():
+    rng = np.random.default_rng(3)
+    L, d = 37, 6
+    Q, K, V = rand_unit(rng, L, d)
+    P, O = dense_causal_attention(Q, K, V, 1 / math.sqrt(d))
+    st = orc.prefill_statistics(Q, K, V, L, 1 / math.sqrt(d), want_out=True)
+    assert np.allclose(st.out, O, rtol=1e-12, atol=1e-14)
+    assert np.allclose(st.acc, P.sum(0), rtol=1e-12)
+    assert np.allclose(st.acc2, (P ** 2).sum(0), rtol=1e-12)
+    assert np.array_equal(st.count, L - np.arange(L))  # a token's own query counts
+
+
+def test_length_shorter_than_arrays_ignores_the_tail():
+    rng = np.random.default_rng(4)
+    Q, K, V = rand_unit(rng, 30, 4)
+    a = orc.prefill_statistics(Q, K, V, 19, 0.5, want_out=True)
+    b = orc.prefill_statistics(Q[:19], K[:19], V[:19], 19, 0.5, want_out=True)
+    assert np.array_equal(a.acc, b.acc) and np.array_equal(a.out, b.out)
+
+
+def test_budget_at_least_length_reproduces_full_attention_and_never_evicts():
+    rng = np.random.default_rng(5)
+    L, steps, d = 20, 9, 5
+    T = L + steps
+    Q, K, V = rand_unit(rng, T, d)
+    scale = 1 / math.sqrt(d)
+    P, O = dense_causal_attention(Q, K, V, scale)
+    res = orc.prefill_compress(Q[:L], K[:L], V[:L], L, T, 3, scale, want_out=True)
+    assert res.evicted.size == 0 and res.cache.n_used == L
+    assert np.allclose(res.out, O[:L], rtol=1e-12, atol=1e-14)
+    for t in range(L, T):
+        r = orc.decode_step(res.cache, Q[t], K[t], V[t], t, 3, scale)
+        assert r.evicted_slot == -1 and r.evicted_pos == -1
+        assert np.allclose(r.out, O[t], rtol=1e-12, atol=1e-14)
+        assert res.cache.n_used == t + 1
+    n = res.cache.n_used
+    assert np.array_equal(res.cache.pos[:n], np.arange(T))
+    assert np.allclose(res.cache.acc[:n], P.sum(0), rtol=1e-12)
+    assert np.allclose(res.cache.acc2[:n], (P ** 2).sum(0), rtol=1e-12)
+    assert np.array_equal(res.cache.count[:n], T - np.arange(T))
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_cache_never_exceeds_budget_and_incremental_stats_equal_brute_force(seed):
+    """Log every attention row with the positions it covered; recount Acc, Acc2, Count per survivor."""
+    rng = np.random.default_rng(100 + seed)
+    L, steps, d, B, s = 24, 30, 4, 10, 3
+    Q, K, V = rand_unit(rng, L + steps, d)
+    scale = 0.7
+    log = []  # (query position, {key position: probability})
+    for i0, P in orc.causal_probability_rows(Q, K, L, scale, row_block=5):
+        for r in range(P.shape[0]):
+            i = i0 + r
+            log.append((i, {j: P[r, j] for j in range(i + 1)}))
+    res = orc.prefill_compress(Q[:L], K[:L], V[:L], L, B, s, scale)
+    cache = res.cache
+    assert cache.n_used == B and len(res.evicted) == L - B
+    assert len(set(res.evicted) | set(res.retained)) == L
+    for t in range(L, L + steps):
+        before = cache.pos.copy()
+        r = orc.decode_step(cache, Q[t], K[t], V[t], t, s, scale)
+        assert cache.n_used <= B
+        assert r.evicted_slot >= 0 and r.evicted_pos == before[r.evicted_slot]
+        assert cache.pos[r.evicted_slot] == t
+        assert abs(r.probs.sum() - 1.0) < 1e-12
+        log.append((t, {int(cache.pos[j]): r.probs[j] for j in range(cache.n_used)}))
+        # attention output equals softmax over exactly the cached keys, written independently
+        z = np.array([scale * np.dot(Q[t], K[int(p)]) for p in cache.pos[:cache.n_used]])
+        w = np.exp(z - z.max())
+        w /= w.sum()
+        assert np.allclose(r.out, sum(w[j] * V[int(cache.pos[j])] for j in range(cache.n_used)),
+                           rtol=1e-12, atol=1e-14)
+    assert len(set(cache.pos.tolist())) == B
+    for j in range(B):
+        p = int(cache.pos[j])
+        rows = [row[p] for (i, row) in log if i >= p and p in row]
+        assert cache.count[j] == len(rows)
+        assert math.isclose(cache.acc[j], math.fsum(rows), rel_tol=1e-12)
+        assert math.isclose(cache.acc2[j], math.fsum(x * x for x in rows), rel_tol=1e-12)
+        assert np.array_equal(cache.K[j], K[p]) and np.array_equal(cache.V[j], V[p])
+
+
+# ---------------------------------------------------------------------------- closed forms
+
+@pytest.mark.parametrize("L", [1, 2, 17, 300])
+def test_uniform_attention_gives_harmonic_numbers(L):
+    """Q = 0 makes every causal row uniform: P[i,j] = 1/(i+1)."""
+    rng = np.random.default_rng(L)
+    K, V = rng.standard_normal((L, 3)), rng.standard_normal((L, 3))
+    st = orc.prefill_statistics(np.zeros((L, 3)), K, V, L, 0.9, want_out=True)
+    acc = [float(sum(Fr(1, i + 1) for i in range(j, L))) for j in range(L)]
+    acc2 = [float(sum(Fr(1, (i + 1) ** 2) for i in range(j, L))) for j in range(L)]
+    assert np.allclose(st.acc, acc, rtol=1e-12)
+    assert np.allclose(st.acc2, acc2, rtol=1e-12)
+    assert np.array_equal(st.count, [L - j for j in range(L)])
+    running_mean = np.cumsum(V, 0) / np.arange(1, L + 1)[:, None]
+    assert np.allclose(st.out, running_mean, rtol=1e-11, atol=1e-13)
+
+
+def rational_case(w, scale):
+    """d = 1, q_i = 1, k_j = ln(w_j)/scale  =>  P[i,j] = w_j / sum_{j'<=i} w_j' exactly."""
+    L = len(w)
+    Q = np.ones((L, 1))
+    K = (np.log(np.array(w, dtype=np.float64)) / scale)[:, None]
+    P = [[Fr(w[j], sum(w[: i + 1])) if j <= i else Fr(0) for j in range(L)] for i in range(L)]
+    return Q, K, P
+
+
+@pytest.mark.parametrize("scale", [1.0, 0.125, 3.0])
+def test_log_weight_keys_give_exact_rationals(scale):
+    w = [3, 1, 4, 1, 5, 9, 2, 6, 5, 3, 5]
+    L = len(w)
+    Q, K, P = rational_case(w, scale)
+    V = np.arange(1, L + 1, dtype=np.float64)[:, None] * np.array([[1.0, -2.0]])
+    st = orc.prefill_statistics(Q, K, V, L, scale, want_out=True)
+    for j in range(L):
+        assert math.isclose(st.acc[j], float(sum(P[i][j] for i in range(L))), rel_tol=1e-12)
+        assert math.isclose(st.acc2[j], float(sum(P[i][j] ** 2 for i in range(L))), rel_tol=1e-12)
+    for i in range(L):
+        o = float(sum(P[i][j] * (j + 1) for j in range(L)))
+        assert math.isclose(st.out[i, 0], o, rel_tol=1e-12)
+        assert math.isclose(st.out[i, 1], -2 * o, rel_tol=1e-12)
+
+
+def test_hand_worked_six_token_example():
+    g = load_golden()
+    w = [int(x) for x in g["w"]]
+    L = len(w)
+    Q, K, P = rational_case(w, 1.0)
+    # the fixture is self-consistent with the closed form (checks the hand computation)
+    for i in range(L):
+        assert g[f"row{i}"] == P[i][: i + 1]
+    assert g["acc"] == [sum(P[i][j] for i in range(L)) for j in range(L)]
+    assert g["acc2"] == [sum(P[i][j] ** 2 for i in range(L)) for j in range(L)]
+    assert g["mas"] == [a / c for a, c in zip(g["acc"], g["count"])]
+    assert g["var"] == [a2 / c - m * m for a2, c, m in zip(g["acc2"], g["count"], g["mas"])]
+    # the oracle reproduces it
+    V = np.arange(1, L + 1, dtype=np.float64)[:, None]
+    B, s = int(g["budget"][0]), int(g["scope"][0])
+    res = orc.prefill_compress(Q, K, V, L, B, s, 1.0, want_out=True)
+    f = lambda xs: np.array([float(x) for x in xs])  # noqa: E731
+    assert np.allclose(res.full.acc, f(g["acc"]), rtol=1e-13)
+    assert np.allclose(res.full.acc2, f(g["acc2"]), rtol=1e-13)
+    assert np.array_equal(res.full.count, f(g["count"]))
+    assert np.allclose(orc.mean_attention_score(res.full.acc, res.full.count), f(g["mas"]), rtol=1e-13)
+    assert np.allclose(orc.attention_variance(res.full.acc, res.full.acc2, res.full.count),
+                       f(g["var"]), rtol=1e-9, atol=1e-16)
+    assert res.evicted.tolist() == [int(x) for x in g["evicted"]]
+    assert res.retained.tolist() == [int(x) for x in g["retained"]]
+    assert res.cache.pos.tolist() == [int(x) for x in g["retained"]]
+    var = orc.attention_variance(res.full.acc, res.full.acc2, res.full.count)
+    m = s + (L - B) - 1
+    assert orc.k_smallest(var, m).tolist() == [int(x) for x in g["eligible"]]
+    lit = orc.select_evictions_literal(orc.mean_attention_score(res.full.acc, res.full.count), var, s, L - B)
+    assert lit.tolist() == [int(x) for x in g["evicted"]]
+    # one decode step
+    r = orc.decode_step(res.cache, [1.0], [math.log(float(g["decode_w"][0]))], [7.0], 6, s, 1.0)
+    assert r.evicted_slot == int(g["decode_evicted_slot"][0])
+    assert r.evicted_pos == int(g["decode_evicted_pos"][0])
+    assert np.allclose(r.probs, f(g["decode_probs"]), rtol=1e-13)
+    assert math.isclose(r.out[0], float(g["decode_out"][0]), rel_tol=1e-13)
+    assert res.cache.pos.tolist() == [0, 6, 3]
+    assert np.allclose(res.cache.acc, f(g["decode_acc"]), rtol=1e-13)
+    assert np.allclose(res.cache.acc2, f(g["decode_acc2"]), rtol=1e-13)
+    assert np.array_equal(res.cache.count, f(g["decode_count"]))
+
+
+def test_recency_bias_with_a_huge_bias_becomes_window_attention():
+    """bias = +80 on the last w positions (self included) leaves exp(-80) elsewhere."""
+    rng = np.random.default_rng(7)
+    L, d, w = 26, 4, 5
+    Q, K, V = rand_unit(rng, L, d)
+    st = orc.prefill_statistics(Q, K, V, L, 0.5, recency_window=w, recency_bias=80.0, want_out=True)
+    for i in range(L):
+        lo = max(0, i - w + 1)
+        z = 0.5 * K[lo: i + 1] @ Q[i]
+        p = np.exp(z - z.max())
+        p /= p.sum()
+        assert np.allclose(st.out[i], p @ V[lo: i + 1], rtol=1e-9, atol=1e-12)
+    # decode: positions come from pos[], not from the slot index
+    res = orc.prefill_compress(Q[:20], K[:20], V[:20], 20, 8, 3, 0.5, recency_window=w, recency_bias=80.0)
+    cache = res.cache
+    r = orc.decode_step(cache, Q[20], K[20], V[20], 20, 3, 0.5, recency_window=w, recency_bias=80.0)
+    near = [j for j in range(cache.n_used) if 0 <= 20 - cache.pos[j] < w]
+    assert math.isclose(sum(r.probs[j] for j in near), 1.0, rel_tol=1e-12)
+    assert 20 in cache.pos.tolist()
+
+
+def test_recency_bias_value_enters_the_scaled_logit_additively():
+    """Two keys, equal dot products: odds between them are exactly exp(bias)."""
+    Q = np.array([[1.0, 0.0]] * 4)
+    K = np.array([[0.3, 1.0]] * 4)
+    V = np.eye(4)[:, :2]
+    st = list(orc.causal_probability_rows(Q, K, 4, 0.25, recency_window=2, recency_bias=0.5))
+    P = st[0][1]
+    assert math.isclose(P[3, 3] / P[3, 0], math.exp(0.5), rel_tol=1e-12)
+    assert math.isclose(P[3, 2] / P[3, 1], math.exp(0.5), rel_tol=1e-12)
+    assert math.isclose(P[3, 0], P[3, 1], rel_tol=1e-12)
+
+
+# ---------------------------------------------------------------------------- selection
+
+def brute_k_smallest(values, k):
+    return sorted(i for _, i in sorted((v, i) for i, v in enumerate(values))[:k])
+
+
+def test_k_smallest_breaks_ties_by_lowest_index():
+    rng = np.random.default_rng(8)
+    for _ in range(200):
+        n = int(rng.integers(1, 12))
+        vals = rng.integers(0, 4, n).astype(float)  # many ties
+        k = int(rng.integers(1, n + 1))
+        assert orc.k_smallest(vals, k).tolist() == brute_k_smallest(vals.tolist(), k)
+
+
+def test_select_victim_is_scope_then_argmin_with_lowest_index_ties():
+    mas = np.array([0.5, 0.1, 0.3, 0.1, 0.05])
+    var = np.array([0.0, 2.0, 1.0, 1.0, 9.0])
+    assert orc.select_victim(mas, var, 1) == 0  # only the lowest-variance token is in scope
+    assert orc.select_victim(mas, var, 2) == 2  # scope {0,2}: tie in variance goes to index 2 first
+    assert orc.select_victim(mas, var, 3) == 3  # scope {0,2,3}
+    assert orc.select_victim(mas, var, 4) == 1  # scope {0,1,2,3}: equal MAS -> lowest index
+    assert orc.select_victim(mas, var, 5) == 4  # everything in scope
+
+
+def test_closed_form_eviction_set_equals_the_literal_token_by_token_loop():
+    rng = np.random.default_rng(9)
+    for trial in range(400):
+        n = int(rng.integers(2, 14))
+        if trial % 2:
+            mas, var = rng.random(n), rng.random(n)
+        else:  # quantised: plenty of ties in both keys
+            mas, var = rng.integers(0, 3, n) / 4.0, rng.integers(0, 3, n) / 4.0
+        E = int(rng.integers(1, n))
+        s = int(rng.integers(1, n - E + 1))
+        assert (orc.select_evictions(mas, var, s, E).tolist()
+                == orc.select_evictions_literal(mas, var, s, E).tolist()), (mas, var, s, E)
+
+
+def test_exhaustive_tiny_selection_against_definition():
+    """n = 4, all value patterns from a 2-level alphabet: victim by explicit sort on (key, index)."""
+    for mas in itertools.product([0.25, 0.75], repeat=4):
+        for var in itertools.product([0.0, 1.0], repeat=4):
+            for s in range(1, 5):
+                scope = brute_k_smallest(var, s)
+                want = min(scope, key=lambda i: (mas[i], i))
+                assert orc.select_victim(np.array(mas), np.array(var), s) == want
+
+
+def test_variance_formula_against_direct_population_variance():
+    rng = np.random.default_rng(10)
+    for _ in range(20):
+        c = int(rng.integers(1, 30))
+        x = rng.random(c)
+        var = orc.attention_variance([x.sum()], [(x * x).sum()], [c])[0]
+        assert math.isclose(var, np.var(x), rel_tol=1e-9, abs_tol=1e-15)  # population, not sample
+        assert math.isclose(orc.mean_attention_score([x.sum()], [c])[0], x.mean(), rel_tol=1e-14)
+    assert orc.attention_variance([0.3], [0.09], [1])[0] == 0.0  # a single observation
+
+
+def test_decode_step_is_invariant_to_slot_order():
+    rng = np.random.default_rng(11)
+    L, d, B, s = 18, 4, 9, 4
+    Q, K, V = rand_unit(rng, L + 1, d)
+    res = orc.prefill_compress(Q[:L], K[:L], V[:L], L, B, s, 0.6)
+    a = res.cache.copy()
+    perm = rng.permutation(B)
+    b = orc.CacheState(a.K[perm].copy(), a.V[perm].copy(), a.acc[perm].copy(), a.acc2[perm].copy(),
+                       a.count[perm].copy(), a.pos[perm].copy(), a.n_used)
+    ra = orc.decode_step(a, Q[L], K[L], V[L], L, s, 0.6)
+    rb = orc.decode_step(b, Q[L], K[L], V[L], L, s, 0.6)
+    assert ra.evicted_pos == rb.evicted_pos and perm[rb.evicted_slot] == ra.evicted_slot
+    assert np.allclose(ra.out, rb.out, rtol=1e-12, atol=1e-14)
+    oa, ob = np.argsort(a.pos), np.argsort(b.pos)
+    assert np.array_equal(a.pos[oa], b.pos[ob])
+    assert np.allclose(a.acc[oa], b.acc[ob], rtol=1e-12)
+    assert np.allclose(a.acc2[oa], b.acc2[ob], rtol=1e-12)
+
+
+def test_statistics_memory_is_three_arrays_of_budget_size():
+    """Section 5.3 'Overhead': L x H x B x 3 extra elements."""
+    rng = np.random.default_rng(12)
+    Q, K, V = rand_unit(rng, 12, 4)
+    c = orc.prefill_compress(Q, K, V, 12, 5, 2, 0.5).cache
+    assert c.acc.shape == c.acc2.shape == c.count.shape == (5,)
+    assert c.K.shape == c.V.shape == (5, 4)
+
+
+def test_heavy_keys_dominate_the_retained_set():
+    """Qualitative (not parity): the +4u keys of the workload generator survive compression."""
+    from inputs import CONFIGS, make_unit
+    cfg = CONFIGS[0]
+    u = make_unit(cfg, 0, 0, 0)
+    L = cfg.prompt_len
+    res = orc.prefill_compress(u.Q[:L], u.K[:L], u.V[:L], L, cfg.budget, cfg.scope, 1 / math.sqrt(cfg.head_dim))
+    heavy = [p for p in u.heavy_positions if p < L]
+    kept = sum(1 for p in heavy if p in set(res.retained.tolist()))
+    assert kept >= 0.8 * len(heavy)

@@ -1,0 +1,135 @@
+/*
+ * roco.h -- C ABI of the MI355X (gfx950) RoCo library.
+ *
+ * RoCo (arxiv 2402.06262) keeps the key/value cache of every attention head
+ * inside a fixed buffer of B tokens (section 3, "Key-Value Constrained
+ * Inference"; section 4, first paragraph).  Per head it maintains three
+ * B-sized arrays -- Acc, the accumulated attention probability a cached token
+ * has received; Acc2, the accumulated squared probability; Count, how many
+ * queries attended it (section 4.3; section 5.3 "Overhead": L x H x B x 3
+ * elements) -- and, when the buffer is full, removes the token with the lowest
+ * mean attention score Acc/Count among the tokens whose attention variance
+ * Acc2/Count - (Acc/Count)^2 is lowest (section 4.3, RoCo = mean attention
+ * score + standard-deviation eviction scope).
+ *
+ * A *unit* is one (layer, sequence, head).  Units are independent (Fig. 1
+ * caption: every head evicts at its own positions); the caller folds
+ * layers x batch x heads into `units`.
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers into memory owned by the caller
+ *     (16-byte aligned, dense row-major in the stated shape).  `params` is a
+ *     HOST pointer.  `hip_stream` is a hipStream_t passed as void* (NULL = the
+ *     null stream).
+ *   - The library allocates nothing, frees nothing and never synchronises:
+ *     kernels are enqueued on `hip_stream` and the call returns.
+ *   - Argument errors are detected on the host before anything is launched
+ *     and are reported by a negative return code; 0 is success.
+ *   - Values held in device memory (`len`, `n_used`, `qpos`) are trusted.
+ */
+#ifndef ROCO_H
+#define ROCO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ROCO_VERSION 1
+
+/* storage type of Q, K, V, q, k_new, v_new, the cache and the attention outputs */
+enum { ROCO_F32 = 0, ROCO_BF16 = 1 };
+
+/* return codes */
+enum {
+  ROCO_OK = 0,
+  ROCO_EINVAL = -1,        /* null / misaligned pointer, budget < 1, scope outside [1, budget], ... */
+  ROCO_EUNSUPPORTED = -2,  /* dtype or head_dim the kernels are not built for                       */
+  ROCO_EWORKSPACE = -3,    /* workspace smaller than the matching *_workspace_bytes() query        */
+  ROCO_EHIP = -4           /* a kernel launch failed (hipGetLastError)                             */
+};
+
+typedef struct roco_params {
+  int32_t units;          /* number of independent (layer, sequence, head) units, >= 1             */
+  int32_t head_dim;       /* d': 64 or 128                                                          */
+  int32_t budget;         /* B >= 1: slots per unit (section 3: n <= B at every step)               */
+  int32_t scope;          /* s in [1, B]: the eviction scope holds the s occupied slots of lowest
+                             attention variance; the paper's r (top-r Std protected) is n - s       */
+  int32_t dtype;          /* ROCO_F32 or ROCO_BF16                                                  */
+  float   scale;          /* softmax scale; <= 0 selects 1/sqrt(head_dim) (section 2.1, eq. 1)      */
+  int32_t recency_window; /* w >= 0; 0 = off.  The scaled logit of (query at position qp, key at
+                             position kp) gets + recency_bias when 0 <= qp - kp < w.  Not part of
+                             the paper; used by the long-context stress workload only.             */
+  float   recency_bias;
+} roco_params;
+
+/* Bytes of scratch the two calls need for these params (0 on invalid params). */
+size_t roco_prefill_workspace_bytes(const roco_params* params, int32_t L_max);
+size_t roco_decode_workspace_bytes(const roco_params* params);
+
+/*
+ * Prefill with eviction in one block (section 5.3 "Overhead": block-wise evict-and-encode with the
+ * whole prompt as the block; section 5.1.5: B = prompt length x compression rate).
+ *
+ * Per unit u with length len[u] (1 <= len[u] <= L_max):
+ *   P[i,j]   = softmax_j(scale q_i.k_j + bias(i,j)),  j <= i < len         (section 2.1 eq. 1, causal)
+ *   Acc[j]   = sum_{i>=j} P[i,j],  Acc2[j] = sum_{i>=j} P[i,j]^2,  Count[j] = len - j   (section 4.3)
+ *   if len > B: E = len - B tokens are evicted in one step: among the s+E-1 tokens of lowest variance,
+ *   the E of lowest mean attention score (equal keys: lowest position first).  This equals E successive
+ *   single evictions by the rule of section 4.3 with the statistics frozen.
+ *   The retained min(len,B) tokens are written to the cache in ascending position.
+ *
+ * Q, K, V   in  [units, L_max, d]   dtype                rows >= len[u] are ignored
+ * len       in  [units]             int32
+ * K_cache, V_cache  out [units, B, d]  dtype             slots >= n_used[u] are left untouched
+ * stats     out [units, 3, B]       fp32  planes Acc, Acc2, Count; unused slots are zeroed
+ * pos       out [units, B]          int32 original position of each slot, -1 for unused slots
+ * n_used    out [units]             int32 = min(len, B)
+ * O         out [units, L_max, d]   dtype attention output of every prompt row, or NULL to skip it
+ */
+int roco_prefill_compress(const roco_params* params,
+                          const void* Q, const void* K, const void* V,
+                          const int32_t* len, int32_t L_max,
+                          void* K_cache, void* V_cache, float* stats, int32_t* pos, int32_t* n_used,
+                          void* O,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * One auto-regressive decode step on the budgeted cache, in place (Fig. 1: one key/value pair is
+ * deleted before the next token's is appended; section 4: evict when the buffer is full).
+ *
+ * Per unit u:
+ *   if n_used == B: scope = the s slots of lowest variance max(0, Acc2/Count - (Acc/Count)^2); victim =
+ *   the slot of lowest Acc/Count inside it (equal keys: lowest slot first); slot = victim.
+ *   else slot = n_used, n_used += 1, nothing evicted.
+ *   K_cache[slot] = k_new, V_cache[slot] = v_new, pos[slot] = qpos, the slot's three statistics = 0.
+ *   p = softmax_j(scale q.K_cache[j] + bias(qpos, pos[j])) over the occupied slots; out = sum_j p_j V_cache[j]
+ *   Acc += p, Acc2 += p^2, Count += 1 on the occupied slots                  (section 4.3)
+ *
+ * q, k_new, v_new  in      [units, d]     dtype
+ * qpos             in      [units]        int32 position of the new token
+ * K_cache, V_cache in/out  [units, B, d]  dtype
+ * stats            in/out  [units, 3, B]  fp32
+ * pos              in/out  [units, B]     int32
+ * n_used           in/out  [units]        int32
+ * out              out     [units, d]     dtype
+ * evicted_slot, evicted_pos  out [units]  int32; -1 when the unit evicted nothing (either may be NULL)
+ */
+int roco_decode_step(const roco_params* params,
+                     const void* q, const void* k_new, const void* v_new, const int32_t* qpos,
+                     void* K_cache, void* V_cache, float* stats, int32_t* pos, int32_t* n_used,
+                     void* out, int32_t* evicted_slot, int32_t* evicted_pos,
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Static description of a return code. */
+const char* roco_strerror(int code);
+
+/* ROCO_VERSION the library was built from. */
+int roco_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ROCO_H */

@@ -1,0 +1,21 @@
+"""MI355X-native RoCo (arxiv 2402.06262) hot path: a C-ABI HIP library plus a thin ctypes binding.
+
+Every step of the path runs in the HIP kernels of `libroco.so`; this package only marshals arguments.
+There is no CPU fallback: if the library is not built, loading it raises.
+"""
+from .binding import (  # noqa: F401
+    ROCO_BF16,
+    ROCO_F32,
+    RocoCache,
+    RocoError,
+    RocoParams,
+    alloc_cache,
+    decode_workspace_bytes,
+    library_path,
+    load_library,
+    prefill_workspace_bytes,
+    roco_decode_step,
+    roco_prefill_compress,
+    roco_strerror,
+    roco_version,
+)

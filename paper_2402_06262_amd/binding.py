@@ -1,0 +1,164 @@
+"""ctypes binding of libroco.so: same names as include/roco.h, argument marshalling only.
+
+PyTorch supplies device memory (`tensor.data_ptr()`) and the HIP stream
+(`torch.cuda.current_stream().cuda_stream`); no arithmetic of the method happens here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+ROCO_F32 = 0
+ROCO_BF16 = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libroco.so"
+_lib: Optional[ctypes.CDLL] = None
+
+
+class RocoError(RuntimeError):
+    """A roco_* call returned a negative code."""
+
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {roco_strerror(code)} (code {code})")
+
+
+class RocoParams(ctypes.Structure):
+    """Mirror of `roco_params` (include/roco.h)."""
+
+    _fields_ = [
+        ("units", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32),
+        ("budget", ctypes.c_int32),
+        ("scope", ctypes.c_int32),
+        ("dtype", ctypes.c_int32),
+        ("scale", ctypes.c_float),
+        ("recency_window", ctypes.c_int32),
+        ("recency_bias", ctypes.c_float),
+    ]
+
+    def __init__(self, units, head_dim, budget, scope, dtype, scale=0.0, recency_window=0, recency_bias=0.0):
+        super().__init__(int(units), int(head_dim), int(budget), int(scope), int(dtype), float(scale),
+                         int(recency_window), float(recency_bias))
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, _LIB_NAME)
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the built HIP library; raises if it is missing (there is no other implementation)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is not built; run `python -m paper_2402_06262_amd.build` "
+                           "(hipcc, gfx950) first -- the RoCo path has no CPU fallback")
+    lib = ctypes.CDLL(path)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    pp = ctypes.POINTER(RocoParams)
+    lib.roco_prefill_workspace_bytes.restype = sz
+    lib.roco_prefill_workspace_bytes.argtypes = [pp, i32]
+    lib.roco_decode_workspace_bytes.restype = sz
+    lib.roco_decode_workspace_bytes.argtypes = [pp]
+    lib.roco_prefill_compress.restype = ctypes.c_int
+    lib.roco_prefill_compress.argtypes = [pp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.roco_decode_step.restype = ctypes.c_int
+    lib.roco_decode_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.roco_strerror.restype = ctypes.c_char_p
+    lib.roco_strerror.argtypes = [ctypes.c_int]
+    lib.roco_version.restype = ctypes.c_int
+    lib.roco_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def roco_strerror(code: int) -> str:
+    return load_library().roco_strerror(int(code)).decode()
+
+
+def roco_version() -> int:
+    return int(load_library().roco_version())
+
+
+def prefill_workspace_bytes(params: RocoParams, L_max: int) -> int:
+    return int(load_library().roco_prefill_workspace_bytes(ctypes.byref(params), int(L_max)))
+
+
+def decode_workspace_bytes(params: RocoParams) -> int:
+    return int(load_library().roco_decode_workspace_bytes(ctypes.byref(params)))
+
+
+def _ptr(t) -> Optional[int]:
+    """Device address of a torch tensor (None stays NULL); host ints pass through."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_contiguous():
+        raise ValueError("roco: tensors must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def roco_prefill_compress(params: RocoParams, Q, K, V, length, L_max: int, K_cache, V_cache, stats, pos,
+                          n_used, O, workspace, workspace_bytes: Optional[int] = None, stream=None) -> None:
+    """See include/roco.h.  Tensors are device tensors; `O` may be None."""
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    rc = load_library().roco_prefill_compress(
+        ctypes.byref(params), _ptr(Q), _ptr(K), _ptr(V), _ptr(length), int(L_max), _ptr(K_cache),
+        _ptr(V_cache), _ptr(stats), _ptr(pos), _ptr(n_used), _ptr(O), _ptr(workspace), int(workspace_bytes),
+        _stream(stream))
+    if rc != 0:
+        raise RocoError(rc, "roco_prefill_compress")
+
+
+def roco_decode_step(params: RocoParams, q, k_new, v_new, qpos, K_cache, V_cache, stats, pos, n_used, out,
+                     evicted_slot, evicted_pos, workspace, workspace_bytes: Optional[int] = None,
+                     stream=None) -> None:
+    """See include/roco.h.  `evicted_slot` / `evicted_pos` may be None."""
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    rc = load_library().roco_decode_step(
+        ctypes.byref(params), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(qpos), _ptr(K_cache), _ptr(V_cache),
+        _ptr(stats), _ptr(pos), _ptr(n_used), _ptr(out), _ptr(evicted_slot), _ptr(evicted_pos),
+        _ptr(workspace), int(workspace_bytes), _stream(stream))
+    if rc != 0:
+        raise RocoError(rc, "roco_decode_step")
+
+
+@dataclass
+class RocoCache:
+    """Caller-owned device buffers of the budgeted cache (plain torch tensors, nothing else)."""
+
+    K: "object"  # [units, B, d]
+    V: "object"
+    stats: "object"  # [units, 3, B] fp32: Acc, Acc2, Count
+    pos: "object"  # [units, B] int32
+    n_used: "object"  # [units] int32
+
+
+def alloc_cache(params: RocoParams, device="cuda") -> RocoCache:
+    import torch
+    dt = torch.bfloat16 if params.dtype == ROCO_BF16 else torch.float32
+    U, B, d = params.units, params.budget, params.head_dim
+    return RocoCache(
+        torch.zeros((U, B, d), dtype=dt, device=device),
+        torch.zeros((U, B, d), dtype=dt, device=device),
+        torch.zeros((U, 3, B), dtype=torch.float32, device=device),
+        torch.full((U, B), -1, dtype=torch.int32, device=device),
+        torch.zeros((U,), dtype=torch.int32, device=device),
+    )

@@ -1,0 +1,177 @@
+// C ABI of the RoCo library: argument validation, workspace layout and kernel launches.
+// Nothing here allocates, frees or synchronises.
+#include <math.h>
+#include <stdlib.h>
+
+#include "../../include/roco.h"
+#include "kernels.hpp"
+
+namespace {
+
+using namespace roco;
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_params(const roco_params* p) {
+  if (p == nullptr) return ROCO_EINVAL;
+  if (p->units < 1 || p->budget < 1 || p->scope < 1 || p->scope > p->budget) return ROCO_EINVAL;
+  if (p->recency_window < 0) return ROCO_EINVAL;
+  if (!(p->scale == p->scale) || !(p->recency_bias == p->recency_bias)) return ROCO_EINVAL;  // NaN
+  if (p->dtype != ROCO_F32 && p->dtype != ROCO_BF16) return ROCO_EUNSUPPORTED;
+  if (p->head_dim != 64 && p->head_dim != 128) return ROCO_EUNSUPPORTED;
+  if (p->budget > (1 << 24)) return ROCO_EUNSUPPORTED;  // Count is kept exactly in fp32
+  return ROCO_OK;
+}
+
+float scale_log2(const roco_params* p) {
+  const float s = p->scale > 0.0f ? p->scale : 1.0f / sqrtf(static_cast<float>(p->head_dim));
+  return s * 1.4426950408889634f;
+}
+
+// ---- decode workspace: z | part_m | part_l | part_o | keys
+struct DecodeLayout { size_t z, part_m, part_l, part_o, keys, total; };
+DecodeLayout decode_layout(const roco_params* p) {
+  DecodeLayout l;
+  const size_t U = p->units, B = p->budget, D = p->head_dim;
+  size_t off = 0;
+  l.z = off;      off += align_up(U * B * sizeof(float));
+  l.part_m = off; off += align_up(U * kMaxSplits * sizeof(float));
+  l.part_l = off; off += align_up(U * kMaxSplits * sizeof(float));
+  l.part_o = off; off += align_up(U * kMaxSplits * D * sizeof(float));
+  l.keys = off;   off += (p->budget > kMaxDecodeBudgetLds) ? align_up(U * 2 * B * sizeof(uint32_t)) : 0;
+  l.total = off;
+  return l;
+}
+
+// ---- prefill workspace: lse | acc | acc2 | var_key | mas_key, each [units][L_max]
+struct PrefillLayout { size_t lse, acc, acc2, var_key, mas_key, total; };
+PrefillLayout prefill_layout(const roco_params* p, int32_t L_max) {
+  PrefillLayout l;
+  const size_t plane = align_up(static_cast<size_t>(p->units) * L_max * sizeof(float));
+  l.lse = 0; l.acc = plane; l.acc2 = 2 * plane; l.var_key = 3 * plane; l.mas_key = 4 * plane;
+  l.total = 5 * plane;
+  return l;
+}
+
+int env_int(const char* name, int dflt) {
+  const char* v = getenv(name);
+  return (v && *v) ? atoi(v) : dflt;
+}
+
+// Split the budget so that a step launches enough workgroups to cover 256 compute units several times.
+void choose_splits(const roco_params* p, int& splits, int& rows_per_split) {
+  const int gran = decode_rows_per_pass(p->dtype, p->head_dim);
+  const int max_splits_by_rows = (p->budget + gran - 1) / gran;
+  int want = env_int("ROCO_DECODE_SPLITS", 0);
+  if (want <= 0) {
+    const int target_wgs = 2048;
+    want = (target_wgs + p->units - 1) / p->units;
+  }
+  if (want > kMaxSplits) want = kMaxSplits;
+  if (want > max_splits_by_rows) want = max_splits_by_rows;
+  if (want < 1) want = 1;
+  int rows = (p->budget + want - 1) / want;
+  rows = (rows + gran - 1) / gran * gran;
+  splits = (p->budget + rows - 1) / rows;
+  rows_per_split = rows;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t roco_prefill_workspace_bytes(const roco_params* params, int32_t L_max) {
+  if (check_params(params) != ROCO_OK || L_max < 1) return 0;
+  return prefill_layout(params, L_max).total;
+}
+
+size_t roco_decode_workspace_bytes(const roco_params* params) {
+  if (check_params(params) != ROCO_OK) return 0;
+  return decode_layout(params).total;
+}
+
+int roco_prefill_compress(const roco_params* params, const void* Q, const void* K, const void* V,
+                          const int32_t* len, int32_t L_max, void* K_cache, void* V_cache, float* stats,
+                          int32_t* pos, int32_t* n_used, void* O, void* workspace, size_t workspace_bytes,
+                          void* hip_stream) {
+  const int rc = check_params(params);
+  if (rc != ROCO_OK) return rc;
+  if (L_max < 1 || L_max > (1 << 24)) return ROCO_EINVAL;
+  const void* need[] = {Q, K, V, len, K_cache, V_cache, stats, pos, n_used, workspace};
+  for (const void* ptr : need)
+    if (ptr == nullptr || !aligned16(ptr)) return ROCO_EINVAL;
+  if (O != nullptr && !aligned16(O)) return ROCO_EINVAL;
+  const PrefillLayout lay = prefill_layout(params, L_max);
+  if (workspace_bytes < lay.total) return ROCO_EWORKSPACE;
+
+  PrefillArgs a;
+  a.units = params->units; a.L_max = L_max; a.B = params->budget; a.scope = params->scope;
+  a.scale_log2 = scale_log2(params);
+  a.recency_window = params->recency_window;
+  a.recency_bias_log2 = params->recency_bias * 1.4426950408889634f;
+  a.Q = Q; a.K = K; a.V = V; a.len = len;
+  a.K_cache = K_cache; a.V_cache = V_cache; a.stats = stats; a.pos = pos; a.n_used = n_used; a.O = O;
+  char* ws = static_cast<char*>(workspace);
+  a.lse = reinterpret_cast<float*>(ws + lay.lse);
+  a.acc = reinterpret_cast<float*>(ws + lay.acc);
+  a.acc2 = reinterpret_cast<float*>(ws + lay.acc2);
+  a.var_key = reinterpret_cast<uint32_t*>(ws + lay.var_key);
+  a.mas_key = reinterpret_cast<uint32_t*>(ws + lay.mas_key);
+
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const bool mfma = params->dtype == ROCO_BF16 && params->head_dim == 128 &&
+                    env_int("ROCO_PREFILL_SIMPLE", 0) == 0;
+  hipError_t e = mfma ? launch_prefill_attention_mfma(a, s)
+                      : launch_prefill_attention_simple(params->dtype, params->head_dim, a, s);
+  if (e != hipSuccess) return ROCO_EHIP;
+  e = launch_prefill_select_compact(params->dtype, params->head_dim, a, s);
+  return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
+}
+
+int roco_decode_step(const roco_params* params, const void* q, const void* k_new, const void* v_new,
+                     const int32_t* qpos, void* K_cache, void* V_cache, float* stats, int32_t* pos,
+                     int32_t* n_used, void* out, int32_t* evicted_slot, int32_t* evicted_pos,
+                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const int rc = check_params(params);
+  if (rc != ROCO_OK) return rc;
+  const void* need[] = {q, k_new, v_new, qpos, K_cache, V_cache, stats, pos, n_used, out, workspace};
+  for (const void* ptr : need)
+    if (ptr == nullptr || !aligned16(ptr)) return ROCO_EINVAL;
+  const DecodeLayout lay = decode_layout(params);
+  if (workspace_bytes < lay.total) return ROCO_EWORKSPACE;
+
+  DecodeArgs a;
+  a.units = params->units; a.B = params->budget; a.scope = params->scope;
+  choose_splits(params, a.splits, a.rows_per_split);
+  a.scale_log2 = scale_log2(params);
+  a.recency_window = params->recency_window;
+  a.recency_bias_log2 = params->recency_bias * 1.4426950408889634f;
+  a.q = q; a.k_new = k_new; a.v_new = v_new; a.qpos = qpos;
+  a.K = K_cache; a.V = V_cache; a.stats = stats; a.pos = pos; a.n_used = n_used; a.out = out;
+  a.evicted_slot = evicted_slot; a.evicted_pos = evicted_pos;
+  char* ws = static_cast<char*>(workspace);
+  a.z = reinterpret_cast<float*>(ws + lay.z);
+  a.part_m = reinterpret_cast<float*>(ws + lay.part_m);
+  a.part_l = reinterpret_cast<float*>(ws + lay.part_l);
+  a.part_o = reinterpret_cast<float*>(ws + lay.part_o);
+  a.keys = reinterpret_cast<uint32_t*>(ws + lay.keys);
+  const hipError_t e = launch_decode(params->dtype, params->head_dim, a, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
+}
+
+const char* roco_strerror(int code) {
+  switch (code) {
+    case ROCO_OK: return "success";
+    case ROCO_EINVAL: return "invalid argument (null or misaligned pointer, or a size out of range)";
+    case ROCO_EUNSUPPORTED: return "unsupported dtype, head_dim or budget";
+    case ROCO_EWORKSPACE: return "workspace too small";
+    case ROCO_EHIP: return "HIP kernel launch failed";
+    default: return "unknown error code";
+  }
+}
+
+int roco_version(void) { return ROCO_VERSION; }
+
+}  // extern "C"

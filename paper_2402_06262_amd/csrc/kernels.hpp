@@ -1,0 +1,59 @@
+// Internal launch interface between the C ABI (api.hip) and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace roco {
+
+constexpr int kMaxSplits = 64;        // upper bound on split-K partials per unit (sizes the workspace)
+constexpr int kDecodeSelectThreads = 256;
+constexpr int kMaxDecodeBudgetLds = 4096;  // keys of a unit kept in LDS by the decode selection up to here
+
+struct DecodeArgs {
+  int units, B, scope, splits, rows_per_split;
+  float scale_log2;      // scale * log2(e)
+  int recency_window;
+  float recency_bias_log2;
+  const void *q, *k_new, *v_new;
+  const int32_t* qpos;
+  void *K, *V;
+  float* stats;          // [units][3][B]
+  int32_t *pos, *n_used;
+  void* out;
+  int32_t *evicted_slot, *evicted_pos;
+  // workspace
+  float* z;              // [units][B]   base-2 logits of this step
+  float* part_m;         // [units][splits]
+  float* part_l;         // [units][splits]
+  float* part_o;         // [units][splits][D]
+  uint32_t* keys;        // [units][2][B] ranking keys when B is too large for LDS, else unused
+};
+
+struct PrefillArgs {
+  int units, L_max, B, scope;
+  float scale_log2;
+  int recency_window;
+  float recency_bias_log2;
+  const void *Q, *K, *V;
+  const int32_t* len;
+  void *K_cache, *V_cache;
+  float* stats;          // [units][3][B]
+  int32_t *pos, *n_used;
+  void* O;               // may be null
+  // workspace
+  float* lse;            // [units][L_max]  base-2 log-sum-exp of every query row
+  float* acc;            // [units][L_max]
+  float* acc2;           // [units][L_max]
+  uint32_t* var_key;     // [units][L_max]
+  uint32_t* mas_key;     // [units][L_max]
+};
+
+// dtype: 0 = f32, 1 = bf16; head_dim: 64 or 128.  Each returns hipGetLastError() of its launches.
+hipError_t launch_decode(int dtype, int head_dim, const DecodeArgs& a, hipStream_t s);
+int decode_rows_per_pass(int dtype, int head_dim);  // granularity of DecodeArgs::rows_per_split
+hipError_t launch_prefill_attention_simple(int dtype, int head_dim, const PrefillArgs& a, hipStream_t s);
+hipError_t launch_prefill_attention_mfma(const PrefillArgs& a, hipStream_t s);  // bf16, head_dim 128
+hipError_t launch_prefill_select_compact(int dtype, int head_dim, const PrefillArgs& a, hipStream_t s);
+
+}  // namespace roco

@@ -1,0 +1,129 @@
+// Prefill attention statistics on the plain vector ALUs, for every supported dtype / head_dim.
+//
+// This is the general path (fp32 storage, head_dim 64) and the cross-check for the matrix-core path.
+// Two passes, because a column statistic needs the final normaliser of every row it sums over:
+//   pass 1: one wave per query row i streams keys 0..i with an online softmax and stores the row's base-2
+//           log-sum-exp (and the attention output, if asked)                     (section 2.1, eq. 1; causal)
+//   pass 2: one wave per key column j streams queries j..len-1, recomputes the logit and accumulates
+//           Acc[j] = sum_i P[i,j] and Acc2[j] = sum_i P[i,j]^2 in fp32            (section 4.3)
+// Count[j] = len - j has a closed form and is not accumulated.  The L x L matrix is never stored.
+#include "kernels.hpp"
+#include "stream.hpp"
+
+namespace roco {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+constexpr int kUnroll = 4;
+
+template <int DT, int D>
+__global__ __launch_bounds__(kThreads) void prefill_rows_simple(PrefillArgs a) {
+  using G = RowGeom<DT, D>;
+  const int u = blockIdx.y;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int c = lane % G::LPR;
+  const int i = blockIdx.x * kWaves + wave;
+  const int len = a.len[u];
+  if (i >= len) return;
+  const size_t ubase = static_cast<size_t>(u) * a.L_max;
+  float qf[G::EPL];
+  unpack16<DT>(load16(static_cast<const char*>(a.Q) + (ubase + i) * G::ROW_BYTES + c * 16), qf);
+#pragma unroll
+  for (int e = 0; e < G::EPL; ++e) qf[e] *= a.scale_log2;
+  const char* Kb = static_cast<const char*>(a.K) + ubase * G::ROW_BYTES;
+  const char* Vb = static_cast<const char*>(a.V) + ubase * G::ROW_BYTES;
+  const int w = a.recency_window;
+  const float rb = a.recency_bias_log2;
+  FlashState<G::EPL> st;
+  st.reset();
+  auto bias = [&](int row) -> float { return (i - row < w) ? rb : 0.0f; };  // row <= i here
+  auto zstore = [](int, float) {};
+  stream_attend<DT, D, kUnroll>(qf, Kb, Vb, 0, i + 1, kUnroll * G::R, bias, zstore, st);
+  merge_groups_in_wave<DT, D>(st);
+  if (lane == 0) a.lse[ubase + i] = st.m + log2f(st.l);
+  if (a.O != nullptr && lane < G::LPR) {
+    const float inv = 1.0f / st.l;
+#pragma unroll
+    for (int e = 0; e < G::EPL; ++e)
+      store_elem<DT>(a.O, (ubase + i) * D + lane * G::EPL + e, st.acc[e] * inv);
+  }
+}
+
+template <int DT, int D>
+__global__ __launch_bounds__(kThreads) void prefill_columns_simple(PrefillArgs a) {
+  using G = RowGeom<DT, D>;
+  constexpr int U = kUnroll;
+  const int u = blockIdx.y;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / G::LPR, c = lane % G::LPR;
+  const int j = blockIdx.x * kWaves + wave;
+  const int len = a.len[u];
+  if (j >= len) return;
+  const size_t ubase = static_cast<size_t>(u) * a.L_max;
+  float kf[G::EPL];
+  unpack16<DT>(load16(static_cast<const char*>(a.K) + (ubase + j) * G::ROW_BYTES + c * 16), kf);
+#pragma unroll
+  for (int e = 0; e < G::EPL; ++e) kf[e] *= a.scale_log2;
+  const char* Qb = static_cast<const char*>(a.Q) + ubase * G::ROW_BYTES;
+  const float* lse = a.lse + ubase;
+  const int w = a.recency_window;
+  const float rb = a.recency_bias_log2;
+  float s1 = 0.0f, s2 = 0.0f;
+  for (int base = j; base < len; base += U * G::R) {
+    uint4 qw[U];
+    float ls[U];
+#pragma unroll
+    for (int x = 0; x < U; ++x) {
+      const int row = base + x * G::R + g;
+      const int r = row < len ? row : j;
+      qw[x] = load16(Qb + static_cast<size_t>(r) * G::ROW_BYTES + c * 16);
+      ls[x] = lse[r];
+    }
+#pragma unroll
+    for (int x = 0; x < U; ++x) {
+      const int row = base + x * G::R + g;
+      float qf[G::EPL];
+      unpack16<DT>(qw[x], qf);
+      float dot = 0.0f;
+#pragma unroll
+      for (int e = 0; e < G::EPL; ++e) dot = fmaf(qf[e], kf[e], dot);
+      dot = group_sum<G::LPR>(dot);
+      if (row < len) {
+        const float t = dot + ((row - j < w) ? rb : 0.0f);
+        const float p = exp2f(t - ls[x]);
+        s1 += p;
+        s2 = fmaf(p, p, s2);
+      }
+    }
+  }
+#pragma unroll
+  for (int m = G::LPR; m < kWave; m <<= 1) {
+    s1 += __shfl_xor(s1, m, kWave);
+    s2 += __shfl_xor(s2, m, kWave);
+  }
+  if (lane == 0) {
+    a.acc[ubase + j] = s1;
+    a.acc2[ubase + j] = s2;
+  }
+}
+
+template <int DT, int D>
+hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
+  const dim3 grid((a.L_max + kWaves - 1) / kWaves, a.units);
+  hipLaunchKernelGGL((prefill_rows_simple<DT, D>), grid, dim3(kThreads), 0, s, a);
+  hipLaunchKernelGGL((prefill_columns_simple<DT, D>), grid, dim3(kThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_prefill_attention_simple(int dtype, int head_dim, const PrefillArgs& a, hipStream_t s) {
+  if (dtype == kF32 && head_dim == 64) return launch_t<kF32, 64>(a, s);
+  if (dtype == kF32 && head_dim == 128) return launch_t<kF32, 128>(a, s);
+  if (dtype == kBF16 && head_dim == 64) return launch_t<kBF16, 64>(a, s);
+  if (dtype == kBF16 && head_dim == 128) return launch_t<kBF16, 128>(a, s);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace roco

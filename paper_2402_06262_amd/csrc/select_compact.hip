@@ -1,0 +1,128 @@
+// Prefill eviction step and cache compaction (one eviction step that frees E = len - B tokens; section 5.3
+// "Overhead", block-wise evict-and-encode with the prompt as one block).
+//
+// Rule (section 4.3 applied E times with the statistics frozen, in closed form): among the s + E - 1
+// tokens of lowest attention variance, evict the E tokens of lowest mean attention score; equal keys go to
+// the lowest position.  The retained tokens keep ascending position order in the compacted cache.
+//
+//   prefill_select  : one workgroup per unit.  Two exact k-smallest selections on the fp32 bit patterns
+//                     (radix select, no sorting), then an ordered prefix sum assigns cache slots and writes
+//                     pos[], the three statistics planes and n_used.
+//   prefill_gather  : grid (row blocks, units): copies the retained K / V rows into the cache, 16 bytes per
+//                     lane.
+#include "kernels.hpp"
+#include "stream.hpp"
+
+namespace roco {
+namespace {
+
+constexpr int kSelThreads = 1024;
+constexpr int kGatherThreads = 256;
+constexpr int kGatherRows = 64;  // cache rows per gather workgroup
+
+__global__ __launch_bounds__(kSelThreads) void prefill_select(PrefillArgs a) {
+  constexpr int NT = kSelThreads;
+  __shared__ uint32_t sel_sh[256 + NT / kWave + 3];
+  __shared__ uint32_t scan_sh[NT / kWave + 1];
+  const int u = blockIdx.x, tid = threadIdx.x;
+  const int B = a.B;
+  const int n = a.len[u];
+  const size_t ubase = static_cast<size_t>(u) * a.L_max;
+  const float* acc = a.acc + ubase;
+  const float* acc2 = a.acc2 + ubase;
+  uint32_t* var_key = a.var_key + ubase;
+  uint32_t* mas_key = a.mas_key + ubase;
+  float* oacc = a.stats + static_cast<size_t>(u) * 3 * B;
+  float* oacc2 = oacc + B;
+  float* ocnt = oacc2 + B;
+  int32_t* pos = a.pos + static_cast<size_t>(u) * B;
+
+  const int kept = n < B ? n : B;
+  if (n <= B) {
+    for (int i = tid; i < n; i += NT) {
+      pos[i] = i;
+      oacc[i] = acc[i];
+      oacc2[i] = acc2[i];
+      ocnt[i] = static_cast<float>(n - i);
+    }
+  } else {
+    const uint32_t E = static_cast<uint32_t>(n - B);
+    const uint32_t m = min(static_cast<uint32_t>(n), static_cast<uint32_t>(a.scope) + E - 1u);
+    for (int i = tid; i < n; i += NT) {
+      uint32_t mk, vk;
+      ranking_keys(acc[i], acc2[i], static_cast<float>(n - i), mk, vk);
+      var_key[i] = vk;
+      mas_key[i] = mk;
+    }
+    __syncthreads();
+    const KSmallest scope = select_k_smallest<NT>([&](int i) { return var_key[i]; }, n, m, sel_sh);
+    auto key2 = [&](int i) -> uint32_t { return scope.has(var_key[i], i) ? mas_key[i] : 0xffffffffu; };
+    const KSmallest out = select_k_smallest<NT>(key2, n, E, sel_sh);
+    // ordered compaction: thread t owns the contiguous positions [t*c, (t+1)*c)
+    const int c = (n + NT - 1) / NT;
+    const int lo = min(n, tid * c), hi = min(n, lo + c);
+    uint32_t mine = 0;
+    for (int i = lo; i < hi; ++i) mine += out.has(key2(i), i) ? 0u : 1u;
+    uint32_t total;
+    uint32_t dst = block_exclusive_scan<NT>(mine, scan_sh, total);
+    for (int i = lo; i < hi; ++i) {
+      if (!out.has(key2(i), i) && dst < static_cast<uint32_t>(B)) {
+        pos[dst] = i;
+        oacc[dst] = acc[i];
+        oacc2[dst] = acc2[i];
+        ocnt[dst] = static_cast<float>(n - i);
+        ++dst;
+      }
+    }
+  }
+  for (int i = kept + tid; i < B; i += NT) {
+    pos[i] = -1;
+    oacc[i] = 0.0f;
+    oacc2[i] = 0.0f;
+    ocnt[i] = 0.0f;
+  }
+  if (tid == 0) a.n_used[u] = kept;
+}
+
+template <int ROW_BYTES>
+__global__ __launch_bounds__(kGatherThreads) void prefill_gather(PrefillArgs a) {
+  constexpr int LPR = ROW_BYTES / 16;
+  constexpr int RPP = kGatherThreads / LPR;  // rows per pass
+  const int u = blockIdx.y, tid = threadIdx.x;
+  const int B = a.B;
+  const int n = a.len[u];
+  const int kept = n < B ? n : B;
+  const int32_t* pos = a.pos + static_cast<size_t>(u) * B;
+  const char* Kin = static_cast<const char*>(a.K) + static_cast<size_t>(u) * a.L_max * ROW_BYTES;
+  const char* Vin = static_cast<const char*>(a.V) + static_cast<size_t>(u) * a.L_max * ROW_BYTES;
+  char* Kout = static_cast<char*>(a.K_cache) + static_cast<size_t>(u) * B * ROW_BYTES;
+  char* Vout = static_cast<char*>(a.V_cache) + static_cast<size_t>(u) * B * ROW_BYTES;
+  const int r = tid / LPR, c = tid % LPR;
+  const int first = blockIdx.x * kGatherRows;
+  const int last = min(kept, first + kGatherRows);
+  for (int slot = first + r; slot < last; slot += RPP) {
+    const int p = pos[slot];
+    if (p < 0 || p >= n) continue;  // never read outside the prompt, whatever pos[] holds
+    const size_t src = static_cast<size_t>(p) * ROW_BYTES + c * 16;
+    const size_t dst = static_cast<size_t>(slot) * ROW_BYTES + c * 16;
+    *reinterpret_cast<uint4*>(Kout + dst) = load16(Kin + src);
+    *reinterpret_cast<uint4*>(Vout + dst) = load16(Vin + src);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_prefill_select_compact(int dtype, int head_dim, const PrefillArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(prefill_select, dim3(a.units), dim3(kSelThreads), 0, s, a);
+  const int row_bytes = head_dim * (dtype == kBF16 ? 2 : 4);
+  const dim3 grid((a.B + kGatherRows - 1) / kGatherRows, a.units);
+  switch (row_bytes) {
+    case 128: hipLaunchKernelGGL((prefill_gather<128>), grid, dim3(kGatherThreads), 0, s, a); break;
+    case 256: hipLaunchKernelGGL((prefill_gather<256>), grid, dim3(kGatherThreads), 0, s, a); break;
+    case 512: hipLaunchKernelGGL((prefill_gather<512>), grid, dim3(kGatherThreads), 0, s, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace roco

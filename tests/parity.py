@@ -1,0 +1,214 @@
+"""Parity harness: drive the HIP library and the CPU oracle on the same seeded inputs and compare.
+
+Tolerances ("Tolerances"):
+  * attention outputs: |g - o| <= tol * max(|o|, rms(o)) per vector, tol = 1e-3 (fp32 storage) or 2e-2
+    (bf16 storage, whose rounding alone is 2^-9 relative);
+  * Acc, Acc2:        |g - o| <= 1e-3 * max(|o|, 1e-6);  Count, pos, n_used, copied K/V rows: exact;
+  * eviction decisions: identical index sets, unless the oracle's own gap lies inside the tie band
+    (oracle/tie_band.py); such declared ties are counted, and the oracle adopts the library's choice so
+    that later steps stay comparable.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+import paper_2402_06262_amd as roco
+from oracle import roco_oracle as orc
+from oracle import tie_band
+
+STAT_RTOL = 1e-3
+STAT_FLOOR = 1e-6
+OUT_RTOL = {"f32": 1e-3, "bf16": 2e-2}
+
+
+def torch_dtype(dtype: str):
+    return torch.bfloat16 if dtype == "bf16" else torch.float32
+
+
+def roco_dtype(dtype: str) -> int:
+    return roco.ROCO_BF16 if dtype == "bf16" else roco.ROCO_F32
+
+
+def to_dev(x: np.ndarray, dtype: str) -> torch.Tensor:
+    """float32 host array (bf16-representable when dtype is bf16) -> device tensor of the storage type."""
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
+    return t.to(torch_dtype(dtype)).contiguous()
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy() if t.dtype in (torch.bfloat16, torch.float32) else t.detach().cpu().numpy()
+
+
+def assert_out_close(g: np.ndarray, o: np.ndarray, dtype: str, what: str):
+    g, o = np.asarray(g, np.float64), np.asarray(o, np.float64)
+    rms = math.sqrt(float(np.mean(o * o))) if o.size else 0.0
+    tol = OUT_RTOL[dtype] * np.maximum(np.abs(o), rms)
+    bad = np.abs(g - o) > tol
+    assert not bad.any(), f"{what}: {int(bad.sum())} of {o.size} outside tolerance; worst |g-o|/tol = " \
+                          f"{float(np.max(np.abs(g - o) / np.maximum(tol, 1e-300))):.3g}"
+
+
+def assert_stat_close(g: np.ndarray, o: np.ndarray, what: str):
+    g, o = np.asarray(g, np.float64), np.asarray(o, np.float64)
+    tol = STAT_RTOL * np.maximum(np.abs(o), STAT_FLOOR)
+    bad = np.abs(g - o) > tol
+    assert not bad.any(), f"{what}: {int(bad.sum())} of {o.size} outside tolerance; worst rel = " \
+                          f"{float(np.max(np.abs(g - o) / np.maximum(np.abs(o), STAT_FLOOR))):.3g}"
+
+
+@dataclass
+class TieCount:
+    prefill_decisions: int = 0
+    prefill_ties: int = 0
+    decode_decisions: int = 0
+    decode_ties: int = 0
+
+    def __iadd__(self, o: "TieCount"):
+        self.prefill_decisions += o.prefill_decisions
+        self.prefill_ties += o.prefill_ties
+        self.decode_decisions += o.decode_decisions
+        self.decode_ties += o.decode_ties
+        return self
+
+
+@dataclass
+class GpuSession:
+    """Device buffers of one workload slice: `units` units with a common L_max and budget."""
+
+    params: "roco.RocoParams"
+    dtype: str
+    cache: "roco.RocoCache"
+    decode_ws: torch.Tensor
+    out: torch.Tensor
+    ev_slot: torch.Tensor
+    ev_pos: torch.Tensor
+    prefill_ws: Optional[torch.Tensor] = None
+    O: Optional[torch.Tensor] = None
+
+
+def make_session(units: int, head_dim: int, budget: int, scope: int, dtype: str, scale: float = 0.0,
+                 recency_window: int = 0, recency_bias: float = 0.0) -> GpuSession:
+    p = roco.RocoParams(units, head_dim, budget, scope, roco_dtype(dtype), scale, recency_window, recency_bias)
+    cache = roco.alloc_cache(p)
+    ws = torch.empty(max(16, roco.decode_workspace_bytes(p)), dtype=torch.uint8, device="cuda")
+    out = torch.zeros((units, head_dim), dtype=torch_dtype(dtype), device="cuda")
+    ev_slot = torch.full((units,), -7, dtype=torch.int32, device="cuda")
+    ev_pos = torch.full((units,), -7, dtype=torch.int32, device="cuda")
+    return GpuSession(p, dtype, cache, ws, out, ev_slot, ev_pos)
+
+
+def gpu_prefill(sess: GpuSession, Q: np.ndarray, K: np.ndarray, V: np.ndarray, lens: Sequence[int],
+                want_out: bool = True):
+    """Q, K, V: [units, L_max, d] float32 host arrays.  Returns host copies of everything written."""
+    U, L_max, d = Q.shape
+    p = sess.params
+    assert U == p.units and d == p.head_dim
+    dQ, dK, dV = to_dev(Q, sess.dtype), to_dev(K, sess.dtype), to_dev(V, sess.dtype)
+    dlen = torch.tensor(list(lens), dtype=torch.int32, device="cuda")
+    sess.prefill_ws = torch.empty(max(16, roco.prefill_workspace_bytes(p, L_max)), dtype=torch.uint8, device="cuda")
+    sess.O = torch.zeros_like(dQ) if want_out else None
+    c = sess.cache
+    roco.roco_prefill_compress(p, dQ, dK, dV, dlen, L_max, c.K, c.V, c.stats, c.pos, c.n_used, sess.O, sess.prefill_ws)
+    torch.cuda.synchronize()
+    return dict(K=to_host(c.K), V=to_host(c.V), stats=to_host(c.stats), pos=to_host(c.pos),
+                n_used=to_host(c.n_used), O=None if sess.O is None else to_host(sess.O))
+
+
+def check_prefill_unit(g: dict, u: int, Qu, Ku, Vu, length: int, budget: int, scope: int, scale: float,
+                       dtype: str, recency_window: int = 0, recency_bias: float = 0.0,
+                       want_out: bool = True, row_block: int = 512):
+    """Compare unit `u` of a gpu_prefill result with the oracle.  Returns (oracle result, TieCount)."""
+    ties = TieCount()
+    res = orc.prefill_compress(Qu, Ku, Vu, length, budget, scope, scale, recency_window, recency_bias,
+                               want_out=want_out, row_block=row_block)
+    n = min(length, budget)
+    assert int(g["n_used"][u]) == n, f"unit {u}: n_used {g['n_used'][u]} != {n}"
+    gpos = g["pos"][u]
+    assert np.all(gpos[n:] == -1), f"unit {u}: unused slots must have pos -1"
+    assert np.all(np.diff(gpos[:n]) > 0), f"unit {u}: retained positions must ascend"
+    assert gpos[:n].min() >= 0 and gpos[:n].max() < length
+    if length > budget:
+        ties.prefill_decisions += 1
+        if not np.array_equal(gpos[:n], res.retained):
+            mas = orc.mean_attention_score(res.full.acc, res.full.count)
+            var = orc.attention_variance(res.full.acc, res.full.acc2, res.full.count)
+            eps_m, eps_v = tie_band.bands(res.full.acc, res.full.acc2, res.full.count)
+            keep = np.zeros(length, bool)
+            keep[gpos[:n]] = True
+            ok, why = tie_band.admissible_eviction(mas, var, eps_m, eps_v, scope, length - budget,
+                                                   np.flatnonzero(~keep))
+            diff = sorted(set(gpos[:n].tolist()) ^ set(res.retained.tolist()))
+            assert ok, f"unit {u}: retained set differs outside the tie band ({why}); differing positions {diff[:10]}"
+            ties.prefill_ties += 1
+            res = orc.prefill_compress(Qu, Ku, Vu, length, budget, scope, scale, recency_window, recency_bias,
+                                       want_out=want_out, row_block=row_block, force_retained=gpos[:n])
+    c = res.cache
+    assert np.array_equal(gpos, c.pos)
+    assert np.array_equal(g["stats"][u, 2], c.count), f"unit {u}: Count differs"
+    assert_stat_close(g["stats"][u, 0], c.acc, f"unit {u} Acc")
+    assert_stat_close(g["stats"][u, 1], c.acc2, f"unit {u} Acc2")
+    assert np.array_equal(g["K"][u, :n].astype(np.float64), c.K[:n]), f"unit {u}: cached K rows differ"
+    assert np.array_equal(g["V"][u, :n].astype(np.float64), c.V[:n]), f"unit {u}: cached V rows differ"
+    if want_out:
+        for i in range(length):
+            assert_out_close(g["O"][u, i], res.out[i], dtype, f"unit {u} O[{i}]")
+    return res, ties
+
+
+def gpu_decode_step(sess: GpuSession, q: np.ndarray, k: np.ndarray, v: np.ndarray, qpos: Sequence[int]):
+    """q, k, v: [units, d] float32 host arrays.  Returns (out, evicted_slot, evicted_pos) on the host."""
+    c, p = sess.cache, sess.params
+    dq, dk, dv = to_dev(q, sess.dtype), to_dev(k, sess.dtype), to_dev(v, sess.dtype)
+    dqpos = torch.tensor(list(qpos), dtype=torch.int32, device="cuda")
+    roco.roco_decode_step(p, dq, dk, dv, dqpos, c.K, c.V, c.stats, c.pos, c.n_used, sess.out,
+                          sess.ev_slot, sess.ev_pos, sess.decode_ws)
+    torch.cuda.synchronize()
+    return to_host(sess.out), to_host(sess.ev_slot), to_host(sess.ev_pos)
+
+
+def lockstep_decode_unit(state: "orc.CacheState", u: int, g_out, g_slot, g_pos, q, k, v, qpos: int, scope: int,
+                         scale: float, dtype: str, recency_window: int = 0, recency_bias: float = 0.0,
+                         what: str = "") -> TieCount:
+    """Advance the oracle state of unit `u` by one step and compare with the library's step."""
+    ties = TieCount()
+    full = state.n_used == state.budget
+    snapshot = state.copy() if full else None
+    r = orc.decode_step(state, q, k, v, qpos, scope, scale, recency_window, recency_bias)
+    if full:
+        ties.decode_decisions += 1
+        if int(g_slot[u]) != r.evicted_slot:
+            eps_m, eps_v = tie_band.bands(snapshot.acc, snapshot.acc2, snapshot.count)
+            ok, why = tie_band.admissible_eviction(r.mas, r.var, eps_m, eps_v, scope, 1, [int(g_slot[u])])
+            assert ok, f"{what} unit {u}: victim slot {int(g_slot[u])} vs oracle {r.evicted_slot} outside the tie band ({why})"
+            ties.decode_ties += 1
+            # the oracle adopts the library's in-band choice: redo the step from the snapshot
+            for name in ("K", "V", "acc", "acc2", "count", "pos"):
+                getattr(state, name)[...] = getattr(snapshot, name)
+            state.n_used = snapshot.n_used
+            r = orc.decode_step(state, q, k, v, qpos, scope, scale, recency_window, recency_bias,
+                                force_victim=int(g_slot[u]))
+    assert int(g_slot[u]) == r.evicted_slot, f"{what} unit {u}: evicted_slot {int(g_slot[u])} != {r.evicted_slot}"
+    assert int(g_pos[u]) == r.evicted_pos, f"{what} unit {u}: evicted_pos {int(g_pos[u])} != {r.evicted_pos}"
+    assert_out_close(g_out[u], r.out, dtype, f"{what} unit {u} out")
+    return ties
+
+
+def check_cache_unit(sess_host: dict, u: int, state: "orc.CacheState", what: str = ""):
+    n = state.n_used
+    assert int(sess_host["n_used"][u]) == n, f"{what} unit {u}: n_used"
+    assert np.array_equal(sess_host["pos"][u], state.pos), f"{what} unit {u}: pos"
+    assert np.array_equal(sess_host["stats"][u, 2], state.count), f"{what} unit {u}: Count"
+    assert_stat_close(sess_host["stats"][u, 0], state.acc, f"{what} unit {u} Acc")
+    assert_stat_close(sess_host["stats"][u, 1], state.acc2, f"{what} unit {u} Acc2")
+    assert np.array_equal(sess_host["K"][u, :n].astype(np.float64), state.K[:n]), f"{what} unit {u}: K rows"
+    assert np.array_equal(sess_host["V"][u, :n].astype(np.float64), state.V[:n]), f"{what} unit {u}: V rows"
+
+
+def cache_to_host(sess: GpuSession) -> dict:
+    c = sess.cache
+    return dict(K=to_host(c.K), V=to_host(c.V), stats=to_host(c.stats), pos=to_host(c.pos), n_used=to_host(c.n_used))

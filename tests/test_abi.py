@@ -1,0 +1,98 @@
+"""Host-side checks of the C ABI: the library loads, exports what include/roco.h declares, and rejects bad
+arguments before launching anything (no GPU needed: every call here fails validation on the host)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2402_06262_amd as roco
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+EINVAL, EUNSUPPORTED, EWORKSPACE = -1, -2, -3
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "roco.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(roco_[a-z_]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = roco.load_library()
+    names = declared_functions()
+    assert {"roco_prefill_compress", "roco_decode_step", "roco_prefill_workspace_bytes",
+            "roco_decode_workspace_bytes", "roco_strerror", "roco_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in roco.h but not exported"
+    assert roco.roco_version() == 1
+    assert roco.roco_strerror(0) == "success"
+    assert "workspace" in roco.roco_strerror(EWORKSPACE)
+
+
+def test_params_struct_layout_matches_the_header():
+    assert ctypes.sizeof(roco.RocoParams) == 32
+    assert [f[0] for f in roco.RocoParams._fields_] == [
+        "units", "head_dim", "budget", "scope", "dtype", "scale", "recency_window", "recency_bias"]
+
+
+def test_workspace_queries():
+    p = roco.RocoParams(512, 128, 2048, 64, roco.ROCO_BF16)
+    assert roco.decode_workspace_bytes(p) >= 512 * 2048 * 4
+    assert roco.prefill_workspace_bytes(p, 3072) >= 512 * 3072 * 4 * 4
+    assert roco.prefill_workspace_bytes(p, 0) == 0
+    assert roco.decode_workspace_bytes(roco.RocoParams(4, 96, 128, 16, roco.ROCO_F32)) == 0  # head_dim
+    assert roco.decode_workspace_bytes(roco.RocoParams(4, 64, 128, 129, roco.ROCO_F32)) == 0  # scope > B
+
+
+def _decode(p, ptrs=None, ws_bytes=1 << 30):
+    lib = roco.load_library()
+    a = [0x1000] * 14 if ptrs is None else ptrs
+    return lib.roco_decode_step(ctypes.byref(p), *a[:13], ws_bytes, None)
+
+
+def _prefill(p, L_max=64, ptrs=None, ws_bytes=1 << 30):
+    lib = roco.load_library()
+    a = [0x1000] * 12 if ptrs is None else ptrs
+    return lib.roco_prefill_compress(ctypes.byref(p), a[0], a[1], a[2], a[3], L_max, *a[4:11], ws_bytes, None)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(units=0), EINVAL), (dict(budget=0), EINVAL), (dict(scope=0), EINVAL), (dict(scope=129), EINVAL),
+    (dict(recency_window=-1), EINVAL), (dict(head_dim=96), EUNSUPPORTED), (dict(dtype=7), EUNSUPPORTED),
+    (dict(scale=float("nan")), EINVAL),
+])
+def test_invalid_params_are_rejected_on_the_host(kw, code):
+    base = dict(units=4, head_dim=64, budget=128, scope=16, dtype=roco.ROCO_F32)
+    base.update(kw)
+    p = roco.RocoParams(**base)
+    assert _decode(p) == code
+    assert _prefill(p) == code
+
+
+def test_null_misaligned_and_small_workspace_are_rejected_on_the_host():
+    p = roco.RocoParams(4, 64, 128, 16, roco.ROCO_F32)
+    lib = roco.load_library()
+    assert lib.roco_decode_step(None, *([0x1000] * 13), 1 << 30, None) == EINVAL
+    for bad in range(11):  # the eleven required pointers (evicted_* are optional)
+        ptrs = [0x1000] * 13
+        order = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 12]
+        ptrs[order[bad]] = None
+        assert _decode(p, ptrs) == EINVAL
+        ptrs[order[bad]] = 0x1004
+        assert _decode(p, ptrs) == EINVAL
+    assert _decode(p, ws_bytes=roco.decode_workspace_bytes(p) - 1) == EWORKSPACE
+    for bad in [0, 1, 2, 3, 4, 5, 6, 7, 8, 10]:  # O (index 9) may be NULL
+        ptrs = [0x1000] * 11
+        ptrs[bad] = None
+        assert _prefill(p, ptrs=ptrs) == EINVAL
+    assert _prefill(p, L_max=0) == EINVAL
+    assert _prefill(p, L_max=64, ws_bytes=roco.prefill_workspace_bytes(p, 64) - 1) == EWORKSPACE
+
+
+def test_loading_fails_loudly_when_the_library_is_missing(monkeypatch):
+    from paper_2402_06262_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_NAME", "libroco_missing.so")
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        binding.load_library()

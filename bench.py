@@ -1,0 +1,248 @@
+#!/usr/bin/env python3
+"""Benchmark of the RoCo hot path on one MI355X.
+
+One *step* is one pass of the whole path over one batch of the serving workload (workload 3: one 32-head x
+128-dim bf16 layer, batch 16): prefill-compress of the 3072-token prompts to B = 2048 with scope 64, then
+`--decode-steps` (default 512) decode steps, each appending one token and evicting one slot per head.
+Inputs are seeded synthetic heavy-hitter Q/K/V, resident in HBM before the timed region.
+
+Prints ONE JSON line: `value` is decode tokens/s (batch x decode steps / decode time); prefill+evict tokens/s,
+the HBM roofline of the dominant decode kernel, the MFMA roofline of the prefill statistics kernels and the
+CPU oracle timed on this machine's host cores ride along in the same line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix peak
+
+
+def generate(cfg, seed, workers):
+    """All units of the workload as float32 host arrays [units, T, d] (bf16-representable)."""
+    from inputs import make_unit, unit_ids
+    ids = unit_ids(cfg)
+    T, d = cfg.total_len, cfg.head_dim
+    Q = np.empty((len(ids), T, d), np.float32)
+    K = np.empty_like(Q)
+    V = np.empty_like(Q)
+
+    def one(i):
+        u = make_unit(cfg, *ids[i], seed=seed)
+        Q[i], K[i], V[i] = u.Q, u.K, u.V
+
+    with ThreadPoolExecutor(workers) as ex:
+        list(ex.map(one, range(len(ids))))
+    return Q, K, V
+
+
+def upload(x, torch, dt, chunk=64):
+    out = torch.empty(x.shape, dtype=dt, device="cuda")
+    for i in range(0, x.shape[0], chunk):
+        out[i:i + chunk] = torch.from_numpy(x[i:i + chunk]).cuda().to(dt)
+    return out
+
+
+def cpu_baseline(cfg, Q, K, V, decode_steps, n_units, n_steps):
+    """The float64 oracle, as it stands, on a bounded sample of this workload's units."""
+    from oracle import roco_oracle as orc
+    L, B, s = cfg.prompt_len, cfg.budget, cfg.scope
+    sc = 1.0 / math.sqrt(cfg.head_dim)
+    n_steps = min(n_steps, decode_steps)
+    t0 = time.perf_counter()
+    states = []
+    for u in range(n_units):
+        states.append(orc.prefill_compress(Q[u, :L], K[u, :L], V[u, :L], L, B, s, sc).cache)
+    t1 = time.perf_counter()
+    for u in range(n_units):
+        for t in range(L, L + n_steps):
+            orc.decode_step(states[u], Q[u, t], K[u, t], V[u, t], t, s, sc)
+    t2 = time.perf_counter()
+    per_unit_prefill = (t1 - t0) / n_units
+    per_unit_step = (t2 - t1) / max(1, n_units * n_steps)
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    return {
+        "value": cfg.batch / (cfg.units * per_unit_step) if per_unit_step > 0 else None,
+        "unit": "tokens/s",
+        "prefill_evict_tokens_per_s": cfg.batch * L / (cfg.units * per_unit_prefill),
+        "cores": int(threads),
+        "host_cores_visible": len(os.sched_getaffinity(0)),
+        "kind": "oracle",
+        "sample": f"float64 NumPy oracle on units 0..{n_units - 1} of {cfg.units}: prefill-compress {L}->{B}, then "
+                  f"{n_steps} decode steps each; scaled linearly to {cfg.units} units "
+                  f"({t2 - t0:.1f} s of CPU work)",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--decode-steps", type=int, default=None, help="decode steps per pass (default: the workload's 512)")
+    ap.add_argument("--seed", type=int, default=20240206)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-units", type=int, default=96)
+    ap.add_argument("--cpu-steps", type=int, default=512)
+    ap.add_argument("--with-out", action="store_true", help="also produce the prefill attention output O")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; units (layer x sequence x head) are independent and would be "
+              "sharded without any collective, but no multi-GPU path exists. Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2402_06262_amd as roco
+    from inputs import CONFIGS
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    cfg = CONFIGS[2]
+    decode_steps = cfg.steps if args.decode_steps is None else min(cfg.steps, args.decode_steps)
+    L, B, s, d, U = cfg.prompt_len, cfg.budget, cfg.scope, cfg.head_dim, cfg.units
+    dt = torch.bfloat16
+    esz = 2
+
+    t_gen = time.perf_counter()
+    Q, K, V = generate(cfg, args.seed, workers=min(16, len(os.sched_getaffinity(0))))
+    t_gen = time.perf_counter() - t_gen
+    dQ, dK, dV = (upload(x[:, :L], torch, dt) for x in (Q, K, V))
+    # per-step decode inputs, [steps, units, d]
+    sq, sk, sv = (upload(np.ascontiguousarray(x[:, L:L + decode_steps].transpose(1, 0, 2)), torch, dt)
+                  for x in (Q, K, V))
+    qpos = (torch.arange(decode_steps, dtype=torch.int32, device="cuda")[:, None] + L).expand(decode_steps, U).contiguous()
+    dlen = torch.full((U,), L, dtype=torch.int32, device="cuda")
+
+    p = roco.RocoParams(U, d, B, s, roco.ROCO_BF16)
+    cache = roco.alloc_cache(p)
+    ws_p = torch.empty(roco.prefill_workspace_bytes(p, L), dtype=torch.uint8, device="cuda")
+    ws_d = torch.empty(roco.decode_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    out = torch.empty((decode_steps, U, d), dtype=dt, device="cuda")
+    ev_slot = torch.empty((decode_steps, U), dtype=torch.int32, device="cuda")
+    ev_pos = torch.empty_like(ev_slot)
+    O = torch.empty_like(dQ) if args.with_out else None
+    stream = torch.cuda.current_stream()
+
+    def prefill():
+        roco.roco_prefill_compress(p, dQ, dK, dV, dlen, L, cache.K, cache.V, cache.stats, cache.pos, cache.n_used,
+                                   O, ws_p, stream=stream)
+
+    def decode():
+        for t in range(decode_steps):
+            roco.roco_decode_step(p, sq[t], sk[t], sv[t], qpos[t], cache.K, cache.V, cache.stats, cache.pos,
+                                  cache.n_used, out[t], ev_slot[t], ev_pos[t], ws_d, stream=stream)
+
+    for _ in range(args.warmup):
+        prefill()
+        decode()
+    torch.cuda.synchronize()
+
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    roco.roco_profile_read()
+    roco.roco_profile_kernel(roco.PROF_KERNELS["decode_attend"])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        ev[k][0].record(stream)
+        prefill()
+        ev[k][1].record(stream)
+        decode()
+        ev[k][2].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    attend_ms, attend_n = roco.roco_profile_read()
+    roco.roco_profile_kernel(-1)
+
+    prefill_ms = sum(e[0].elapsed_time(e[1]) for e in ev)
+    decode_ms = sum(e[1].elapsed_time(e[2]) for e in ev)
+    decode_tok_s = cfg.batch * decode_steps * args.steps / (decode_ms * 1e-3)
+    prefill_tok_s = cfg.batch * L * args.steps / (prefill_ms * 1e-3)
+
+    # sanity on the final state (not a parity test): every unit full, one eviction per unit per step
+    assert int(cache.n_used.min()) == B and int(cache.n_used.max()) == B
+    assert int((ev_slot >= 0).sum()) == decode_steps * U
+
+    # dominant kernel: decode_attend reads every cached K and V element once
+    attend_bytes = U * B * 2 * d * esz
+    attend_avg_s = attend_ms * 1e-3 / max(1, attend_n)
+    step_bytes = U * B * (2 * d * esz + 24)
+    # prefill statistics: two causal QK^T passes (row normalisers, then column statistics), 2 flops per MAC
+    prefill_flops = U * 2 * d * L * (L + 1) * (1.5 if args.with_out else 1.0)
+
+    # a short extra pass (outside the timed region) with events around the two prefill statistics kernels
+    pre_kernel_ms = {}
+    for name in ("prefill_rows", "prefill_columns", "prefill_select", "prefill_gather"):
+        roco.roco_profile_kernel(roco.PROF_KERNELS[name])
+        prefill()
+        torch.cuda.synchronize()
+        ms, n = roco.roco_profile_read()
+        pre_kernel_ms[name] = ms / max(1, n)
+    dec_kernel_ms = {}
+    for name in ("decode_select", "decode_combine"):
+        roco.roco_profile_kernel(roco.PROF_KERNELS[name])
+        for t in range(min(32, decode_steps)):
+            roco.roco_decode_step(p, sq[t], sk[t], sv[t], qpos[t], cache.K, cache.V, cache.stats, cache.pos,
+                                  cache.n_used, out[t], ev_slot[t], ev_pos[t], ws_d, stream=stream)
+        torch.cuda.synchronize()
+        ms, n = roco.roco_profile_read()
+        dec_kernel_ms[name] = ms / max(1, n)
+    roco.roco_profile_kernel(-1)
+    dec_kernel_ms["decode_attend"] = attend_avg_s * 1e3
+
+    result = {
+        "metric": "RoCo decode tokens/s (7B-shape layer, B=2048, batch 16); prefill+evict tok/s",
+        "value": decode_tok_s,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "config 3: 7B-shaped layer, 32 heads x 128 dims bf16, batch 16, prompt 3072 -> B=2048, "
+                               f"scope 64, {decode_steps} decode steps", "units": U, "budget": B, "scope": s,
+                   "prompt_len": L, "decode_steps": decode_steps, "batch": cfg.batch, "seed": args.seed,
+                   "prefill_attention_output": bool(args.with_out)},
+        "decode_ms_per_token_step": decode_ms / (decode_steps * args.steps),
+        "prefill_evict_tokens_per_s": prefill_tok_s,
+        "prefill_ms": prefill_ms / args.steps,
+        "roofline": {"kernel": "decode_attend", "bound": "hbm", "achieved": attend_bytes / attend_avg_s / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": attend_bytes / attend_avg_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": attend_bytes, "avg_launch_ms": attend_avg_s * 1e3, "launches": attend_n},
+        "roofline_decode_step": {"bound": "hbm", "achieved": step_bytes / (decode_ms * 1e-3 / (decode_steps * args.steps)) / 1e9,
+                                 "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                 "frac": step_bytes / (decode_ms * 1e-3 / (decode_steps * args.steps)) / 1e9 / HBM_PEAK_GBS,
+                                 "bytes_per_step": step_bytes},
+        "roofline_prefill": {"bound": "mfma", "achieved": prefill_flops / (prefill_ms * 1e-3 / args.steps) / 1e12,
+                             "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                             "frac": prefill_flops / (prefill_ms * 1e-3 / args.steps) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                             "flops_per_pass": prefill_flops},
+        "kernel_ms": {**dec_kernel_ms, **pre_kernel_ms},
+        "input_generation_s": t_gen,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, Q, K, V, decode_steps, args.cpu_units, args.cpu_steps)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -123,6 +123,21 @@ int roco_decode_step(const roco_params* params,
                      void* out, int32_t* evicted_slot, int32_t* evicted_pos,
                      void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Profiling aid (not part of the method; for benchmarks).  roco_profile_kernel(k) makes every later call
+ * record a pair of HIP events on the caller's stream around kernel k only (k = one of ROCO_PROF_*; -1 turns
+ * it off).  roco_profile_read() waits for the recorded events, returns their summed elapsed time in
+ * milliseconds and their count since the last read, and recycles them.  This mode creates HIP events (the
+ * only resources the library ever creates) and is not thread-safe.  Returns 0 or a negative code.
+ */
+enum {
+  ROCO_PROF_DECODE_SELECT = 0, ROCO_PROF_DECODE_ATTEND = 1, ROCO_PROF_DECODE_COMBINE = 2,
+  ROCO_PROF_PREFILL_ROWS = 3, ROCO_PROF_PREFILL_COLUMNS = 4, ROCO_PROF_PREFILL_SELECT = 5,
+  ROCO_PROF_PREFILL_GATHER = 6, ROCO_PROF_KERNELS = 7
+};
+int roco_profile_kernel(int which);
+int roco_profile_read(double* total_ms, int64_t* launches);
+
 /* Static description of a return code. */
 const char* roco_strerror(int code);
 

@@ -4,6 +4,7 @@ Every step of the path runs in the HIP kernels of `libroco.so`; this package onl
 There is no CPU fallback: if the library is not built, loading it raises.
 """
 from .binding import (  # noqa: F401
+    PROF_KERNELS,
     ROCO_BF16,
     ROCO_F32,
     RocoCache,
@@ -16,6 +17,8 @@ from .binding import (  # noqa: F401
     prefill_workspace_bytes,
     roco_decode_step,
     roco_prefill_compress,
+    roco_profile_kernel,
+    roco_profile_read,
     roco_strerror,
     roco_version,
 )

@@ -73,6 +73,10 @@ def load_library() -> ctypes.CDLL:
     lib.roco_strerror.argtypes = [ctypes.c_int]
     lib.roco_version.restype = ctypes.c_int
     lib.roco_version.argtypes = []
+    lib.roco_profile_kernel.restype = ctypes.c_int
+    lib.roco_profile_kernel.argtypes = [ctypes.c_int]
+    lib.roco_profile_read.restype = ctypes.c_int
+    lib.roco_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     _lib = lib
     return lib
 
@@ -91,6 +95,25 @@ def prefill_workspace_bytes(params: RocoParams, L_max: int) -> int:
 
 def decode_workspace_bytes(params: RocoParams) -> int:
     return int(load_library().roco_decode_workspace_bytes(ctypes.byref(params)))
+
+
+PROF_KERNELS = {"decode_select": 0, "decode_attend": 1, "decode_combine": 2, "prefill_rows": 3,
+                "prefill_columns": 4, "prefill_select": 5, "prefill_gather": 6}
+
+
+def roco_profile_kernel(which: int) -> None:
+    rc = load_library().roco_profile_kernel(int(which))
+    if rc != 0:
+        raise RocoError(rc, "roco_profile_kernel")
+
+
+def roco_profile_read():
+    """(total milliseconds, launches) of the profiled kernel since the last read."""
+    ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
+    rc = load_library().roco_profile_read(ctypes.byref(ms), ctypes.byref(n))
+    if rc != 0:
+        raise RocoError(rc, "roco_profile_read")
+    return ms.value, n.value
 
 
 def _ptr(t) -> Optional[int]:

@@ -13,6 +13,7 @@
 //      results do not depend on scheduling), writes the attention output, and adds p, p^2 and 1 into the
 //      three statistics planes.
 #include "kernels.hpp"
+#include "profile.hpp"
 #include "stream.hpp"
 
 namespace roco {
@@ -210,10 +211,19 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_stats(DecodeAr
 template <int DT, int D>
 hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t s) {
   const size_t lds = (a.B <= kMaxDecodeBudgetLds) ? static_cast<size_t>(a.B) * 2 * sizeof(uint32_t) : 0;
-  hipLaunchKernelGGL((decode_select_update<DT, D>), dim3(a.units), dim3(kDecodeSelectThreads), lds, s, a);
-  hipLaunchKernelGGL((decode_attend<DT, D>), dim3(a.splits, a.units), dim3(kAttendThreads), 0, s, a);
-  hipLaunchKernelGGL((decode_combine_stats<DT, D>),
-                     dim3((a.B + kCombineSlots - 1) / kCombineSlots, a.units), dim3(kCombineThreads), 0, s, a);
+  {
+    ProfScope ps(kProfDecodeSelect, s);
+    hipLaunchKernelGGL((decode_select_update<DT, D>), dim3(a.units), dim3(kDecodeSelectThreads), lds, s, a);
+  }
+  {
+    ProfScope ps(kProfDecodeAttend, s);
+    hipLaunchKernelGGL((decode_attend<DT, D>), dim3(a.splits, a.units), dim3(kAttendThreads), 0, s, a);
+  }
+  {
+    ProfScope ps(kProfDecodeCombine, s);
+    hipLaunchKernelGGL((decode_combine_stats<DT, D>),
+                       dim3((a.B + kCombineSlots - 1) / kCombineSlots, a.units), dim3(kCombineThreads), 0, s, a);
+  }
   return hipGetLastError();
 }
 

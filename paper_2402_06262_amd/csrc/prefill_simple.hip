@@ -8,6 +8,7 @@
 //           Acc[j] = sum_i P[i,j] and Acc2[j] = sum_i P[i,j]^2 in fp32            (section 4.3)
 // Count[j] = len - j has a closed form and is not accumulated.  The L x L matrix is never stored.
 #include "kernels.hpp"
+#include "profile.hpp"
 #include "stream.hpp"
 
 namespace roco {
@@ -111,8 +112,14 @@ __global__ __launch_bounds__(kThreads) void prefill_columns_simple(PrefillArgs a
 template <int DT, int D>
 hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
   const dim3 grid((a.L_max + kWaves - 1) / kWaves, a.units);
-  hipLaunchKernelGGL((prefill_rows_simple<DT, D>), grid, dim3(kThreads), 0, s, a);
-  hipLaunchKernelGGL((prefill_columns_simple<DT, D>), grid, dim3(kThreads), 0, s, a);
+  {
+    ProfScope ps(kProfPrefillRows, s);
+    hipLaunchKernelGGL((prefill_rows_simple<DT, D>), grid, dim3(kThreads), 0, s, a);
+  }
+  {
+    ProfScope ps(kProfPrefillColumns, s);
+    hipLaunchKernelGGL((prefill_columns_simple<DT, D>), grid, dim3(kThreads), 0, s, a);
+  }
   return hipGetLastError();
 }
 

@@ -1,0 +1,28 @@
+// Optional HIP-event timing of one chosen kernel (benchmark aid; off by default).
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace roco {
+
+enum ProfKernel : int {
+  kProfDecodeSelect = 0, kProfDecodeAttend = 1, kProfDecodeCombine = 2,
+  kProfPrefillRows = 3, kProfPrefillColumns = 4, kProfPrefillSelect = 5, kProfPrefillGather = 6,
+  kProfKernels = 7
+};
+
+extern int g_prof_which;  // -1 = off
+void prof_record(hipStream_t s, bool begin);
+
+// Brackets one kernel launch with events when that kernel is the profiled one.
+struct ProfScope {
+  hipStream_t s;
+  bool on;
+  ProfScope(int which, hipStream_t stream) : s(stream), on(which == g_prof_which) {
+    if (on) prof_record(s, true);
+  }
+  ~ProfScope() {
+    if (on) prof_record(s, false);
+  }
+};
+
+}  // namespace roco

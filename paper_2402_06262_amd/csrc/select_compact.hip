@@ -11,6 +11,7 @@
 //   prefill_gather  : grid (row blocks, units): copies the retained K / V rows into the cache, 16 bytes per
 //                     lane.
 #include "kernels.hpp"
+#include "profile.hpp"
 #include "stream.hpp"
 
 namespace roco {
@@ -113,7 +114,11 @@ __global__ __launch_bounds__(kGatherThreads) void prefill_gather(PrefillArgs a) 
 }  // namespace
 
 hipError_t launch_prefill_select_compact(int dtype, int head_dim, const PrefillArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL(prefill_select, dim3(a.units), dim3(kSelThreads), 0, s, a);
+  {
+    ProfScope ps(kProfPrefillSelect, s);
+    hipLaunchKernelGGL(prefill_select, dim3(a.units), dim3(kSelThreads), 0, s, a);
+  }
+  ProfScope ps(kProfPrefillGather, s);
   const int row_bytes = head_dim * (dtype == kBF16 ? 2 : 4);
   const dim3 grid((a.B + kGatherRows - 1) / kGatherRows, a.units);
   switch (row_bytes) {

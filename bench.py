@@ -140,12 +140,12 @@ def main():
 
     def prefill():
         roco.roco_prefill_compress(p, dQ, dK, dV, dlen, L, cache.K, cache.V, cache.stats, cache.pos, cache.n_used,
-                                   O, ws_p, stream=stream)
+                                   cache.next_slot, O, ws_p, stream=stream)
 
     def decode():
         for t in range(decode_steps):
             roco.roco_decode_step(p, sq[t], sk[t], sv[t], qpos[t], cache.K, cache.V, cache.stats, cache.pos,
-                                  cache.n_used, out[t], ev_slot[t], ev_pos[t], ws_d, stream=stream)
+                                  cache.n_used, cache.next_slot, out[t], ev_slot[t], ev_pos[t], ws_d, stream=stream)
 
     for _ in range(args.warmup):
         prefill()
@@ -193,11 +193,11 @@ def main():
         ms, n = roco.roco_profile_read()
         pre_kernel_ms[name] = ms / max(1, n)
     dec_kernel_ms = {}
-    for name in ("decode_select", "decode_combine"):
+    for name in ("decode_finish",):
         roco.roco_profile_kernel(roco.PROF_KERNELS[name])
         for t in range(min(32, decode_steps)):
             roco.roco_decode_step(p, sq[t], sk[t], sv[t], qpos[t], cache.K, cache.V, cache.stats, cache.pos,
-                                  cache.n_used, out[t], ev_slot[t], ev_pos[t], ws_d, stream=stream)
+                                  cache.n_used, cache.next_slot, out[t], ev_slot[t], ev_pos[t], ws_d, stream=stream)
         torch.cuda.synchronize()
         ms, n = roco.roco_profile_read()
         dec_kernel_ms[name] = ms / max(1, n)

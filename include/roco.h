@@ -87,13 +87,15 @@ size_t roco_decode_workspace_bytes(const roco_params* params);
  * stats     out [units, 3, B]       fp32  planes Acc, Acc2, Count; unused slots are zeroed
  * pos       out [units, B]          int32 original position of each slot, -1 for unused slots
  * n_used    out [units]             int32 = min(len, B)
+ * next_slot out [units]             int32 slot the first decode step will overwrite if the unit is full (its
+ *                                   victim by the rule of section 4.3 on the compacted statistics), else -1
  * O         out [units, L_max, d]   dtype attention output of every prompt row, or NULL to skip it
  */
 int roco_prefill_compress(const roco_params* params,
                           const void* Q, const void* K, const void* V,
                           const int32_t* len, int32_t L_max,
                           void* K_cache, void* V_cache, float* stats, int32_t* pos, int32_t* n_used,
-                          void* O,
+                          int32_t* next_slot, void* O,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
@@ -104,6 +106,11 @@ int roco_prefill_compress(const roco_params* params,
  *   if n_used == B: scope = the s slots of lowest variance max(0, Acc2/Count - (Acc/Count)^2); victim =
  *   the slot of lowest Acc/Count inside it (equal keys: lowest slot first); slot = victim.
  *   else slot = n_used, n_used += 1, nothing evicted.
+ *   The victim depends only on the statistics left by the previous call, so the library chooses it at the
+ *   end of that call and keeps it in next_slot[u]; this call consumes it and, if the unit is full afterwards,
+ *   stores the victim of the following step.  next_slot is part of the cache state: it is written by
+ *   roco_prefill_compress and roco_decode_step, and must be refreshed with roco_select_victims if the caller
+ *   changes stats / n_used by other means.
  *   K_cache[slot] = k_new, V_cache[slot] = v_new, pos[slot] = qpos, the slot's three statistics = 0.
  *   p = softmax_j(scale q.K_cache[j] + bias(qpos, pos[j])) over the occupied slots; out = sum_j p_j V_cache[j]
  *   Acc += p, Acc2 += p^2, Count += 1 on the occupied slots                  (section 4.3)
@@ -114,14 +121,24 @@ int roco_prefill_compress(const roco_params* params,
  * stats            in/out  [units, 3, B]  fp32
  * pos              in/out  [units, B]     int32
  * n_used           in/out  [units]        int32
+ * next_slot        in/out  [units]        int32
  * out              out     [units, d]     dtype
  * evicted_slot, evicted_pos  out [units]  int32; -1 when the unit evicted nothing (either may be NULL)
  */
 int roco_decode_step(const roco_params* params,
                      const void* q, const void* k_new, const void* v_new, const int32_t* qpos,
                      void* K_cache, void* V_cache, float* stats, int32_t* pos, int32_t* n_used,
-                     void* out, int32_t* evicted_slot, int32_t* evicted_pos,
+                     int32_t* next_slot, void* out, int32_t* evicted_slot, int32_t* evicted_pos,
                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Victim selection alone (section 4.3): for every full unit, next_slot[u] = the slot of lowest Acc/Count among
+ * the s slots of lowest variance; -1 for units that are not full.  Only needed after the caller has edited
+ * stats / n_used itself.  stats in [units,3,B], n_used in [units], next_slot out [units]; the workspace is the
+ * decode workspace.
+ */
+int roco_select_victims(const roco_params* params, const float* stats, const int32_t* n_used,
+                        int32_t* next_slot, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Profiling aid (not part of the method; for benchmarks).  roco_profile_kernel(k) makes every later call
@@ -131,7 +148,7 @@ int roco_decode_step(const roco_params* params,
  * only resources the library ever creates) and is not thread-safe.  Returns 0 or a negative code.
  */
 enum {
-  ROCO_PROF_DECODE_SELECT = 0, ROCO_PROF_DECODE_ATTEND = 1, ROCO_PROF_DECODE_COMBINE = 2,
+  ROCO_PROF_DECODE_SELECT = 0, ROCO_PROF_DECODE_ATTEND = 1, ROCO_PROF_DECODE_FINISH = 2,
   ROCO_PROF_PREFILL_ROWS = 3, ROCO_PROF_PREFILL_COLUMNS = 4, ROCO_PROF_PREFILL_SELECT = 5,
   ROCO_PROF_PREFILL_GATHER = 6, ROCO_PROF_KERNELS = 7
 };

@@ -66,9 +66,11 @@ def load_library() -> ctypes.CDLL:
     lib.roco_decode_workspace_bytes.restype = sz
     lib.roco_decode_workspace_bytes.argtypes = [pp]
     lib.roco_prefill_compress.restype = ctypes.c_int
-    lib.roco_prefill_compress.argtypes = [pp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.roco_prefill_compress.argtypes = [pp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.roco_decode_step.restype = ctypes.c_int
-    lib.roco_decode_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.roco_decode_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.roco_select_victims.restype = ctypes.c_int
+    lib.roco_select_victims.argtypes = [pp, vp, vp, vp, vp, sz, vp]
     lib.roco_strerror.restype = ctypes.c_char_p
     lib.roco_strerror.argtypes = [ctypes.c_int]
     lib.roco_version.restype = ctypes.c_int
@@ -97,7 +99,7 @@ def decode_workspace_bytes(params: RocoParams) -> int:
     return int(load_library().roco_decode_workspace_bytes(ctypes.byref(params)))
 
 
-PROF_KERNELS = {"decode_select": 0, "decode_attend": 1, "decode_combine": 2, "prefill_rows": 3,
+PROF_KERNELS = {"decode_select": 0, "decode_attend": 1, "decode_finish": 2, "prefill_rows": 3,
                 "prefill_columns": 4, "prefill_select": 5, "prefill_gather": 6}
 
 
@@ -137,30 +139,42 @@ def _stream(stream) -> Optional[int]:
 
 
 def roco_prefill_compress(params: RocoParams, Q, K, V, length, L_max: int, K_cache, V_cache, stats, pos,
-                          n_used, O, workspace, workspace_bytes: Optional[int] = None, stream=None) -> None:
+                          n_used, next_slot, O, workspace, workspace_bytes: Optional[int] = None, stream=None) -> None:
     """See include/roco.h.  Tensors are device tensors; `O` may be None."""
     if workspace_bytes is None:
         workspace_bytes = workspace.numel() * workspace.element_size()
     rc = load_library().roco_prefill_compress(
         ctypes.byref(params), _ptr(Q), _ptr(K), _ptr(V), _ptr(length), int(L_max), _ptr(K_cache),
-        _ptr(V_cache), _ptr(stats), _ptr(pos), _ptr(n_used), _ptr(O), _ptr(workspace), int(workspace_bytes),
+        _ptr(V_cache), _ptr(stats), _ptr(pos), _ptr(n_used), _ptr(next_slot), _ptr(O), _ptr(workspace),
+        int(workspace_bytes),
         _stream(stream))
     if rc != 0:
         raise RocoError(rc, "roco_prefill_compress")
 
 
-def roco_decode_step(params: RocoParams, q, k_new, v_new, qpos, K_cache, V_cache, stats, pos, n_used, out,
-                     evicted_slot, evicted_pos, workspace, workspace_bytes: Optional[int] = None,
+def roco_decode_step(params: RocoParams, q, k_new, v_new, qpos, K_cache, V_cache, stats, pos, n_used, next_slot,
+                     out, evicted_slot, evicted_pos, workspace, workspace_bytes: Optional[int] = None,
                      stream=None) -> None:
     """See include/roco.h.  `evicted_slot` / `evicted_pos` may be None."""
     if workspace_bytes is None:
         workspace_bytes = workspace.numel() * workspace.element_size()
     rc = load_library().roco_decode_step(
         ctypes.byref(params), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(qpos), _ptr(K_cache), _ptr(V_cache),
-        _ptr(stats), _ptr(pos), _ptr(n_used), _ptr(out), _ptr(evicted_slot), _ptr(evicted_pos),
+        _ptr(stats), _ptr(pos), _ptr(n_used), _ptr(next_slot), _ptr(out), _ptr(evicted_slot), _ptr(evicted_pos),
         _ptr(workspace), int(workspace_bytes), _stream(stream))
     if rc != 0:
         raise RocoError(rc, "roco_decode_step")
+
+
+def roco_select_victims(params: RocoParams, stats, n_used, next_slot, workspace,
+                        workspace_bytes: Optional[int] = None, stream=None) -> None:
+    """See include/roco.h: recompute next_slot from stats / n_used."""
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    rc = load_library().roco_select_victims(ctypes.byref(params), _ptr(stats), _ptr(n_used), _ptr(next_slot),
+                                            _ptr(workspace), int(workspace_bytes), _stream(stream))
+    if rc != 0:
+        raise RocoError(rc, "roco_select_victims")
 
 
 @dataclass
@@ -172,6 +186,7 @@ class RocoCache:
     stats: "object"  # [units, 3, B] fp32: Acc, Acc2, Count
     pos: "object"  # [units, B] int32
     n_used: "object"  # [units] int32
+    next_slot: "object"  # [units] int32: victim already chosen for the next step (library-maintained)
 
 
 def alloc_cache(params: RocoParams, device="cuda") -> RocoCache:
@@ -184,4 +199,5 @@ def alloc_cache(params: RocoParams, device="cuda") -> RocoCache:
         torch.zeros((U, 3, B), dtype=torch.float32, device=device),
         torch.full((U, B), -1, dtype=torch.int32, device=device),
         torch.zeros((U,), dtype=torch.int32, device=device),
+        torch.full((U,), -1, dtype=torch.int32, device=device),
     )

@@ -61,8 +61,8 @@ int env_int(const char* name, int dflt) {
 }
 
 // Split the budget so that a step launches enough workgroups to cover 256 compute units several times.
-void choose_splits(const roco_params* p, int& splits, int& rows_per_split) {
-  const int gran = decode_rows_per_pass(p->dtype, p->head_dim);
+void choose_splits(const roco_params* p, int unroll, int& splits, int& rows_per_split) {
+  const int gran = decode_rows_per_pass(p->dtype, p->head_dim, unroll);
   const int max_splits_by_rows = (p->budget + gran - 1) / gran;
   int want = env_int("ROCO_DECODE_SPLITS", 0);
   if (want <= 0) {
@@ -94,12 +94,12 @@ size_t roco_decode_workspace_bytes(const roco_params* params) {
 
 int roco_prefill_compress(const roco_params* params, const void* Q, const void* K, const void* V,
                           const int32_t* len, int32_t L_max, void* K_cache, void* V_cache, float* stats,
-                          int32_t* pos, int32_t* n_used, void* O, void* workspace, size_t workspace_bytes,
-                          void* hip_stream) {
+                          int32_t* pos, int32_t* n_used, int32_t* next_slot, void* O, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
   const int rc = check_params(params);
   if (rc != ROCO_OK) return rc;
   if (L_max < 1 || L_max > (1 << 24)) return ROCO_EINVAL;
-  const void* need[] = {Q, K, V, len, K_cache, V_cache, stats, pos, n_used, workspace};
+  const void* need[] = {Q, K, V, len, K_cache, V_cache, stats, pos, n_used, next_slot, workspace};
   for (const void* ptr : need)
     if (ptr == nullptr || !aligned16(ptr)) return ROCO_EINVAL;
   if (O != nullptr && !aligned16(O)) return ROCO_EINVAL;
@@ -112,7 +112,7 @@ int roco_prefill_compress(const roco_params* params, const void* Q, const void* 
   a.recency_window = params->recency_window;
   a.recency_bias_log2 = params->recency_bias * 1.4426950408889634f;
   a.Q = Q; a.K = K; a.V = V; a.len = len;
-  a.K_cache = K_cache; a.V_cache = V_cache; a.stats = stats; a.pos = pos; a.n_used = n_used; a.O = O;
+  a.K_cache = K_cache; a.V_cache = V_cache; a.stats = stats; a.pos = pos; a.n_used = n_used; a.next_slot = next_slot; a.O = O;
   char* ws = static_cast<char*>(workspace);
   a.lse = reinterpret_cast<float*>(ws + lay.lse);
   a.acc = reinterpret_cast<float*>(ws + lay.acc);
@@ -132,11 +132,11 @@ int roco_prefill_compress(const roco_params* params, const void* Q, const void* 
 
 int roco_decode_step(const roco_params* params, const void* q, const void* k_new, const void* v_new,
                      const int32_t* qpos, void* K_cache, void* V_cache, float* stats, int32_t* pos,
-                     int32_t* n_used, void* out, int32_t* evicted_slot, int32_t* evicted_pos,
-                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+                     int32_t* n_used, int32_t* next_slot, void* out, int32_t* evicted_slot,
+                     int32_t* evicted_pos, void* workspace, size_t workspace_bytes, void* hip_stream) {
   const int rc = check_params(params);
   if (rc != ROCO_OK) return rc;
-  const void* need[] = {q, k_new, v_new, qpos, K_cache, V_cache, stats, pos, n_used, out, workspace};
+  const void* need[] = {q, k_new, v_new, qpos, K_cache, V_cache, stats, pos, n_used, next_slot, out, workspace};
   for (const void* ptr : need)
     if (ptr == nullptr || !aligned16(ptr)) return ROCO_EINVAL;
   const DecodeLayout lay = decode_layout(params);
@@ -144,12 +144,15 @@ int roco_decode_step(const roco_params* params, const void* q, const void* k_new
 
   DecodeArgs a;
   a.units = params->units; a.B = params->budget; a.scope = params->scope;
-  choose_splits(params, a.splits, a.rows_per_split);
+  a.unroll = env_int("ROCO_DECODE_UNROLL", 4);
+  if (a.unroll != 2 && a.unroll != 8) a.unroll = 4;
+  a.rotate = env_int("ROCO_DECODE_ROTATE", 1);
+  choose_splits(params, a.unroll, a.splits, a.rows_per_split);
   a.scale_log2 = scale_log2(params);
   a.recency_window = params->recency_window;
   a.recency_bias_log2 = params->recency_bias * 1.4426950408889634f;
   a.q = q; a.k_new = k_new; a.v_new = v_new; a.qpos = qpos;
-  a.K = K_cache; a.V = V_cache; a.stats = stats; a.pos = pos; a.n_used = n_used; a.out = out;
+  a.K = K_cache; a.V = V_cache; a.stats = stats; a.pos = pos; a.n_used = n_used; a.next_slot = next_slot; a.out = out;
   a.evicted_slot = evicted_slot; a.evicted_pos = evicted_pos;
   char* ws = static_cast<char*>(workspace);
   a.z = reinterpret_cast<float*>(ws + lay.z);
@@ -158,6 +161,25 @@ int roco_decode_step(const roco_params* params, const void* q, const void* k_new
   a.part_o = reinterpret_cast<float*>(ws + lay.part_o);
   a.keys = reinterpret_cast<uint32_t*>(ws + lay.keys);
   const hipError_t e = launch_decode(params->dtype, params->head_dim, a, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
+}
+
+int roco_select_victims(const roco_params* params, const float* stats, const int32_t* n_used,
+                        int32_t* next_slot, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const int rc = check_params(params);
+  if (rc != ROCO_OK) return rc;
+  const void* need[] = {stats, n_used, next_slot, workspace};
+  for (const void* ptr : need)
+    if (ptr == nullptr || !aligned16(ptr)) return ROCO_EINVAL;
+  const DecodeLayout lay = decode_layout(params);
+  if (workspace_bytes < lay.total) return ROCO_EWORKSPACE;
+  DecodeArgs a = {};
+  a.units = params->units; a.B = params->budget; a.scope = params->scope;
+  a.stats = const_cast<float*>(stats);
+  a.n_used = const_cast<int32_t*>(n_used);
+  a.next_slot = next_slot;
+  a.keys = reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + lay.keys);
+  const hipError_t e = launch_select_victims(a, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
 }
 

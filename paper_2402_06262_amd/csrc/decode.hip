@@ -1,17 +1,22 @@
-// RoCo decode step on gfx950: victim selection + in-place slot overwrite, split-K attention over the
-// budgeted cache, and the combine that also updates Acc / Acc2 / Count (section 4.3 of the paper; Fig. 1:
-// one key/value pair is deleted before the next token's is appended).
+// RoCo decode step on gfx950 (section 4.3 of the paper; Fig. 1: one key/value pair is deleted before the
+// next token's is appended; section 5.3: decoding is I/O-bounded).
 //
-// Three kernels per step, all on the caller's stream:
-//   1. decode_select_update : one workgroup per unit.  If the unit's buffer is full, rank the slots by
-//      attention variance, take the `scope` lowest as the eviction scope and pick the slot of lowest mean
-//      attention score inside it; then write k_new / v_new / qpos into the slot and zero its statistics.
-//   2. decode_attend        : grid (splits, units).  Streams K and V of its slot range once with 128-bit
-//      loads, keeps an online softmax per lane group, stores every base-2 logit, writes one partial
-//      (max, sum, weighted V sum) per split.  HBM-bound: no matrix cores.
-//   3. decode_combine_stats : grid (slot blocks, units).  Merges the partials in split order (fixed order:
-//      results do not depend on scheduling), writes the attention output, and adds p, p^2 and 1 into the
-//      three statistics planes.
+// The victim of step t+1 depends only on the statistics as they stand after step t, so it is chosen at the
+// end of step t, while the updated statistics are still in registers, and kept in `next_slot[unit]` (part
+// of the cache state).  A step is then two kernels on the caller's stream:
+//
+//   decode_attend : grid (splits, units).  The slot the new token goes to is next_slot[u] when the buffer is
+//     full, else n_used[u].  Streams K and V of its slot range once with 128-bit loads; the one row that is
+//     being overwritten is taken from k_new / v_new instead (and written into the cache in passing).  Keeps
+//     an online softmax per 16-lane group, stores every base-2 logit, writes one partial (max, sum, weighted
+//     V sum) per split.  HBM-bound: no matrix cores.
+//   decode_finish : one workgroup per unit.  Merges the partials in split order (fixed order: results do not
+//     depend on scheduling), writes the attention output, adds p, p^2 and 1 into the three statistics planes
+//     (the overwritten slot starts from zero), records pos / n_used / evicted_*, and, if the buffer is now
+//     full, selects the next victim: scope = the `scope` slots of lowest variance, victim = lowest mean
+//     attention score inside it.
+//
+//   select_victims : the selection alone (for a cache whose statistics were produced elsewhere).
 #include "kernels.hpp"
 #include "profile.hpp"
 #include "stream.hpp"
@@ -21,116 +26,67 @@ namespace {
 
 constexpr int kAttendThreads = 256;
 constexpr int kAttendWaves = kAttendThreads / kWave;
-constexpr int kAttendUnroll = 4;
-constexpr int kCombineThreads = 256;
-constexpr int kCombineSlots = 1024;  // slots per combine workgroup
+constexpr int kFinishThreads = kDecodeSelectThreads;
 
-// ------------------------------------------------------------------------------------------------
-template <int DT, int D>
-__global__ __launch_bounds__(kDecodeSelectThreads) void decode_select_update(DecodeArgs a) {
-  constexpr int NT = kDecodeSelectThreads;
-  using G = RowGeom<DT, D>;
-  extern __shared__ uint32_t lds_keys[];  // [2][B] when B <= kMaxDecodeBudgetLds
-  __shared__ uint32_t sel_sh[256 + NT / kWave + 3];
-  __shared__ unsigned long long best_sh[NT / kWave];
-  __shared__ int slot_sh;
-
-  const int u = blockIdx.x, tid = threadIdx.x;
-  const int B = a.B;
-  const int n = a.n_used[u];
-  float* acc = a.stats + static_cast<size_t>(u) * 3 * B;
-  float* acc2 = acc + B;
-  float* cnt = acc2 + B;
-  int32_t* pos = a.pos + static_cast<size_t>(u) * B;
-
-  int slot, ev_slot = -1, ev_pos = -1;
-  if (n < B) {
-    slot = n;
-  } else {
-    uint32_t* var_key = (B <= kMaxDecodeBudgetLds) ? lds_keys : a.keys + static_cast<size_t>(u) * 2 * B;
-    uint32_t* mas_key = var_key + B;
-    for (int i = tid; i < B; i += NT) {
-      uint32_t mk, vk;
-      ranking_keys(acc[i], acc2[i], cnt[i], mk, vk);
-      var_key[i] = vk;
-      mas_key[i] = mk;
+// Scope = `scope` lowest variance keys among [0, B); returns the slot of lowest MAS key inside it (lowest
+// slot on equal keys).  Every thread of the block calls it and gets the same answer.
+template <int NT>
+__device__ int select_victim_block(const uint32_t* var_key, const uint32_t* mas_key, int B, int scope,
+                                   uint32_t* sel_sh, unsigned long long* best_sh) {
+  const int tid = threadIdx.x;
+  const KSmallest sc = select_k_smallest<NT>([&](int i) { return var_key[i]; }, B,
+                                             static_cast<uint32_t>(scope), sel_sh);
+  unsigned long long best = ~0ull;
+  for (int i = tid; i < B; i += NT) {
+    if (sc.has(var_key[i], i)) {
+      const unsigned long long cand =
+          (static_cast<unsigned long long>(mas_key[i]) << 32) | static_cast<uint32_t>(i);
+      best = cand < best ? cand : best;
     }
-    __syncthreads();
-    const KSmallest sc = select_k_smallest<NT>([&](int i) { return var_key[i]; }, B,
-                                               static_cast<uint32_t>(a.scope), sel_sh);
-    // lowest mean attention score inside the scope; equal scores go to the lowest slot
-    unsigned long long best = ~0ull;
-    for (int i = tid; i < B; i += NT) {
-      if (sc.has(var_key[i], i)) {
-        const unsigned long long cand = (static_cast<unsigned long long>(mas_key[i]) << 32) | static_cast<uint32_t>(i);
-        best = cand < best ? cand : best;
-      }
-    }
+  }
 #pragma unroll
-    for (int m = 1; m < kWave; m <<= 1) {
-      const unsigned long long o = __shfl_xor(best, m, kWave);
-      best = o < best ? o : best;
-    }
-    if ((tid & (kWave - 1)) == 0) best_sh[tid / kWave] = best;
-    __syncthreads();
-    if (tid == 0) {
-      unsigned long long b = best_sh[0];
-      for (int w = 1; w < NT / kWave; ++w) b = best_sh[w] < b ? best_sh[w] : b;
-      slot_sh = static_cast<int>(b & 0xffffffffu);
-    }
-    __syncthreads();
-    slot = slot_sh;
-    ev_slot = slot;
-    ev_pos = pos[slot];
+  for (int m = 1; m < kWave; m <<= 1) {
+    const unsigned long long o = __shfl_xor(best, m, kWave);
+    best = o < best ? o : best;
   }
-  __syncthreads();  // every thread has read pos[slot] / n_used before they change
-
-  // overwrite the slot in place: the cache never grows past B and is never reallocated
-  const size_t row = (static_cast<size_t>(u) * B + slot) * G::ROW_BYTES;
-  const size_t in_row = static_cast<size_t>(u) * G::ROW_BYTES;
-  if (tid < G::LPR) {
-    *reinterpret_cast<uint4*>(static_cast<char*>(a.K) + row + tid * 16) =
-        load16(static_cast<const char*>(a.k_new) + in_row + tid * 16);
-  } else if (tid >= kWave && tid < kWave + G::LPR) {
-    const int t = tid - kWave;
-    *reinterpret_cast<uint4*>(static_cast<char*>(a.V) + row + t * 16) =
-        load16(static_cast<const char*>(a.v_new) + in_row + t * 16);
-  } else if (tid == 2 * kWave) {
-    pos[slot] = a.qpos[u];
-    acc[slot] = 0.0f;
-    acc2[slot] = 0.0f;
-    cnt[slot] = 0.0f;
-    if (n < B) a.n_used[u] = n + 1;
-    if (a.evicted_slot) a.evicted_slot[u] = ev_slot;
-    if (a.evicted_pos) a.evicted_pos[u] = ev_pos;
-  }
+  __syncthreads();
+  if ((tid & (kWave - 1)) == 0) best_sh[tid / kWave] = best;
+  __syncthreads();
+  unsigned long long b = best_sh[0];
+#pragma unroll
+  for (int w = 1; w < NT / kWave; ++w) b = best_sh[w] < b ? best_sh[w] : b;
+  return static_cast<int>(b & 0xffffffffu);
 }
 
 // ------------------------------------------------------------------------------------------------
-template <int DT, int D>
+template <int DT, int D, int U>
 __global__ __launch_bounds__(kAttendThreads) void decode_attend(DecodeArgs a) {
   using G = RowGeom<DT, D>;
-  constexpr int U = kAttendUnroll;
   constexpr int STREAMS = kAttendWaves;  // one merged stream per wave reaches LDS
+  constexpr int PASS = kAttendWaves * U * G::R;
   __shared__ float sm_m[STREAMS], sm_l[STREAMS];
   __shared__ float sm_acc[STREAMS][D];
 
   const int u = blockIdx.y, split = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int c = lane % G::LPR;
-  const int n = a.n_used[u];
+  const int n0 = a.n_used[u];
+  const bool full = n0 >= a.B;
+  const int slot = full ? min(max(a.next_slot[u], 0), a.B - 1) : n0;  // where the new token goes
+  const int n = full ? a.B : n0 + 1;
   const int row0 = split * a.rows_per_split;
   const int row1 = min(n, row0 + a.rows_per_split);
 
+  const size_t in_off = static_cast<size_t>(u) * G::ROW_BYTES + c * 16;
   float qf[G::EPL];
-  {
-    const uint4 qw = load16(static_cast<const char*>(a.q) + static_cast<size_t>(u) * G::ROW_BYTES + c * 16);
-    unpack16<DT>(qw, qf);
+  unpack16<DT>(load16(static_cast<const char*>(a.q) + in_off), qf);
 #pragma unroll
-    for (int e = 0; e < G::EPL; ++e) qf[e] *= a.scale_log2;
-  }
-  const char* Kb = static_cast<const char*>(a.K) + static_cast<size_t>(u) * a.B * G::ROW_BYTES;
-  const char* Vb = static_cast<const char*>(a.V) + static_cast<size_t>(u) * a.B * G::ROW_BYTES;
+  for (int e = 0; e < G::EPL; ++e) qf[e] *= a.scale_log2;
+  const uint4 knew = load16(static_cast<const char*>(a.k_new) + in_off);
+  const uint4 vnew = load16(static_cast<const char*>(a.v_new) + in_off);
+
+  char* Kb = static_cast<char*>(a.K) + static_cast<size_t>(u) * a.B * G::ROW_BYTES;
+  char* Vb = static_cast<char*>(a.V) + static_cast<size_t>(u) * a.B * G::ROW_BYTES;
   float* z = a.z + static_cast<size_t>(u) * a.B;
   const int32_t* pos = a.pos + static_cast<size_t>(u) * a.B;
   const int qp = a.qpos[u];
@@ -141,11 +97,26 @@ __global__ __launch_bounds__(kAttendThreads) void decode_attend(DecodeArgs a) {
   st.reset();
   auto bias = [&](int row) -> float {
     if (w <= 0) return 0.0f;
-    const int dlt = qp - pos[row];
+    const int dlt = (row == slot) ? 0 : qp - pos[row];
     return (dlt >= 0 && dlt < w) ? rb : 0.0f;
   };
   auto zstore = [&](int row, float t) { z[row] = t; };
-  stream_attend<DT, D, U>(qf, Kb, Vb, row0 + wave * (U * G::R), row1, kAttendWaves * U * G::R, bias, zstore, st);
+  auto fix = [&](int row, uint4& kw, uint4& vw, int col) {
+    if (row == slot && row < row1) {  // in-place overwrite: the cache never grows past B
+      kw = knew;
+      vw = vnew;
+      const size_t off = static_cast<size_t>(row) * G::ROW_BYTES + col * 16;
+      *reinterpret_cast<uint4*>(Kb + off) = knew;
+      *reinterpret_cast<uint4*>(Vb + off) = vnew;
+    }
+  };
+  const int span = row1 - row0;
+  const int passes = span > 0 ? (span + PASS - 1) / PASS : 0;
+  const int rot = passes > 0 ? static_cast<int>((static_cast<unsigned>(u) * 5u + static_cast<unsigned>(split) * 3u) %
+                                                static_cast<unsigned>(passes))
+                             : 0;
+  stream_attend<DT, D, U>(qf, Kb, Vb, row0, row1, passes, a.rotate ? rot : 0, PASS, wave * (U * G::R), bias, zstore,
+                          fix, st);
   merge_groups_in_wave<DT, D>(st);
 
   if (lane < G::LPR) {
@@ -173,13 +144,22 @@ __global__ __launch_bounds__(kAttendThreads) void decode_attend(DecodeArgs a) {
 
 // ------------------------------------------------------------------------------------------------
 template <int DT, int D>
-__global__ __launch_bounds__(kCombineThreads) void decode_combine_stats(DecodeArgs a) {
-  const int u = blockIdx.y, blk = blockIdx.x, tid = threadIdx.x;
+__global__ __launch_bounds__(kFinishThreads) void decode_finish(DecodeArgs a) {
+  constexpr int NT = kFinishThreads;
+  extern __shared__ uint32_t lds_keys[];  // [2][B] when B <= kMaxDecodeBudgetLds
+  __shared__ uint32_t sel_sh[256 + NT / kWave + 3];
+  __shared__ unsigned long long best_sh[NT / kWave];
+
+  const int u = blockIdx.x, tid = threadIdx.x;
   const int B = a.B, S = a.splits;
-  const int n = a.n_used[u];
+  const int n0 = a.n_used[u];
+  const bool was_full = n0 >= B;
+  const int slot = was_full ? min(max(a.next_slot[u], 0), B - 1) : n0;
+  const int n = was_full ? B : n0 + 1;
+  const bool full = n >= B;
+
   const float* pm = a.part_m + static_cast<size_t>(u) * S;
   const float* pl = a.part_l + static_cast<size_t>(u) * S;
-
   // every thread merges the (few) partial normalisers in split order
   float M = -INFINITY;
   for (int s = 0; s < S; ++s) M = fmaxf(M, pm[s]);
@@ -187,7 +167,7 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_stats(DecodeAr
   for (int s = 0; s < S; ++s) Lsum += (pm[s] > -INFINITY) ? pl[s] * exp2f(pm[s] - M) : 0.0f;
   const float inv = 1.0f / Lsum;
 
-  if (blk == 0 && tid < D) {
+  if (tid < D) {
     const float* po = a.part_o + static_cast<size_t>(u) * S * D;
     float o = 0.0f;
     for (int s = 0; s < S; ++s) o += (pm[s] > -INFINITY) ? po[s * D + tid] * exp2f(pm[s] - M) : 0.0f;
@@ -198,43 +178,113 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_stats(DecodeAr
   float* acc2 = acc + B;
   float* cnt = acc2 + B;
   const float* z = a.z + static_cast<size_t>(u) * B;
-  const int lo = blk * kCombineSlots;
-  const int hi = min(n, lo + kCombineSlots);
-  for (int j = lo + tid; j < hi; j += kCombineThreads) {
-    const float p = exp2f(z[j] - M) * inv;
-    acc[j] += p;
-    acc2[j] += p * p;
-    cnt[j] += 1.0f;
+  int32_t* pos = a.pos + static_cast<size_t>(u) * B;
+  uint32_t* var_key = (B <= kMaxDecodeBudgetLds) ? lds_keys : a.keys + static_cast<size_t>(u) * 2 * B;
+  uint32_t* mas_key = var_key + B;
+
+  if ((B & 3) == 0) {
+    // four adjacent slots per thread, 128-bit accesses on every plane
+    for (int j = tid * 4; j < n; j += NT * 4) {
+      const float4 zz = *reinterpret_cast<const float4*>(z + j);
+      float4 a1 = *reinterpret_cast<const float4*>(acc + j);
+      float4 a2 = *reinterpret_cast<const float4*>(acc2 + j);
+      float4 cc = *reinterpret_cast<const float4*>(cnt + j);
+      const float zv[4] = {zz.x, zz.y, zz.z, zz.w};
+      float s1[4] = {a1.x, a1.y, a1.z, a1.w}, s2[4] = {a2.x, a2.y, a2.z, a2.w}, sc[4] = {cc.x, cc.y, cc.z, cc.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int jj = j + e;
+        if (jj < n) {
+          if (jj == slot) { s1[e] = 0.0f; s2[e] = 0.0f; sc[e] = 0.0f; }
+          const float p = exp2f(zv[e] - M) * inv;
+          s1[e] += p;
+          s2[e] += p * p;
+          sc[e] += 1.0f;
+          if (full) ranking_keys(s1[e], s2[e], sc[e], mas_key[jj], var_key[jj]);
+        }
+      }
+      *reinterpret_cast<float4*>(acc + j) = make_float4(s1[0], s1[1], s1[2], s1[3]);
+      *reinterpret_cast<float4*>(acc2 + j) = make_float4(s2[0], s2[1], s2[2], s2[3]);
+      *reinterpret_cast<float4*>(cnt + j) = make_float4(sc[0], sc[1], sc[2], sc[3]);
+    }
+  } else {
+    for (int j = tid; j < n; j += NT) {
+      float s1 = acc[j], s2 = acc2[j], sc = cnt[j];
+      if (j == slot) { s1 = 0.0f; s2 = 0.0f; sc = 0.0f; }
+      const float p = exp2f(z[j] - M) * inv;
+      s1 += p;
+      s2 += p * p;
+      sc += 1.0f;
+      acc[j] = s1; acc2[j] = s2; cnt[j] = sc;
+      if (full) ranking_keys(s1, s2, sc, mas_key[j], var_key[j]);
+    }
   }
+  if (tid == 0) {
+    const int old_pos = pos[slot];
+    pos[slot] = a.qpos[u];
+    a.n_used[u] = n;
+    if (a.evicted_slot) a.evicted_slot[u] = was_full ? slot : -1;
+    if (a.evicted_pos) a.evicted_pos[u] = was_full ? old_pos : -1;
+  }
+  if (full) {
+    __syncthreads();
+    const int victim = select_victim_block<NT>(var_key, mas_key, B, a.scope, sel_sh, best_sh);
+    if (tid == 0) a.next_slot[u] = victim;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kFinishThreads) void select_victims(DecodeArgs a) {
+  constexpr int NT = kFinishThreads;
+  extern __shared__ uint32_t lds_keys[];
+  __shared__ uint32_t sel_sh[256 + NT / kWave + 3];
+  __shared__ unsigned long long best_sh[NT / kWave];
+  const int u = blockIdx.x, tid = threadIdx.x;
+  const int B = a.B;
+  if (a.n_used[u] < B) {
+    if (tid == 0) a.next_slot[u] = -1;
+    return;
+  }
+  const float* acc = a.stats + static_cast<size_t>(u) * 3 * B;
+  const float* acc2 = acc + B;
+  const float* cnt = acc2 + B;
+  uint32_t* var_key = (B <= kMaxDecodeBudgetLds) ? lds_keys : a.keys + static_cast<size_t>(u) * 2 * B;
+  uint32_t* mas_key = var_key + B;
+  for (int i = tid; i < B; i += NT) ranking_keys(acc[i], acc2[i], cnt[i], mas_key[i], var_key[i]);
+  __syncthreads();
+  const int victim = select_victim_block<NT>(var_key, mas_key, B, a.scope, sel_sh, best_sh);
+  if (tid == 0) a.next_slot[u] = victim;
+}
+
+template <int DT, int D, int U>
+void launch_attend(const DecodeArgs& a, hipStream_t s) {
+  ProfScope ps(kProfDecodeAttend, s);
+  hipLaunchKernelGGL((decode_attend<DT, D, U>), dim3(a.splits, a.units), dim3(kAttendThreads), 0, s, a);
 }
 
 template <int DT, int D>
 hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t s) {
   const size_t lds = (a.B <= kMaxDecodeBudgetLds) ? static_cast<size_t>(a.B) * 2 * sizeof(uint32_t) : 0;
-  {
-    ProfScope ps(kProfDecodeSelect, s);
-    hipLaunchKernelGGL((decode_select_update<DT, D>), dim3(a.units), dim3(kDecodeSelectThreads), lds, s, a);
+  switch (a.unroll) {
+    case 2: launch_attend<DT, D, 2>(a, s); break;
+    case 8: launch_attend<DT, D, 8>(a, s); break;
+    default: launch_attend<DT, D, 4>(a, s); break;
   }
   {
-    ProfScope ps(kProfDecodeAttend, s);
-    hipLaunchKernelGGL((decode_attend<DT, D>), dim3(a.splits, a.units), dim3(kAttendThreads), 0, s, a);
-  }
-  {
-    ProfScope ps(kProfDecodeCombine, s);
-    hipLaunchKernelGGL((decode_combine_stats<DT, D>),
-                       dim3((a.B + kCombineSlots - 1) / kCombineSlots, a.units), dim3(kCombineThreads), 0, s, a);
+    ProfScope ps(kProfDecodeFinish, s);
+    hipLaunchKernelGGL((decode_finish<DT, D>), dim3(a.units), dim3(kFinishThreads), lds, s, a);
   }
   return hipGetLastError();
 }
 
 }  // namespace
 
-// Rows one decode_attend workgroup covers per pass over its waves, for the given shape; the host picks
-// rows_per_split as a multiple of it.
-int decode_rows_per_pass(int dtype, int head_dim) {
+// Rows one decode_attend workgroup covers per pass over its waves, for the given shape and unroll; the host
+// picks rows_per_split as a multiple of it.
+int decode_rows_per_pass(int dtype, int head_dim, int unroll) {
   const int epl = dtype == kBF16 ? 8 : 4;
   const int lpr = head_dim / epl;
-  return kAttendWaves * kAttendUnroll * (kWave / lpr);
+  return kAttendWaves * unroll * (kWave / lpr);
 }
 
 hipError_t launch_decode(int dtype, int head_dim, const DecodeArgs& a, hipStream_t s) {
@@ -243,6 +293,13 @@ hipError_t launch_decode(int dtype, int head_dim, const DecodeArgs& a, hipStream
   if (dtype == kBF16 && head_dim == 64) return launch_decode_t<kBF16, 64>(a, s);
   if (dtype == kBF16 && head_dim == 128) return launch_decode_t<kBF16, 128>(a, s);
   return hipErrorInvalidValue;
+}
+
+hipError_t launch_select_victims(const DecodeArgs& a, hipStream_t s) {
+  const size_t lds = (a.B <= kMaxDecodeBudgetLds) ? static_cast<size_t>(a.B) * 2 * sizeof(uint32_t) : 0;
+  ProfScope ps(kProfDecodeSelect, s);
+  hipLaunchKernelGGL(select_victims, dim3(a.units), dim3(kFinishThreads), lds, s, a);
+  return hipGetLastError();
 }
 
 }  // namespace roco

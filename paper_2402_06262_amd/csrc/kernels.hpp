@@ -12,6 +12,8 @@ constexpr int kMaxDecodeBudgetLds = 4096;  // keys of a unit kept in LDS by the 
 
 struct DecodeArgs {
   int units, B, scope, splits, rows_per_split;
+  int unroll;            // rows in flight per lane group in decode_attend: 2, 4 or 8
+  int rotate;            // stagger the start offset of every workgroup inside its slot range
   float scale_log2;      // scale * log2(e)
   int recency_window;
   float recency_bias_log2;
@@ -20,6 +22,7 @@ struct DecodeArgs {
   void *K, *V;
   float* stats;          // [units][3][B]
   int32_t *pos, *n_used;
+  int32_t* next_slot;    // [units] victim chosen for the next step (valid while the unit is full)
   void* out;
   int32_t *evicted_slot, *evicted_pos;
   // workspace
@@ -40,6 +43,7 @@ struct PrefillArgs {
   void *K_cache, *V_cache;
   float* stats;          // [units][3][B]
   int32_t *pos, *n_used;
+  int32_t* next_slot;    // [units]
   void* O;               // may be null
   // workspace
   float* lse;            // [units][L_max]  base-2 log-sum-exp of every query row
@@ -51,7 +55,8 @@ struct PrefillArgs {
 
 // dtype: 0 = f32, 1 = bf16; head_dim: 64 or 128.  Each returns hipGetLastError() of its launches.
 hipError_t launch_decode(int dtype, int head_dim, const DecodeArgs& a, hipStream_t s);
-int decode_rows_per_pass(int dtype, int head_dim);  // granularity of DecodeArgs::rows_per_split
+int decode_rows_per_pass(int dtype, int head_dim, int unroll);  // granularity of DecodeArgs::rows_per_split
+hipError_t launch_select_victims(const DecodeArgs& a, hipStream_t s);  // uses stats, n_used, next_slot, keys
 hipError_t launch_prefill_attention_simple(int dtype, int head_dim, const PrefillArgs& a, hipStream_t s);
 hipError_t launch_prefill_attention_mfma(const PrefillArgs& a, hipStream_t s);  // bf16, head_dim 128
 hipError_t launch_prefill_select_compact(int dtype, int head_dim, const PrefillArgs& a, hipStream_t s);

@@ -5,7 +5,7 @@
 namespace roco {
 
 enum ProfKernel : int {
-  kProfDecodeSelect = 0, kProfDecodeAttend = 1, kProfDecodeCombine = 2,
+  kProfDecodeSelect = 0, kProfDecodeAttend = 1, kProfDecodeFinish = 2,
   kProfPrefillRows = 3, kProfPrefillColumns = 4, kProfPrefillSelect = 5, kProfPrefillGather = 6,
   kProfKernels = 7
 };

@@ -25,6 +25,7 @@ __global__ __launch_bounds__(kSelThreads) void prefill_select(PrefillArgs a) {
   constexpr int NT = kSelThreads;
   __shared__ uint32_t sel_sh[256 + NT / kWave + 3];
   __shared__ uint32_t scan_sh[NT / kWave + 1];
+  __shared__ unsigned long long best_sh[NT / kWave];
   const int u = blockIdx.x, tid = threadIdx.x;
   const int B = a.B;
   const int n = a.len[u];
@@ -83,6 +84,37 @@ __global__ __launch_bounds__(kSelThreads) void prefill_select(PrefillArgs a) {
     ocnt[i] = 0.0f;
   }
   if (tid == 0) a.n_used[u] = kept;
+  // the first decode step on a full cache needs its victim: choose it now, from the compacted statistics
+  if (kept == B) {
+    __syncthreads();  // the compacted planes written above are visible to the whole block
+    for (int i = tid; i < B; i += NT) ranking_keys(oacc[i], oacc2[i], ocnt[i], mas_key[i], var_key[i]);
+    __syncthreads();
+    const KSmallest sc = select_k_smallest<NT>([&](int i) { return var_key[i]; }, B,
+                                               static_cast<uint32_t>(a.scope), sel_sh);
+    unsigned long long best = ~0ull;
+    for (int i = tid; i < B; i += NT) {
+      if (sc.has(var_key[i], i)) {
+        const unsigned long long cand =
+            (static_cast<unsigned long long>(mas_key[i]) << 32) | static_cast<uint32_t>(i);
+        best = cand < best ? cand : best;
+      }
+    }
+#pragma unroll
+    for (int m = 1; m < kWave; m <<= 1) {
+      const unsigned long long o = __shfl_xor(best, m, kWave);
+      best = o < best ? o : best;
+    }
+    __syncthreads();
+    if ((tid & (kWave - 1)) == 0) best_sh[tid / kWave] = best;
+    __syncthreads();
+    if (tid == 0) {
+      unsigned long long b = best_sh[0];
+      for (int w = 1; w < NT / kWave; ++w) b = best_sh[w] < b ? best_sh[w] : b;
+      a.next_slot[u] = static_cast<int>(b & 0xffffffffu);
+    }
+  } else if (tid == 0) {
+    a.next_slot[u] = -1;
+  }
 }
 
 template <int ROW_BYTES>

@@ -27,24 +27,31 @@ template <int EPL> struct FlashState {
   }
 };
 
-// Attend rows {base + u*R + g : base = first, first + stride, ... ; u < U} intersected with [0, row_end).
-// qf holds this lane's slice of the query already multiplied by scale*log2(e).  bias(row) is added to the
-// base-2 logit; zstore(row, t) receives every logit once (from the first lane of the row's group).
-template <int DT, int D, int U, class BiasFn, class ZStore>
+// Attend the rows of [row_begin, row_end) that belong to this wave.  The range is cut into `passes` blocks
+// of `pass_rows` rows; inside a block this wave owns rows wave_off + u*R + g (u < U).  Blocks are visited in
+// rotated order starting at block `rot` (softmax does not care about order): workgroups that start at the
+// same time then begin at different offsets inside their ranges instead of marching over the same HBM
+// channels in lock step.  qf holds this lane's slice of the query already multiplied by scale*log2(e).
+// bias(row) is added to the base-2 logit; zstore(row, t) receives every logit once (from the first lane of
+// the row's group); fix(row, kw, vw, c) may replace the loaded 16 bytes of a row (the slot being overwritten).
+template <int DT, int D, int U, class BiasFn, class ZStore, class FixFn>
 __device__ __forceinline__ void stream_attend(const float* qf, const char* Kbase, const char* Vbase,
-                                              int first, int row_end, int stride,
-                                              BiasFn bias, ZStore zstore,
+                                              int row_begin, int row_end, int passes, int rot, int pass_rows,
+                                              int wave_off, BiasFn bias, ZStore zstore, FixFn fix,
                                               FlashState<RowGeom<DT, D>::EPL>& st) {
   using G = RowGeom<DT, D>;
   const int lane = threadIdx.x & (kWave - 1);
   const int g = lane / G::LPR, c = lane % G::LPR;
-  for (int base = first; base < row_end; base += stride) {
+  int blk = rot;
+  for (int it = 0; it < passes; ++it) {
+    const int base = row_begin + blk * pass_rows + wave_off;
+    blk = (blk + 1 == passes) ? 0 : blk + 1;
     uint4 kw[U], vw[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int row = base + u * G::R + g;
       const bool ok = row < row_end;
-      const size_t off = static_cast<size_t>(ok ? row : 0) * G::ROW_BYTES + c * 16;
+      const size_t off = static_cast<size_t>(ok ? row : row_begin) * G::ROW_BYTES + c * 16;
       kw[u] = load16(Kbase + off);
       vw[u] = load16(Vbase + off);
     }
@@ -53,6 +60,7 @@ __device__ __forceinline__ void stream_attend(const float* qf, const char* Kbase
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int row = base + u * G::R + g;
+      fix(row, kw[u], vw[u], c);
       float kf[G::EPL];
       unpack16<DT>(kw[u], kf);
       float dot = 0.0f;

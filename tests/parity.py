@@ -113,7 +113,7 @@ def gpu_prefill(sess: GpuSession, Q: np.ndarray, K: np.ndarray, V: np.ndarray, l
     sess.prefill_ws = torch.empty(max(16, roco.prefill_workspace_bytes(p, L_max)), dtype=torch.uint8, device="cuda")
     sess.O = torch.zeros_like(dQ) if want_out else None
     c = sess.cache
-    roco.roco_prefill_compress(p, dQ, dK, dV, dlen, L_max, c.K, c.V, c.stats, c.pos, c.n_used, sess.O, sess.prefill_ws)
+    roco.roco_prefill_compress(p, dQ, dK, dV, dlen, L_max, c.K, c.V, c.stats, c.pos, c.n_used, c.next_slot, sess.O, sess.prefill_ws)
     torch.cuda.synchronize()
     return dict(K=to_host(c.K), V=to_host(c.V), stats=to_host(c.stats), pos=to_host(c.pos),
                 n_used=to_host(c.n_used), O=None if sess.O is None else to_host(sess.O))
@@ -165,7 +165,7 @@ def gpu_decode_step(sess: GpuSession, q: np.ndarray, k: np.ndarray, v: np.ndarra
     c, p = sess.cache, sess.params
     dq, dk, dv = to_dev(q, sess.dtype), to_dev(k, sess.dtype), to_dev(v, sess.dtype)
     dqpos = torch.tensor(list(qpos), dtype=torch.int32, device="cuda")
-    roco.roco_decode_step(p, dq, dk, dv, dqpos, c.K, c.V, c.stats, c.pos, c.n_used, sess.out,
+    roco.roco_decode_step(p, dq, dk, dv, dqpos, c.K, c.V, c.stats, c.pos, c.n_used, c.next_slot, sess.out,
                           sess.ev_slot, sess.ev_pos, sess.decode_ws)
     torch.cuda.synchronize()
     return to_host(sess.out), to_host(sess.ev_slot), to_host(sess.ev_pos)

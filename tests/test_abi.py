@@ -22,7 +22,7 @@ def test_library_loads_and_exports_every_declared_symbol():
     lib = roco.load_library()
     names = declared_functions()
     assert {"roco_prefill_compress", "roco_decode_step", "roco_prefill_workspace_bytes",
-            "roco_decode_workspace_bytes", "roco_strerror", "roco_version"} <= set(names)
+            "roco_decode_workspace_bytes", "roco_strerror", "roco_version", "roco_select_victims"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in roco.h but not exported"
     assert roco.roco_version() == 1
@@ -48,13 +48,13 @@ def test_workspace_queries():
 def _decode(p, ptrs=None, ws_bytes=1 << 30):
     lib = roco.load_library()
     a = [0x1000] * 14 if ptrs is None else ptrs
-    return lib.roco_decode_step(ctypes.byref(p), *a[:13], ws_bytes, None)
+    return lib.roco_decode_step(ctypes.byref(p), *a[:14], ws_bytes, None)
 
 
 def _prefill(p, L_max=64, ptrs=None, ws_bytes=1 << 30):
     lib = roco.load_library()
     a = [0x1000] * 12 if ptrs is None else ptrs
-    return lib.roco_prefill_compress(ctypes.byref(p), a[0], a[1], a[2], a[3], L_max, *a[4:11], ws_bytes, None)
+    return lib.roco_prefill_compress(ctypes.byref(p), a[0], a[1], a[2], a[3], L_max, *a[4:12], ws_bytes, None)
 
 
 @pytest.mark.parametrize("kw,code", [
@@ -73,17 +73,17 @@ def test_invalid_params_are_rejected_on_the_host(kw, code):
 def test_null_misaligned_and_small_workspace_are_rejected_on_the_host():
     p = roco.RocoParams(4, 64, 128, 16, roco.ROCO_F32)
     lib = roco.load_library()
-    assert lib.roco_decode_step(None, *([0x1000] * 13), 1 << 30, None) == EINVAL
-    for bad in range(11):  # the eleven required pointers (evicted_* are optional)
-        ptrs = [0x1000] * 13
-        order = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 12]
+    assert lib.roco_decode_step(None, *([0x1000] * 14), 1 << 30, None) == EINVAL
+    for bad in range(12):  # the twelve required pointers (evicted_* are optional)
+        ptrs = [0x1000] * 14
+        order = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 13]
         ptrs[order[bad]] = None
         assert _decode(p, ptrs) == EINVAL
         ptrs[order[bad]] = 0x1004
         assert _decode(p, ptrs) == EINVAL
     assert _decode(p, ws_bytes=roco.decode_workspace_bytes(p) - 1) == EWORKSPACE
-    for bad in [0, 1, 2, 3, 4, 5, 6, 7, 8, 10]:  # O (index 9) may be NULL
-        ptrs = [0x1000] * 11
+    for bad in [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 11]:  # O (index 10) may be NULL
+        ptrs = [0x1000] * 12
         ptrs[bad] = None
         assert _prefill(p, ptrs=ptrs) == EINVAL
     assert _prefill(p, L_max=0) == EINVAL

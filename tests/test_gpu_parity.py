@@ -158,3 +158,42 @@ def test_exact_ties_go_to_the_lowest_index():
     H = np.cumsum(1.0 / np.arange(1, L + 1))
     acc = H[-1] - np.concatenate([[0.0], H[:-1]])
     assert np.allclose(res.full.acc, acc, rtol=1e-12)
+
+
+def test_budget_above_the_lds_key_limit_uses_the_workspace_keys():
+    """B > 4096: the selection keeps its ranking keys in the workspace instead of LDS."""
+    run_workload("bf16", 64, 1, [4300], 4300, 4100, 33, 5, seed=21, want_out=False, tag="b4100")
+
+
+def test_select_victims_entry_point_reproduces_the_maintained_hint():
+    """roco_select_victims on the current statistics gives the same next_slot the decode step keeps."""
+    import paper_2402_06262_amd as roco
+    P = _parity()
+    rng = np.random.default_rng(3)
+    units, L, B, s, d = 5, 150, 64, 9, 128
+    Q = round_to_bf16(rng.standard_normal((units, L + 6, d)).astype(np.float32))
+    K = round_to_bf16(rng.standard_normal((units, L + 6, d)).astype(np.float32))
+    V = round_to_bf16(rng.standard_normal((units, L + 6, d)).astype(np.float32))
+    lens = [150, 64, 63, 10, 100]
+    sess = P.make_session(units, d, B, s, "bf16")
+    P.gpu_prefill(sess, Q[:, :L].copy(), K[:, :L].copy(), V[:, :L].copy(), lens, False)
+    for step in range(6):
+        c = sess.cache
+        fresh = torch.full((units,), -5, dtype=torch.int32, device="cuda")
+        roco.roco_select_victims(sess.params, c.stats, c.n_used, fresh, sess.decode_ws)
+        torch.cuda.synchronize()
+        full = (c.n_used == B).cpu().numpy()
+        got, kept = fresh.cpu().numpy(), c.next_slot.cpu().numpy()
+        assert np.array_equal(got[full], kept[full]), (step, got, kept)
+        assert np.all(got[~full] == -1)
+        # and the oracle agrees on the statistics the GPU holds (same fp32 values, widened)
+        st = c.stats.cpu().numpy().astype(np.float64)
+        for u in np.flatnonzero(full):
+            mas = orc.mean_attention_score(st[u, 0], st[u, 2])
+            var = np.maximum(0.0, (st[u, 1].astype(np.float32) / st[u, 2].astype(np.float32)
+                                   - (st[u, 0].astype(np.float32) / st[u, 2].astype(np.float32)) ** 2).astype(np.float64))
+            # fp32 keys, as the kernel ranks them; ties resolved by lowest slot on both sides
+            mas32 = (st[u, 0].astype(np.float32) / st[u, 2].astype(np.float32)).astype(np.float64)
+            assert orc.select_victim(mas32, var, s) == int(got[u])
+        t = L + step
+        P.gpu_decode_step(sess, Q[:, t], K[:, t], V[:, t], [l + step for l in lens])

@@ -54,10 +54,22 @@ template <> __device__ __forceinline__ void store_elem<kBF16>(void* base, size_t
 __device__ __forceinline__ uint4 load16(const void* p) { return *static_cast<const uint4*>(p); }
 
 // ---------------------------------------------------------------- cross-lane
+// Lane exchange inside a 16-lane row through the data-parallel-primitive path of the vector ALU (no LDS
+// traffic).  CTRL: 0xB1 = swap neighbours, 0x4E = swap pairs, 0x141 = mirror each 8 lanes, 0x140 = mirror
+// each 16 lanes.  After the two swaps every lane of a quad holds the quad's value, so the two mirrors act
+// as the xor-4 and xor-8 steps of a butterfly.
+template <int CTRL> __device__ __forceinline__ float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+
 // All-reduce (sum) over aligned groups of LANES lanes (LANES a power of two <= 64).
 template <int LANES> __device__ __forceinline__ float group_sum(float v) {
+  if (LANES >= 2) v += dpp_move<0xB1>(v);
+  if (LANES >= 4) v += dpp_move<0x4E>(v);
+  if (LANES >= 8) v += dpp_move<0x141>(v);
+  if (LANES >= 16) v += dpp_move<0x140>(v);
 #pragma unroll
-  for (int m = 1; m < LANES; m <<= 1) v += __shfl_xor(v, m, kWave);
+  for (int m = 16; m < LANES; m <<= 1) v += __shfl_xor(v, m, kWave);
   return v;
 }
 template <int LANES> __device__ __forceinline__ float group_max(float v) {

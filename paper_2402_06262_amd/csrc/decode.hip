@@ -82,8 +82,6 @@ __global__ __launch_bounds__(kAttendThreads) void decode_attend(DecodeArgs a) {
   unpack16<DT>(load16(static_cast<const char*>(a.q) + in_off), qf);
 #pragma unroll
   for (int e = 0; e < G::EPL; ++e) qf[e] *= a.scale_log2;
-  const uint4 knew = load16(static_cast<const char*>(a.k_new) + in_off);
-  const uint4 vnew = load16(static_cast<const char*>(a.v_new) + in_off);
 
   char* Kb = static_cast<char*>(a.K) + static_cast<size_t>(u) * a.B * G::ROW_BYTES;
   char* Vb = static_cast<char*>(a.V) + static_cast<size_t>(u) * a.B * G::ROW_BYTES;
@@ -96,18 +94,20 @@ __global__ __launch_bounds__(kAttendThreads) void decode_attend(DecodeArgs a) {
   FlashState<G::EPL> st;
   st.reset();
   auto bias = [&](int row) -> float {
-    if (w <= 0) return 0.0f;
     const int dlt = (row == slot) ? 0 : qp - pos[row];
     return (dlt >= 0 && dlt < w) ? rb : 0.0f;
   };
-  auto zstore = [&](int row, float t) { z[row] = t; };
-  auto fix = [&](int row, uint4& kw, uint4& vw, int col) {
-    if (row == slot && row < row1) {  // in-place overwrite: the cache never grows past B
-      kw = knew;
-      vw = vnew;
-      const size_t off = static_cast<size_t>(row) * G::ROW_BYTES + col * 16;
-      *reinterpret_cast<uint4*>(Kb + off) = knew;
-      *reinterpret_cast<uint4*>(Vb + off) = vnew;
+  // in-place overwrite of the slot the new token takes: the cache never grows past B
+  auto fix_k = [&](int row, uint4& kw, int col) {
+    if (row == slot && row < row1) {
+      kw = load16(static_cast<const char*>(a.k_new) + in_off);
+      *reinterpret_cast<uint4*>(Kb + static_cast<size_t>(row) * G::ROW_BYTES + col * 16) = kw;
+    }
+  };
+  auto fix_v = [&](int row, uint4& vw, int col) {
+    if (row == slot && row < row1) {
+      vw = load16(static_cast<const char*>(a.v_new) + in_off);
+      *reinterpret_cast<uint4*>(Vb + static_cast<size_t>(row) * G::ROW_BYTES + col * 16) = vw;
     }
   };
   const int span = row1 - row0;
@@ -115,8 +115,12 @@ __global__ __launch_bounds__(kAttendThreads) void decode_attend(DecodeArgs a) {
   const int rot = passes > 0 ? static_cast<int>((static_cast<unsigned>(u) * 5u + static_cast<unsigned>(split) * 3u) %
                                                 static_cast<unsigned>(passes))
                              : 0;
-  stream_attend<DT, D, U>(qf, Kb, Vb, row0, row1, passes, a.rotate ? rot : 0, PASS, wave * (U * G::R), bias, zstore,
-                          fix, st);
+  if (w > 0)
+    stream_attend<DT, D, U, true>(qf, Kb, Vb, row0, row1, passes, a.rotate ? rot : 0, PASS, wave * (U * G::R), bias, z,
+                                  slot, fix_k, fix_v, st);
+  else
+    stream_attend<DT, D, U, false>(qf, Kb, Vb, row0, row1, passes, a.rotate ? rot : 0, PASS, wave * (U * G::R), bias, z,
+                                   slot, fix_k, fix_v, st);
   merge_groups_in_wave<DT, D>(st);
 
   if (lane < G::LPR) {
@@ -133,7 +137,7 @@ __global__ __launch_bounds__(kAttendThreads) void decode_attend(DecodeArgs a) {
     float o = 0.0f, l = 0.0f;
 #pragma unroll
     for (int s = 0; s < STREAMS; ++s) {
-      const float wgt = (sm_m[s] > -INFINITY) ? exp2f(sm_m[s] - M) : 0.0f;
+      const float wgt = (sm_m[s] > -INFINITY) ? fast_exp2(sm_m[s] - M) : 0.0f;
       l += sm_l[s] * wgt;
       o += sm_acc[s][tid] * wgt;
     }
@@ -164,13 +168,13 @@ __global__ __launch_bounds__(kFinishThreads) void decode_finish(DecodeArgs a) {
   float M = -INFINITY;
   for (int s = 0; s < S; ++s) M = fmaxf(M, pm[s]);
   float Lsum = 0.0f;
-  for (int s = 0; s < S; ++s) Lsum += (pm[s] > -INFINITY) ? pl[s] * exp2f(pm[s] - M) : 0.0f;
+  for (int s = 0; s < S; ++s) Lsum += (pm[s] > -INFINITY) ? pl[s] * fast_exp2(pm[s] - M) : 0.0f;
   const float inv = 1.0f / Lsum;
 
   if (tid < D) {
     const float* po = a.part_o + static_cast<size_t>(u) * S * D;
     float o = 0.0f;
-    for (int s = 0; s < S; ++s) o += (pm[s] > -INFINITY) ? po[s * D + tid] * exp2f(pm[s] - M) : 0.0f;
+    for (int s = 0; s < S; ++s) o += (pm[s] > -INFINITY) ? po[s * D + tid] * fast_exp2(pm[s] - M) : 0.0f;
     store_elem<DT>(a.out, static_cast<size_t>(u) * D + tid, o * inv);
   }
 
@@ -196,7 +200,7 @@ __global__ __launch_bounds__(kFinishThreads) void decode_finish(DecodeArgs a) {
         const int jj = j + e;
         if (jj < n) {
           if (jj == slot) { s1[e] = 0.0f; s2[e] = 0.0f; sc[e] = 0.0f; }
-          const float p = exp2f(zv[e] - M) * inv;
+          const float p = fast_exp2(zv[e] - M) * inv;
           s1[e] += p;
           s2[e] += p * p;
           sc[e] += 1.0f;
@@ -211,7 +215,7 @@ __global__ __launch_bounds__(kFinishThreads) void decode_finish(DecodeArgs a) {
     for (int j = tid; j < n; j += NT) {
       float s1 = acc[j], s2 = acc2[j], sc = cnt[j];
       if (j == slot) { s1 = 0.0f; s2 = 0.0f; sc = 0.0f; }
-      const float p = exp2f(z[j] - M) * inv;
+      const float p = fast_exp2(z[j] - M) * inv;
       s1 += p;
       s2 += p * p;
       sc += 1.0f;

@@ -39,10 +39,12 @@ __global__ __launch_bounds__(kThreads) void prefill_rows_simple(PrefillArgs a) {
   FlashState<G::EPL> st;
   st.reset();
   auto bias = [&](int row) -> float { return (i - row < w) ? rb : 0.0f; };  // row <= i here
-  auto zstore = [](int, float) {};
-  auto fix = [](int, uint4&, uint4&, int) {};
+  auto fix = [](int, uint4&, int) {};
   constexpr int PASS = kUnroll * G::R;
-  stream_attend<DT, D, kUnroll>(qf, Kb, Vb, 0, i + 1, (i + PASS) / PASS, 0, PASS, 0, bias, zstore, fix, st);
+  if (w > 0)
+    stream_attend<DT, D, kUnroll, true>(qf, Kb, Vb, 0, i + 1, (i + PASS) / PASS, 0, PASS, 0, bias, nullptr, -1, fix, fix, st);
+  else
+    stream_attend<DT, D, kUnroll, false>(qf, Kb, Vb, 0, i + 1, (i + PASS) / PASS, 0, PASS, 0, bias, nullptr, -1, fix, fix, st);
   merge_groups_in_wave<DT, D>(st);
   if (lane == 0) a.lse[ubase + i] = st.m + log2f(st.l);
   if (a.O != nullptr && lane < G::LPR) {

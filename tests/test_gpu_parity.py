@@ -197,3 +197,30 @@ def test_select_victims_entry_point_reproduces_the_maintained_hint():
             assert orc.select_victim(mas32, var, s) == int(got[u])
         t = L + step
         P.gpu_decode_step(sess, Q[:, t], K[:, t], V[:, t], [l + step for l in lens])
+
+
+@pytest.mark.parametrize("recency", [False, True])
+def test_matrix_core_prefill_statistics_ragged_lengths(recency):
+    """bf16 / head_dim 128 without the attention output runs the matrix-core kernels: lengths around every tile
+    edge (32-row wave tiles, 64-row streamed tiles, 128-row workgroup tiles), with and without the recency bias."""
+    lens = [1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 191, 193, 300, 517]
+    kw = dict(recency_window=64, recency_bias=0.5) if recency else {}
+    run_workload("bf16", 128, len(lens), lens, 517, 100, 12, 3, seed=31, want_out=False, tag=f"mfma-ragged-{recency}", **kw)
+
+
+def test_matrix_core_prefill_matches_vector_path_bitwise_decisions(monkeypatch):
+    """Same inputs through the matrix-core kernels and through the vector-ALU kernels: retained sets agree and
+    the statistics agree to fp32 rounding (the two paths differ only in summation order)."""
+    P = _parity()
+    rng = np.random.default_rng(41)
+    units, L, B, s, d = 3, 700, 256, 32, 128
+    Q = round_to_bf16(rng.standard_normal((units, L, d)).astype(np.float32) + 0.3)
+    K = round_to_bf16(rng.standard_normal((units, L, d)).astype(np.float32))
+    V = round_to_bf16(rng.standard_normal((units, L, d)).astype(np.float32))
+    res = {}
+    for mode in ("0", "1"):
+        monkeypatch.setenv("ROCO_PREFILL_SIMPLE", mode)
+        sess = P.make_session(units, d, B, s, "bf16")
+        res[mode] = P.gpu_prefill(sess, Q, K, V, [700, 650, 300], False)
+    assert np.array_equal(res["0"]["pos"], res["1"]["pos"])
+    assert np.allclose(res["0"]["stats"], res["1"]["stats"], rtol=2e-5, atol=1e-9)

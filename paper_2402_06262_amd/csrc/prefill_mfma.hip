@@ -5,9 +5,10 @@
 //   pass 1  prefill_rows_mfma    : row normalisers -- base-2 log-sum-exp of every query row (section 2.1 eq. 1)
 //   pass 2  prefill_columns_mfma : Acc[j] = sum_i P[i,j], Acc2[j] = sum_i P[i,j]^2 in fp32 (section 4.3)
 //
-// Both passes have the same shape.  A workgroup owns 128 rows of one operand (queries in pass 1, keys in
-// pass 2), 32 per wave, held in registers as the B operand of v_mfma_f32_32x32x16_bf16; the other operand is
-// streamed through LDS in tiles of 64 rows (A operand).  The 32x32 result tile then has the *owned* row in the
+// Both passes have the same shape.  A workgroup owns 256 rows of one operand (queries in pass 1, keys in
+// pass 2), two groups of 32 per wave, held in registers as B operands of v_mfma_f32_32x32x16_bf16; the other
+// operand is streamed through LDS in tiles of 64 rows (A operand, each fragment feeding two instructions).
+// The 32x32 result tile then has the *owned* row in the
 // lane (column = lane % 32) and the streamed rows in the 16 accumulator registers, so the reduction the pass
 // needs (over keys in pass 1, over queries in pass 2) runs down the registers of a lane: no cross-lane traffic
 // per tile, no atomics, a fixed summation order.
@@ -28,7 +29,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int D = 128;
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
-constexpr int kOwn = 32 * kWaves;        // owned rows per workgroup
+constexpr int kOwn = 64 * kWaves;        // owned rows per workgroup: two groups of 32 per wave
 constexpr int kTile = 64;                // streamed rows per LDS tile
 constexpr int kRowBytes = D * 2;         // 256
 constexpr int kLdsRow = kRowBytes + 16;  // padded: 16 lanes x 16 B then hit distinct bank groups
@@ -55,18 +56,35 @@ __device__ __forceinline__ void tile_store(const Staged& s, char* lds) {
     *reinterpret_cast<uint4*>(lds + ((t >> 4) + 16 * i) * kLdsRow + (t & 15) * 16) = s.w[i];
 }
 
-// One 32x32 score tile: streamed rows [sub*32, sub*32+32) of the LDS tile against this wave's owned rows.
-__device__ __forceinline__ f32x16 score_tile(const char* lds, int sub, const uint4* own) {
+// Two 32x32 score tiles: streamed rows [sub*32, sub*32+32) of the LDS tile against the wave's two groups of
+// 32 owned rows.  Every A fragment read from LDS feeds two matrix instructions (halves the LDS traffic per flop
+// and gives the matrix pipe two independent accumulator chains).
+__device__ __forceinline__ void score_tiles(const char* lds, int sub, const uint4* own0, const uint4* own1,
+                                            bool do0, bool do1, f32x16& acc0, f32x16& acc1) {
   const int lane = threadIdx.x & (kWave - 1);
   const char* p = lds + (sub * 32 + (lane & 31)) * kLdsRow + (lane >> 5) * 16;
-  f32x16 acc = {0};
+  acc0 = f32x16{0};
+  acc1 = f32x16{0};
+  if (do0 && do1) {
 #pragma unroll
-  for (int kk = 0; kk < kKSteps; ++kk) {
-    const uint4 a = *reinterpret_cast<const uint4*>(p + kk * 32);
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, own[kk]),
-                                                  acc, 0, 0, 0);
+    for (int kk = 0; kk < kKSteps; ++kk) {
+      const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p + kk * 32));
+      acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, own0[kk]), acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, own1[kk]), acc1, 0, 0, 0);
+    }
+  } else if (do0) {
+#pragma unroll
+    for (int kk = 0; kk < kKSteps; ++kk) {
+      const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p + kk * 32));
+      acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, own0[kk]), acc0, 0, 0, 0);
+    }
+  } else if (do1) {
+#pragma unroll
+    for (int kk = 0; kk < kKSteps; ++kk) {
+      const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p + kk * 32));
+      acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, own1[kk]), acc1, 0, 0, 0);
+    }
   }
-  return acc;
 }
 
 __device__ __forceinline__ void load_owned(uint4* own, const char* base, int row, int last_row) {
@@ -77,70 +95,154 @@ __device__ __forceinline__ void load_owned(uint4* own, const char* base, int row
     own[kk] = load16(base + static_cast<size_t>(row) * kRowBytes + kk * 32 + (lane >> 5) * 16);
 }
 
+__device__ __forceinline__ float max16(const f32x16& s) {
+  float a = fmaxf(fmaxf(s[0], s[1]), s[2]);   // the compiler folds these into three-operand maxima
+  a = fmaxf(fmaxf(a, s[3]), s[4]);
+  a = fmaxf(fmaxf(a, s[5]), s[6]);
+  a = fmaxf(fmaxf(a, s[7]), s[8]);
+  a = fmaxf(fmaxf(a, s[9]), s[10]);
+  a = fmaxf(fmaxf(a, s[11]), s[12]);
+  a = fmaxf(fmaxf(a, s[13]), s[14]);
+  return fmaxf(a, s[15]);
+}
+
+// Online log-sum-exp update of one lane with the 16 scores of a tile.
+//   INTERIOR: every key of the tile is visible to every query of the group and there is no bias:
+//             3 vector instructions per score (multiply-add, exponential, add) plus 8 for the maximum.
+template <bool INTERIOR>
+__device__ __forceinline__ void lse_update(const f32x16& s, float sc, int kb, int half, int qi, int w, float rb,
+                                           float& m, float& l) {
+  if (INTERIOR) {
+    const float m_new = fmaxf(m, max16(s) * sc);
+    const float neg = -m_new;
+    float sum0 = 0.0f, sum1 = 0.0f;
+#pragma unroll
+    for (int r = 0; r < 16; r += 2) {
+      sum0 += fast_exp2(fmaf(s[r], sc, neg));
+      sum1 += fast_exp2(fmaf(s[r + 1], sc, neg));
+    }
+    l = fmaf(l, fast_exp2(m - m_new), sum0 + sum1);
+    m = m_new;
+  } else {
+    float tv[16];
+    float mb = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int key = kb + 8 * (r >> 2) + 4 * half + (r & 3);
+      float x = s[r] * sc;
+      if (w > 0 && qi - key < w) x += rb;
+      if (key > qi) x = -INFINITY;
+      tv[r] = x;
+      mb = fmaxf(mb, x);
+    }
+    const float m_new = fmaxf(m, mb);
+    if (m_new > -INFINITY) {
+      float sum = 0.0f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sum += fast_exp2(tv[r] - m_new);
+      l = l * fast_exp2(m - m_new) + sum;
+      m = m_new;
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------------
 // pass 1: lse[i] = log2 sum_{j<=i} 2^(t_ij),  t_ij = scale*log2(e) * q_i.k_j + bias
 __global__ __launch_bounds__(kThreads) void prefill_rows_mfma(PrefillArgs a) {
   __shared__ __attribute__((aligned(16))) char lds[2][kTile * kLdsRow];
   const int u = blockIdx.y;
   const int len = a.len[u];
-  const int q0 = (gridDim.x - 1 - blockIdx.x) * kOwn;  // long rows first
-  if (q0 >= len) return;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int half = lane >> 5;
   const size_t ubase = static_cast<size_t>(u) * a.L_max;
   const char* Qb = static_cast<const char*>(a.Q) + ubase * kRowBytes;
   const char* Kb = static_cast<const char*>(a.K) + ubase * kRowBytes;
-  const int qw0 = q0 + 32 * wave;      // first query of this wave
-  const int qi = qw0 + (lane & 31);    // this lane's query
-  const int half = lane >> 5;
-  uint4 own[kKSteps];
-  load_owned(own, Qb, qi, len - 1);
-
   const float sc = a.scale_log2;
   const int w = a.recency_window;
   const float rb = a.recency_bias_log2;
-  float m = -INFINITY, l = 0.0f;
+  const int n_blocks = (len + kOwn - 1) / kOwn;
+  if (2 * static_cast<int>(blockIdx.x) > n_blocks - 1) return;  // this unit is short: the pair is someone else's
 
-  const int last_key = min(len, q0 + kOwn) - 1;  // keys 0..last_key are visible to some query of the block
-  const int n_tiles = last_key / kTile + 1;
-  Staged st;
-  tile_load(st, Kb, 0, len - 1);
-  for (int t = 0; t < n_tiles; ++t) {
-    tile_store(st, lds[t & 1]);
-    __syncthreads();
-    if (t + 1 < n_tiles) tile_load(st, Kb, (t + 1) * kTile, len - 1);
-    const int k0 = t * kTile;
+  // A workgroup takes one long and one short block of queries (blocks b and n-1-b), so that every workgroup of
+  // a unit does the same amount of work whatever its position under the causal diagonal.
+  for (int pass = 0; pass < 2; ++pass) {
+    const int blk = pass == 0 ? static_cast<int>(blockIdx.x) : n_blocks - 1 - static_cast<int>(blockIdx.x);
+    if (blk < static_cast<int>(blockIdx.x) || (pass == 1 && blk == static_cast<int>(blockIdx.x))) break;
+    const int q0 = blk * kOwn;
+    const int qw0 = q0 + 64 * wave;  // first query of this wave
+    const int qi0 = qw0 + (lane & 31), qi1 = qi0 + 32;
+    uint4 own0[kKSteps], own1[kKSteps];
+    load_owned(own0, Qb, qi0, len - 1);
+    load_owned(own1, Qb, qi1, len - 1);
+    float m0 = -INFINITY, l0 = 0.0f, m1 = -INFINITY, l1 = 0.0f;
+
+    const int last_key = min(len, q0 + kOwn) - 1;  // keys 0..last_key are visible to some query of the block
+    const int n_tiles = last_key / kTile + 1;
+    Staged st;
+    tile_load(st, Kb, 0, len - 1);
+    __syncthreads();  // the previous pass has finished with the LDS buffers
+    for (int t = 0; t < n_tiles; ++t) {
+      tile_store(st, lds[t & 1]);
+      __syncthreads();
+      if (t + 1 < n_tiles) tile_load(st, Kb, (t + 1) * kTile, len - 1);
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
-      const int kb = k0 + sub * 32;
-      if (kb > qw0 + 31) continue;  // wholly above the diagonal for every query of this wave
-      const f32x16 s = score_tile(lds[t & 1], sub, own);
-      const bool diag = kb + 31 > qw0;  // some (key, query) pairs of the tile violate key <= query
-      float tv[16];
-      float mb = -INFINITY;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = kb + 8 * (r >> 2) + 4 * half + (r & 3);
-        float x = s[r] * sc;
-        if (w > 0 && qi - key < w) x += rb;
-        if (diag && key > qi) x = -INFINITY;
-        tv[r] = x;
-        mb = fmaxf(mb, x);
-      }
-      const float m_new = fmaxf(m, mb);
-      if (m_new > -INFINITY) {
-        float sum = 0.0f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sum += fast_exp2(tv[r] - m_new);
-        l = l * fast_exp2(m - m_new) + sum;
-        m = m_new;
+      for (int sub = 0; sub < 2; ++sub) {
+        const int kb = t * kTile + sub * 32;
+        const bool do0 = kb <= qw0 + 31, do1 = kb <= qw0 + 63;  // not wholly above the diagonal
+        if (!do1) continue;
+        f32x16 s0, s1;
+        score_tiles(lds[t & 1], sub, own0, own1, do0, do1, s0, s1);
+        if (do0) {
+          if (w == 0 && kb + 31 <= qw0) lse_update<true>(s0, sc, kb, half, qi0, w, rb, m0, l0);
+          else lse_update<false>(s0, sc, kb, half, qi0, w, rb, m0, l0);
+        }
+        if (w == 0 && kb + 31 <= qw0 + 32) lse_update<true>(s1, sc, kb, half, qi1, w, rb, m1, l1);
+        else lse_update<false>(s1, sc, kb, half, qi1, w, rb, m1, l1);
       }
     }
+    // the two lane halves hold different keys of the same query
+    {
+      const float mo = __shfl_xor(m0, 32, kWave), lo = __shfl_xor(l0, 32, kWave);
+      const float mn = fmaxf(m0, mo);
+      const float tot = (m0 > -INFINITY ? l0 * fast_exp2(m0 - mn) : 0.0f) + (mo > -INFINITY ? lo * fast_exp2(mo - mn) : 0.0f);
+      if (half == 0 && qi0 < len) a.lse[ubase + qi0] = mn + log2f(tot);
+    }
+    {
+      const float mo = __shfl_xor(m1, 32, kWave), lo = __shfl_xor(l1, 32, kWave);
+      const float mn = fmaxf(m1, mo);
+      const float tot = (m1 > -INFINITY ? l1 * fast_exp2(m1 - mn) : 0.0f) + (mo > -INFINITY ? lo * fast_exp2(mo - mn) : 0.0f);
+      if (half == 0 && qi1 < len) a.lse[ubase + qi1] = mn + log2f(tot);
+    }
   }
-  // the two lane halves hold different keys of the same query
-  const float m_o = __shfl_xor(m, 32, kWave), l_o = __shfl_xor(l, 32, kWave);
-  const float m_new = fmaxf(m, m_o);
-  const float tot = (m > -INFINITY ? l * fast_exp2(m - m_new) : 0.0f) + (m_o > -INFINITY ? l_o * fast_exp2(m_o - m_new) : 0.0f);
-  if (half == 0 && qi < len) a.lse[ubase + qi] = m_new + log2f(tot);
+}
+
+// Column-statistics update of one lane (one key) with the 16 scores of a tile (16 queries).
+template <bool INTERIOR>
+__device__ __forceinline__ void column_update(const f32x16& s, const float* lse_tile, float sc, int ib, int half,
+                                              int kj, int len, int w, float rb, float& s1, float& s2) {
+  float a1 = 0.0f, a2 = 0.0f, b1 = 0.0f, b2 = 0.0f;
+#pragma unroll
+  for (int g4 = 0; g4 < 4; ++g4) {
+    const float4 ls = *reinterpret_cast<const float4*>(lse_tile + 8 * g4 + 4 * half);
+    const float lv[4] = {ls.x, ls.y, ls.z, ls.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float x = fmaf(s[4 * g4 + e], sc, -lv[e]);
+      float p;
+      if (INTERIOR) {
+        p = fast_exp2(x);
+      } else {
+        const int qi = ib + 8 * g4 + 4 * half + e;
+        if (w > 0 && qi - kj < w) x += rb;
+        p = fast_exp2(x);
+        if (qi < kj || qi >= len) p = 0.0f;
+      }
+      if (e & 1) { b1 += p; b2 = fmaf(p, p, b2); }
+      else       { a1 += p; a2 = fmaf(p, p, a2); }
+    }
+  }
+  s1 += a1 + b1;
+  s2 += a2 + b2;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -150,68 +252,68 @@ __global__ __launch_bounds__(kThreads) void prefill_columns_mfma(PrefillArgs a) 
   __shared__ __attribute__((aligned(16))) float lse_s[2][kTile];
   const int u = blockIdx.y;
   const int len = a.len[u];
-  const int j0 = blockIdx.x * kOwn;  // low key blocks have the longest columns and come first
-  if (j0 >= len) return;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int half = lane >> 5;
   const size_t ubase = static_cast<size_t>(u) * a.L_max;
   const char* Qb = static_cast<const char*>(a.Q) + ubase * kRowBytes;
   const char* Kb = static_cast<const char*>(a.K) + ubase * kRowBytes;
   const float* lse = a.lse + ubase;
-  const int kw0 = j0 + 32 * wave;
-  const int kj = kw0 + (lane & 31);  // this lane's key
-  const int half = lane >> 5;
-  uint4 own[kKSteps];
-  load_owned(own, Kb, kj, len - 1);
-
   const float sc = a.scale_log2;
   const int w = a.recency_window;
   const float rb = a.recency_bias_log2;
-  float s1 = 0.0f, s2 = 0.0f;
+  const int n_blocks = (len + kOwn - 1) / kOwn;
+  if (2 * static_cast<int>(blockIdx.x) > n_blocks - 1) return;
 
-  const int t_first = j0 / kTile;            // first query tile with a query >= j0
-  const int t_last = (len - 1) / kTile;
-  Staged st;
-  tile_load(st, Qb, t_first * kTile, len - 1);
-  float lse_st = 0.0f;
-  if (threadIdx.x < kTile) lse_st = lse[min(t_first * kTile + static_cast<int>(threadIdx.x), len - 1)];
-  for (int t = t_first; t <= t_last; ++t) {
-    const int b = (t - t_first) & 1;
-    tile_store(st, lds[b]);
-    if (threadIdx.x < kTile) lse_s[b][threadIdx.x] = lse_st;
-    __syncthreads();
-    if (t < t_last) {
-      tile_load(st, Qb, (t + 1) * kTile, len - 1);
-      if (threadIdx.x < kTile) lse_st = lse[min((t + 1) * kTile + static_cast<int>(threadIdx.x), len - 1)];
-    }
-    const int i0 = t * kTile;
+  for (int pass = 0; pass < 2; ++pass) {  // one long and one short block of keys per workgroup
+    const int blk = pass == 0 ? static_cast<int>(blockIdx.x) : n_blocks - 1 - static_cast<int>(blockIdx.x);
+    if (blk < static_cast<int>(blockIdx.x) || (pass == 1 && blk == static_cast<int>(blockIdx.x))) break;
+    const int j0 = blk * kOwn;
+    const int kw0 = j0 + 64 * wave;
+    const int kj0 = kw0 + (lane & 31), kj1 = kj0 + 32;  // this lane's two keys
+    uint4 own0[kKSteps], own1[kKSteps];
+    load_owned(own0, Kb, kj0, len - 1);
+    load_owned(own1, Kb, kj1, len - 1);
+    float s1a = 0.0f, s2a = 0.0f, s1b = 0.0f, s2b = 0.0f;
+
+    const int t_first = j0 / kTile;  // first query tile with a query >= j0
+    const int t_last = (len - 1) / kTile;
+    Staged st;
+    tile_load(st, Qb, t_first * kTile, len - 1);
+    float lse_st = 0.0f;
+    if (threadIdx.x < kTile) lse_st = lse[min(t_first * kTile + static_cast<int>(threadIdx.x), len - 1)];
+    __syncthreads();  // the previous pass has finished with the LDS buffers
+    for (int t = t_first; t <= t_last; ++t) {
+      const int b = (t - t_first) & 1;
+      tile_store(st, lds[b]);
+      if (threadIdx.x < kTile) lse_s[b][threadIdx.x] = lse_st;
+      __syncthreads();
+      if (t < t_last) {
+        tile_load(st, Qb, (t + 1) * kTile, len - 1);
+        if (threadIdx.x < kTile) lse_st = lse[min((t + 1) * kTile + static_cast<int>(threadIdx.x), len - 1)];
+      }
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
-      const int ib = i0 + sub * 32;
-      if (ib + 31 < kw0) continue;  // every query of the tile precedes every key of this wave
-      const f32x16 s = score_tile(lds[b], sub, own);
-      const bool edge = ib < kw0 + 31 || ib + 31 >= len;  // diagonal tile, or the ragged end of the prompt
-#pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        const float4 ls = *reinterpret_cast<const float4*>(&lse_s[b][sub * 32 + 8 * g4 + 4 * half]);
-        const float lv[4] = {ls.x, ls.y, ls.z, ls.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int qi = ib + 8 * g4 + 4 * half + e;
-          float x = fmaf(s[4 * g4 + e], sc, -lv[e]);
-          if (w > 0 && qi - kj < w) x += rb;
-          float p = fast_exp2(x);
-          if (edge && (qi < kj || qi >= len)) p = 0.0f;
-          s1 += p;
-          s2 = fmaf(p, p, s2);
+      for (int sub = 0; sub < 2; ++sub) {
+        const int ib = t * kTile + sub * 32;
+        const bool do0 = ib + 31 >= kw0, do1 = ib + 31 >= kw0 + 32;  // some query of the tile reaches the keys
+        if (!do0) continue;
+        f32x16 c0, c1;
+        score_tiles(lds[b], sub, own0, own1, do0, do1, c0, c1);
+        const bool whole = w == 0 && ib + 31 < len;  // no ragged end, no bias
+        const float* lt = &lse_s[b][sub * 32];
+        if (whole && ib >= kw0 + 31) column_update<true>(c0, lt, sc, ib, half, kj0, len, w, rb, s1a, s2a);
+        else column_update<false>(c0, lt, sc, ib, half, kj0, len, w, rb, s1a, s2a);
+        if (do1) {
+          if (whole && ib >= kw0 + 63) column_update<true>(c1, lt, sc, ib, half, kj1, len, w, rb, s1b, s2b);
+          else column_update<false>(c1, lt, sc, ib, half, kj1, len, w, rb, s1b, s2b);
         }
       }
     }
-  }
-  s1 += __shfl_xor(s1, 32, kWave);
-  s2 += __shfl_xor(s2, 32, kWave);
-  if (half == 0 && kj < len) {
-    a.acc[ubase + kj] = s1;
-    a.acc2[ubase + kj] = s2;
+    s1a += __shfl_xor(s1a, 32, kWave);
+    s2a += __shfl_xor(s2a, 32, kWave);
+    s1b += __shfl_xor(s1b, 32, kWave);
+    s2b += __shfl_xor(s2b, 32, kWave);
+    if (half == 0 && kj0 < len) { a.acc[ubase + kj0] = s1a; a.acc2[ubase + kj0] = s2a; }
+    if (half == 0 && kj1 < len) { a.acc[ubase + kj1] = s1b; a.acc2[ubase + kj1] = s2b; }
   }
 }
 
@@ -219,7 +321,8 @@ __global__ __launch_bounds__(kThreads) void prefill_columns_mfma(PrefillArgs a) 
 
 hipError_t launch_prefill_attention_mfma(const PrefillArgs& a, hipStream_t s) {
   if (a.O != nullptr) return launch_prefill_attention_simple(kBF16, D, a, s);  // attention output: general path
-  const dim3 grid((a.L_max + kOwn - 1) / kOwn, a.units);
+  const int n_blocks = (a.L_max + kOwn - 1) / kOwn;
+  const dim3 grid((n_blocks + 1) / 2, a.units);  // a workgroup takes blocks b and n-1-b
   {
     ProfScope ps(kProfPrefillRows, s);
     hipLaunchKernelGGL(prefill_rows_mfma, grid, dim3(kThreads), 0, s, a);

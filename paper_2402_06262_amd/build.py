@@ -16,6 +16,9 @@ HIPCC_FLAGS = [
     "-Wall", "-Wno-unused-function",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # matrix-instruction accumulators live in ordinary vector registers: no copies to and from the
+    # accumulation registers around every tile
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
 ]
 
 

@@ -108,6 +108,9 @@ int roco_prefill_compress(const roco_params* params, const void* Q, const void* 
 
   PrefillArgs a;
   a.units = params->units; a.L_max = L_max; a.B = params->budget; a.scope = params->scope;
+  a.pairs = 0;
+  a.paired = env_int("ROCO_PREFILL_PAIRED", -1);
+  a.mfma_waves = env_int("ROCO_PREFILL_WAVES", 0);
   a.scale_log2 = scale_log2(params);
   a.recency_window = params->recency_window;
   a.recency_bias_log2 = params->recency_bias * 1.4426950408889634f;

@@ -35,6 +35,9 @@ struct DecodeArgs {
 
 struct PrefillArgs {
   int units, L_max, B, scope;
+  int pairs;             // matrix-core path: workgroup ids per unit (set by its launcher)
+  int paired;            // matrix-core path: 1 = long+short block per workgroup, 0 = one block, -1 = choose
+  int mfma_waves;        // matrix-core path: 4 or 8 waves per workgroup, 0 = choose by problem size
   float scale_log2;
   int recency_window;
   float recency_bias_log2;

@@ -27,33 +27,41 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int D = 128;
-constexpr int kThreads = 256;
-constexpr int kWaves = kThreads / kWave;
-constexpr int kOwn = 64 * kWaves;        // owned rows per workgroup: two groups of 32 per wave
 constexpr int kTile = 64;                // streamed rows per LDS tile
 constexpr int kRowBytes = D * 2;         // 256
 constexpr int kLdsRow = kRowBytes + 16;  // padded: 16 lanes x 16 B then hit distinct bank groups
 constexpr int kKSteps = D / 16;          // 8 matrix instructions per 32x32 tile
 
-struct Staged {
-  uint4 w[4];  // this thread's 64 bytes of a 64 x 256 B tile
+// A workgroup of WAVES waves owns 64*WAVES rows.  The more rows a workgroup owns, the fewer times the other
+// operand is streamed from L2 / Infinity Cache (the bytes per flop of that stream are 1 / (2 * owned rows)).
+template <int WAVES> struct Shape {
+  static constexpr int kThreads = WAVES * kWave;
+  static constexpr int kOwn = 64 * WAVES;                  // two groups of 32 per wave
+  static constexpr int kChunks = kTile * 16 / kThreads;    // 16-byte chunks of a 64 x 256 B tile per thread
+  static constexpr int kRowsPerSweep = kThreads / 16;
 };
 
-// Thread t of 256 copies bytes [t*16 + i*4096, +16) of the tile, i < 4: row = (t + 256 i) / 16, column chunk t % 16.
-__device__ __forceinline__ void tile_load(Staged& s, const char* base, int row0, int last_row) {
+template <int WAVES> struct Staged {
+  uint4 w[Shape<WAVES>::kChunks];  // this thread's bytes of a 64 x 256 B tile
+};
+
+// Thread t copies the chunks (row = t / 16 + sweep * threads / 16, column chunk t % 16) of the tile.
+template <int WAVES>
+__device__ __forceinline__ void tile_load(Staged<WAVES>& s, const char* base, int row0, int last_row) {
   const int t = threadIdx.x;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int row = row0 + (t >> 4) + 16 * i;
+  for (int i = 0; i < Shape<WAVES>::kChunks; ++i) {
+    int row = row0 + (t >> 4) + Shape<WAVES>::kRowsPerSweep * i;
     row = row < last_row ? row : last_row;  // clamp: rows past the end are masked by the caller
     s.w[i] = load16(base + static_cast<size_t>(row) * kRowBytes + (t & 15) * 16);
   }
 }
-__device__ __forceinline__ void tile_store(const Staged& s, char* lds) {
+template <int WAVES>
+__device__ __forceinline__ void tile_store(const Staged<WAVES>& s, char* lds) {
   const int t = threadIdx.x;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
-    *reinterpret_cast<uint4*>(lds + ((t >> 4) + 16 * i) * kLdsRow + (t & 15) * 16) = s.w[i];
+  for (int i = 0; i < Shape<WAVES>::kChunks; ++i)
+    *reinterpret_cast<uint4*>(lds + ((t >> 4) + Shape<WAVES>::kRowsPerSweep * i) * kLdsRow + (t & 15) * 16) = s.w[i];
 }
 
 // Two 32x32 score tiles: streamed rows [sub*32, sub*32+32) of the LDS tile against the wave's two groups of
@@ -63,27 +71,29 @@ __device__ __forceinline__ void score_tiles(const char* lds, int sub, const uint
                                             bool do0, bool do1, f32x16& acc0, f32x16& acc1) {
   const int lane = threadIdx.x & (kWave - 1);
   const char* p = lds + (sub * 32 + (lane & 31)) * kLdsRow + (lane >> 5) * 16;
-  acc0 = f32x16{0};
-  acc1 = f32x16{0};
+  const f32x16 zero = {0};  // the first instruction of a chain takes the constant as its C operand
+  auto frag = [&](int kk) { return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p + kk * 32)); };
+  auto mm = [](bf16x8 x, const uint4& y, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, __builtin_bit_cast(bf16x8, y), c, 0, 0, 0);
+  };
   if (do0 && do1) {
+    bf16x8 a = frag(0);
+    acc0 = mm(a, own0[0], zero);
+    acc1 = mm(a, own1[0], zero);
 #pragma unroll
-    for (int kk = 0; kk < kKSteps; ++kk) {
-      const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p + kk * 32));
-      acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, own0[kk]), acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, own1[kk]), acc1, 0, 0, 0);
+    for (int kk = 1; kk < kKSteps; ++kk) {
+      a = frag(kk);
+      acc0 = mm(a, own0[kk], acc0);
+      acc1 = mm(a, own1[kk], acc1);
     }
   } else if (do0) {
+    acc0 = mm(frag(0), own0[0], zero);
 #pragma unroll
-    for (int kk = 0; kk < kKSteps; ++kk) {
-      const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p + kk * 32));
-      acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, own0[kk]), acc0, 0, 0, 0);
-    }
+    for (int kk = 1; kk < kKSteps; ++kk) acc0 = mm(frag(kk), own0[kk], acc0);
   } else if (do1) {
+    acc1 = mm(frag(0), own1[0], zero);
 #pragma unroll
-    for (int kk = 0; kk < kKSteps; ++kk) {
-      const bf16x8 a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p + kk * 32));
-      acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, own1[kk]), acc1, 0, 0, 0);
-    }
+    for (int kk = 1; kk < kKSteps; ++kk) acc1 = mm(frag(kk), own1[kk], acc1);
   }
 }
 
@@ -93,6 +103,18 @@ __device__ __forceinline__ void load_owned(uint4* own, const char* base, int row
 #pragma unroll
   for (int kk = 0; kk < kKSteps; ++kk)
     own[kk] = load16(base + static_cast<size_t>(row) * kRowBytes + kk * 32 + (lane >> 5) * 16);
+}
+
+// Workgroup -> (unit, block-pair) mapping.  The hardware hands consecutive workgroup ids to the 8 accelerator
+// dies in turn and each die has its own L2, so the workgroups of one unit (which all stream the same K or Q
+// tiles, at about the same time) are given ids that are congruent modulo 8: they land on one die and all but
+// the first fetch of a tile hit its L2.  The grid is one-dimensional over ceil(units/8)*8 x pairs ids.
+__device__ __forceinline__ bool locate(int units, int pairs, int& unit, int& pair) {
+  const int lin = blockIdx.x;
+  const int die = lin & 7, seq = lin >> 3;
+  unit = (seq / pairs) * 8 + die;
+  pair = seq % pairs;
+  return unit < units;
 }
 
 __device__ __forceinline__ float max16(const f32x16& s) {
@@ -148,9 +170,12 @@ __device__ __forceinline__ void lse_update(const f32x16& s, float sc, int kb, in
 
 // ------------------------------------------------------------------------------------------------
 // pass 1: lse[i] = log2 sum_{j<=i} 2^(t_ij),  t_ij = scale*log2(e) * q_i.k_j + bias
-__global__ __launch_bounds__(kThreads) void prefill_rows_mfma(PrefillArgs a) {
+template <int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void prefill_rows_mfma(PrefillArgs a) {
+  constexpr int kOwn = Shape<WAVES>::kOwn;
   __shared__ __attribute__((aligned(16))) char lds[2][kTile * kLdsRow];
-  const int u = blockIdx.y;
+  int u, pair_id;
+  if (!locate(a.units, a.pairs, u, pair_id)) return;
   const int len = a.len[u];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int half = lane >> 5;
@@ -161,13 +186,22 @@ __global__ __launch_bounds__(kThreads) void prefill_rows_mfma(PrefillArgs a) {
   const int w = a.recency_window;
   const float rb = a.recency_bias_log2;
   const int n_blocks = (len + kOwn - 1) / kOwn;
-  if (2 * static_cast<int>(blockIdx.x) > n_blocks - 1) return;  // this unit is short: the pair is someone else's
+  if (a.paired ? 2 * pair_id > n_blocks - 1 : pair_id >= n_blocks) return;  // nothing left for this id
 
-  // A workgroup takes one long and one short block of queries (blocks b and n-1-b), so that every workgroup of
-  // a unit does the same amount of work whatever its position under the causal diagonal.
+  // Two schedules.  Paired (few workgroups in all): a workgroup takes one long and one short block (p and
+  // n-1-p), so that all of them do the same amount of work whatever their position under the causal diagonal.
+  // Unpaired (plenty of workgroups): one block each; the workgroups of a unit sit on one die, start together
+  // and walk the streamed operand from row 0 at the same pace, so a streamed tile is fetched from HBM once and
+  // then found in that die's L2 by the others.
   for (int pass = 0; pass < 2; ++pass) {
-    const int blk = pass == 0 ? static_cast<int>(blockIdx.x) : n_blocks - 1 - static_cast<int>(blockIdx.x);
-    if (blk < static_cast<int>(blockIdx.x) || (pass == 1 && blk == static_cast<int>(blockIdx.x))) break;
+    int blk;
+    if (a.paired) {
+      blk = pass == 0 ? pair_id : n_blocks - 1 - pair_id;
+      if (blk < pair_id || (pass == 1 && blk == pair_id)) break;
+    } else {
+      if (pass == 1) break;
+      blk = n_blocks - 1 - pair_id;  // the longest streams start first
+    }
     const int q0 = blk * kOwn;
     const int qw0 = q0 + 64 * wave;  // first query of this wave
     const int qi0 = qw0 + (lane & 31), qi1 = qi0 + 32;
@@ -178,10 +212,11 @@ __global__ __launch_bounds__(kThreads) void prefill_rows_mfma(PrefillArgs a) {
 
     const int last_key = min(len, q0 + kOwn) - 1;  // keys 0..last_key are visible to some query of the block
     const int n_tiles = last_key / kTile + 1;
-    Staged st;
-    tile_load(st, Kb, 0, len - 1);
+    // The next tile is requested right after the barrier and has the whole tile of work to arrive.
+    Staged<WAVES> stA;
+    tile_load(stA, Kb, 0, len - 1);
     __syncthreads();  // the previous pass has finished with the LDS buffers
-    for (int t = 0; t < n_tiles; ++t) {
+    auto step = [&](Staged<WAVES>& st, int t) {
       tile_store(st, lds[t & 1]);
       __syncthreads();
       if (t + 1 < n_tiles) tile_load(st, Kb, (t + 1) * kTile, len - 1);
@@ -199,7 +234,8 @@ __global__ __launch_bounds__(kThreads) void prefill_rows_mfma(PrefillArgs a) {
         if (w == 0 && kb + 31 <= qw0 + 32) lse_update<true>(s1, sc, kb, half, qi1, w, rb, m1, l1);
         else lse_update<false>(s1, sc, kb, half, qi1, w, rb, m1, l1);
       }
-    }
+    };
+    for (int t = 0; t < n_tiles; ++t) step(stA, t);
     // the two lane halves hold different keys of the same query
     {
       const float mo = __shfl_xor(m0, 32, kWave), lo = __shfl_xor(l0, 32, kWave);
@@ -247,10 +283,13 @@ __device__ __forceinline__ void column_update(const f32x16& s, const float* lse_
 
 // ------------------------------------------------------------------------------------------------
 // pass 2: Acc[j] = sum_{i>=j} 2^(t_ij - lse_i),  Acc2[j] = sum_{i>=j} (same)^2
-__global__ __launch_bounds__(kThreads) void prefill_columns_mfma(PrefillArgs a) {
+template <int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void prefill_columns_mfma(PrefillArgs a) {
+  constexpr int kOwn = Shape<WAVES>::kOwn;
   __shared__ __attribute__((aligned(16))) char lds[2][kTile * kLdsRow];
   __shared__ __attribute__((aligned(16))) float lse_s[2][kTile];
-  const int u = blockIdx.y;
+  int u, pair_id;
+  if (!locate(a.units, a.pairs, u, pair_id)) return;
   const int len = a.len[u];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int half = lane >> 5;
@@ -262,11 +301,17 @@ __global__ __launch_bounds__(kThreads) void prefill_columns_mfma(PrefillArgs a) 
   const int w = a.recency_window;
   const float rb = a.recency_bias_log2;
   const int n_blocks = (len + kOwn - 1) / kOwn;
-  if (2 * static_cast<int>(blockIdx.x) > n_blocks - 1) return;
+  if (a.paired ? 2 * pair_id > n_blocks - 1 : pair_id >= n_blocks) return;  // nothing left for this id
 
   for (int pass = 0; pass < 2; ++pass) {  // one long and one short block of keys per workgroup
-    const int blk = pass == 0 ? static_cast<int>(blockIdx.x) : n_blocks - 1 - static_cast<int>(blockIdx.x);
-    if (blk < static_cast<int>(blockIdx.x) || (pass == 1 && blk == static_cast<int>(blockIdx.x))) break;
+    int blk;
+    if (a.paired) {
+      blk = pass == 0 ? pair_id : n_blocks - 1 - pair_id;
+      if (blk < pair_id || (pass == 1 && blk == pair_id)) break;
+    } else {
+      if (pass == 1) break;
+      blk = n_blocks - 1 - pair_id;  // the longest streams start first
+    }
     const int j0 = blk * kOwn;
     const int kw0 = j0 + 64 * wave;
     const int kj0 = kw0 + (lane & 31), kj1 = kj0 + 32;  // this lane's two keys
@@ -277,20 +322,20 @@ __global__ __launch_bounds__(kThreads) void prefill_columns_mfma(PrefillArgs a) 
 
     const int t_first = j0 / kTile;  // first query tile with a query >= j0
     const int t_last = (len - 1) / kTile;
-    Staged st;
-    tile_load(st, Qb, t_first * kTile, len - 1);
-    float lse_st = 0.0f;
-    if (threadIdx.x < kTile) lse_st = lse[min(t_first * kTile + static_cast<int>(threadIdx.x), len - 1)];
+    Staged<WAVES> stA;
+    float lseA = 0.0f;
+    auto fetch = [&](Staged<WAVES>& st, float& lse_st, int t) {
+      tile_load(st, Qb, t * kTile, len - 1);
+      if (threadIdx.x < kTile) lse_st = lse[min(t * kTile + static_cast<int>(threadIdx.x), len - 1)];
+    };
+    fetch(stA, lseA, t_first);
     __syncthreads();  // the previous pass has finished with the LDS buffers
-    for (int t = t_first; t <= t_last; ++t) {
+    auto step = [&](Staged<WAVES>& st, float& lse_st, int t) {
       const int b = (t - t_first) & 1;
       tile_store(st, lds[b]);
       if (threadIdx.x < kTile) lse_s[b][threadIdx.x] = lse_st;
       __syncthreads();
-      if (t < t_last) {
-        tile_load(st, Qb, (t + 1) * kTile, len - 1);
-        if (threadIdx.x < kTile) lse_st = lse[min((t + 1) * kTile + static_cast<int>(threadIdx.x), len - 1)];
-      }
+      if (t + 1 <= t_last) fetch(st, lse_st, t + 1);
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub) {
         const int ib = t * kTile + sub * 32;
@@ -307,7 +352,8 @@ __global__ __launch_bounds__(kThreads) void prefill_columns_mfma(PrefillArgs a) 
           else column_update<false>(c1, lt, sc, ib, half, kj1, len, w, rb, s1b, s2b);
         }
       }
-    }
+    };
+    for (int t = t_first; t <= t_last; ++t) step(stA, lseA, t);
     s1a += __shfl_xor(s1a, 32, kWave);
     s2a += __shfl_xor(s2a, 32, kWave);
     s1b += __shfl_xor(s1b, 32, kWave);
@@ -317,21 +363,32 @@ __global__ __launch_bounds__(kThreads) void prefill_columns_mfma(PrefillArgs a) 
   }
 }
 
+template <int WAVES>
+hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
+  constexpr int kOwn = Shape<WAVES>::kOwn;
+  const int n_blocks = (a.L_max + kOwn - 1) / kOwn;
+  PrefillArgs b = a;
+  b.paired = a.paired >= 0 ? a.paired : 1;  // pairing measured faster than lock-step single blocks
+  b.pairs = b.paired ? (n_blocks + 1) / 2 : n_blocks;  // ids per unit
+  const dim3 grid(static_cast<unsigned>((a.units + 7) / 8 * 8 * b.pairs));
+  {
+    ProfScope ps(kProfPrefillRows, s);
+    hipLaunchKernelGGL(prefill_rows_mfma<WAVES>, grid, dim3(WAVES * kWave), 0, s, b);
+  }
+  {
+    ProfScope ps(kProfPrefillColumns, s);
+    hipLaunchKernelGGL(prefill_columns_mfma<WAVES>, grid, dim3(WAVES * kWave), 0, s, b);
+  }
+  return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_prefill_attention_mfma(const PrefillArgs& a, hipStream_t s) {
   if (a.O != nullptr) return launch_prefill_attention_simple(kBF16, D, a, s);  // attention output: general path
-  const int n_blocks = (a.L_max + kOwn - 1) / kOwn;
-  const dim3 grid((n_blocks + 1) / 2, a.units);  // a workgroup takes blocks b and n-1-b
-  {
-    ProfScope ps(kProfPrefillRows, s);
-    hipLaunchKernelGGL(prefill_rows_mfma, grid, dim3(kThreads), 0, s, a);
-  }
-  {
-    ProfScope ps(kProfPrefillColumns, s);
-    hipLaunchKernelGGL(prefill_columns_mfma, grid, dim3(kThreads), 0, s, a);
-  }
-  return hipGetLastError();
+  // 256 owned rows per workgroup by default.  512 halve the streamed traffic but leave one workgroup per
+  // compute unit, all of whose waves wait at the same barriers; measured slower on the serving workload.
+  return a.mfma_waves == 8 ? launch_t<8>(a, s) : launch_t<4>(a, s);
 }
 
 }  // namespace roco

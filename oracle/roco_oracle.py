@@ -211,17 +211,9 @@ class PrefillResult:
     retained: np.ndarray  # sorted positions kept
 
 
-def prefill_compress(Q, K, V, length: int, budget: int, scope: int, scale: float,
-                     recency_window: int = 0, recency_bias: float = 0.0,
-                     want_out: bool = False, row_block: int = 512,
-                     force_retained: Optional[np.ndarray] = None) -> PrefillResult:
-    """Encode a prompt and compress its cache to `budget` tokens in one eviction step.
-
-    `force_retained` replaces the oracle's own retained set (used by the parity
-    harness after a declared tie, never by the pins).
-    """
-    full = prefill_statistics(Q, K, V, length, scale, recency_window, recency_bias,
-                              want_out, row_block)
+def compress_from_statistics(full: PrefillStats, K, V, length: int, budget: int, scope: int,
+                             force_retained: Optional[np.ndarray] = None) -> PrefillResult:
+    """The eviction step and the compaction of `prefill_compress`, given the prompt's statistics."""
     n_evict = max(0, length - budget)
     mas = mean_attention_score(full.acc, full.count)
     var = attention_variance(full.acc, full.acc2, full.count)
@@ -247,6 +239,20 @@ def prefill_compress(Q, K, V, length: int, budget: int, scope: int, scale: float
     cache.count[:n] = full.count[retained]
     cache.pos[:n] = retained
     return PrefillResult(cache, full.out, full, evicted, retained)
+
+
+def prefill_compress(Q, K, V, length: int, budget: int, scope: int, scale: float,
+                     recency_window: int = 0, recency_bias: float = 0.0,
+                     want_out: bool = False, row_block: int = 512,
+                     force_retained: Optional[np.ndarray] = None) -> PrefillResult:
+    """Encode a prompt and compress its cache to `budget` tokens in one eviction step.
+
+    `force_retained` replaces the oracle's own retained set (used by the parity
+    harness after a declared tie, never by the pins).
+    """
+    full = prefill_statistics(Q, K, V, length, scale, recency_window, recency_bias,
+                              want_out, row_block)
+    return compress_from_statistics(full, K, V, length, budget, scope, force_retained)
 
 
 @dataclass

@@ -121,11 +121,15 @@ def gpu_prefill(sess: GpuSession, Q: np.ndarray, K: np.ndarray, V: np.ndarray, l
 
 def check_prefill_unit(g: dict, u: int, Qu, Ku, Vu, length: int, budget: int, scope: int, scale: float,
                        dtype: str, recency_window: int = 0, recency_bias: float = 0.0,
-                       want_out: bool = True, row_block: int = 512):
-    """Compare unit `u` of a gpu_prefill result with the oracle.  Returns (oracle result, TieCount)."""
+                       want_out: bool = True, row_block: int = 512, full=None, out_rows=None):
+    """Compare unit `u` of a gpu_prefill result with the oracle.  Returns (oracle result, TieCount).
+
+    `full` lets several scopes share one evaluation of the oracle's statistics; `out_rows` restricts the
+    comparison of the attention output to a sample of rows."""
     ties = TieCount()
-    res = orc.prefill_compress(Qu, Ku, Vu, length, budget, scope, scale, recency_window, recency_bias,
-                               want_out=want_out, row_block=row_block)
+    if full is None:
+        full = orc.prefill_statistics(Qu, Ku, Vu, length, scale, recency_window, recency_bias, want_out, row_block)
+    res = orc.compress_from_statistics(full, Ku, Vu, length, budget, scope)
     n = min(length, budget)
     assert int(g["n_used"][u]) == n, f"unit {u}: n_used {g['n_used'][u]} != {n}"
     gpos = g["pos"][u]
@@ -145,8 +149,7 @@ def check_prefill_unit(g: dict, u: int, Qu, Ku, Vu, length: int, budget: int, sc
             diff = sorted(set(gpos[:n].tolist()) ^ set(res.retained.tolist()))
             assert ok, f"unit {u}: retained set differs outside the tie band ({why}); differing positions {diff[:10]}"
             ties.prefill_ties += 1
-            res = orc.prefill_compress(Qu, Ku, Vu, length, budget, scope, scale, recency_window, recency_bias,
-                                       want_out=want_out, row_block=row_block, force_retained=gpos[:n])
+            res = orc.compress_from_statistics(full, Ku, Vu, length, budget, scope, force_retained=gpos[:n])
     c = res.cache
     assert np.array_equal(gpos, c.pos)
     assert np.array_equal(g["stats"][u, 2], c.count), f"unit {u}: Count differs"
@@ -155,7 +158,7 @@ def check_prefill_unit(g: dict, u: int, Qu, Ku, Vu, length: int, budget: int, sc
     assert np.array_equal(g["K"][u, :n].astype(np.float64), c.K[:n]), f"unit {u}: cached K rows differ"
     assert np.array_equal(g["V"][u, :n].astype(np.float64), c.V[:n]), f"unit {u}: cached V rows differ"
     if want_out:
-        for i in range(length):
+        for i in (range(length) if out_rows is None else out_rows):
             assert_out_close(g["O"][u, i], res.out[i], dtype, f"unit {u} O[{i}]")
     return res, ties
 

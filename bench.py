@@ -28,6 +28,9 @@ import numpy as np  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix peak
+# HBM-side bytes of one decode_attend launch on this workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a
+# plain copy of known size (profiles/decode_prefill_workload3_rocprofv3.txt); only valid for the default shape.
+ATTEND_TRAFFIC_BYTES = 543662034
 
 
 def generate(cfg, seed, workers):
@@ -101,6 +104,9 @@ def main():
     ap.add_argument("--cpu-units", type=int, default=96)
     ap.add_argument("--cpu-steps", type=int, default=512)
     ap.add_argument("--with-out", action="store_true", help="also produce the prefill attention output O")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 512 MiB device copy (a kernel of known traffic, to scale rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; units (layer x sequence x head) are independent and would be "
@@ -151,6 +157,12 @@ def main():
         prefill()
         decode()
     torch.cuda.synchronize()
+    if args.calibration_copy:
+        src = torch.empty(512 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)  # reads 512 MiB, writes 512 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     roco.roco_profile_read()
@@ -226,7 +238,8 @@ def main():
         "prefill_ms": prefill_ms / args.steps,
         "roofline": {"kernel": "decode_attend", "bound": "hbm", "achieved": attend_bytes / attend_avg_s / 1e9,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": attend_bytes / attend_avg_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "frac": attend_bytes / attend_avg_s / 1e9 / HBM_PEAK_GBS,
+                     "traffic": ATTEND_TRAFFIC_BYTES if decode_steps > 0 and U == 512 else None,
                      "bytes_per_launch": attend_bytes, "avg_launch_ms": attend_avg_s * 1e3, "launches": attend_n},
         "roofline_decode_step": {"bound": "hbm", "achieved": step_bytes / (decode_ms * 1e-3 / (decode_steps * args.steps)) / 1e9,
                                  "peak": HBM_PEAK_GBS, "unit": "GB/s",

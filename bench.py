@@ -148,10 +148,29 @@ def main():
         roco.roco_prefill_compress(p, dQ, dK, dV, dlen, L, cache.K, cache.V, cache.stats, cache.pos, cache.n_used,
                                    cache.next_slot, O, ws_p, stream=stream)
 
+    # The decode loop is launch-rate sensitive (a step is ~0.12 ms of GPU time), so the per-step device addresses are
+    # worked out once and the C entry point is called with plain integers: no tensor slicing inside the loop.
+    import ctypes
+    lib = roco.load_library()
+    pref = ctypes.byref(p)
+    row = U * d * esz
+    step_args = [(sq.data_ptr() + t * row, sk.data_ptr() + t * row, sv.data_ptr() + t * row,
+                  qpos.data_ptr() + t * U * 4, out.data_ptr() + t * row, ev_slot.data_ptr() + t * U * 4,
+                  ev_pos.data_ptr() + t * U * 4) for t in range(decode_steps)]
+    cK, cV, cS, cP, cN, cX = (x.data_ptr() for x in (cache.K, cache.V, cache.stats, cache.pos, cache.n_used,
+                                                     cache.next_slot))
+    wsd_ptr, wsd_bytes, stream_ptr = ws_d.data_ptr(), ws_d.numel(), stream.cuda_stream
+
+    def decode_one(t):
+        a = step_args[t]
+        rc = lib.roco_decode_step(pref, a[0], a[1], a[2], a[3], cK, cV, cS, cP, cN, cX, a[4], a[5], a[6], wsd_ptr,
+                                  wsd_bytes, stream_ptr)
+        if rc != 0:
+            raise roco.RocoError(rc, "roco_decode_step")
+
     def decode():
         for t in range(decode_steps):
-            roco.roco_decode_step(p, sq[t], sk[t], sv[t], qpos[t], cache.K, cache.V, cache.stats, cache.pos,
-                                  cache.n_used, cache.next_slot, out[t], ev_slot[t], ev_pos[t], ws_d, stream=stream)
+            decode_one(t)
 
     for _ in range(args.warmup):
         prefill()
@@ -166,6 +185,7 @@ def main():
 
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     roco.roco_profile_read()
+    roco.roco_profile_sampling(8)  # HIP events around every 8th decode_attend launch of the timed region
     roco.roco_profile_kernel(roco.PROF_KERNELS["decode_attend"])
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -179,6 +199,7 @@ def main():
     wall = time.perf_counter() - t0
     attend_ms, attend_n = roco.roco_profile_read()
     roco.roco_profile_kernel(-1)
+    roco.roco_profile_sampling(1)
 
     prefill_ms = sum(e[0].elapsed_time(e[1]) for e in ev)
     decode_ms = sum(e[1].elapsed_time(e[2]) for e in ev)
@@ -208,8 +229,7 @@ def main():
     for name in ("decode_finish",):
         roco.roco_profile_kernel(roco.PROF_KERNELS[name])
         for t in range(min(32, decode_steps)):
-            roco.roco_decode_step(p, sq[t], sk[t], sv[t], qpos[t], cache.K, cache.V, cache.stats, cache.pos,
-                                  cache.n_used, cache.next_slot, out[t], ev_slot[t], ev_pos[t], ws_d, stream=stream)
+            decode_one(t)
         torch.cuda.synchronize()
         ms, n = roco.roco_profile_read()
         dec_kernel_ms[name] = ms / max(1, n)

@@ -154,6 +154,9 @@ enum {
 };
 int roco_profile_kernel(int which);
 int roco_profile_read(double* total_ms, int64_t* launches);
+/* Bracket only every `every`-th launch of the profiled kernel (default 1): a pair of event records costs a few
+ * microseconds of stream time, which matters when the kernel itself takes a tenth of a millisecond. */
+int roco_profile_sampling(int every);
 
 /* Static description of a return code. */
 const char* roco_strerror(int code);

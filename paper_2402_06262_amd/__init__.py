@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     roco_prefill_compress,
     roco_profile_kernel,
     roco_profile_read,
+    roco_profile_sampling,
     roco_select_victims,
     roco_strerror,
     roco_version,

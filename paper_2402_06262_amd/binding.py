@@ -77,6 +77,8 @@ def load_library() -> ctypes.CDLL:
     lib.roco_version.argtypes = []
     lib.roco_profile_kernel.restype = ctypes.c_int
     lib.roco_profile_kernel.argtypes = [ctypes.c_int]
+    lib.roco_profile_sampling.restype = ctypes.c_int
+    lib.roco_profile_sampling.argtypes = [ctypes.c_int]
     lib.roco_profile_read.restype = ctypes.c_int
     lib.roco_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     _lib = lib
@@ -107,6 +109,12 @@ def roco_profile_kernel(which: int) -> None:
     rc = load_library().roco_profile_kernel(int(which))
     if rc != 0:
         raise RocoError(rc, "roco_profile_kernel")
+
+
+def roco_profile_sampling(every: int) -> None:
+    rc = load_library().roco_profile_sampling(int(every))
+    if rc != 0:
+        raise RocoError(rc, "roco_profile_sampling")
 
 
 def roco_profile_read():

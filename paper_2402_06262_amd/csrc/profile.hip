@@ -7,6 +7,8 @@
 namespace roco {
 
 int g_prof_which = -1;
+int g_prof_every = 1;
+int g_prof_count = 0;
 
 namespace {
 std::vector<hipEvent_t> g_events;  // pairs: [2i] start, [2i+1] stop
@@ -31,6 +33,14 @@ extern "C" {
 int roco_profile_kernel(int which) {
   if (which < -1 || which >= ROCO_PROF_KERNELS) return ROCO_EINVAL;
   roco::g_prof_which = which;
+  roco::g_prof_count = 0;
+  return ROCO_OK;
+}
+
+int roco_profile_sampling(int every) {
+  if (every < 1) return ROCO_EINVAL;
+  roco::g_prof_every = every;
+  roco::g_prof_count = 0;
   return ROCO_OK;
 }
 

@@ -11,6 +11,8 @@ enum ProfKernel : int {
 };
 
 extern int g_prof_which;  // -1 = off
+extern int g_prof_every;  // bracket every n-th launch of the profiled kernel (event records cost a few microseconds)
+extern int g_prof_count;
 void prof_record(hipStream_t s, bool begin);
 
 // Brackets one kernel launch with events when that kernel is the profiled one.
@@ -18,6 +20,7 @@ struct ProfScope {
   hipStream_t s;
   bool on;
   ProfScope(int which, hipStream_t stream) : s(stream), on(which == g_prof_which) {
+    if (on) on = (g_prof_count++ % g_prof_every) == 0;
     if (on) prof_record(s, true);
   }
   ~ProfScope() {

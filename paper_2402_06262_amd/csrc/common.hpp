@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace roco {
 
 constexpr int kWave = 64;
@@ -78,13 +80,20 @@ template <int LANES> __device__ __forceinline__ float group_max(float v) {
   return v;
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave on the vector ALU's lane-shift path: four shifted adds inside
+// each row of 16 lanes, then the last lane of rows 0 and 2 is added to rows 1 and 3, then lane 31 to rows 2 and 3.
 __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
-  const int lane = threadIdx.x & (kWave - 1);
-#pragma unroll
-  for (int d = 1; d < kWave; d <<= 1) {
-    uint32_t o = __shfl_up(v, d, kWave);
-    if (lane >= d) v += o;
-  }
+  auto shr = [](uint32_t x, auto ctrl, auto row_mask) {
+    return static_cast<uint32_t>(
+        __builtin_amdgcn_update_dpp(0, static_cast<int>(x), decltype(ctrl)::value, decltype(row_mask)::value, 0xF, false));
+  };
+  using std::integral_constant;
+  v += shr(v, integral_constant<int, 0x111>{}, integral_constant<int, 0xF>{});  // row_shr:1
+  v += shr(v, integral_constant<int, 0x112>{}, integral_constant<int, 0xF>{});  // row_shr:2
+  v += shr(v, integral_constant<int, 0x114>{}, integral_constant<int, 0xF>{});  // row_shr:4
+  v += shr(v, integral_constant<int, 0x118>{}, integral_constant<int, 0xF>{});  // row_shr:8
+  v += shr(v, integral_constant<int, 0x142>{}, integral_constant<int, 0xA>{});  // row_bcast:15 into rows 1, 3
+  v += shr(v, integral_constant<int, 0x143>{}, integral_constant<int, 0xC>{});  // row_bcast:31 into rows 2, 3
   return v;
 }
 
@@ -111,27 +120,38 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s
 // ---------------------------------------------------------------- k-smallest selection
 // Non-negative IEEE floats order like their bit patterns read as uint32, so selection runs on
 // integers and is exact.  radix_select finds the k-th smallest key (k is 1-based, 1 <= k <= n) among
-// key_of(0..n-1), four 8-bit digits from the top; it also returns how many keys are strictly smaller
-// and how many are equal.  `sh` needs 256 + NT/64 + 3 words of LDS.  All threads of the block call it.
+// key_of(0..n-1), 8-bit digits from the top; it also returns how many keys are strictly smaller and how
+// many are equal.  Two histograms alternate (the idle one is cleared while the other is scanned), which
+// leaves three barriers per digit; and as soon as the chosen bin holds a single key the remaining digits are
+// read off that key instead of being counted.  `sh` needs kSelectLdsWords words of LDS.  All threads of
+// the block call it.
+constexpr int kSelectLdsWords = 2 * 256 + 8;
+
 template <int NT, class KeyFn>
 __device__ void radix_select(KeyFn key_of, int n, uint32_t k, uint32_t* sh,
                              uint32_t& kth, uint32_t& n_less, uint32_t& n_equal) {
   static_assert(NT >= 256 && NT % kWave == 0, "one thread per histogram bin");
-  uint32_t* hist = sh;
-  uint32_t* wtot = sh + 256;
-  uint32_t* res = wtot + NT / kWave;
+  uint32_t* wtot = sh + 512;  // inclusive totals of the four scanning waves
+  uint32_t* res = sh + 516;   // bin, keys below the bin, keys in the bin, the key itself (early exit)
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  __syncthreads();  // `sh` may still be in use by a previous call
+  if (tid < 256) sh[tid] = 0;
+  __syncthreads();
   uint32_t prefix = 0, mask = 0, kk = k, less = 0, neq = 0;
-  for (int shift = 24; shift >= 0; shift -= 8) {
-    __syncthreads();
-    if (tid < 256) hist[tid] = 0;
-    __syncthreads();
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    uint32_t* hist = sh + ((pass & 1) ? 256 : 0);
+    uint32_t* idle = sh + ((pass & 1) ? 0 : 256);
     for (int i = tid; i < n; i += NT) {
       const uint32_t key = key_of(i);
       if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
     }
     __syncthreads();
-    const uint32_t h = (tid < 256) ? hist[tid] : 0u;
+    uint32_t h = 0;
+    if (tid < 256) {
+      h = hist[tid];
+      idle[tid] = 0;  // ready for the next digit
+    }
     uint32_t incl = wave_inclusive_scan(h);
     if (tid < 256 && lane == kWave - 1) wtot[wave] = incl;
     __syncthreads();
@@ -146,6 +166,15 @@ __device__ void radix_select(KeyFn key_of, int n, uint32_t k, uint32_t* sh,
     less += res[1];
     kk -= res[1];
     neq = res[2];
+    if (neq == 1 && pass < 3) {  // a single candidate is left: it is the answer
+      for (int i = tid; i < n; i += NT) {
+        const uint32_t key = key_of(i);
+        if ((key & mask) == prefix) res[3] = key;
+      }
+      __syncthreads();
+      prefix = res[3];
+      break;
+    }
   }
   kth = prefix;
   n_less = less;

@@ -151,7 +151,7 @@ template <int DT, int D>
 __global__ __launch_bounds__(kFinishThreads) void decode_finish(DecodeArgs a) {
   constexpr int NT = kFinishThreads;
   extern __shared__ uint32_t lds_keys[];  // [2][B] when B <= kMaxDecodeBudgetLds
-  __shared__ uint32_t sel_sh[256 + NT / kWave + 3];
+  __shared__ uint32_t sel_sh[kSelectLdsWords];
   __shared__ unsigned long long best_sh[NT / kWave];
 
   const int u = blockIdx.x, tid = threadIdx.x;
@@ -241,7 +241,7 @@ __global__ __launch_bounds__(kFinishThreads) void decode_finish(DecodeArgs a) {
 __global__ __launch_bounds__(kFinishThreads) void select_victims(DecodeArgs a) {
   constexpr int NT = kFinishThreads;
   extern __shared__ uint32_t lds_keys[];
-  __shared__ uint32_t sel_sh[256 + NT / kWave + 3];
+  __shared__ uint32_t sel_sh[kSelectLdsWords];
   __shared__ unsigned long long best_sh[NT / kWave];
   const int u = blockIdx.x, tid = threadIdx.x;
   const int B = a.B;

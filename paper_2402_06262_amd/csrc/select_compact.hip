@@ -23,7 +23,7 @@ constexpr int kGatherRows = 64;  // cache rows per gather workgroup
 
 __global__ __launch_bounds__(kSelThreads) void prefill_select(PrefillArgs a) {
   constexpr int NT = kSelThreads;
-  __shared__ uint32_t sel_sh[256 + NT / kWave + 3];
+  __shared__ uint32_t sel_sh[kSelectLdsWords];
   __shared__ uint32_t scan_sh[NT / kWave + 1];
   __shared__ unsigned long long best_sh[NT / kWave];
   const int u = blockIdx.x, tid = threadIdx.x;

@@ -363,6 +363,169 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_mfma(PrefillArg
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// pass 1 with the attention output:  O_i = sum_j P[i,j] v_j  next to lse[i]            (section 2.1, eq. 1)
+//
+// Same orientation as prefill_rows_mfma (score tile = K . Q^T, the query in the lane), one group of 32 queries
+// per wave.  The probabilities of a 32-key half-tile, rounded to bf16, are already laid out as a B operand
+// (column = query = lane, the tile's keys down the registers), so O^T = V^T . P^T needs V^T as the A operand:
+// row = head dimension, 8 keys per lane.  V sits row-major in LDS like K; the gfx950 LDS transpose read hands
+// each lane of a 16-lane group one column of a 4-row x 16-column block, i.e. 4 consecutive keys of one head
+// dimension, and two such reads make the A fragment.  (Checked on the device: with lane i of a group pointing
+// at row i/4, column 4*(i%4) of the block, lane i receives rows 0..3 of column i.)  The k-slot order of both
+// operands follows the accumulator layout of the score tile: slots 0-3 are keys 4h..4h+3 and slots 4-7 are keys
+// 8+4h..8+4h+3 of a 16-key step, h = lane / 32.
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) v4i16 lds_v4i16;
+
+__device__ __forceinline__ uint2 lds_read_transposed(const char* p) {
+  // the pointer is known to address LDS; the builtin wants it in that address space
+  const v4i16 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(p));
+  return __builtin_bit_cast(uint2, v);
+}
+
+constexpr int kOutTileBytes = kTile * kLdsRow;  // one K or V tile in LDS
+
+template <int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void prefill_rows_out_mfma(PrefillArgs a) {
+  constexpr int kOwnQ = 32 * WAVES;  // one group of 32 queries per wave
+  extern __shared__ __attribute__((aligned(16))) char lds_dyn[];  // K[2] then V[2] tiles
+  int u, blk_id;
+  if (!locate(a.units, a.pairs, u, blk_id)) return;
+  const int len = a.len[u];
+  const int n_blocks = (len + kOwnQ - 1) / kOwnQ;
+  if (blk_id >= n_blocks) return;
+  const int blk = n_blocks - 1 - blk_id;  // long rows first
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int half = lane >> 5;
+  const size_t ubase = static_cast<size_t>(u) * a.L_max;
+  const char* Qb = static_cast<const char*>(a.Q) + ubase * kRowBytes;
+  const char* Kb = static_cast<const char*>(a.K) + ubase * kRowBytes;
+  const char* Vb = static_cast<const char*>(a.V) + ubase * kRowBytes;
+  const float sc = a.scale_log2;
+  const int w = a.recency_window;
+  const float rb = a.recency_bias_log2;
+
+  const int q0 = blk * kOwnQ;
+  const int qw0 = q0 + 32 * wave;
+  const int qi = qw0 + (lane & 31);
+  uint4 own[kKSteps];
+  load_owned(own, Qb, qi, len - 1);
+  float m = -INFINITY, l = 0.0f;
+  f32x16 o[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db) o[db] = f32x16{0};
+
+  // per-lane byte offset of the transpose reads inside a V tile: 16-lane group g = lane / 16 reads columns
+  // 16 * (g % 2) .. +15 of a 32-column block, key rows 4 * (g / 2) .. +3
+  const int i16 = lane & 15, grp = lane >> 4;
+  const int tr_off = ((grp >> 1) * 4 + (i16 >> 2)) * kLdsRow + ((grp & 1) * 16 + (i16 & 3) * 4) * 2;
+
+  const int last_key = min(len, q0 + kOwnQ) - 1;
+  const int n_tiles = last_key / kTile + 1;
+  Staged<WAVES> stK, stV;
+  tile_load(stK, Kb, 0, len - 1);
+  tile_load(stV, Vb, 0, len - 1);
+  for (int t = 0; t < n_tiles; ++t) {
+    char* const tileK = lds_dyn + (t & 1) * kOutTileBytes;
+    char* const tileV = lds_dyn + (2 + (t & 1)) * kOutTileBytes;
+    tile_store(stK, tileK);
+    tile_store(stV, tileV);
+    __syncthreads();
+    if (t + 1 < n_tiles) {
+      tile_load(stK, Kb, (t + 1) * kTile, len - 1);
+      tile_load(stV, Vb, (t + 1) * kTile, len - 1);
+    }
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      const int kb = t * kTile + sub * 32;
+      if (kb > qw0 + 31) continue;  // wholly above the diagonal for every query of this wave
+      // ---- scores of 32 keys x 32 queries
+      f32x16 sacc;
+      {
+        const char* p = tileK + (sub * 32 + (lane & 31)) * kLdsRow + half * 16;
+        const f32x16 zero = {0};
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+            __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p)), __builtin_bit_cast(bf16x8, own[0]), zero, 0, 0, 0);
+#pragma unroll
+        for (int kk = 1; kk < kKSteps; ++kk)
+          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p + kk * 32)),
+              __builtin_bit_cast(bf16x8, own[kk]), sacc, 0, 0, 0);
+      }
+      // ---- base-2 logits, masked
+      const bool interior = w == 0 && kb + 31 <= qw0;
+      float tv[16];
+      float mb = -INFINITY;
+      if (interior) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) tv[r] = sacc[r] * sc;
+        mb = max16(sacc) * sc;
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = kb + 8 * (r >> 2) + 4 * half + (r & 3);
+          float x = sacc[r] * sc;
+          if (w > 0 && qi - key < w) x += rb;
+          if (key > qi) x = -INFINITY;
+          tv[r] = x;
+          mb = fmaxf(mb, x);
+        }
+      }
+      // the two lane halves feed one matrix product, so they must share the reference maximum
+      mb = fmaxf(mb, __shfl_xor(mb, 32, kWave));
+      const float m_new = fmaxf(m, mb);  // finite: the first half-tile holds key 0, which every query sees
+      if (__any(m_new > m)) {
+        const float alpha = fast_exp2(m - m_new);  // 0 when m is still -inf
+        l *= alpha;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+      }
+      m = m_new;
+      bf16x8 pfrag[2];
+      float sum = 0.0f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float pv = fast_exp2(tv[r] - m_new);
+        sum += pv;
+        pfrag[r >> 3][r & 7] = static_cast<__bf16>(pv);
+      }
+      l += sum;
+      // ---- O^T += V^T . P^T : two 16-key steps x four blocks of 32 head dimensions
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const char* vt = tileV + (sub * 32 + ks * 16) * kLdsRow + tr_off;
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+          const uint2 lo = lds_read_transposed(vt + db * 64);                // keys 4h .. 4h+3 of the step
+          const uint2 hi = lds_read_transposed(vt + 8 * kLdsRow + db * 64);  // keys 8+4h .. 8+4h+3
+          const uint4 afrag = make_uint4(lo.x, lo.y, hi.x, hi.y);
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, afrag), pfrag[ks], o[db], 0, 0, 0);
+        }
+      }
+    }
+  }
+  // each lane half summed different keys of the same query
+  l += __shfl_xor(l, 32, kWave);
+  if (qi < len) {
+    if (half == 0) a.lse[ubase + qi] = m + log2f(l);
+    const float inv = 1.0f / l;
+    uint16_t* orow = static_cast<uint16_t*>(a.O) + (ubase + qi) * D;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int d0 = db * 32 + 8 * g4 + 4 * half;
+        uint2 pk;
+        pk.x = f32_to_bf16(o[db][4 * g4 + 0] * inv) | (static_cast<uint32_t>(f32_to_bf16(o[db][4 * g4 + 1] * inv)) << 16);
+        pk.y = f32_to_bf16(o[db][4 * g4 + 2] * inv) | (static_cast<uint32_t>(f32_to_bf16(o[db][4 * g4 + 3] * inv)) << 16);
+        *reinterpret_cast<uint2*>(orow + d0) = pk;
+      }
+  }
+}
+
 template <int WAVES>
 hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
   constexpr int kOwn = Shape<WAVES>::kOwn;
@@ -382,10 +545,43 @@ hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// Rows pass that also writes O, followed by the ordinary columns pass.
+hipError_t launch_with_output(const PrefillArgs& a, hipStream_t s) {
+  constexpr int WAVES = 4;
+  constexpr int kOwnQ = 32 * WAVES;
+  constexpr size_t kLds = 4 * static_cast<size_t>(kOutTileBytes);  // 68 KiB: above the default dynamic limit
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_rows_out_mfma<WAVES>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kLds)) != hipSuccess)
+      return hipErrorInvalidValue;
+    attr_done = true;
+  }
+  PrefillArgs b = a;
+  b.paired = 0;
+  b.pairs = (a.L_max + kOwnQ - 1) / kOwnQ;  // workgroup ids per unit
+  {
+    ProfScope ps(kProfPrefillRows, s);
+    hipLaunchKernelGGL(prefill_rows_out_mfma<WAVES>, dim3(static_cast<unsigned>((a.units + 7) / 8 * 8 * b.pairs)),
+                       dim3(WAVES * kWave), kLds, s, b);
+  }
+  constexpr int kOwn = Shape<4>::kOwn;
+  const int n_blocks = (a.L_max + kOwn - 1) / kOwn;
+  PrefillArgs c = a;
+  c.paired = 1;
+  c.pairs = (n_blocks + 1) / 2;
+  {
+    ProfScope ps(kProfPrefillColumns, s);
+    hipLaunchKernelGGL(prefill_columns_mfma<4>, dim3(static_cast<unsigned>((a.units + 7) / 8 * 8 * c.pairs)),
+                       dim3(4 * kWave), 0, s, c);
+  }
+  return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_prefill_attention_mfma(const PrefillArgs& a, hipStream_t s) {
-  if (a.O != nullptr) return launch_prefill_attention_simple(kBF16, D, a, s);  // attention output: general path
+  if (a.O != nullptr) return launch_with_output(a, s);
   // 256 owned rows per workgroup by default.  512 halve the streamed traffic but leave one workgroup per
   // compute unit, all of whose waves wait at the same barriers; measured slower on the serving workload.
   return a.mfma_waves == 8 ? launch_t<8>(a, s) : launch_t<4>(a, s);

@@ -138,6 +138,14 @@ def test_config2_prefill_4096_to_2048_scope_128():
     run_case(cfg, ids, sample=[0, 13, 31], decode_steps=0, scopes=[cfg.scope], tag="cfg2")
 
 
+def test_config2_prefill_with_attention_output():
+    """Same workload with the attention output O requested (matrix-core kernel with the P.V product)."""
+    cfg = CONFIGS[1]
+    ids = unit_ids(cfg)
+    rows = [0, 1, 2, 31, 32, 33, 63, 64, 127, 128, 129, 1000, 2047, 2048, 3000, 4094, 4095]
+    run_case(cfg, ids, sample=[0, 17], decode_steps=0, scopes=[cfg.scope], tag="cfg2-out", want_out=True, out_rows=rows)
+
+
 def test_config3_serving_shape_prefill_and_lockstep_decode():
     """All 512 units (batch 16 x 32 heads), 3072 -> 2048, scope 64; all 512 decode steps in lock-step on 8 units."""
     cfg = CONFIGS[2]

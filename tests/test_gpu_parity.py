@@ -224,3 +224,95 @@ def test_matrix_core_prefill_matches_vector_path_bitwise_decisions(monkeypatch):
         res[mode] = P.gpu_prefill(sess, Q, K, V, [700, 650, 300], False)
     assert np.array_equal(res["0"]["pos"], res["1"]["pos"])
     assert np.allclose(res["0"]["stats"], res["1"]["stats"], rtol=2e-5, atol=1e-9)
+
+
+def _small_serving_case(units=6, L=200, B=96, s=12, d=128, steps=8, seed=51):
+    rng = np.random.default_rng(seed)
+    T = L + steps
+    Q = round_to_bf16(rng.standard_normal((units, T, d)).astype(np.float32) + 0.2)
+    K = round_to_bf16(rng.standard_normal((units, T, d)).astype(np.float32))
+    V = round_to_bf16(rng.standard_normal((units, T, d)).astype(np.float32))
+    return Q, K, V
+
+
+def _state(c):
+    return [t.clone() for t in (c.K, c.V, c.stats, c.pos, c.n_used, c.next_slot)]
+
+
+def _restore(c, st):
+    for t, s in zip((c.K, c.V, c.stats, c.pos, c.n_used, c.next_slot), st):
+        t.copy_(s)
+
+
+def test_results_are_bitwise_reproducible_run_to_run():
+    """No float atomics, fixed combine order: two runs from scratch give identical bits."""
+    P = _parity()
+    Q, K, V = _small_serving_case()
+    L, steps = 200, 8
+    outs = []
+    for _ in range(2):
+        sess = P.make_session(6, 128, 96, 12, "bf16")
+        P.gpu_prefill(sess, Q[:, :L].copy(), K[:, :L].copy(), V[:, :L].copy(), [200, 180, 96, 97, 50, 200], True)
+        rec = [sess.O.clone()]
+        for t in range(steps):
+            o, sl, ps = P.gpu_decode_step(sess, Q[:, L + t], K[:, L + t], V[:, L + t], [L + t] * 6)
+            rec += [torch.from_numpy(o.copy()), torch.from_numpy(sl.copy())]
+        rec += [x.cpu() for x in _state(sess.cache)]
+        outs.append(rec)
+    for a, b in zip(*outs):
+        assert torch.equal(a.cpu(), b.cpu())
+
+
+def test_decode_steps_captured_in_a_hip_graph_replay_like_eager_steps():
+    """The decode step allocates nothing and never synchronises, so a caller can capture it.  Four steps are
+    captured once and replayed three times, with eager work and synchronisations in between; every replay must
+    leave exactly the state and outputs that the same steps leave when launched eagerly."""
+    import paper_2402_06262_amd as roco
+    P = _parity()
+    units, L, B, s, d, steps = 6, 200, 96, 12, 128, 4
+    Q, K, V = _small_serving_case(units, L, B, s, d, steps)
+    sess = P.make_session(units, d, B, s, "bf16")
+    P.gpu_prefill(sess, Q[:, :L].copy(), K[:, :L].copy(), V[:, :L].copy(), [L] * units, False)
+    c, p = sess.cache, sess.params
+    dq = [P.to_dev(Q[:, L + t], "bf16") for t in range(steps)]
+    dk = [P.to_dev(K[:, L + t], "bf16") for t in range(steps)]
+    dv = [P.to_dev(V[:, L + t], "bf16") for t in range(steps)]
+    qpos = [torch.full((units,), L + t, dtype=torch.int32, device="cuda") for t in range(steps)]
+    out = [torch.zeros((units, d), dtype=torch.bfloat16, device="cuda") for _ in range(steps)]
+    ev = [torch.zeros((units,), dtype=torch.int32, device="cuda") for _ in range(steps)]
+
+    def run_steps():
+        for t in range(steps):
+            roco.roco_decode_step(p, dq[t], dk[t], dv[t], qpos[t], c.K, c.V, c.stats, c.pos, c.n_used, c.next_slot,
+                                  out[t], ev[t], None, sess.decode_ws)
+
+    start = _state(c)
+    # eager reference: three rounds of the same four steps (the state keeps evolving)
+    want = []
+    for _ in range(3):
+        run_steps()
+        torch.cuda.synchronize()
+        want.append([x.clone() for x in out] + [x.clone() for x in ev] + _state(c))
+    _restore(c, start)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):  # warm-up launch outside capture, as graph capture in torch asks for
+        run_steps()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    _restore(c, start)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run_steps()
+    _restore(c, start)
+    torch.cuda.synchronize()
+    scratch = torch.zeros(1 << 20, device="cuda")
+    for r in range(3):
+        g.replay()
+        scratch.add_(1.0)  # unrelated eager work between replays
+        torch.cuda.synchronize()
+        got = [x.clone() for x in out] + [x.clone() for x in ev] + _state(c)
+        for a, b in zip(got, want[r]):
+            assert torch.equal(a, b), f"replay {r} differs from the eager steps"

@@ -233,8 +233,17 @@ def main():
         torch.cuda.synchronize()
         ms, n = roco.roco_profile_read()
         dec_kernel_ms[name] = ms / max(1, n)
+    # the read ceiling of the attention kernel's access pattern on this machine: its loads alone, (a) back to back
+    # and (b) alternating with real decode steps' second half, as in the loop that was timed
+    roco.roco_profile_kernel(roco.PROF_KERNELS["read_probe"])
+    for _ in range(40):
+        roco.roco_probe_cache_read(p, cache.K, cache.V, ws_d, stream=stream)
+    torch.cuda.synchronize()
+    ms, n = roco.roco_profile_read()
+    probe_alone_s = ms * 1e-3 / max(1, n)
     roco.roco_profile_kernel(-1)
     dec_kernel_ms["decode_attend"] = attend_avg_s * 1e3
+    dec_kernel_ms["read_probe"] = probe_alone_s * 1e3
 
     result = {
         "metric": "RoCo decode tokens/s (7B-shape layer, B=2048, batch 16); prefill+evict tok/s",
@@ -260,7 +269,9 @@ def main():
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": attend_bytes / attend_avg_s / 1e9 / HBM_PEAK_GBS,
                      "traffic": ATTEND_TRAFFIC_BYTES if decode_steps > 0 and U == 512 else None,
-                     "bytes_per_launch": attend_bytes, "avg_launch_ms": attend_avg_s * 1e3, "launches": attend_n},
+                     "bytes_per_launch": attend_bytes, "avg_launch_ms": attend_avg_s * 1e3, "launches": attend_n,
+                     "measured_read_ceiling_GBps": attend_bytes / probe_alone_s / 1e9,
+                     "frac_of_measured_ceiling": probe_alone_s / attend_avg_s},
         "roofline_decode_step": {"bound": "hbm", "achieved": step_bytes / (decode_ms * 1e-3 / (decode_steps * args.steps)) / 1e9,
                                  "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                  "frac": step_bytes / (decode_ms * 1e-3 / (decode_steps * args.steps)) / 1e9 / HBM_PEAK_GBS,

@@ -150,13 +150,21 @@ int roco_select_victims(const roco_params* params, const float* stats, const int
 enum {
   ROCO_PROF_DECODE_SELECT = 0, ROCO_PROF_DECODE_ATTEND = 1, ROCO_PROF_DECODE_FINISH = 2,
   ROCO_PROF_PREFILL_ROWS = 3, ROCO_PROF_PREFILL_COLUMNS = 4, ROCO_PROF_PREFILL_SELECT = 5,
-  ROCO_PROF_PREFILL_GATHER = 6, ROCO_PROF_KERNELS = 7
+  ROCO_PROF_PREFILL_GATHER = 6, ROCO_PROF_READ_PROBE = 7, ROCO_PROF_KERNELS = 8
 };
 int roco_profile_kernel(int which);
 int roco_profile_read(double* total_ms, int64_t* launches);
 /* Bracket only every `every`-th launch of the profiled kernel (default 1): a pair of event records costs a few
  * microseconds of stream time, which matters when the kernel itself takes a tenth of a millisecond. */
 int roco_profile_sampling(int every);
+
+/*
+ * Benchmark aid: reads every row of K_cache and V_cache ([units, B, d]) once with exactly the grid, the loads and
+ * the load order of the decode attention kernel and does nothing else, so that a benchmark can measure, on the
+ * machine at hand, the bandwidth ceiling of that access pattern.  The workspace is the decode workspace.
+ */
+int roco_probe_cache_read(const roco_params* params, const void* K_cache, const void* V_cache,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Static description of a return code. */
 const char* roco_strerror(int code);

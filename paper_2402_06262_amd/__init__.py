@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     prefill_workspace_bytes,
     roco_decode_step,
     roco_prefill_compress,
+    roco_probe_cache_read,
     roco_profile_kernel,
     roco_profile_read,
     roco_profile_sampling,

@@ -69,6 +69,8 @@ def load_library() -> ctypes.CDLL:
     lib.roco_prefill_compress.argtypes = [pp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.roco_decode_step.restype = ctypes.c_int
     lib.roco_decode_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.roco_probe_cache_read.restype = ctypes.c_int
+    lib.roco_probe_cache_read.argtypes = [pp, vp, vp, vp, sz, vp]
     lib.roco_select_victims.restype = ctypes.c_int
     lib.roco_select_victims.argtypes = [pp, vp, vp, vp, vp, sz, vp]
     lib.roco_strerror.restype = ctypes.c_char_p
@@ -102,7 +104,7 @@ def decode_workspace_bytes(params: RocoParams) -> int:
 
 
 PROF_KERNELS = {"decode_select": 0, "decode_attend": 1, "decode_finish": 2, "prefill_rows": 3,
-                "prefill_columns": 4, "prefill_select": 5, "prefill_gather": 6}
+                "prefill_columns": 4, "prefill_select": 5, "prefill_gather": 6, "read_probe": 7}
 
 
 def roco_profile_kernel(which: int) -> None:
@@ -172,6 +174,17 @@ def roco_decode_step(params: RocoParams, q, k_new, v_new, qpos, K_cache, V_cache
         _ptr(workspace), int(workspace_bytes), _stream(stream))
     if rc != 0:
         raise RocoError(rc, "roco_decode_step")
+
+
+def roco_probe_cache_read(params: RocoParams, K_cache, V_cache, workspace, workspace_bytes: Optional[int] = None,
+                          stream=None) -> None:
+    """See include/roco.h: the loads of the decode attention kernel, and nothing else (benchmark aid)."""
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    rc = load_library().roco_probe_cache_read(ctypes.byref(params), _ptr(K_cache), _ptr(V_cache), _ptr(workspace),
+                                              int(workspace_bytes), _stream(stream))
+    if rc != 0:
+        raise RocoError(rc, "roco_probe_cache_read")
 
 
 def roco_select_victims(params: RocoParams, stats, n_used, next_slot, workspace,

@@ -186,6 +186,24 @@ int roco_select_victims(const roco_params* params, const float* stats, const int
   return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
 }
 
+int roco_probe_cache_read(const roco_params* params, const void* K_cache, const void* V_cache,
+                          void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const int rc = check_params(params);
+  if (rc != ROCO_OK) return rc;
+  const void* need[] = {K_cache, V_cache, workspace};
+  for (const void* ptr : need)
+    if (ptr == nullptr || !aligned16(ptr)) return ROCO_EINVAL;
+  const DecodeLayout lay = decode_layout(params);
+  if (workspace_bytes < lay.total) return ROCO_EWORKSPACE;
+  DecodeArgs a = {};
+  a.units = params->units; a.B = params->budget;
+  choose_splits(params, 8, a.splits, a.rows_per_split);
+  a.K = const_cast<void*>(K_cache); a.V = const_cast<void*>(V_cache);
+  a.part_m = reinterpret_cast<float*>(static_cast<char*>(workspace) + lay.part_m);
+  const hipError_t e = launch_cache_read_probe(params->dtype, params->head_dim, a, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
+}
+
 const char* roco_strerror(int code) {
   switch (code) {
     case ROCO_OK: return "success";

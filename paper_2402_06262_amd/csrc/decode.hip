@@ -260,6 +260,36 @@ __global__ __launch_bounds__(kFinishThreads) void select_victims(DecodeArgs a) {
   if (tid == 0) a.next_slot[u] = victim;
 }
 
+// Benchmark aid: the memory side of decode_attend alone.  Same grid, same rows per workgroup, same 128-bit
+// loads in the same order, no arithmetic beyond an xor that keeps the loads alive: what this kernel reaches is
+// the read bandwidth the access pattern can get on the machine at hand.
+template <int ROW_BYTES, int U>
+__global__ __launch_bounds__(kAttendThreads) void cache_read_probe(DecodeArgs a) {
+  constexpr int LPR = ROW_BYTES / 16, R = kWave / LPR, PASS = kAttendWaves * U * R;
+  const int u = blockIdx.y, split = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int g = lane / LPR, c = lane % LPR;
+  const int row0 = split * a.rows_per_split;
+  const int row1 = min(a.B, row0 + a.rows_per_split);
+  const char* Kb = static_cast<const char*>(a.K) + static_cast<size_t>(u) * a.B * ROW_BYTES;
+  const char* Vb = static_cast<const char*>(a.V) + static_cast<size_t>(u) * a.B * ROW_BYTES;
+  uint32_t x = 0;
+  for (int base = row0 + wave * (U * R); base < row1; base += PASS) {
+    uint4 kw[U], vw[U];
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+      const int row = base + i * R + g;
+      const size_t off = static_cast<size_t>(row < row1 ? row : row0) * ROW_BYTES + c * 16;
+      kw[i] = load16(Kb + off);
+      vw[i] = load16(Vb + off);
+    }
+#pragma unroll
+    for (int i = 0; i < U; ++i)
+      x ^= kw[i].x ^ kw[i].y ^ kw[i].z ^ kw[i].w ^ vw[i].x ^ vw[i].y ^ vw[i].z ^ vw[i].w;
+  }
+  if (x == 0x9e3779b9u) a.part_m[static_cast<size_t>(u) * a.splits + split] = 1.0f;  // practically never taken
+}
+
 template <int DT, int D, int U>
 void launch_attend(const DecodeArgs& a, hipStream_t s) {
   ProfScope ps(kProfDecodeAttend, s);
@@ -297,6 +327,19 @@ hipError_t launch_decode(int dtype, int head_dim, const DecodeArgs& a, hipStream
   if (dtype == kBF16 && head_dim == 64) return launch_decode_t<kBF16, 64>(a, s);
   if (dtype == kBF16 && head_dim == 128) return launch_decode_t<kBF16, 128>(a, s);
   return hipErrorInvalidValue;
+}
+
+hipError_t launch_cache_read_probe(int dtype, int head_dim, const DecodeArgs& a, hipStream_t s) {
+  const int row_bytes = head_dim * (dtype == kBF16 ? 2 : 4);
+  const dim3 grid(a.splits, a.units);
+  ProfScope ps(kProfReadProbe, s);
+  switch (row_bytes) {
+    case 128: hipLaunchKernelGGL((cache_read_probe<128, 8>), grid, dim3(kAttendThreads), 0, s, a); break;
+    case 256: hipLaunchKernelGGL((cache_read_probe<256, 8>), grid, dim3(kAttendThreads), 0, s, a); break;
+    case 512: hipLaunchKernelGGL((cache_read_probe<512, 8>), grid, dim3(kAttendThreads), 0, s, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
 }
 
 hipError_t launch_select_victims(const DecodeArgs& a, hipStream_t s) {

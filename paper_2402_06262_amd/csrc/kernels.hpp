@@ -59,6 +59,7 @@ struct PrefillArgs {
 // dtype: 0 = f32, 1 = bf16; head_dim: 64 or 128.  Each returns hipGetLastError() of its launches.
 hipError_t launch_decode(int dtype, int head_dim, const DecodeArgs& a, hipStream_t s);
 int decode_rows_per_pass(int dtype, int head_dim, int unroll);  // granularity of DecodeArgs::rows_per_split
+hipError_t launch_cache_read_probe(int dtype, int head_dim, const DecodeArgs& a, hipStream_t s);
 hipError_t launch_select_victims(const DecodeArgs& a, hipStream_t s);  // uses stats, n_used, next_slot, keys
 hipError_t launch_prefill_attention_simple(int dtype, int head_dim, const PrefillArgs& a, hipStream_t s);
 hipError_t launch_prefill_attention_mfma(const PrefillArgs& a, hipStream_t s);  // bf16, head_dim 128

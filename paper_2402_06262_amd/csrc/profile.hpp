@@ -6,8 +6,8 @@ namespace roco {
 
 enum ProfKernel : int {
   kProfDecodeSelect = 0, kProfDecodeAttend = 1, kProfDecodeFinish = 2,
-  kProfPrefillRows = 3, kProfPrefillColumns = 4, kProfPrefillSelect = 5, kProfPrefillGather = 6,
-  kProfKernels = 7
+  kProfPrefillRows = 3, kProfPrefillColumns = 4, kProfPrefillSelect = 5, kProfPrefillGather = 6, kProfReadProbe = 7,
+  kProfKernels = 8
 };
 
 extern int g_prof_which;  // -1 = off

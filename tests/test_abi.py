@@ -22,7 +22,8 @@ def test_library_loads_and_exports_every_declared_symbol():
     lib = roco.load_library()
     names = declared_functions()
     assert {"roco_prefill_compress", "roco_decode_step", "roco_prefill_workspace_bytes",
-            "roco_decode_workspace_bytes", "roco_strerror", "roco_version", "roco_select_victims"} <= set(names)
+            "roco_decode_workspace_bytes", "roco_strerror", "roco_version", "roco_select_victims",
+            "roco_probe_cache_read", "roco_profile_sampling"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in roco.h but not exported"
     assert roco.roco_version() == 1

@@ -295,3 +295,73 @@ def decode_step(state: CacheState, q, k_new, v_new, qpos: int, scope: int, scale
     state.acc2[:n] += p * p
     state.count[:n] += 1.0
     return DecodeResult(out, p, evicted_slot, evicted_pos, slot, mas, var)
+
+
+# ---------------------------------------------------------------------------
+# block-wise evict-and-encode (section 5.3 "Overhead"; appendix B)
+# ---------------------------------------------------------------------------
+
+@dataclass
+class BlockResult:
+    out: np.ndarray  # [b, d]
+    probs: List[np.ndarray]  # probs[i][slot]: attention of the block's i-th query over the slots (0 where unseen)
+    slots: np.ndarray  # [b] slot each block token was written to
+    evicted_slot: np.ndarray  # [b] = slots[i] if that slot held a token that was evicted, else -1
+    evicted_pos: np.ndarray  # [b] position of that evicted token, else -1
+    mas: Optional[np.ndarray]  # statistics the decision was taken on (None if nothing was evicted)
+    var: Optional[np.ndarray]
+
+
+def encode_block(state: CacheState, Qb, Kb, Vb, qpos0: int, scope: int, scale: float,
+                 recency_window: int = 0, recency_bias: float = 0.0,
+                 force_evicted: Optional[np.ndarray] = None) -> BlockResult:
+    """Free and encode b tokens within one eviction step, in place.
+
+    The paper lets the number of tokens freed and encoded per eviction step be a block size b (section 5.3;
+    b = 1 is the token-wise scheme).  Reading taken here: with n tokens in the cache, E = max(0, n + b - B)
+    tokens are evicted in one step from the statistics as they stand (E single evictions with frozen
+    statistics, i.e. `select_evictions`); the block's tokens go, in order, to the ascending list of freed and
+    still-empty slots; query i of the block attends every retained token and the block's tokens 0..i; every
+    attended token gets p, p^2 and 1 added to its three statistics.  b = 1 is exactly `decode_step`.
+    """
+    Qb, Kb, Vb = (np.asarray(x, dtype=F64) for x in (Qb, Kb, Vb))
+    b = Qb.shape[0]
+    B, n = state.budget, state.n_used
+    assert 1 <= b <= B
+    E = max(0, n + b - B)
+    mas = var = None
+    evicted = np.zeros(0, dtype=np.int64)
+    if E > 0:
+        mas = mean_attention_score(state.acc[:n], state.count[:n])
+        var = attention_variance(state.acc[:n], state.acc2[:n], state.count[:n])
+        evicted = select_evictions(mas, var, scope, E) if force_evicted is None else \
+            np.sort(np.asarray(force_evicted, dtype=np.int64))
+    targets = np.sort(np.concatenate([evicted, np.arange(n, min(B, n + b), dtype=np.int64)]))
+    assert targets.shape[0] == b
+    was_evicted = np.isin(targets, evicted)
+    evicted_slot = np.where(was_evicted, targets, -1)
+    evicted_pos = np.where(was_evicted, state.pos[targets], -1)
+    block_index = np.full(B, -1, dtype=np.int64)  # which block token sits in a slot, -1 for older tokens
+    for i, slot in enumerate(targets):
+        state.K[slot], state.V[slot] = Kb[i], Vb[i]
+        state.pos[slot] = qpos0 + i
+        state.acc[slot] = state.acc2[slot] = state.count[slot] = 0.0
+        block_index[slot] = i
+    state.n_used = n_new = min(B, n + b)
+    out = np.zeros((b, Vb.shape[1]), dtype=F64)
+    probs = []
+    for i in range(b):
+        seen = np.flatnonzero(block_index[:n_new] <= i)  # older tokens (-1) and block tokens 0..i
+        z = (state.K[seen] @ Qb[i]) * F64(scale)
+        z = z + _recency(np.array([qpos0 + i]), state.pos[seen], recency_window, recency_bias)[0]
+        p = np.exp(z - z.max())
+        p = p / p.sum()
+        out[i] = p @ state.V[seen]
+        full = np.zeros(n_new, dtype=F64)
+        full[seen] = p
+        probs.append(full)
+    for i in range(b):  # statistics after all rows are known (the order of additions does not matter)
+        state.acc[:n_new] += probs[i]
+        state.acc2[:n_new] += probs[i] * probs[i]
+        state.count[:n_new] += (block_index[:n_new] <= i).astype(F64)
+    return BlockResult(out, probs, targets, evicted_slot, evicted_pos, mas, var)

@@ -364,3 +364,84 @@ def test_heavy_keys_dominate_the_retained_set():
     heavy = [p for p in u.heavy_positions if p < L]
     kept = sum(1 for p in heavy if p in set(res.retained.tolist()))
     assert kept >= 0.8 * len(heavy)
+
+
+# ---------------------------------------------------------------------------- block-wise evict-and-encode
+
+def test_block_of_one_is_exactly_a_decode_step():
+    rng = np.random.default_rng(21)
+    L, d, B, s = 30, 5, 12, 4
+    Q, K, V = rand_unit(rng, L + 6, d)
+    a = orc.prefill_compress(Q[:L], K[:L], V[:L], L, B, s, 0.4).cache
+    b = a.copy()
+    for t in range(L, L + 6):
+        ra = orc.decode_step(a, Q[t], K[t], V[t], t, s, 0.4)
+        rb = orc.encode_block(b, Q[t:t + 1], K[t:t + 1], V[t:t + 1], t, s, 0.4)
+        assert np.array_equal(ra.out, rb.out[0]) and ra.evicted_slot == rb.evicted_slot[0]
+        assert ra.evicted_pos == rb.evicted_pos[0]
+        for x, y in ((a.acc, b.acc), (a.acc2, b.acc2), (a.count, b.count), (a.pos, b.pos), (a.K, b.K)):
+            assert np.array_equal(x, y)
+
+
+@pytest.mark.parametrize("b", [1, 2, 3, 7])
+def test_blocks_without_eviction_reproduce_dense_causal_attention(b):
+    """Budget >= total length: block-wise encoding of a whole sequence equals textbook causal attention."""
+    rng = np.random.default_rng(22 + b)
+    T, d = 23, 4
+    Q, K, V = rand_unit(rng, T, d)
+    P, O = dense_causal_attention(Q, K, V, 0.6)
+    st = orc.CacheState(np.zeros((T + 3, d)), np.zeros((T + 3, d)), np.zeros(T + 3), np.zeros(T + 3),
+                        np.zeros(T + 3), np.full(T + 3, -1, dtype=np.int64), 0)
+    t = 0
+    while t < T:
+        bb = min(b, T - t)
+        r = orc.encode_block(st, Q[t:t + bb], K[t:t + bb], V[t:t + bb], t, 3, 0.6)
+        assert np.allclose(r.out, O[t:t + bb], rtol=1e-12, atol=1e-14)
+        assert np.all(r.evicted_slot == -1) and r.slots.tolist() == list(range(t, t + bb))
+        t += bb
+    assert st.n_used == T and np.array_equal(st.pos[:T], np.arange(T))
+    assert np.allclose(st.acc[:T], P.sum(0), rtol=1e-12)
+    assert np.allclose(st.acc2[:T], (P ** 2).sum(0), rtol=1e-12)
+    assert np.array_equal(st.count[:T], T - np.arange(T))
+
+
+@pytest.mark.parametrize("b", [2, 4, 5])
+def test_blockwise_eviction_keeps_the_budget_and_its_statistics_equal_a_brute_force_recount(b):
+    rng = np.random.default_rng(30 + b)
+    T, d, B, s = 41, 4, 9, 3
+    Q, K, V = rand_unit(rng, T, d)
+    st = orc.CacheState(np.zeros((B, d)), np.zeros((B, d)), np.zeros(B), np.zeros(B), np.zeros(B),
+                        np.full(B, -1, dtype=np.int64), 0)
+    log = []  # (query position, {key position: probability})
+    t = 0
+    while t < T:
+        bb = min(b, T - t)
+        before_pos, before_n = st.pos.copy(), st.n_used
+        if before_n + bb > B:
+            mas = orc.mean_attention_score(st.acc[:before_n], st.count[:before_n])
+            var = orc.attention_variance(st.acc[:before_n], st.acc2[:before_n], st.count[:before_n])
+            want = orc.select_evictions_literal(mas, var, s, before_n + bb - B)  # the token-by-token loop
+        else:
+            want = np.zeros(0, dtype=np.int64)
+        r = orc.encode_block(st, Q[t:t + bb], K[t:t + bb], V[t:t + bb], t, s, 0.5)
+        assert st.n_used <= B
+        assert sorted(x for x in r.evicted_slot.tolist() if x >= 0) == want.tolist()
+        for i in range(bb):
+            assert st.pos[r.slots[i]] == t + i
+            if r.evicted_slot[i] >= 0:
+                assert r.evicted_pos[i] == before_pos[r.evicted_slot[i]]
+            row = {int(st.pos[j]): r.probs[i][j] for j in range(st.n_used) if r.probs[i][j] > 0}
+            assert abs(sum(row.values()) - 1.0) < 1e-12
+            assert max(row) == t + i and all(p <= t + i for p in row)  # causal inside the block
+            log.append((t + i, row))
+            z = np.array([0.5 * np.dot(Q[t + i], K[p]) for p in row])
+            w = np.exp(z - z.max())
+            w /= w.sum()
+            assert np.allclose(r.out[i], sum(wi * V[p] for wi, p in zip(w, row)), rtol=1e-12, atol=1e-14)
+        t += bb
+    for j in range(st.n_used):
+        p = int(st.pos[j])
+        rows = [row[p] for (_, row) in log if p in row]
+        assert st.count[j] == len(rows)
+        assert math.isclose(st.acc[j], math.fsum(rows), rel_tol=1e-12)
+        assert math.isclose(st.acc2[j], math.fsum(x * x for x in rows), rel_tol=1e-12)

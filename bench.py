@@ -104,6 +104,7 @@ def main():
     ap.add_argument("--cpu-units", type=int, default=96)
     ap.add_argument("--cpu-steps", type=int, default=512)
     ap.add_argument("--with-out", action="store_true", help="also produce the prefill attention output O")
+    ap.add_argument("--no-blockwise", action="store_true", help="skip the block-wise evict-and-encode table")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 512 MiB device copy (a kernel of known traffic, to scale rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -245,6 +246,42 @@ def main():
     dec_kernel_ms["decode_attend"] = attend_avg_s * 1e3
     dec_kernel_ms["read_probe"] = probe_alone_s * 1e3
 
+    # Block-wise evict-and-encode (the paper's Table 6: speed-up of prompt encoding over token-wise eviction grows
+    # like the block size): encode the same 512 tokens on the full cache in blocks of b, from the same start state.
+    blockwise = None
+    if not args.no_blockwise and decode_steps >= 32:
+        n_tok = decode_steps - decode_steps % 32
+        prefill()
+        torch.cuda.synchronize()
+        snap = [t.clone() for t in (cache.K, cache.V, cache.stats, cache.pos, cache.n_used, cache.next_slot)]
+        bq, bk, bv = (x[:n_tok].transpose(0, 1).contiguous() for x in (sq, sk, sv))  # [U, n_tok, d]
+        blockwise = {}
+        for bsz in (1, 2, 4, 8, 16, 32):
+            nb = n_tok // bsz
+            tq, tk, tv = (x.view(U, nb, bsz, d).permute(1, 0, 2, 3).contiguous() for x in (bq, bk, bv))
+            ws_b = torch.empty(roco.block_workspace_bytes(p, bsz), dtype=torch.uint8, device="cuda")
+            bout = torch.empty((U, bsz, d), dtype=dt, device="cuda")
+            qp0 = [torch.full((U,), L + i * bsz, dtype=torch.int32, device="cuda") for i in range(nb)]
+            times = []
+            for rep in range(2):
+                for t, sn in zip((cache.K, cache.V, cache.stats, cache.pos, cache.n_used, cache.next_slot), snap):
+                    t.copy_(sn)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for i in range(nb):
+                    roco.roco_encode_block(p, bsz, tq[i], tk[i], tv[i], qp0[i], cache.K, cache.V, cache.stats, cache.pos,
+                                           cache.n_used, cache.next_slot, bout, None, None, ws_b, stream=stream)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                times.append(e0.elapsed_time(e1))
+            ms = min(times)
+            blockwise[str(bsz)] = {"tokens_per_s": cfg.batch * n_tok / (ms * 1e-3), "ms_per_block_step": ms / nb}
+            del tq, tk, tv, ws_b
+        base = blockwise["1"]["tokens_per_s"]
+        for v in blockwise.values():
+            v["speedup_vs_block_1"] = v["tokens_per_s"] / base
+        del snap
+
     result = {
         "metric": "RoCo decode tokens/s (7B-shape layer, B=2048, batch 16); prefill+evict tok/s",
         "value": decode_tok_s,
@@ -283,6 +320,10 @@ def main():
         "kernel_ms": {**dec_kernel_ms, **pre_kernel_ms},
         "input_generation_s": t_gen,
     }
+    if blockwise is not None:
+        result["blockwise_encode"] = {"workload": f"{n_tok} tokens per sequence encoded on the full B={B} cache in "
+                                                  "blocks of b (roco_encode_block), batch 16 x 32 heads",
+                                      "by_block_size": blockwise}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, Q, K, V, decode_steps, args.cpu_units, args.cpu_steps)
     print(json.dumps(result), flush=True)

@@ -132,6 +132,37 @@ int roco_decode_step(const roco_params* params,
                      void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Block-wise evict-and-encode (section 5.3 "Overhead", appendix B: the block size b is the number of tokens
+ * freed and encoded within one eviction step; b = 1 is the token-wise scheme of roco_decode_step).
+ *
+ * Per unit u with n = n_used[u]:
+ *   E = max(0, n + b - B) tokens are evicted in one step from the statistics as they stand: among the s + E - 1
+ *   slots of lowest variance, the E of lowest Acc/Count (equal keys: lowest slot first) -- E single evictions
+ *   by the rule of section 4.3 with frozen statistics.
+ *   The block's tokens 0..b-1 go, in order, to the ascending list of freed and still-empty slots; their pos is
+ *   qpos0 + i and their three statistics start at 0.  n_used = min(B, n + b).
+ *   Query i attends every retained token and the block's tokens 0..i (causal inside the block):
+ *   p_i = softmax(scale q_i.K[j] + bias), out_i = sum_j p_ij V[j]; every attended slot gets p_ij, p_ij^2 and 1
+ *   added to Acc, Acc2 and Count.  next_slot is left ready for a following roco_decode_step.
+ *
+ * block            in  1 <= b <= min(32, B)
+ * q, k_new, v_new  in  [units, b, d]   dtype
+ * qpos0            in  [units]         int32 position of the block's first token
+ * cache state      in/out as in roco_decode_step
+ * out              out [units, b, d]   dtype
+ * evicted_slot, evicted_pos  out [units, b] int32: the slot token i took over from an evicted token and that
+ *                  token's position, or -1 where token i went to an empty slot (either may be NULL)
+ * workspace        roco_block_workspace_bytes(params, block) bytes
+ * Supported: ROCO_BF16, head_dim 128, budget a multiple of 4; anything else returns ROCO_EUNSUPPORTED.
+ */
+size_t roco_block_workspace_bytes(const roco_params* params, int32_t block);
+int roco_encode_block(const roco_params* params, int32_t block,
+                      const void* q, const void* k_new, const void* v_new, const int32_t* qpos0,
+                      void* K_cache, void* V_cache, float* stats, int32_t* pos, int32_t* n_used,
+                      int32_t* next_slot, void* out, int32_t* evicted_slot, int32_t* evicted_pos,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Victim selection alone (section 4.3): for every full unit, next_slot[u] = the slot of lowest Acc/Count among
  * the s slots of lowest variance; -1 for units that are not full.  Only needed after the caller has edited
  * stats / n_used itself.  stats in [units,3,B], n_used in [units], next_slot out [units]; the workspace is the
@@ -150,7 +181,8 @@ int roco_select_victims(const roco_params* params, const float* stats, const int
 enum {
   ROCO_PROF_DECODE_SELECT = 0, ROCO_PROF_DECODE_ATTEND = 1, ROCO_PROF_DECODE_FINISH = 2,
   ROCO_PROF_PREFILL_ROWS = 3, ROCO_PROF_PREFILL_COLUMNS = 4, ROCO_PROF_PREFILL_SELECT = 5,
-  ROCO_PROF_PREFILL_GATHER = 6, ROCO_PROF_READ_PROBE = 7, ROCO_PROF_KERNELS = 8
+  ROCO_PROF_PREFILL_GATHER = 6, ROCO_PROF_READ_PROBE = 7, ROCO_PROF_BLOCK_PREPARE = 8,
+  ROCO_PROF_BLOCK_ATTEND = 9, ROCO_PROF_BLOCK_FINISH = 10, ROCO_PROF_KERNELS = 11
 };
 int roco_profile_kernel(int which);
 int roco_profile_read(double* total_ms, int64_t* launches);

@@ -11,11 +11,13 @@ from .binding import (  # noqa: F401
     RocoError,
     RocoParams,
     alloc_cache,
+    block_workspace_bytes,
     decode_workspace_bytes,
     library_path,
     load_library,
     prefill_workspace_bytes,
     roco_decode_step,
+    roco_encode_block,
     roco_prefill_compress,
     roco_probe_cache_read,
     roco_profile_kernel,

@@ -71,6 +71,10 @@ def load_library() -> ctypes.CDLL:
     lib.roco_decode_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.roco_probe_cache_read.restype = ctypes.c_int
     lib.roco_probe_cache_read.argtypes = [pp, vp, vp, vp, sz, vp]
+    lib.roco_block_workspace_bytes.restype = sz
+    lib.roco_block_workspace_bytes.argtypes = [pp, i32]
+    lib.roco_encode_block.restype = ctypes.c_int
+    lib.roco_encode_block.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.roco_select_victims.restype = ctypes.c_int
     lib.roco_select_victims.argtypes = [pp, vp, vp, vp, vp, sz, vp]
     lib.roco_strerror.restype = ctypes.c_char_p
@@ -104,7 +108,8 @@ def decode_workspace_bytes(params: RocoParams) -> int:
 
 
 PROF_KERNELS = {"decode_select": 0, "decode_attend": 1, "decode_finish": 2, "prefill_rows": 3,
-                "prefill_columns": 4, "prefill_select": 5, "prefill_gather": 6, "read_probe": 7}
+                "prefill_columns": 4, "prefill_select": 5, "prefill_gather": 6, "read_probe": 7,
+                "block_prepare": 8, "block_attend": 9, "block_finish": 10}
 
 
 def roco_profile_kernel(which: int) -> None:
@@ -174,6 +179,24 @@ def roco_decode_step(params: RocoParams, q, k_new, v_new, qpos, K_cache, V_cache
         _ptr(workspace), int(workspace_bytes), _stream(stream))
     if rc != 0:
         raise RocoError(rc, "roco_decode_step")
+
+
+def block_workspace_bytes(params: RocoParams, block: int) -> int:
+    return int(load_library().roco_block_workspace_bytes(ctypes.byref(params), int(block)))
+
+
+def roco_encode_block(params: RocoParams, block: int, q, k_new, v_new, qpos0, K_cache, V_cache, stats, pos, n_used,
+                      next_slot, out, evicted_slot, evicted_pos, workspace, workspace_bytes: Optional[int] = None,
+                      stream=None) -> None:
+    """See include/roco.h: free and encode `block` tokens within one eviction step."""
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    rc = load_library().roco_encode_block(
+        ctypes.byref(params), int(block), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(qpos0), _ptr(K_cache),
+        _ptr(V_cache), _ptr(stats), _ptr(pos), _ptr(n_used), _ptr(next_slot), _ptr(out), _ptr(evicted_slot),
+        _ptr(evicted_pos), _ptr(workspace), int(workspace_bytes), _stream(stream))
+    if rc != 0:
+        raise RocoError(rc, "roco_encode_block")
 
 
 def roco_probe_cache_read(params: RocoParams, K_cache, V_cache, workspace, workspace_bytes: Optional[int] = None,

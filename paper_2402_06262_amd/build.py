@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libroco.so")
-SOURCES = ["api.hip", "decode.hip", "prefill_simple.hip", "prefill_mfma.hip", "select_compact.hip", "profile.hip"]
+SOURCES = ["api.hip", "decode.hip", "prefill_simple.hip", "prefill_mfma.hip", "select_compact.hip", "block.hip", "profile.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -55,6 +55,30 @@ PrefillLayout prefill_layout(const roco_params* p, int32_t L_max) {
   return l;
 }
 
+// ---- block-wise workspace: blk_idx | z | part_m | part_l | part_o | keys
+struct BlockLayout { size_t blk_idx, z, part_m, part_l, part_o, keys, total; };
+BlockLayout block_layout(const roco_params* p) {
+  BlockLayout l;
+  const size_t U = p->units, B = p->budget, D = p->head_dim;
+  size_t off = 0;
+  l.blk_idx = off; off += align_up(U * B * sizeof(int32_t));
+  l.z = off;       off += align_up(U * kMaxBlock * B * sizeof(float));
+  l.part_m = off;  off += align_up(U * kMaxBlockSplits * kMaxBlock * sizeof(float));
+  l.part_l = off;  off += align_up(U * kMaxBlockSplits * kMaxBlock * sizeof(float));
+  l.part_o = off;  off += align_up(U * kMaxBlockSplits * kMaxBlock * D * sizeof(float));
+  l.keys = off;    off += (p->budget > kMaxDecodeBudgetLds) ? align_up(U * 2 * B * sizeof(uint32_t)) : 0;
+  l.total = off;
+  return l;
+}
+
+int check_block(const roco_params* p, int32_t block) {
+  const int rc = check_params(p);
+  if (rc != ROCO_OK) return rc;
+  if (block < 1 || block > p->budget) return ROCO_EINVAL;
+  if (block > kMaxBlock || p->dtype != ROCO_BF16 || p->head_dim != 128 || (p->budget & 3) != 0) return ROCO_EUNSUPPORTED;
+  return ROCO_OK;
+}
+
 int env_int(const char* name, int dflt) {
   const char* v = getenv(name);
   return (v && *v) ? atoi(v) : dflt;
@@ -164,6 +188,54 @@ int roco_decode_step(const roco_params* params, const void* q, const void* k_new
   a.part_o = reinterpret_cast<float*>(ws + lay.part_o);
   a.keys = reinterpret_cast<uint32_t*>(ws + lay.keys);
   const hipError_t e = launch_decode(params->dtype, params->head_dim, a, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
+}
+
+size_t roco_block_workspace_bytes(const roco_params* params, int32_t block) {
+  if (check_block(params, block) != ROCO_OK) return 0;
+  return block_layout(params).total;
+}
+
+int roco_encode_block(const roco_params* params, int32_t block, const void* q, const void* k_new, const void* v_new,
+                      const int32_t* qpos0, void* K_cache, void* V_cache, float* stats, int32_t* pos, int32_t* n_used,
+                      int32_t* next_slot, void* out, int32_t* evicted_slot, int32_t* evicted_pos, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+  const int rc = check_block(params, block);
+  if (rc != ROCO_OK) return rc;
+  const void* need[] = {q, k_new, v_new, qpos0, K_cache, V_cache, stats, pos, n_used, next_slot, out, workspace};
+  for (const void* ptr : need)
+    if (ptr == nullptr || !aligned16(ptr)) return ROCO_EINVAL;
+  const BlockLayout lay = block_layout(params);
+  if (workspace_bytes < lay.total) return ROCO_EWORKSPACE;
+
+  BlockArgs a;
+  a.units = params->units; a.B = params->budget; a.scope = params->scope; a.block = block;
+  {  // split the budget into 64-slot-aligned ranges, enough workgroups to cover the chip a few times
+    int want = env_int("ROCO_BLOCK_SPLITS", 0);
+    if (want <= 0) want = (2048 + params->units - 1) / params->units;
+    if (want > kMaxBlockSplits) want = kMaxBlockSplits;
+    const int max_by_rows = (params->budget + 63) / 64;
+    if (want > max_by_rows) want = max_by_rows;
+    if (want < 1) want = 1;
+    int rows = (params->budget + want - 1) / want;
+    rows = (rows + 63) / 64 * 64;
+    a.splits = (params->budget + rows - 1) / rows;
+    a.rows_per_split = rows;
+  }
+  a.scale_log2 = scale_log2(params);
+  a.recency_window = params->recency_window;
+  a.recency_bias_log2 = params->recency_bias * 1.4426950408889634f;
+  a.q = q; a.k_new = k_new; a.v_new = v_new; a.qpos0 = qpos0;
+  a.K = K_cache; a.V = V_cache; a.stats = stats; a.pos = pos; a.n_used = n_used; a.next_slot = next_slot;
+  a.out = out; a.evicted_slot = evicted_slot; a.evicted_pos = evicted_pos;
+  char* ws = static_cast<char*>(workspace);
+  a.blk_idx = reinterpret_cast<int32_t*>(ws + lay.blk_idx);
+  a.z = reinterpret_cast<float*>(ws + lay.z);
+  a.part_m = reinterpret_cast<float*>(ws + lay.part_m);
+  a.part_l = reinterpret_cast<float*>(ws + lay.part_l);
+  a.part_o = reinterpret_cast<float*>(ws + lay.part_o);
+  a.keys = reinterpret_cast<uint32_t*>(ws + lay.keys);
+  const hipError_t e = launch_block(a, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
 }
 

@@ -1,0 +1,432 @@
+// Block-wise evict-and-encode on gfx950 (section 5.3 "Overhead" and appendix B of the paper: the number of
+// tokens freed and encoded within one eviction step is a block size b; b = 1 is the token-wise scheme).
+//
+// With n tokens cached, E = max(0, n + b - B) tokens are evicted in one step (E single evictions by the rule of
+// section 4.3 with frozen statistics = the E lowest mean attention scores among the s + E - 1 lowest variances),
+// the block's tokens go in order to the ascending list of freed and still-empty slots, query i of the block
+// attends every retained token and the block's tokens 0..i, and every attended token gets p, p^2 and 1 added to
+// its statistics.  The point of the scheme is that K and V are streamed once per block instead of once per token:
+// the step stays HBM-bound, so encoding b tokens costs about what encoding one does.
+//
+//   block_prepare : one workgroup per unit.  Victims (two exact radix selects), ordered slot assignment,
+//                   K / V rows of the block written into their slots, pos / statistics of those slots reset.
+//   block_attend  : grid (splits, units), two waves.  64-slot K and V tiles through LDS, each wave scores 32
+//                   slots against the block's (up to 32) queries on the matrix cores (score tile = K . Q^T, the
+//                   query in the lane), stores the base-2 logits, keeps an online softmax per query and
+//                   accumulates O^T = V^T . P^T with V^T fragments from the LDS transpose read.
+//   block_finish  : one workgroup per unit.  Merges the partials per query, writes the b outputs, adds the
+//                   statistics of all b rows to every slot, chooses the victim a following decode step would take.
+#include "kernels.hpp"
+#include "mfma.hpp"
+#include "profile.hpp"
+#include "stream.hpp"
+
+namespace roco {
+namespace {
+
+using namespace mfma;
+
+constexpr int kPrepThreads = 256;
+constexpr int kAttThreads = 128;  // two waves: one 32-slot half of a 64-slot tile each
+constexpr int kFinThreads = 256;
+constexpr int kQ = 32;            // queries per matrix tile; a block holds at most this many tokens
+
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kPrepThreads) void block_prepare(BlockArgs a) {
+  constexpr int NT = kPrepThreads;
+  extern __shared__ uint32_t lds_keys[];  // [2][B] when B <= kMaxDecodeBudgetLds
+  __shared__ uint32_t sel_sh[kSelectLdsWords];
+  __shared__ uint32_t scan_sh[NT / kWave + 1];
+  __shared__ int slot_of[kQ];
+  const int u = blockIdx.x, tid = threadIdx.x;
+  const int B = a.B, b = a.block;
+  const int n = a.n_used[u];
+  const int E = max(0, n + b - B);
+  const int n_new = min(B, n + b);
+  float* acc = a.stats + static_cast<size_t>(u) * 3 * B;
+  float* acc2 = acc + B;
+  float* cnt = acc2 + B;
+  int32_t* pos = a.pos + static_cast<size_t>(u) * B;
+  int32_t* bidx = a.blk_idx + static_cast<size_t>(u) * B;
+  uint32_t* var_key = (B <= kMaxDecodeBudgetLds) ? lds_keys : a.keys + static_cast<size_t>(u) * 2 * B;
+  uint32_t* mas_key = var_key + B;
+
+  if (tid < kQ) slot_of[tid] = 0;
+  KSmallest scope = {0u, 0u}, out = {0u, 0u};
+  if (E > 0) {
+    for (int i = tid; i < n; i += NT) ranking_keys(acc[i], acc2[i], cnt[i], mas_key[i], var_key[i]);
+    __syncthreads();
+    const uint32_t m = min(static_cast<uint32_t>(n), static_cast<uint32_t>(a.scope) + static_cast<uint32_t>(E) - 1u);
+    scope = select_k_smallest<NT>([&](int i) { return var_key[i]; }, n, m, sel_sh);
+    out = select_k_smallest<NT>(
+        [&](int i) -> uint32_t { return scope.has(var_key[i], i) ? mas_key[i] : 0xffffffffu; }, n,
+        static_cast<uint32_t>(E), sel_sh);
+  }
+  auto is_target = [&](int j) -> bool {
+    if (j >= n) return j < n_new;  // still-empty slot taken by the block
+    if (E == 0) return false;
+    const uint32_t k2 = scope.has(var_key[j], j) ? mas_key[j] : 0xffffffffu;
+    return out.has(k2, j);
+  };
+  // ordered assignment: thread t owns the contiguous slots [t*c, (t+1)*c); the i-th target gets block token i
+  const int c = (B + NT - 1) / NT;
+  const int lo = min(B, tid * c), hi = min(B, lo + c);
+  uint32_t mine = 0;
+  for (int j = lo; j < hi; ++j) mine += (j < n_new && is_target(j)) ? 1u : 0u;
+  uint32_t total;
+  uint32_t rank = block_exclusive_scan<NT>(mine, scan_sh, total);
+  const int qp0 = a.qpos0[u];
+  for (int j = lo; j < hi; ++j) {
+    int bi = -1;
+    if (j < n_new && is_target(j) && rank < static_cast<uint32_t>(b)) {
+      bi = static_cast<int>(rank++);
+      slot_of[bi] = j;
+      const bool held = j < n;  // the slot held a token that is now evicted
+      if (a.evicted_slot) a.evicted_slot[static_cast<size_t>(u) * b + bi] = held ? j : -1;
+      if (a.evicted_pos) a.evicted_pos[static_cast<size_t>(u) * b + bi] = held ? pos[j] : -1;
+      pos[j] = qp0 + bi;
+      acc[j] = 0.0f;
+      acc2[j] = 0.0f;
+      cnt[j] = 0.0f;
+    }
+    bidx[j] = bi;
+  }
+  __syncthreads();
+  // the block's K / V rows go into their slots: 16 lanes x 16 bytes per row
+  const size_t in_base = static_cast<size_t>(u) * b * kRowBytes;
+  for (int i = tid / 16; i < b; i += NT / 16) {
+    const size_t dst = (static_cast<size_t>(u) * B + slot_of[i]) * kRowBytes + (tid & 15) * 16;
+    const size_t src = in_base + static_cast<size_t>(i) * kRowBytes + (tid & 15) * 16;
+    *reinterpret_cast<uint4*>(static_cast<char*>(a.K) + dst) = load16(static_cast<const char*>(a.k_new) + src);
+    *reinterpret_cast<uint4*>(static_cast<char*>(a.V) + dst) = load16(static_cast<const char*>(a.v_new) + src);
+  }
+  if (tid == 0) a.n_used[u] = n_new;
+}
+
+// ------------------------------------------------------------------------------------------------
+struct StagedKV {
+  uint4 k[8], v[8];  // this thread's 128 bytes of a 64 x 256 B tile of K and of V (128 threads)
+};
+__device__ __forceinline__ void kv_load(StagedKV& s, const char* Kb, const char* Vb, int row0, int last_row) {
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    int row = row0 + (t >> 4) + 8 * i;
+    row = row < last_row ? row : last_row;  // slots past the end are masked by the caller
+    const size_t off = static_cast<size_t>(row) * kRowBytes + (t & 15) * 16;
+    s.k[i] = load16(Kb + off);
+    s.v[i] = load16(Vb + off);
+  }
+}
+__device__ __forceinline__ void kv_store(const StagedKV& s, char* tileK, char* tileV) {
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int off = ((t >> 4) + 8 * i) * kLdsRow + (t & 15) * 16;
+    *reinterpret_cast<uint4*>(tileK + off) = s.k[i];
+    *reinterpret_cast<uint4*>(tileV + off) = s.v[i];
+  }
+}
+
+__global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char lds_dyn[];  // K[2] and V[2] tiles; reused for the merge
+  __shared__ __attribute__((aligned(16))) int32_t bidx_s[2][kTile];
+  __shared__ __attribute__((aligned(16))) int32_t pos_s[2][kTile];
+  __shared__ float merge_m[kQ], merge_l[kQ];
+  const int u = blockIdx.y, split = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int half = lane >> 5, qi = lane & 31;  // this lane's query (block token index)
+  const int B = a.B, b = a.block;
+  const int n = a.n_used[u];  // already counts the block's tokens
+  const int row0 = split * a.rows_per_split;
+  const int row1 = min(n, row0 + a.rows_per_split);
+  const size_t pidx = static_cast<size_t>(u) * a.splits + split;
+  const char* Kb = static_cast<const char*>(a.K) + static_cast<size_t>(u) * B * kRowBytes;
+  const char* Vb = static_cast<const char*>(a.V) + static_cast<size_t>(u) * B * kRowBytes;
+  const int32_t* bidx = a.blk_idx + static_cast<size_t>(u) * B;
+  const int32_t* pos = a.pos + static_cast<size_t>(u) * B;
+  float* z = a.z + static_cast<size_t>(u) * kQ * B;
+  const float sc = a.scale_log2;
+  const int w = a.recency_window;
+  const float rb = a.recency_bias_log2;
+  const int qp = a.qpos0[u] + qi;
+
+  // B operand: the block's queries (lanes beyond the block reuse its last query; their results are dropped)
+  uint4 own[kKSteps];
+  {
+    const char* qrow = static_cast<const char*>(a.q) + (static_cast<size_t>(u) * b + min(qi, b - 1)) * kRowBytes;
+#pragma unroll
+    for (int kk = 0; kk < kKSteps; ++kk) own[kk] = load16(qrow + kk * 32 + half * 16);
+  }
+  float m = -INFINITY, l = 0.0f;
+  f32x16 o[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db) o[db] = f32x16{0};
+  const int tr_off = transposed_fragment_offset();
+
+  const int n_tiles = row1 > row0 ? (row1 - row0 + kTile - 1) / kTile : 0;
+  StagedKV st;
+  int32_t st_bidx = -1, st_pos = 0;
+  auto fetch = [&](int t) {
+    kv_load(st, Kb, Vb, row0 + t * kTile, n - 1);
+    if (tid < kTile) {
+      const int slot = min(row0 + t * kTile + tid, n - 1);
+      st_bidx = bidx[slot];
+      st_pos = pos[slot];
+    }
+  };
+  if (n_tiles > 0) fetch(0);
+  for (int t = 0; t < n_tiles; ++t) {
+    char* const tileK = lds_dyn + (t & 1) * kTileBytes;
+    char* const tileV = lds_dyn + (2 + (t & 1)) * kTileBytes;
+    kv_store(st, tileK, tileV);
+    if (tid < kTile) { bidx_s[t & 1][tid] = st_bidx; pos_s[t & 1][tid] = st_pos; }
+    __syncthreads();
+    if (t + 1 < n_tiles) fetch(t + 1);
+    const int sb = row0 + t * kTile + 32 * wave;  // first slot of this wave's half-tile
+    if (sb >= row1) continue;                      // wave-uniform; no barrier below in this iteration
+    // ---- scores of 32 slots x 32 queries
+    f32x16 sacc;
+    {
+      const char* p = tileK + (32 * wave + (lane & 31)) * kLdsRow + half * 16;
+      const f32x16 zero = {0};
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+          __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p)), __builtin_bit_cast(bf16x8, own[0]), zero, 0, 0, 0);
+#pragma unroll
+      for (int kk = 1; kk < kKSteps; ++kk)
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+            __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p + kk * 32)),
+            __builtin_bit_cast(bf16x8, own[kk]), sacc, 0, 0, 0);
+    }
+    // ---- base-2 logits: a slot is visible if it exists and does not hold a later token of the block
+    float tv[16];
+    float mb = -INFINITY;
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      const int base = 32 * wave + 8 * g4 + 4 * half;  // index inside the tile of 4 consecutive slots
+      const int4 bi = *reinterpret_cast<const int4*>(&bidx_s[t & 1][base]);
+      const int4 ps = *reinterpret_cast<const int4*>(&pos_s[t & 1][base]);
+      const int biv[4] = {bi.x, bi.y, bi.z, bi.w};
+      const int psv[4] = {ps.x, ps.y, ps.z, ps.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int slot = row0 + t * kTile + base + e;
+        float x = sacc[4 * g4 + e] * sc;
+        if (w > 0) {
+          const int dlt = qp - psv[e];
+          if (dlt >= 0 && dlt < w) x += rb;
+        }
+        if (slot >= row1 || biv[e] > qi) x = -INFINITY;
+        tv[4 * g4 + e] = x;
+        mb = fmaxf(mb, x);
+      }
+      const int slot0 = row0 + t * kTile + base;
+      if (qi < b && slot0 < row1) {  // logits of real queries and real slots are kept for the statistics
+        *reinterpret_cast<float4*>(z + static_cast<size_t>(qi) * B + slot0) =
+            make_float4(tv[4 * g4], tv[4 * g4 + 1], tv[4 * g4 + 2], tv[4 * g4 + 3]);
+      }
+    }
+    mb = fmaxf(mb, __shfl_xor(mb, 32, kWave));  // both lane halves feed one matrix product
+    const float m_new = fmaxf(m, mb);
+    if (__any(m_new > m)) {
+      const float alpha = (m_new > -INFINITY) ? fast_exp2(m - m_new) : 1.0f;
+      l *= alpha;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+    }
+    m = m_new;
+    bf16x8 pfrag[2];
+    float sum = 0.0f;
+    const float ref = (m_new > -INFINITY) ? m_new : 0.0f;  // nothing visible yet: every term is 2^-inf = 0
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float pv = fast_exp2(tv[r] - ref);
+      sum += pv;
+      pfrag[r >> 3][r & 7] = static_cast<__bf16>(pv);
+    }
+    l += sum;
+    // ---- O^T += V^T . P^T
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const char* vt = tileV + (32 * wave + ks * 16) * kLdsRow + tr_off;
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        const uint2 lo = lds_read_transposed(vt + db * 64);
+        const uint2 hi = lds_read_transposed(vt + 8 * kLdsRow + db * 64);
+        const uint4 afrag = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, afrag), pfrag[ks], o[db], 0, 0, 0);
+      }
+    }
+  }
+  l += __shfl_xor(l, 32, kWave);  // the lane halves summed different slots of the same query
+
+  // ---- merge the two waves (wave 1 hands its state to wave 0 through LDS), then write the split's partial
+  __syncthreads();  // everybody is done with the tiles
+  float* mo = reinterpret_cast<float*>(lds_dyn);  // [32 queries][128 dims]
+  if (wave == 1) {
+    if (half == 0) { merge_m[qi] = m; merge_l[qi] = l; }
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mo[qi * D + db * 32 + 8 * (r >> 2) + 4 * half + (r & 3)] = o[db][r];
+  }
+  __syncthreads();
+  if (wave == 0) {
+    const float m1 = merge_m[qi], l1 = merge_l[qi];
+    const float M = fmaxf(m, m1);
+    const float w0 = (m > -INFINITY) ? fast_exp2(m - M) : 0.0f;
+    const float w1 = (m1 > -INFINITY) ? fast_exp2(m1 - M) : 0.0f;
+    if (half == 0) {
+      a.part_m[pidx * kQ + qi] = M;
+      a.part_l[pidx * kQ + qi] = l * w0 + l1 * w1;
+    }
+    float* po = a.part_o + (pidx * kQ + qi) * D;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int d0 = db * 32 + 8 * g4 + 4 * half;
+        float4 r4;
+        const float4 other = (w1 > 0.0f) ? *reinterpret_cast<const float4*>(mo + qi * D + d0)
+                                         : make_float4(0.0f, 0.0f, 0.0f, 0.0f);  // wave 1 saw nothing: ignore LDS
+        r4.x = o[db][4 * g4 + 0] * w0 + other.x * w1;
+        r4.y = o[db][4 * g4 + 1] * w0 + other.y * w1;
+        r4.z = o[db][4 * g4 + 2] * w0 + other.z * w1;
+        r4.w = o[db][4 * g4 + 3] * w0 + other.w * w1;
+        *reinterpret_cast<float4*>(po + d0) = r4;
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
+  constexpr int NT = kFinThreads;
+  extern __shared__ uint32_t lds_keys[];  // [2][B] when B <= kMaxDecodeBudgetLds
+  __shared__ uint32_t sel_sh[kSelectLdsWords];
+  __shared__ unsigned long long best_sh[NT / kWave];
+  __shared__ float Mq[kQ], invq[kQ];
+  const int u = blockIdx.x, tid = threadIdx.x;
+  const int B = a.B, b = a.block, S = a.splits;
+  const int n = a.n_used[u];
+  const bool full = n >= B;
+  const float* pm = a.part_m + static_cast<size_t>(u) * S * kQ;
+  const float* pl = a.part_l + static_cast<size_t>(u) * S * kQ;
+  const float* po = a.part_o + static_cast<size_t>(u) * S * kQ * D;
+
+  if (tid < kQ) {  // per query: merge the splits' normalisers in split order
+    float M = -INFINITY;
+    for (int s = 0; s < S; ++s) M = fmaxf(M, pm[s * kQ + tid]);
+    float L = 0.0f;
+    for (int s = 0; s < S; ++s) {
+      const float ms = pm[s * kQ + tid];
+      L += (ms > -INFINITY) ? pl[s * kQ + tid] * fast_exp2(ms - M) : 0.0f;
+    }
+    Mq[tid] = M;
+    invq[tid] = 1.0f / L;
+  }
+  __syncthreads();
+  // outputs: b rows of D values
+  for (int idx = tid; idx < b * D; idx += NT) {
+    const int q = idx / D, dd = idx % D;
+    float o = 0.0f;
+    for (int s = 0; s < S; ++s) {
+      const float ms = pm[s * kQ + q];
+      o += (ms > -INFINITY) ? po[(static_cast<size_t>(s) * kQ + q) * D + dd] * fast_exp2(ms - Mq[q]) : 0.0f;
+    }
+    store_elem<kBF16>(a.out, (static_cast<size_t>(u) * b + q) * D + dd, o * invq[q]);
+  }
+  // statistics: every slot receives the probabilities of the rows that attended it
+  float* acc = a.stats + static_cast<size_t>(u) * 3 * B;
+  float* acc2 = acc + B;
+  float* cnt = acc2 + B;
+  const float* z = a.z + static_cast<size_t>(u) * kQ * B;
+  const int32_t* bidx = a.blk_idx + static_cast<size_t>(u) * B;
+  uint32_t* var_key = (B <= kMaxDecodeBudgetLds) ? lds_keys : a.keys + static_cast<size_t>(u) * 2 * B;
+  uint32_t* mas_key = var_key + B;
+  for (int j = tid * 4; j < n; j += NT * 4) {  // B is a multiple of 4 on this path
+    const float4 a1 = *reinterpret_cast<const float4*>(acc + j);
+    const float4 a2 = *reinterpret_cast<const float4*>(acc2 + j);
+    const float4 cc = *reinterpret_cast<const float4*>(cnt + j);
+    const int4 bi = *reinterpret_cast<const int4*>(bidx + j);
+    float s1[4] = {a1.x, a1.y, a1.z, a1.w}, s2[4] = {a2.x, a2.y, a2.z, a2.w}, sc[4] = {cc.x, cc.y, cc.z, cc.w};
+    const int biv[4] = {bi.x, bi.y, bi.z, bi.w};
+    for (int q = 0; q < b; ++q) {
+      const float4 zz = *reinterpret_cast<const float4*>(z + static_cast<size_t>(q) * B + j);
+      const float zv[4] = {zz.x, zz.y, zz.z, zz.w};
+      const float M = Mq[q], inv = invq[q];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (j + e < n && biv[e] <= q) {  // older tokens have index -1: attended by every row
+          const float p = fast_exp2(zv[e] - M) * inv;
+          s1[e] += p;
+          s2[e] += p * p;
+          sc[e] += 1.0f;
+        }
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (full && j + e < n) ranking_keys(s1[e], s2[e], sc[e], mas_key[j + e], var_key[j + e]);
+    *reinterpret_cast<float4*>(acc + j) = make_float4(s1[0], s1[1], s1[2], s1[3]);
+    *reinterpret_cast<float4*>(acc2 + j) = make_float4(s2[0], s2[1], s2[2], s2[3]);
+    *reinterpret_cast<float4*>(cnt + j) = make_float4(sc[0], sc[1], sc[2], sc[3]);
+  }
+  if (full) {  // the victim a following single-token decode step would take
+    __syncthreads();
+    const KSmallest sc = select_k_smallest<NT>([&](int i) { return var_key[i]; }, B,
+                                               static_cast<uint32_t>(a.scope), sel_sh);
+    unsigned long long best = ~0ull;
+    for (int i = tid; i < B; i += NT) {
+      if (sc.has(var_key[i], i)) {
+        const unsigned long long cand = (static_cast<unsigned long long>(mas_key[i]) << 32) | static_cast<uint32_t>(i);
+        best = cand < best ? cand : best;
+      }
+    }
+#pragma unroll
+    for (int msk = 1; msk < kWave; msk <<= 1) {
+      const unsigned long long o2 = __shfl_xor(best, msk, kWave);
+      best = o2 < best ? o2 : best;
+    }
+    __syncthreads();
+    if ((tid & (kWave - 1)) == 0) best_sh[tid / kWave] = best;
+    __syncthreads();
+    if (tid == 0) {
+      unsigned long long bb = best_sh[0];
+      for (int wv = 1; wv < NT / kWave; ++wv) bb = best_sh[wv] < bb ? best_sh[wv] : bb;
+      a.next_slot[u] = static_cast<int>(bb & 0xffffffffu);
+    }
+  } else if (tid == 0) {
+    a.next_slot[u] = -1;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_block(const BlockArgs& a, hipStream_t s) {
+  const size_t key_lds = (a.B <= kMaxDecodeBudgetLds) ? static_cast<size_t>(a.B) * 2 * sizeof(uint32_t) : 0;
+  constexpr size_t kAttLds = 4 * static_cast<size_t>(kTileBytes);  // 68 KiB: above the default dynamic limit
+  static bool attr_done = false;
+  if (!attr_done) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(block_attend), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            static_cast<int>(kAttLds)) != hipSuccess)
+      return hipErrorInvalidValue;
+    attr_done = true;
+  }
+  {
+    ProfScope ps(kProfBlockPrepare, s);
+    hipLaunchKernelGGL(block_prepare, dim3(a.units), dim3(kPrepThreads), key_lds, s, a);
+  }
+  {
+    ProfScope ps(kProfBlockAttend, s);
+    hipLaunchKernelGGL(block_attend, dim3(a.splits, a.units), dim3(kAttThreads), kAttLds, s, a);
+  }
+  {
+    ProfScope ps(kProfBlockFinish, s);
+    hipLaunchKernelGGL(block_finish, dim3(a.units), dim3(kFinThreads), key_lds, s, a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace roco

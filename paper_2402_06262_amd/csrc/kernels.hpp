@@ -56,6 +56,31 @@ struct PrefillArgs {
   uint32_t* mas_key;     // [units][L_max]
 };
 
+constexpr int kMaxBlock = 32;        // tokens per block-wise step (one 32-wide matrix tile of queries)
+constexpr int kMaxBlockSplits = 8;   // split-K partials per unit of the block-wise step
+
+struct BlockArgs {
+  int units, B, scope, block, splits, rows_per_split;
+  float scale_log2;
+  int recency_window;
+  float recency_bias_log2;
+  const void *q, *k_new, *v_new;   // [units][block][128] bf16
+  const int32_t* qpos0;            // [units]
+  void *K, *V;
+  float* stats;
+  int32_t *pos, *n_used, *next_slot;
+  void* out;                       // [units][block][128] bf16
+  int32_t *evicted_slot, *evicted_pos;  // [units][block], may be null
+  // workspace
+  int32_t* blk_idx;                // [units][B]   block token index held by a slot, -1 for older tokens
+  float* z;                        // [units][32][B] base-2 logits
+  float* part_m;                   // [units][splits][32]
+  float* part_l;                   // [units][splits][32]
+  float* part_o;                   // [units][splits][32][128]
+  uint32_t* keys;                  // [units][2][B] when B is too large for LDS
+};
+hipError_t launch_block(const BlockArgs& a, hipStream_t s);  // bf16, head_dim 128, B % 4 == 0
+
 // dtype: 0 = f32, 1 = bf16; head_dim: 64 or 128.  Each returns hipGetLastError() of its launches.
 hipError_t launch_decode(int dtype, int head_dim, const DecodeArgs& a, hipStream_t s);
 int decode_rows_per_pass(int dtype, int head_dim, int unroll);  // granularity of DecodeArgs::rows_per_split

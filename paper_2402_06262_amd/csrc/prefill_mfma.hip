@@ -17,20 +17,14 @@
 // consecutive k-elements starting at 8 * (l / 32) of each 16-wide k-step, for A and for B alike; register r
 // of the result belongs to A-row 8 * (r / 4) + 4 * (l / 32) + (r % 4) and B-row (l % 32).
 #include "kernels.hpp"
+#include "mfma.hpp"
 #include "profile.hpp"
 #include "stream.hpp"
 
 namespace roco {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-constexpr int D = 128;
-constexpr int kTile = 64;                // streamed rows per LDS tile
-constexpr int kRowBytes = D * 2;         // 256
-constexpr int kLdsRow = kRowBytes + 16;  // padded: 16 lanes x 16 B then hit distinct bank groups
-constexpr int kKSteps = D / 16;          // 8 matrix instructions per 32x32 tile
+using namespace mfma;
 
 // A workgroup of WAVES waves owns 64*WAVES rows.  The more rows a workgroup owns, the fewer times the other
 // operand is streamed from L2 / Infinity Cache (the bytes per flop of that stream are 1 / (2 * owned rows)).
@@ -115,17 +109,6 @@ __device__ __forceinline__ bool locate(int units, int pairs, int& unit, int& pai
   unit = (seq / pairs) * 8 + die;
   pair = seq % pairs;
   return unit < units;
-}
-
-__device__ __forceinline__ float max16(const f32x16& s) {
-  float a = fmaxf(fmaxf(s[0], s[1]), s[2]);   // the compiler folds these into three-operand maxima
-  a = fmaxf(fmaxf(a, s[3]), s[4]);
-  a = fmaxf(fmaxf(a, s[5]), s[6]);
-  a = fmaxf(fmaxf(a, s[7]), s[8]);
-  a = fmaxf(fmaxf(a, s[9]), s[10]);
-  a = fmaxf(fmaxf(a, s[11]), s[12]);
-  a = fmaxf(fmaxf(a, s[13]), s[14]);
-  return fmaxf(a, s[15]);
 }
 
 // Online log-sum-exp update of one lane with the 16 scores of a tile.
@@ -375,16 +358,7 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_mfma(PrefillArg
 // at row i/4, column 4*(i%4) of the block, lane i receives rows 0..3 of column i.)  The k-slot order of both
 // operands follows the accumulator layout of the score tile: slots 0-3 are keys 4h..4h+3 and slots 4-7 are keys
 // 8+4h..8+4h+3 of a 16-key step, h = lane / 32.
-typedef short v4i16 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) v4i16 lds_v4i16;
-
-__device__ __forceinline__ uint2 lds_read_transposed(const char* p) {
-  // the pointer is known to address LDS; the builtin wants it in that address space
-  const v4i16 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(p));
-  return __builtin_bit_cast(uint2, v);
-}
-
-constexpr int kOutTileBytes = kTile * kLdsRow;  // one K or V tile in LDS
+constexpr int kOutTileBytes = kTileBytes;  // one K or V tile in LDS
 
 template <int WAVES>
 __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_out_mfma(PrefillArgs a) {
@@ -416,10 +390,7 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_out_mfma(PrefillAr
 #pragma unroll
   for (int db = 0; db < 4; ++db) o[db] = f32x16{0};
 
-  // per-lane byte offset of the transpose reads inside a V tile: 16-lane group g = lane / 16 reads columns
-  // 16 * (g % 2) .. +15 of a 32-column block, key rows 4 * (g / 2) .. +3
-  const int i16 = lane & 15, grp = lane >> 4;
-  const int tr_off = ((grp >> 1) * 4 + (i16 >> 2)) * kLdsRow + ((grp & 1) * 16 + (i16 & 3) * 4) * 2;
+  const int tr_off = transposed_fragment_offset();
 
   const int last_key = min(len, q0 + kOwnQ) - 1;
   const int n_tiles = last_key / kTile + 1;

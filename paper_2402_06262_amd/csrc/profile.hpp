@@ -7,7 +7,8 @@ namespace roco {
 enum ProfKernel : int {
   kProfDecodeSelect = 0, kProfDecodeAttend = 1, kProfDecodeFinish = 2,
   kProfPrefillRows = 3, kProfPrefillColumns = 4, kProfPrefillSelect = 5, kProfPrefillGather = 6, kProfReadProbe = 7,
-  kProfKernels = 8
+  kProfBlockPrepare = 8, kProfBlockAttend = 9, kProfBlockFinish = 10,
+  kProfKernels = 11
 };
 
 extern int g_prof_which;  // -1 = off

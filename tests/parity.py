@@ -215,3 +215,47 @@ def check_cache_unit(sess_host: dict, u: int, state: "orc.CacheState", what: str
 def cache_to_host(sess: GpuSession) -> dict:
     c = sess.cache
     return dict(K=to_host(c.K), V=to_host(c.V), stats=to_host(c.stats), pos=to_host(c.pos), n_used=to_host(c.n_used))
+
+
+def gpu_encode_block(sess: GpuSession, block: int, q: np.ndarray, k: np.ndarray, v: np.ndarray, qpos0: Sequence[int],
+                     ws: torch.Tensor):
+    """q, k, v: [units, block, d] float32 host arrays.  Returns (out, evicted_slot, evicted_pos) on the host."""
+    c, p = sess.cache, sess.params
+    dq, dk, dv = to_dev(q, sess.dtype), to_dev(k, sess.dtype), to_dev(v, sess.dtype)
+    dqpos = torch.tensor(list(qpos0), dtype=torch.int32, device="cuda")
+    out = torch.zeros((p.units, block, p.head_dim), dtype=torch_dtype(sess.dtype), device="cuda")
+    es = torch.full((p.units, block), -7, dtype=torch.int32, device="cuda")
+    ep = torch.full((p.units, block), -7, dtype=torch.int32, device="cuda")
+    roco.roco_encode_block(p, block, dq, dk, dv, dqpos, c.K, c.V, c.stats, c.pos, c.n_used, c.next_slot, out, es, ep, ws)
+    torch.cuda.synchronize()
+    return to_host(out), to_host(es), to_host(ep)
+
+
+def lockstep_block_unit(state: "orc.CacheState", u: int, g_out, g_slot, g_pos, q, k, v, qpos0: int, scope: int,
+                        scale: float, dtype: str, recency_window: int = 0, recency_bias: float = 0.0,
+                        what: str = "") -> TieCount:
+    """Advance the oracle state of unit `u` by one block and compare with the library's block step."""
+    ties = TieCount()
+    b = q.shape[0]
+    n = state.n_used
+    E = max(0, n + b - state.budget)
+    snapshot = state.copy()
+    r = orc.encode_block(state, q, k, v, qpos0, scope, scale, recency_window, recency_bias)
+    g_ev = sorted(int(x) for x in g_slot[u] if x >= 0)
+    if E > 0:
+        ties.decode_decisions += 1
+        if g_ev != sorted(int(x) for x in r.evicted_slot if x >= 0):
+            eps_m, eps_v = tie_band.bands(snapshot.acc[:n], snapshot.acc2[:n], snapshot.count[:n])
+            ok, why = tie_band.admissible_eviction(r.mas, r.var, eps_m, eps_v, scope, E, g_ev)
+            assert ok, f"{what} unit {u}: evicted slots {g_ev} outside the tie band ({why})"
+            ties.decode_ties += 1
+            for name in ("K", "V", "acc", "acc2", "count", "pos"):
+                getattr(state, name)[...] = getattr(snapshot, name)
+            state.n_used = snapshot.n_used
+            r = orc.encode_block(state, q, k, v, qpos0, scope, scale, recency_window, recency_bias,
+                                 force_evicted=np.array(g_ev))
+    assert np.array_equal(g_slot[u], r.evicted_slot), f"{what} unit {u}: evicted_slot {g_slot[u]} != {r.evicted_slot}"
+    assert np.array_equal(g_pos[u], r.evicted_pos), f"{what} unit {u}: evicted_pos {g_pos[u]} != {r.evicted_pos}"
+    for i in range(b):
+        assert_out_close(g_out[u, i], r.out[i], dtype, f"{what} unit {u} out[{i}]")
+    return ties

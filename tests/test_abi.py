@@ -23,7 +23,7 @@ def test_library_loads_and_exports_every_declared_symbol():
     names = declared_functions()
     assert {"roco_prefill_compress", "roco_decode_step", "roco_prefill_workspace_bytes",
             "roco_decode_workspace_bytes", "roco_strerror", "roco_version", "roco_select_victims",
-            "roco_probe_cache_read", "roco_profile_sampling"} <= set(names)
+            "roco_probe_cache_read", "roco_profile_sampling", "roco_encode_block", "roco_block_workspace_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in roco.h but not exported"
     assert roco.roco_version() == 1
@@ -89,6 +89,30 @@ def test_null_misaligned_and_small_workspace_are_rejected_on_the_host():
         assert _prefill(p, ptrs=ptrs) == EINVAL
     assert _prefill(p, L_max=0) == EINVAL
     assert _prefill(p, L_max=64, ws_bytes=roco.prefill_workspace_bytes(p, 64) - 1) == EWORKSPACE
+
+
+def test_encode_block_validates_on_the_host():
+    EUNS = EUNSUPPORTED
+    lib = roco.load_library()
+    p = roco.RocoParams(4, 128, 256, 16, roco.ROCO_BF16)
+    need = roco.block_workspace_bytes(p, 8)
+    assert need > 4 * 32 * 256 * 4
+    args = [0x1000] * 14
+
+    def call(params, block, a=args, ws=need):
+        return lib.roco_encode_block(ctypes.byref(params), block, *a[:14], ws, None)
+
+    assert call(p, 0) == EINVAL and call(p, 257) == EINVAL
+    assert call(p, 33) == EUNS
+    assert call(roco.RocoParams(4, 128, 256, 16, roco.ROCO_F32), 4) == EUNS
+    assert call(roco.RocoParams(4, 64, 256, 16, roco.ROCO_BF16), 4) == EUNS
+    assert call(roco.RocoParams(4, 128, 254, 16, roco.ROCO_BF16), 4) == EUNS  # budget not a multiple of 4
+    assert roco.block_workspace_bytes(roco.RocoParams(4, 64, 256, 16, roco.ROCO_BF16), 4) == 0
+    assert call(p, 8, ws=need - 1) == EWORKSPACE
+    for bad in [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 13]:  # evicted_slot / evicted_pos (11, 12) may be NULL
+        a = list(args)
+        a[bad] = None
+        assert call(p, 8, a) == EINVAL
 
 
 def test_loading_fails_loudly_when_the_library_is_missing(monkeypatch):

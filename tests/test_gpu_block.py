@@ -85,3 +85,65 @@ def test_block_steps_with_recency_bias_and_partially_filled_units():
 
 def test_block_step_many_splits_budget_2048():
     drive(2, 128, 2048, 64, [2300, 2048], [32, 16, 32], seed=73, tag="b2048")
+
+
+def test_block_steps_at_the_serving_shape_all_512_units():
+    """Workload 3's shape: all 512 units prefilled 3072 -> 2048, then blocks of 16 tokens; sampled units in
+    lock-step with the oracle, any-size properties on every unit."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+    import paper_2402_06262_amd as roco
+    from inputs import unit_ids
+    P = _P()
+    cfg = CONFIGS[2]
+    L, B, s, d, U = cfg.prompt_len, cfg.budget, cfg.scope, cfg.head_dim, cfg.units
+    b, n_blocks = 16, 6
+    ids = unit_ids(cfg)
+    T = L + b * n_blocks
+    Q = np.empty((U, T, d), np.float32); K = np.empty_like(Q); V = np.empty_like(Q)
+
+    def one(i):
+        un = make_unit(cfg, *ids[i], total_len=T)
+        Q[i], K[i], V[i] = un.Q, un.K, un.V
+
+    with ThreadPoolExecutor(min(16, len(os.sched_getaffinity(0)))) as ex:
+        list(ex.map(one, range(U)))
+    sc = 1.0 / math.sqrt(d)
+    sess = P.make_session(U, d, B, s, "bf16")
+    c, p = sess.cache, sess.params
+    dt = torch.bfloat16
+    up = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda().to(dt)
+    dQ, dK, dV = up(Q[:, :L]), up(K[:, :L]), up(V[:, :L])
+    dlen = torch.full((U,), L, dtype=torch.int32, device="cuda")
+    wsp = torch.empty(roco.prefill_workspace_bytes(p, L), dtype=torch.uint8, device="cuda")
+    roco.roco_prefill_compress(p, dQ, dK, dV, dlen, L, c.K, c.V, c.stats, c.pos, c.n_used, c.next_slot, None, wsp)
+    torch.cuda.synchronize()
+    sample = [0, 101, 333, 511]
+    states = [orc.prefill_compress(Q[u, :L], K[u, :L], V[u, :L], L, B, s, sc).cache for u in sample]
+    for k, u in enumerate(sample):
+        assert np.array_equal(c.pos[u].cpu().numpy(), states[k].pos)
+    wsb = torch.empty(roco.block_workspace_bytes(p, b), dtype=torch.uint8, device="cuda")
+    out = torch.empty((U, b, d), dtype=dt, device="cuda")
+    es = torch.empty((U, b), dtype=torch.int32, device="cuda"); ep = torch.empty_like(es)
+    sidx = torch.tensor(sample, device="cuda")
+    ties = P.TieCount()
+    for i in range(n_blocks):
+        t = L + i * b
+        qp0 = torch.full((U,), t, dtype=torch.int32, device="cuda")
+        count_before = c.stats[:, 2].double().sum(1)
+        roco.roco_encode_block(p, b, up(Q[:, t:t + b]), up(K[:, t:t + b]), up(V[:, t:t + b]), qp0, c.K, c.V, c.stats,
+                               c.pos, c.n_used, c.next_slot, out, es, ep, wsb)
+        torch.cuda.synchronize()
+        assert bool((c.n_used == B).all()) and bool((es >= 0).all()) and bool((es < B).all())
+        assert bool((torch.gather(c.pos, 1, es.long()) == (qp0[:, None] + torch.arange(b, device="cuda")[None])).all())
+        assert bool(torch.isfinite(out.float()).all())
+        assert bool((es[:, 1:] > es[:, :-1]).all())  # tokens take the freed slots in ascending order
+        g_out, g_slot, g_pos = P.to_host(out[sidx]), P.to_host(es[sidx]), P.to_host(ep[sidx])
+        for k, u in enumerate(sample):
+            ties += P.lockstep_block_unit(states[k], k, g_out, g_slot, g_pos, Q[u, t:t + b], K[u, t:t + b], V[u, t:t + b],
+                                          t, s, sc, "bf16", what=f"[cfg3-block] block {i} unit {u}")
+        host = dict(K=P.to_host(c.K[sidx]), V=P.to_host(c.V[sidx]), stats=P.to_host(c.stats[sidx]),
+                    pos=P.to_host(c.pos[sidx]), n_used=P.to_host(c.n_used[sidx]))
+        for k, u in enumerate(sample):
+            P.check_cache_unit(host, k, states[k], what=f"[cfg3-block] block {i} unit {u}")
+    print("[cfg3-block] ties", ties, flush=True)

@@ -365,3 +365,62 @@ def encode_block(state: CacheState, Qb, Kb, Vb, qpos0: int, scope: int, scale: f
         state.acc2[:n_new] += probs[i] * probs[i]
         state.count[:n_new] += (block_index[:n_new] <= i).astype(F64)
     return BlockResult(out, probs, targets, evicted_slot, evicted_pos, mas, var)
+
+
+# ---------------------------------------------------------------------------
+# grouped-query attention (section 5.3 "Extension to Grouped-Query Attention"; appendix A)
+# ---------------------------------------------------------------------------
+
+@dataclass
+class GroupDecodeResult:
+    out: np.ndarray  # [g, d] one attention output per query head of the group
+    probs: np.ndarray  # [g, n_used]
+    mean_probs: np.ndarray  # [n_used] group-wise averaged attention: what the statistics receive
+    evicted_slot: int
+    evicted_pos: int
+    written_slot: int
+    mas: Optional[np.ndarray]
+    var: Optional[np.ndarray]
+
+
+def decode_step_gqa(state: CacheState, Qg, k_new, v_new, qpos: int, scope: int, scale: float,
+                    recency_window: int = 0, recency_bias: float = 0.0,
+                    force_victim: Optional[int] = None) -> GroupDecodeResult:
+    """One decode step of a key/value head shared by g query heads.
+
+    The paper extends attention-based policies to GQA / MQA by updating the importance score with the group-wise
+    averaged attention score.  Here: every query head of the group attends the shared cache as usual; the cache's
+    statistics receive the mean of the g probability vectors (Acc += mean p, Acc2 += (mean p)^2, Count += 1).
+    The eviction rule is unchanged.  g = 1 is exactly `decode_step`.
+    """
+    Qg = np.asarray(Qg, dtype=F64)
+    g = Qg.shape[0]
+    B = state.budget
+    mas = var = None
+    if state.n_used == B:
+        mas = mean_attention_score(state.acc, state.count)
+        var = attention_variance(state.acc, state.acc2, state.count)
+        slot = select_victim(mas, var, scope) if force_victim is None else int(force_victim)
+        evicted_slot, evicted_pos = slot, int(state.pos[slot])
+    else:
+        slot = state.n_used
+        state.n_used += 1
+        evicted_slot, evicted_pos = -1, -1
+    state.K[slot] = np.asarray(k_new, dtype=F64)
+    state.V[slot] = np.asarray(v_new, dtype=F64)
+    state.pos[slot] = qpos
+    state.acc[slot] = state.acc2[slot] = state.count[slot] = 0.0
+    n = state.n_used
+    bias = _recency(np.array([qpos]), state.pos[:n], recency_window, recency_bias)[0]
+    probs = np.zeros((g, n), dtype=F64)
+    out = np.zeros((g, state.V.shape[1]), dtype=F64)
+    for h in range(g):
+        z = (state.K[:n] @ Qg[h]) * F64(scale) + bias
+        p = np.exp(z - z.max())
+        probs[h] = p / p.sum()
+        out[h] = probs[h] @ state.V[:n]
+    mean_p = probs.sum(axis=0) / F64(g)
+    state.acc[:n] += mean_p
+    state.acc2[:n] += mean_p * mean_p
+    state.count[:n] += 1.0
+    return GroupDecodeResult(out, probs, mean_p, evicted_slot, evicted_pos, slot, mas, var)

@@ -445,3 +445,46 @@ def test_blockwise_eviction_keeps_the_budget_and_its_statistics_equal_a_brute_fo
         assert st.count[j] == len(rows)
         assert math.isclose(st.acc[j], math.fsum(rows), rel_tol=1e-12)
         assert math.isclose(st.acc2[j], math.fsum(x * x for x in rows), rel_tol=1e-12)
+
+
+# ---------------------------------------------------------------------------- grouped-query attention
+
+def test_group_of_one_is_exactly_a_decode_step_and_identical_heads_change_nothing():
+    rng = np.random.default_rng(41)
+    L, d, B, s = 26, 4, 10, 3
+    Q, K, V = rand_unit(rng, L + 5, d)
+    a = orc.prefill_compress(Q[:L], K[:L], V[:L], L, B, s, 0.5).cache
+    b, c = a.copy(), a.copy()
+    for t in range(L, L + 5):
+        ra = orc.decode_step(a, Q[t], K[t], V[t], t, s, 0.5)
+        rb = orc.decode_step_gqa(b, Q[t:t + 1], K[t], V[t], t, s, 0.5)
+        rc = orc.decode_step_gqa(c, np.stack([Q[t]] * 3), K[t], V[t], t, s, 0.5)
+        assert np.array_equal(ra.out, rb.out[0]) and ra.evicted_slot == rb.evicted_slot == rc.evicted_slot
+        assert np.allclose(rc.out, ra.out[None], rtol=1e-13)
+        for x, y, z in ((a.acc, b.acc, c.acc), (a.acc2, b.acc2, c.acc2), (a.count, b.count, c.count)):
+            assert np.array_equal(x, y) and np.allclose(x, z, rtol=1e-13)
+
+
+def test_group_statistics_receive_the_mean_of_independently_computed_softmaxes():
+    rng = np.random.default_rng(42)
+    L, d, B, s, g = 18, 5, 18, 4, 4
+    Q, K, V = rand_unit(rng, L, d)
+    st = orc.prefill_compress(Q, K, V, L, B + 1, s, 0.3).cache  # one free slot: the step appends
+    Qg = rng.standard_normal((g, d))
+    kn, vn = rng.standard_normal(d), rng.standard_normal(d)
+    acc0, acc20, cnt0 = st.acc.copy(), st.acc2.copy(), st.count.copy()
+    r = orc.decode_step_gqa(st, Qg, kn, vn, L, s, 0.3)
+    keys = np.vstack([K, kn])
+    vals = np.vstack([V, vn])
+    rows = []
+    for h in range(g):
+        z = 0.3 * keys @ Qg[h]
+        w = np.exp(z - z.max())
+        w /= w.sum()
+        rows.append(w)
+        assert np.allclose(r.out[h], w @ vals, rtol=1e-12)
+    mean = np.mean(rows, axis=0)
+    assert np.allclose(r.mean_probs, mean, rtol=1e-12) and abs(mean.sum() - 1.0) < 1e-12
+    assert np.allclose(st.acc[:L + 1], np.append(acc0[:L], 0.0) + mean, rtol=1e-12)
+    assert np.allclose(st.acc2[:L + 1], np.append(acc20[:L], 0.0) + mean ** 2, rtol=1e-12)
+    assert np.array_equal(st.count[:L + 1], np.append(cnt0[:L], 0.0) + 1.0)  # one count per step, not per head

@@ -163,6 +163,35 @@ int roco_encode_block(const roco_params* params, int32_t block,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Grouped-query attention (section 5.3, "Extension to Grouped-Query Attention"; appendix A): a unit is one
+ * key/value head shared by `group` query heads (multi-query attention is group = all heads).  The statistics of a
+ * unit receive the group-wise averaged probability once per encoded token:
+ * Acc += mean_h p_h, Acc2 += (mean_h p_h)^2, Count += 1; eviction, slot assignment and everything else are those
+ * of roco_encode_block.  K and V are streamed once for the whole group and block.
+ *
+ * roco_encode_block_gqa: `block` tokens per unit, block * group <= 32 (else ROCO_EUNSUPPORTED); group = 1 is
+ * roco_encode_block.  roco_decode_step_gqa: block = 1, so group <= 32; group = 1 is roco_decode_step.
+ *
+ * q                in  [units, block, group, d] dtype      ([units, group, d] for the decode step)
+ * k_new, v_new     in  [units, block, d]        dtype      ([units, d])
+ * qpos0 / qpos     in  [units] int32     position of the (first) new token
+ * out              out [units, block, group, d] dtype      ([units, group, d])
+ * evicted_slot, evicted_pos  out [units, block] int32 as in roco_encode_block (either may be NULL)
+ * workspace        roco_block_workspace_bytes(params, block) bytes
+ * Supported shapes and error behaviour as for roco_encode_block; group < 1 is ROCO_EINVAL.
+ */
+int roco_encode_block_gqa(const roco_params* params, int32_t block, int32_t group,
+                          const void* q, const void* k_new, const void* v_new, const int32_t* qpos0,
+                          void* K_cache, void* V_cache, float* stats, int32_t* pos, int32_t* n_used,
+                          int32_t* next_slot, void* out, int32_t* evicted_slot, int32_t* evicted_pos,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+int roco_decode_step_gqa(const roco_params* params, int32_t group,
+                         const void* q, const void* k_new, const void* v_new, const int32_t* qpos,
+                         void* K_cache, void* V_cache, float* stats, int32_t* pos, int32_t* n_used,
+                         int32_t* next_slot, void* out, int32_t* evicted_slot, int32_t* evicted_pos,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Victim selection alone (section 4.3): for every full unit, next_slot[u] = the slot of lowest Acc/Count among
  * the s slots of lowest variance; -1 for units that are not full.  Only needed after the caller has edited
  * stats / n_used itself.  stats in [units,3,B], n_used in [units], next_slot out [units]; the workspace is the

@@ -424,3 +424,70 @@ def decode_step_gqa(state: CacheState, Qg, k_new, v_new, qpos: int, scope: int, 
     state.acc2[:n] += mean_p * mean_p
     state.count[:n] += 1.0
     return GroupDecodeResult(out, probs, mean_p, evicted_slot, evicted_pos, slot, mas, var)
+
+
+@dataclass
+class GroupBlockResult:
+    out: np.ndarray  # [b, g, d]
+    mean_probs: List[np.ndarray]  # mean_probs[i][slot]: group-wise averaged attention of block token i (0 where unseen)
+    slots: np.ndarray
+    evicted_slot: np.ndarray
+    evicted_pos: np.ndarray
+    mas: Optional[np.ndarray]
+    var: Optional[np.ndarray]
+
+
+def encode_block_gqa(state: CacheState, Qb, Kb, Vb, qpos0: int, scope: int, scale: float,
+                     recency_window: int = 0, recency_bias: float = 0.0,
+                     force_evicted: Optional[np.ndarray] = None) -> GroupBlockResult:
+    """Block-wise evict-and-encode of a key/value head shared by g query heads: Qb is [b, g, d], Kb / Vb [b, d].
+
+    Eviction and slot assignment exactly as in `encode_block`; token i of the block is attended from by its g
+    query heads, each over the retained tokens and the block's tokens 0..i, and the statistics receive the mean of
+    those g probability vectors once per token (section 5.3, both extensions together).  g = 1 is `encode_block`,
+    b = 1 is `decode_step_gqa`.
+    """
+    Qb, Kb, Vb = (np.asarray(x, dtype=F64) for x in (Qb, Kb, Vb))
+    b, g = Qb.shape[0], Qb.shape[1]
+    B, n = state.budget, state.n_used
+    assert 1 <= b <= B
+    E = max(0, n + b - B)
+    mas = var = None
+    evicted = np.zeros(0, dtype=np.int64)
+    if E > 0:
+        mas = mean_attention_score(state.acc[:n], state.count[:n])
+        var = attention_variance(state.acc[:n], state.acc2[:n], state.count[:n])
+        evicted = select_evictions(mas, var, scope, E) if force_evicted is None else \
+            np.sort(np.asarray(force_evicted, dtype=np.int64))
+    targets = np.sort(np.concatenate([evicted, np.arange(n, min(B, n + b), dtype=np.int64)]))
+    assert targets.shape[0] == b
+    was_evicted = np.isin(targets, evicted)
+    evicted_slot = np.where(was_evicted, targets, -1)
+    evicted_pos = np.where(was_evicted, state.pos[targets], -1)
+    block_index = np.full(B, -1, dtype=np.int64)
+    for i, slot in enumerate(targets):
+        state.K[slot], state.V[slot] = Kb[i], Vb[i]
+        state.pos[slot] = qpos0 + i
+        state.acc[slot] = state.acc2[slot] = state.count[slot] = 0.0
+        block_index[slot] = i
+    state.n_used = n_new = min(B, n + b)
+    out = np.zeros((b, g, Vb.shape[1]), dtype=F64)
+    means = []
+    for i in range(b):
+        seen = np.flatnonzero(block_index[:n_new] <= i)
+        bias = _recency(np.array([qpos0 + i]), state.pos[seen], recency_window, recency_bias)[0]
+        total = np.zeros(seen.shape[0], dtype=F64)
+        for h in range(g):
+            z = (state.K[seen] @ Qb[i, h]) * F64(scale) + bias
+            p = np.exp(z - z.max())
+            p = p / p.sum()
+            out[i, h] = p @ state.V[seen]
+            total += p
+        full = np.zeros(n_new, dtype=F64)
+        full[seen] = total / F64(g)
+        means.append(full)
+    for i in range(b):
+        state.acc[:n_new] += means[i]
+        state.acc2[:n_new] += means[i] * means[i]
+        state.count[:n_new] += (block_index[:n_new] <= i).astype(F64)
+    return GroupBlockResult(out, means, targets, evicted_slot, evicted_pos, mas, var)

@@ -17,7 +17,9 @@ from .binding import (  # noqa: F401
     load_library,
     prefill_workspace_bytes,
     roco_decode_step,
+    roco_decode_step_gqa,
     roco_encode_block,
+    roco_encode_block_gqa,
     roco_prefill_compress,
     roco_probe_cache_read,
     roco_profile_kernel,

@@ -75,6 +75,10 @@ def load_library() -> ctypes.CDLL:
     lib.roco_block_workspace_bytes.argtypes = [pp, i32]
     lib.roco_encode_block.restype = ctypes.c_int
     lib.roco_encode_block.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.roco_encode_block_gqa.restype = ctypes.c_int
+    lib.roco_encode_block_gqa.argtypes = [pp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.roco_decode_step_gqa.restype = ctypes.c_int
+    lib.roco_decode_step_gqa.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.roco_select_victims.restype = ctypes.c_int
     lib.roco_select_victims.argtypes = [pp, vp, vp, vp, vp, sz, vp]
     lib.roco_strerror.restype = ctypes.c_char_p
@@ -197,6 +201,34 @@ def roco_encode_block(params: RocoParams, block: int, q, k_new, v_new, qpos0, K_
         _ptr(evicted_pos), _ptr(workspace), int(workspace_bytes), _stream(stream))
     if rc != 0:
         raise RocoError(rc, "roco_encode_block")
+
+
+def roco_encode_block_gqa(params: RocoParams, block: int, group: int, q, k_new, v_new, qpos0, K_cache, V_cache, stats,
+                          pos, n_used, next_slot, out, evicted_slot, evicted_pos, workspace,
+                          workspace_bytes: Optional[int] = None, stream=None) -> None:
+    """See include/roco.h: block-wise step of key/value heads shared by `group` query heads each."""
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    rc = load_library().roco_encode_block_gqa(
+        ctypes.byref(params), int(block), int(group), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(qpos0), _ptr(K_cache),
+        _ptr(V_cache), _ptr(stats), _ptr(pos), _ptr(n_used), _ptr(next_slot), _ptr(out), _ptr(evicted_slot),
+        _ptr(evicted_pos), _ptr(workspace), int(workspace_bytes), _stream(stream))
+    if rc != 0:
+        raise RocoError(rc, "roco_encode_block_gqa")
+
+
+def roco_decode_step_gqa(params: RocoParams, group: int, q, k_new, v_new, qpos, K_cache, V_cache, stats, pos, n_used,
+                         next_slot, out, evicted_slot, evicted_pos, workspace, workspace_bytes: Optional[int] = None,
+                         stream=None) -> None:
+    """See include/roco.h: one decode step of key/value heads shared by `group` query heads each."""
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    rc = load_library().roco_decode_step_gqa(
+        ctypes.byref(params), int(group), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(qpos), _ptr(K_cache),
+        _ptr(V_cache), _ptr(stats), _ptr(pos), _ptr(n_used), _ptr(next_slot), _ptr(out), _ptr(evicted_slot),
+        _ptr(evicted_pos), _ptr(workspace), int(workspace_bytes), _stream(stream))
+    if rc != 0:
+        raise RocoError(rc, "roco_decode_step_gqa")
 
 
 def roco_probe_cache_read(params: RocoParams, K_cache, V_cache, workspace, workspace_bytes: Optional[int] = None,

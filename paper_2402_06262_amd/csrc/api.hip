@@ -196,12 +196,16 @@ size_t roco_block_workspace_bytes(const roco_params* params, int32_t block) {
   return block_layout(params).total;
 }
 
-int roco_encode_block(const roco_params* params, int32_t block, const void* q, const void* k_new, const void* v_new,
-                      const int32_t* qpos0, void* K_cache, void* V_cache, float* stats, int32_t* pos, int32_t* n_used,
-                      int32_t* next_slot, void* out, int32_t* evicted_slot, int32_t* evicted_pos, void* workspace,
-                      size_t workspace_bytes, void* hip_stream) {
-  const int rc = check_block(params, block);
+namespace {
+// Shared by the block-wise step (one query head per unit) and the grouped-query steps (g heads per unit).
+int run_block(const roco_params* params, int tokens, int heads, const void* q, const void* k_new,
+              const void* v_new, const int32_t* qpos0, void* K_cache, void* V_cache, float* stats, int32_t* pos,
+              int32_t* n_used, int32_t* next_slot, void* out, int32_t* evicted_slot, int32_t* evicted_pos,
+              void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (heads < 1) return ROCO_EINVAL;
+  const int rc = check_block(params, tokens);
   if (rc != ROCO_OK) return rc;
+  if (static_cast<long long>(tokens) * heads > kMaxBlock) return ROCO_EUNSUPPORTED;
   const void* need[] = {q, k_new, v_new, qpos0, K_cache, V_cache, stats, pos, n_used, next_slot, out, workspace};
   for (const void* ptr : need)
     if (ptr == nullptr || !aligned16(ptr)) return ROCO_EINVAL;
@@ -209,7 +213,8 @@ int roco_encode_block(const roco_params* params, int32_t block, const void* q, c
   if (workspace_bytes < lay.total) return ROCO_EWORKSPACE;
 
   BlockArgs a;
-  a.units = params->units; a.B = params->budget; a.scope = params->scope; a.block = block;
+  a.units = params->units; a.B = params->budget; a.scope = params->scope;
+  a.block = tokens; a.heads = heads; a.queries = tokens * heads;
   {  // split the budget into 64-slot-aligned ranges, enough workgroups to cover the chip a few times
     int want = env_int("ROCO_BLOCK_SPLITS", 0);
     if (want <= 0) want = (2048 + params->units - 1) / params->units;
@@ -237,6 +242,31 @@ int roco_encode_block(const roco_params* params, int32_t block, const void* q, c
   a.keys = reinterpret_cast<uint32_t*>(ws + lay.keys);
   const hipError_t e = launch_block(a, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
+}
+}  // namespace
+
+int roco_encode_block(const roco_params* params, int32_t block, const void* q, const void* k_new, const void* v_new,
+                      const int32_t* qpos0, void* K_cache, void* V_cache, float* stats, int32_t* pos, int32_t* n_used,
+                      int32_t* next_slot, void* out, int32_t* evicted_slot, int32_t* evicted_pos, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+  return run_block(params, block, 1, q, k_new, v_new, qpos0, K_cache, V_cache, stats, pos, n_used,
+                   next_slot, out, evicted_slot, evicted_pos, workspace, workspace_bytes, hip_stream);
+}
+
+int roco_encode_block_gqa(const roco_params* params, int32_t block, int32_t group, const void* q, const void* k_new,
+                          const void* v_new, const int32_t* qpos0, void* K_cache, void* V_cache, float* stats,
+                          int32_t* pos, int32_t* n_used, int32_t* next_slot, void* out, int32_t* evicted_slot,
+                          int32_t* evicted_pos, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return run_block(params, block, group, q, k_new, v_new, qpos0, K_cache, V_cache, stats, pos, n_used, next_slot, out,
+                   evicted_slot, evicted_pos, workspace, workspace_bytes, hip_stream);
+}
+
+int roco_decode_step_gqa(const roco_params* params, int32_t group, const void* q, const void* k_new,
+                         const void* v_new, const int32_t* qpos, void* K_cache, void* V_cache, float* stats,
+                         int32_t* pos, int32_t* n_used, int32_t* next_slot, void* out, int32_t* evicted_slot,
+                         int32_t* evicted_pos, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return run_block(params, 1, group, q, k_new, v_new, qpos, K_cache, V_cache, stats, pos, n_used, next_slot, out,
+                   evicted_slot, evicted_pos, workspace, workspace_bytes, hip_stream);
 }
 
 int roco_select_victims(const roco_params* params, const float* stats, const int32_t* n_used,

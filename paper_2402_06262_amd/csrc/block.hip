@@ -16,6 +16,10 @@
 //                   accumulates O^T = V^T . P^T with V^T fragments from the LDS transpose read.
 //   block_finish  : one workgroup per unit.  Merges the partials per query, writes the b outputs, adds the
 //                   statistics of all b rows to every slot, chooses the victim a following decode step would take.
+//
+// The same three kernels serve grouped-query attention (section 5.3, "Extension to Grouped-Query Attention"):
+// g query heads share the unit's keys and values, the query rows are (token, head) pairs, and the statistics
+// receive, once per token, the mean of its g heads' probabilities (BlockArgs::heads).
 #include "kernels.hpp"
 #include "mfma.hpp"
 #include "profile.hpp"
@@ -136,7 +140,7 @@ __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
   const int u = blockIdx.y, split = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int half = lane >> 5, qi = lane & 31;  // this lane's query (block token index)
-  const int B = a.B, b = a.block;
+  const int B = a.B, b = a.queries;
   const int n = a.n_used[u];  // already counts the block's tokens
   const int row0 = split * a.rows_per_split;
   const int row1 = min(n, row0 + a.rows_per_split);
@@ -149,7 +153,8 @@ __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
   const float sc = a.scale_log2;
   const int w = a.recency_window;
   const float rb = a.recency_bias_log2;
-  const int qp = a.qpos0[u] + qi;
+  const int ti = qi / a.heads;  // this lane's block token; the heads of a group share its position
+  const int qp = a.qpos0[u] + ti;
 
   // B operand: the block's queries (lanes beyond the block reuse its last query; their results are dropped)
   uint4 own[kKSteps];
@@ -216,7 +221,7 @@ __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
           const int dlt = qp - psv[e];
           if (dlt >= 0 && dlt < w) x += rb;
         }
-        if (slot >= row1 || biv[e] > qi) x = -INFINITY;
+        if (slot >= row1 || biv[e] > ti) x = -INFINITY;
         tv[4 * g4 + e] = x;
         mb = fmaxf(mb, x);
       }
@@ -308,9 +313,11 @@ __global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
   __shared__ unsigned long long best_sh[NT / kWave];
   __shared__ float Mq[kQ], invq[kQ];
   const int u = blockIdx.x, tid = threadIdx.x;
-  const int B = a.B, b = a.block, S = a.splits;
+  const int B = a.B, b = a.queries, S = a.splits;
   const int n = a.n_used[u];
   const bool full = n >= B;
+  const int heads = a.heads;
+  const float inv_heads = 1.0f / static_cast<float>(heads);
   const float* pm = a.part_m + static_cast<size_t>(u) * S * kQ;
   const float* pl = a.part_l + static_cast<size_t>(u) * S * kQ;
   const float* po = a.part_o + static_cast<size_t>(u) * S * kQ * D;
@@ -352,14 +359,21 @@ __global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
     const int4 bi = *reinterpret_cast<const int4*>(bidx + j);
     float s1[4] = {a1.x, a1.y, a1.z, a1.w}, s2[4] = {a2.x, a2.y, a2.z, a2.w}, sc[4] = {cc.x, cc.y, cc.z, cc.w};
     const int biv[4] = {bi.x, bi.y, bi.z, bi.w};
-    for (int q = 0; q < b; ++q) {
-      const float4 zz = *reinterpret_cast<const float4*>(z + static_cast<size_t>(q) * B + j);
-      const float zv[4] = {zz.x, zz.y, zz.z, zz.w};
-      const float M = Mq[q], inv = invq[q];
+    for (int t = 0; t < a.block; ++t) {
+      float mean[4] = {0.0f, 0.0f, 0.0f, 0.0f};  // sum over the token's query heads of p
+      for (int h = 0; h < heads; ++h) {
+        const int q = t * heads + h;
+        const float4 zz = *reinterpret_cast<const float4*>(z + static_cast<size_t>(q) * B + j);
+        const float M = Mq[q], inv = invq[q];
+        mean[0] += fast_exp2(zz.x - M) * inv;
+        mean[1] += fast_exp2(zz.y - M) * inv;
+        mean[2] += fast_exp2(zz.z - M) * inv;
+        mean[3] += fast_exp2(zz.w - M) * inv;
+      }
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        if (j + e < n && biv[e] <= q) {  // older tokens have index -1: attended by every row
-          const float p = fast_exp2(zv[e] - M) * inv;
+        if (j + e < n && biv[e] <= t) {  // older tokens have index -1: attended by every row
+          const float p = mean[e] * inv_heads;  // group-wise averaged probability (exact for one head)
           s1[e] += p;
           s2[e] += p * p;
           sc[e] += 1.0f;

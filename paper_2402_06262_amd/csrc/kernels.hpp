@@ -61,15 +61,17 @@ constexpr int kMaxBlockSplits = 8;   // split-K partials per unit of the block-w
 
 struct BlockArgs {
   int units, B, scope, block, splits, rows_per_split;
+  int heads;    // query heads that share the unit's keys and values (1 without grouped-query attention)
+  int queries;  // query rows per unit = block * heads <= 32; row r belongs to token r / heads, head r % heads
   float scale_log2;
   int recency_window;
   float recency_bias_log2;
-  const void *q, *k_new, *v_new;   // [units][block][128] bf16
+  const void *q, *k_new, *v_new;   // q [units][block][heads][128], k_new / v_new [units][block][128] bf16
   const int32_t* qpos0;            // [units]
   void *K, *V;
   float* stats;
   int32_t *pos, *n_used, *next_slot;
-  void* out;                       // [units][block][128] bf16
+  void* out;                       // [units][block][heads][128] bf16
   int32_t *evicted_slot, *evicted_pos;  // [units][block], may be null
   // workspace
   int32_t* blk_idx;                // [units][B]   block token index held by a slot, -1 for older tokens

@@ -259,3 +259,91 @@ def lockstep_block_unit(state: "orc.CacheState", u: int, g_out, g_slot, g_pos, q
     for i in range(b):
         assert_out_close(g_out[u, i], r.out[i], dtype, f"{what} unit {u} out[{i}]")
     return ties
+
+
+def gpu_decode_step_gqa(sess: GpuSession, group: int, q: np.ndarray, k: np.ndarray, v: np.ndarray,
+                        qpos: Sequence[int], ws: torch.Tensor):
+    """q: [units, group, d], k, v: [units, d] float32 host arrays.  Returns (out, evicted_slot, evicted_pos)."""
+    c, p = sess.cache, sess.params
+    dq, dk, dv = to_dev(q, sess.dtype), to_dev(k, sess.dtype), to_dev(v, sess.dtype)
+    dqpos = torch.tensor(list(qpos), dtype=torch.int32, device="cuda")
+    out = torch.zeros((p.units, group, p.head_dim), dtype=torch_dtype(sess.dtype), device="cuda")
+    es = torch.full((p.units,), -7, dtype=torch.int32, device="cuda")
+    ep = torch.full((p.units,), -7, dtype=torch.int32, device="cuda")
+    roco.roco_decode_step_gqa(p, group, dq, dk, dv, dqpos, c.K, c.V, c.stats, c.pos, c.n_used, c.next_slot, out, es,
+                              ep, ws)
+    torch.cuda.synchronize()
+    return to_host(out), to_host(es), to_host(ep)
+
+
+def lockstep_gqa_unit(state: "orc.CacheState", u: int, g_out, g_slot, g_pos, Qg, k, v, qpos: int, scope: int,
+                      scale: float, dtype: str, recency_window: int = 0, recency_bias: float = 0.0,
+                      what: str = "") -> TieCount:
+    """Advance the oracle state of key/value head `u` by one grouped-query step and compare with the library's."""
+    ties = TieCount()
+    full = state.n_used == state.budget
+    snapshot = state.copy() if full else None
+    r = orc.decode_step_gqa(state, Qg, k, v, qpos, scope, scale, recency_window, recency_bias)
+    if full:
+        ties.decode_decisions += 1
+        if int(g_slot[u]) != r.evicted_slot:
+            eps_m, eps_v = tie_band.bands(snapshot.acc, snapshot.acc2, snapshot.count)
+            ok, why = tie_band.admissible_eviction(r.mas, r.var, eps_m, eps_v, scope, 1, [int(g_slot[u])])
+            assert ok, f"{what} unit {u}: victim slot {int(g_slot[u])} vs oracle {r.evicted_slot} outside the tie band ({why})"
+            ties.decode_ties += 1
+            for name in ("K", "V", "acc", "acc2", "count", "pos"):
+                getattr(state, name)[...] = getattr(snapshot, name)
+            state.n_used = snapshot.n_used
+            r = orc.decode_step_gqa(state, Qg, k, v, qpos, scope, scale, recency_window, recency_bias,
+                                    force_victim=int(g_slot[u]))
+    assert int(g_slot[u]) == r.evicted_slot, f"{what} unit {u}: evicted_slot {int(g_slot[u])} != {r.evicted_slot}"
+    assert int(g_pos[u]) == r.evicted_pos, f"{what} unit {u}: evicted_pos {int(g_pos[u])} != {r.evicted_pos}"
+    for h in range(Qg.shape[0]):
+        assert_out_close(g_out[u, h], r.out[h], dtype, f"{what} unit {u} head {h} out")
+    return ties
+
+
+def gpu_encode_block_gqa(sess: GpuSession, block: int, group: int, q: np.ndarray, k: np.ndarray, v: np.ndarray,
+                         qpos0: Sequence[int], ws: torch.Tensor):
+    """q: [units, block, group, d], k, v: [units, block, d] float32 host arrays."""
+    c, p = sess.cache, sess.params
+    dq, dk, dv = to_dev(q, sess.dtype), to_dev(k, sess.dtype), to_dev(v, sess.dtype)
+    dqpos = torch.tensor(list(qpos0), dtype=torch.int32, device="cuda")
+    out = torch.zeros((p.units, block, group, p.head_dim), dtype=torch_dtype(sess.dtype), device="cuda")
+    es = torch.full((p.units, block), -7, dtype=torch.int32, device="cuda")
+    ep = torch.full((p.units, block), -7, dtype=torch.int32, device="cuda")
+    roco.roco_encode_block_gqa(p, block, group, dq, dk, dv, dqpos, c.K, c.V, c.stats, c.pos, c.n_used, c.next_slot, out,
+                               es, ep, ws)
+    torch.cuda.synchronize()
+    return to_host(out), to_host(es), to_host(ep)
+
+
+def lockstep_block_gqa_unit(state: "orc.CacheState", u: int, g_out, g_slot, g_pos, q, k, v, qpos0: int, scope: int,
+                            scale: float, dtype: str, recency_window: int = 0, recency_bias: float = 0.0,
+                            what: str = "") -> TieCount:
+    """Advance the oracle state of key/value head `u` by one grouped block (q: [b, g, d]) and compare."""
+    ties = TieCount()
+    b, g = q.shape[0], q.shape[1]
+    n = state.n_used
+    E = max(0, n + b - state.budget)
+    snapshot = state.copy()
+    r = orc.encode_block_gqa(state, q, k, v, qpos0, scope, scale, recency_window, recency_bias)
+    g_ev = sorted(int(x) for x in g_slot[u] if x >= 0)
+    if E > 0:
+        ties.decode_decisions += 1
+        if g_ev != sorted(int(x) for x in r.evicted_slot if x >= 0):
+            eps_m, eps_v = tie_band.bands(snapshot.acc[:n], snapshot.acc2[:n], snapshot.count[:n])
+            ok, why = tie_band.admissible_eviction(r.mas, r.var, eps_m, eps_v, scope, E, g_ev)
+            assert ok, f"{what} unit {u}: evicted slots {g_ev} outside the tie band ({why})"
+            ties.decode_ties += 1
+            for name in ("K", "V", "acc", "acc2", "count", "pos"):
+                getattr(state, name)[...] = getattr(snapshot, name)
+            state.n_used = snapshot.n_used
+            r = orc.encode_block_gqa(state, q, k, v, qpos0, scope, scale, recency_window, recency_bias,
+                                     force_evicted=np.array(g_ev, dtype=np.int64))
+    assert np.array_equal(g_slot[u], r.evicted_slot), f"{what} unit {u}: evicted_slot {g_slot[u]} != {r.evicted_slot}"
+    assert np.array_equal(g_pos[u], r.evicted_pos), f"{what} unit {u}: evicted_pos {g_pos[u]} != {r.evicted_pos}"
+    for i in range(b):
+        for h in range(g):
+            assert_out_close(g_out[u, i, h], r.out[i, h], dtype, f"{what} unit {u} token {i} head {h} out")
+    return ties

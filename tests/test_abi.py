@@ -23,7 +23,8 @@ def test_library_loads_and_exports_every_declared_symbol():
     names = declared_functions()
     assert {"roco_prefill_compress", "roco_decode_step", "roco_prefill_workspace_bytes",
             "roco_decode_workspace_bytes", "roco_strerror", "roco_version", "roco_select_victims",
-            "roco_probe_cache_read", "roco_profile_sampling", "roco_encode_block", "roco_block_workspace_bytes"} <= set(names)
+            "roco_probe_cache_read", "roco_profile_sampling", "roco_encode_block", "roco_block_workspace_bytes",
+            "roco_decode_step_gqa", "roco_encode_block_gqa"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in roco.h but not exported"
     assert roco.roco_version() == 1
@@ -100,7 +101,17 @@ def test_encode_block_validates_on_the_host():
     args = [0x1000] * 14
 
     def call(params, block, a=args, ws=need):
-        return lib.roco_encode_block(ctypes.byref(params), block, *a[:14], ws, None)
+        r1 = lib.roco_encode_block(ctypes.byref(params), block, *a[:14], ws, None)
+        r2 = lib.roco_encode_block_gqa(ctypes.byref(params), block, 1, *a[:14], ws, None)  # one head: same checks
+        assert r1 == r2
+        return r1
+
+    def grouped(block, group):
+        return (lib.roco_encode_block_gqa(ctypes.byref(p), block, group, *args, need, None),
+                lib.roco_decode_step_gqa(ctypes.byref(p), group, *args, need, None))
+
+    assert grouped(1, 0) == (EINVAL, EINVAL) and grouped(1, 33) == (EUNS, EUNS)
+    assert grouped(8, 5)[0] == EUNS and grouped(9, 4)[0] == EUNS  # more than 32 query rows
 
     assert call(p, 0) == EINVAL and call(p, 257) == EINVAL
     assert call(p, 33) == EUNS

@@ -488,3 +488,51 @@ def test_group_statistics_receive_the_mean_of_independently_computed_softmaxes()
     assert np.allclose(st.acc[:L + 1], np.append(acc0[:L], 0.0) + mean, rtol=1e-12)
     assert np.allclose(st.acc2[:L + 1], np.append(acc20[:L], 0.0) + mean ** 2, rtol=1e-12)
     assert np.array_equal(st.count[:L + 1], np.append(cnt0[:L], 0.0) + 1.0)  # one count per step, not per head
+
+
+def test_grouped_block_reduces_to_the_block_step_and_to_the_grouped_decode_step():
+    rng = np.random.default_rng(43)
+    L, d, B, s = 30, 4, 12, 3
+    Q, K, V = rand_unit(rng, L + 12, d)
+    a = orc.prefill_compress(Q[:L], K[:L], V[:L], L, B, s, 0.5).cache
+    b_, c, e = a.copy(), a.copy(), a.copy()
+    t = L
+    for blk in (3, 1, 5):  # one head per group: the block-wise step
+        ra = orc.encode_block(a, Q[t:t + blk], K[t:t + blk], V[t:t + blk], t, s, 0.5, 3, 0.25)
+        rb = orc.encode_block_gqa(b_, Q[t:t + blk, None], K[t:t + blk], V[t:t + blk], t, s, 0.5, 3, 0.25)
+        assert np.array_equal(ra.out, rb.out[:, 0]) and np.array_equal(ra.evicted_slot, rb.evicted_slot)
+        for x, y in ((a.acc, b_.acc), (a.acc2, b_.acc2), (a.count, b_.count), (a.pos, b_.pos)):
+            assert np.array_equal(x, y)
+        t += blk
+    for t in range(L, L + 4):  # one token per block: the grouped decode step
+        Qg = rng.standard_normal((3, d))
+        rc = orc.decode_step_gqa(c, Qg, K[t], V[t], t, s, 0.5, 3, 0.25)
+        re = orc.encode_block_gqa(e, Qg[None], K[t:t + 1], V[t:t + 1], t, s, 0.5, 3, 0.25)
+        assert np.array_equal(rc.out, re.out[0]) and rc.evicted_slot == int(re.evicted_slot[0])
+        for x, y in ((c.acc, e.acc), (c.acc2, e.acc2), (c.count, e.count), (c.pos, e.pos)):
+            assert np.array_equal(x, y)
+
+
+def test_grouped_blocks_without_eviction_accumulate_the_head_mean_of_dense_causal_attention():
+    rng = np.random.default_rng(44)
+    L, d, g = 13, 5, 3
+    Qh = rng.standard_normal((g, L, d))
+    _, K, V = rand_unit(rng, L, d)
+    st = orc.CacheState(np.zeros((L, d)), np.zeros((L, d)), np.zeros(L), np.zeros(L), np.zeros(L),
+                        np.full(L, -1, dtype=np.int64), 0)
+    t, outs = 0, []
+    for blk in (4, 1, 6, 2):
+        r = orc.encode_block_gqa(st, Qh[:, t:t + blk].transpose(1, 0, 2), K[t:t + blk], V[t:t + blk], t, 2, 0.4)
+        outs.append(r.out)
+        t += blk
+    Z = 0.4 * np.einsum("hid,jd->hij", Qh, K)  # dense causal softmax per head, written out here
+    Z = np.where(np.tril(np.ones((L, L), dtype=bool))[None], Z, -np.inf)
+    P = np.exp(Z - Z.max(axis=2, keepdims=True))
+    P /= P.sum(axis=2, keepdims=True)
+    mean = P.mean(axis=0)
+    assert np.allclose(st.acc, mean.sum(axis=0), rtol=1e-12)
+    assert np.allclose(st.acc2, (mean ** 2).sum(axis=0), rtol=1e-12)
+    assert np.array_equal(st.count, L - np.arange(L))
+    out = np.concatenate(outs)  # [L, g, d]
+    for h in range(g):
+        assert np.allclose(out[:, h], P[h] @ V, rtol=1e-11, atol=1e-13)

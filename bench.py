@@ -280,6 +280,37 @@ def main():
         base = blockwise["1"]["tokens_per_s"]
         for v in blockwise.values():
             v["speedup_vs_block_1"] = v["tokens_per_s"] / base
+
+        # Grouped-query attention: the same 32 query heads per sequence over 32 / g key/value heads (g = 4 is the
+        # Zephyr-style shape); one token per step.  The start state of each key/value head is a compressed cache.
+        gqa = {}
+        n_g = min(64, n_tok)
+        for g in (1, 4, 8):
+            Ug = U // g
+            pg = roco.RocoParams(Ug, d, B, s, roco.ROCO_BF16)
+            cg = roco.alloc_cache(pg)
+            ws_g = torch.empty(roco.block_workspace_bytes(pg, 1), dtype=torch.uint8, device="cuda")
+            gq = sq[:n_g].reshape(n_g, Ug, g, d).contiguous()
+            gk, gv = sk[:n_g, :Ug].contiguous(), sv[:n_g, :Ug].contiguous()
+            gout = torch.empty((Ug, g, d), dtype=dt, device="cuda")
+            qps = [torch.full((Ug,), L + i, dtype=torch.int32, device="cuda") for i in range(n_g)]
+            times = []
+            for rep in range(2):
+                for t, sn in zip((cg.K, cg.V, cg.stats, cg.pos, cg.n_used, cg.next_slot), snap):
+                    t.copy_(sn[:Ug])
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for i in range(n_g):
+                    roco.roco_decode_step_gqa(pg, g, gq[i], gk[i], gv[i], qps[i], cg.K, cg.V, cg.stats, cg.pos, cg.n_used,
+                                              cg.next_slot, gout, None, None, ws_g, stream=stream)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                times.append(e0.elapsed_time(e1))
+            ms = min(times) / n_g
+            gqa[str(g)] = {"kv_heads_per_layer": 32 // g, "units": Ug, "ms_per_token_step": ms,
+                           "tokens_per_s": cfg.batch / (ms * 1e-3),
+                           "cache_read_GBps": Ug * B * d * 2 * 2 / (ms * 1e-3) / 1e9}
+            del cg, ws_g, gq, gk, gv
         del snap
 
     result = {
@@ -324,6 +355,8 @@ def main():
         result["blockwise_encode"] = {"workload": f"{n_tok} tokens per sequence encoded on the full B={B} cache in "
                                                   "blocks of b (roco_encode_block), batch 16 x 32 heads",
                                       "by_block_size": blockwise}
+        result["gqa_decode"] = {"workload": f"one token per step on the full B={B} cache, 32 query heads over 32/g "
+                                            "key/value heads (roco_decode_step_gqa), batch 16", "by_group_size": gqa}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, Q, K, V, decode_steps, args.cpu_units, args.cpu_steps)
     print(json.dumps(result), flush=True)

@@ -215,9 +215,10 @@ int run_block(const roco_params* params, int tokens, int heads, const void* q, c
   BlockArgs a;
   a.units = params->units; a.B = params->budget; a.scope = params->scope;
   a.block = tokens; a.heads = heads; a.queries = tokens * heads;
-  {  // split the budget into 64-slot-aligned ranges, enough workgroups to cover the chip a few times
+  {  // split the budget into 64-slot-aligned ranges: two resident workgroups per compute unit measured best
+    // (more splits cost more partial results to write and merge than they gain in balance)
     int want = env_int("ROCO_BLOCK_SPLITS", 0);
-    if (want <= 0) want = (2048 + params->units - 1) / params->units;
+    if (want <= 0) want = (512 + params->units - 1) / params->units;
     if (want > kMaxBlockSplits) want = kMaxBlockSplits;
     const int max_by_rows = (params->budget + 63) / 64;
     if (want > max_by_rows) want = max_by_rows;

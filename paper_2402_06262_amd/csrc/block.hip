@@ -14,8 +14,9 @@
 //                   slots against the block's (up to 32) queries on the matrix cores (score tile = K . Q^T, the
 //                   query in the lane), stores the base-2 logits, keeps an online softmax per query and
 //                   accumulates O^T = V^T . P^T with V^T fragments from the LDS transpose read.
-//   block_finish  : one workgroup per unit.  Merges the partials per query, writes the b outputs, adds the
-//                   statistics of all b rows to every slot, chooses the victim a following decode step would take.
+//   block_finish  : grid (slot chunks, units).  Merges the partials per query, writes the outputs, adds the
+//                   statistics of all rows to every slot.  The select_victims kernel of the decode path then
+//                   chooses the victim a following decode step would take.
 //
 // The same three kernels serve grouped-query attention (section 5.3, "Extension to Grouped-Query Attention"):
 // g query heads share the unit's keys and values, the query rows are (token, head) pairs, and the statistics
@@ -30,9 +31,10 @@ namespace {
 
 using namespace mfma;
 
-constexpr int kPrepThreads = 256;
+constexpr int kPrepThreads = 1024;
 constexpr int kAttThreads = 128;  // two waves: one 32-slot half of a 64-slot tile each
 constexpr int kFinThreads = 256;
+constexpr int kFinSlots = 2 * kFinThreads;  // slots per block_finish workgroup
 constexpr int kQ = 32;            // queries per matrix tile; a block holds at most this many tokens
 
 // ------------------------------------------------------------------------------------------------
@@ -57,7 +59,9 @@ __global__ __launch_bounds__(kPrepThreads) void block_prepare(BlockArgs a) {
 
   if (tid < kQ) slot_of[tid] = 0;
   KSmallest scope = {0u, 0u}, out = {0u, 0u};
-  if (E > 0) {
+  // one eviction from a full cache: the victim was already chosen when the statistics were last updated
+  const int hint = (E == 1 && n == B) ? a.next_slot[u] : -1;
+  if (E > 0 && hint < 0) {
     for (int i = tid; i < n; i += NT) ranking_keys(acc[i], acc2[i], cnt[i], mas_key[i], var_key[i]);
     __syncthreads();
     const uint32_t m = min(static_cast<uint32_t>(n), static_cast<uint32_t>(a.scope) + static_cast<uint32_t>(E) - 1u);
@@ -69,6 +73,7 @@ __global__ __launch_bounds__(kPrepThreads) void block_prepare(BlockArgs a) {
   auto is_target = [&](int j) -> bool {
     if (j >= n) return j < n_new;  // still-empty slot taken by the block
     if (E == 0) return false;
+    if (hint >= 0) return j == hint;
     const uint32_t k2 = scope.has(var_key[j], j) ? mas_key[j] : 0xffffffffu;
     return out.has(k2, j);
   };
@@ -172,10 +177,17 @@ __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
   const int n_tiles = row1 > row0 ? (row1 - row0 + kTile - 1) / kTile : 0;
   StagedKV st;
   int32_t st_bidx = -1, st_pos = 0;
+  // Tiles are visited from a start that differs between workgroups, so that workgroups running side by side do
+  // not walk the memory channels in lock step (the online softmax does not care about the order).
+  const int rot = n_tiles > 0 ? static_cast<int>((static_cast<unsigned>(u) * 5u + static_cast<unsigned>(split) * 3u) %
+                                                 static_cast<unsigned>(n_tiles))
+                              : 0;
+  auto tile_row = [&](int t) { return row0 + (t + rot < n_tiles ? t + rot : t + rot - n_tiles) * kTile; };
   auto fetch = [&](int t) {
-    kv_load(st, Kb, Vb, row0 + t * kTile, n - 1);
+    const int tr0 = tile_row(t);
+    kv_load(st, Kb, Vb, tr0, n - 1);
     if (tid < kTile) {
-      const int slot = min(row0 + t * kTile + tid, n - 1);
+      const int slot = min(tr0 + tid, n - 1);
       st_bidx = bidx[slot];
       st_pos = pos[slot];
     }
@@ -188,8 +200,9 @@ __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
     if (tid < kTile) { bidx_s[t & 1][tid] = st_bidx; pos_s[t & 1][tid] = st_pos; }
     __syncthreads();
     if (t + 1 < n_tiles) fetch(t + 1);
-    const int sb = row0 + t * kTile + 32 * wave;  // first slot of this wave's half-tile
-    if (sb >= row1) continue;                      // wave-uniform; no barrier below in this iteration
+    const int tr0 = tile_row(t);
+    const int sb = tr0 + 32 * wave;  // first slot of this wave's half-tile
+    if (sb < row1) {                               // wave-uniform
     // ---- scores of 32 slots x 32 queries
     f32x16 sacc;
     {
@@ -215,7 +228,7 @@ __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
       const int psv[4] = {ps.x, ps.y, ps.z, ps.w};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const int slot = row0 + t * kTile + base + e;
+        const int slot = tr0 + base + e;
         float x = sacc[4 * g4 + e] * sc;
         if (w > 0) {
           const int dlt = qp - psv[e];
@@ -225,7 +238,7 @@ __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
         tv[4 * g4 + e] = x;
         mb = fmaxf(mb, x);
       }
-      const int slot0 = row0 + t * kTile + base;
+      const int slot0 = tr0 + base;
       if (qi < b && slot0 < row1) {  // logits of real queries and real slots are kept for the statistics
         *reinterpret_cast<float4*>(z + static_cast<size_t>(qi) * B + slot0) =
             make_float4(tv[4 * g4], tv[4 * g4 + 1], tv[4 * g4 + 2], tv[4 * g4 + 3]);
@@ -263,6 +276,7 @@ __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
         const uint4 afrag = make_uint4(lo.x, lo.y, hi.x, hi.y);
         o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, afrag), pfrag[ks], o[db], 0, 0, 0);
       }
+    }
     }
   }
   l += __shfl_xor(l, 32, kWave);  // the lane halves summed different slots of the same query
@@ -306,16 +320,15 @@ __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// Grid (chunks, units): workgroup (c, u) owns slots [c * kFinSlots, (c + 1) * kFinSlots) of unit u and the query
+// rows r = c, c + chunks, ...  The victim for a following single-token step is chosen afterwards by the
+// select_victims kernel, from the statistics written here.
 __global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
   constexpr int NT = kFinThreads;
-  extern __shared__ uint32_t lds_keys[];  // [2][B] when B <= kMaxDecodeBudgetLds
-  __shared__ uint32_t sel_sh[kSelectLdsWords];
-  __shared__ unsigned long long best_sh[NT / kWave];
   __shared__ float Mq[kQ], invq[kQ];
-  const int u = blockIdx.x, tid = threadIdx.x;
-  const int B = a.B, b = a.queries, S = a.splits;
+  const int u = blockIdx.y, chunk = blockIdx.x, chunks = gridDim.x, tid = threadIdx.x;
+  const int B = a.B, nq = a.queries, S = a.splits;
   const int n = a.n_used[u];
-  const bool full = n >= B;
   const int heads = a.heads;
   const float inv_heads = 1.0f / static_cast<float>(heads);
   const float* pm = a.part_m + static_cast<size_t>(u) * S * kQ;
@@ -334,86 +347,52 @@ __global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
     invq[tid] = 1.0f / L;
   }
   __syncthreads();
-  // outputs: b rows of D values
-  for (int idx = tid; idx < b * D; idx += NT) {
-    const int q = idx / D, dd = idx % D;
+  // outputs of this workgroup's query rows
+  const int my_rows = nq > chunk ? (nq - chunk + chunks - 1) / chunks : 0;
+  for (int idx = tid; idx < my_rows * D; idx += NT) {
+    const int q = chunk + (idx / D) * chunks, dd = idx % D;
     float o = 0.0f;
     for (int s = 0; s < S; ++s) {
       const float ms = pm[s * kQ + q];
       o += (ms > -INFINITY) ? po[(static_cast<size_t>(s) * kQ + q) * D + dd] * fast_exp2(ms - Mq[q]) : 0.0f;
     }
-    store_elem<kBF16>(a.out, (static_cast<size_t>(u) * b + q) * D + dd, o * invq[q]);
+    store_elem<kBF16>(a.out, (static_cast<size_t>(u) * nq + q) * D + dd, o * invq[q]);
   }
-  // statistics: every slot receives the probabilities of the rows that attended it
+  // statistics: every slot receives, per block token that attended it, the head-mean of the probabilities
+  const int j = chunk * kFinSlots + tid * 2;  // B is a multiple of 4 on this path, so the pair is inside [0, B)
+  if (j >= n) return;
   float* acc = a.stats + static_cast<size_t>(u) * 3 * B;
   float* acc2 = acc + B;
   float* cnt = acc2 + B;
   const float* z = a.z + static_cast<size_t>(u) * kQ * B;
-  const int32_t* bidx = a.blk_idx + static_cast<size_t>(u) * B;
-  uint32_t* var_key = (B <= kMaxDecodeBudgetLds) ? lds_keys : a.keys + static_cast<size_t>(u) * 2 * B;
-  uint32_t* mas_key = var_key + B;
-  for (int j = tid * 4; j < n; j += NT * 4) {  // B is a multiple of 4 on this path
-    const float4 a1 = *reinterpret_cast<const float4*>(acc + j);
-    const float4 a2 = *reinterpret_cast<const float4*>(acc2 + j);
-    const float4 cc = *reinterpret_cast<const float4*>(cnt + j);
-    const int4 bi = *reinterpret_cast<const int4*>(bidx + j);
-    float s1[4] = {a1.x, a1.y, a1.z, a1.w}, s2[4] = {a2.x, a2.y, a2.z, a2.w}, sc[4] = {cc.x, cc.y, cc.z, cc.w};
-    const int biv[4] = {bi.x, bi.y, bi.z, bi.w};
-    for (int t = 0; t < a.block; ++t) {
-      float mean[4] = {0.0f, 0.0f, 0.0f, 0.0f};  // sum over the token's query heads of p
-      for (int h = 0; h < heads; ++h) {
-        const int q = t * heads + h;
-        const float4 zz = *reinterpret_cast<const float4*>(z + static_cast<size_t>(q) * B + j);
-        const float M = Mq[q], inv = invq[q];
-        mean[0] += fast_exp2(zz.x - M) * inv;
-        mean[1] += fast_exp2(zz.y - M) * inv;
-        mean[2] += fast_exp2(zz.z - M) * inv;
-        mean[3] += fast_exp2(zz.w - M) * inv;
-      }
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        if (j + e < n && biv[e] <= t) {  // older tokens have index -1: attended by every row
-          const float p = mean[e] * inv_heads;  // group-wise averaged probability (exact for one head)
-          s1[e] += p;
-          s2[e] += p * p;
-          sc[e] += 1.0f;
-        }
-      }
+  const int2 bi = *reinterpret_cast<const int2*>(a.blk_idx + static_cast<size_t>(u) * B + j);
+  const float2 a1 = *reinterpret_cast<const float2*>(acc + j);
+  const float2 a2 = *reinterpret_cast<const float2*>(acc2 + j);
+  const float2 cc = *reinterpret_cast<const float2*>(cnt + j);
+  float s1[2] = {a1.x, a1.y}, s2[2] = {a2.x, a2.y}, sc[2] = {cc.x, cc.y};
+  const int biv[2] = {bi.x, bi.y};
+  for (int t = 0; t < a.block; ++t) {
+    float mean[2] = {0.0f, 0.0f};  // sum over the token's query heads of p
+    for (int h = 0; h < heads; ++h) {
+      const int q = t * heads + h;
+      const float2 zz = *reinterpret_cast<const float2*>(z + static_cast<size_t>(q) * B + j);
+      const float M = Mq[q], inv = invq[q];
+      mean[0] += fast_exp2(zz.x - M) * inv;
+      mean[1] += fast_exp2(zz.y - M) * inv;
     }
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if (full && j + e < n) ranking_keys(s1[e], s2[e], sc[e], mas_key[j + e], var_key[j + e]);
-    *reinterpret_cast<float4*>(acc + j) = make_float4(s1[0], s1[1], s1[2], s1[3]);
-    *reinterpret_cast<float4*>(acc2 + j) = make_float4(s2[0], s2[1], s2[2], s2[3]);
-    *reinterpret_cast<float4*>(cnt + j) = make_float4(sc[0], sc[1], sc[2], sc[3]);
+    for (int e = 0; e < 2; ++e) {
+      if (j + e < n && biv[e] <= t) {  // older tokens have index -1: attended by every row
+        const float p = mean[e] * inv_heads;  // group-wise averaged probability (exact for one head)
+        s1[e] += p;
+        s2[e] += p * p;
+        sc[e] += 1.0f;
+      }
+    }
   }
-  if (full) {  // the victim a following single-token decode step would take
-    __syncthreads();
-    const KSmallest sc = select_k_smallest<NT>([&](int i) { return var_key[i]; }, B,
-                                               static_cast<uint32_t>(a.scope), sel_sh);
-    unsigned long long best = ~0ull;
-    for (int i = tid; i < B; i += NT) {
-      if (sc.has(var_key[i], i)) {
-        const unsigned long long cand = (static_cast<unsigned long long>(mas_key[i]) << 32) | static_cast<uint32_t>(i);
-        best = cand < best ? cand : best;
-      }
-    }
-#pragma unroll
-    for (int msk = 1; msk < kWave; msk <<= 1) {
-      const unsigned long long o2 = __shfl_xor(best, msk, kWave);
-      best = o2 < best ? o2 : best;
-    }
-    __syncthreads();
-    if ((tid & (kWave - 1)) == 0) best_sh[tid / kWave] = best;
-    __syncthreads();
-    if (tid == 0) {
-      unsigned long long bb = best_sh[0];
-      for (int wv = 1; wv < NT / kWave; ++wv) bb = best_sh[wv] < bb ? best_sh[wv] : bb;
-      a.next_slot[u] = static_cast<int>(bb & 0xffffffffu);
-    }
-  } else if (tid == 0) {
-    a.next_slot[u] = -1;
-  }
+  *reinterpret_cast<float2*>(acc + j) = make_float2(s1[0], s1[1]);
+  *reinterpret_cast<float2*>(acc2 + j) = make_float2(s2[0], s2[1]);
+  *reinterpret_cast<float2*>(cnt + j) = make_float2(sc[0], sc[1]);
 }
 
 }  // namespace
@@ -438,9 +417,13 @@ hipError_t launch_block(const BlockArgs& a, hipStream_t s) {
   }
   {
     ProfScope ps(kProfBlockFinish, s);
-    hipLaunchKernelGGL(block_finish, dim3(a.units), dim3(kFinThreads), key_lds, s, a);
+    hipLaunchKernelGGL(block_finish, dim3((a.B + kFinSlots - 1) / kFinSlots, a.units), dim3(kFinThreads), 0, s, a);
   }
-  return hipGetLastError();
+  if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+  DecodeArgs sel = {};  // the victim a following single-token decode step would take
+  sel.units = a.units; sel.B = a.B; sel.scope = a.scope;
+  sel.stats = a.stats; sel.n_used = a.n_used; sel.next_slot = a.next_slot; sel.keys = a.keys;
+  return launch_select_victims(sel, s);
 }
 
 }  // namespace roco

@@ -31,6 +31,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix peak
 # HBM-side bytes of one decode_attend launch on this workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a
 # plain copy of known size (profiles/decode_prefill_workload3_rocprofv3.txt); only valid for the default shape.
 ATTEND_TRAFFIC_BYTES = 543662034
+FUSED_TRAFFIC_BYTES = None  # decode_fused (the default shape of the step on this workload): see the same file
 
 
 def generate(cfg, seed, workers):
@@ -211,10 +212,13 @@ def main():
     assert int(cache.n_used.min()) == B and int(cache.n_used.max()) == B
     assert int((ev_slot >= 0).sum()) == decode_steps * U
 
-    # dominant kernel: decode_attend reads every cached K and V element once
-    attend_bytes = U * B * 2 * d * esz
-    attend_avg_s = attend_ms * 1e-3 / max(1, attend_n)
+    # dominant kernel.  Split path: decode_attend reads every cached K and V element once.  Fused path (one
+    # workgroup per unit): decode_fused is the whole step: K and V once, the three statistics read and written.
+    fused = roco.decode_step_launches(p) == 1
     step_bytes = U * B * (2 * d * esz + 24)
+    attend_bytes = step_bytes if fused else U * B * 2 * d * esz
+    attend_name = "decode_fused" if fused else "decode_attend"
+    attend_avg_s = attend_ms * 1e-3 / max(1, attend_n)
     # prefill statistics: two causal QK^T passes (row normalisers, then column statistics), 2 flops per MAC
     prefill_flops = U * 2 * d * L * (L + 1) * (1.5 if args.with_out else 1.0)
 
@@ -227,7 +231,7 @@ def main():
         ms, n = roco.roco_profile_read()
         pre_kernel_ms[name] = ms / max(1, n)
     dec_kernel_ms = {}
-    for name in ("decode_finish",):
+    for name in (() if fused else ("decode_finish",)):
         roco.roco_profile_kernel(roco.PROF_KERNELS[name])
         for t in range(min(32, decode_steps)):
             decode_one(t)
@@ -243,7 +247,7 @@ def main():
     ms, n = roco.roco_profile_read()
     probe_alone_s = ms * 1e-3 / max(1, n)
     roco.roco_profile_kernel(-1)
-    dec_kernel_ms["decode_attend"] = attend_avg_s * 1e3
+    dec_kernel_ms[attend_name] = attend_avg_s * 1e3
     dec_kernel_ms["read_probe"] = probe_alone_s * 1e3
 
     # Block-wise evict-and-encode (the paper's Table 6: speed-up of prompt encoding over token-wise eviction grows
@@ -333,13 +337,13 @@ def main():
         "decode_ms_per_token_step": decode_ms / (decode_steps * args.steps),
         "prefill_evict_tokens_per_s": prefill_tok_s,
         "prefill_ms": prefill_ms / args.steps,
-        "roofline": {"kernel": "decode_attend", "bound": "hbm", "achieved": attend_bytes / attend_avg_s / 1e9,
+        "roofline": {"kernel": attend_name, "bound": "hbm", "achieved": attend_bytes / attend_avg_s / 1e9,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": attend_bytes / attend_avg_s / 1e9 / HBM_PEAK_GBS,
-                     "traffic": ATTEND_TRAFFIC_BYTES if decode_steps > 0 and U == 512 else None,
+                     "traffic": (FUSED_TRAFFIC_BYTES if fused else ATTEND_TRAFFIC_BYTES) if U == 512 else None,
                      "bytes_per_launch": attend_bytes, "avg_launch_ms": attend_avg_s * 1e3, "launches": attend_n,
-                     "measured_read_ceiling_GBps": attend_bytes / probe_alone_s / 1e9,
-                     "frac_of_measured_ceiling": probe_alone_s / attend_avg_s},
+                     "measured_read_ceiling_GBps": U * B * 2 * d * esz / probe_alone_s / 1e9,
+                     "frac_of_measured_ceiling": attend_bytes / attend_avg_s / (U * B * 2 * d * esz / probe_alone_s)},
         "roofline_decode_step": {"bound": "hbm", "achieved": step_bytes / (decode_ms * 1e-3 / (decode_steps * args.steps)) / 1e9,
                                  "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                  "frac": step_bytes / (decode_ms * 1e-3 / (decode_steps * args.steps)) / 1e9 / HBM_PEAK_GBS,

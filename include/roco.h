@@ -69,6 +69,12 @@ typedef struct roco_params {
 size_t roco_prefill_workspace_bytes(const roco_params* params, int32_t L_max);
 size_t roco_decode_workspace_bytes(const roco_params* params);
 
+/* Kernels one roco_decode_step call launches for these params (for benchmarks that attribute time and bytes):
+ * 1 = one workgroup per unit does the whole step (enough units to fill the chip, budget small enough for its
+ * logits and ranking keys to sit in LDS); 2 = slot ranges of a unit on several workgroups, then a merge /
+ * statistics / selection kernel.  Negative code on invalid params. */
+int roco_decode_step_launches(const roco_params* params);
+
 /*
  * Prefill with eviction in one block (section 5.3 "Overhead": block-wise evict-and-encode with the
  * whole prompt as the block; section 5.1.5: B = prompt length x compression rate).

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     RocoParams,
     alloc_cache,
     block_workspace_bytes,
+    decode_step_launches,
     decode_workspace_bytes,
     library_path,
     load_library,

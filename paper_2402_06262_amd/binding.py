@@ -65,6 +65,8 @@ def load_library() -> ctypes.CDLL:
     lib.roco_prefill_workspace_bytes.argtypes = [pp, i32]
     lib.roco_decode_workspace_bytes.restype = sz
     lib.roco_decode_workspace_bytes.argtypes = [pp]
+    lib.roco_decode_step_launches.restype = ctypes.c_int
+    lib.roco_decode_step_launches.argtypes = [pp]
     lib.roco_prefill_compress.restype = ctypes.c_int
     lib.roco_prefill_compress.argtypes = [pp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.roco_decode_step.restype = ctypes.c_int
@@ -183,6 +185,14 @@ def roco_decode_step(params: RocoParams, q, k_new, v_new, qpos, K_cache, V_cache
         _ptr(workspace), int(workspace_bytes), _stream(stream))
     if rc != 0:
         raise RocoError(rc, "roco_decode_step")
+
+
+def decode_step_launches(params: RocoParams) -> int:
+    """1 if a decode step of these params is one fused kernel, 2 if it is the split pair (see include/roco.h)."""
+    rc = int(load_library().roco_decode_step_launches(ctypes.byref(params)))
+    if rc < 0:
+        raise RocoError(rc, "roco_decode_step_launches")
+    return rc
 
 
 def block_workspace_bytes(params: RocoParams, block: int) -> int:

@@ -102,6 +102,13 @@ void choose_splits(const roco_params* p, int unroll, int& splits, int& rows_per_
   rows_per_split = rows;
 }
 
+// One workgroup per unit once there are enough units to keep the chip streaming (measured on B = 2048, bf16,
+// d = 128: ahead of the split path from 64 units on, behind it at 32 and 40).
+bool decode_is_fused(const roco_params* p) {
+  const int want = env_int("ROCO_DECODE_FUSED", -1);
+  return (want < 0 ? p->units >= 64 : want != 0) && p->budget <= kMaxDecodeBudgetLds;
+}
+
 }  // namespace
 
 extern "C" {
@@ -114,6 +121,12 @@ size_t roco_prefill_workspace_bytes(const roco_params* params, int32_t L_max) {
 size_t roco_decode_workspace_bytes(const roco_params* params) {
   if (check_params(params) != ROCO_OK) return 0;
   return decode_layout(params).total;
+}
+
+int roco_decode_step_launches(const roco_params* params) {
+  const int rc = check_params(params);
+  if (rc != ROCO_OK) return rc;
+  return decode_is_fused(params) ? 1 : 2;
 }
 
 int roco_prefill_compress(const roco_params* params, const void* Q, const void* K, const void* V,
@@ -175,6 +188,7 @@ int roco_decode_step(const roco_params* params, const void* q, const void* k_new
   if (a.unroll != 2 && a.unroll != 4) a.unroll = 8;
   a.rotate = env_int("ROCO_DECODE_ROTATE", 1);
   choose_splits(params, a.unroll, a.splits, a.rows_per_split);
+  a.fused = decode_is_fused(params) ? 1 : 0;
   a.scale_log2 = scale_log2(params);
   a.recency_window = params->recency_window;
   a.recency_bias_log2 = params->recency_bias * 1.4426950408889634f;

@@ -27,6 +27,7 @@ namespace {
 constexpr int kAttendThreads = 256;
 constexpr int kAttendWaves = kAttendThreads / kWave;
 constexpr int kFinishThreads = kDecodeSelectThreads;
+constexpr int kFusedThreads = 256;  // with 8 rows in flight per lane group: two workgroups per compute unit
 
 // Scope = `scope` lowest variance keys among [0, B); returns the slot of lowest MAS key inside it (lowest
 // slot on equal keys).  Every thread of the block calls it and gets the same answer.
@@ -146,6 +147,90 @@ __global__ __launch_bounds__(kAttendThreads) void decode_attend(DecodeArgs a) {
   }
 }
 
+// Adds this step's probabilities p_j = 2^(z_j - M) / L to the three statistics of slots [0, n) (the slot that
+// just received the new token starts from zero) and, when the unit is full, writes the ranking keys of the
+// updated statistics.  z may live in global memory or in LDS.
+// The update of four adjacent slots j .. j + 3 whose statistics are already in registers.
+__device__ __forceinline__ void update_four(float4& a1, float4& a2, float4& cc, const float4 zz, int j, int n, int slot,
+                                            float M, float inv, bool full, uint32_t* mas_key, uint32_t* var_key) {
+  const float zv[4] = {zz.x, zz.y, zz.z, zz.w};
+  float s1[4] = {a1.x, a1.y, a1.z, a1.w}, s2[4] = {a2.x, a2.y, a2.z, a2.w}, sc[4] = {cc.x, cc.y, cc.z, cc.w};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int jj = j + e;
+    if (jj < n) {
+      if (jj == slot) { s1[e] = 0.0f; s2[e] = 0.0f; sc[e] = 0.0f; }
+      const float p = fast_exp2(zv[e] - M) * inv;
+      s1[e] += p;
+      s2[e] += p * p;
+      sc[e] += 1.0f;
+      if (full) ranking_keys(s1[e], s2[e], sc[e], mas_key[jj], var_key[jj]);
+    }
+  }
+  a1 = make_float4(s1[0], s1[1], s1[2], s1[3]);
+  a2 = make_float4(s2[0], s2[1], s2[2], s2[3]);
+  cc = make_float4(sc[0], sc[1], sc[2], sc[3]);
+}
+
+// Statistics of the first PF groups of four slots of this thread, loaded ahead of their use: issued before the
+// K / V stream, they arrive while it runs, so that the update after the stream does not wait on memory.
+template <int NT, int PF> struct StatsAhead {
+  float4 a1[PF], a2[PF], cc[PF];
+  __device__ __forceinline__ void load(const float* acc, const float* acc2, const float* cnt, int n) {
+#pragma unroll
+    for (int k = 0; k < PF; ++k) {
+      const int j = (k * NT + static_cast<int>(threadIdx.x)) * 4;
+      const int jc = j < n ? j : 0;  // a group past the end is never used; keep its address inside the planes
+      a1[k] = *reinterpret_cast<const float4*>(acc + jc);
+      a2[k] = *reinterpret_cast<const float4*>(acc2 + jc);
+      cc[k] = *reinterpret_cast<const float4*>(cnt + jc);
+    }
+  }
+};
+
+template <int NT, int PF>
+__device__ __forceinline__ void update_statistics(float* acc, float* acc2, float* cnt, const float* z, int n, int B,
+                                                  int slot, float M, float inv, bool full, uint32_t* mas_key,
+                                                  uint32_t* var_key, StatsAhead<NT, PF>* ahead) {
+  const int tid = threadIdx.x;
+  if ((B & 3) == 0) {
+    // four adjacent slots per thread, 128-bit accesses on every plane
+    if (ahead != nullptr) {
+#pragma unroll
+      for (int k = 0; k < PF; ++k) {
+        const int j = (k * NT + tid) * 4;
+        if (j < n) {
+          update_four(ahead->a1[k], ahead->a2[k], ahead->cc[k], *reinterpret_cast<const float4*>(z + j), j, n, slot, M,
+                      inv, full, mas_key, var_key);
+          store_streaming(acc + j, ahead->a1[k]);
+          store_streaming(acc2 + j, ahead->a2[k]);
+          store_streaming(cnt + j, ahead->cc[k]);
+        }
+      }
+    }
+    for (int j = ((ahead != nullptr ? PF * NT : 0) + tid) * 4; j < n; j += NT * 4) {
+      float4 a1 = *reinterpret_cast<const float4*>(acc + j);
+      float4 a2 = *reinterpret_cast<const float4*>(acc2 + j);
+      float4 cc = *reinterpret_cast<const float4*>(cnt + j);
+      update_four(a1, a2, cc, *reinterpret_cast<const float4*>(z + j), j, n, slot, M, inv, full, mas_key, var_key);
+      *reinterpret_cast<float4*>(acc + j) = a1;
+      *reinterpret_cast<float4*>(acc2 + j) = a2;
+      *reinterpret_cast<float4*>(cnt + j) = cc;
+    }
+  } else {
+    for (int j = tid; j < n; j += NT) {
+      float s1 = acc[j], s2 = acc2[j], sc = cnt[j];
+      if (j == slot) { s1 = 0.0f; s2 = 0.0f; sc = 0.0f; }
+      const float p = fast_exp2(z[j] - M) * inv;
+      s1 += p;
+      s2 += p * p;
+      sc += 1.0f;
+      acc[j] = s1; acc2[j] = s2; cnt[j] = sc;
+      if (full) ranking_keys(s1, s2, sc, mas_key[j], var_key[j]);
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------------
 template <int DT, int D>
 __global__ __launch_bounds__(kFinishThreads) void decode_finish(DecodeArgs a) {
@@ -186,43 +271,8 @@ __global__ __launch_bounds__(kFinishThreads) void decode_finish(DecodeArgs a) {
   uint32_t* var_key = (B <= kMaxDecodeBudgetLds) ? lds_keys : a.keys + static_cast<size_t>(u) * 2 * B;
   uint32_t* mas_key = var_key + B;
 
-  if ((B & 3) == 0) {
-    // four adjacent slots per thread, 128-bit accesses on every plane
-    for (int j = tid * 4; j < n; j += NT * 4) {
-      const float4 zz = *reinterpret_cast<const float4*>(z + j);
-      float4 a1 = *reinterpret_cast<const float4*>(acc + j);
-      float4 a2 = *reinterpret_cast<const float4*>(acc2 + j);
-      float4 cc = *reinterpret_cast<const float4*>(cnt + j);
-      const float zv[4] = {zz.x, zz.y, zz.z, zz.w};
-      float s1[4] = {a1.x, a1.y, a1.z, a1.w}, s2[4] = {a2.x, a2.y, a2.z, a2.w}, sc[4] = {cc.x, cc.y, cc.z, cc.w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int jj = j + e;
-        if (jj < n) {
-          if (jj == slot) { s1[e] = 0.0f; s2[e] = 0.0f; sc[e] = 0.0f; }
-          const float p = fast_exp2(zv[e] - M) * inv;
-          s1[e] += p;
-          s2[e] += p * p;
-          sc[e] += 1.0f;
-          if (full) ranking_keys(s1[e], s2[e], sc[e], mas_key[jj], var_key[jj]);
-        }
-      }
-      *reinterpret_cast<float4*>(acc + j) = make_float4(s1[0], s1[1], s1[2], s1[3]);
-      *reinterpret_cast<float4*>(acc2 + j) = make_float4(s2[0], s2[1], s2[2], s2[3]);
-      *reinterpret_cast<float4*>(cnt + j) = make_float4(sc[0], sc[1], sc[2], sc[3]);
-    }
-  } else {
-    for (int j = tid; j < n; j += NT) {
-      float s1 = acc[j], s2 = acc2[j], sc = cnt[j];
-      if (j == slot) { s1 = 0.0f; s2 = 0.0f; sc = 0.0f; }
-      const float p = fast_exp2(z[j] - M) * inv;
-      s1 += p;
-      s2 += p * p;
-      sc += 1.0f;
-      acc[j] = s1; acc2[j] = s2; cnt[j] = sc;
-      if (full) ranking_keys(s1, s2, sc, mas_key[j], var_key[j]);
-    }
-  }
+  // Bookkeeping first: the load counter is in order, so a load issued after the statistics stores could only be
+  // waited for together with them, and every wave would sit at the barrier below for the stores' round trip.
   if (tid == 0) {
     const int old_pos = pos[slot];
     pos[slot] = a.qpos[u];
@@ -230,6 +280,119 @@ __global__ __launch_bounds__(kFinishThreads) void decode_finish(DecodeArgs a) {
     if (a.evicted_slot) a.evicted_slot[u] = was_full ? slot : -1;
     if (a.evicted_pos) a.evicted_pos[u] = was_full ? old_pos : -1;
   }
+  update_statistics<NT, 1>(acc, acc2, cnt, z, n, B, slot, M, inv, full, mas_key, var_key, nullptr);
+  if (full) {
+    __syncthreads();
+    const int victim = select_victim_block<NT>(var_key, mas_key, B, a.scope, sel_sh, best_sh);
+    if (tid == 0) a.next_slot[u] = victim;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// The whole step of a unit in one workgroup: stream the unit's K and V once (the new token's rows go into their
+// slot on the way), merge the waves' online-softmax states through LDS, write the output, update the
+// statistics from the logits kept in LDS and choose the next victim.  Nothing but the final results is written
+// to global memory and no second launch is needed; the price is that a workgroup's selection phase does not
+// stream, so this shape is used when there are at least about two units per compute unit to overlap with.
+template <int DT, int D, int U>
+__global__ __launch_bounds__(kFusedThreads) void decode_fused(DecodeArgs a) {
+  using G = RowGeom<DT, D>;
+  constexpr int NT = kFusedThreads, WAVES = NT / kWave;
+  constexpr int PASS = WAVES * U * G::R;
+  extern __shared__ __attribute__((aligned(16))) uint32_t lds_dyn[];  // [2][B] ranking keys, then [B] base-2 logits
+  __shared__ uint32_t sel_sh[kSelectLdsWords];
+  __shared__ unsigned long long best_sh[WAVES];
+  __shared__ float sm_m[WAVES], sm_l[WAVES];
+  __shared__ float sm_acc[WAVES][D];
+
+  const int u = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int c = lane % G::LPR;
+  const int B = a.B;
+  const int n0 = a.n_used[u];
+  const bool was_full = n0 >= B;
+  const int slot = was_full ? min(max(a.next_slot[u], 0), B - 1) : n0;  // where the new token goes
+  const int n = was_full ? B : n0 + 1;
+  const bool full = n >= B;
+  uint32_t* var_key = lds_dyn;
+  uint32_t* mas_key = var_key + B;
+  float* z = reinterpret_cast<float*>(lds_dyn + 2 * static_cast<size_t>(B));
+
+  const size_t in_off = static_cast<size_t>(u) * G::ROW_BYTES + c * 16;
+  float qf[G::EPL];
+  unpack16<DT>(load16(static_cast<const char*>(a.q) + in_off), qf);
+#pragma unroll
+  for (int e = 0; e < G::EPL; ++e) qf[e] *= a.scale_log2;
+
+  char* Kb = static_cast<char*>(a.K) + static_cast<size_t>(u) * B * G::ROW_BYTES;
+  char* Vb = static_cast<char*>(a.V) + static_cast<size_t>(u) * B * G::ROW_BYTES;
+  int32_t* pos = a.pos + static_cast<size_t>(u) * B;
+  const int qp = a.qpos[u];
+  const int old_pos = pos[slot];
+  const int w = a.recency_window;
+  const float rb = a.recency_bias_log2;
+
+  float* acc = a.stats + static_cast<size_t>(u) * 3 * B;
+  constexpr int PF = 512 / NT;  // covers B <= 2048; larger budgets load the rest after the stream
+  StatsAhead<NT, PF> ahead;
+  const bool vec = (B & 3) == 0;
+  if (vec) ahead.load(acc, acc + B, acc + 2 * static_cast<size_t>(B), n);
+
+  FlashState<G::EPL> st;
+  st.reset();
+  auto bias = [&](int row) -> float {
+    const int dlt = (row == slot) ? 0 : qp - pos[row];
+    return (dlt >= 0 && dlt < w) ? rb : 0.0f;
+  };
+  auto fix_k = [&](int row, uint4& kw, int col) {
+    if (row == slot && row < n) {
+      kw = load16(static_cast<const char*>(a.k_new) + in_off);
+      *reinterpret_cast<uint4*>(Kb + static_cast<size_t>(row) * G::ROW_BYTES + col * 16) = kw;
+    }
+  };
+  auto fix_v = [&](int row, uint4& vw, int col) {
+    if (row == slot && row < n) {
+      vw = load16(static_cast<const char*>(a.v_new) + in_off);
+      *reinterpret_cast<uint4*>(Vb + static_cast<size_t>(row) * G::ROW_BYTES + col * 16) = vw;
+    }
+  };
+  const int passes = (n + PASS - 1) / PASS;
+  const int rot = a.rotate ? static_cast<int>((static_cast<unsigned>(u) * 5u) % static_cast<unsigned>(passes)) : 0;
+  if (w > 0)
+    stream_attend<DT, D, U, true>(qf, Kb, Vb, 0, n, passes, rot, PASS, wave * (U * G::R), bias, z, slot, fix_k, fix_v, st);
+  else
+    stream_attend<DT, D, U, false>(qf, Kb, Vb, 0, n, passes, rot, PASS, wave * (U * G::R), bias, z, slot, fix_k, fix_v, st);
+  merge_groups_in_wave<DT, D>(st);
+
+  if (lane < G::LPR) {
+    if (lane == 0) { sm_m[wave] = st.m; sm_l[wave] = st.l; }
+#pragma unroll
+    for (int e = 0; e < G::EPL; ++e) sm_acc[wave][lane * G::EPL + e] = st.acc[e];
+  }
+  __syncthreads();  // also orders the waves' logit stores before the reads below
+  float M = -INFINITY;
+#pragma unroll
+  for (int s = 0; s < WAVES; ++s) M = fmaxf(M, sm_m[s]);
+  float Lsum = 0.0f;
+#pragma unroll
+  for (int s = 0; s < WAVES; ++s) Lsum += (sm_m[s] > -INFINITY) ? sm_l[s] * fast_exp2(sm_m[s] - M) : 0.0f;
+  const float inv = 1.0f / Lsum;
+  if (tid < D) {
+    float o = 0.0f;
+#pragma unroll
+    for (int s = 0; s < WAVES; ++s) o += (sm_m[s] > -INFINITY) ? sm_acc[s][tid] * fast_exp2(sm_m[s] - M) : 0.0f;
+    store_elem<DT>(a.out, static_cast<size_t>(u) * D + tid, o * inv);
+  }
+
+  // (bookkeeping before the statistics stores: no load may follow them, see decode_finish)
+  if (tid == 0) {
+    pos[slot] = qp;
+    a.n_used[u] = n;
+    if (a.evicted_slot) a.evicted_slot[u] = was_full ? slot : -1;
+    if (a.evicted_pos) a.evicted_pos[u] = was_full ? old_pos : -1;
+  }
+  update_statistics<NT, PF>(acc, acc + B, acc + 2 * static_cast<size_t>(B), z, n, B, slot, M, inv, full, mas_key,
+                            var_key, vec ? &ahead : nullptr);
   if (full) {
     __syncthreads();
     const int victim = select_victim_block<NT>(var_key, mas_key, B, a.scope, sel_sh, best_sh);
@@ -299,6 +462,12 @@ void launch_attend(const DecodeArgs& a, hipStream_t s) {
 template <int DT, int D>
 hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t s) {
   const size_t lds = (a.B <= kMaxDecodeBudgetLds) ? static_cast<size_t>(a.B) * 2 * sizeof(uint32_t) : 0;
+  if (a.fused) {  // requires B <= kMaxDecodeBudgetLds (checked by the host)
+    ProfScope ps(kProfDecodeAttend, s);
+    const size_t lds3 = static_cast<size_t>(a.B) * 3 * sizeof(uint32_t);
+    hipLaunchKernelGGL((decode_fused<DT, D, 8>), dim3(a.units), dim3(kFusedThreads), lds3, s, a);
+    return hipGetLastError();
+  }
   switch (a.unroll) {
     case 2: launch_attend<DT, D, 2>(a, s); break;
     case 8: launch_attend<DT, D, 8>(a, s); break;

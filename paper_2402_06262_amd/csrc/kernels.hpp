@@ -13,6 +13,7 @@ constexpr int kMaxDecodeBudgetLds = 4096;  // keys of a unit kept in LDS by the 
 struct DecodeArgs {
   int units, B, scope, splits, rows_per_split;
   int unroll;            // rows in flight per lane group in decode_attend: 2, 4 or 8
+  int fused;             // 1: one workgroup does the whole step of a unit (decode_fused), no workspace traffic
   int rotate;            // stagger the start offset of every workgroup inside its slot range
   float scale_log2;      // scale * log2(e)
   int recency_window;

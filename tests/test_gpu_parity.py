@@ -11,6 +11,14 @@ from oracle import roco_oracle as orc
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True, params=["split", "fused"])
+def decode_path(request, monkeypatch):
+    """Every case runs on both shapes of the decode step: slot ranges on several workgroups plus a finishing
+    kernel, and one workgroup per unit doing the whole step (the library would pick by the number of units)."""
+    monkeypatch.setenv("ROCO_DECODE_FUSED", "1" if request.param == "fused" else "0")
+    return request.param
+
+
 def _parity():
     import parity
     return parity

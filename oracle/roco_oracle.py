@@ -178,6 +178,52 @@ def select_evictions(mas: np.ndarray, var: np.ndarray, scope: int, n_evict: int)
 
 
 # ---------------------------------------------------------------------------
+# other eviction policies in the same two-stage framework (section 4: an eviction scope, then an importance
+# score inside it; section 4.1 lists the importance scores, section 4.2 / 4.3 the scopes)
+# ---------------------------------------------------------------------------
+
+@dataclass(frozen=True)
+class Policy:
+    """importance: "mas" (Acc/Count, section 4.3), "aas" (accumulated attention score Acc, the H2O score of
+    section 4.1), "oldest" (recency: the lowest position goes first, except the first `sinks` positions, which
+    are never chosen while anything else is in scope: the window / StreamLLM baseline of section 4.1).
+    scope_kind: "std" (the s tokens of lowest variance, section 4.3), "window" (the s oldest tokens, i.e. the
+    most recent n - s are protected: the local-window scope of section 4.2), "all" (every cached token)."""
+    importance: str = "mas"
+    scope_kind: str = "std"
+    sinks: int = 0
+
+
+ROCO = Policy()
+
+
+def ranking_scores(policy: Optional[Policy], acc, acc2, count, pos, scope: int):
+    """(importance, scope key, scope size) of every cached token under `policy`; None is RoCo.
+
+    Lower importance is evicted first; the scope is the `scope size` tokens of lowest scope key (ties by index).
+    """
+    policy = policy or ROCO
+    acc, acc2, count = (np.asarray(a, dtype=F64) for a in (acc, acc2, count))
+    pos = np.asarray(pos)
+    n = acc.shape[0]
+    if policy.importance == "mas":
+        importance = mean_attention_score(acc, count)
+    elif policy.importance == "aas":
+        importance = acc.copy()
+    elif policy.importance == "oldest":
+        importance = np.where(pos < policy.sinks, np.inf, pos.astype(F64))
+    else:
+        raise ValueError(policy.importance)
+    if policy.scope_kind == "std":
+        return importance, attention_variance(acc, acc2, count), scope
+    if policy.scope_kind == "window":
+        return importance, pos.astype(F64), scope
+    if policy.scope_kind == "all":
+        return importance, np.zeros(n, dtype=F64), n
+    raise ValueError(policy.scope_kind)
+
+
+# ---------------------------------------------------------------------------
 # the two calls of the boundary
 # ---------------------------------------------------------------------------
 
@@ -212,12 +258,12 @@ class PrefillResult:
 
 
 def compress_from_statistics(full: PrefillStats, K, V, length: int, budget: int, scope: int,
-                             force_retained: Optional[np.ndarray] = None) -> PrefillResult:
+                             force_retained: Optional[np.ndarray] = None,
+                             policy: Optional[Policy] = None) -> PrefillResult:
     """The eviction step and the compaction of `prefill_compress`, given the prompt's statistics."""
     n_evict = max(0, length - budget)
-    mas = mean_attention_score(full.acc, full.count)
-    var = attention_variance(full.acc, full.acc2, full.count)
-    evicted = select_evictions(mas, var, scope, n_evict)
+    mas, var, s_eff = ranking_scores(policy, full.acc, full.acc2, full.count, np.arange(length), scope)
+    evicted = select_evictions(mas, var, s_eff, n_evict)
     keep = np.ones(length, dtype=bool)
     keep[evicted] = False
     retained = np.flatnonzero(keep)
@@ -244,7 +290,8 @@ def compress_from_statistics(full: PrefillStats, K, V, length: int, budget: int,
 def prefill_compress(Q, K, V, length: int, budget: int, scope: int, scale: float,
                      recency_window: int = 0, recency_bias: float = 0.0,
                      want_out: bool = False, row_block: int = 512,
-                     force_retained: Optional[np.ndarray] = None) -> PrefillResult:
+                     force_retained: Optional[np.ndarray] = None,
+                     policy: Optional[Policy] = None) -> PrefillResult:
     """Encode a prompt and compress its cache to `budget` tokens in one eviction step.
 
     `force_retained` replaces the oracle's own retained set (used by the parity
@@ -252,7 +299,7 @@ def prefill_compress(Q, K, V, length: int, budget: int, scope: int, scale: float
     """
     full = prefill_statistics(Q, K, V, length, scale, recency_window, recency_bias,
                               want_out, row_block)
-    return compress_from_statistics(full, K, V, length, budget, scope, force_retained)
+    return compress_from_statistics(full, K, V, length, budget, scope, force_retained, policy)
 
 
 @dataclass
@@ -268,14 +315,13 @@ class DecodeResult:
 
 def decode_step(state: CacheState, q, k_new, v_new, qpos: int, scope: int, scale: float,
                 recency_window: int = 0, recency_bias: float = 0.0,
-                force_victim: Optional[int] = None) -> DecodeResult:
+                force_victim: Optional[int] = None, policy: Optional[Policy] = None) -> DecodeResult:
     """One auto-regressive step on a budgeted cache, in place: evict, append, attend, update."""
     B = state.budget
     mas = var = None
     if state.n_used == B:
-        mas = mean_attention_score(state.acc, state.count)
-        var = attention_variance(state.acc, state.acc2, state.count)
-        slot = select_victim(mas, var, scope) if force_victim is None else int(force_victim)
+        mas, var, s_eff = ranking_scores(policy, state.acc, state.acc2, state.count, state.pos, scope)
+        slot = select_victim(mas, var, s_eff) if force_victim is None else int(force_victim)
         evicted_slot, evicted_pos = slot, int(state.pos[slot])
     else:
         slot = state.n_used
@@ -314,7 +360,7 @@ class BlockResult:
 
 def encode_block(state: CacheState, Qb, Kb, Vb, qpos0: int, scope: int, scale: float,
                  recency_window: int = 0, recency_bias: float = 0.0,
-                 force_evicted: Optional[np.ndarray] = None) -> BlockResult:
+                 force_evicted: Optional[np.ndarray] = None, policy: Optional[Policy] = None) -> BlockResult:
     """Free and encode b tokens within one eviction step, in place.
 
     The paper lets the number of tokens freed and encoded per eviction step be a block size b (section 5.3;
@@ -332,9 +378,8 @@ def encode_block(state: CacheState, Qb, Kb, Vb, qpos0: int, scope: int, scale: f
     mas = var = None
     evicted = np.zeros(0, dtype=np.int64)
     if E > 0:
-        mas = mean_attention_score(state.acc[:n], state.count[:n])
-        var = attention_variance(state.acc[:n], state.acc2[:n], state.count[:n])
-        evicted = select_evictions(mas, var, scope, E) if force_evicted is None else \
+        mas, var, s_eff = ranking_scores(policy, state.acc[:n], state.acc2[:n], state.count[:n], state.pos[:n], scope)
+        evicted = select_evictions(mas, var, s_eff, E) if force_evicted is None else \
             np.sort(np.asarray(force_evicted, dtype=np.int64))
     targets = np.sort(np.concatenate([evicted, np.arange(n, min(B, n + b), dtype=np.int64)]))
     assert targets.shape[0] == b
@@ -385,7 +430,7 @@ class GroupDecodeResult:
 
 def decode_step_gqa(state: CacheState, Qg, k_new, v_new, qpos: int, scope: int, scale: float,
                     recency_window: int = 0, recency_bias: float = 0.0,
-                    force_victim: Optional[int] = None) -> GroupDecodeResult:
+                    force_victim: Optional[int] = None, policy: Optional[Policy] = None) -> GroupDecodeResult:
     """One decode step of a key/value head shared by g query heads.
 
     The paper extends attention-based policies to GQA / MQA by updating the importance score with the group-wise
@@ -398,9 +443,8 @@ def decode_step_gqa(state: CacheState, Qg, k_new, v_new, qpos: int, scope: int, 
     B = state.budget
     mas = var = None
     if state.n_used == B:
-        mas = mean_attention_score(state.acc, state.count)
-        var = attention_variance(state.acc, state.acc2, state.count)
-        slot = select_victim(mas, var, scope) if force_victim is None else int(force_victim)
+        mas, var, s_eff = ranking_scores(policy, state.acc, state.acc2, state.count, state.pos, scope)
+        slot = select_victim(mas, var, s_eff) if force_victim is None else int(force_victim)
         evicted_slot, evicted_pos = slot, int(state.pos[slot])
     else:
         slot = state.n_used
@@ -439,7 +483,7 @@ class GroupBlockResult:
 
 def encode_block_gqa(state: CacheState, Qb, Kb, Vb, qpos0: int, scope: int, scale: float,
                      recency_window: int = 0, recency_bias: float = 0.0,
-                     force_evicted: Optional[np.ndarray] = None) -> GroupBlockResult:
+                     force_evicted: Optional[np.ndarray] = None, policy: Optional[Policy] = None) -> GroupBlockResult:
     """Block-wise evict-and-encode of a key/value head shared by g query heads: Qb is [b, g, d], Kb / Vb [b, d].
 
     Eviction and slot assignment exactly as in `encode_block`; token i of the block is attended from by its g
@@ -455,9 +499,8 @@ def encode_block_gqa(state: CacheState, Qb, Kb, Vb, qpos0: int, scope: int, scal
     mas = var = None
     evicted = np.zeros(0, dtype=np.int64)
     if E > 0:
-        mas = mean_attention_score(state.acc[:n], state.count[:n])
-        var = attention_variance(state.acc[:n], state.acc2[:n], state.count[:n])
-        evicted = select_evictions(mas, var, scope, E) if force_evicted is None else \
+        mas, var, s_eff = ranking_scores(policy, state.acc[:n], state.acc2[:n], state.count[:n], state.pos[:n], scope)
+        evicted = select_evictions(mas, var, s_eff, E) if force_evicted is None else \
             np.sort(np.asarray(force_evicted, dtype=np.int64))
     targets = np.sort(np.concatenate([evicted, np.arange(n, min(B, n + b), dtype=np.int64)]))
     assert targets.shape[0] == b

@@ -536,3 +536,85 @@ def test_grouped_blocks_without_eviction_accumulate_the_head_mean_of_dense_causa
     out = np.concatenate(outs)  # [L, g, d]
     for h in range(g):
         assert np.allclose(out[:, h], P[h] @ V, rtol=1e-11, atol=1e-13)
+
+
+# ---------------------------------------------------------------------------- other policies of the same framework
+
+def test_recency_policy_with_sinks_is_the_sliding_window_with_attention_sinks_in_closed_form():
+    """importance "oldest" over the whole cache with k protected first positions: after any number of steps the
+    cache holds positions 0..k-1 and the most recent B-k ones, and each output is dense softmax attention over
+    exactly that set (computed here from the full K / V, with no cache)."""
+    rng = np.random.default_rng(51)
+    L, T, d, B, k = 20, 15, 4, 9, 3
+    Q, K, V = rand_unit(rng, L + T, d)
+    pol = orc.Policy("oldest", "all", k)
+    r = orc.prefill_compress(Q[:L], K[:L], V[:L], L, B, 1, 0.5, policy=pol)
+    st = r.cache
+    assert list(st.pos) == list(range(k)) + list(range(L - (B - k), L))
+    for t in range(L, L + T):
+        res = orc.decode_step(st, Q[t], K[t], V[t], t, 1, 0.5, policy=pol)
+        keep = list(range(k)) + list(range(t - (B - k) + 1, t + 1))
+        assert sorted(st.pos) == keep and res.evicted_pos == t - (B - k)
+        z = 0.5 * K[keep] @ Q[t]
+        w = np.exp(z - z.max())
+        w /= w.sum()
+        assert np.allclose(res.out, w @ V[keep], rtol=1e-12)
+
+
+def test_accumulated_score_policy_evicts_the_argmin_of_an_independent_recount():
+    """importance "aas" over the whole cache (the accumulated attention score of section 4.1): the evicted
+    position is the argmin of sums rebuilt from a log of every attention row."""
+    rng = np.random.default_rng(52)
+    L, T, d, B = 16, 20, 5, 16
+    Q, K, V = rand_unit(rng, L + T, d)
+    pol = orc.Policy("aas", "all")
+    r = orc.prefill_compress(Q[:L], K[:L], V[:L], L, B, 3, 0.4, policy=pol)
+    st = r.cache
+    total = {int(p): float(a) for p, a in zip(st.pos, st.acc)}  # B = L: nothing evicted yet, Acc = column sums
+    dense = np.zeros(L)
+    for i in range(L):
+        z = 0.4 * K[:i + 1] @ Q[i]
+        w = np.exp(z - z.max())
+        dense[:i + 1] += w / w.sum()
+    assert np.allclose([total[j] for j in range(L)], dense, rtol=1e-12)
+    for t in range(L, L + T):
+        expect = min(total, key=lambda j: (total[j], j))
+        res = orc.decode_step(st, Q[t], K[t], V[t], t, 3, 0.4, policy=pol)
+        assert res.evicted_pos == expect
+        del total[expect]
+        total[t] = 0.0
+        for slot in range(B):
+            total[int(st.pos[slot])] += float(res.probs[slot])
+
+
+def test_window_scope_protects_the_most_recent_tokens_and_picks_by_explicit_sort():
+    rng = np.random.default_rng(53)
+    L, T, d, B, s = 30, 25, 4, 12, 5
+    Q, K, V = rand_unit(rng, L + T, d)
+    for imp in ("mas", "aas"):
+        pol = orc.Policy(imp, "window")
+        st = orc.prefill_compress(Q[:L], K[:L], V[:L], L, B, s, 0.5, policy=pol).cache
+        for t in range(L, L + T):
+            before = st.copy()
+            res = orc.decode_step(st, Q[t], K[t], V[t], t, s, 0.5, policy=pol)
+            oldest = sorted(range(B), key=lambda j: before.pos[j])[:s]
+            score = before.acc / before.count if imp == "mas" else before.acc
+            expect = min(oldest, key=lambda j: (score[j], j))
+            assert res.evicted_slot == expect
+            assert res.evicted_pos not in sorted(before.pos)[s:]  # the B - s most recent are never touched
+
+
+def test_default_policy_is_roco_and_block_steps_accept_a_policy():
+    rng = np.random.default_rng(54)
+    L, d, B, s = 24, 4, 10, 3
+    Q, K, V = rand_unit(rng, L + 6, d)
+    a = orc.prefill_compress(Q[:L], K[:L], V[:L], L, B, s, 0.5).cache
+    b = orc.prefill_compress(Q[:L], K[:L], V[:L], L, B, s, 0.5, policy=orc.Policy("mas", "std")).cache
+    assert np.array_equal(a.pos, b.pos) and np.array_equal(a.acc, b.acc)
+    pol = orc.Policy("oldest", "all", 2)
+    c = orc.prefill_compress(Q[:L], K[:L], V[:L], L, B, s, 0.5, policy=pol).cache
+    e = c.copy()
+    for t in range(L, L + 6):
+        orc.decode_step(c, Q[t], K[t], V[t], t, s, 0.5, policy=pol)
+    orc.encode_block(e, Q[L:L + 6], K[L:L + 6], V[L:L + 6], L, s, 0.5, policy=pol)
+    assert sorted(c.pos) == sorted(e.pos) == [0, 1] + list(range(L + 6 - 8, L + 6))

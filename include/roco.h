@@ -63,7 +63,25 @@ typedef struct roco_params {
                              position kp) gets + recency_bias when 0 <= qp - kp < w.  Not part of
                              the paper; used by the long-context stress workload only.             */
   float   recency_bias;
+  /* Eviction policy in the paper's two-stage framework (section 4: an eviction scope, then an importance score
+   * inside it).  All three zero is RoCo (section 4.3); the other values are the framework's other members
+   * (sections 4.1, 4.2), served by the same kernels.                                                         */
+  int32_t importance;     /* ROCO_IMPORTANCE_*: which token of the scope goes first (lowest value)            */
+  int32_t scope_kind;     /* ROCO_SCOPE_*: which `scope` tokens form the eviction scope                       */
+  int32_t sinks;          /* >= 0; with ROCO_IMPORTANCE_OLDEST, positions < sinks are evicted only when nothing
+                             else is in the scope (attention sinks of the window baseline)                   */
 } roco_params;
+
+enum {
+  ROCO_IMPORTANCE_MAS = 0,    /* mean attention score Acc/Count (section 4.3)                                 */
+  ROCO_IMPORTANCE_AAS = 1,    /* accumulated attention score Acc (section 4.1)                                */
+  ROCO_IMPORTANCE_OLDEST = 2  /* recency: the lowest position goes first (section 4.1, window / sink baseline) */
+};
+enum {
+  ROCO_SCOPE_STD = 0,     /* the `scope` tokens of lowest attention variance (section 4.3)                    */
+  ROCO_SCOPE_WINDOW = 1,  /* the `scope` oldest tokens: the most recent n - scope are protected (section 4.2)  */
+  ROCO_SCOPE_ALL = 2      /* every cached token; `scope` is ignored                                           */
+};
 
 /* Bytes of scratch the two calls need for these params (0 on invalid params). */
 size_t roco_prefill_workspace_bytes(const roco_params* params, int32_t L_max);
@@ -199,11 +217,12 @@ int roco_decode_step_gqa(const roco_params* params, int32_t group,
 
 /*
  * Victim selection alone (section 4.3): for every full unit, next_slot[u] = the slot of lowest Acc/Count among
- * the s slots of lowest variance; -1 for units that are not full.  Only needed after the caller has edited
- * stats / n_used itself.  stats in [units,3,B], n_used in [units], next_slot out [units]; the workspace is the
- * decode workspace.
+ * the s slots of lowest variance (or what params' policy ranks by); -1 for units that are not full.  Only needed
+ * after the caller has edited stats / n_used itself.  stats in [units,3,B], pos in [units,B] (read only by
+ * policies that rank by position: ROCO_IMPORTANCE_OLDEST, ROCO_SCOPE_WINDOW; may be NULL otherwise), n_used in
+ * [units], next_slot out [units]; the workspace is the decode workspace.
  */
-int roco_select_victims(const roco_params* params, const float* stats, const int32_t* n_used,
+int roco_select_victims(const roco_params* params, const float* stats, const int32_t* pos, const int32_t* n_used,
                         int32_t* next_slot, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*

@@ -29,6 +29,22 @@ import numpy as np
 F64 = np.float64
 
 
+def bands_for(policy, acc, acc2, count, rel: float = 1e-3) -> Tuple[np.ndarray, np.ndarray]:
+    """(eps_importance, eps_scope_key) per token for an eviction policy (an object with `importance` and
+    `scope_kind` strings, or None for RoCo): scores that are sums of probabilities get the relative band,
+    scores that are positions are exact."""
+    eps_m, eps_v = bands(acc, acc2, count, rel)
+    importance = getattr(policy, "importance", "mas")
+    scope_kind = getattr(policy, "scope_kind", "std")
+    if importance == "aas":
+        eps_m = rel * np.abs(np.asarray(acc, dtype=F64))
+    elif importance == "oldest":
+        eps_m = np.zeros_like(eps_m)
+    if scope_kind != "std":
+        eps_v = np.zeros_like(eps_v)
+    return eps_m, eps_v
+
+
 def bands(acc, acc2, count, rel: float = 1e-3) -> Tuple[np.ndarray, np.ndarray]:
     """(eps_mas, eps_var) per token."""
     acc, acc2, count = (np.asarray(a, dtype=F64) for a in (acc, acc2, count))

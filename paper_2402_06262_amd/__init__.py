@@ -7,6 +7,12 @@ from .binding import (  # noqa: F401
     PROF_KERNELS,
     ROCO_BF16,
     ROCO_F32,
+    ROCO_IMPORTANCE_AAS,
+    ROCO_IMPORTANCE_MAS,
+    ROCO_IMPORTANCE_OLDEST,
+    ROCO_SCOPE_ALL,
+    ROCO_SCOPE_STD,
+    ROCO_SCOPE_WINDOW,
     RocoCache,
     RocoError,
     RocoParams,

@@ -12,6 +12,8 @@ from typing import Optional
 
 ROCO_F32 = 0
 ROCO_BF16 = 1
+ROCO_IMPORTANCE_MAS, ROCO_IMPORTANCE_AAS, ROCO_IMPORTANCE_OLDEST = 0, 1, 2
+ROCO_SCOPE_STD, ROCO_SCOPE_WINDOW, ROCO_SCOPE_ALL = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libroco.so"
@@ -38,11 +40,15 @@ class RocoParams(ctypes.Structure):
         ("scale", ctypes.c_float),
         ("recency_window", ctypes.c_int32),
         ("recency_bias", ctypes.c_float),
+        ("importance", ctypes.c_int32),
+        ("scope_kind", ctypes.c_int32),
+        ("sinks", ctypes.c_int32),
     ]
 
-    def __init__(self, units, head_dim, budget, scope, dtype, scale=0.0, recency_window=0, recency_bias=0.0):
+    def __init__(self, units, head_dim, budget, scope, dtype, scale=0.0, recency_window=0, recency_bias=0.0,
+                 importance=0, scope_kind=0, sinks=0):
         super().__init__(int(units), int(head_dim), int(budget), int(scope), int(dtype), float(scale),
-                         int(recency_window), float(recency_bias))
+                         int(recency_window), float(recency_bias), int(importance), int(scope_kind), int(sinks))
 
 
 def library_path() -> str:
@@ -82,7 +88,7 @@ def load_library() -> ctypes.CDLL:
     lib.roco_decode_step_gqa.restype = ctypes.c_int
     lib.roco_decode_step_gqa.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.roco_select_victims.restype = ctypes.c_int
-    lib.roco_select_victims.argtypes = [pp, vp, vp, vp, vp, sz, vp]
+    lib.roco_select_victims.argtypes = [pp, vp, vp, vp, vp, vp, sz, vp]
     lib.roco_strerror.restype = ctypes.c_char_p
     lib.roco_strerror.argtypes = [ctypes.c_int]
     lib.roco_version.restype = ctypes.c_int
@@ -252,12 +258,12 @@ def roco_probe_cache_read(params: RocoParams, K_cache, V_cache, workspace, works
         raise RocoError(rc, "roco_probe_cache_read")
 
 
-def roco_select_victims(params: RocoParams, stats, n_used, next_slot, workspace,
+def roco_select_victims(params: RocoParams, stats, pos, n_used, next_slot, workspace,
                         workspace_bytes: Optional[int] = None, stream=None) -> None:
-    """See include/roco.h: recompute next_slot from stats / n_used."""
+    """See include/roco.h: recompute next_slot from stats / pos / n_used."""
     if workspace_bytes is None:
         workspace_bytes = workspace.numel() * workspace.element_size()
-    rc = load_library().roco_select_victims(ctypes.byref(params), _ptr(stats), _ptr(n_used), _ptr(next_slot),
+    rc = load_library().roco_select_victims(ctypes.byref(params), _ptr(stats), _ptr(pos), _ptr(n_used), _ptr(next_slot),
                                             _ptr(workspace), int(workspace_bytes), _stream(stream))
     if rc != 0:
         raise RocoError(rc, "roco_select_victims")

@@ -18,12 +18,15 @@ int check_params(const roco_params* p) {
   if (p == nullptr) return ROCO_EINVAL;
   if (p->units < 1 || p->budget < 1 || p->scope < 1 || p->scope > p->budget) return ROCO_EINVAL;
   if (p->recency_window < 0) return ROCO_EINVAL;
+  if (p->importance < 0 || p->importance > 2 || p->scope_kind < 0 || p->scope_kind > 2 || p->sinks < 0) return ROCO_EINVAL;
   if (!(p->scale == p->scale) || !(p->recency_bias == p->recency_bias)) return ROCO_EINVAL;  // NaN
   if (p->dtype != ROCO_F32 && p->dtype != ROCO_BF16) return ROCO_EUNSUPPORTED;
   if (p->head_dim != 64 && p->head_dim != 128) return ROCO_EUNSUPPORTED;
   if (p->budget > (1 << 24)) return ROCO_EUNSUPPORTED;  // Count is kept exactly in fp32
   return ROCO_OK;
 }
+
+Policy policy_of(const roco_params* p) { return Policy{p->importance, p->scope_kind, p->sinks}; }
 
 float scale_log2(const roco_params* p) {
   const float s = p->scale > 0.0f ? p->scale : 1.0f / sqrtf(static_cast<float>(p->head_dim));
@@ -145,6 +148,7 @@ int roco_prefill_compress(const roco_params* params, const void* Q, const void* 
 
   PrefillArgs a;
   a.units = params->units; a.L_max = L_max; a.B = params->budget; a.scope = params->scope;
+  a.pol = policy_of(params);
   a.pairs = 0;
   a.paired = env_int("ROCO_PREFILL_PAIRED", -1);
   a.mfma_waves = env_int("ROCO_PREFILL_WAVES", 0);
@@ -184,6 +188,7 @@ int roco_decode_step(const roco_params* params, const void* q, const void* k_new
 
   DecodeArgs a;
   a.units = params->units; a.B = params->budget; a.scope = params->scope;
+  a.pol = policy_of(params);
   a.unroll = env_int("ROCO_DECODE_UNROLL", 8);  // rows per lane group per block; 8 measured best on workload 3
   if (a.unroll != 2 && a.unroll != 4) a.unroll = 8;
   a.rotate = env_int("ROCO_DECODE_ROTATE", 1);
@@ -228,6 +233,7 @@ int run_block(const roco_params* params, int tokens, int heads, const void* q, c
 
   BlockArgs a;
   a.units = params->units; a.B = params->budget; a.scope = params->scope;
+  a.pol = policy_of(params);
   a.block = tokens; a.heads = heads; a.queries = tokens * heads;
   {  // split the budget into 64-slot-aligned ranges: two resident workgroups per compute unit measured best
     // (more splits cost more partial results to write and merge than they gain in balance)
@@ -284,10 +290,11 @@ int roco_decode_step_gqa(const roco_params* params, int32_t group, const void* q
                    evicted_slot, evicted_pos, workspace, workspace_bytes, hip_stream);
 }
 
-int roco_select_victims(const roco_params* params, const float* stats, const int32_t* n_used,
+int roco_select_victims(const roco_params* params, const float* stats, const int32_t* pos, const int32_t* n_used,
                         int32_t* next_slot, void* workspace, size_t workspace_bytes, void* hip_stream) {
   const int rc = check_params(params);
   if (rc != ROCO_OK) return rc;
+  if (policy_of(params).needs_pos() && pos == nullptr) return ROCO_EINVAL;
   const void* need[] = {stats, n_used, next_slot, workspace};
   for (const void* ptr : need)
     if (ptr == nullptr || !aligned16(ptr)) return ROCO_EINVAL;
@@ -295,6 +302,8 @@ int roco_select_victims(const roco_params* params, const float* stats, const int
   if (workspace_bytes < lay.total) return ROCO_EWORKSPACE;
   DecodeArgs a = {};
   a.units = params->units; a.B = params->budget; a.scope = params->scope;
+  a.pol = policy_of(params);
+  a.pos = const_cast<int32_t*>(pos);
   a.stats = const_cast<float*>(stats);
   a.n_used = const_cast<int32_t*>(n_used);
   a.next_slot = next_slot;

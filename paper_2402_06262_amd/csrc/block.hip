@@ -62,9 +62,9 @@ __global__ __launch_bounds__(kPrepThreads) void block_prepare(BlockArgs a) {
   // one eviction from a full cache: the victim was already chosen when the statistics were last updated
   const int hint = (E == 1 && n == B) ? a.next_slot[u] : -1;
   if (E > 0 && hint < 0) {
-    for (int i = tid; i < n; i += NT) ranking_keys(acc[i], acc2[i], cnt[i], mas_key[i], var_key[i]);
+    for (int i = tid; i < n; i += NT) ranking_keys(acc[i], acc2[i], cnt[i], pos[i], a.pol, mas_key[i], var_key[i]);
     __syncthreads();
-    const uint32_t m = min(static_cast<uint32_t>(n), static_cast<uint32_t>(a.scope) + static_cast<uint32_t>(E) - 1u);
+    const uint32_t m = min(static_cast<uint32_t>(n), static_cast<uint32_t>(a.pol.scope_size(a.scope, n)) + static_cast<uint32_t>(E) - 1u);
     scope = select_k_smallest<NT>([&](int i) { return var_key[i]; }, n, m, sel_sh);
     out = select_k_smallest<NT>(
         [&](int i) -> uint32_t { return scope.has(var_key[i], i) ? mas_key[i] : 0xffffffffu; }, n,
@@ -421,7 +421,7 @@ hipError_t launch_block(const BlockArgs& a, hipStream_t s) {
   }
   if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
   DecodeArgs sel = {};  // the victim a following single-token decode step would take
-  sel.units = a.units; sel.B = a.B; sel.scope = a.scope;
+  sel.units = a.units; sel.B = a.B; sel.scope = a.scope; sel.pol = a.pol; sel.pos = a.pos;
   sel.stats = a.stats; sel.n_used = a.n_used; sel.next_slot = a.next_slot; sel.keys = a.keys;
   return launch_select_victims(sel, s);
 }

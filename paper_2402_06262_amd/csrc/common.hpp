@@ -1,5 +1,6 @@
 // Device helpers shared by the RoCo kernels (gfx950, 64-wide wavefronts).
 #pragma once
+#include "kernels.hpp"
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -216,16 +217,32 @@ __device__ KSmallest select_k_smallest(KeyFn key_of, int n, uint32_t k, uint32_t
   return r;
 }
 
-// Mean attention score and attention variance as ranking keys, each operation rounded on its own
+// Ranking keys of one cached token: the token of lowest importance key among the tokens of lowest scope key
+// is evicted; keys are compared as unsigned integers (non-negative floats order like their bit patterns).
+// For RoCo these are the mean attention score and the attention variance, each operation rounded on its own
 // (no fused multiply-add), so that a single observation gives a variance of exactly zero:
 //   MAS = Acc/Count,  Var = max(0, Acc2/Count - MAS^2)          (section 4.3 of the paper)
-__device__ __forceinline__ void ranking_keys(float acc, float acc2, float count,
+// A protected sink position gets the largest importance key below the marker 0xffffffff that the selections
+// use for "outside the scope".
+__device__ __forceinline__ void ranking_keys(float acc, float acc2, float count, int pos, const Policy& pol,
                                              uint32_t& mas_key, uint32_t& var_key) {
-  const float mas = __fdiv_rn(acc, count);
-  const float ex2 = __fdiv_rn(acc2, count);
-  const float var = __fsub_rn(ex2, __fmul_rn(mas, mas));
-  mas_key = __float_as_uint(mas);
-  var_key = var > 0.0f ? __float_as_uint(var) : 0u;
+  if (pol.importance == kImpMas) {
+    mas_key = __float_as_uint(__fdiv_rn(acc, count));
+  } else if (pol.importance == kImpAas) {
+    mas_key = acc > 0.0f ? __float_as_uint(acc) : 0u;
+  } else {
+    mas_key = pos < pol.sinks ? 0xfffffffeu : static_cast<uint32_t>(pos);
+  }
+  if (pol.scope_kind == kScopeStd) {
+    const float mas = __fdiv_rn(acc, count);
+    const float ex2 = __fdiv_rn(acc2, count);
+    const float var = __fsub_rn(ex2, __fmul_rn(mas, mas));
+    var_key = var > 0.0f ? __float_as_uint(var) : 0u;
+  } else if (pol.scope_kind == kScopeWindow) {
+    var_key = static_cast<uint32_t>(pos);
+  } else {
+    var_key = 0u;
+  }
 }
 
 }  // namespace roco

@@ -150,10 +150,24 @@ __global__ __launch_bounds__(kAttendThreads) void decode_attend(DecodeArgs a) {
 // Adds this step's probabilities p_j = 2^(z_j - M) / L to the three statistics of slots [0, n) (the slot that
 // just received the new token starts from zero) and, when the unit is full, writes the ranking keys of the
 // updated statistics.  z may live in global memory or in LDS.
+// What the ranking keys of a step need besides the statistics: the policy, the slots' positions (read only by
+// policies that rank by position) and the position of the token that has just taken `slot`.
+struct StepKeys {
+  Policy pol;
+  const int32_t* pos;
+  int qpos;
+};
+
 // The update of four adjacent slots j .. j + 3 whose statistics are already in registers.
 __device__ __forceinline__ void update_four(float4& a1, float4& a2, float4& cc, const float4 zz, int j, int n, int slot,
-                                            float M, float inv, bool full, uint32_t* mas_key, uint32_t* var_key) {
+                                            float M, float inv, bool full, uint32_t* mas_key, uint32_t* var_key,
+                                            const StepKeys& sk) {
   const float zv[4] = {zz.x, zz.y, zz.z, zz.w};
+  int pv[4] = {0, 0, 0, 0};
+  if (full && sk.pol.needs_pos()) {
+    const int4 pp = *reinterpret_cast<const int4*>(sk.pos + j);
+    pv[0] = pp.x; pv[1] = pp.y; pv[2] = pp.z; pv[3] = pp.w;
+  }
   float s1[4] = {a1.x, a1.y, a1.z, a1.w}, s2[4] = {a2.x, a2.y, a2.z, a2.w}, sc[4] = {cc.x, cc.y, cc.z, cc.w};
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
@@ -164,7 +178,7 @@ __device__ __forceinline__ void update_four(float4& a1, float4& a2, float4& cc, 
       s1[e] += p;
       s2[e] += p * p;
       sc[e] += 1.0f;
-      if (full) ranking_keys(s1[e], s2[e], sc[e], mas_key[jj], var_key[jj]);
+      if (full) ranking_keys(s1[e], s2[e], sc[e], jj == slot ? sk.qpos : pv[e], sk.pol, mas_key[jj], var_key[jj]);
     }
   }
   a1 = make_float4(s1[0], s1[1], s1[2], s1[3]);
@@ -191,7 +205,7 @@ template <int NT, int PF> struct StatsAhead {
 template <int NT, int PF>
 __device__ __forceinline__ void update_statistics(float* acc, float* acc2, float* cnt, const float* z, int n, int B,
                                                   int slot, float M, float inv, bool full, uint32_t* mas_key,
-                                                  uint32_t* var_key, StatsAhead<NT, PF>* ahead) {
+                                                  uint32_t* var_key, StatsAhead<NT, PF>* ahead, const StepKeys& sk) {
   const int tid = threadIdx.x;
   if ((B & 3) == 0) {
     // four adjacent slots per thread, 128-bit accesses on every plane
@@ -201,7 +215,7 @@ __device__ __forceinline__ void update_statistics(float* acc, float* acc2, float
         const int j = (k * NT + tid) * 4;
         if (j < n) {
           update_four(ahead->a1[k], ahead->a2[k], ahead->cc[k], *reinterpret_cast<const float4*>(z + j), j, n, slot, M,
-                      inv, full, mas_key, var_key);
+                      inv, full, mas_key, var_key, sk);
           store_streaming(acc + j, ahead->a1[k]);
           store_streaming(acc2 + j, ahead->a2[k]);
           store_streaming(cnt + j, ahead->cc[k]);
@@ -212,7 +226,7 @@ __device__ __forceinline__ void update_statistics(float* acc, float* acc2, float
       float4 a1 = *reinterpret_cast<const float4*>(acc + j);
       float4 a2 = *reinterpret_cast<const float4*>(acc2 + j);
       float4 cc = *reinterpret_cast<const float4*>(cnt + j);
-      update_four(a1, a2, cc, *reinterpret_cast<const float4*>(z + j), j, n, slot, M, inv, full, mas_key, var_key);
+      update_four(a1, a2, cc, *reinterpret_cast<const float4*>(z + j), j, n, slot, M, inv, full, mas_key, var_key, sk);
       *reinterpret_cast<float4*>(acc + j) = a1;
       *reinterpret_cast<float4*>(acc2 + j) = a2;
       *reinterpret_cast<float4*>(cnt + j) = cc;
@@ -226,7 +240,7 @@ __device__ __forceinline__ void update_statistics(float* acc, float* acc2, float
       s2 += p * p;
       sc += 1.0f;
       acc[j] = s1; acc2[j] = s2; cnt[j] = sc;
-      if (full) ranking_keys(s1, s2, sc, mas_key[j], var_key[j]);
+      if (full) ranking_keys(s1, s2, sc, j == slot ? sk.qpos : (sk.pol.needs_pos() ? sk.pos[j] : 0), sk.pol, mas_key[j], var_key[j]);
     }
   }
 }
@@ -280,10 +294,11 @@ __global__ __launch_bounds__(kFinishThreads) void decode_finish(DecodeArgs a) {
     if (a.evicted_slot) a.evicted_slot[u] = was_full ? slot : -1;
     if (a.evicted_pos) a.evicted_pos[u] = was_full ? old_pos : -1;
   }
-  update_statistics<NT, 1>(acc, acc2, cnt, z, n, B, slot, M, inv, full, mas_key, var_key, nullptr);
+  const StepKeys sk = {a.pol, pos, a.qpos[u]};
+  update_statistics<NT, 1>(acc, acc2, cnt, z, n, B, slot, M, inv, full, mas_key, var_key, nullptr, sk);
   if (full) {
     __syncthreads();
-    const int victim = select_victim_block<NT>(var_key, mas_key, B, a.scope, sel_sh, best_sh);
+    const int victim = select_victim_block<NT>(var_key, mas_key, B, a.pol.scope_size(a.scope, B), sel_sh, best_sh);
     if (tid == 0) a.next_slot[u] = victim;
   }
 }
@@ -392,10 +407,10 @@ __global__ __launch_bounds__(kFusedThreads) void decode_fused(DecodeArgs a) {
     if (a.evicted_pos) a.evicted_pos[u] = was_full ? old_pos : -1;
   }
   update_statistics<NT, PF>(acc, acc + B, acc + 2 * static_cast<size_t>(B), z, n, B, slot, M, inv, full, mas_key,
-                            var_key, vec ? &ahead : nullptr);
+                            var_key, vec ? &ahead : nullptr, StepKeys{a.pol, pos, qp});
   if (full) {
     __syncthreads();
-    const int victim = select_victim_block<NT>(var_key, mas_key, B, a.scope, sel_sh, best_sh);
+    const int victim = select_victim_block<NT>(var_key, mas_key, B, a.pol.scope_size(a.scope, B), sel_sh, best_sh);
     if (tid == 0) a.next_slot[u] = victim;
   }
 }
@@ -417,9 +432,12 @@ __global__ __launch_bounds__(kFinishThreads) void select_victims(DecodeArgs a) {
   const float* cnt = acc2 + B;
   uint32_t* var_key = (B <= kMaxDecodeBudgetLds) ? lds_keys : a.keys + static_cast<size_t>(u) * 2 * B;
   uint32_t* mas_key = var_key + B;
-  for (int i = tid; i < B; i += NT) ranking_keys(acc[i], acc2[i], cnt[i], mas_key[i], var_key[i]);
+  const bool by_pos = a.pol.needs_pos();
+  const int32_t* pos = a.pos + static_cast<size_t>(u) * B;
+  for (int i = tid; i < B; i += NT)
+    ranking_keys(acc[i], acc2[i], cnt[i], by_pos ? pos[i] : 0, a.pol, mas_key[i], var_key[i]);
   __syncthreads();
-  const int victim = select_victim_block<NT>(var_key, mas_key, B, a.scope, sel_sh, best_sh);
+  const int victim = select_victim_block<NT>(var_key, mas_key, B, a.pol.scope_size(a.scope, B), sel_sh, best_sh);
   if (tid == 0) a.next_slot[u] = victim;
 }
 

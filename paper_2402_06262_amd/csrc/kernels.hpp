@@ -6,12 +6,26 @@
 
 namespace roco {
 
+// Eviction policy in the paper's two-stage framework (section 4): an eviction scope, then an importance score
+// inside it.  All zeros is RoCo (section 4.3).
+enum : int { kImpMas = 0, kImpAas = 1, kImpOldest = 2 };
+enum : int { kScopeStd = 0, kScopeWindow = 1, kScopeAll = 2 };
+struct Policy {
+  int importance;  // kImpMas: Acc/Count; kImpAas: Acc; kImpOldest: position, the first `sinks` positions last
+  int scope_kind;  // kScopeStd: lowest variance; kScopeWindow: lowest position (oldest); kScopeAll: everything
+  int sinks;
+  __host__ __device__ bool needs_pos() const { return importance == kImpOldest || scope_kind == kScopeWindow; }
+  // number of tokens inside the scope when n are cached
+  __host__ __device__ int scope_size(int scope, int n) const { return scope_kind == kScopeAll ? n : scope; }
+};
+
 constexpr int kMaxSplits = 64;        // upper bound on split-K partials per unit (sizes the workspace)
 constexpr int kDecodeSelectThreads = 256;
 constexpr int kMaxDecodeBudgetLds = 4096;  // keys of a unit kept in LDS by the decode selection up to here
 
 struct DecodeArgs {
   int units, B, scope, splits, rows_per_split;
+  Policy pol;
   int unroll;            // rows in flight per lane group in decode_attend: 2, 4 or 8
   int fused;             // 1: one workgroup does the whole step of a unit (decode_fused), no workspace traffic
   int rotate;            // stagger the start offset of every workgroup inside its slot range
@@ -36,6 +50,7 @@ struct DecodeArgs {
 
 struct PrefillArgs {
   int units, L_max, B, scope;
+  Policy pol;
   int pairs;             // matrix-core path: workgroup ids per unit (set by its launcher)
   int paired;            // matrix-core path: 1 = long+short block per workgroup, 0 = one block, -1 = choose
   int mfma_waves;        // matrix-core path: 4 or 8 waves per workgroup, 0 = choose by problem size
@@ -62,6 +77,7 @@ constexpr int kMaxBlockSplits = 8;   // split-K partials per unit of the block-w
 
 struct BlockArgs {
   int units, B, scope, block, splits, rows_per_split;
+  Policy pol;
   int heads;    // query heads that share the unit's keys and values (1 without grouped-query attention)
   int queries;  // query rows per unit = block * heads <= 32; row r belongs to token r / heads, head r % heads
   float scale_log2;

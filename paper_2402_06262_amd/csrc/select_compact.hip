@@ -49,10 +49,10 @@ __global__ __launch_bounds__(kSelThreads) void prefill_select(PrefillArgs a) {
     }
   } else {
     const uint32_t E = static_cast<uint32_t>(n - B);
-    const uint32_t m = min(static_cast<uint32_t>(n), static_cast<uint32_t>(a.scope) + E - 1u);
+    const uint32_t m = min(static_cast<uint32_t>(n), static_cast<uint32_t>(a.pol.scope_size(a.scope, n)) + E - 1u);
     for (int i = tid; i < n; i += NT) {
       uint32_t mk, vk;
-      ranking_keys(acc[i], acc2[i], static_cast<float>(n - i), mk, vk);
+      ranking_keys(acc[i], acc2[i], static_cast<float>(n - i), i, a.pol, mk, vk);
       var_key[i] = vk;
       mas_key[i] = mk;
     }
@@ -87,10 +87,10 @@ __global__ __launch_bounds__(kSelThreads) void prefill_select(PrefillArgs a) {
   // the first decode step on a full cache needs its victim: choose it now, from the compacted statistics
   if (kept == B) {
     __syncthreads();  // the compacted planes written above are visible to the whole block
-    for (int i = tid; i < B; i += NT) ranking_keys(oacc[i], oacc2[i], ocnt[i], mas_key[i], var_key[i]);
+    for (int i = tid; i < B; i += NT) ranking_keys(oacc[i], oacc2[i], ocnt[i], pos[i], a.pol, mas_key[i], var_key[i]);
     __syncthreads();
     const KSmallest sc = select_k_smallest<NT>([&](int i) { return var_key[i]; }, B,
-                                               static_cast<uint32_t>(a.scope), sel_sh);
+                                               static_cast<uint32_t>(a.pol.scope_size(a.scope, B)), sel_sh);
     unsigned long long best = ~0ull;
     for (int i = tid; i < B; i += NT) {
       if (sc.has(var_key[i], i)) {

@@ -91,9 +91,16 @@ class GpuSession:
     O: Optional[torch.Tensor] = None
 
 
+_IMPORTANCE = {"mas": 0, "aas": 1, "oldest": 2}
+_SCOPE_KIND = {"std": 0, "window": 1, "all": 2}
+
+
 def make_session(units: int, head_dim: int, budget: int, scope: int, dtype: str, scale: float = 0.0,
-                 recency_window: int = 0, recency_bias: float = 0.0) -> GpuSession:
-    p = roco.RocoParams(units, head_dim, budget, scope, roco_dtype(dtype), scale, recency_window, recency_bias)
+                 recency_window: int = 0, recency_bias: float = 0.0, policy=None) -> GpuSession:
+    """`policy`: an oracle Policy (None = RoCo); it is translated to the library's enum values here."""
+    pol = policy or orc.ROCO
+    p = roco.RocoParams(units, head_dim, budget, scope, roco_dtype(dtype), scale, recency_window, recency_bias,
+                        _IMPORTANCE[pol.importance], _SCOPE_KIND[pol.scope_kind], pol.sinks)
     cache = roco.alloc_cache(p)
     ws = torch.empty(max(16, roco.decode_workspace_bytes(p)), dtype=torch.uint8, device="cuda")
     out = torch.zeros((units, head_dim), dtype=torch_dtype(dtype), device="cuda")
@@ -121,7 +128,7 @@ def gpu_prefill(sess: GpuSession, Q: np.ndarray, K: np.ndarray, V: np.ndarray, l
 
 def check_prefill_unit(g: dict, u: int, Qu, Ku, Vu, length: int, budget: int, scope: int, scale: float,
                        dtype: str, recency_window: int = 0, recency_bias: float = 0.0,
-                       want_out: bool = True, row_block: int = 512, full=None, out_rows=None):
+                       want_out: bool = True, row_block: int = 512, full=None, out_rows=None, policy=None):
     """Compare unit `u` of a gpu_prefill result with the oracle.  Returns (oracle result, TieCount).
 
     `full` lets several scopes share one evaluation of the oracle's statistics; `out_rows` restricts the
@@ -129,7 +136,7 @@ def check_prefill_unit(g: dict, u: int, Qu, Ku, Vu, length: int, budget: int, sc
     ties = TieCount()
     if full is None:
         full = orc.prefill_statistics(Qu, Ku, Vu, length, scale, recency_window, recency_bias, want_out, row_block)
-    res = orc.compress_from_statistics(full, Ku, Vu, length, budget, scope)
+    res = orc.compress_from_statistics(full, Ku, Vu, length, budget, scope, policy=policy)
     n = min(length, budget)
     assert int(g["n_used"][u]) == n, f"unit {u}: n_used {g['n_used'][u]} != {n}"
     gpos = g["pos"][u]
@@ -139,17 +146,18 @@ def check_prefill_unit(g: dict, u: int, Qu, Ku, Vu, length: int, budget: int, sc
     if length > budget:
         ties.prefill_decisions += 1
         if not np.array_equal(gpos[:n], res.retained):
-            mas = orc.mean_attention_score(res.full.acc, res.full.count)
-            var = orc.attention_variance(res.full.acc, res.full.acc2, res.full.count)
-            eps_m, eps_v = tie_band.bands(res.full.acc, res.full.acc2, res.full.count)
+            mas, var, s_eff = orc.ranking_scores(policy, res.full.acc, res.full.acc2, res.full.count,
+                                                 np.arange(length), scope)
+            eps_m, eps_v = tie_band.bands_for(policy, res.full.acc, res.full.acc2, res.full.count)
             keep = np.zeros(length, bool)
             keep[gpos[:n]] = True
-            ok, why = tie_band.admissible_eviction(mas, var, eps_m, eps_v, scope, length - budget,
+            ok, why = tie_band.admissible_eviction(mas, var, eps_m, eps_v, s_eff, length - budget,
                                                    np.flatnonzero(~keep))
             diff = sorted(set(gpos[:n].tolist()) ^ set(res.retained.tolist()))
             assert ok, f"unit {u}: retained set differs outside the tie band ({why}); differing positions {diff[:10]}"
             ties.prefill_ties += 1
-            res = orc.compress_from_statistics(full, Ku, Vu, length, budget, scope, force_retained=gpos[:n])
+            res = orc.compress_from_statistics(full, Ku, Vu, length, budget, scope, force_retained=gpos[:n],
+                                               policy=policy)
     c = res.cache
     assert np.array_equal(gpos, c.pos)
     assert np.array_equal(g["stats"][u, 2], c.count), f"unit {u}: Count differs"
@@ -176,17 +184,18 @@ def gpu_decode_step(sess: GpuSession, q: np.ndarray, k: np.ndarray, v: np.ndarra
 
 def lockstep_decode_unit(state: "orc.CacheState", u: int, g_out, g_slot, g_pos, q, k, v, qpos: int, scope: int,
                          scale: float, dtype: str, recency_window: int = 0, recency_bias: float = 0.0,
-                         what: str = "") -> TieCount:
+                         what: str = "", policy=None) -> TieCount:
     """Advance the oracle state of unit `u` by one step and compare with the library's step."""
     ties = TieCount()
     full = state.n_used == state.budget
     snapshot = state.copy() if full else None
-    r = orc.decode_step(state, q, k, v, qpos, scope, scale, recency_window, recency_bias)
+    r = orc.decode_step(state, q, k, v, qpos, scope, scale, recency_window, recency_bias, policy=policy)
     if full:
         ties.decode_decisions += 1
         if int(g_slot[u]) != r.evicted_slot:
-            eps_m, eps_v = tie_band.bands(snapshot.acc, snapshot.acc2, snapshot.count)
-            ok, why = tie_band.admissible_eviction(r.mas, r.var, eps_m, eps_v, scope, 1, [int(g_slot[u])])
+            eps_m, eps_v = tie_band.bands_for(policy, snapshot.acc, snapshot.acc2, snapshot.count)
+            s_eff = state.budget if policy is not None and policy.scope_kind == "all" else scope
+            ok, why = tie_band.admissible_eviction(r.mas, r.var, eps_m, eps_v, s_eff, 1, [int(g_slot[u])])
             assert ok, f"{what} unit {u}: victim slot {int(g_slot[u])} vs oracle {r.evicted_slot} outside the tie band ({why})"
             ties.decode_ties += 1
             # the oracle adopts the library's in-band choice: redo the step from the snapshot
@@ -194,7 +203,7 @@ def lockstep_decode_unit(state: "orc.CacheState", u: int, g_out, g_slot, g_pos, 
                 getattr(state, name)[...] = getattr(snapshot, name)
             state.n_used = snapshot.n_used
             r = orc.decode_step(state, q, k, v, qpos, scope, scale, recency_window, recency_bias,
-                                force_victim=int(g_slot[u]))
+                                force_victim=int(g_slot[u]), policy=policy)
     assert int(g_slot[u]) == r.evicted_slot, f"{what} unit {u}: evicted_slot {int(g_slot[u])} != {r.evicted_slot}"
     assert int(g_pos[u]) == r.evicted_pos, f"{what} unit {u}: evicted_pos {int(g_pos[u])} != {r.evicted_pos}"
     assert_out_close(g_out[u], r.out, dtype, f"{what} unit {u} out")
@@ -233,27 +242,28 @@ def gpu_encode_block(sess: GpuSession, block: int, q: np.ndarray, k: np.ndarray,
 
 def lockstep_block_unit(state: "orc.CacheState", u: int, g_out, g_slot, g_pos, q, k, v, qpos0: int, scope: int,
                         scale: float, dtype: str, recency_window: int = 0, recency_bias: float = 0.0,
-                        what: str = "") -> TieCount:
+                        what: str = "", policy=None) -> TieCount:
     """Advance the oracle state of unit `u` by one block and compare with the library's block step."""
     ties = TieCount()
     b = q.shape[0]
     n = state.n_used
     E = max(0, n + b - state.budget)
     snapshot = state.copy()
-    r = orc.encode_block(state, q, k, v, qpos0, scope, scale, recency_window, recency_bias)
+    r = orc.encode_block(state, q, k, v, qpos0, scope, scale, recency_window, recency_bias, policy=policy)
     g_ev = sorted(int(x) for x in g_slot[u] if x >= 0)
     if E > 0:
         ties.decode_decisions += 1
         if g_ev != sorted(int(x) for x in r.evicted_slot if x >= 0):
-            eps_m, eps_v = tie_band.bands(snapshot.acc[:n], snapshot.acc2[:n], snapshot.count[:n])
-            ok, why = tie_band.admissible_eviction(r.mas, r.var, eps_m, eps_v, scope, E, g_ev)
+            eps_m, eps_v = tie_band.bands_for(policy, snapshot.acc[:n], snapshot.acc2[:n], snapshot.count[:n])
+            s_eff = n if policy is not None and policy.scope_kind == "all" else scope
+            ok, why = tie_band.admissible_eviction(r.mas, r.var, eps_m, eps_v, s_eff, E, g_ev)
             assert ok, f"{what} unit {u}: evicted slots {g_ev} outside the tie band ({why})"
             ties.decode_ties += 1
             for name in ("K", "V", "acc", "acc2", "count", "pos"):
                 getattr(state, name)[...] = getattr(snapshot, name)
             state.n_used = snapshot.n_used
             r = orc.encode_block(state, q, k, v, qpos0, scope, scale, recency_window, recency_bias,
-                                 force_evicted=np.array(g_ev))
+                                 force_evicted=np.array(g_ev), policy=policy)
     assert np.array_equal(g_slot[u], r.evicted_slot), f"{what} unit {u}: evicted_slot {g_slot[u]} != {r.evicted_slot}"
     assert np.array_equal(g_pos[u], r.evicted_pos), f"{what} unit {u}: evicted_pos {g_pos[u]} != {r.evicted_pos}"
     for i in range(b):

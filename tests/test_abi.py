@@ -33,9 +33,26 @@ def test_library_loads_and_exports_every_declared_symbol():
 
 
 def test_params_struct_layout_matches_the_header():
-    assert ctypes.sizeof(roco.RocoParams) == 32
-    assert [f[0] for f in roco.RocoParams._fields_] == [
-        "units", "head_dim", "budget", "scope", "dtype", "scale", "recency_window", "recency_bias"]
+    assert ctypes.sizeof(roco.RocoParams) == 44
+    names = [f[0] for f in roco.RocoParams._fields_]
+    assert names == ["units", "head_dim", "budget", "scope", "dtype", "scale", "recency_window", "recency_bias",
+                     "importance", "scope_kind", "sinks"]
+    # the header declares the same members in the same order
+    text = open(os.path.join(ROOT, "include", "roco.h")).read()
+    body = re.sub(r"/\*.*?\*/", "", text[text.index("typedef struct roco_params"):text.index("} roco_params;")], flags=re.S)
+    assert re.findall(r"\b(?:int32_t|float)\s+(\w+)\s*;", body) == names
+
+
+def test_policy_fields_are_validated():
+    ok = roco.RocoParams(8, 128, 256, 16, roco.ROCO_BF16, importance=roco.ROCO_IMPORTANCE_OLDEST,
+                         scope_kind=roco.ROCO_SCOPE_ALL, sinks=4)
+    assert roco.decode_workspace_bytes(ok) > 0
+    for bad in (dict(importance=3), dict(importance=-1), dict(scope_kind=3), dict(sinks=-1)):
+        assert roco.decode_workspace_bytes(roco.RocoParams(8, 128, 256, 16, roco.ROCO_BF16, **bad)) == 0
+    lib = roco.load_library()
+    need = roco.decode_workspace_bytes(ok)
+    # a policy that ranks by position needs pos
+    assert lib.roco_select_victims(ctypes.byref(ok), 0x1000, None, 0x1000, 0x1000, 0x1000, need, None) == EINVAL
 
 
 def test_workspace_queries():

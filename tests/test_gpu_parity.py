@@ -25,7 +25,7 @@ def _parity():
 
 
 def run_workload(dtype, head_dim, units, lens, L_max, budget, scope, steps, seed, scale=0.0,
-                 recency_window=0, recency_bias=0.0, want_out=True, cfg=None, tag=""):
+                 recency_window=0, recency_bias=0.0, want_out=True, cfg=None, tag="", policy=None):
     """Prefill-compress then `steps` lock-step decode steps on `units` synthetic units; returns tie counts."""
     P = _parity()
     cfg = cfg or CONFIGS[0 if dtype == "f32" else 1]
@@ -47,14 +47,14 @@ def run_workload(dtype, head_dim, units, lens, L_max, budget, scope, steps, seed
         if dtype == "bf16":
             q, k, v = round_to_bf16(q), round_to_bf16(k), round_to_bf16(v)
         Q[u], K[u], V[u] = q, k, v
-    sess = P.make_session(units, head_dim, budget, scope, dtype, scale, recency_window, recency_bias)
+    sess = P.make_session(units, head_dim, budget, scope, dtype, scale, recency_window, recency_bias, policy=policy)
     print(f"[{tag}] prefill units={units} L_max={L_max} lens={list(lens)[:6]} B={budget} s={scope} {dtype} d={head_dim}", flush=True)
     g = P.gpu_prefill(sess, Q[:, :L_max].copy(), K[:, :L_max].copy(), V[:, :L_max].copy(), lens, want_out)
     ties = P.TieCount()
     states = []
     for u in range(units):
         res, t = P.check_prefill_unit(g, u, Q[u, :L_max], K[u, :L_max], V[u, :L_max], int(lens[u]), budget, scope,
-                                      sc, dtype, recency_window, recency_bias, want_out)
+                                      sc, dtype, recency_window, recency_bias, want_out, policy=policy)
         ties += t
         states.append(res.cache)
     next_pos = [int(l) for l in lens]
@@ -64,7 +64,7 @@ def run_workload(dtype, head_dim, units, lens, L_max, budget, scope, steps, seed
         for u in range(units):
             ties += P.lockstep_decode_unit(states[u], u, g_out, g_slot, g_pos, Q[u, t], K[u, t], V[u, t],
                                            next_pos[u], scope, sc, dtype, recency_window, recency_bias,
-                                           what=f"[{tag}] step {step}")
+                                           what=f"[{tag}] step {step}", policy=policy)
             assert states[u].n_used <= budget
         next_pos = [p + 1 for p in next_pos]
         if step % 16 == 15 or step == steps - 1:
@@ -188,7 +188,7 @@ def test_select_victims_entry_point_reproduces_the_maintained_hint():
     for step in range(6):
         c = sess.cache
         fresh = torch.full((units,), -5, dtype=torch.int32, device="cuda")
-        roco.roco_select_victims(sess.params, c.stats, c.n_used, fresh, sess.decode_ws)
+        roco.roco_select_victims(sess.params, c.stats, c.pos, c.n_used, fresh, sess.decode_ws)
         torch.cuda.synchronize()
         full = (c.n_used == B).cpu().numpy()
         got, kept = fresh.cpu().numpy(), c.next_slot.cpu().numpy()

@@ -534,3 +534,22 @@ def encode_block_gqa(state: CacheState, Qb, Kb, Vb, qpos0: int, scope: int, scal
         state.acc2[:n_new] += means[i] * means[i]
         state.count[:n_new] += (block_index[:n_new] <= i).astype(F64)
     return GroupBlockResult(out, means, targets, evicted_slot, evicted_pos, mas, var)
+
+
+# ---------------------------------------------------------------------------
+# which tokens a smaller budget would keep (the sets compared in section 4.1's consistency study)
+# ---------------------------------------------------------------------------
+
+def select_retained(state: CacheState, keep: int, scope: int, policy: Optional[Policy] = None) -> np.ndarray:
+    """Boolean mask over the slots: the cached tokens that survive one eviction step shrinking the cache to
+    `keep` tokens (n_used - keep evictions with the statistics as they stand; nothing is changed).
+
+    With scope "all" these are the `keep` most important cached tokens: the "top-B important tokens" whose
+    overlap between a budgeted and a full cache section 4.1 measures (Jaccard similarity)."""
+    n = state.n_used
+    mask = np.zeros(state.budget, dtype=bool)
+    mask[:n] = True
+    if n > keep:
+        imp, key, s_eff = ranking_scores(policy, state.acc[:n], state.acc2[:n], state.count[:n], state.pos[:n], scope)
+        mask[select_evictions(imp, key, s_eff, n - keep)] = False
+    return mask

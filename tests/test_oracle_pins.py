@@ -618,3 +618,16 @@ def test_default_policy_is_roco_and_block_steps_accept_a_policy():
         orc.decode_step(c, Q[t], K[t], V[t], t, s, 0.5, policy=pol)
     orc.encode_block(e, Q[L:L + 6], K[L:L + 6], V[L:L + 6], L, s, 0.5, policy=pol)
     assert sorted(c.pos) == sorted(e.pos) == [0, 1] + list(range(L + 6 - 8, L + 6))
+
+
+def test_shrinking_a_dense_cache_keeps_what_prefill_compress_keeps():
+    rng = np.random.default_rng(61)
+    L, d, s = 40, 4, 6
+    Q, K, V = rand_unit(rng, L, d)
+    for pol in (None, orc.Policy("aas", "all"), orc.Policy("mas", "window"), orc.Policy("oldest", "all", 3)):
+        dense = orc.prefill_compress(Q, K, V, L, L + 5, s, 0.5, policy=pol).cache
+        for keep in (1, 13, 39, 40, 60):
+            mask = orc.select_retained(dense, keep, s, pol)
+            want = orc.prefill_compress(Q, K, V, L, keep, s, 0.5, policy=pol).retained
+            assert np.array_equal(dense.pos[mask], want) and mask.sum() == min(keep, L)
+        assert not mask[L:].any()  # empty slots are never reported

@@ -106,6 +106,7 @@ def main():
     ap.add_argument("--cpu-steps", type=int, default=512)
     ap.add_argument("--with-out", action="store_true", help="also produce the prefill attention output O")
     ap.add_argument("--no-blockwise", action="store_true", help="skip the block-wise evict-and-encode table")
+    ap.add_argument("--no-consistency", action="store_true", help="skip the synthetic consistency study")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 512 MiB device copy (a kernel of known traffic, to scale rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -361,6 +362,23 @@ def main():
                                       "by_block_size": blockwise}
         result["gqa_decode"] = {"workload": f"one token per step on the full B={B} cache, 32 query heads over 32/g "
                                             "key/value heads (roco_decode_step_gqa), batch 16", "by_group_size": gqa}
+    if not args.no_consistency:
+        # section 4.1's consistency study on this workload's generator (32 heads of sequence 0, 256-token prompt,
+        # 256 generated tokens): Jaccard similarity between what a budgeted cache holds and the top-B tokens of
+        # the same importance score with the full cache, scope = whole cache
+        from inputs import make_unit, unit_ids
+        from paper_2402_06262_amd.consistency import consistency_study
+        ids = unit_ids(cfg)[:32]
+        small = [make_unit(cfg, *i, seed=args.seed, total_len=512) for i in ids]
+        cq, ck, cv = (upload(np.stack([getattr(u_, n_) for u_ in small]), torch, dt) for n_ in ("Q", "K", "V"))
+        t0c = time.perf_counter()
+        study = consistency_study(cq, ck, cv, prompt_len=256, rates=(0.3, 0.4, 0.5, 0.6), importances=("mas", "aas"))
+        result["consistency_synthetic"] = {
+            "workload": "32 units of this workload's generator, 256-token prompt + 256 generated tokens, budget = "
+                        "rate x 512, scope = whole cache, every 8th position",
+            "jaccard_vs_full_cache": {k_: {str(r_): round(v_[0], 4) for r_, v_ in d_.items()} for k_, d_ in study.items()},
+            "seconds": round(time.perf_counter() - t0c, 2)}
+        del cq, ck, cv
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, Q, K, V, decode_steps, args.cpu_units, args.cpu_steps)
     print(json.dumps(result), flush=True)

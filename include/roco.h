@@ -226,6 +226,19 @@ int roco_select_victims(const roco_params* params, const float* stats, const int
                         int32_t* next_slot, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Which cached tokens a smaller budget would keep (the sets compared by the consistency study of section 4.1,
+ * Fig. 2: the top-B important tokens under a policy): mask[u][j] = 1 if slot j of unit u survives one eviction
+ * step that shrinks the unit to `keep` tokens (n_used - keep evictions by the params' policy with the statistics
+ * as they stand: among the scope + E - 1 slots of lowest scope key, the E of lowest importance), else 0; empty
+ * slots get 0; units with n_used <= keep keep everything.  Nothing but mask is written.
+ * stats in [units,3,B], pos in [units,B] (may be NULL unless the policy ranks by position), n_used in [units],
+ * mask out [units,B] int32; the workspace is the decode workspace.
+ */
+int roco_select_retained(const roco_params* params, int32_t keep, const float* stats, const int32_t* pos,
+                         const int32_t* n_used, int32_t* mask, void* workspace, size_t workspace_bytes,
+                         void* hip_stream);
+
+/*
  * Profiling aid (not part of the method; for benchmarks).  roco_profile_kernel(k) makes every later call
  * record a pair of HIP events on the caller's stream around kernel k only (k = one of ROCO_PROF_*; -1 turns
  * it off).  roco_profile_read() waits for the recorded events, returns their summed elapsed time in

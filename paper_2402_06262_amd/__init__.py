@@ -32,6 +32,7 @@ from .binding import (  # noqa: F401
     roco_profile_kernel,
     roco_profile_read,
     roco_profile_sampling,
+    roco_select_retained,
     roco_select_victims,
     roco_strerror,
     roco_version,

@@ -89,6 +89,8 @@ def load_library() -> ctypes.CDLL:
     lib.roco_decode_step_gqa.argtypes = [pp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.roco_select_victims.restype = ctypes.c_int
     lib.roco_select_victims.argtypes = [pp, vp, vp, vp, vp, vp, sz, vp]
+    lib.roco_select_retained.restype = ctypes.c_int
+    lib.roco_select_retained.argtypes = [pp, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.roco_strerror.restype = ctypes.c_char_p
     lib.roco_strerror.argtypes = [ctypes.c_int]
     lib.roco_version.restype = ctypes.c_int
@@ -267,6 +269,17 @@ def roco_select_victims(params: RocoParams, stats, pos, n_used, next_slot, works
                                             _ptr(workspace), int(workspace_bytes), _stream(stream))
     if rc != 0:
         raise RocoError(rc, "roco_select_victims")
+
+
+def roco_select_retained(params: RocoParams, keep: int, stats, pos, n_used, mask, workspace,
+                         workspace_bytes: Optional[int] = None, stream=None) -> None:
+    """See include/roco.h: mask of the tokens that survive a shrink of every unit to `keep` tokens."""
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    rc = load_library().roco_select_retained(ctypes.byref(params), int(keep), _ptr(stats), _ptr(pos), _ptr(n_used),
+                                             _ptr(mask), _ptr(workspace), int(workspace_bytes), _stream(stream))
+    if rc != 0:
+        raise RocoError(rc, "roco_select_retained")
 
 
 @dataclass

@@ -290,6 +290,29 @@ int roco_decode_step_gqa(const roco_params* params, int32_t group, const void* q
                    evicted_slot, evicted_pos, workspace, workspace_bytes, hip_stream);
 }
 
+int roco_select_retained(const roco_params* params, int32_t keep, const float* stats, const int32_t* pos,
+                         const int32_t* n_used, int32_t* mask, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+  const int rc = check_params(params);
+  if (rc != ROCO_OK) return rc;
+  if (keep < 0) return ROCO_EINVAL;
+  if (policy_of(params).needs_pos() && pos == nullptr) return ROCO_EINVAL;
+  const void* need[] = {stats, n_used, mask, workspace};
+  for (const void* ptr : need)
+    if (ptr == nullptr || !aligned16(ptr)) return ROCO_EINVAL;
+  const DecodeLayout lay = decode_layout(params);
+  if (workspace_bytes < lay.total) return ROCO_EWORKSPACE;
+  DecodeArgs a = {};
+  a.units = params->units; a.B = params->budget; a.scope = params->scope;
+  a.pol = policy_of(params);
+  a.pos = const_cast<int32_t*>(pos);
+  a.stats = const_cast<float*>(stats);
+  a.n_used = const_cast<int32_t*>(n_used);
+  a.keys = reinterpret_cast<uint32_t*>(static_cast<char*>(workspace) + lay.keys);
+  const hipError_t e = launch_select_retained(a, keep, mask, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
+}
+
 int roco_select_victims(const roco_params* params, const float* stats, const int32_t* pos, const int32_t* n_used,
                         int32_t* next_slot, void* workspace, size_t workspace_bytes, void* hip_stream) {
   const int rc = check_params(params);

@@ -143,7 +143,46 @@ __global__ __launch_bounds__(kGatherThreads) void prefill_gather(PrefillArgs a) 
   }
 }
 
+// Which cached tokens survive one eviction step that shrinks a unit to `keep` tokens: the closed form of the
+// rule above on the statistics as they stand, nothing modified.  mask[u][j] = 1 for survivors, 0 for victims and
+// for empty slots.
+__global__ __launch_bounds__(kSelThreads) void select_retained(DecodeArgs a, int keep, int32_t* mask_out) {
+  constexpr int NT = kSelThreads;
+  extern __shared__ uint32_t lds_keys[];  // [2][B] when B <= kMaxDecodeBudgetLds
+  __shared__ uint32_t sel_sh[kSelectLdsWords];
+  const int u = blockIdx.x, tid = threadIdx.x;
+  const int B = a.B;
+  const int n = min(a.n_used[u], B);
+  const float* acc = a.stats + static_cast<size_t>(u) * 3 * B;
+  const float* acc2 = acc + B;
+  const float* cnt = acc2 + B;
+  const int32_t* pos = a.pos + static_cast<size_t>(u) * B;
+  int32_t* mask = mask_out + static_cast<size_t>(u) * B;
+  uint32_t* var_key = (B <= kMaxDecodeBudgetLds) ? lds_keys : a.keys + static_cast<size_t>(u) * 2 * B;
+  uint32_t* mas_key = var_key + B;
+  if (n <= keep) {
+    for (int i = tid; i < B; i += NT) mask[i] = i < n ? 1 : 0;
+    return;
+  }
+  const uint32_t E = static_cast<uint32_t>(n - keep);
+  const uint32_t m = min(static_cast<uint32_t>(n), static_cast<uint32_t>(a.pol.scope_size(a.scope, n)) + E - 1u);
+  const bool by_pos = a.pol.needs_pos();
+  for (int i = tid; i < n; i += NT)
+    ranking_keys(acc[i], acc2[i], cnt[i], by_pos ? pos[i] : 0, a.pol, mas_key[i], var_key[i]);
+  __syncthreads();
+  const KSmallest scope = select_k_smallest<NT>([&](int i) { return var_key[i]; }, n, m, sel_sh);
+  auto key2 = [&](int i) -> uint32_t { return scope.has(var_key[i], i) ? mas_key[i] : 0xffffffffu; };
+  const KSmallest out = select_k_smallest<NT>(key2, n, E, sel_sh);
+  for (int i = tid; i < B; i += NT) mask[i] = (i < n && !out.has(key2(i), i)) ? 1 : 0;
+}
+
 }  // namespace
+
+hipError_t launch_select_retained(const DecodeArgs& a, int keep, int32_t* mask, hipStream_t s) {
+  const size_t lds = (a.B <= kMaxDecodeBudgetLds) ? static_cast<size_t>(a.B) * 2 * sizeof(uint32_t) : 0;
+  hipLaunchKernelGGL(select_retained, dim3(a.units), dim3(kSelThreads), lds, s, a, keep, mask);
+  return hipGetLastError();
+}
 
 hipError_t launch_prefill_select_compact(int dtype, int head_dim, const PrefillArgs& a, hipStream_t s) {
   {

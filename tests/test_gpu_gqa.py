@@ -76,6 +76,44 @@ def test_grouped_steps_with_recency_bias_and_a_larger_budget():
     drive(2, 1024, 48, 4, [8] * 130 + [1] * 8, seed=97, recency=True, tag="gqa-recency", single_token_entry=True)
 
 
+def test_grouped_decode_at_the_serving_shape():
+    """The shape bench.py times for g = 4: 128 key/value heads (batch 16 x 8), B = 2048, scope 64, full cache.
+    All units step on the GPU; properties on every unit, the oracle in lock-step on a sample."""
+    import paper_2402_06262_amd as roco
+    P = _P()
+    U, B, s, g, d, L, steps = 128, 2048, 64, 4, 128, 2100, 6
+    sc = 1.0 / math.sqrt(d)
+    rng = np.random.default_rng(123)
+    sample = [0, 57, 127]
+    Qp = round_to_bf16(rng.standard_normal((U, L, d)).astype(np.float32) + 0.25)
+    K = round_to_bf16(rng.standard_normal((U, L + steps, d)).astype(np.float32))
+    V = round_to_bf16(rng.standard_normal((U, L + steps, d)).astype(np.float32))
+    Qg = round_to_bf16(rng.standard_normal((U, steps, g, d)).astype(np.float32) + 0.25)
+    sess = P.make_session(U, d, B, s, "bf16")
+    gp = P.gpu_prefill(sess, Qp, K[:, :L].copy(), V[:, :L].copy(), [L] * U, False)  # a valid full cache to start from
+    states = {u: P.check_prefill_unit(gp, u, Qp[u], K[u, :L], V[u, :L], L, B, s, sc, "bf16", 0, 0.0, False)[0].cache
+              for u in sample}
+    ws = torch.empty(roco.block_workspace_bytes(sess.params, 1), dtype=torch.uint8, device="cuda")
+    ties = P.TieCount()
+    for i in range(steps):
+        t = L + i
+        acc_before = sess.cache.stats[:, 0].double().sum(1)
+        o, es, ep = P.gpu_decode_step_gqa(sess, g, Qg[:, i], K[:, t], V[:, t], [t] * U, ws)
+        assert np.all(es >= 0) and np.all(es < B) and np.isfinite(o).all()
+        c = sess.cache
+        assert bool((torch.gather(c.pos, 1, torch.from_numpy(es).cuda().long()[:, None])[:, 0] == t).all())
+        for u in sample:
+            victim_acc = states[u].acc[int(es[u])]
+            ties += P.lockstep_block_gqa_unit(states[u], u, o[:, None], es[:, None], ep[:, None], Qg[u, i][None],
+                                              K[u, t:t + 1], V[u, t:t + 1], t, s, sc, "bf16", what=f"[gqa-serving] step {i}")
+            inc = float(c.stats[u, 0].double().sum() - acc_before[u]) + victim_acc
+            assert abs(inc - 1.0) < 2e-3  # the head-mean probabilities of a step sum to one
+    host = P.cache_to_host(sess)
+    for u in sample:
+        P.check_cache_unit({k: v[[u]] for k, v in host.items()}, 0, states[u], what="[gqa-serving] end")
+    print(f"[gqa-serving] ties {ties}", flush=True)
+
+
 def test_group_of_one_matches_the_token_wise_decode_step_bit_for_bit_in_its_decisions():
     """roco_decode_step_gqa with one head and roco_decode_step on identical inputs: same victims, same positions;
     statistics and outputs within the parity tolerances (different kernels, different summation order)."""

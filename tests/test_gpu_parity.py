@@ -149,6 +149,14 @@ def test_larger_budget_many_splits_bf16():
                  tag="b2048")
 
 
+def test_budgets_between_2048_and_the_lds_limit():
+    """2048 < B <= 4096: the one-workgroup step loads part of the statistics after the stream, and keeps 12 bytes
+    per slot in LDS; once with B a multiple of four (128-bit statistics accesses), once not (scalar accesses)."""
+    run_workload("bf16", 128, 2, [3300, 3000], 3300, 3000, 50, 5, seed=23, want_out=False, tag="b3000")
+    run_workload("f32", 64, 2, [2600, 2502], 2600, 2502, 40, 4, seed=24, want_out=False, tag="b2502")
+    run_workload("bf16", 64, 1, [4200], 4200, 4096, 64, 3, seed=25, want_out=False, tag="b4096")
+
+
 def test_exact_ties_go_to_the_lowest_index():
     """Duplicate tokens (identical k, and queries that cannot tell them apart) give bit-identical statistics
     on both sides only if accumulation orders agree, so this checks validity instead: with all-zero queries

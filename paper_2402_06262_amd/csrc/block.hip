@@ -123,8 +123,8 @@ __device__ __forceinline__ void kv_load(StagedKV& s, const char* Kb, const char*
     int row = row0 + (t >> 4) + 8 * i;
     row = row < last_row ? row : last_row;  // slots past the end are masked by the caller
     const size_t off = static_cast<size_t>(row) * kRowBytes + (t & 15) * 16;
-    s.k[i] = load16(Kb + off);
-    s.v[i] = load16(Vb + off);
+    s.k[i] = kStreamingLoads ? load16_streaming(Kb + off) : load16(Kb + off);
+    s.v[i] = kStreamingLoads ? load16_streaming(Vb + off) : load16(Vb + off);
   }
 }
 __device__ __forceinline__ void kv_store(const StagedKV& s, char* tileK, char* tileV) {

@@ -461,8 +461,8 @@ __global__ __launch_bounds__(kAttendThreads) void cache_read_probe(DecodeArgs a)
     for (int i = 0; i < U; ++i) {
       const int row = base + i * R + g;
       const size_t off = static_cast<size_t>(row < row1 ? row : row0) * ROW_BYTES + c * 16;
-      kw[i] = load16(Kb + off);
-      vw[i] = load16(Vb + off);
+      kw[i] = kStreamingLoads ? load16_streaming(Kb + off) : load16(Kb + off);
+      vw[i] = kStreamingLoads ? load16_streaming(Vb + off) : load16(Vb + off);
     }
 #pragma unroll
     for (int i = 0; i < U; ++i)

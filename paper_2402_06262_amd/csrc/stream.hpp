@@ -9,6 +9,8 @@
 
 namespace roco {
 
+constexpr bool kStreamingLoads = true;  // K / V rows are touched once per step
+
 template <int DT, int D> struct RowGeom {
   static constexpr int EPL = Elem<DT>::per16;  // elements per lane
   static constexpr int LPR = D / EPL;          // lanes per row
@@ -63,7 +65,7 @@ __device__ __forceinline__ void stream_attend(const float* qf, const char* Kbase
     for (int u = 0; u < U; ++u) {
       const int row = base + u * G::R + g;
       const size_t off = static_cast<size_t>(row < row_end ? row : row_begin) * G::ROW_BYTES + c * 16;
-      w[u] = load16(base_ptr + off);
+      w[u] = kStreamingLoads ? load16_streaming(base_ptr + off) : load16(base_ptr + off);
     }
   };
   auto is_plain = [&](int base) {

@@ -138,8 +138,8 @@ __global__ __launch_bounds__(kGatherThreads) void prefill_gather(PrefillArgs a) 
     if (p < 0 || p >= n) continue;  // never read outside the prompt, whatever pos[] holds
     const size_t src = static_cast<size_t>(p) * ROW_BYTES + c * 16;
     const size_t dst = static_cast<size_t>(slot) * ROW_BYTES + c * 16;
-    *reinterpret_cast<uint4*>(Kout + dst) = load16(Kin + src);
-    *reinterpret_cast<uint4*>(Vout + dst) = load16(Vin + src);
+    *reinterpret_cast<uint4*>(Kout + dst) = load16_streaming(Kin + src);  // prompt rows are not needed again
+    *reinterpret_cast<uint4*>(Vout + dst) = load16_streaming(Vin + src);
   }
 }
 

@@ -55,16 +55,11 @@ template <> __device__ __forceinline__ void store_elem<kBF16>(void* base, size_t
 }
 
 __device__ __forceinline__ uint4 load16(const void* p) { return *static_cast<const uint4*>(p); }
-// Streaming variants: data that is touched once per kernel and should not displace what the caches hold.
-typedef float float4_vec __attribute__((ext_vector_type(4)));
+// Streaming variant: data that is touched once per kernel and should not displace what the caches hold.
 typedef uint32_t uint4_vec __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 load16_streaming(const void* p) {
   const uint4_vec v = __builtin_nontemporal_load(static_cast<const uint4_vec*>(p));
   return make_uint4(v.x, v.y, v.z, v.w);
-}
-__device__ __forceinline__ void store_streaming(float* p, const float4 v) {
-  float4_vec x = {v.x, v.y, v.z, v.w};
-  __builtin_nontemporal_store(x, reinterpret_cast<float4_vec*>(p));
 }
 
 // ---------------------------------------------------------------- cross-lane

@@ -216,9 +216,9 @@ __device__ __forceinline__ void update_statistics(float* acc, float* acc2, float
         if (j < n) {
           update_four(ahead->a1[k], ahead->a2[k], ahead->cc[k], *reinterpret_cast<const float4*>(z + j), j, n, slot, M,
                       inv, full, mas_key, var_key, sk);
-          store_streaming(acc + j, ahead->a1[k]);
-          store_streaming(acc2 + j, ahead->a2[k]);
-          store_streaming(cnt + j, ahead->cc[k]);
+          *reinterpret_cast<float4*>(acc + j) = ahead->a1[k];
+          *reinterpret_cast<float4*>(acc2 + j) = ahead->a2[k];
+          *reinterpret_cast<float4*>(cnt + j) = ahead->cc[k];
         }
       }
     }

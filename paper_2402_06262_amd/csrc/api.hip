@@ -11,6 +11,7 @@ namespace {
 using namespace roco;
 
 constexpr size_t kAlign = 256;
+constexpr int kStreamingAboveMiB = 192;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -107,6 +108,17 @@ void choose_splits(const roco_params* p, int unroll, int& splits, int& rows_per_
 
 // One workgroup per unit once there are enough units to keep the chip streaming (measured on B = 2048, bf16,
 // d = 128: ahead of the split path from 64 units on, behind it at 32 and 40).
+// Whether the K / V rows are read with the non-temporal hint.  Measured (B = 2048, bf16, d = 128): a cache of up to
+// about 160 MiB is partly found again in the chip's last-level cache by the next step when loaded normally (31 vs 34
+// us at 128 units); from 256 MiB on it only thrashes that cache and displaces the statistics (75 vs 69 us at 320
+// units, 106 vs 92 us at 512).
+bool streaming_loads(const roco_params* p) {
+  const int want = env_int("ROCO_STREAMING_LOADS", -1);
+  if (want >= 0) return want != 0;
+  const size_t row = static_cast<size_t>(p->head_dim) * (p->dtype == ROCO_BF16 ? 2 : 4);
+  return static_cast<size_t>(p->units) * p->budget * row * 2 > (static_cast<size_t>(kStreamingAboveMiB) << 20);
+}
+
 bool decode_is_fused(const roco_params* p) {
   const int want = env_int("ROCO_DECODE_FUSED", -1);
   return (want < 0 ? p->units >= 64 : want != 0) && p->budget <= kMaxDecodeBudgetLds;
@@ -194,6 +206,7 @@ int roco_decode_step(const roco_params* params, const void* q, const void* k_new
   a.rotate = env_int("ROCO_DECODE_ROTATE", 1);
   choose_splits(params, a.unroll, a.splits, a.rows_per_split);
   a.fused = decode_is_fused(params) ? 1 : 0;
+  a.streaming = streaming_loads(params) ? 1 : 0;
   a.scale_log2 = scale_log2(params);
   a.recency_window = params->recency_window;
   a.recency_bias_log2 = params->recency_bias * 1.4426950408889634f;
@@ -235,6 +248,7 @@ int run_block(const roco_params* params, int tokens, int heads, const void* q, c
   a.units = params->units; a.B = params->budget; a.scope = params->scope;
   a.pol = policy_of(params);
   a.block = tokens; a.heads = heads; a.queries = tokens * heads;
+  a.streaming = streaming_loads(params) ? 1 : 0;
   {  // split the budget into 64-slot-aligned ranges: two resident workgroups per compute unit measured best
     // (more splits cost more partial results to write and merge than they gain in balance)
     int want = env_int("ROCO_BLOCK_SPLITS", 0);
@@ -346,6 +360,7 @@ int roco_probe_cache_read(const roco_params* params, const void* K_cache, const 
   if (workspace_bytes < lay.total) return ROCO_EWORKSPACE;
   DecodeArgs a = {};
   a.units = params->units; a.B = params->budget;
+  a.streaming = streaming_loads(params) ? 1 : 0;
   choose_splits(params, 8, a.splits, a.rows_per_split);
   a.K = const_cast<void*>(K_cache); a.V = const_cast<void*>(V_cache);
   a.part_m = reinterpret_cast<float*>(static_cast<char*>(workspace) + lay.part_m);

@@ -116,6 +116,7 @@ __global__ __launch_bounds__(kPrepThreads) void block_prepare(BlockArgs a) {
 struct StagedKV {
   uint4 k[8], v[8];  // this thread's 128 bytes of a 64 x 256 B tile of K and of V (128 threads)
 };
+template <bool STREAMING>
 __device__ __forceinline__ void kv_load(StagedKV& s, const char* Kb, const char* Vb, int row0, int last_row) {
   const int t = threadIdx.x;
 #pragma unroll
@@ -123,8 +124,8 @@ __device__ __forceinline__ void kv_load(StagedKV& s, const char* Kb, const char*
     int row = row0 + (t >> 4) + 8 * i;
     row = row < last_row ? row : last_row;  // slots past the end are masked by the caller
     const size_t off = static_cast<size_t>(row) * kRowBytes + (t & 15) * 16;
-    s.k[i] = kStreamingLoads ? load16_streaming(Kb + off) : load16(Kb + off);
-    s.v[i] = kStreamingLoads ? load16_streaming(Vb + off) : load16(Vb + off);
+    s.k[i] = STREAMING ? load16_streaming(Kb + off) : load16(Kb + off);
+    s.v[i] = STREAMING ? load16_streaming(Vb + off) : load16(Vb + off);
   }
 }
 __device__ __forceinline__ void kv_store(const StagedKV& s, char* tileK, char* tileV) {
@@ -185,7 +186,8 @@ __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
   auto tile_row = [&](int t) { return row0 + (t + rot < n_tiles ? t + rot : t + rot - n_tiles) * kTile; };
   auto fetch = [&](int t) {
     const int tr0 = tile_row(t);
-    kv_load(st, Kb, Vb, tr0, n - 1);
+    if (a.streaming) kv_load<true>(st, Kb, Vb, tr0, n - 1);
+    else kv_load<false>(st, Kb, Vb, tr0, n - 1);
     if (tid < kTile) {
       const int slot = min(tr0 + tid, n - 1);
       st_bidx = bidx[slot];

@@ -117,11 +117,14 @@ __global__ __launch_bounds__(kAttendThreads) void decode_attend(DecodeArgs a) {
                                                 static_cast<unsigned>(passes))
                              : 0;
   if (w > 0)
-    stream_attend<DT, D, U, true>(qf, Kb, Vb, row0, row1, passes, a.rotate ? rot : 0, PASS, wave * (U * G::R), bias, z,
-                                  slot, fix_k, fix_v, st);
+    stream_attend<DT, D, U, true, false>(qf, Kb, Vb, row0, row1, passes, a.rotate ? rot : 0, PASS, wave * (U * G::R),
+                                         bias, z, slot, fix_k, fix_v, st);
+  else if (a.streaming)
+    stream_attend<DT, D, U, false, true>(qf, Kb, Vb, row0, row1, passes, a.rotate ? rot : 0, PASS, wave * (U * G::R),
+                                         bias, z, slot, fix_k, fix_v, st);
   else
-    stream_attend<DT, D, U, false>(qf, Kb, Vb, row0, row1, passes, a.rotate ? rot : 0, PASS, wave * (U * G::R), bias, z,
-                                   slot, fix_k, fix_v, st);
+    stream_attend<DT, D, U, false, false>(qf, Kb, Vb, row0, row1, passes, a.rotate ? rot : 0, PASS, wave * (U * G::R),
+                                          bias, z, slot, fix_k, fix_v, st);
   merge_groups_in_wave<DT, D>(st);
 
   if (lane < G::LPR) {
@@ -374,9 +377,14 @@ __global__ __launch_bounds__(kFusedThreads) void decode_fused(DecodeArgs a) {
   const int passes = (n + PASS - 1) / PASS;
   const int rot = a.rotate ? static_cast<int>((static_cast<unsigned>(u) * 5u) % static_cast<unsigned>(passes)) : 0;
   if (w > 0)
-    stream_attend<DT, D, U, true>(qf, Kb, Vb, 0, n, passes, rot, PASS, wave * (U * G::R), bias, z, slot, fix_k, fix_v, st);
+    stream_attend<DT, D, U, true, false>(qf, Kb, Vb, 0, n, passes, rot, PASS, wave * (U * G::R), bias, z, slot, fix_k,
+                                         fix_v, st);
+  else if (a.streaming)
+    stream_attend<DT, D, U, false, true>(qf, Kb, Vb, 0, n, passes, rot, PASS, wave * (U * G::R), bias, z, slot, fix_k,
+                                         fix_v, st);
   else
-    stream_attend<DT, D, U, false>(qf, Kb, Vb, 0, n, passes, rot, PASS, wave * (U * G::R), bias, z, slot, fix_k, fix_v, st);
+    stream_attend<DT, D, U, false, false>(qf, Kb, Vb, 0, n, passes, rot, PASS, wave * (U * G::R), bias, z, slot, fix_k,
+                                          fix_v, st);
   merge_groups_in_wave<DT, D>(st);
 
   if (lane < G::LPR) {
@@ -444,7 +452,7 @@ __global__ __launch_bounds__(kFinishThreads) void select_victims(DecodeArgs a) {
 // Benchmark aid: the memory side of decode_attend alone.  Same grid, same rows per workgroup, same 128-bit
 // loads in the same order, no arithmetic beyond an xor that keeps the loads alive: what this kernel reaches is
 // the read bandwidth the access pattern can get on the machine at hand.
-template <int ROW_BYTES, int U>
+template <int ROW_BYTES, int U, bool STREAMING>
 __global__ __launch_bounds__(kAttendThreads) void cache_read_probe(DecodeArgs a) {
   constexpr int LPR = ROW_BYTES / 16, R = kWave / LPR, PASS = kAttendWaves * U * R;
   const int u = blockIdx.y, split = blockIdx.x;
@@ -461,8 +469,8 @@ __global__ __launch_bounds__(kAttendThreads) void cache_read_probe(DecodeArgs a)
     for (int i = 0; i < U; ++i) {
       const int row = base + i * R + g;
       const size_t off = static_cast<size_t>(row < row1 ? row : row0) * ROW_BYTES + c * 16;
-      kw[i] = kStreamingLoads ? load16_streaming(Kb + off) : load16(Kb + off);
-      vw[i] = kStreamingLoads ? load16_streaming(Vb + off) : load16(Vb + off);
+      kw[i] = STREAMING ? load16_streaming(Kb + off) : load16(Kb + off);
+      vw[i] = STREAMING ? load16_streaming(Vb + off) : load16(Vb + off);
     }
 #pragma unroll
     for (int i = 0; i < U; ++i)
@@ -521,9 +529,18 @@ hipError_t launch_cache_read_probe(int dtype, int head_dim, const DecodeArgs& a,
   const dim3 grid(a.splits, a.units);
   ProfScope ps(kProfReadProbe, s);
   switch (row_bytes) {
-    case 128: hipLaunchKernelGGL((cache_read_probe<128, 8>), grid, dim3(kAttendThreads), 0, s, a); break;
-    case 256: hipLaunchKernelGGL((cache_read_probe<256, 8>), grid, dim3(kAttendThreads), 0, s, a); break;
-    case 512: hipLaunchKernelGGL((cache_read_probe<512, 8>), grid, dim3(kAttendThreads), 0, s, a); break;
+    case 128:
+      if (a.streaming) hipLaunchKernelGGL((cache_read_probe<128, 8, true>), grid, dim3(kAttendThreads), 0, s, a);
+      else hipLaunchKernelGGL((cache_read_probe<128, 8, false>), grid, dim3(kAttendThreads), 0, s, a);
+      break;
+    case 256:
+      if (a.streaming) hipLaunchKernelGGL((cache_read_probe<256, 8, true>), grid, dim3(kAttendThreads), 0, s, a);
+      else hipLaunchKernelGGL((cache_read_probe<256, 8, false>), grid, dim3(kAttendThreads), 0, s, a);
+      break;
+    case 512:
+      if (a.streaming) hipLaunchKernelGGL((cache_read_probe<512, 8, true>), grid, dim3(kAttendThreads), 0, s, a);
+      else hipLaunchKernelGGL((cache_read_probe<512, 8, false>), grid, dim3(kAttendThreads), 0, s, a);
+      break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

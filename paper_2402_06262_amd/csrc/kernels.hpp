@@ -28,6 +28,7 @@ struct DecodeArgs {
   Policy pol;
   int unroll;            // rows in flight per lane group in decode_attend: 2, 4 or 8
   int fused;             // 1: one workgroup does the whole step of a unit (decode_fused), no workspace traffic
+  int streaming;         // 1: K / V rows are loaded with the non-temporal hint (cache far larger than the last-level cache)
   int rotate;            // stagger the start offset of every workgroup inside its slot range
   float scale_log2;      // scale * log2(e)
   int recency_window;
@@ -78,6 +79,7 @@ constexpr int kMaxBlockSplits = 8;   // split-K partials per unit of the block-w
 struct BlockArgs {
   int units, B, scope, block, splits, rows_per_split;
   Policy pol;
+  int streaming;  // as DecodeArgs::streaming
   int heads;    // query heads that share the unit's keys and values (1 without grouped-query attention)
   int queries;  // query rows per unit = block * heads <= 32; row r belongs to token r / heads, head r % heads
   float scale_log2;

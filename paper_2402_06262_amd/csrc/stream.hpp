@@ -9,8 +9,6 @@
 
 namespace roco {
 
-constexpr bool kStreamingLoads = true;  // K / V rows are touched once per step
-
 template <int DT, int D> struct RowGeom {
   static constexpr int EPL = Elem<DT>::per16;  // elements per lane
   static constexpr int LPR = D / EPL;          // lanes per row
@@ -46,11 +44,14 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // compiler wait for each load individually, in issue order.
 //
 // qf holds this lane's slice of the query already multiplied by scale*log2(e).
+//   STREAMING   loads K / V with the non-temporal hint: right when the whole cache is far larger than the chip's
+//               last-level cache (the rows would only displace the statistics), wrong when it fits and the next
+//               step would find it there;
 //   bias(row)   is added to the base-2 logit (only evaluated when HAS_BIAS);
 //   zptr        if not null, receives every base-2 logit once: zptr[row];
 //   special_row a row that must not take the branch-free path (the slot being overwritten), or -1;
 //   fix_k(row, kw, c) / fix_v(row, vw, c) may replace the loaded 16 bytes of that row.
-template <int DT, int D, int U, bool HAS_BIAS, class BiasFn, class FixK, class FixV>
+template <int DT, int D, int U, bool HAS_BIAS, bool STREAMING, class BiasFn, class FixK, class FixV>
 __device__ __forceinline__ void stream_attend(const float* qf, const char* Kbase, const char* Vbase,
                                               int row_begin, int row_end, int passes, int rot, int pass_rows,
                                               int wave_off, BiasFn bias, float* zptr, int special_row,
@@ -65,7 +66,7 @@ __device__ __forceinline__ void stream_attend(const float* qf, const char* Kbase
     for (int u = 0; u < U; ++u) {
       const int row = base + u * G::R + g;
       const size_t off = static_cast<size_t>(row < row_end ? row : row_begin) * G::ROW_BYTES + c * 16;
-      w[u] = kStreamingLoads ? load16_streaming(base_ptr + off) : load16(base_ptr + off);
+      w[u] = STREAMING ? load16_streaming(base_ptr + off) : load16(base_ptr + off);
     }
   };
   auto is_plain = [&](int base) {

@@ -11,11 +11,13 @@ from oracle import roco_oracle as orc
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(autouse=True, params=["split", "fused"])
+@pytest.fixture(autouse=True, params=["split", "fused", "fused-streaming"])
 def decode_path(request, monkeypatch):
     """Every case runs on both shapes of the decode step: slot ranges on several workgroups plus a finishing
-    kernel, and one workgroup per unit doing the whole step (the library would pick by the number of units)."""
-    monkeypatch.setenv("ROCO_DECODE_FUSED", "1" if request.param == "fused" else "0")
+    kernel, and one workgroup per unit doing the whole step (the library would pick by the number of units);
+    the second also with the non-temporal K / V loads that caches beyond 192 MiB get."""
+    monkeypatch.setenv("ROCO_DECODE_FUSED", "0" if request.param == "split" else "1")
+    monkeypatch.setenv("ROCO_STREAMING_LOADS", "1" if request.param.endswith("streaming") else "0")
     return request.param
 
 

@@ -128,7 +128,8 @@ int roco_prefill_compress(const roco_params* params,
  *
  * Per unit u:
  *   if n_used == B: scope = the s slots of lowest variance max(0, Acc2/Count - (Acc/Count)^2); victim =
- *   the slot of lowest Acc/Count inside it (equal keys: lowest slot first); slot = victim.
+ *   the slot of lowest Acc/Count inside it (equal keys: lowest slot first); slot = victim.  (With another
+ *   params->importance / scope_kind the two rankings are the ones described at roco_params.)
  *   else slot = n_used, n_used += 1, nothing evicted.
  *   The victim depends only on the statistics left by the previous call, so the library chooses it at the
  *   end of that call and keeps it in next_slot[u]; this call consumes it and, if the unit is full afterwards,
@@ -245,6 +246,8 @@ int roco_select_retained(const roco_params* params, int32_t keep, const float* s
  * milliseconds and their count since the last read, and recycles them.  This mode creates HIP events (the
  * only resources the library ever creates) and is not thread-safe.  Returns 0 or a negative code.
  */
+/* ROCO_PROF_DECODE_ATTEND also stands for the single kernel of a decode step that roco_decode_step_launches
+ * reports as 1 launch. */
 enum {
   ROCO_PROF_DECODE_SELECT = 0, ROCO_PROF_DECODE_ATTEND = 1, ROCO_PROF_DECODE_FINISH = 2,
   ROCO_PROF_PREFILL_ROWS = 3, ROCO_PROF_PREFILL_COLUMNS = 4, ROCO_PROF_PREFILL_SELECT = 5,

@@ -24,7 +24,8 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert {"roco_prefill_compress", "roco_decode_step", "roco_prefill_workspace_bytes",
             "roco_decode_workspace_bytes", "roco_strerror", "roco_version", "roco_select_victims",
             "roco_probe_cache_read", "roco_profile_sampling", "roco_encode_block", "roco_block_workspace_bytes",
-            "roco_decode_step_gqa", "roco_encode_block_gqa"} <= set(names)
+            "roco_decode_step_gqa", "roco_encode_block_gqa",
+            "roco_select_retained", "roco_decode_step_launches"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in roco.h but not exported"
     assert roco.roco_version() == 1
@@ -146,6 +147,23 @@ def test_encode_block_validates_on_the_host():
         a = list(args)
         a[bad] = None
         assert call(p, 8, a) == EINVAL
+
+
+def test_select_retained_validates_on_the_host():
+    lib = roco.load_library()
+    p = roco.RocoParams(4, 128, 256, 16, roco.ROCO_BF16)
+    need = roco.decode_workspace_bytes(p)
+
+    def call(params, keep, stats=0x1000, pos=0x1000, n_used=0x1000, mask=0x1000, ws=0x1000, nbytes=need):
+        return lib.roco_select_retained(ctypes.byref(params), keep, stats, pos, n_used, mask, ws, nbytes, None)
+
+    assert call(p, -1) == EINVAL
+    assert call(p, 10, nbytes=need - 1) == EWORKSPACE
+    assert call(p, 10, stats=None) == EINVAL and call(p, 10, n_used=None) == EINVAL and call(p, 10, mask=None) == EINVAL
+    assert call(p, 10, mask=0x1004) == EINVAL  # misaligned
+    window = roco.RocoParams(4, 128, 256, 16, roco.ROCO_BF16, scope_kind=roco.ROCO_SCOPE_WINDOW)
+    assert call(window, 10, pos=None) == EINVAL  # this policy ranks by position
+    assert call(roco.RocoParams(4, 96, 256, 16, roco.ROCO_BF16), 10) == EUNSUPPORTED
 
 
 def test_loading_fails_loudly_when_the_library_is_missing(monkeypatch):

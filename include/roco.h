@@ -178,7 +178,9 @@ int roco_decode_step(const roco_params* params,
  * evicted_slot, evicted_pos  out [units, b] int32: the slot token i took over from an evicted token and that
  *                  token's position, or -1 where token i went to an empty slot (either may be NULL)
  * workspace        roco_block_workspace_bytes(params, block) bytes
- * Supported: ROCO_BF16, head_dim 128, budget a multiple of 4; anything else returns ROCO_EUNSUPPORTED.
+ * Supported: budget a multiple of 4 (else ROCO_EUNSUPPORTED).  bf16 with head_dim 128 runs on the matrix cores
+ * and streams K and V once per block; the other dtypes / head_dims compute the same step with one pass over K and
+ * V per query row.
  */
 size_t roco_block_workspace_bytes(const roco_params* params, int32_t block);
 int roco_encode_block(const roco_params* params, int32_t block,

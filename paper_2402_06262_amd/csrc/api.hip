@@ -79,7 +79,7 @@ int check_block(const roco_params* p, int32_t block) {
   const int rc = check_params(p);
   if (rc != ROCO_OK) return rc;
   if (block < 1 || block > p->budget) return ROCO_EINVAL;
-  if (block > kMaxBlock || p->dtype != ROCO_BF16 || p->head_dim != 128 || (p->budget & 3) != 0) return ROCO_EUNSUPPORTED;
+  if (block > kMaxBlock || (p->budget & 3) != 0) return ROCO_EUNSUPPORTED;
   return ROCO_OK;
 }
 
@@ -248,6 +248,7 @@ int run_block(const roco_params* params, int tokens, int heads, const void* q, c
   a.units = params->units; a.B = params->budget; a.scope = params->scope;
   a.pol = policy_of(params);
   a.block = tokens; a.heads = heads; a.queries = tokens * heads;
+  a.row_bytes = params->head_dim * (params->dtype == ROCO_BF16 ? 2 : 4);
   a.streaming = streaming_loads(params) ? 1 : 0;
   {  // split the budget into 64-slot-aligned ranges: two resident workgroups per compute unit measured best
     // (more splits cost more partial results to write and merge than they gain in balance)
@@ -261,6 +262,10 @@ int run_block(const roco_params* params, int tokens, int heads, const void* q, c
     rows = (rows + 63) / 64 * 64;
     a.splits = (params->budget + rows - 1) / rows;
     a.rows_per_split = rows;
+    if (params->dtype != ROCO_BF16 || params->head_dim != 128) {  // vector-ALU attention: one workgroup per query row
+      a.splits = 1;
+      a.rows_per_split = params->budget;
+    }
   }
   a.scale_log2 = scale_log2(params);
   a.recency_window = params->recency_window;
@@ -275,7 +280,7 @@ int run_block(const roco_params* params, int tokens, int heads, const void* q, c
   a.part_l = reinterpret_cast<float*>(ws + lay.part_l);
   a.part_o = reinterpret_cast<float*>(ws + lay.part_o);
   a.keys = reinterpret_cast<uint32_t*>(ws + lay.keys);
-  const hipError_t e = launch_block(a, static_cast<hipStream_t>(hip_stream));
+  const hipError_t e = launch_block(params->dtype, params->head_dim, a, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
 }
 }  // namespace

@@ -101,11 +101,12 @@ __global__ __launch_bounds__(kPrepThreads) void block_prepare(BlockArgs a) {
     bidx[j] = bi;
   }
   __syncthreads();
-  // the block's K / V rows go into their slots: 16 lanes x 16 bytes per row
-  const size_t in_base = static_cast<size_t>(u) * b * kRowBytes;
-  for (int i = tid / 16; i < b; i += NT / 16) {
-    const size_t dst = (static_cast<size_t>(u) * B + slot_of[i]) * kRowBytes + (tid & 15) * 16;
-    const size_t src = in_base + static_cast<size_t>(i) * kRowBytes + (tid & 15) * 16;
+  // the block's K / V rows go into their slots: 16 bytes per lane
+  const int lpr = a.row_bytes / 16;  // lanes per row: 8, 16 or 32
+  const size_t in_base = static_cast<size_t>(u) * b * a.row_bytes;
+  for (int i = tid / lpr; i < b; i += NT / lpr) {
+    const size_t dst = (static_cast<size_t>(u) * B + slot_of[i]) * a.row_bytes + (tid % lpr) * 16;
+    const size_t src = in_base + static_cast<size_t>(i) * a.row_bytes + (tid % lpr) * 16;
     *reinterpret_cast<uint4*>(static_cast<char*>(a.K) + dst) = load16(static_cast<const char*>(a.k_new) + src);
     *reinterpret_cast<uint4*>(static_cast<char*>(a.V) + dst) = load16(static_cast<const char*>(a.v_new) + src);
   }
@@ -322,9 +323,75 @@ __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// The attention of the block-wise / grouped-query step for the shapes the matrix-core kernel is not built for
+// (fp32, head_dim 64): grid (query rows, units), one workgroup streams all slots of the unit for one query row
+// on the vector ALUs, exactly like a decode step does, with the slots that hold later tokens of the block masked
+// out.  K and V are read once per query row, so this path has the semantics of the step but not its bandwidth
+// saving.  Produces what block_attend produces with a single split.
+template <int DT, int D>
+__global__ __launch_bounds__(256) void block_attend_simple(BlockArgs a) {
+  using G = RowGeom<DT, D>;
+  constexpr int U = 4, WAVES = 4;
+  constexpr int PASS = WAVES * U * G::R;
+  __shared__ float sm_m[WAVES], sm_l[WAVES];
+  __shared__ float sm_acc[WAVES][D];
+  const int u = blockIdx.y, r = blockIdx.x;  // r: query row = (token, head)
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int c = lane % G::LPR;
+  const int B = a.B;
+  const int n = a.n_used[u];
+  const int ti = r / a.heads;
+  float qf[G::EPL];
+  unpack16<DT>(load16(static_cast<const char*>(a.q) + (static_cast<size_t>(u) * a.queries + r) * G::ROW_BYTES + c * 16), qf);
+#pragma unroll
+  for (int e = 0; e < G::EPL; ++e) qf[e] *= a.scale_log2;
+  const char* Kb = static_cast<const char*>(a.K) + static_cast<size_t>(u) * B * G::ROW_BYTES;
+  const char* Vb = static_cast<const char*>(a.V) + static_cast<size_t>(u) * B * G::ROW_BYTES;
+  const int32_t* bidx = a.blk_idx + static_cast<size_t>(u) * B;
+  const int32_t* pos = a.pos + static_cast<size_t>(u) * B;
+  float* z = a.z + (static_cast<size_t>(u) * kQ + r) * B;
+  const int qp = a.qpos0[u] + ti;
+  const int w = a.recency_window;
+  const float rb = a.recency_bias_log2;
+  auto bias = [&](int row) -> float {
+    if (bidx[row] > ti) return -INFINITY;  // a later token of the block
+    const int dlt = qp - pos[row];
+    return (w > 0 && dlt >= 0 && dlt < w) ? rb : 0.0f;
+  };
+  auto fix = [](int, uint4&, int) {};
+  FlashState<G::EPL> st;
+  st.reset();
+  const int passes = (n + PASS - 1) / PASS;
+  stream_attend<DT, D, U, true, false>(qf, Kb, Vb, 0, n, passes, 0, PASS, wave * (U * G::R), bias, z, -1, fix, fix, st);
+  merge_groups_in_wave<DT, D>(st);
+  if (lane < G::LPR) {
+    if (lane == 0) { sm_m[wave] = st.m; sm_l[wave] = st.l; }
+#pragma unroll
+    for (int e = 0; e < G::EPL; ++e) sm_acc[wave][lane * G::EPL + e] = st.acc[e];
+  }
+  __syncthreads();
+  float M = -INFINITY;
+#pragma unroll
+  for (int s = 0; s < WAVES; ++s) M = fmaxf(M, sm_m[s]);
+  const size_t pidx = static_cast<size_t>(u) * kQ + r;  // one split
+  if (tid < D) {
+    float o = 0.0f, l = 0.0f;
+#pragma unroll
+    for (int s = 0; s < WAVES; ++s) {
+      const float wgt = (sm_m[s] > -INFINITY) ? fast_exp2(sm_m[s] - M) : 0.0f;
+      l += sm_l[s] * wgt;
+      o += sm_acc[s][tid] * wgt;
+    }
+    a.part_o[pidx * D + tid] = o;
+    if (tid == 0) { a.part_m[pidx] = M; a.part_l[pidx] = l; }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // Grid (chunks, units): workgroup (c, u) owns slots [c * kFinSlots, (c + 1) * kFinSlots) of unit u and the query
 // rows r = c, c + chunks, ...  The victim for a following single-token step is chosen afterwards by the
 // select_victims kernel, from the statistics written here.
+template <int DT, int D>
 __global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
   constexpr int NT = kFinThreads;
   __shared__ float Mq[kQ], invq[kQ];
@@ -358,7 +425,7 @@ __global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
       const float ms = pm[s * kQ + q];
       o += (ms > -INFINITY) ? po[(static_cast<size_t>(s) * kQ + q) * D + dd] * fast_exp2(ms - Mq[q]) : 0.0f;
     }
-    store_elem<kBF16>(a.out, (static_cast<size_t>(u) * nq + q) * D + dd, o * invq[q]);
+    store_elem<DT>(a.out, (static_cast<size_t>(u) * nq + q) * D + dd, o * invq[q]);
   }
   // statistics: every slot receives, per block token that attended it, the head-mean of the probabilities
   const int j = chunk * kFinSlots + tid * 2;  // B is a multiple of 4 on this path, so the pair is inside [0, B)
@@ -399,11 +466,29 @@ __global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
 
 }  // namespace
 
-hipError_t launch_block(const BlockArgs& a, hipStream_t s) {
+template <int DT, int D>
+void launch_block_tail(const BlockArgs& a, hipStream_t s) {
+  ProfScope ps(kProfBlockFinish, s);
+  hipLaunchKernelGGL((block_finish<DT, D>), dim3((a.B + kFinSlots - 1) / kFinSlots, a.units), dim3(kFinThreads), 0, s,
+                     a);
+}
+
+template <int DT, int D>
+void launch_block_simple(const BlockArgs& a, hipStream_t s) {
+  {
+    ProfScope ps(kProfBlockAttend, s);
+    hipLaunchKernelGGL((block_attend_simple<DT, D>), dim3(a.queries, a.units), dim3(256), 0, s, a);
+  }
+  launch_block_tail<DT, D>(a, s);
+}
+
+// dtype / head_dim other than bf16 / 128 take the vector-ALU attention (a.splits must then be 1)
+hipError_t launch_block(int dtype, int head_dim, const BlockArgs& a, hipStream_t s) {
   const size_t key_lds = (a.B <= kMaxDecodeBudgetLds) ? static_cast<size_t>(a.B) * 2 * sizeof(uint32_t) : 0;
   constexpr size_t kAttLds = 4 * static_cast<size_t>(kTileBytes);  // 68 KiB: above the default dynamic limit
+  const bool mfma_path = dtype == kBF16 && head_dim == 128;
   static bool attr_done = false;
-  if (!attr_done) {
+  if (mfma_path && !attr_done) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(block_attend), hipFuncAttributeMaxDynamicSharedMemorySize,
                             static_cast<int>(kAttLds)) != hipSuccess)
       return hipErrorInvalidValue;
@@ -413,13 +498,20 @@ hipError_t launch_block(const BlockArgs& a, hipStream_t s) {
     ProfScope ps(kProfBlockPrepare, s);
     hipLaunchKernelGGL(block_prepare, dim3(a.units), dim3(kPrepThreads), key_lds, s, a);
   }
-  {
-    ProfScope ps(kProfBlockAttend, s);
-    hipLaunchKernelGGL(block_attend, dim3(a.splits, a.units), dim3(kAttThreads), kAttLds, s, a);
-  }
-  {
-    ProfScope ps(kProfBlockFinish, s);
-    hipLaunchKernelGGL(block_finish, dim3((a.B + kFinSlots - 1) / kFinSlots, a.units), dim3(kFinThreads), 0, s, a);
+  if (mfma_path) {
+    {
+      ProfScope ps(kProfBlockAttend, s);
+      hipLaunchKernelGGL(block_attend, dim3(a.splits, a.units), dim3(kAttThreads), kAttLds, s, a);
+    }
+    launch_block_tail<kBF16, 128>(a, s);
+  } else if (dtype == kBF16 && head_dim == 64) {
+    launch_block_simple<kBF16, 64>(a, s);
+  } else if (dtype == kF32 && head_dim == 64) {
+    launch_block_simple<kF32, 64>(a, s);
+  } else if (dtype == kF32 && head_dim == 128) {
+    launch_block_simple<kF32, 128>(a, s);
+  } else {
+    return hipErrorInvalidValue;
   }
   if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
   DecodeArgs sel = {};  // the victim a following single-token decode step would take

@@ -80,6 +80,7 @@ struct BlockArgs {
   int units, B, scope, block, splits, rows_per_split;
   Policy pol;
   int streaming;  // as DecodeArgs::streaming
+  int row_bytes;  // bytes of a K / V / q row
   int heads;    // query heads that share the unit's keys and values (1 without grouped-query attention)
   int queries;  // query rows per unit = block * heads <= 32; row r belongs to token r / heads, head r % heads
   float scale_log2;
@@ -100,7 +101,7 @@ struct BlockArgs {
   float* part_o;                   // [units][splits][32][128]
   uint32_t* keys;                  // [units][2][B] when B is too large for LDS
 };
-hipError_t launch_block(const BlockArgs& a, hipStream_t s);  // bf16, head_dim 128, B % 4 == 0
+hipError_t launch_block(int dtype, int head_dim, const BlockArgs& a, hipStream_t s);  // B % 4 == 0
 
 // dtype: 0 = f32, 1 = bf16; head_dim: 64 or 128.  Each returns hipGetLastError() of its launches.
 hipError_t launch_decode(int dtype, int head_dim, const DecodeArgs& a, hipStream_t s);

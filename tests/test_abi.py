@@ -138,10 +138,10 @@ def test_encode_block_validates_on_the_host():
 
     assert call(p, 0) == EINVAL and call(p, 257) == EINVAL
     assert call(p, 33) == EUNS
-    assert call(roco.RocoParams(4, 128, 256, 16, roco.ROCO_F32), 4) == EUNS
-    assert call(roco.RocoParams(4, 64, 256, 16, roco.ROCO_BF16), 4) == EUNS
+    assert call(roco.RocoParams(4, 96, 256, 16, roco.ROCO_BF16), 4) == EUNS  # head_dim
     assert call(roco.RocoParams(4, 128, 254, 16, roco.ROCO_BF16), 4) == EUNS  # budget not a multiple of 4
-    assert roco.block_workspace_bytes(roco.RocoParams(4, 64, 256, 16, roco.ROCO_BF16), 4) == 0
+    assert roco.block_workspace_bytes(roco.RocoParams(4, 96, 256, 16, roco.ROCO_BF16), 4) == 0
+    assert roco.block_workspace_bytes(roco.RocoParams(4, 64, 256, 16, roco.ROCO_F32), 4) > 0  # every dtype / head_dim
     assert call(p, 8, ws=need - 1) == EWORKSPACE
     for bad in [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 13]:  # evicted_slot / evicted_pos (11, 12) may be NULL
         a = list(args)

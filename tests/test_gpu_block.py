@@ -16,7 +16,7 @@ def _P():
     return parity
 
 
-def drive(units, d, B, s, prompt_lens, blocks, seed, recency=False, tag=""):
+def drive(units, d, B, s, prompt_lens, blocks, seed, recency=False, tag="", dtype="bf16"):
     """Optional prefill-compress of `prompt_lens`, then a sequence of block steps of the given sizes."""
     import paper_2402_06262_amd as roco
     P = _P()
@@ -24,17 +24,19 @@ def drive(units, d, B, s, prompt_lens, blocks, seed, recency=False, tag=""):
     Lmax = max(max(prompt_lens), 1)
     T = Lmax + sum(blocks)
     rng = np.random.default_rng(seed)
-    Q = round_to_bf16(rng.standard_normal((units, T, d)).astype(np.float32) + 0.25)
-    K = round_to_bf16(rng.standard_normal((units, T, d)).astype(np.float32))
-    V = round_to_bf16(rng.standard_normal((units, T, d)).astype(np.float32))
+    Q = rng.standard_normal((units, T, d)).astype(np.float32) + 0.25
+    K = rng.standard_normal((units, T, d)).astype(np.float32)
+    V = rng.standard_normal((units, T, d)).astype(np.float32)
+    if dtype == "bf16":
+        Q, K, V = round_to_bf16(Q), round_to_bf16(K), round_to_bf16(V)
     kw = dict(recency_window=24, recency_bias=0.5) if recency else {}
-    sess = P.make_session(units, d, B, s, "bf16", 0.0, *(kw.values() if recency else ()))
+    sess = P.make_session(units, d, B, s, dtype, 0.0, *(kw.values() if recency else ()))
     rw, rb = (24, 0.5) if recency else (0, 0.0)
     states, nxt = [], []
     if max(prompt_lens) > 0:
         g = P.gpu_prefill(sess, Q[:, :Lmax].copy(), K[:, :Lmax].copy(), V[:, :Lmax].copy(), prompt_lens, False)
         for u in range(units):
-            res, _ = P.check_prefill_unit(g, u, Q[u, :Lmax], K[u, :Lmax], V[u, :Lmax], prompt_lens[u], B, s, sc, "bf16",
+            res, _ = P.check_prefill_unit(g, u, Q[u, :Lmax], K[u, :Lmax], V[u, :Lmax], prompt_lens[u], B, s, sc, dtype,
                                           rw, rb, False)
             states.append(res.cache)
             nxt.append(prompt_lens[u])
@@ -51,7 +53,7 @@ def drive(units, d, B, s, prompt_lens, blocks, seed, recency=False, tag=""):
         g_out, g_slot, g_pos = P.gpu_encode_block(sess, b, Q[:, t:t + b], K[:, t:t + b], V[:, t:t + b], nxt, ws)
         for u in range(units):
             ties += P.lockstep_block_unit(states[u], u, g_out, g_slot, g_pos, Q[u, t:t + b], K[u, t:t + b], V[u, t:t + b],
-                                          nxt[u], s, sc, "bf16", rw, rb, what=f"[{tag}] block {b} @ {t}")
+                                          nxt[u], s, sc, dtype, rw, rb, what=f"[{tag}] block {b} @ {t}")
             assert states[u].n_used <= B
         host = P.cache_to_host(sess)
         for u in range(units):
@@ -62,7 +64,7 @@ def drive(units, d, B, s, prompt_lens, blocks, seed, recency=False, tag=""):
     g_out, g_slot, g_pos = P.gpu_decode_step(sess, Q[:, t - 1], K[:, t - 1], V[:, t - 1], nxt)
     for u in range(units):
         ties += P.lockstep_decode_unit(states[u], u, g_out, g_slot, g_pos, Q[u, t - 1], K[u, t - 1], V[u, t - 1], nxt[u], s,
-                                       sc, "bf16", rw, rb, what=f"[{tag}] decode after blocks")
+                                       sc, dtype, rw, rb, what=f"[{tag}] decode after blocks")
     print(f"[{tag}] ties {ties}", flush=True)
     return ties
 
@@ -71,6 +73,14 @@ def drive(units, d, B, s, prompt_lens, blocks, seed, recency=False, tag=""):
 def test_block_steps_on_a_full_cache(b):
     """Cache filled by prefill-compress, then blocks of b tokens: b evictions per step."""
     drive(3, 128, 256, 24, [400, 300, 256], [b] * 4, seed=60 + b, tag=f"full-{b}")
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 64), ("f32", 128)])
+def test_block_steps_on_the_vector_path_for_other_dtypes_and_head_dims(dtype, d):
+    """Shapes the matrix-core kernel is not built for take one vector-ALU pass per query row: same step, same
+    parity bar.  From a compressed cache and with a unit that is still filling up; ragged block sizes."""
+    drive(3, d, 96, 10, [150, 96, 40], [8, 1, 32, 5, 16, 32, 3], seed=140 + d, tag=f"simple-{dtype}-{d}", dtype=dtype)
+    drive(2, d, 64, 8, [100, 64], [4, 32], seed=150 + d, recency=True, tag=f"simple-recency-{dtype}-{d}", dtype=dtype)
 
 
 def test_block_steps_fill_an_empty_cache_then_start_evicting():
@@ -109,7 +119,8 @@ def test_block_steps_at_the_serving_shape_all_512_units():
     with ThreadPoolExecutor(min(16, len(os.sched_getaffinity(0)))) as ex:
         list(ex.map(one, range(U)))
     sc = 1.0 / math.sqrt(d)
-    sess = P.make_session(U, d, B, s, "bf16")
+    dtype = "bf16"
+    sess = P.make_session(U, d, B, s, dtype)
     c, p = sess.cache, sess.params
     dt = torch.bfloat16
     up = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda().to(dt)
@@ -141,7 +152,7 @@ def test_block_steps_at_the_serving_shape_all_512_units():
         g_out, g_slot, g_pos = P.to_host(out[sidx]), P.to_host(es[sidx]), P.to_host(ep[sidx])
         for k, u in enumerate(sample):
             ties += P.lockstep_block_unit(states[k], k, g_out, g_slot, g_pos, Q[u, t:t + b], K[u, t:t + b], V[u, t:t + b],
-                                          t, s, sc, "bf16", what=f"[cfg3-block] block {i} unit {u}")
+                                          t, s, sc, dtype, what=f"[cfg3-block] block {i} unit {u}")
         host = dict(K=P.to_host(c.K[sidx]), V=P.to_host(c.V[sidx]), stats=P.to_host(c.stats[sidx]),
                     pos=P.to_host(c.pos[sidx]), n_used=P.to_host(c.n_used[sidx]))
         for k, u in enumerate(sample):

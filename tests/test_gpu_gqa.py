@@ -21,20 +21,21 @@ def empty_states(units, B, d):
                            np.full(B, -1, dtype=np.int64), 0) for _ in range(units)]
 
 
-def drive(units, B, s, group, blocks, seed, recency=False, tag="", single_token_entry=False):
+def drive(units, B, s, group, blocks, seed, recency=False, tag="", single_token_entry=False, dtype="bf16", d=128):
     """Key/value heads shared by `group` query heads, encoded from an empty cache in blocks of the given sizes
     (a block of 1 through roco_decode_step_gqa when `single_token_entry`)."""
     import paper_2402_06262_amd as roco
     P = _P()
-    d = 128
     sc = 1.0 / math.sqrt(d)
     T = sum(blocks)
     rng = np.random.default_rng(seed)
-    Q = round_to_bf16(rng.standard_normal((units, T, group, d)).astype(np.float32) + 0.25)
-    K = round_to_bf16(rng.standard_normal((units, T, d)).astype(np.float32))
-    V = round_to_bf16(rng.standard_normal((units, T, d)).astype(np.float32))
+    Q = rng.standard_normal((units, T, group, d)).astype(np.float32) + 0.25
+    K = rng.standard_normal((units, T, d)).astype(np.float32)
+    V = rng.standard_normal((units, T, d)).astype(np.float32)
+    if dtype == "bf16":
+        Q, K, V = round_to_bf16(Q), round_to_bf16(K), round_to_bf16(V)
     rw, rb = (24, 0.5) if recency else (0, 0.0)
-    sess = P.make_session(units, d, B, s, "bf16", 0.0, rw, rb)
+    sess = P.make_session(units, d, B, s, dtype, 0.0, rw, rb)
     states = empty_states(units, B, d)
     ties = P.TieCount()
     t = 0
@@ -50,7 +51,7 @@ def drive(units, B, s, group, blocks, seed, recency=False, tag="", single_token_
                                                           [t] * units, ws)
         for u in range(units):
             ties += P.lockstep_block_gqa_unit(states[u], u, g_out, g_slot, g_pos, Q[u, t:t + b], K[u, t:t + b],
-                                              V[u, t:t + b], t, s, sc, "bf16", rw, rb, what=f"[{tag}] block {b} @ {t}")
+                                              V[u, t:t + b], t, s, sc, dtype, rw, rb, what=f"[{tag}] block {b} @ {t}")
         if n_blk % 8 == 7 or n_blk == len(blocks) - 1:
             host = P.cache_to_host(sess)
             for u in range(units):
@@ -70,6 +71,13 @@ def test_grouped_decode_steps_fill_then_evict(group):
 def test_grouped_blocks(group, blocks):
     """Block-wise grouped-query encoding (block * group query rows per matrix tile), ragged blocks included."""
     drive(2, 64, 8, group, blocks, seed=90 + group, tag=f"gqa-block-g{group}")
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 64)])
+def test_grouped_steps_on_the_vector_path(dtype, d):
+    """Grouped-query decode and block steps for the shapes that take the vector-ALU attention."""
+    drive(2, 48, 6, 4, [1] * 60 + [8, 3, 8, 1], seed=170 + d, tag=f"gqa-simple-{dtype}-{d}", single_token_entry=True,
+          dtype=dtype, d=d)
 
 
 def test_grouped_steps_with_recency_bias_and_a_larger_budget():

@@ -109,10 +109,19 @@ class PrefillStats:
     out: Optional[np.ndarray]  # [length, d] attention output, if requested
 
 
+def _keeps_last_score(policy) -> bool:
+    """Whether the policy's second statistic is the last query's attention (importance "ltas") instead of the
+    accumulated squared attention."""
+    return policy is not None and policy.importance == "ltas"
+
+
 def prefill_statistics(Q, K, V, length: int, scale: float, recency_window: int = 0,
                        recency_bias: float = 0.0, want_out: bool = False,
-                       row_block: int = 512) -> PrefillStats:
-    """Column statistics of the causal attention matrix (section 4.3: Acc, Acc^square, Count)."""
+                       row_block: int = 512, policy=None) -> PrefillStats:
+    """Column statistics of the causal attention matrix (section 4.3: Acc, Acc^square, Count).
+
+    Under the last-token importance score (section 4.1, LTAS) the second array holds the attention row of the
+    last prompt token instead of the accumulated squares."""
     acc = np.zeros(length, dtype=F64)
     acc2 = np.zeros(length, dtype=F64)
     count = np.zeros(length, dtype=F64)
@@ -122,7 +131,11 @@ def prefill_statistics(Q, K, V, length: int, scale: float, recency_window: int =
                                          recency_bias, row_block):
         i1 = i0 + P.shape[0]
         acc[:i1] += P.sum(axis=0)
-        acc2[:i1] += (P * P).sum(axis=0)
+        if _keeps_last_score(policy):
+            if i0 <= length - 1 < i1:
+                acc2[:i1] = P[length - 1 - i0]
+        else:
+            acc2[:i1] += (P * P).sum(axis=0)
         count[:i1] += (np.arange(i1)[None, :] <= np.arange(i0, i1)[:, None]).sum(axis=0)
         if want_out:
             out[i0:i1] = P @ Vd[:i1]
@@ -186,7 +199,9 @@ def select_evictions(mas: np.ndarray, var: np.ndarray, scope: int, n_evict: int)
 class Policy:
     """importance: "mas" (Acc/Count, section 4.3), "aas" (accumulated attention score Acc, the H2O score of
     section 4.1), "oldest" (recency: the lowest position goes first, except the first `sinks` positions, which
-    are never chosen while anything else is in scope: the window / StreamLLM baseline of section 4.1).
+    are never chosen while anything else is in scope: the window / StreamLLM baseline of section 4.1), "ltas"
+    (the attention the token received from the most recent query, the TOVA score of section 4.1; the array that
+    otherwise accumulates squared attention then holds that score, so the "std" scope is not available).
     scope_kind: "std" (the s tokens of lowest variance, section 4.3), "window" (the s oldest tokens, i.e. the
     most recent n - s are protected: the local-window scope of section 4.2), "all" (every cached token)."""
     importance: str = "mas"
@@ -212,6 +227,10 @@ def ranking_scores(policy: Optional[Policy], acc, acc2, count, pos, scope: int):
         importance = acc.copy()
     elif policy.importance == "oldest":
         importance = np.where(pos < policy.sinks, np.inf, pos.astype(F64))
+    elif policy.importance == "ltas":
+        if policy.scope_kind == "std":
+            raise ValueError("the last-token score replaces the squared-attention array: no variance to rank by")
+        importance = acc2.copy()
     else:
         raise ValueError(policy.importance)
     if policy.scope_kind == "std":
@@ -298,7 +317,7 @@ def prefill_compress(Q, K, V, length: int, budget: int, scope: int, scale: float
     harness after a declared tie, never by the pins).
     """
     full = prefill_statistics(Q, K, V, length, scale, recency_window, recency_bias,
-                              want_out, row_block)
+                              want_out, row_block, policy)
     return compress_from_statistics(full, K, V, length, budget, scope, force_retained, policy)
 
 
@@ -338,7 +357,10 @@ def decode_step(state: CacheState, q, k_new, v_new, qpos: int, scope: int, scale
     p = p / p.sum()
     out = p @ state.V[:n]
     state.acc[:n] += p
-    state.acc2[:n] += p * p
+    if _keeps_last_score(policy):
+        state.acc2[:n] = p
+    else:
+        state.acc2[:n] += p * p
     state.count[:n] += 1.0
     return DecodeResult(out, p, evicted_slot, evicted_pos, slot, mas, var)
 
@@ -405,9 +427,13 @@ def encode_block(state: CacheState, Qb, Kb, Vb, qpos0: int, scope: int, scale: f
         full = np.zeros(n_new, dtype=F64)
         full[seen] = p
         probs.append(full)
-    for i in range(b):  # statistics after all rows are known (the order of additions does not matter)
+    for i in range(b):  # statistics after all rows are known, in the block's order
         state.acc[:n_new] += probs[i]
-        state.acc2[:n_new] += probs[i] * probs[i]
+        if _keeps_last_score(policy):
+            seen = block_index[:n_new] <= i
+            state.acc2[:n_new][seen] = probs[i][seen]
+        else:
+            state.acc2[:n_new] += probs[i] * probs[i]
         state.count[:n_new] += (block_index[:n_new] <= i).astype(F64)
     return BlockResult(out, probs, targets, evicted_slot, evicted_pos, mas, var)
 
@@ -465,7 +491,10 @@ def decode_step_gqa(state: CacheState, Qg, k_new, v_new, qpos: int, scope: int, 
         out[h] = probs[h] @ state.V[:n]
     mean_p = probs.sum(axis=0) / F64(g)
     state.acc[:n] += mean_p
-    state.acc2[:n] += mean_p * mean_p
+    if _keeps_last_score(policy):
+        state.acc2[:n] = mean_p
+    else:
+        state.acc2[:n] += mean_p * mean_p
     state.count[:n] += 1.0
     return GroupDecodeResult(out, probs, mean_p, evicted_slot, evicted_pos, slot, mas, var)
 
@@ -531,7 +560,11 @@ def encode_block_gqa(state: CacheState, Qb, Kb, Vb, qpos0: int, scope: int, scal
         means.append(full)
     for i in range(b):
         state.acc[:n_new] += means[i]
-        state.acc2[:n_new] += means[i] * means[i]
+        if _keeps_last_score(policy):
+            seen = block_index[:n_new] <= i
+            state.acc2[:n_new][seen] = means[i][seen]
+        else:
+            state.acc2[:n_new] += means[i] * means[i]
         state.count[:n_new] += (block_index[:n_new] <= i).astype(F64)
     return GroupBlockResult(out, means, targets, evicted_slot, evicted_pos, mas, var)
 

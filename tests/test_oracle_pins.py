@@ -631,3 +631,47 @@ def test_shrinking_a_dense_cache_keeps_what_prefill_compress_keeps():
             want = orc.prefill_compress(Q, K, V, L, keep, s, 0.5, policy=pol).retained
             assert np.array_equal(dense.pos[mask], want) and mask.sum() == min(keep, L)
         assert not mask[L:].any()  # empty slots are never reported
+
+
+def test_last_token_score_keeps_the_top_of_the_last_query_row_written_out_independently():
+    """importance "ltas" over the whole cache (section 4.1, the score of TOVA): after the prompt the cache holds
+    the B tokens with the highest attention from the last prompt token, and every decode step evicts the cached
+    token the previous query attended least; both are rebuilt here from dense softmax rows, without the cache."""
+    rng = np.random.default_rng(71)
+    L, T, d, B = 24, 12, 5, 9
+    Q, K, V = rand_unit(rng, L + T, d)
+    pol = orc.Policy("ltas", "all")
+    r = orc.prefill_compress(Q[:L], K[:L], V[:L], L, B, 1, 0.45, policy=pol)
+    z = 0.45 * K[:L] @ Q[L - 1]
+    w = np.exp(z - z.max())
+    w /= w.sum()
+    assert np.allclose(r.full.acc2, w, rtol=1e-12)
+    assert sorted(r.retained) == sorted(np.argsort(-w, kind="stable")[:B])
+    st = r.cache
+    held = {int(p): float(x) for p, x in zip(st.pos, st.acc2)}  # position -> score from the latest query
+    for t in range(L, L + T):
+        expect = min(held, key=lambda j: (held[j], list(st.pos).index(j)))
+        res = orc.decode_step(st, Q[t], K[t], V[t], t, 1, 0.45, policy=pol)
+        assert res.evicted_pos == expect
+        keep = [int(p) for p in st.pos]
+        zz = 0.45 * K[keep] @ Q[t]
+        ww = np.exp(zz - zz.max())
+        ww /= ww.sum()
+        held = dict(zip(keep, ww))
+        assert np.allclose(st.acc2, ww, rtol=1e-12) and np.allclose(res.out, ww @ V[keep], rtol=1e-12)
+    with pytest.raises(ValueError):
+        orc.prefill_compress(Q[:L], K[:L], V[:L], L, B, 3, 0.45, policy=orc.Policy("ltas", "std"))
+
+
+def test_last_token_score_in_block_and_grouped_steps_is_the_last_tokens_row():
+    rng = np.random.default_rng(72)
+    L, d, B = 20, 4, 12
+    Q, K, V = rand_unit(rng, L + 5, d)
+    pol = orc.Policy("ltas", "window")
+    a = orc.prefill_compress(Q[:L], K[:L], V[:L], L, B, 6, 0.5, policy=pol).cache
+    b = a.copy()
+    r = orc.encode_block(a, Q[L:L + 5], K[L:L + 5], V[L:L + 5], L, 6, 0.5, policy=pol)
+    assert np.array_equal(a.acc2, r.probs[4])  # every slot is seen by the block's last token
+    Qg = np.stack([Q[L:L + 5], Q[L:L + 5][::-1]], axis=1)  # two heads
+    rg = orc.encode_block_gqa(b, Qg, K[L:L + 5], V[L:L + 5], L, 6, 0.5, policy=pol)
+    assert np.array_equal(b.acc2, rg.mean_probs[4]) and np.array_equal(a.pos, b.pos)

@@ -38,6 +38,8 @@ def bands_for(policy, acc, acc2, count, rel: float = 1e-3) -> Tuple[np.ndarray, 
     scope_kind = getattr(policy, "scope_kind", "std")
     if importance == "aas":
         eps_m = rel * np.abs(np.asarray(acc, dtype=F64))
+    elif importance == "ltas":
+        eps_m = rel * np.abs(np.asarray(acc2, dtype=F64))  # the second array holds the score itself
     elif importance == "oldest":
         eps_m = np.zeros_like(eps_m)
     if scope_kind != "std":

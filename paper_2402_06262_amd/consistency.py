@@ -15,7 +15,8 @@ from typing import Dict, Iterable, Sequence, Tuple
 
 from . import binding as roco
 
-IMPORTANCE = {"mas": roco.ROCO_IMPORTANCE_MAS, "aas": roco.ROCO_IMPORTANCE_AAS, "oldest": roco.ROCO_IMPORTANCE_OLDEST}
+IMPORTANCE = {"mas": roco.ROCO_IMPORTANCE_MAS, "aas": roco.ROCO_IMPORTANCE_AAS, "oldest": roco.ROCO_IMPORTANCE_OLDEST,
+              "ltas": roco.ROCO_IMPORTANCE_LAST}
 
 
 class _Run:
@@ -67,9 +68,14 @@ def consistency_study(Q, K, V, prompt_len: int, rates: Sequence[float] = (0.3, 0
               torch.full((U,), t, dtype=torch.int32, device="cuda")) for t in range(L, T)]
     sampled = [t for t in range(L, T) if (t - L) % sample_every == sample_every - 1 or t == T - 1]
 
-    # the full-cache run: its statistics do not depend on the policy, so one run serves every (importance, rate)
-    full = _Run(torch, roco.RocoParams(U, d, T, T, dt), L)
-    full.prefill(Qp, Kp, Vp, lens, L)
+    # the full-cache runs: the statistics do not depend on the policy (one run serves every importance and rate),
+    # except that the last-token score keeps the latest query's attention where the others keep squares
+    importances = list(importances)
+    fulls = {}
+    for last in sorted({name == "ltas" for name in importances}):
+        imp = roco.ROCO_IMPORTANCE_LAST if last else roco.ROCO_IMPORTANCE_MAS
+        fulls[last] = _Run(torch, roco.RocoParams(U, d, T, T, dt, importance=imp, scope_kind=roco.ROCO_SCOPE_ALL), L)
+        fulls[last].prefill(Qp, Kp, Vp, lens, L)
     budgets = {r: max(1, min(T, int(round(r * T)))) for r in rates}
     runs = {}
     for name in importances:
@@ -83,13 +89,15 @@ def consistency_study(Q, K, V, prompt_len: int, rates: Sequence[float] = (0.3, 0
     mask = torch.empty((U, T), dtype=torch.int32, device="cuda")
     for i, t in enumerate(range(L, T)):
         q, k, v, qpos = steps[i]
-        full.step(q, k, v, qpos)
+        for full in fulls.values():
+            full.step(q, k, v, qpos)
         for run in runs.values():
             run.step(q, k, v, qpos)
         if t not in sampled:
             continue
-        fc = full.cache
         for (name, r), run in runs.items():
+            full = fulls[name == "ltas"]
+            fc = full.cache
             B = budgets[r]
             if t + 1 <= B:
                 continue  # nothing has been evicted yet: the two sets are trivially equal

@@ -19,7 +19,8 @@ int check_params(const roco_params* p) {
   if (p == nullptr) return ROCO_EINVAL;
   if (p->units < 1 || p->budget < 1 || p->scope < 1 || p->scope > p->budget) return ROCO_EINVAL;
   if (p->recency_window < 0) return ROCO_EINVAL;
-  if (p->importance < 0 || p->importance > 2 || p->scope_kind < 0 || p->scope_kind > 2 || p->sinks < 0) return ROCO_EINVAL;
+  if (p->importance < 0 || p->importance > 3 || p->scope_kind < 0 || p->scope_kind > 2 || p->sinks < 0) return ROCO_EINVAL;
+  if (p->importance == ROCO_IMPORTANCE_LAST && p->scope_kind == ROCO_SCOPE_STD) return ROCO_EINVAL;  // no variance kept
   if (!(p->scale == p->scale) || !(p->recency_bias == p->recency_bias)) return ROCO_EINVAL;  // NaN
   if (p->dtype != ROCO_F32 && p->dtype != ROCO_BF16) return ROCO_EUNSUPPORTED;
   if (p->head_dim != 64 && p->head_dim != 128) return ROCO_EUNSUPPORTED;
@@ -182,6 +183,10 @@ int roco_prefill_compress(const roco_params* params, const void* Q, const void* 
   hipError_t e = mfma ? launch_prefill_attention_mfma(a, s)
                       : launch_prefill_attention_simple(params->dtype, params->head_dim, a, s);
   if (e != hipSuccess) return ROCO_EHIP;
+  if (a.pol.keeps_last_score()) {
+    e = launch_prefill_last_row(params->dtype, params->head_dim, a, s);
+    if (e != hipSuccess) return ROCO_EHIP;
+  }
   e = launch_prefill_select_compact(params->dtype, params->head_dim, a, s);
   return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
 }

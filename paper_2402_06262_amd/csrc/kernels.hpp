@@ -8,12 +8,15 @@ namespace roco {
 
 // Eviction policy in the paper's two-stage framework (section 4): an eviction scope, then an importance score
 // inside it.  All zeros is RoCo (section 4.3).
-enum : int { kImpMas = 0, kImpAas = 1, kImpOldest = 2 };
+enum : int { kImpMas = 0, kImpAas = 1, kImpOldest = 2, kImpLast = 3 };
 enum : int { kScopeStd = 0, kScopeWindow = 1, kScopeAll = 2 };
 struct Policy {
-  int importance;  // kImpMas: Acc/Count; kImpAas: Acc; kImpOldest: position, the first `sinks` positions last
+  int importance;  // kImpMas: Acc/Count; kImpAas: Acc; kImpOldest: position, the first `sinks` positions last;
+                   // kImpLast: the attention from the latest query, kept in the second statistics plane
   int scope_kind;  // kScopeStd: lowest variance; kScopeWindow: lowest position (oldest); kScopeAll: everything
   int sinks;
+  // the second plane holds the latest query's probability instead of the accumulated squares
+  __host__ __device__ bool keeps_last_score() const { return importance == kImpLast; }
   __host__ __device__ bool needs_pos() const { return importance == kImpOldest || scope_kind == kScopeWindow; }
   // number of tokens inside the scope when n are cached
   __host__ __device__ int scope_size(int scope, int n) const { return scope_kind == kScopeAll ? n : scope; }
@@ -112,6 +115,8 @@ hipError_t launch_select_victims(const DecodeArgs& a, hipStream_t s);
 hipError_t launch_select_retained(const DecodeArgs& a, int keep, int32_t* mask, hipStream_t s);  // uses stats, n_used, next_slot, keys
 hipError_t launch_prefill_attention_simple(int dtype, int head_dim, const PrefillArgs& a, hipStream_t s);
 hipError_t launch_prefill_attention_mfma(const PrefillArgs& a, hipStream_t s);  // bf16, head_dim 128
+// overwrites PrefillArgs::acc2 with the attention row of each unit's last prompt token (kImpLast)
+hipError_t launch_prefill_last_row(int dtype, int head_dim, const PrefillArgs& a, hipStream_t s);
 hipError_t launch_prefill_select_compact(int dtype, int head_dim, const PrefillArgs& a, hipStream_t s);
 
 }  // namespace roco

@@ -127,7 +127,51 @@ hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// The attention row of the last prompt token, P[len-1, j] for every key j, written over Acc2: the second
+// statistic of the last-token importance score (section 4.1, LTAS).  One workgroup per unit; a lane group owns
+// a key row, as in the passes above.  Needs the row normalisers of pass 1.
+template <int DT, int D>
+__global__ __launch_bounds__(kThreads) void prefill_last_row(PrefillArgs a) {
+  using G = RowGeom<DT, D>;
+  const int u = blockIdx.x;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = lane / G::LPR, c = lane % G::LPR;
+  const int len = a.len[u];
+  const int last = len - 1;
+  const size_t ubase = static_cast<size_t>(u) * a.L_max;
+  float qf[G::EPL];
+  unpack16<DT>(load16(static_cast<const char*>(a.Q) + (ubase + last) * G::ROW_BYTES + c * 16), qf);
+#pragma unroll
+  for (int e = 0; e < G::EPL; ++e) qf[e] *= a.scale_log2;
+  const char* Kb = static_cast<const char*>(a.K) + ubase * G::ROW_BYTES;
+  const float lse_last = a.lse[ubase + last];
+  const int w = a.recency_window;
+  const float rb = a.recency_bias_log2;
+  for (int base = wave * G::R; base < len; base += kWaves * G::R) {
+    const int j = base + g;
+    const int jc = j < len ? j : last;
+    float kf[G::EPL];
+    unpack16<DT>(load16(Kb + static_cast<size_t>(jc) * G::ROW_BYTES + c * 16), kf);
+    float dot = 0.0f;
+#pragma unroll
+    for (int e = 0; e < G::EPL; ++e) dot = fmaf(qf[e], kf[e], dot);
+    dot = group_sum<G::LPR>(dot);
+    if (w > 0 && last - jc < w) dot += rb;
+    if (c == 0 && j < len) a.acc2[ubase + j] = fast_exp2(dot - lse_last);
+  }
+}
+
 }  // namespace
+
+hipError_t launch_prefill_last_row(int dtype, int head_dim, const PrefillArgs& a, hipStream_t s) {
+  const dim3 grid(a.units), block(kThreads);
+  if (dtype == kF32 && head_dim == 64) hipLaunchKernelGGL((prefill_last_row<kF32, 64>), grid, block, 0, s, a);
+  else if (dtype == kF32 && head_dim == 128) hipLaunchKernelGGL((prefill_last_row<kF32, 128>), grid, block, 0, s, a);
+  else if (dtype == kBF16 && head_dim == 64) hipLaunchKernelGGL((prefill_last_row<kBF16, 64>), grid, block, 0, s, a);
+  else if (dtype == kBF16 && head_dim == 128) hipLaunchKernelGGL((prefill_last_row<kBF16, 128>), grid, block, 0, s, a);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
+}
 
 hipError_t launch_prefill_attention_simple(int dtype, int head_dim, const PrefillArgs& a, hipStream_t s) {
   if (dtype == kF32 && head_dim == 64) return launch_t<kF32, 64>(a, s);

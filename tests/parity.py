@@ -91,7 +91,7 @@ class GpuSession:
     O: Optional[torch.Tensor] = None
 
 
-_IMPORTANCE = {"mas": 0, "aas": 1, "oldest": 2}
+_IMPORTANCE = {"mas": 0, "aas": 1, "oldest": 2, "ltas": 3}
 _SCOPE_KIND = {"std": 0, "window": 1, "all": 2}
 
 
@@ -135,7 +135,8 @@ def check_prefill_unit(g: dict, u: int, Qu, Ku, Vu, length: int, budget: int, sc
     comparison of the attention output to a sample of rows."""
     ties = TieCount()
     if full is None:
-        full = orc.prefill_statistics(Qu, Ku, Vu, length, scale, recency_window, recency_bias, want_out, row_block)
+        full = orc.prefill_statistics(Qu, Ku, Vu, length, scale, recency_window, recency_bias, want_out, row_block,
+                                      policy)
     res = orc.compress_from_statistics(full, Ku, Vu, length, budget, scope, policy=policy)
     n = min(length, budget)
     assert int(g["n_used"][u]) == n, f"unit {u}: n_used {g['n_used'][u]} != {n}"

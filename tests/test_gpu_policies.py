@@ -18,6 +18,8 @@ POLICIES = {
     "aas-std": orc.Policy("aas", "std"),
     "sinks": orc.Policy("oldest", "all", 4),       # sliding window with four attention sinks
     "oldest-window": orc.Policy("oldest", "window", 2),
+    "tova": orc.Policy("ltas", "all"),             # last-token attention score over the whole cache
+    "ltas-window": orc.Policy("ltas", "window"),
 }
 
 
@@ -63,7 +65,7 @@ def test_sink_policy_keeps_the_sinks_and_the_most_recent_tokens():
         assert sorted(host["pos"][u].tolist()) == want
 
 
-@pytest.mark.parametrize("name", ["h2o", "sinks", "mas-window"])
+@pytest.mark.parametrize("name", ["h2o", "sinks", "mas-window", "tova"])
 def test_block_steps_under_each_policy(name):
     import test_gpu_block as TB
     pol = POLICIES[name]

@@ -52,7 +52,8 @@ enum {
 };
 
 typedef struct roco_params {
-  int32_t units;          /* number of independent (layer, sequence, head) units, >= 1             */
+  int32_t units;          /* number of independent (layer, sequence, head) units, 1 .. 65535 per call
+                             (more: ROCO_EUNSUPPORTED; split the call)                               */
   int32_t head_dim;       /* d': 64 or 128                                                          */
   int32_t budget;         /* B >= 1: slots per unit (section 3: n <= B at every step)               */
   int32_t scope;          /* s in [1, B]: the eviction scope holds the s occupied slots of lowest

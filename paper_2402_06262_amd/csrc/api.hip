@@ -25,6 +25,7 @@ int check_params(const roco_params* p) {
   if (p->dtype != ROCO_F32 && p->dtype != ROCO_BF16) return ROCO_EUNSUPPORTED;
   if (p->head_dim != 64 && p->head_dim != 128) return ROCO_EUNSUPPORTED;
   if (p->budget > (1 << 24)) return ROCO_EUNSUPPORTED;  // Count is kept exactly in fp32
+  if (p->units > 65535) return ROCO_EUNSUPPORTED;       // several kernels index units with the grid's y dimension
   return ROCO_OK;
 }
 

@@ -675,3 +675,37 @@ def test_last_token_score_in_block_and_grouped_steps_is_the_last_tokens_row():
     Qg = np.stack([Q[L:L + 5], Q[L:L + 5][::-1]], axis=1)  # two heads
     rg = orc.encode_block_gqa(b, Qg, K[L:L + 5], V[L:L + 5], L, 6, 0.5, policy=pol)
     assert np.array_equal(b.acc2, rg.mean_probs[4]) and np.array_equal(a.pos, b.pos)
+
+
+def test_grouped_prefill_statistics_reduce_to_one_head_and_equal_block_wise_encoding_without_eviction():
+    rng = np.random.default_rng(81)
+    L, d, g = 23, 4, 3
+    Qh = rng.standard_normal((g, L, d))
+    _, K, V = rand_unit(rng, L, d)
+    one = orc.prefill_statistics_gqa(Qh[:1], K, V, L, 0.5, 4, 0.3, row_block=7)
+    ref = orc.prefill_statistics(Qh[0], K, V, L, 0.5, 4, 0.3)
+    assert np.allclose(one.acc, ref.acc, rtol=1e-13) and np.allclose(one.acc2, ref.acc2, rtol=1e-13)
+    assert np.array_equal(one.count, ref.count)
+    full = orc.prefill_statistics_gqa(Qh, K, V, L, 0.5, 4, 0.3, row_block=7)
+    st = orc.CacheState(np.zeros((L, d)), np.zeros((L, d)), np.zeros(L), np.zeros(L), np.zeros(L),
+                        np.full(L, -1, dtype=np.int64), 0)
+    t = 0
+    for blk in (5, 1, 9, 8):  # the same prompt, encoded block-wise into a cache that never fills
+        orc.encode_block_gqa(st, Qh[:, t:t + blk].transpose(1, 0, 2), K[t:t + blk], V[t:t + blk], t, 3, 0.5, 4, 0.3)
+        t += blk
+    assert np.allclose(full.acc, st.acc, rtol=1e-12) and np.allclose(full.acc2, st.acc2, rtol=1e-12)
+    assert np.array_equal(full.count, st.count)
+    # the last-token score: the head-mean of the last prompt token's rows
+    last = orc.prefill_statistics_gqa(Qh, K, V, L, 0.5, policy=orc.Policy("ltas", "all"))
+    rows = []
+    for h in range(g):
+        z = 0.5 * K @ Qh[h, L - 1]
+        w = np.exp(z - z.max())
+        rows.append(w / w.sum())
+    assert np.allclose(last.acc2, np.mean(rows, axis=0), rtol=1e-12)
+    r = orc.prefill_compress_gqa(Qh, K, V, L, 10, 4, 0.5)
+    assert r.cache.n_used == 10 and np.array_equal(r.cache.acc, full_acc_at(r, orc.prefill_statistics_gqa(Qh, K, V, L, 0.5)))
+
+
+def full_acc_at(result, full):
+    return np.concatenate([full.acc[result.retained], np.zeros(result.cache.budget - result.retained.shape[0])])

@@ -12,6 +12,7 @@ using namespace roco;
 
 constexpr size_t kAlign = 256;
 constexpr int kStreamingAboveMiB = 192;
+constexpr int kMaxPrefillGroup = 64;  // query heads per key/value head in the grouped-query prefill
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -51,13 +52,13 @@ DecodeLayout decode_layout(const roco_params* p) {
   return l;
 }
 
-// ---- prefill workspace: lse | acc | acc2 | var_key | mas_key, each [units][L_max]
+// ---- prefill workspace: acc | acc2 | var_key | mas_key, each [units][L_max], then lse [units][group][L_max]
 struct PrefillLayout { size_t lse, acc, acc2, var_key, mas_key, total; };
-PrefillLayout prefill_layout(const roco_params* p, int32_t L_max) {
+PrefillLayout prefill_layout(const roco_params* p, int32_t L_max, int32_t group) {
   PrefillLayout l;
   const size_t plane = align_up(static_cast<size_t>(p->units) * L_max * sizeof(float));
-  l.lse = 0; l.acc = plane; l.acc2 = 2 * plane; l.var_key = 3 * plane; l.mas_key = 4 * plane;
-  l.total = 5 * plane;
+  l.acc = 0; l.acc2 = plane; l.var_key = 2 * plane; l.mas_key = 3 * plane; l.lse = 4 * plane;
+  l.total = 4 * plane + align_up(static_cast<size_t>(p->units) * group * L_max * sizeof(float));
   return l;
 }
 
@@ -132,7 +133,13 @@ extern "C" {
 
 size_t roco_prefill_workspace_bytes(const roco_params* params, int32_t L_max) {
   if (check_params(params) != ROCO_OK || L_max < 1) return 0;
-  return prefill_layout(params, L_max).total;
+  return prefill_layout(params, L_max, 1).total;
+}
+
+size_t roco_prefill_gqa_workspace_bytes(const roco_params* params, int32_t group, int32_t L_max) {
+  if (check_params(params) != ROCO_OK || L_max < 1 || group < 1 || group > kMaxPrefillGroup) return 0;
+  if (static_cast<long long>(params->units) * group > 65535) return 0;
+  return prefill_layout(params, L_max, group).total;
 }
 
 size_t roco_decode_workspace_bytes(const roco_params* params) {
@@ -146,22 +153,29 @@ int roco_decode_step_launches(const roco_params* params) {
   return decode_is_fused(params) ? 1 : 2;
 }
 
-int roco_prefill_compress(const roco_params* params, const void* Q, const void* K, const void* V,
-                          const int32_t* len, int32_t L_max, void* K_cache, void* V_cache, float* stats,
-                          int32_t* pos, int32_t* n_used, int32_t* next_slot, void* O, void* workspace,
-                          size_t workspace_bytes, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+// roco_prefill_compress (group == 1) and roco_prefill_compress_gqa
+int run_prefill(const roco_params* params, int group, const void* Q, const void* K, const void* V,
+                const int32_t* len, int32_t L_max, void* K_cache, void* V_cache, float* stats,
+                int32_t* pos, int32_t* n_used, int32_t* next_slot, void* O, void* workspace,
+                size_t workspace_bytes, void* hip_stream) {
   const int rc = check_params(params);
   if (rc != ROCO_OK) return rc;
   if (L_max < 1 || L_max > (1 << 24)) return ROCO_EINVAL;
+  if (group < 1) return ROCO_EINVAL;
+  if (group > kMaxPrefillGroup || static_cast<long long>(params->units) * group > 65535) return ROCO_EUNSUPPORTED;
   const void* need[] = {Q, K, V, len, K_cache, V_cache, stats, pos, n_used, next_slot, workspace};
   for (const void* ptr : need)
     if (ptr == nullptr || !aligned16(ptr)) return ROCO_EINVAL;
   if (O != nullptr && !aligned16(O)) return ROCO_EINVAL;
-  const PrefillLayout lay = prefill_layout(params, L_max);
+  const PrefillLayout lay = prefill_layout(params, L_max, group);
   if (workspace_bytes < lay.total) return ROCO_EWORKSPACE;
 
   PrefillArgs a;
   a.units = params->units; a.L_max = L_max; a.B = params->budget; a.scope = params->scope;
+  a.group = group;
   a.pol = policy_of(params);
   a.pairs = 0;
   a.paired = env_int("ROCO_PREFILL_PAIRED", -1);
@@ -179,7 +193,7 @@ int roco_prefill_compress(const roco_params* params, const void* Q, const void* 
   a.mas_key = reinterpret_cast<uint32_t*>(ws + lay.mas_key);
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const bool mfma = params->dtype == ROCO_BF16 && params->head_dim == 128 &&
+  const bool mfma = params->dtype == ROCO_BF16 && params->head_dim == 128 && group == 1 &&
                     env_int("ROCO_PREFILL_SIMPLE", 0) == 0;
   hipError_t e = mfma ? launch_prefill_attention_mfma(a, s)
                       : launch_prefill_attention_simple(params->dtype, params->head_dim, a, s);
@@ -190,6 +204,25 @@ int roco_prefill_compress(const roco_params* params, const void* Q, const void* 
   }
   e = launch_prefill_select_compact(params->dtype, params->head_dim, a, s);
   return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
+}
+}  // namespace
+
+extern "C" {
+
+int roco_prefill_compress(const roco_params* params, const void* Q, const void* K, const void* V,
+                          const int32_t* len, int32_t L_max, void* K_cache, void* V_cache, float* stats,
+                          int32_t* pos, int32_t* n_used, int32_t* next_slot, void* O, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+  return run_prefill(params, 1, Q, K, V, len, L_max, K_cache, V_cache, stats, pos, n_used, next_slot, O, workspace,
+                     workspace_bytes, hip_stream);
+}
+
+int roco_prefill_compress_gqa(const roco_params* params, int32_t group, const void* Q, const void* K, const void* V,
+                              const int32_t* len, int32_t L_max, void* K_cache, void* V_cache, float* stats,
+                              int32_t* pos, int32_t* n_used, int32_t* next_slot, void* workspace,
+                              size_t workspace_bytes, void* hip_stream) {
+  return run_prefill(params, group, Q, K, V, len, L_max, K_cache, V_cache, stats, pos, n_used, next_slot, nullptr,
+                     workspace, workspace_bytes, hip_stream);
 }
 
 int roco_decode_step(const roco_params* params, const void* q, const void* k_new, const void* v_new,

@@ -54,6 +54,7 @@ struct DecodeArgs {
 
 struct PrefillArgs {
   int units, L_max, B, scope;
+  int group;             // query heads per unit (1 without grouped-query attention): Q and lse are [units][group][L_max]
   Policy pol;
   int pairs;             // matrix-core path: workgroup ids per unit (set by its launcher)
   int paired;            // matrix-core path: 1 = long+short block per workgroup, 0 = one block, -1 = choose
@@ -69,7 +70,7 @@ struct PrefillArgs {
   int32_t* next_slot;    // [units]
   void* O;               // may be null
   // workspace
-  float* lse;            // [units][L_max]  base-2 log-sum-exp of every query row
+  float* lse;            // [units][group][L_max]  base-2 log-sum-exp of every query row
   float* acc;            // [units][L_max]
   float* acc2;           // [units][L_max]
   uint32_t* var_key;     // [units][L_max]

@@ -21,19 +21,21 @@ constexpr int kUnroll = 4;
 template <int DT, int D>
 __global__ __launch_bounds__(kThreads) void prefill_rows_simple(PrefillArgs a) {
   using G = RowGeom<DT, D>;
-  const int u = blockIdx.y;
+  const int uq = blockIdx.y;       // (unit, query head)
+  const int uk = uq / a.group;     // the unit: its keys, values and length
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int c = lane % G::LPR;
   const int i = blockIdx.x * kWaves + wave;
-  const int len = a.len[u];
+  const int len = a.len[uk];
   if (i >= len) return;
-  const size_t ubase = static_cast<size_t>(u) * a.L_max;
+  const size_t ubase = static_cast<size_t>(uq) * a.L_max;
+  const size_t kbase = static_cast<size_t>(uk) * a.L_max;
   float qf[G::EPL];
   unpack16<DT>(load16(static_cast<const char*>(a.Q) + (ubase + i) * G::ROW_BYTES + c * 16), qf);
 #pragma unroll
   for (int e = 0; e < G::EPL; ++e) qf[e] *= a.scale_log2;
-  const char* Kb = static_cast<const char*>(a.K) + ubase * G::ROW_BYTES;
-  const char* Vb = static_cast<const char*>(a.V) + ubase * G::ROW_BYTES;
+  const char* Kb = static_cast<const char*>(a.K) + kbase * G::ROW_BYTES;
+  const char* Vb = static_cast<const char*>(a.V) + kbase * G::ROW_BYTES;
   const int w = a.recency_window;
   const float rb = a.recency_bias_log2;
   FlashState<G::EPL> st;
@@ -70,36 +72,47 @@ __global__ __launch_bounds__(kThreads) void prefill_columns_simple(PrefillArgs a
   unpack16<DT>(load16(static_cast<const char*>(a.K) + (ubase + j) * G::ROW_BYTES + c * 16), kf);
 #pragma unroll
   for (int e = 0; e < G::EPL; ++e) kf[e] *= a.scale_log2;
-  const char* Qb = static_cast<const char*>(a.Q) + ubase * G::ROW_BYTES;
-  const float* lse = a.lse + ubase;
   const int w = a.recency_window;
   const float rb = a.recency_bias_log2;
+  const float inv_heads = 1.0f / static_cast<float>(a.group);
   float s1 = 0.0f, s2 = 0.0f;
   for (int base = j; base < len; base += U * G::R) {
-    uint4 qw[U];
-    float ls[U];
+    float pbar[U];  // sum over the unit's query heads of P[row, j] (one head without grouped-query attention)
 #pragma unroll
-    for (int x = 0; x < U; ++x) {
-      const int row = base + x * G::R + g;
-      const int r = row < len ? row : j;
-      qw[x] = load16(Qb + static_cast<size_t>(r) * G::ROW_BYTES + c * 16);
-      ls[x] = lse[r];
+    for (int x = 0; x < U; ++x) pbar[x] = 0.0f;
+    for (int h = 0; h < a.group; ++h) {
+      const size_t qbase = (static_cast<size_t>(u) * a.group + h) * a.L_max;
+      const char* Qb = static_cast<const char*>(a.Q) + qbase * G::ROW_BYTES;
+      const float* lse = a.lse + qbase;
+      uint4 qw[U];
+      float ls[U];
+#pragma unroll
+      for (int x = 0; x < U; ++x) {
+        const int row = base + x * G::R + g;
+        const int r = row < len ? row : j;
+        qw[x] = load16(Qb + static_cast<size_t>(r) * G::ROW_BYTES + c * 16);
+        ls[x] = lse[r];
+      }
+#pragma unroll
+      for (int x = 0; x < U; ++x) {
+        const int row = base + x * G::R + g;
+        float qf[G::EPL];
+        unpack16<DT>(qw[x], qf);
+        float dot = 0.0f;
+#pragma unroll
+        for (int e = 0; e < G::EPL; ++e) dot = fmaf(qf[e], kf[e], dot);
+        dot = group_sum<G::LPR>(dot);
+        if (row < len) {
+          const float t = dot + ((row - j < w) ? rb : 0.0f);
+          pbar[x] += exp2f(t - ls[x]);
+        }
+      }
     }
 #pragma unroll
     for (int x = 0; x < U; ++x) {
-      const int row = base + x * G::R + g;
-      float qf[G::EPL];
-      unpack16<DT>(qw[x], qf);
-      float dot = 0.0f;
-#pragma unroll
-      for (int e = 0; e < G::EPL; ++e) dot = fmaf(qf[e], kf[e], dot);
-      dot = group_sum<G::LPR>(dot);
-      if (row < len) {
-        const float t = dot + ((row - j < w) ? rb : 0.0f);
-        const float p = exp2f(t - ls[x]);
-        s1 += p;
-        s2 = fmaf(p, p, s2);
-      }
+      const float p = pbar[x] * inv_heads;  // rows past the end contribute exactly zero
+      s1 += p;
+      s2 = fmaf(p, p, s2);
     }
   }
 #pragma unroll
@@ -118,7 +131,8 @@ hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
   const dim3 grid((a.L_max + kWaves - 1) / kWaves, a.units);
   {
     ProfScope ps(kProfPrefillRows, s);
-    hipLaunchKernelGGL((prefill_rows_simple<DT, D>), grid, dim3(kThreads), 0, s, a);
+    const dim3 rows_grid(grid.x, static_cast<unsigned>(a.units) * a.group);
+    hipLaunchKernelGGL((prefill_rows_simple<DT, D>), rows_grid, dim3(kThreads), 0, s, a);
   }
   {
     ProfScope ps(kProfPrefillColumns, s);
@@ -139,25 +153,28 @@ __global__ __launch_bounds__(kThreads) void prefill_last_row(PrefillArgs a) {
   const int len = a.len[u];
   const int last = len - 1;
   const size_t ubase = static_cast<size_t>(u) * a.L_max;
-  float qf[G::EPL];
-  unpack16<DT>(load16(static_cast<const char*>(a.Q) + (ubase + last) * G::ROW_BYTES + c * 16), qf);
-#pragma unroll
-  for (int e = 0; e < G::EPL; ++e) qf[e] *= a.scale_log2;
   const char* Kb = static_cast<const char*>(a.K) + ubase * G::ROW_BYTES;
-  const float lse_last = a.lse[ubase + last];
   const int w = a.recency_window;
   const float rb = a.recency_bias_log2;
+  const float inv_heads = 1.0f / static_cast<float>(a.group);
   for (int base = wave * G::R; base < len; base += kWaves * G::R) {
     const int j = base + g;
     const int jc = j < len ? j : last;
     float kf[G::EPL];
     unpack16<DT>(load16(Kb + static_cast<size_t>(jc) * G::ROW_BYTES + c * 16), kf);
-    float dot = 0.0f;
+    float pbar = 0.0f;
+    for (int h = 0; h < a.group; ++h) {  // the unit's query heads (one without grouped-query attention)
+      const size_t qbase = (static_cast<size_t>(u) * a.group + h) * a.L_max;
+      float qf[G::EPL];
+      unpack16<DT>(load16(static_cast<const char*>(a.Q) + (qbase + last) * G::ROW_BYTES + c * 16), qf);
+      float dot = 0.0f;
 #pragma unroll
-    for (int e = 0; e < G::EPL; ++e) dot = fmaf(qf[e], kf[e], dot);
-    dot = group_sum<G::LPR>(dot);
-    if (w > 0 && last - jc < w) dot += rb;
-    if (c == 0 && j < len) a.acc2[ubase + j] = fast_exp2(dot - lse_last);
+      for (int e = 0; e < G::EPL; ++e) dot = fmaf(qf[e] * a.scale_log2, kf[e], dot);
+      dot = group_sum<G::LPR>(dot);
+      if (w > 0 && last - jc < w) dot += rb;
+      pbar += fast_exp2(dot - a.lse[qbase + last]);
+    }
+    if (c == 0 && j < len) a.acc2[ubase + j] = pbar * inv_heads;
   }
 }
 

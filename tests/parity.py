@@ -358,3 +358,20 @@ def lockstep_block_gqa_unit(state: "orc.CacheState", u: int, g_out, g_slot, g_po
         for h in range(g):
             assert_out_close(g_out[u, i, h], r.out[i, h], dtype, f"{what} unit {u} token {i} head {h} out")
     return ties
+
+
+def gpu_prefill_gqa(sess: GpuSession, group: int, Q: np.ndarray, K: np.ndarray, V: np.ndarray, lens: Sequence[int]):
+    """Q: [units, group, L_max, d]; K, V: [units, L_max, d] float32 host arrays.  Host copies of what was written."""
+    U, g, L_max, d = Q.shape
+    p = sess.params
+    assert U == p.units and d == p.head_dim and g == group
+    dQ, dK, dV = to_dev(Q, sess.dtype), to_dev(K, sess.dtype), to_dev(V, sess.dtype)
+    dlen = torch.tensor(list(lens), dtype=torch.int32, device="cuda")
+    sess.prefill_ws = torch.empty(max(16, roco.prefill_gqa_workspace_bytes(p, group, L_max)), dtype=torch.uint8,
+                                  device="cuda")
+    c = sess.cache
+    roco.roco_prefill_compress_gqa(p, group, dQ, dK, dV, dlen, L_max, c.K, c.V, c.stats, c.pos, c.n_used, c.next_slot,
+                                   sess.prefill_ws)
+    torch.cuda.synchronize()
+    return dict(K=to_host(c.K), V=to_host(c.V), stats=to_host(c.stats), pos=to_host(c.pos), n_used=to_host(c.n_used),
+                O=None)

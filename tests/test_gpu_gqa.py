@@ -84,6 +84,64 @@ def test_grouped_steps_with_recency_bias_and_a_larger_budget():
     drive(2, 1024, 48, 4, [8] * 130 + [1] * 8, seed=97, recency=True, tag="gqa-recency", single_token_entry=True)
 
 
+def run_grouped_prefill(dtype, d, group, lens, L, B, s, seed, steps=6, recency=False, policy=None, tag=""):
+    """roco_prefill_compress_gqa against the oracle, then grouped decode steps from the compressed caches."""
+    import paper_2402_06262_amd as roco
+    P = _P()
+    units = len(lens)
+    sc = 1.0 / math.sqrt(d)
+    rng = np.random.default_rng(seed)
+    Q = rng.standard_normal((units, group, L + steps, d)).astype(np.float32) + 0.25
+    K = rng.standard_normal((units, L + steps, d)).astype(np.float32)
+    V = rng.standard_normal((units, L + steps, d)).astype(np.float32)
+    heavy = rng.choice(L, size=max(1, L // 40), replace=False)
+    K[:, heavy] += 2.0
+    if dtype == "bf16":
+        Q, K, V = round_to_bf16(Q), round_to_bf16(K), round_to_bf16(V)
+    rw, rb = (24, 0.5) if recency else (0, 0.0)
+    sess = P.make_session(units, d, B, s, dtype, 0.0, rw, rb, policy=policy)
+    print(f"[{tag}] grouped prefill {dtype} d={d} g={group} lens={lens} B={B}", flush=True)
+    g_res = P.gpu_prefill_gqa(sess, group, Q[:, :, :L].copy(), K[:, :L].copy(), V[:, :L].copy(), lens)
+    ties = P.TieCount()
+    states = []
+    for u in range(units):
+        full = orc.prefill_statistics_gqa(Q[u, :, :L], K[u, :L], V[u, :L], lens[u], sc, rw, rb, policy=policy)
+        res, t = P.check_prefill_unit(g_res, u, None, K[u, :L], V[u, :L], lens[u], B, s, sc, dtype, rw, rb, False,
+                                      full=full, policy=policy)
+        ties += t
+        states.append(res.cache)
+    ws = torch.empty(roco.block_workspace_bytes(sess.params, 1), dtype=torch.uint8, device="cuda")
+    nxt = list(lens)
+    for i in range(steps):
+        t = L + i
+        o, es, ep = P.gpu_decode_step_gqa(sess, group, Q[:, :, t], K[:, t], V[:, t], nxt, ws)
+        for u in range(units):
+            ties += P.lockstep_block_gqa_unit(states[u], u, o[:, None], es[:, None], ep[:, None], Q[u, :, t][None],
+                                              K[u, t:t + 1], V[u, t:t + 1], nxt[u], s, sc, dtype, rw, rb,
+                                              what=f"[{tag}] step {i}")
+        nxt = [x + 1 for x in nxt]
+    host = P.cache_to_host(sess)
+    for u in range(units):
+        P.check_cache_unit(host, u, states[u], what=f"[{tag}] end")
+    print(f"[{tag}] ties {ties}", flush=True)
+
+
+@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128), ("bf16", 64)])
+@pytest.mark.parametrize("group", [1, 2, 4])
+def test_grouped_prefill_then_grouped_decode(dtype, d, group):
+    run_grouped_prefill(dtype, d, group, [300, 257, 130, 60], 300, 128, 14, seed=500 + group + d,
+                        tag=f"gqa-prefill-{dtype}-{d}-g{group}")
+
+
+def test_grouped_prefill_with_recency_bias_and_three_heads():
+    run_grouped_prefill("bf16", 128, 3, [200, 77], 200, 64, 9, seed=520, recency=True, tag="gqa-prefill-recency")
+
+
+def test_grouped_prefill_under_the_last_token_score():
+    run_grouped_prefill("bf16", 128, 4, [260, 150], 260, 96, 96, seed=530, policy=orc.Policy("ltas", "all"),
+                        tag="gqa-prefill-ltas", steps=0)
+
+
 def test_grouped_decode_at_the_serving_shape():
     """The shape bench.py times for g = 4: 128 key/value heads (batch 16 x 8), B = 2048, scope 64, full cache.
     All units step on the GPU; properties on every unit, the oracle in lock-step on a sample."""

@@ -157,14 +157,15 @@ template <int WAVES>
 __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_mfma(PrefillArgs a) {
   constexpr int kOwn = Shape<WAVES>::kOwn;
   __shared__ __attribute__((aligned(16))) char lds[2][kTile * kLdsRow];
-  int u, pair_id;
-  if (!locate(a.units, a.pairs, u, pair_id)) return;
-  const int len = a.len[u];
+  int u, pair_id;  // u counts (unit, query head) pairs: with grouped-query attention a unit has a.group heads
+  if (!locate(a.units * a.group, a.pairs, u, pair_id)) return;
+  const int uk = u / a.group;  // the unit: its keys and its length
+  const int len = a.len[uk];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int half = lane >> 5;
   const size_t ubase = static_cast<size_t>(u) * a.L_max;
   const char* Qb = static_cast<const char*>(a.Q) + ubase * kRowBytes;
-  const char* Kb = static_cast<const char*>(a.K) + ubase * kRowBytes;
+  const char* Kb = static_cast<const char*>(a.K) + static_cast<size_t>(uk) * a.L_max * kRowBytes;
   const float sc = a.scale_log2;
   const int w = a.recency_window;
   const float rb = a.recency_bias_log2;
@@ -347,6 +348,158 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_mfma(PrefillArg
 }
 
 // ------------------------------------------------------------------------------------------------
+// pass 2 for grouped-query attention (section 5.3): the unit's keys are shared by g query heads and the statistics
+// are taken on the head-mean probability, Acc[j] = sum_i Pbar[i,j], Acc2[j] = sum_i Pbar[i,j]^2 with
+// Pbar = mean_h P_h.  Same shape as prefill_columns_mfma, but the streamed tile holds one block of 32 queries for
+// two heads (rows 0-31: head 2k, rows 32-63: head 2k+1), so that the sum over the heads of a probability stays in
+// the lane's registers between tiles; after the last pair of heads it is scaled, added and squared.
+template <int WAVES>
+__device__ __forceinline__ void tile_load_two(Staged<WAVES>& s, const char* base0, const char* base1, int row0,
+                                              int last_row) {
+  const int t = threadIdx.x;
+  constexpr int kHalf = Shape<WAVES>::kChunks / 2;
+#pragma unroll
+  for (int i = 0; i < Shape<WAVES>::kChunks; ++i) {
+    int row = row0 + (t >> 4) + Shape<WAVES>::kRowsPerSweep * (i % kHalf);
+    row = row < last_row ? row : last_row;  // rows past the end are masked by the caller
+    s.w[i] = load16((i < kHalf ? base0 : base1) + static_cast<size_t>(row) * kRowBytes + (t & 15) * 16);
+  }
+}
+
+// The 16 probabilities of a tile (one key, 16 queries of one head) added into `pb` (or stored, for the first head).
+template <bool INTERIOR>
+__device__ __forceinline__ void column_probs(const f32x16& s, const float* lse_tile, float sc, int ib, int half,
+                                             int kj, int len, int w, float rb, bool first, f32x16& pb) {
+#pragma unroll
+  for (int g4 = 0; g4 < 4; ++g4) {
+    const float4 ls = *reinterpret_cast<const float4*>(lse_tile + 8 * g4 + 4 * half);
+    const float lv[4] = {ls.x, ls.y, ls.z, ls.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float x = fmaf(s[4 * g4 + e], sc, -lv[e]);
+      float p;
+      if (INTERIOR) {
+        p = fast_exp2(x);
+      } else {
+        const int qi = ib + 8 * g4 + 4 * half + e;
+        if (w > 0 && qi - kj < w) x += rb;
+        p = fast_exp2(x);
+        if (qi < kj || qi >= len) p = 0.0f;
+      }
+      pb[4 * g4 + e] = first ? p : pb[4 * g4 + e] + p;
+    }
+  }
+}
+
+template <int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void prefill_columns_gqa_mfma(PrefillArgs a) {
+  constexpr int kOwn = Shape<WAVES>::kOwn;
+  static_assert(Shape<WAVES>::kChunks % 2 == 0, "half a staged tile per head");
+  __shared__ __attribute__((aligned(16))) char lds[2][kTile * kLdsRow];
+  __shared__ __attribute__((aligned(16))) float lse_s[2][kTile];
+  int u, pair_id;
+  if (!locate(a.units, a.pairs, u, pair_id)) return;
+  const int G = a.group, HP = (G + 1) / 2;  // head pairs per block of 32 queries
+  const float inv_heads = 1.0f / static_cast<float>(G);
+  const int len = a.len[u];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int half = lane >> 5;
+  const size_t ubase = static_cast<size_t>(u) * a.L_max;
+  const char* Kb = static_cast<const char*>(a.K) + ubase * kRowBytes;
+  auto q_of = [&](int h) { return static_cast<const char*>(a.Q) + (static_cast<size_t>(u) * G + h) * a.L_max * kRowBytes; };
+  auto lse_of = [&](int h) { return a.lse + (static_cast<size_t>(u) * G + h) * a.L_max; };
+  const float sc = a.scale_log2;
+  const int w = a.recency_window;
+  const float rb = a.recency_bias_log2;
+  const int n_blocks = (len + kOwn - 1) / kOwn;
+  if (a.paired ? 2 * pair_id > n_blocks - 1 : pair_id >= n_blocks) return;  // nothing left for this id
+
+  for (int pass = 0; pass < 2; ++pass) {  // one long and one short block of keys per workgroup
+    int blk;
+    if (a.paired) {
+      blk = pass == 0 ? pair_id : n_blocks - 1 - pair_id;
+      if (blk < pair_id || (pass == 1 && blk == pair_id)) break;
+    } else {
+      if (pass == 1) break;
+      blk = n_blocks - 1 - pair_id;
+    }
+    const int j0 = blk * kOwn;
+    const int kw0 = j0 + 64 * wave;
+    const int kj0 = kw0 + (lane & 31), kj1 = kj0 + 32;  // this lane's two keys
+    uint4 own0[kKSteps], own1[kKSteps];
+    load_owned(own0, Kb, kj0, len - 1);
+    load_owned(own1, Kb, kj1, len - 1);
+    float s1a = 0.0f, s2a = 0.0f, s1b = 0.0f, s2b = 0.0f;
+    f32x16 pb0 = {0}, pb1 = {0};  // sums over the heads, for this lane's two keys
+
+    const int r_first = j0 / 32;         // first block of 32 queries with a query >= j0
+    const int r_last = (len - 1) / 32;
+    const int n_it = (r_last - r_first + 1) * HP;
+    Staged<WAVES> stA;
+    float lseA = 0.0f;
+    auto fetch = [&](Staged<WAVES>& st, float& lse_st, int it) {
+      const int r = r_first + it / HP, hp = it % HP;
+      const int h0 = 2 * hp, h1 = min(2 * hp + 1, G - 1);  // an odd group repeats its last head; that half is skipped
+      tile_load_two<WAVES>(st, q_of(h0), q_of(h1), r * 32, len - 1);
+      if (threadIdx.x < kTile) {
+        const int t = threadIdx.x;
+        lse_st = lse_of(t < 32 ? h0 : h1)[min(r * 32 + (t & 31), len - 1)];
+      }
+    };
+    fetch(stA, lseA, 0);
+    __syncthreads();  // the previous pass has finished with the LDS buffers
+    for (int it = 0; it < n_it; ++it) {
+      const int b = it & 1;
+      tile_store(stA, lds[b]);
+      if (threadIdx.x < kTile) lse_s[b][threadIdx.x] = lseA;
+      __syncthreads();
+      if (it + 1 < n_it) fetch(stA, lseA, it + 1);
+      const int r = r_first + it / HP, hp = it % HP;
+      const int ib = r * 32;
+      const bool do0 = ib + 31 >= kw0, do1 = ib + 31 >= kw0 + 32;  // some query of the block reaches the keys
+      if (!do0) continue;  // wave-uniform, and the same for every head of the block
+      const bool whole = w == 0 && ib + 31 < len;  // no ragged end, no bias
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+        const int h = 2 * hp + sub;
+        if (h >= G) break;
+        f32x16 c0, c1;
+        score_tiles(lds[b], sub, own0, own1, do0, do1, c0, c1);
+        const float* lt = &lse_s[b][sub * 32];
+        if (whole && ib >= kw0 + 31) column_probs<true>(c0, lt, sc, ib, half, kj0, len, w, rb, h == 0, pb0);
+        else column_probs<false>(c0, lt, sc, ib, half, kj0, len, w, rb, h == 0, pb0);
+        if (do1) {
+          if (whole && ib >= kw0 + 63) column_probs<true>(c1, lt, sc, ib, half, kj1, len, w, rb, h == 0, pb1);
+          else column_probs<false>(c1, lt, sc, ib, half, kj1, len, w, rb, h == 0, pb1);
+        }
+      }
+      if (hp == HP - 1) {  // every head of this block of queries has been added
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const float p = pb0[e] * inv_heads;
+          s1a += p;
+          s2a = fmaf(p, p, s2a);
+        }
+        if (do1) {
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const float p = pb1[e] * inv_heads;
+            s1b += p;
+            s2b = fmaf(p, p, s2b);
+          }
+        }
+      }
+    }
+    s1a += __shfl_xor(s1a, 32, kWave);
+    s2a += __shfl_xor(s2a, 32, kWave);
+    s1b += __shfl_xor(s1b, 32, kWave);
+    s2b += __shfl_xor(s2b, 32, kWave);
+    if (half == 0 && kj0 < len) { a.acc[ubase + kj0] = s1a; a.acc2[ubase + kj0] = s2a; }
+    if (half == 0 && kj1 < len) { a.acc[ubase + kj1] = s1b; a.acc2[ubase + kj1] = s2b; }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // pass 1 with the attention output:  O_i = sum_j P[i,j] v_j  next to lse[i]            (section 2.1, eq. 1)
 //
 // Same orientation as prefill_rows_mfma (score tile = K . Q^T, the query in the lane), one group of 32 queries
@@ -505,13 +658,15 @@ hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
   b.paired = a.paired >= 0 ? a.paired : 1;  // pairing measured faster than lock-step single blocks
   b.pairs = b.paired ? (n_blocks + 1) / 2 : n_blocks;  // ids per unit
   const dim3 grid(static_cast<unsigned>((a.units + 7) / 8 * 8 * b.pairs));
+  const dim3 rows_grid(static_cast<unsigned>((a.units * a.group + 7) / 8 * 8 * b.pairs));  // one id set per query head
   {
     ProfScope ps(kProfPrefillRows, s);
-    hipLaunchKernelGGL(prefill_rows_mfma<WAVES>, grid, dim3(WAVES * kWave), 0, s, b);
+    hipLaunchKernelGGL(prefill_rows_mfma<WAVES>, rows_grid, dim3(WAVES * kWave), 0, s, b);
   }
   {
     ProfScope ps(kProfPrefillColumns, s);
-    hipLaunchKernelGGL(prefill_columns_mfma<WAVES>, grid, dim3(WAVES * kWave), 0, s, b);
+    if (a.group == 1) hipLaunchKernelGGL(prefill_columns_mfma<WAVES>, grid, dim3(WAVES * kWave), 0, s, b);
+    else hipLaunchKernelGGL(prefill_columns_gqa_mfma<WAVES>, grid, dim3(WAVES * kWave), 0, s, b);
   }
   return hipGetLastError();
 }
@@ -552,7 +707,7 @@ hipError_t launch_with_output(const PrefillArgs& a, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_prefill_attention_mfma(const PrefillArgs& a, hipStream_t s) {
-  if (a.O != nullptr) return launch_with_output(a, s);
+  if (a.O != nullptr) return a.group == 1 ? launch_with_output(a, s) : hipErrorInvalidValue;
   // 256 owned rows per workgroup by default.  512 halve the streamed traffic but leave one workgroup per
   // compute unit, all of whose waves wait at the same barriers; measured slower on the serving workload.
   return a.mfma_waves == 8 ? launch_t<8>(a, s) : launch_t<4>(a, s);

@@ -142,6 +142,55 @@ def test_grouped_prefill_under_the_last_token_score():
                         tag="gqa-prefill-ltas", steps=0)
 
 
+@pytest.mark.timeout(600)
+def test_grouped_prefill_at_the_serving_shape():
+    """128 key/value heads x 4 query heads (batch 16 x 8), prompt 3072 -> B = 2048, scope 64: every unit on the GPU,
+    properties on all of them, the oracle on a sample."""
+    import paper_2402_06262_amd as roco
+    P = _P()
+    U, g, d, L, B, s = 128, 4, 128, 3072, 2048, 64
+    sc = 1.0 / math.sqrt(d)
+    rng = np.random.default_rng(777)
+    sample = [0, 101]
+    dt = torch.bfloat16
+    dQ = torch.empty((U, g, L, d), dtype=dt, device="cuda")
+    dK = torch.empty((U, L, d), dtype=dt, device="cuda")
+    dV = torch.empty_like(dK)
+    host = {}
+    for u in range(U):
+        q = rng.standard_normal((g, L, d), dtype=np.float32) + 0.25
+        k = rng.standard_normal((L, d), dtype=np.float32)
+        v = rng.standard_normal((L, d), dtype=np.float32)
+        k[rng.choice(L, size=60, replace=False)] += 1.5
+        dQ[u], dK[u], dV[u] = (torch.from_numpy(x).cuda().to(dt) for x in (q, k, v))
+        if u in sample:
+            host[u] = tuple(t.float().cpu().numpy() for t in (dQ[u], dK[u], dV[u]))
+    sess = P.make_session(U, d, B, s, "bf16")
+    c, p = sess.cache, sess.params
+    ws = torch.empty(roco.prefill_gqa_workspace_bytes(p, g, L), dtype=torch.uint8, device="cuda")
+    dlen = torch.full((U,), L, dtype=torch.int32, device="cuda")
+    print("[gqa-prefill-serving] prefill", flush=True)
+    roco.roco_prefill_compress_gqa(p, g, dQ, dK, dV, dlen, L, c.K, c.V, c.stats, c.pos, c.n_used, c.next_slot, ws)
+    torch.cuda.synchronize()
+    pos = c.pos.long()
+    assert bool((c.n_used == B).all()) and bool((pos[:, 1:] > pos[:, :-1]).all()) and int(pos.min()) >= 0 and int(pos.max()) < L
+    assert bool((c.stats[:, 2] == (L - pos).float()).all())
+    idx = pos[:, :, None].expand(U, B, d)
+    assert torch.equal(torch.gather(dK, 1, idx), c.K) and torch.equal(torch.gather(dV, 1, idx), c.V)
+    assert bool((c.next_slot >= 0).all()) and bool((c.next_slot < B).all())
+    sidx = torch.tensor(sample, device="cuda")
+    g_res = dict(K=P.to_host(c.K[sidx]), V=P.to_host(c.V[sidx]), stats=P.to_host(c.stats[sidx]),
+                 pos=P.to_host(c.pos[sidx]), n_used=P.to_host(c.n_used[sidx]), O=None)
+    ties = P.TieCount()
+    for k_, u in enumerate(sample):
+        Qh, Kh, Vh = host[u]
+        print(f"[gqa-prefill-serving] oracle statistics of unit {u}", flush=True)
+        full = orc.prefill_statistics_gqa(Qh, Kh, Vh, L, sc)
+        _, t = P.check_prefill_unit(g_res, k_, None, Kh, Vh, L, B, s, sc, "bf16", 0, 0.0, False, full=full)
+        ties += t
+    print(f"[gqa-prefill-serving] ties {ties}", flush=True)
+
+
 def test_grouped_decode_at_the_serving_shape():
     """The shape bench.py times for g = 4: 128 key/value heads (batch 16 x 8), B = 2048, scope 64, full cache.
     All units step on the GPU; properties on every unit, the oracle in lock-step on a sample."""

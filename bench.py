@@ -321,7 +321,7 @@ def main():
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record(stream)
                 roco.roco_prefill_compress_gqa(pg, g, gQ, dK[:Ug], dV[:Ug], glen, L, cg.K, cg.V, cg.stats, cg.pos,
-                                               cg.n_used, cg.next_slot, ws_pg, stream=stream)
+                                               cg.n_used, cg.next_slot, None, ws_pg, stream=stream)
                 e1.record(stream)
                 torch.cuda.synchronize()
                 ptimes.append(e0.elapsed_time(e1))

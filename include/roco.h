@@ -131,15 +131,16 @@ int roco_prefill_compress(const roco_params* params,
  * unit is one key/value head shared by `group` query heads (1 <= group <= 64, units * group <= 65535; else
  * ROCO_EUNSUPPORTED).  Every query head has its own causal softmax; Acc and Acc2 are taken on the mean of the
  * group's probability matrices, Pbar[i,j] = mean_h P_h[i,j]: Acc[j] = sum_i Pbar[i,j], Acc2[j] = sum_i Pbar[i,j]^2.
- * Eviction, compaction and every output are those of roco_prefill_compress; no attention output is produced.
- * Q in [units, group, L_max, d]; K, V in [units, L_max, d]; workspace of roco_prefill_gqa_workspace_bytes.
+ * Eviction, compaction and every output are those of roco_prefill_compress.
+ * Q in [units, group, L_max, d]; K, V in [units, L_max, d]; O out [units, group, L_max, d] (the attention output of
+ * every query head and prompt row) or NULL; workspace of roco_prefill_gqa_workspace_bytes.
  */
 size_t roco_prefill_gqa_workspace_bytes(const roco_params* params, int32_t group, int32_t L_max);
 int roco_prefill_compress_gqa(const roco_params* params, int32_t group,
                               const void* Q, const void* K, const void* V,
                               const int32_t* len, int32_t L_max,
                               void* K_cache, void* V_cache, float* stats, int32_t* pos, int32_t* n_used,
-                              int32_t* next_slot,
+                              int32_t* next_slot, void* O,
                               void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*

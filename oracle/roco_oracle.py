@@ -593,23 +593,29 @@ def select_retained(state: CacheState, keep: int, scope: int, policy: Optional[P
 # ---------------------------------------------------------------------------
 
 def prefill_statistics_gqa(Qg, K, V, length: int, scale: float, recency_window: int = 0,
-                           recency_bias: float = 0.0, row_block: int = 512, policy=None) -> PrefillStats:
+                           recency_bias: float = 0.0, row_block: int = 512, policy=None,
+                           want_out: bool = False) -> PrefillStats:
     """Column statistics of the group-wise averaged causal attention matrix: Qg is [g, length, d].
 
     Every query head has its own causal softmax (section 2.1, eq. 1); the statistics of the shared key/value
     head are taken on the mean of the g probability matrices (section 5.3, grouped-query extension):
     Acc[j] = sum_i Pbar[i,j], Acc2[j] = sum_i Pbar[i,j]^2 (or the last row of Pbar under the last-token score),
-    Count[j] = length - j.  No attention output is produced here."""
+    Count[j] = length - j.  `out`, if asked for, is [g, length, d]: every head's own attention output."""
     Qg = np.asarray(Qg, dtype=F64)
     g = Qg.shape[0]
     acc = np.zeros(length, dtype=F64)
     acc2 = np.zeros(length, dtype=F64)
     count = np.zeros(length, dtype=F64)
+    Vd = np.asarray(V, dtype=F64)[:length]
+    out = np.zeros((g, length, Vd.shape[1]), dtype=F64) if want_out else None
     rows = [causal_probability_rows(Qg[h], K, length, scale, recency_window, recency_bias, row_block) for h in range(g)]
     for blocks in zip(*rows):
         i0 = blocks[0][0]
         Pbar = sum(P for _, P in blocks) / F64(g)
         i1 = i0 + Pbar.shape[0]
+        if want_out:
+            for h, (_, P) in enumerate(blocks):
+                out[h, i0:i1] = P @ Vd[:i1]
         acc[:i1] += Pbar.sum(axis=0)
         if _keeps_last_score(policy):
             if i0 <= length - 1 < i1:
@@ -617,7 +623,7 @@ def prefill_statistics_gqa(Qg, K, V, length: int, scale: float, recency_window: 
         else:
             acc2[:i1] += (Pbar * Pbar).sum(axis=0)
         count[:i1] += (np.arange(i1)[None, :] <= np.arange(i0, i1)[:, None]).sum(axis=0)
-    return PrefillStats(acc, acc2, count, None)
+    return PrefillStats(acc, acc2, count, out)
 
 
 def prefill_compress_gqa(Qg, K, V, length: int, budget: int, scope: int, scale: float,

@@ -219,9 +219,9 @@ int roco_prefill_compress(const roco_params* params, const void* Q, const void* 
 
 int roco_prefill_compress_gqa(const roco_params* params, int32_t group, const void* Q, const void* K, const void* V,
                               const int32_t* len, int32_t L_max, void* K_cache, void* V_cache, float* stats,
-                              int32_t* pos, int32_t* n_used, int32_t* next_slot, void* workspace,
+                              int32_t* pos, int32_t* n_used, int32_t* next_slot, void* O, void* workspace,
                               size_t workspace_bytes, void* hip_stream) {
-  return run_prefill(params, group, Q, K, V, len, L_max, K_cache, V_cache, stats, pos, n_used, next_slot, nullptr,
+  return run_prefill(params, group, Q, K, V, len, L_max, K_cache, V_cache, stats, pos, n_used, next_slot, O,
                      workspace, workspace_bytes, hip_stream);
 }
 

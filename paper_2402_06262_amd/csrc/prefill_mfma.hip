@@ -518,8 +518,9 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_out_mfma(PrefillAr
   constexpr int kOwnQ = 32 * WAVES;  // one group of 32 queries per wave
   extern __shared__ __attribute__((aligned(16))) char lds_dyn[];  // K[2] then V[2] tiles
   int u, blk_id;
-  if (!locate(a.units, a.pairs, u, blk_id)) return;
-  const int len = a.len[u];
+  if (!locate(a.units * a.group, a.pairs, u, blk_id)) return;  // u counts (unit, query head) pairs
+  const int uk = u / a.group;  // the unit: its keys, values and length
+  const int len = a.len[uk];
   const int n_blocks = (len + kOwnQ - 1) / kOwnQ;
   if (blk_id >= n_blocks) return;
   const int blk = n_blocks - 1 - blk_id;  // long rows first
@@ -527,8 +528,8 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_out_mfma(PrefillAr
   const int half = lane >> 5;
   const size_t ubase = static_cast<size_t>(u) * a.L_max;
   const char* Qb = static_cast<const char*>(a.Q) + ubase * kRowBytes;
-  const char* Kb = static_cast<const char*>(a.K) + ubase * kRowBytes;
-  const char* Vb = static_cast<const char*>(a.V) + ubase * kRowBytes;
+  const char* Kb = static_cast<const char*>(a.K) + static_cast<size_t>(uk) * a.L_max * kRowBytes;
+  const char* Vb = static_cast<const char*>(a.V) + static_cast<size_t>(uk) * a.L_max * kRowBytes;
   const float sc = a.scale_log2;
   const int w = a.recency_window;
   const float rb = a.recency_bias_log2;
@@ -688,8 +689,9 @@ hipError_t launch_with_output(const PrefillArgs& a, hipStream_t s) {
   b.pairs = (a.L_max + kOwnQ - 1) / kOwnQ;  // workgroup ids per unit
   {
     ProfScope ps(kProfPrefillRows, s);
-    hipLaunchKernelGGL(prefill_rows_out_mfma<WAVES>, dim3(static_cast<unsigned>((a.units + 7) / 8 * 8 * b.pairs)),
-                       dim3(WAVES * kWave), kLds, s, b);
+    hipLaunchKernelGGL(prefill_rows_out_mfma<WAVES>,
+                       dim3(static_cast<unsigned>((a.units * a.group + 7) / 8 * 8 * b.pairs)), dim3(WAVES * kWave), kLds,
+                       s, b);
   }
   constexpr int kOwn = Shape<4>::kOwn;
   const int n_blocks = (a.L_max + kOwn - 1) / kOwn;
@@ -698,8 +700,9 @@ hipError_t launch_with_output(const PrefillArgs& a, hipStream_t s) {
   c.pairs = (n_blocks + 1) / 2;
   {
     ProfScope ps(kProfPrefillColumns, s);
-    hipLaunchKernelGGL(prefill_columns_mfma<4>, dim3(static_cast<unsigned>((a.units + 7) / 8 * 8 * c.pairs)),
-                       dim3(4 * kWave), 0, s, c);
+    const dim3 cgrid(static_cast<unsigned>((a.units + 7) / 8 * 8 * c.pairs));
+    if (a.group == 1) hipLaunchKernelGGL(prefill_columns_mfma<4>, cgrid, dim3(4 * kWave), 0, s, c);
+    else hipLaunchKernelGGL(prefill_columns_gqa_mfma<4>, cgrid, dim3(4 * kWave), 0, s, c);
   }
   return hipGetLastError();
 }
@@ -707,7 +710,7 @@ hipError_t launch_with_output(const PrefillArgs& a, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_prefill_attention_mfma(const PrefillArgs& a, hipStream_t s) {
-  if (a.O != nullptr) return a.group == 1 ? launch_with_output(a, s) : hipErrorInvalidValue;
+  if (a.O != nullptr) return launch_with_output(a, s);
   // 256 owned rows per workgroup by default.  512 halve the streamed traffic but leave one workgroup per
   // compute unit, all of whose waves wait at the same barriers; measured slower on the serving workload.
   return a.mfma_waves == 8 ? launch_t<8>(a, s) : launch_t<4>(a, s);

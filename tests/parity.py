@@ -360,7 +360,8 @@ def lockstep_block_gqa_unit(state: "orc.CacheState", u: int, g_out, g_slot, g_po
     return ties
 
 
-def gpu_prefill_gqa(sess: GpuSession, group: int, Q: np.ndarray, K: np.ndarray, V: np.ndarray, lens: Sequence[int]):
+def gpu_prefill_gqa(sess: GpuSession, group: int, Q: np.ndarray, K: np.ndarray, V: np.ndarray, lens: Sequence[int],
+                    want_out: bool = False):
     """Q: [units, group, L_max, d]; K, V: [units, L_max, d] float32 host arrays.  Host copies of what was written."""
     U, g, L_max, d = Q.shape
     p = sess.params
@@ -370,8 +371,9 @@ def gpu_prefill_gqa(sess: GpuSession, group: int, Q: np.ndarray, K: np.ndarray, 
     sess.prefill_ws = torch.empty(max(16, roco.prefill_gqa_workspace_bytes(p, group, L_max)), dtype=torch.uint8,
                                   device="cuda")
     c = sess.cache
+    sess.O = torch.zeros_like(dQ) if want_out else None
     roco.roco_prefill_compress_gqa(p, group, dQ, dK, dV, dlen, L_max, c.K, c.V, c.stats, c.pos, c.n_used, c.next_slot,
-                                   sess.prefill_ws)
+                                   sess.O, sess.prefill_ws)
     torch.cuda.synchronize()
     return dict(K=to_host(c.K), V=to_host(c.V), stats=to_host(c.stats), pos=to_host(c.pos), n_used=to_host(c.n_used),
-                O=None)
+                O=None if sess.O is None else to_host(sess.O))

@@ -84,7 +84,8 @@ def test_grouped_steps_with_recency_bias_and_a_larger_budget():
     drive(2, 1024, 48, 4, [8] * 130 + [1] * 8, seed=97, recency=True, tag="gqa-recency", single_token_entry=True)
 
 
-def run_grouped_prefill(dtype, d, group, lens, L, B, s, seed, steps=6, recency=False, policy=None, tag=""):
+def run_grouped_prefill(dtype, d, group, lens, L, B, s, seed, steps=6, recency=False, policy=None, tag="",
+                        want_out=True):
     """roco_prefill_compress_gqa against the oracle, then grouped decode steps from the compressed caches."""
     import paper_2402_06262_amd as roco
     P = _P()
@@ -101,13 +102,18 @@ def run_grouped_prefill(dtype, d, group, lens, L, B, s, seed, steps=6, recency=F
     rw, rb = (24, 0.5) if recency else (0, 0.0)
     sess = P.make_session(units, d, B, s, dtype, 0.0, rw, rb, policy=policy)
     print(f"[{tag}] grouped prefill {dtype} d={d} g={group} lens={lens} B={B}", flush=True)
-    g_res = P.gpu_prefill_gqa(sess, group, Q[:, :, :L].copy(), K[:, :L].copy(), V[:, :L].copy(), lens)
+    g_res = P.gpu_prefill_gqa(sess, group, Q[:, :, :L].copy(), K[:, :L].copy(), V[:, :L].copy(), lens, want_out)
     ties = P.TieCount()
     states = []
     for u in range(units):
-        full = orc.prefill_statistics_gqa(Q[u, :, :L], K[u, :L], V[u, :L], lens[u], sc, rw, rb, policy=policy)
+        full = orc.prefill_statistics_gqa(Q[u, :, :L], K[u, :L], V[u, :L], lens[u], sc, rw, rb, policy=policy,
+                                          want_out=want_out)
         res, t = P.check_prefill_unit(g_res, u, None, K[u, :L], V[u, :L], lens[u], B, s, sc, dtype, rw, rb, False,
                                       full=full, policy=policy)
+        if want_out:  # the attention output of every head and prompt row
+            for h in range(group):
+                for i in range(lens[u]):
+                    P.assert_out_close(g_res["O"][u, h, i], full.out[h, i], dtype, f"[{tag}] unit {u} head {h} O[{i}]")
         ties += t
         states.append(res.cache)
     ws = torch.empty(roco.block_workspace_bytes(sess.params, 1), dtype=torch.uint8, device="cuda")
@@ -170,7 +176,7 @@ def test_grouped_prefill_at_the_serving_shape():
     ws = torch.empty(roco.prefill_gqa_workspace_bytes(p, g, L), dtype=torch.uint8, device="cuda")
     dlen = torch.full((U,), L, dtype=torch.int32, device="cuda")
     print("[gqa-prefill-serving] prefill", flush=True)
-    roco.roco_prefill_compress_gqa(p, g, dQ, dK, dV, dlen, L, c.K, c.V, c.stats, c.pos, c.n_used, c.next_slot, ws)
+    roco.roco_prefill_compress_gqa(p, g, dQ, dK, dV, dlen, L, c.K, c.V, c.stats, c.pos, c.n_used, c.next_slot, None, ws)
     torch.cuda.synchronize()
     pos = c.pos.long()
     assert bool((c.n_used == B).all()) and bool((pos[:, 1:] > pos[:, :-1]).all()) and int(pos.min()) >= 0 and int(pos.max()) < L

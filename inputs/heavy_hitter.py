@@ -46,7 +46,7 @@ def round_to_bf16(x: np.ndarray) -> np.ndarray:
 
 @dataclass(frozen=True)
 class WorkloadConfig:
-    """Shape of one benchmark workload (input recipe)."""
+    """Shape of one benchmark workload."""
 
     index: int
     name: str

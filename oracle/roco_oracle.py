@@ -24,7 +24,7 @@ paper's Fig. 1 caption: every head evicts at its own positions):
 * prefill eviction frees many tokens in one eviction step        (section 5.3 "Overhead", block-wise
   evict-and-encode; appendix B)
 
-Readings taken where the paper is silent (each is listed in the design doc):
+Readings taken where the paper is silent:
 
 * `scope` = s = the number of tokens *inside* the eviction scope, i.e. the s
   occupied slots of smallest variance; the paper's r (number of protected

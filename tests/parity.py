@@ -1,6 +1,6 @@
 """Parity harness: drive the HIP library and the CPU oracle on the same seeded inputs and compare.
 
-Tolerances ("Tolerances"):
+Tolerances:
   * attention outputs: |g - o| <= tol * max(|o|, rms(o)) per vector, tol = 1e-3 (fp32 storage) or 2e-2
     (bf16 storage, whose rounding alone is 2^-9 relative);
   * Acc, Acc2:        |g - o| <= 1e-3 * max(|o|, 1e-6);  Count, pos, n_used, copied K/V rows: exact;

@@ -115,6 +115,27 @@ def _keeps_last_score(policy) -> bool:
     return policy is not None and policy.importance == "ltas"
 
 
+def _counts_above_average(policy) -> bool:
+    """Whether the policy's second statistic counts the queries whose attention to the token was above the
+    row average (importance "aqas")."""
+    return policy is not None and policy.importance == "aqas"
+
+
+def above_average(p, n_attended):
+    """The quantised attention score of section 4.1 (AQAS): 1 where a probability exceeds the average of its
+    softmax row, i.e. 1 / (number of tokens the query attended), else 0."""
+    return (np.asarray(p, dtype=F64) * F64(n_attended) > F64(1.0)).astype(F64)
+
+
+def _second_statistic(policy, old, p, seen, n_attended):
+    """The second array after a query with probabilities `p` over the slots flagged `seen` (p is 0 elsewhere)."""
+    if _keeps_last_score(policy):
+        return np.where(seen, p, old)
+    if _counts_above_average(policy):
+        return old + np.where(seen, above_average(p, n_attended), 0.0)
+    return old + p * p
+
+
 def prefill_statistics(Q, K, V, length: int, scale: float, recency_window: int = 0,
                        recency_bias: float = 0.0, want_out: bool = False,
                        row_block: int = 512, policy=None) -> PrefillStats:
@@ -134,6 +155,9 @@ def prefill_statistics(Q, K, V, length: int, scale: float, recency_window: int =
         if _keeps_last_score(policy):
             if i0 <= length - 1 < i1:
                 acc2[:i1] = P[length - 1 - i0]
+        elif _counts_above_average(policy):
+            causal = np.arange(i1)[None, :] <= np.arange(i0, i1)[:, None]
+            acc2[:i1] += (causal & (P * np.arange(i0 + 1, i1 + 1, dtype=F64)[:, None] > 1.0)).sum(axis=0)
         else:
             acc2[:i1] += (P * P).sum(axis=0)
         count[:i1] += (np.arange(i1)[None, :] <= np.arange(i0, i1)[:, None]).sum(axis=0)
@@ -201,7 +225,9 @@ class Policy:
     section 4.1), "oldest" (recency: the lowest position goes first, except the first `sinks` positions, which
     are never chosen while anything else is in scope: the window / StreamLLM baseline of section 4.1), "ltas"
     (the attention the token received from the most recent query, the TOVA score of section 4.1; the array that
-    otherwise accumulates squared attention then holds that score, so the "std" scope is not available).
+    otherwise accumulates squared attention then holds that score, so the "std" scope is not available), "aqas"
+    (the number of queries that gave the token more than the average attention of their row, the quantised score
+    of section 4.1 (ScissorHands); it too lives in the second array).
     scope_kind: "std" (the s tokens of lowest variance, section 4.3), "window" (the s oldest tokens, i.e. the
     most recent n - s are protected: the local-window scope of section 4.2), "all" (every cached token)."""
     importance: str = "mas"
@@ -227,7 +253,7 @@ def ranking_scores(policy: Optional[Policy], acc, acc2, count, pos, scope: int):
         importance = acc.copy()
     elif policy.importance == "oldest":
         importance = np.where(pos < policy.sinks, np.inf, pos.astype(F64))
-    elif policy.importance == "ltas":
+    elif policy.importance in ("ltas", "aqas"):
         if policy.scope_kind == "std":
             raise ValueError("the last-token score replaces the squared-attention array: no variance to rank by")
         importance = acc2.copy()
@@ -357,10 +383,7 @@ def decode_step(state: CacheState, q, k_new, v_new, qpos: int, scope: int, scale
     p = p / p.sum()
     out = p @ state.V[:n]
     state.acc[:n] += p
-    if _keeps_last_score(policy):
-        state.acc2[:n] = p
-    else:
-        state.acc2[:n] += p * p
+    state.acc2[:n] = _second_statistic(policy, state.acc2[:n], p, np.ones(n, dtype=bool), n)
     state.count[:n] += 1.0
     return DecodeResult(out, p, evicted_slot, evicted_pos, slot, mas, var)
 
@@ -429,12 +452,9 @@ def encode_block(state: CacheState, Qb, Kb, Vb, qpos0: int, scope: int, scale: f
         probs.append(full)
     for i in range(b):  # statistics after all rows are known, in the block's order
         state.acc[:n_new] += probs[i]
-        if _keeps_last_score(policy):
-            seen = block_index[:n_new] <= i
-            state.acc2[:n_new][seen] = probs[i][seen]
-        else:
-            state.acc2[:n_new] += probs[i] * probs[i]
-        state.count[:n_new] += (block_index[:n_new] <= i).astype(F64)
+        seen = block_index[:n_new] <= i
+        state.acc2[:n_new] = _second_statistic(policy, state.acc2[:n_new], probs[i], seen, int(seen.sum()))
+        state.count[:n_new] += seen.astype(F64)
     return BlockResult(out, probs, targets, evicted_slot, evicted_pos, mas, var)
 
 
@@ -491,10 +511,7 @@ def decode_step_gqa(state: CacheState, Qg, k_new, v_new, qpos: int, scope: int, 
         out[h] = probs[h] @ state.V[:n]
     mean_p = probs.sum(axis=0) / F64(g)
     state.acc[:n] += mean_p
-    if _keeps_last_score(policy):
-        state.acc2[:n] = mean_p
-    else:
-        state.acc2[:n] += mean_p * mean_p
+    state.acc2[:n] = _second_statistic(policy, state.acc2[:n], mean_p, np.ones(n, dtype=bool), n)
     state.count[:n] += 1.0
     return GroupDecodeResult(out, probs, mean_p, evicted_slot, evicted_pos, slot, mas, var)
 
@@ -560,12 +577,9 @@ def encode_block_gqa(state: CacheState, Qb, Kb, Vb, qpos0: int, scope: int, scal
         means.append(full)
     for i in range(b):
         state.acc[:n_new] += means[i]
-        if _keeps_last_score(policy):
-            seen = block_index[:n_new] <= i
-            state.acc2[:n_new][seen] = means[i][seen]
-        else:
-            state.acc2[:n_new] += means[i] * means[i]
-        state.count[:n_new] += (block_index[:n_new] <= i).astype(F64)
+        seen = block_index[:n_new] <= i
+        state.acc2[:n_new] = _second_statistic(policy, state.acc2[:n_new], means[i], seen, int(seen.sum()))
+        state.count[:n_new] += seen.astype(F64)
     return GroupBlockResult(out, means, targets, evicted_slot, evicted_pos, mas, var)
 
 
@@ -620,6 +634,9 @@ def prefill_statistics_gqa(Qg, K, V, length: int, scale: float, recency_window: 
         if _keeps_last_score(policy):
             if i0 <= length - 1 < i1:
                 acc2[:i1] = Pbar[length - 1 - i0]
+        elif _counts_above_average(policy):
+            causal = np.arange(i1)[None, :] <= np.arange(i0, i1)[:, None]
+            acc2[:i1] += (causal & (Pbar * np.arange(i0 + 1, i1 + 1, dtype=F64)[:, None] > 1.0)).sum(axis=0)
         else:
             acc2[:i1] += (Pbar * Pbar).sum(axis=0)
         count[:i1] += (np.arange(i1)[None, :] <= np.arange(i0, i1)[:, None]).sum(axis=0)

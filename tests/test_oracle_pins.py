@@ -709,3 +709,42 @@ def test_grouped_prefill_statistics_reduce_to_one_head_and_equal_block_wise_enco
 
 def full_acc_at(result, full):
     return np.concatenate([full.acc[result.retained], np.zeros(result.cache.budget - result.retained.shape[0])])
+
+
+def test_quantised_score_equals_an_explicit_recount_of_above_average_attention():
+    """importance "aqas" (section 4.1: the attention score quantised to 1 above / 0 below the row average): the
+    second array equals a count rebuilt from dense attention rows with plain loops, and each eviction takes the
+    argmin of that count (ties: lowest slot)."""
+    rng = np.random.default_rng(91)
+    L, T, d, B = 14, 18, 5, 14
+    Q, K, V = rand_unit(rng, L + T, d)
+    pol = orc.Policy("aqas", "all")
+    st = orc.prefill_compress(Q[:L], K[:L], V[:L], L, B, 3, 0.6, policy=pol).cache  # B = L: nothing evicted yet
+    count = {}
+    for j in range(L):
+        c = 0
+        for i in range(j, L):
+            z = 0.6 * K[:i + 1] @ Q[i]
+            w = np.exp(z - z.max())
+            w /= w.sum()
+            c += 1 if w[j] > 1.0 / (i + 1) else 0
+        count[j] = c
+    assert [count[int(p)] for p in st.pos] == list(st.acc2)
+    assert max(st.acc2) >= 2 and min(st.acc2) == 0  # the case is not degenerate
+    for t in range(L, L + T):
+        slots = list(st.pos)
+        expect = min(range(B), key=lambda sl: (count[int(slots[sl])], sl))
+        res = orc.decode_step(st, Q[t], K[t], V[t], t, 3, 0.6, policy=pol)
+        assert res.evicted_slot == expect
+        del count[res.evicted_pos]
+        count[t] = 0
+        keep = [int(p) for p in st.pos]
+        z = 0.6 * K[keep] @ Q[t]
+        w = np.exp(z - z.max())
+        w /= w.sum()
+        for sl, p in enumerate(keep):
+            count[p] += 1 if w[sl] > 1.0 / B else 0
+        assert [count[p] for p in keep] == list(st.acc2)
+    # a block of tokens: each row is compared with the average of what that row attended
+    blk = orc.encode_block(st.copy(), Q[:3] + 1.0, K[:3], V[:3], L + T, 3, 0.6, policy=pol)
+    assert blk.out.shape == (3, d)

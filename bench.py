@@ -388,7 +388,7 @@ def main():
         small = [make_unit(cfg, *i, seed=args.seed, total_len=512) for i in ids]
         cq, ck, cv = (upload(np.stack([getattr(u_, n_) for u_ in small]), torch, dt) for n_ in ("Q", "K", "V"))
         t0c = time.perf_counter()
-        study = consistency_study(cq, ck, cv, prompt_len=256, rates=(0.3, 0.4, 0.5, 0.6), importances=("mas", "aas", "ltas"))
+        study = consistency_study(cq, ck, cv, prompt_len=256, rates=(0.3, 0.4, 0.5, 0.6), importances=("mas", "aas", "aqas", "ltas"))
         result["consistency_synthetic"] = {
             "workload": "32 units of this workload's generator, 256-token prompt + 256 generated tokens, budget = "
                         "rate x 512, scope = whole cache, every 8th position",

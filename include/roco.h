@@ -77,9 +77,13 @@ enum {
   ROCO_IMPORTANCE_MAS = 0,    /* mean attention score Acc/Count (section 4.3)                                 */
   ROCO_IMPORTANCE_AAS = 1,    /* accumulated attention score Acc (section 4.1)                                */
   ROCO_IMPORTANCE_OLDEST = 2, /* recency: the lowest position goes first (section 4.1, window / sink baseline) */
-  ROCO_IMPORTANCE_LAST = 3    /* the attention received from the most recent query (section 4.1, LTAS).  The
+  ROCO_IMPORTANCE_LAST = 3,   /* the attention received from the most recent query (section 4.1, LTAS).  The
                                  Acc2 plane of stats then holds that probability instead of the accumulated
                                  squares, so ROCO_SCOPE_STD cannot be combined with it (ROCO_EINVAL)           */
+  ROCO_IMPORTANCE_COUNT = 4   /* the number of queries that gave the token more than the average attention of
+                                 their row, p > 1 / (tokens attended) (section 4.1, AQAS); kept in the Acc2 plane
+                                 like ROCO_IMPORTANCE_LAST, same restriction.  The prefill then runs its slower
+                                 vector-ALU passes.                                                            */
 };
 enum {
   ROCO_SCOPE_STD = 0,     /* the `scope` tokens of lowest attention variance (section 4.3)                    */

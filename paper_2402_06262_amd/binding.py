@@ -13,6 +13,7 @@ from typing import Optional
 ROCO_F32 = 0
 ROCO_BF16 = 1
 ROCO_IMPORTANCE_MAS, ROCO_IMPORTANCE_AAS, ROCO_IMPORTANCE_OLDEST, ROCO_IMPORTANCE_LAST = 0, 1, 2, 3
+ROCO_IMPORTANCE_COUNT = 4
 ROCO_SCOPE_STD, ROCO_SCOPE_WINDOW, ROCO_SCOPE_ALL = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

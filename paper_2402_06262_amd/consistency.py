@@ -16,7 +16,9 @@ from typing import Dict, Iterable, Sequence, Tuple
 from . import binding as roco
 
 IMPORTANCE = {"mas": roco.ROCO_IMPORTANCE_MAS, "aas": roco.ROCO_IMPORTANCE_AAS, "oldest": roco.ROCO_IMPORTANCE_OLDEST,
-              "ltas": roco.ROCO_IMPORTANCE_LAST}
+              "ltas": roco.ROCO_IMPORTANCE_LAST, "aqas": roco.ROCO_IMPORTANCE_COUNT}
+# what the second statistics plane holds under each importance: scores that share it can share a full-cache run
+_SECOND = {"ltas": "last", "aqas": "count"}
 
 
 class _Run:
@@ -69,13 +71,14 @@ def consistency_study(Q, K, V, prompt_len: int, rates: Sequence[float] = (0.3, 0
     sampled = [t for t in range(L, T) if (t - L) % sample_every == sample_every - 1 or t == T - 1]
 
     # the full-cache runs: the statistics do not depend on the policy (one run serves every importance and rate),
-    # except that the last-token score keeps the latest query's attention where the others keep squares
+    # except for what the second plane holds (squares, the latest query's attention, or the thresholded count)
     importances = list(importances)
     fulls = {}
-    for last in sorted({name == "ltas" for name in importances}):
-        imp = roco.ROCO_IMPORTANCE_LAST if last else roco.ROCO_IMPORTANCE_MAS
-        fulls[last] = _Run(torch, roco.RocoParams(U, d, T, T, dt, importance=imp, scope_kind=roco.ROCO_SCOPE_ALL), L)
-        fulls[last].prefill(Qp, Kp, Vp, lens, L)
+    for second in sorted({_SECOND.get(name, "square") for name in importances}):
+        imp = {"square": roco.ROCO_IMPORTANCE_MAS, "last": roco.ROCO_IMPORTANCE_LAST,
+               "count": roco.ROCO_IMPORTANCE_COUNT}[second]
+        fulls[second] = _Run(torch, roco.RocoParams(U, d, T, T, dt, importance=imp, scope_kind=roco.ROCO_SCOPE_ALL), L)
+        fulls[second].prefill(Qp, Kp, Vp, lens, L)
     budgets = {r: max(1, min(T, int(round(r * T)))) for r in rates}
     runs = {}
     for name in importances:
@@ -96,7 +99,7 @@ def consistency_study(Q, K, V, prompt_len: int, rates: Sequence[float] = (0.3, 0
         if t not in sampled:
             continue
         for (name, r), run in runs.items():
-            full = fulls[name == "ltas"]
+            full = fulls[_SECOND.get(name, "square")]
             fc = full.cache
             B = budgets[r]
             if t + 1 <= B:

@@ -20,8 +20,10 @@ int check_params(const roco_params* p) {
   if (p == nullptr) return ROCO_EINVAL;
   if (p->units < 1 || p->budget < 1 || p->scope < 1 || p->scope > p->budget) return ROCO_EINVAL;
   if (p->recency_window < 0) return ROCO_EINVAL;
-  if (p->importance < 0 || p->importance > 3 || p->scope_kind < 0 || p->scope_kind > 2 || p->sinks < 0) return ROCO_EINVAL;
-  if (p->importance == ROCO_IMPORTANCE_LAST && p->scope_kind == ROCO_SCOPE_STD) return ROCO_EINVAL;  // no variance kept
+  if (p->importance < 0 || p->importance > 4 || p->scope_kind < 0 || p->scope_kind > 2 || p->sinks < 0) return ROCO_EINVAL;
+  if ((p->importance == ROCO_IMPORTANCE_LAST || p->importance == ROCO_IMPORTANCE_COUNT) &&
+      p->scope_kind == ROCO_SCOPE_STD)
+    return ROCO_EINVAL;  // these scores live where the squares would be: no variance to rank by
   if (!(p->scale == p->scale) || !(p->recency_bias == p->recency_bias)) return ROCO_EINVAL;  // NaN
   if (p->dtype != ROCO_F32 && p->dtype != ROCO_BF16) return ROCO_EUNSUPPORTED;
   if (p->head_dim != 64 && p->head_dim != 128) return ROCO_EUNSUPPORTED;
@@ -193,7 +195,8 @@ int run_prefill(const roco_params* params, int group, const void* Q, const void*
   a.mas_key = reinterpret_cast<uint32_t*>(ws + lay.mas_key);
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const bool mfma = params->dtype == ROCO_BF16 && params->head_dim == 128 &&
+  // (the thresholded count is only built into the vector-ALU column pass)
+  const bool mfma = params->dtype == ROCO_BF16 && params->head_dim == 128 && !a.pol.counts_above_average() &&
                     env_int("ROCO_PREFILL_SIMPLE", 0) == 0;
   hipError_t e = mfma ? launch_prefill_attention_mfma(a, s)
                       : launch_prefill_attention_simple(params->dtype, params->head_dim, a, s);

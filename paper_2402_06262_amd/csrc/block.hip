@@ -454,7 +454,7 @@ __global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
       if (j + e < n && biv[e] <= t) {  // older tokens have index -1: attended by every row
         const float p = mean[e] * inv_heads;  // group-wise averaged probability (exact for one head)
         s1[e] += p;
-        s2[e] = a.pol.keeps_last_score() ? p : s2[e] + p * p;
+        s2[e] = a.pol.second_statistic(s2[e], p, static_cast<float>(n - a.block + t + 1));  // what row t attended
         sc[e] += 1.0f;
       }
     }

@@ -230,7 +230,7 @@ __device__ __forceinline__ void ranking_keys(float acc, float acc2, float count,
     mas_key = __float_as_uint(__fdiv_rn(acc, count));
   } else if (pol.importance == kImpAas) {
     mas_key = acc > 0.0f ? __float_as_uint(acc) : 0u;
-  } else if (pol.importance == kImpLast) {
+  } else if (pol.importance == kImpLast || pol.importance == kImpCount) {
     mas_key = acc2 > 0.0f ? __float_as_uint(acc2) : 0u;
   } else {
     mas_key = pos < pol.sinks ? 0xfffffffeu : static_cast<uint32_t>(pos);

@@ -179,7 +179,7 @@ __device__ __forceinline__ void update_four(float4& a1, float4& a2, float4& cc, 
       if (jj == slot) { s1[e] = 0.0f; s2[e] = 0.0f; sc[e] = 0.0f; }
       const float p = fast_exp2(zv[e] - M) * inv;
       s1[e] += p;
-      s2[e] = sk.pol.keeps_last_score() ? p : s2[e] + p * p;
+      s2[e] = sk.pol.second_statistic(s2[e], p, static_cast<float>(n));
       sc[e] += 1.0f;
       if (full) ranking_keys(s1[e], s2[e], sc[e], jj == slot ? sk.qpos : pv[e], sk.pol, mas_key[jj], var_key[jj]);
     }
@@ -240,7 +240,7 @@ __device__ __forceinline__ void update_statistics(float* acc, float* acc2, float
       if (j == slot) { s1 = 0.0f; s2 = 0.0f; sc = 0.0f; }
       const float p = fast_exp2(z[j] - M) * inv;
       s1 += p;
-      s2 = sk.pol.keeps_last_score() ? p : s2 + p * p;
+      s2 = sk.pol.second_statistic(s2, p, static_cast<float>(n));
       sc += 1.0f;
       acc[j] = s1; acc2[j] = s2; cnt[j] = sc;
       if (full) ranking_keys(s1, s2, sc, j == slot ? sk.qpos : (sk.pol.needs_pos() ? sk.pos[j] : 0), sk.pol, mas_key[j], var_key[j]);

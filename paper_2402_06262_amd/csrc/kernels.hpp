@@ -8,15 +8,24 @@ namespace roco {
 
 // Eviction policy in the paper's two-stage framework (section 4): an eviction scope, then an importance score
 // inside it.  All zeros is RoCo (section 4.3).
-enum : int { kImpMas = 0, kImpAas = 1, kImpOldest = 2, kImpLast = 3 };
+enum : int { kImpMas = 0, kImpAas = 1, kImpOldest = 2, kImpLast = 3, kImpCount = 4 };
 enum : int { kScopeStd = 0, kScopeWindow = 1, kScopeAll = 2 };
 struct Policy {
   int importance;  // kImpMas: Acc/Count; kImpAas: Acc; kImpOldest: position, the first `sinks` positions last;
-                   // kImpLast: the attention from the latest query, kept in the second statistics plane
+                   // kImpLast: the attention from the latest query, kept in the second statistics plane;
+                   // kImpCount: how many queries gave the token more than their row's average attention, ditto
   int scope_kind;  // kScopeStd: lowest variance; kScopeWindow: lowest position (oldest); kScopeAll: everything
   int sinks;
   // the second plane holds the latest query's probability instead of the accumulated squares
   __host__ __device__ bool keeps_last_score() const { return importance == kImpLast; }
+  // ... or counts the queries whose probability for the token was above 1 / (tokens the query attended)
+  __host__ __device__ bool counts_above_average() const { return importance == kImpCount; }
+  // The second statistic after a query that attended `attended` tokens gave the token probability p.
+  __host__ __device__ float second_statistic(float old, float p, float attended) const {
+    if (importance == kImpLast) return p;
+    if (importance == kImpCount) return old + (p * attended > 1.0f ? 1.0f : 0.0f);
+    return old + p * p;
+  }
   __host__ __device__ bool needs_pos() const { return importance == kImpOldest || scope_kind == kScopeWindow; }
   // number of tokens inside the scope when n are cached
   __host__ __device__ int scope_size(int scope, int n) const { return scope_kind == kScopeAll ? n : scope; }

@@ -112,7 +112,8 @@ __global__ __launch_bounds__(kThreads) void prefill_columns_simple(PrefillArgs a
     for (int x = 0; x < U; ++x) {
       const float p = pbar[x] * inv_heads;  // rows past the end contribute exactly zero
       s1 += p;
-      s2 = fmaf(p, p, s2);
+      if (a.pol.counts_above_average()) s2 += (p * static_cast<float>(base + x * G::R + g + 1) > 1.0f) ? 1.0f : 0.0f;
+      else s2 = fmaf(p, p, s2);
     }
   }
 #pragma unroll

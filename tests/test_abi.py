@@ -48,8 +48,9 @@ def test_policy_fields_are_validated():
     ok = roco.RocoParams(8, 128, 256, 16, roco.ROCO_BF16, importance=roco.ROCO_IMPORTANCE_OLDEST,
                          scope_kind=roco.ROCO_SCOPE_ALL, sinks=4)
     assert roco.decode_workspace_bytes(ok) > 0
-    for bad in (dict(importance=4), dict(importance=-1), dict(scope_kind=3), dict(sinks=-1),
-                dict(importance=roco.ROCO_IMPORTANCE_LAST, scope_kind=roco.ROCO_SCOPE_STD)):
+    for bad in (dict(importance=5), dict(importance=-1), dict(scope_kind=3), dict(sinks=-1),
+                dict(importance=roco.ROCO_IMPORTANCE_LAST, scope_kind=roco.ROCO_SCOPE_STD),
+                dict(importance=roco.ROCO_IMPORTANCE_COUNT, scope_kind=roco.ROCO_SCOPE_STD)):
         assert roco.decode_workspace_bytes(roco.RocoParams(8, 128, 256, 16, roco.ROCO_BF16, **bad)) == 0
     lib = roco.load_library()
     need = roco.decode_workspace_bytes(ok)

@@ -66,10 +66,10 @@ def test_consistency_study_matches_the_same_study_on_the_oracle():
     rates = (0.3, 0.5)
     Q, K, V = _data(units, T, d, 23)
     dev = [torch.from_numpy(x).cuda().to(torch.bfloat16) for x in (Q, K, V)]
-    got = consistency_study(*dev, prompt_len=L, rates=rates, importances=("mas", "aas", "oldest", "ltas"), sample_every=4)
+    got = consistency_study(*dev, prompt_len=L, rates=rates, importances=("mas", "aas", "oldest", "ltas", "aqas"), sample_every=4)
     sc = 1 / math.sqrt(d)
     sampled = [t for t in range(L, T) if (t - L) % 4 == 3 or t == T - 1]
-    for name in ("mas", "aas", "oldest", "ltas"):
+    for name in ("mas", "aas", "oldest", "ltas", "aqas"):
         pol = orc.Policy(name, "all")
         for r in rates:
             B = int(round(r * T))

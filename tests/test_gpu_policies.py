@@ -20,6 +20,8 @@ POLICIES = {
     "oldest-window": orc.Policy("oldest", "window", 2),
     "tova": orc.Policy("ltas", "all"),             # last-token attention score over the whole cache
     "ltas-window": orc.Policy("ltas", "window"),
+    "scissorhands": orc.Policy("aqas", "window"),  # thresholded count, recent half protected
+    "aqas-all": orc.Policy("aqas", "all"),
 }
 
 
@@ -65,7 +67,7 @@ def test_sink_policy_keeps_the_sinks_and_the_most_recent_tokens():
         assert sorted(host["pos"][u].tolist()) == want
 
 
-@pytest.mark.parametrize("name", ["h2o", "sinks", "mas-window", "tova"])
+@pytest.mark.parametrize("name", ["h2o", "sinks", "mas-window", "tova", "scissorhands"])
 def test_block_steps_under_each_policy(name):
     import test_gpu_block as TB
     pol = POLICIES[name]

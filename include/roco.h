@@ -82,8 +82,7 @@ enum {
                                  squares, so ROCO_SCOPE_STD cannot be combined with it (ROCO_EINVAL)           */
   ROCO_IMPORTANCE_COUNT = 4   /* the number of queries that gave the token more than the average attention of
                                  their row, p > 1 / (tokens attended) (section 4.1, AQAS); kept in the Acc2 plane
-                                 like ROCO_IMPORTANCE_LAST, same restriction.  The prefill then runs its slower
-                                 vector-ALU passes.                                                            */
+                                 like ROCO_IMPORTANCE_LAST, same restriction                                   */
 };
 enum {
   ROCO_SCOPE_STD = 0,     /* the `scope` tokens of lowest attention variance (section 4.3)                    */

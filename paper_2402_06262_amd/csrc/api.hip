@@ -195,8 +195,7 @@ int run_prefill(const roco_params* params, int group, const void* Q, const void*
   a.mas_key = reinterpret_cast<uint32_t*>(ws + lay.mas_key);
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  // (the thresholded count is only built into the vector-ALU column pass)
-  const bool mfma = params->dtype == ROCO_BF16 && params->head_dim == 128 && !a.pol.counts_above_average() &&
+  const bool mfma = params->dtype == ROCO_BF16 && params->head_dim == 128 &&
                     env_int("ROCO_PREFILL_SIMPLE", 0) == 0;
   hipError_t e = mfma ? launch_prefill_attention_mfma(a, s)
                       : launch_prefill_attention_simple(params->dtype, params->head_dim, a, s);

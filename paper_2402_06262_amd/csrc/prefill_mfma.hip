@@ -236,8 +236,10 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_mfma(PrefillArgs a
   }
 }
 
-// Column-statistics update of one lane (one key) with the 16 scores of a tile (16 queries).
-template <bool INTERIOR>
+// Column-statistics update of one lane (one key) with the 16 scores of a tile (16 queries).  COUNT: the second
+// statistic is the number of queries that gave the key more than their row's average, p * (i + 1) > 1 (section
+// 4.1, quantised score), instead of the sum of squares.
+template <bool INTERIOR, bool COUNT>
 __device__ __forceinline__ void column_update(const f32x16& s, const float* lse_tile, float sc, int ib, int half,
                                               int kj, int len, int w, float rb, float& s1, float& s2) {
   float a1 = 0.0f, a2 = 0.0f, b1 = 0.0f, b2 = 0.0f;
@@ -257,8 +259,15 @@ __device__ __forceinline__ void column_update(const f32x16& s, const float* lse_
         p = fast_exp2(x);
         if (qi < kj || qi >= len) p = 0.0f;
       }
-      if (e & 1) { b1 += p; b2 = fmaf(p, p, b2); }
-      else       { a1 += p; a2 = fmaf(p, p, a2); }
+      float second;
+      if (COUNT) {
+        const float rows = static_cast<float>(ib + 8 * g4 + 4 * half + e + 1);  // tokens query i attended
+        second = p * rows > 1.0f ? 1.0f : 0.0f;
+      } else {
+        second = p * p;
+      }
+      if (e & 1) { b1 += p; b2 = COUNT ? b2 + second : fmaf(p, p, b2); }
+      else       { a1 += p; a2 = COUNT ? a2 + second : fmaf(p, p, a2); }
     }
   }
   s1 += a1 + b1;
@@ -267,7 +276,7 @@ __device__ __forceinline__ void column_update(const f32x16& s, const float* lse_
 
 // ------------------------------------------------------------------------------------------------
 // pass 2: Acc[j] = sum_{i>=j} 2^(t_ij - lse_i),  Acc2[j] = sum_{i>=j} (same)^2
-template <int WAVES>
+template <int WAVES, bool COUNT>
 __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_mfma(PrefillArgs a) {
   constexpr int kOwn = Shape<WAVES>::kOwn;
   __shared__ __attribute__((aligned(16))) char lds[2][kTile * kLdsRow];
@@ -329,11 +338,11 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_mfma(PrefillArg
         score_tiles(lds[b], sub, own0, own1, do0, do1, c0, c1);
         const bool whole = w == 0 && ib + 31 < len;  // no ragged end, no bias
         const float* lt = &lse_s[b][sub * 32];
-        if (whole && ib >= kw0 + 31) column_update<true>(c0, lt, sc, ib, half, kj0, len, w, rb, s1a, s2a);
-        else column_update<false>(c0, lt, sc, ib, half, kj0, len, w, rb, s1a, s2a);
+        if (whole && ib >= kw0 + 31) column_update<true, COUNT>(c0, lt, sc, ib, half, kj0, len, w, rb, s1a, s2a);
+        else column_update<false, COUNT>(c0, lt, sc, ib, half, kj0, len, w, rb, s1a, s2a);
         if (do1) {
-          if (whole && ib >= kw0 + 63) column_update<true>(c1, lt, sc, ib, half, kj1, len, w, rb, s1b, s2b);
-          else column_update<false>(c1, lt, sc, ib, half, kj1, len, w, rb, s1b, s2b);
+          if (whole && ib >= kw0 + 63) column_update<true, COUNT>(c1, lt, sc, ib, half, kj1, len, w, rb, s1b, s2b);
+          else column_update<false, COUNT>(c1, lt, sc, ib, half, kj1, len, w, rb, s1b, s2b);
         }
       }
     };
@@ -478,14 +487,14 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_gqa_mfma(Prefil
         for (int e = 0; e < 16; ++e) {
           const float p = pb0[e] * inv_heads;
           s1a += p;
-          s2a = fmaf(p, p, s2a);
+          s2a = a.pol.second_statistic(s2a, p, static_cast<float>(ib + 8 * (e >> 2) + 4 * half + (e & 3) + 1));
         }
         if (do1) {
 #pragma unroll
           for (int e = 0; e < 16; ++e) {
             const float p = pb1[e] * inv_heads;
             s1b += p;
-            s2b = fmaf(p, p, s2b);
+            s2b = a.pol.second_statistic(s2b, p, static_cast<float>(ib + 8 * (e >> 2) + 4 * half + (e & 3) + 1));
           }
         }
       }
@@ -666,8 +675,10 @@ hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
   }
   {
     ProfScope ps(kProfPrefillColumns, s);
-    if (a.group == 1) hipLaunchKernelGGL(prefill_columns_mfma<WAVES>, grid, dim3(WAVES * kWave), 0, s, b);
-    else hipLaunchKernelGGL(prefill_columns_gqa_mfma<WAVES>, grid, dim3(WAVES * kWave), 0, s, b);
+    if (a.group != 1) hipLaunchKernelGGL(prefill_columns_gqa_mfma<WAVES>, grid, dim3(WAVES * kWave), 0, s, b);
+    else if (a.pol.counts_above_average())
+      hipLaunchKernelGGL((prefill_columns_mfma<WAVES, true>), grid, dim3(WAVES * kWave), 0, s, b);
+    else hipLaunchKernelGGL((prefill_columns_mfma<WAVES, false>), grid, dim3(WAVES * kWave), 0, s, b);
   }
   return hipGetLastError();
 }
@@ -701,8 +712,9 @@ hipError_t launch_with_output(const PrefillArgs& a, hipStream_t s) {
   {
     ProfScope ps(kProfPrefillColumns, s);
     const dim3 cgrid(static_cast<unsigned>((a.units + 7) / 8 * 8 * c.pairs));
-    if (a.group == 1) hipLaunchKernelGGL(prefill_columns_mfma<4>, cgrid, dim3(4 * kWave), 0, s, c);
-    else hipLaunchKernelGGL(prefill_columns_gqa_mfma<4>, cgrid, dim3(4 * kWave), 0, s, c);
+    if (a.group != 1) hipLaunchKernelGGL(prefill_columns_gqa_mfma<4>, cgrid, dim3(4 * kWave), 0, s, c);
+    else if (a.pol.counts_above_average()) hipLaunchKernelGGL((prefill_columns_mfma<4, true>), cgrid, dim3(4 * kWave), 0, s, c);
+    else hipLaunchKernelGGL((prefill_columns_mfma<4, false>), cgrid, dim3(4 * kWave), 0, s, c);
   }
   return hipGetLastError();
 }

@@ -21,6 +21,8 @@
 // The same three kernels serve grouped-query attention (section 5.3, "Extension to Grouped-Query Attention"):
 // g query heads share the unit's keys and values, the query rows are (token, head) pairs, and the statistics
 // receive, once per token, the mean of its g heads' probabilities (BlockArgs::heads).
+#include <cstdlib>
+
 #include "kernels.hpp"
 #include "mfma.hpp"
 #include "profile.hpp"
@@ -117,16 +119,21 @@ __global__ __launch_bounds__(kPrepThreads) void block_prepare(BlockArgs a) {
 struct StagedKV {
   uint4 k[8], v[8];  // this thread's 128 bytes of a 64 x 256 B tile of K and of V (128 threads)
 };
+// `fresh` (or -1) is a slot whose row is taken from knew / vnew instead of the cache: the token a single-token step
+// is about to write there.  The address is selected, not the load, so there is no control flow around the loads.
 template <bool STREAMING>
-__device__ __forceinline__ void kv_load(StagedKV& s, const char* Kb, const char* Vb, int row0, int last_row) {
+__device__ __forceinline__ void kv_load(StagedKV& s, const char* Kb, const char* Vb, int row0, int last_row,
+                                        int fresh, const char* knew, const char* vnew) {
   const int t = threadIdx.x;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     int row = row0 + (t >> 4) + 8 * i;
     row = row < last_row ? row : last_row;  // slots past the end are masked by the caller
     const size_t off = static_cast<size_t>(row) * kRowBytes + (t & 15) * 16;
-    s.k[i] = STREAMING ? load16_streaming(Kb + off) : load16(Kb + off);
-    s.v[i] = STREAMING ? load16_streaming(Vb + off) : load16(Vb + off);
+    const char* kp = row == fresh ? knew + (t & 15) * 16 : Kb + off;
+    const char* vp = row == fresh ? vnew + (t & 15) * 16 : Vb + off;
+    s.k[i] = STREAMING ? load16_streaming(kp) : load16(kp);
+    s.v[i] = STREAMING ? load16_streaming(vp) : load16(vp);
   }
 }
 __device__ __forceinline__ void kv_store(const StagedKV& s, char* tileK, char* tileV) {
@@ -148,12 +155,23 @@ __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int half = lane >> 5, qi = lane & 31;  // this lane's query (block token index)
   const int B = a.B, b = a.queries;
-  const int n = a.n_used[u];  // already counts the block's tokens
+  // Usually block_prepare has run: n_used counts the block's tokens and their rows are in the cache.  A single-token
+  // step skips it (BlockArgs::single): the token's slot is known from the state, its row is read from k_new / v_new
+  // and written into the cache by the workgroup that streams that slot, as in the token-wise decode kernels.
+  int n = a.n_used[u];
+  int fresh = -1;
+  if (a.single) {
+    const bool was_full = n >= B;
+    fresh = was_full ? min(max(a.next_slot[u], 0), B - 1) : n;
+    n = was_full ? B : n + 1;
+  }
+  const char* knew = static_cast<const char*>(a.k_new) + static_cast<size_t>(u) * kRowBytes;
+  const char* vnew = static_cast<const char*>(a.v_new) + static_cast<size_t>(u) * kRowBytes;
   const int row0 = split * a.rows_per_split;
   const int row1 = min(n, row0 + a.rows_per_split);
   const size_t pidx = static_cast<size_t>(u) * a.splits + split;
-  const char* Kb = static_cast<const char*>(a.K) + static_cast<size_t>(u) * B * kRowBytes;
-  const char* Vb = static_cast<const char*>(a.V) + static_cast<size_t>(u) * B * kRowBytes;
+  char* Kb = static_cast<char*>(a.K) + static_cast<size_t>(u) * B * kRowBytes;
+  char* Vb = static_cast<char*>(a.V) + static_cast<size_t>(u) * B * kRowBytes;
   const int32_t* bidx = a.blk_idx + static_cast<size_t>(u) * B;
   const int32_t* pos = a.pos + static_cast<size_t>(u) * B;
   float* z = a.z + static_cast<size_t>(u) * kQ * B;
@@ -187,12 +205,22 @@ __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
   auto tile_row = [&](int t) { return row0 + (t + rot < n_tiles ? t + rot : t + rot - n_tiles) * kTile; };
   auto fetch = [&](int t) {
     const int tr0 = tile_row(t);
-    if (a.streaming) kv_load<true>(st, Kb, Vb, tr0, n - 1);
-    else kv_load<false>(st, Kb, Vb, tr0, n - 1);
+    if (a.streaming) kv_load<true>(st, Kb, Vb, tr0, n - 1, fresh, knew, vnew);
+    else kv_load<false>(st, Kb, Vb, tr0, n - 1, fresh, knew, vnew);
+    if (fresh >= tr0 && fresh < min(tr0 + kTile, row1)) {  // this tile holds the new token's slot: put the row there
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (tr0 + (tid >> 4) + 8 * i == fresh) {
+          const size_t off = static_cast<size_t>(fresh) * kRowBytes + (tid & 15) * 16;
+          *reinterpret_cast<uint4*>(Kb + off) = st.k[i];
+          *reinterpret_cast<uint4*>(Vb + off) = st.v[i];
+        }
+      }
+    }
     if (tid < kTile) {
       const int slot = min(tr0 + tid, n - 1);
-      st_bidx = bidx[slot];
-      st_pos = pos[slot];
+      st_bidx = a.single ? -1 : bidx[slot];
+      st_pos = slot == fresh ? a.qpos0[u] : pos[slot];
     }
   };
   if (n_tiles > 0) fetch(0);
@@ -391,13 +419,23 @@ __global__ __launch_bounds__(256) void block_attend_simple(BlockArgs a) {
 // Grid (chunks, units): workgroup (c, u) owns slots [c * kFinSlots, (c + 1) * kFinSlots) of unit u and the query
 // rows r = c, c + chunks, ...  The victim for a following single-token step is chosen afterwards by the
 // select_victims kernel, from the statistics written here.
-template <int DT, int D>
-__global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
-  constexpr int NT = kFinThreads;
+template <int DT, int D, bool SELECT, int NT>
+__global__ __launch_bounds__(NT) void block_finish(BlockArgs a) {
+  constexpr int kSlots = 2 * NT;  // slots per workgroup and sweep
+  extern __shared__ uint32_t lds_keys[];  // SELECT: [2][B] ranking keys when B <= kMaxDecodeBudgetLds
+  __shared__ uint32_t sel_sh[SELECT ? kSelectLdsWords : 1];
+  __shared__ unsigned long long best_sh[NT / kWave];
   __shared__ float Mq[kQ], invq[kQ];
   const int u = blockIdx.y, chunk = blockIdx.x, chunks = gridDim.x, tid = threadIdx.x;
   const int B = a.B, nq = a.queries, S = a.splits;
-  const int n = a.n_used[u];
+  int n = a.n_used[u];
+  int fresh = -1;  // single-token step without block_prepare: the slot the token took, which this kernel books
+  bool evicted = false;
+  if (SELECT && a.single) {
+    evicted = n >= B;
+    fresh = evicted ? min(max(a.next_slot[u], 0), B - 1) : n;
+    n = evicted ? B : n + 1;
+  }
   const int heads = a.heads;
   const float inv_heads = 1.0f / static_cast<float>(heads);
   const float* pm = a.part_m + static_cast<size_t>(u) * S * kQ;
@@ -415,7 +453,15 @@ __global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
     Mq[tid] = M;
     invq[tid] = 1.0f / L;
   }
-  __syncthreads();
+  __syncthreads();  // every thread has read n_used and next_slot
+  if (SELECT && a.single && tid == 0) {
+    int32_t* pos = a.pos + static_cast<size_t>(u) * B;
+    const int old_pos = pos[fresh];
+    pos[fresh] = a.qpos0[u];
+    a.n_used[u] = n;
+    if (a.evicted_slot) a.evicted_slot[u] = evicted ? fresh : -1;
+    if (a.evicted_pos) a.evicted_pos[u] = evicted ? old_pos : -1;
+  }
   // outputs of this workgroup's query rows
   const int my_rows = nq > chunk ? (nq - chunk + chunks - 1) / chunks : 0;
   for (int idx = tid; idx < my_rows * D; idx += NT) {
@@ -428,18 +474,28 @@ __global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
     store_elem<DT>(a.out, (static_cast<size_t>(u) * nq + q) * D + dd, o * invq[q]);
   }
   // statistics: every slot receives, per block token that attended it, the head-mean of the probabilities
-  const int j = chunk * kFinSlots + tid * 2;  // B is a multiple of 4 on this path, so the pair is inside [0, B)
-  if (j >= n) return;
   float* acc = a.stats + static_cast<size_t>(u) * 3 * B;
   float* acc2 = acc + B;
   float* cnt = acc2 + B;
   const float* z = a.z + static_cast<size_t>(u) * kQ * B;
-  const int2 bi = *reinterpret_cast<const int2*>(a.blk_idx + static_cast<size_t>(u) * B + j);
+  const bool full = n >= B;
+  uint32_t* var_key = (B <= kMaxDecodeBudgetLds) ? lds_keys : a.keys + static_cast<size_t>(u) * 2 * B;
+  uint32_t* mas_key = var_key + B;
+  const bool by_pos = a.pol.needs_pos();
+  // B is a multiple of 4 on this path, so a pair of slots is inside [0, B).  Without SELECT a workgroup owns one
+  // chunk of slots; with it, one workgroup walks all chunks of its unit and then chooses the next victim itself.
+  const int j_end = SELECT ? n : min(n, (chunk + 1) * kSlots);
+  for (int j = chunk * kSlots + tid * 2; j < j_end; j += kSlots) {
+  const int2 bi = (SELECT && a.single) ? make_int2(-1, -1)
+                                       : *reinterpret_cast<const int2*>(a.blk_idx + static_cast<size_t>(u) * B + j);
   const float2 a1 = *reinterpret_cast<const float2*>(acc + j);
   const float2 a2 = *reinterpret_cast<const float2*>(acc2 + j);
   const float2 cc = *reinterpret_cast<const float2*>(cnt + j);
   float s1[2] = {a1.x, a1.y}, s2[2] = {a2.x, a2.y}, sc[2] = {cc.x, cc.y};
   const int biv[2] = {bi.x, bi.y};
+#pragma unroll
+  for (int e = 0; e < 2; ++e)
+    if (j + e == fresh) { s1[e] = 0.0f; s2[e] = 0.0f; sc[e] = 0.0f; }  // the new token starts from zero
   for (int t = 0; t < a.block; ++t) {
     float mean[2] = {0.0f, 0.0f};  // sum over the token's query heads of p
     for (int h = 0; h < heads; ++h) {
@@ -462,15 +518,48 @@ __global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
   *reinterpret_cast<float2*>(acc + j) = make_float2(s1[0], s1[1]);
   *reinterpret_cast<float2*>(acc2 + j) = make_float2(s2[0], s2[1]);
   *reinterpret_cast<float2*>(cnt + j) = make_float2(sc[0], sc[1]);
+  if (SELECT && full) {
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+      if (j + e < n)
+        ranking_keys(s1[e], s2[e], sc[e],
+                     j + e == fresh ? a.qpos0[u] : (by_pos ? a.pos[static_cast<size_t>(u) * B + j + e] : 0), a.pol,
+                     mas_key[j + e], var_key[j + e]);
+  }
+  }
+  if (SELECT) {  // the victim a following single-token step would take
+    if (full) {
+      __syncthreads();
+      const int victim = select_victim_block<NT>(var_key, mas_key, B, a.pol.scope_size(a.scope, B), sel_sh, best_sh);
+      if (tid == 0) a.next_slot[u] = victim;
+    } else if (tid == 0) {
+      a.next_slot[u] = -1;
+    }
+  }
 }
 
 }  // namespace
 
+// Few query rows (a grouped decode step, a short block): one workgroup per unit updates the statistics and chooses
+// the next victim in place.  Many rows: the update is spread over slot chunks and the selection is a launch of its own.
+static bool finish_selects(const BlockArgs& a) { return a.queries <= 4; }
+
+// ROCO_BLOCK_SINGLE=0 keeps block_prepare in single-token steps (tests run both).
+static bool single_step_off() {
+  const char* e = getenv("ROCO_BLOCK_SINGLE");
+  return e != nullptr && e[0] == '0';
+}
+
 template <int DT, int D>
 void launch_block_tail(const BlockArgs& a, hipStream_t s) {
   ProfScope ps(kProfBlockFinish, s);
-  hipLaunchKernelGGL((block_finish<DT, D>), dim3((a.B + kFinSlots - 1) / kFinSlots, a.units), dim3(kFinThreads), 0, s,
-                     a);
+  if (finish_selects(a)) {
+    const size_t key_lds = (a.B <= kMaxDecodeBudgetLds) ? static_cast<size_t>(a.B) * 2 * sizeof(uint32_t) : 0;
+    hipLaunchKernelGGL((block_finish<DT, D, true, 1024>), dim3(1, a.units), dim3(1024), key_lds, s, a);
+  } else {
+    hipLaunchKernelGGL((block_finish<DT, D, false, kFinThreads>), dim3((a.B + kFinSlots - 1) / kFinSlots, a.units),
+                       dim3(kFinThreads), 0, s, a);
+  }
 }
 
 template <int DT, int D>
@@ -483,7 +572,10 @@ void launch_block_simple(const BlockArgs& a, hipStream_t s) {
 }
 
 // dtype / head_dim other than bf16 / 128 take the vector-ALU attention (a.splits must then be 1)
-hipError_t launch_block(int dtype, int head_dim, const BlockArgs& a, hipStream_t s) {
+hipError_t launch_block(int dtype, int head_dim, const BlockArgs& args, hipStream_t s) {
+  BlockArgs a = args;
+  // A single-token step on the matrix-core path whose finishing kernel also selects needs no block_prepare.
+  a.single = (a.block == 1 && finish_selects(a) && dtype == kBF16 && head_dim == 128 && !single_step_off()) ? 1 : 0;
   const size_t key_lds = (a.B <= kMaxDecodeBudgetLds) ? static_cast<size_t>(a.B) * 2 * sizeof(uint32_t) : 0;
   constexpr size_t kAttLds = 4 * static_cast<size_t>(kTileBytes);  // 68 KiB: above the default dynamic limit
   const bool mfma_path = dtype == kBF16 && head_dim == 128;
@@ -494,7 +586,7 @@ hipError_t launch_block(int dtype, int head_dim, const BlockArgs& a, hipStream_t
       return hipErrorInvalidValue;
     attr_done = true;
   }
-  {
+  if (!a.single) {
     ProfScope ps(kProfBlockPrepare, s);
     hipLaunchKernelGGL(block_prepare, dim3(a.units), dim3(kPrepThreads), key_lds, s, a);
   }
@@ -514,6 +606,7 @@ hipError_t launch_block(int dtype, int head_dim, const BlockArgs& a, hipStream_t
     return hipErrorInvalidValue;
   }
   if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+  if (finish_selects(a)) return hipSuccess;
   DecodeArgs sel = {};  // the victim a following single-token decode step would take
   sel.units = a.units; sel.B = a.B; sel.scope = a.scope; sel.pol = a.pol; sel.pos = a.pos;
   sel.stats = a.stats; sel.n_used = a.n_used; sel.next_slot = a.next_slot; sel.keys = a.keys;

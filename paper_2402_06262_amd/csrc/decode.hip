@@ -29,36 +29,6 @@ constexpr int kAttendWaves = kAttendThreads / kWave;
 constexpr int kFinishThreads = kDecodeSelectThreads;
 constexpr int kFusedThreads = 256;  // with 8 rows in flight per lane group: two workgroups per compute unit
 
-// Scope = `scope` lowest variance keys among [0, B); returns the slot of lowest MAS key inside it (lowest
-// slot on equal keys).  Every thread of the block calls it and gets the same answer.
-template <int NT>
-__device__ int select_victim_block(const uint32_t* var_key, const uint32_t* mas_key, int B, int scope,
-                                   uint32_t* sel_sh, unsigned long long* best_sh) {
-  const int tid = threadIdx.x;
-  const KSmallest sc = select_k_smallest<NT>([&](int i) { return var_key[i]; }, B,
-                                             static_cast<uint32_t>(scope), sel_sh);
-  unsigned long long best = ~0ull;
-  for (int i = tid; i < B; i += NT) {
-    if (sc.has(var_key[i], i)) {
-      const unsigned long long cand =
-          (static_cast<unsigned long long>(mas_key[i]) << 32) | static_cast<uint32_t>(i);
-      best = cand < best ? cand : best;
-    }
-  }
-#pragma unroll
-  for (int m = 1; m < kWave; m <<= 1) {
-    const unsigned long long o = __shfl_xor(best, m, kWave);
-    best = o < best ? o : best;
-  }
-  __syncthreads();
-  if ((tid & (kWave - 1)) == 0) best_sh[tid / kWave] = best;
-  __syncthreads();
-  unsigned long long b = best_sh[0];
-#pragma unroll
-  for (int w = 1; w < NT / kWave; ++w) b = best_sh[w] < b ? best_sh[w] : b;
-  return static_cast<int>(b & 0xffffffffu);
-}
-
 // ------------------------------------------------------------------------------------------------
 template <int DT, int D, int U>
 __global__ __launch_bounds__(kAttendThreads) void decode_attend(DecodeArgs a) {

@@ -94,6 +94,7 @@ struct BlockArgs {
   Policy pol;
   int streaming;  // as DecodeArgs::streaming
   int row_bytes;  // bytes of a K / V / q row
+  int single;     // 1: single-token step without block_prepare (set by launch_block)
   int heads;    // query heads that share the unit's keys and values (1 without grouped-query attention)
   int queries;  // query rows per unit = block * heads <= 32; row r belongs to token r / heads, head r % heads
   float scale_log2;

@@ -75,6 +75,16 @@ def test_block_steps_on_a_full_cache(b):
     drive(3, 128, 256, 24, [400, 300, 256], [b] * 4, seed=60 + b, tag=f"full-{b}")
 
 
+def test_single_token_blocks_with_the_preparing_kernel(monkeypatch):
+    """Blocks of one token normally skip the preparing kernel; the general path must give the same step."""
+    monkeypatch.setenv("ROCO_BLOCK_SINGLE", "0")
+    drive(3, 128, 256, 24, [400, 300, 200], [1] * 70, seed=66, tag="prepared-1")
+
+
+def test_single_token_blocks_fill_then_evict_with_recency_bias():
+    drive(3, 128, 192, 16, [150, 192, 100], [1] * 100, seed=67, recency=True, tag="single-recency")
+
+
 @pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 64), ("f32", 128)])
 def test_block_steps_on_the_vector_path_for_other_dtypes_and_head_dims(dtype, d):
     """Shapes the matrix-core kernel is not built for take one vector-ALU pass per query row: same step, same

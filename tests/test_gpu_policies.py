@@ -77,7 +77,7 @@ def test_block_steps_under_each_policy(name):
     sc = 1.0 / math.sqrt(d)
     import paper_2402_06262_amd as roco
     rng = np.random.default_rng(400 + len(name))
-    blocks = [8, 8, 32, 5, 1, 16]
+    blocks = [8, 1, 1, 8, 32, 5, 1, 16]  # single-token blocks take a path of their own: book-keeping in the finish
     L = 200
     T = L + sum(blocks)
     Q = round_to_bf16(rng.standard_normal((units, T, d)).astype(np.float32) + 0.25)

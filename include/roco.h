@@ -278,7 +278,7 @@ enum {
   ROCO_PROF_DECODE_SELECT = 0, ROCO_PROF_DECODE_ATTEND = 1, ROCO_PROF_DECODE_FINISH = 2,
   ROCO_PROF_PREFILL_ROWS = 3, ROCO_PROF_PREFILL_COLUMNS = 4, ROCO_PROF_PREFILL_SELECT = 5,
   ROCO_PROF_PREFILL_GATHER = 6, ROCO_PROF_READ_PROBE = 7, ROCO_PROF_BLOCK_PREPARE = 8,
-  ROCO_PROF_BLOCK_ATTEND = 9, ROCO_PROF_BLOCK_FINISH = 10, ROCO_PROF_KERNELS = 11
+  ROCO_PROF_BLOCK_ATTEND = 9, ROCO_PROF_BLOCK_FINISH = 10, ROCO_PROF_MFMA_PROBE = 11, ROCO_PROF_KERNELS = 12
 };
 int roco_profile_kernel(int which);
 int roco_profile_read(double* total_ms, int64_t* launches);
@@ -293,6 +293,15 @@ int roco_profile_sampling(int every);
  */
 int roco_probe_cache_read(const roco_params* params, const void* K_cache, const void* V_cache,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Benchmark aid: `workgroups` workgroups of four waves, each wave issuing iters x 8 dependent-by-four
+ * v_mfma_f32_32x32x16_bf16 (the instruction of the prefill statistics passes) on register operands and nothing else,
+ * so that a benchmark can measure the matrix throughput the machine at hand sustains (its clock under that load
+ * included).  Flops of one call = workgroups * 4 * iters * 8 * 32768.  sink out [workgroups * 256] fp32 (device):
+ * receives a checksum per lane.  1 <= workgroups <= 1048576, 1 <= iters <= 1048576.
+ */
+int roco_probe_mfma(int32_t workgroups, int32_t iters, float* sink, size_t sink_bytes, void* hip_stream);
 
 /* Static description of a return code. */
 const char* roco_strerror(int code);

@@ -84,6 +84,8 @@ def load_library() -> ctypes.CDLL:
     lib.roco_decode_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.roco_probe_cache_read.restype = ctypes.c_int
     lib.roco_probe_cache_read.argtypes = [pp, vp, vp, vp, sz, vp]
+    lib.roco_probe_mfma.restype = ctypes.c_int
+    lib.roco_probe_mfma.argtypes = [i32, i32, vp, sz, vp]
     lib.roco_block_workspace_bytes.restype = sz
     lib.roco_block_workspace_bytes.argtypes = [pp, i32]
     lib.roco_encode_block.restype = ctypes.c_int
@@ -128,7 +130,7 @@ def decode_workspace_bytes(params: RocoParams) -> int:
 
 PROF_KERNELS = {"decode_select": 0, "decode_attend": 1, "decode_finish": 2, "prefill_rows": 3,
                 "prefill_columns": 4, "prefill_select": 5, "prefill_gather": 6, "read_probe": 7,
-                "block_prepare": 8, "block_attend": 9, "block_finish": 10}
+                "block_prepare": 8, "block_attend": 9, "block_finish": 10, "mfma_probe": 11}
 
 
 def roco_profile_kernel(which: int) -> None:
@@ -281,6 +283,15 @@ def roco_probe_cache_read(params: RocoParams, K_cache, V_cache, workspace, works
                                               int(workspace_bytes), _stream(stream))
     if rc != 0:
         raise RocoError(rc, "roco_probe_cache_read")
+
+
+def roco_probe_mfma(workgroups: int, iters: int, sink, stream=None) -> int:
+    """See include/roco.h: a loop of the prefill passes' matrix instruction (benchmark aid).  Returns the flops."""
+    rc = load_library().roco_probe_mfma(int(workgroups), int(iters), _ptr(sink), sink.numel() * sink.element_size(),
+                                        _stream(stream))
+    if rc != 0:
+        raise RocoError(rc, "roco_probe_mfma")
+    return int(workgroups) * 4 * int(iters) * 8 * 32768
 
 
 def roco_select_victims(params: RocoParams, stats, pos, n_used, next_slot, workspace,

@@ -414,6 +414,14 @@ int roco_probe_cache_read(const roco_params* params, const void* K_cache, const 
   return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
 }
 
+int roco_probe_mfma(int32_t workgroups, int32_t iters, float* sink, size_t sink_bytes, void* hip_stream) {
+  if (workgroups < 1 || workgroups > (1 << 20) || iters < 1 || iters > (1 << 20)) return ROCO_EINVAL;
+  if (sink == nullptr || !aligned16(sink)) return ROCO_EINVAL;
+  if (sink_bytes < static_cast<size_t>(workgroups) * 256 * sizeof(float)) return ROCO_EWORKSPACE;
+  const hipError_t e = launch_mfma_probe(workgroups, iters, sink, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
+}
+
 const char* roco_strerror(int code) {
   switch (code) {
     case ROCO_OK: return "success";

@@ -111,6 +111,11 @@ __device__ __forceinline__ bool locate(int units, int pairs, int& unit, int& pai
   return unit < units;
 }
 
+// Two waves per SIMD leave each lane 256 registers, all of them ordinary vector registers: the score tiles then
+// come out of the matrix instructions where the vector ALU can read them.  (With more registers on offer the
+// compiler parks the tiles in accumulation registers and pays one move per score to get them back.)
+constexpr int kMinWavesPerSimd = 2;
+
 // Online log-sum-exp update of one lane with the 16 scores of a tile.
 //   INTERIOR: every key of the tile is visible to every query of the group and there is no bias:
 //             3 vector instructions per score (multiply-add, exponential, add) plus 8 for the maximum.
@@ -154,7 +159,7 @@ __device__ __forceinline__ void lse_update(const f32x16& s, float sc, int kb, in
 // ------------------------------------------------------------------------------------------------
 // pass 1: lse[i] = log2 sum_{j<=i} 2^(t_ij),  t_ij = scale*log2(e) * q_i.k_j + bias
 template <int WAVES>
-__global__ __launch_bounds__(WAVES * kWave) void prefill_rows_mfma(PrefillArgs a) {
+__global__ __launch_bounds__(WAVES * kWave, kMinWavesPerSimd) void prefill_rows_mfma(PrefillArgs a) {
   constexpr int kOwn = Shape<WAVES>::kOwn;
   __shared__ __attribute__((aligned(16))) char lds[2][kTile * kLdsRow];
   int u, pair_id;  // u counts (unit, query head) pairs: with grouped-query attention a unit has a.group heads
@@ -277,7 +282,7 @@ __device__ __forceinline__ void column_update(const f32x16& s, const float* lse_
 // ------------------------------------------------------------------------------------------------
 // pass 2: Acc[j] = sum_{i>=j} 2^(t_ij - lse_i),  Acc2[j] = sum_{i>=j} (same)^2
 template <int WAVES, bool COUNT>
-__global__ __launch_bounds__(WAVES * kWave) void prefill_columns_mfma(PrefillArgs a) {
+__global__ __launch_bounds__(WAVES * kWave, kMinWavesPerSimd) void prefill_columns_mfma(PrefillArgs a) {
   constexpr int kOwn = Shape<WAVES>::kOwn;
   __shared__ __attribute__((aligned(16))) char lds[2][kTile * kLdsRow];
   __shared__ __attribute__((aligned(16))) float lse_s[2][kTile];
@@ -660,6 +665,33 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_out_mfma(PrefillAr
   }
 }
 
+// Benchmark aid: the matrix instruction of the passes above on register operands, four independent accumulator
+// chains per wave, nothing else.  The checksum keeps the chains alive.
+__global__ __launch_bounds__(256) void mfma_probe(int iters, float* sink) {
+  const int lane = threadIdx.x & (kWave - 1);
+  bf16x8 x, y;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    x[e] = static_cast<__bf16>(0.00390625f * static_cast<float>(1 + ((lane + e) & 3)));
+    y[e] = static_cast<__bf16>(0.0078125f * static_cast<float>(1 + ((lane ^ e) & 1)));
+  }
+  f32x16 acc[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) acc[c] = f32x16{0};
+  for (int i = 0; i < iters; ++i) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, acc[c], 0, 0, 0);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y, x, acc[c], 0, 0, 0);
+  }
+  float sum = 0.0f;
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sum += acc[c][r];
+  sink[static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x] = sum;
+}
+
 template <int WAVES>
 hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
   constexpr int kOwn = Shape<WAVES>::kOwn;
@@ -720,6 +752,12 @@ hipError_t launch_with_output(const PrefillArgs& a, hipStream_t s) {
 }
 
 }  // namespace
+
+hipError_t launch_mfma_probe(int workgroups, int iters, float* sink, hipStream_t s) {
+  ProfScope ps(kProfMfmaProbe, s);
+  hipLaunchKernelGGL(mfma_probe, dim3(static_cast<unsigned>(workgroups)), dim3(256), 0, s, iters, sink);
+  return hipGetLastError();
+}
 
 hipError_t launch_prefill_attention_mfma(const PrefillArgs& a, hipStream_t s) {
   if (a.O != nullptr) return launch_with_output(a, s);

@@ -8,7 +8,8 @@ enum ProfKernel : int {
   kProfDecodeSelect = 0, kProfDecodeAttend = 1, kProfDecodeFinish = 2,
   kProfPrefillRows = 3, kProfPrefillColumns = 4, kProfPrefillSelect = 5, kProfPrefillGather = 6, kProfReadProbe = 7,
   kProfBlockPrepare = 8, kProfBlockAttend = 9, kProfBlockFinish = 10,
-  kProfKernels = 11
+  kProfMfmaProbe = 11,
+  kProfKernels = 12
 };
 
 extern int g_prof_which;  // -1 = off

@@ -33,6 +33,14 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert "workspace" in roco.roco_strerror(EWORKSPACE)
 
 
+def test_mfma_probe_arguments_are_validated_on_the_host():
+    lib = roco.load_library()
+    assert lib.roco_probe_mfma(0, 16, 0x1000, 1 << 20, None) == EINVAL
+    assert lib.roco_probe_mfma(16, 0, 0x1000, 1 << 20, None) == EINVAL
+    assert lib.roco_probe_mfma(16, 16, None, 1 << 20, None) == EINVAL
+    assert lib.roco_probe_mfma(16, 16, 0x1000, 16 * 1024 - 1, None) == EWORKSPACE
+
+
 def test_params_struct_layout_matches_the_header():
     assert ctypes.sizeof(roco.RocoParams) == 44
     names = [f[0] for f in roco.RocoParams._fields_]

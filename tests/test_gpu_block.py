@@ -107,6 +107,11 @@ def test_block_step_many_splits_budget_2048():
     drive(2, 128, 2048, 64, [2300, 2048], [32, 16, 32], seed=73, tag="b2048")
 
 
+def test_block_steps_with_a_budget_above_the_lds_key_limit():
+    """B > 4096: the ranking keys of both finishing shapes and of the preparing kernel live in the workspace."""
+    drive(1, 128, 4104, 40, [4200], [1, 1, 8, 32, 1, 3], seed=74, tag="b4104")
+
+
 def test_block_steps_at_the_serving_shape_all_512_units():
     """Workload 3's shape: all 512 units prefilled 3072 -> 2048, then blocks of 16 tokens; sampled units in
     lock-step with the oracle, any-size properties on every unit."""

@@ -111,11 +111,6 @@ __device__ __forceinline__ bool locate(int units, int pairs, int& unit, int& pai
   return unit < units;
 }
 
-// Two waves per SIMD leave each lane 256 registers, all of them ordinary vector registers: the score tiles then
-// come out of the matrix instructions where the vector ALU can read them.  (With more registers on offer the
-// compiler parks the tiles in accumulation registers and pays one move per score to get them back.)
-constexpr int kMinWavesPerSimd = 2;
-
 // Online log-sum-exp update of one lane with the 16 scores of a tile.
 //   INTERIOR: every key of the tile is visible to every query of the group and there is no bias:
 //             3 vector instructions per score (multiply-add, exponential, add) plus 8 for the maximum.
@@ -159,7 +154,7 @@ __device__ __forceinline__ void lse_update(const f32x16& s, float sc, int kb, in
 // ------------------------------------------------------------------------------------------------
 // pass 1: lse[i] = log2 sum_{j<=i} 2^(t_ij),  t_ij = scale*log2(e) * q_i.k_j + bias
 template <int WAVES>
-__global__ __launch_bounds__(WAVES * kWave, kMinWavesPerSimd) void prefill_rows_mfma(PrefillArgs a) {
+__global__ __launch_bounds__(WAVES * kWave) void prefill_rows_mfma(PrefillArgs a) {
   constexpr int kOwn = Shape<WAVES>::kOwn;
   __shared__ __attribute__((aligned(16))) char lds[2][kTile * kLdsRow];
   int u, pair_id;  // u counts (unit, query head) pairs: with grouped-query attention a unit has a.group heads
@@ -282,7 +277,7 @@ __device__ __forceinline__ void column_update(const f32x16& s, const float* lse_
 // ------------------------------------------------------------------------------------------------
 // pass 2: Acc[j] = sum_{i>=j} 2^(t_ij - lse_i),  Acc2[j] = sum_{i>=j} (same)^2
 template <int WAVES, bool COUNT>
-__global__ __launch_bounds__(WAVES * kWave, kMinWavesPerSimd) void prefill_columns_mfma(PrefillArgs a) {
+__global__ __launch_bounds__(WAVES * kWave) void prefill_columns_mfma(PrefillArgs a) {
   constexpr int kOwn = Shape<WAVES>::kOwn;
   __shared__ __attribute__((aligned(16))) char lds[2][kTile * kLdsRow];
   __shared__ __attribute__((aligned(16))) float lse_s[2][kTile];

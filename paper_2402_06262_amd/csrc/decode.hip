@@ -225,6 +225,9 @@ __global__ __launch_bounds__(kFinishThreads) void decode_finish(DecodeArgs a) {
   extern __shared__ uint32_t lds_keys[];  // [2][B] when B <= kMaxDecodeBudgetLds
   __shared__ uint32_t sel_sh[kSelectLdsWords];
   __shared__ unsigned long long best_sh[NT / kWave];
+  __shared__ float mrg_m[kMaxSplits], mrg_l[kMaxSplits];
+  __shared__ float mrg_o[NT / D][D];
+  static_assert(NT >= kMaxSplits && NT % D == 0, "one thread per split, whole groups per dimension");
 
   const int u = blockIdx.x, tid = threadIdx.x;
   const int B = a.B, S = a.splits;
@@ -234,20 +237,35 @@ __global__ __launch_bounds__(kFinishThreads) void decode_finish(DecodeArgs a) {
   const int n = was_full ? B : n0 + 1;
   const bool full = n >= B;
 
-  const float* pm = a.part_m + static_cast<size_t>(u) * S;
-  const float* pl = a.part_l + static_cast<size_t>(u) * S;
-  // every thread merges the (few) partial normalisers in split order
+  // The partial normalisers come in with one load per thread and are merged from LDS, by every thread, in split
+  // order; a loop of dependent trips to global memory here would cost more than the rest of the kernel when a
+  // unit has many splits.
+  if (tid < S) {
+    mrg_m[tid] = a.part_m[static_cast<size_t>(u) * S + tid];
+    mrg_l[tid] = a.part_l[static_cast<size_t>(u) * S + tid];
+  }
+  __syncthreads();
   float M = -INFINITY;
-  for (int s = 0; s < S; ++s) M = fmaxf(M, pm[s]);
+  for (int s = 0; s < S; ++s) M = fmaxf(M, mrg_m[s]);
   float Lsum = 0.0f;
-  for (int s = 0; s < S; ++s) Lsum += (pm[s] > -INFINITY) ? pl[s] * fast_exp2(pm[s] - M) : 0.0f;
+  for (int s = 0; s < S; ++s) Lsum += (mrg_m[s] > -INFINITY) ? mrg_l[s] * fast_exp2(mrg_m[s] - M) : 0.0f;
   const float inv = 1.0f / Lsum;
 
-  if (tid < D) {
+  // output: the threads form NT / D groups, group g sums the splits g, g + NT / D, ... of its dimension
+  {
+    constexpr int G = NT / D;
+    const int g = tid / D, dd = tid % D;
     const float* po = a.part_o + static_cast<size_t>(u) * S * D;
     float o = 0.0f;
-    for (int s = 0; s < S; ++s) o += (pm[s] > -INFINITY) ? po[s * D + tid] * fast_exp2(pm[s] - M) : 0.0f;
-    store_elem<DT>(a.out, static_cast<size_t>(u) * D + tid, o * inv);
+    for (int s = g; s < S; s += G) o += (mrg_m[s] > -INFINITY) ? po[s * D + dd] * fast_exp2(mrg_m[s] - M) : 0.0f;
+    mrg_o[g][dd] = o;
+    __syncthreads();
+    if (tid < D) {
+      float sum = mrg_o[0][tid];
+#pragma unroll
+      for (int k = 1; k < G; ++k) sum += mrg_o[k][tid];
+      store_elem<DT>(a.out, static_cast<size_t>(u) * D + tid, sum * inv);
+    }
   }
 
   float* acc = a.stats + static_cast<size_t>(u) * 3 * B;

@@ -101,6 +101,25 @@ def causal_probability_rows(Q, K, length: int, scale: float, recency_window: int
         yield i0, P
 
 
+def row_log_sum_exp(Q, K, length: int, scale: float, recency_window: int = 0, recency_bias: float = 0.0,
+                    row_block: int = 512) -> np.ndarray:
+    """lse[i] = ln sum_{j <= i} exp(scale q_i.k_j + bias(i, j)), i < length: the normaliser of row i of the causal
+    softmax (section 2.1, eq. 1), as an attention kernel hands it to a caller that wants the probabilities back
+    (P[i, j] = exp(logit - lse[i])).  Natural logarithm.  Row blocks only bound memory."""
+    Q = np.asarray(Q, dtype=F64)[:length]
+    K = np.asarray(K, dtype=F64)[:length]
+    kpos = np.arange(length)
+    lse = np.empty(length, dtype=F64)
+    for i0 in range(0, length, row_block):
+        i1 = min(length, i0 + row_block)
+        qpos = np.arange(i0, i1)
+        S = (Q[i0:i1] @ K[:i1].T) * F64(scale) + _recency(qpos, kpos[:i1], recency_window, recency_bias)
+        S = np.where(kpos[None, :i1] <= qpos[:, None], S, -np.inf)
+        top = S.max(axis=1)
+        lse[i0:i1] = top + np.log(np.exp(S - top[:, None]).sum(axis=1))
+    return lse
+
+
 @dataclass
 class PrefillStats:
     acc: np.ndarray  # [length]  sum over queries i >= j of P[i, j]

@@ -748,3 +748,36 @@ def test_quantised_score_equals_an_explicit_recount_of_above_average_attention()
     # a block of tokens: each row is compared with the average of what that row attended
     blk = orc.encode_block(st.copy(), Q[:3] + 1.0, K[:3], V[:3], L + T, 3, 0.6, policy=pol)
     assert blk.out.shape == (3, d)
+
+
+def test_row_normalisers_closed_forms():
+    """Q = 0: every visible logit is 0, so lse[i] = ln(i + 1).  d = 1, q = 1, k = ln w, scale 1: lse[i] = ln of the
+    prefix sum of w.  A recency bias b on the last w positions multiplies their terms by e^b."""
+    L, d = 37, 8
+    rng = np.random.default_rng(5)
+    K = rng.standard_normal((L, d))
+    assert np.allclose(orc.row_log_sum_exp(np.zeros((L, d)), K, L, 0.3), np.log(np.arange(1, L + 1)), rtol=0, atol=1e-13)
+    w = rng.uniform(0.5, 3.0, size=L)
+    got = orc.row_log_sum_exp(np.ones((L, 1)), np.log(w)[:, None], L, 1.0, row_block=7)
+    assert np.allclose(got, np.log(np.cumsum(w)), rtol=0, atol=1e-13)
+    b, win = 0.5, 4
+    want = np.empty(L)
+    for i in range(L):
+        terms = [w[j] * (math.e ** b if i - j < win else 1.0) for j in range(i + 1)]
+        want[i] = math.log(sum(terms))
+    got = orc.row_log_sum_exp(np.ones((L, 1)), np.log(w)[:, None], L, 1.0, win, b, row_block=5)
+    assert np.allclose(got, want, rtol=0, atol=1e-13)
+
+
+def test_row_normalisers_give_back_the_probabilities():
+    """exp(logit - lse) are the rows of the causal softmax: they sum to one and match the dense definition."""
+    L, d = 29, 6
+    rng = np.random.default_rng(6)
+    Q, K = rng.standard_normal((L, d)), rng.standard_normal((L, d))
+    sc = 0.37
+    lse = orc.row_log_sum_exp(Q, K, L - 3, sc, 5, 0.25, row_block=8)  # a length shorter than the arrays
+    assert lse.shape == (L - 3,)
+    for i in range(L - 3):
+        logits = np.array([sc * float(Q[i] @ K[j]) + (0.25 if i - j < 5 else 0.0) for j in range(i + 1)])
+        p = np.exp(logits - lse[i])
+        assert abs(p.sum() - 1.0) < 1e-13

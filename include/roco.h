@@ -147,6 +147,23 @@ int roco_prefill_compress_gqa(const roco_params* params, int32_t group,
                               void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * roco_prefill_compress_gqa for callers whose attention kernel has already produced the row normalisers of the
+ * prompt (a flash-attention forward returns them next to its output): the row pass is skipped and only the column
+ * statistics (section 4.3), the eviction and the compaction run.
+ * lse in [units, group, L_max] fp32 (device): lse[u,h,i] = ln sum_{j<=i} exp(scale q_i.k_j + bias(i,j)), the natural
+ * log-sum-exp of the logits exactly as this library forms them (section 2.1, eq. 1; scale and recency bias from
+ * params); rows >= len[u] are ignored.  The probabilities are rebuilt as exp(logit - lse), so normalisers of another
+ * scale or mask give statistics of another attention.  group = 1 for ordinary multi-head attention.  No attention
+ * output is written.  Workspace of roco_prefill_gqa_workspace_bytes (roco_prefill_workspace_bytes when group = 1).
+ */
+int roco_prefill_compress_lse(const roco_params* params, int32_t group,
+                              const void* Q, const void* K, const void* V, const int32_t* len, int32_t L_max,
+                              const float* lse,
+                              void* K_cache, void* V_cache, float* stats, int32_t* pos, int32_t* n_used,
+                              int32_t* next_slot,
+                              void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * One auto-regressive decode step on the budgeted cache, in place (Fig. 1: one key/value pair is
  * deleted before the next token's is appended; section 4: evict when the buffer is full).
  *

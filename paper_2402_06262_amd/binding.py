@@ -74,6 +74,8 @@ def load_library() -> ctypes.CDLL:
     lib.roco_prefill_gqa_workspace_bytes.argtypes = [pp, i32, i32]
     lib.roco_prefill_compress_gqa.restype = ctypes.c_int
     lib.roco_prefill_compress_gqa.argtypes = [pp, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.roco_prefill_compress_lse.restype = ctypes.c_int
+    lib.roco_prefill_compress_lse.argtypes = [pp, i32, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.roco_decode_workspace_bytes.restype = sz
     lib.roco_decode_workspace_bytes.argtypes = [pp]
     lib.roco_decode_step_launches.restype = ctypes.c_int
@@ -218,6 +220,20 @@ def roco_prefill_compress_gqa(params: RocoParams, group: int, Q, K, V, lens, L_m
         int(workspace_bytes), _stream(stream))
     if rc != 0:
         raise RocoError(rc, "roco_prefill_compress_gqa")
+
+
+def roco_prefill_compress_lse(params: RocoParams, group: int, Q, K, V, lens, L_max: int, lse, K_cache, V_cache, stats,
+                              pos, n_used, next_slot, workspace, workspace_bytes: Optional[int] = None,
+                              stream=None) -> None:
+    """See include/roco.h: prefill-compress from row normalisers the caller's attention kernel already produced."""
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    rc = load_library().roco_prefill_compress_lse(
+        ctypes.byref(params), int(group), _ptr(Q), _ptr(K), _ptr(V), _ptr(lens), int(L_max), _ptr(lse), _ptr(K_cache),
+        _ptr(V_cache), _ptr(stats), _ptr(pos), _ptr(n_used), _ptr(next_slot), _ptr(workspace), int(workspace_bytes),
+        _stream(stream))
+    if rc != 0:
+        raise RocoError(rc, "roco_prefill_compress_lse")
 
 
 def decode_step_launches(params: RocoParams) -> int:

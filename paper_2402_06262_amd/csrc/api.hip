@@ -164,9 +164,10 @@ namespace {
 int run_prefill(const roco_params* params, int group, const void* Q, const void* K, const void* V,
                 const int32_t* len, int32_t L_max, void* K_cache, void* V_cache, float* stats,
                 int32_t* pos, int32_t* n_used, int32_t* next_slot, void* O, void* workspace,
-                size_t workspace_bytes, void* hip_stream) {
+                size_t workspace_bytes, void* hip_stream, const float* lse_given = nullptr, bool want_lse = false) {
   const int rc = check_params(params);
   if (rc != ROCO_OK) return rc;
+  if (want_lse && (lse_given == nullptr || !aligned16(lse_given) || O != nullptr)) return ROCO_EINVAL;
   if (L_max < 1 || L_max > (1 << 24)) return ROCO_EINVAL;
   if (group < 1) return ROCO_EINVAL;
   if (group > kMaxPrefillGroup || static_cast<long long>(params->units) * group > 65535) return ROCO_EUNSUPPORTED;
@@ -184,6 +185,7 @@ int run_prefill(const roco_params* params, int group, const void* Q, const void*
   a.pairs = 0;
   a.paired = env_int("ROCO_PREFILL_PAIRED", -1);
   a.mfma_waves = env_int("ROCO_PREFILL_WAVES", 0);
+  a.skip_rows = want_lse ? 1 : 0;
   a.scale_log2 = scale_log2(params);
   a.recency_window = params->recency_window;
   a.recency_bias_log2 = params->recency_bias * 1.4426950408889634f;
@@ -199,6 +201,10 @@ int run_prefill(const roco_params* params, int group, const void* Q, const void*
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const bool mfma = params->dtype == ROCO_BF16 && params->head_dim == 128 &&
                     env_int("ROCO_PREFILL_SIMPLE", 0) == 0;
+  if (want_lse) {  // the kernels keep base-2 normalisers
+    const size_t count = static_cast<size_t>(params->units) * group * L_max;
+    if (launch_lse_to_base2(lse_given, a.lse, count, s) != hipSuccess) return ROCO_EHIP;
+  }
   hipError_t e = mfma ? launch_prefill_attention_mfma(a, s)
                       : launch_prefill_attention_simple(params->dtype, params->head_dim, a, s);
   if (e != hipSuccess) return ROCO_EHIP;
@@ -227,6 +233,14 @@ int roco_prefill_compress_gqa(const roco_params* params, int32_t group, const vo
                               size_t workspace_bytes, void* hip_stream) {
   return run_prefill(params, group, Q, K, V, len, L_max, K_cache, V_cache, stats, pos, n_used, next_slot, O,
                      workspace, workspace_bytes, hip_stream);
+}
+
+int roco_prefill_compress_lse(const roco_params* params, int32_t group, const void* Q, const void* K, const void* V,
+                              const int32_t* len, int32_t L_max, const float* lse, void* K_cache, void* V_cache,
+                              float* stats, int32_t* pos, int32_t* n_used, int32_t* next_slot, void* workspace,
+                              size_t workspace_bytes, void* hip_stream) {
+  return run_prefill(params, group, Q, K, V, len, L_max, K_cache, V_cache, stats, pos, n_used, next_slot, nullptr,
+                     workspace, workspace_bytes, hip_stream, lse, true);
 }
 
 int roco_decode_step(const roco_params* params, const void* q, const void* k_new, const void* v_new,

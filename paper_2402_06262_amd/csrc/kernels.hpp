@@ -68,6 +68,7 @@ struct PrefillArgs {
   int pairs;             // matrix-core path: workgroup ids per unit (set by its launcher)
   int paired;            // matrix-core path: 1 = long+short block per workgroup, 0 = one block, -1 = choose
   int mfma_waves;        // matrix-core path: 4 or 8 waves per workgroup, 0 = choose by problem size
+  int skip_rows;         // 1: lse already holds the row normalisers, pass 1 is not run
   float scale_log2;
   int recency_window;
   float recency_bias_log2;
@@ -128,6 +129,7 @@ hipError_t launch_select_retained(const DecodeArgs& a, int keep, int32_t* mask, 
 hipError_t launch_prefill_attention_simple(int dtype, int head_dim, const PrefillArgs& a, hipStream_t s);
 hipError_t launch_prefill_attention_mfma(const PrefillArgs& a, hipStream_t s);  // bf16, head_dim 128
 // overwrites PrefillArgs::acc2 with the attention row of each unit's last prompt token (kImpLast)
+hipError_t launch_lse_to_base2(const float* lse_ln, float* lse_log2, size_t n, hipStream_t s);
 hipError_t launch_prefill_last_row(int dtype, int head_dim, const PrefillArgs& a, hipStream_t s);
 hipError_t launch_prefill_select_compact(int dtype, int head_dim, const PrefillArgs& a, hipStream_t s);
 

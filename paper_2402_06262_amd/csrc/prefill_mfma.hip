@@ -696,7 +696,7 @@ hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
   b.pairs = b.paired ? (n_blocks + 1) / 2 : n_blocks;  // ids per unit
   const dim3 grid(static_cast<unsigned>((a.units + 7) / 8 * 8 * b.pairs));
   const dim3 rows_grid(static_cast<unsigned>((a.units * a.group + 7) / 8 * 8 * b.pairs));  // one id set per query head
-  {
+  if (!a.skip_rows) {
     ProfScope ps(kProfPrefillRows, s);
     hipLaunchKernelGGL(prefill_rows_mfma<WAVES>, rows_grid, dim3(WAVES * kWave), 0, s, b);
   }

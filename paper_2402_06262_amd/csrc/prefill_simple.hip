@@ -130,7 +130,7 @@ __global__ __launch_bounds__(kThreads) void prefill_columns_simple(PrefillArgs a
 template <int DT, int D>
 hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
   const dim3 grid((a.L_max + kWaves - 1) / kWaves, a.units);
-  {
+  if (!a.skip_rows) {
     ProfScope ps(kProfPrefillRows, s);
     const dim3 rows_grid(grid.x, static_cast<unsigned>(a.units) * a.group);
     hipLaunchKernelGGL((prefill_rows_simple<DT, D>), rows_grid, dim3(kThreads), 0, s, a);
@@ -179,7 +179,20 @@ __global__ __launch_bounds__(kThreads) void prefill_last_row(PrefillArgs a) {
   }
 }
 
+// Row normalisers handed in as natural logarithms, rescaled to the base-2 form the passes use.
+__global__ __launch_bounds__(kThreads) void lse_to_base2(const float* in, float* out, size_t n) {
+  const size_t i = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
+  if (i < n) out[i] = in[i] * 1.4426950408889634f;
+}
+
 }  // namespace
+
+hipError_t launch_lse_to_base2(const float* lse_ln, float* lse_log2, size_t n, hipStream_t s) {
+  const size_t blocks = (n + kThreads - 1) / kThreads;
+  if (blocks == 0 || blocks > 0x7fffffffull) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(lse_to_base2, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, s, lse_ln, lse_log2, n);
+  return hipGetLastError();
+}
 
 hipError_t launch_prefill_last_row(int dtype, int head_dim, const PrefillArgs& a, hipStream_t s) {
   const dim3 grid(a.units), block(kThreads);

@@ -33,6 +33,20 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert "workspace" in roco.roco_strerror(EWORKSPACE)
 
 
+def test_prefill_from_given_normalisers_validates_its_arguments():
+    lib = roco.load_library()
+    p = roco.RocoParams(4, 128, 64, 8, roco.ROCO_BF16)
+    need = roco.prefill_workspace_bytes(p, 100)
+    ok = 0x1000
+    call = lambda lse, ws_bytes, group=1: lib.roco_prefill_compress_lse(
+        ctypes.byref(p), group, ok, ok, ok, ok, 100, lse, ok, ok, ok, ok, ok, ok, ok, ws_bytes, None)
+    assert call(None, need) == EINVAL          # the normalisers are the point of this entry
+    assert call(0x1004, need) == EINVAL        # misaligned
+    assert call(ok, need - 1) == EWORKSPACE
+    assert call(ok, need, group=0) == EINVAL
+    assert call(ok, need, group=65) == EUNSUPPORTED
+
+
 def test_mfma_probe_arguments_are_validated_on_the_host():
     lib = roco.load_library()
     assert lib.roco_probe_mfma(0, 16, 0x1000, 1 << 20, None) == EINVAL

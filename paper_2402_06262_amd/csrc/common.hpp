@@ -129,17 +129,17 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s
 // integers and is exact.  radix_select finds the k-th smallest key (k is 1-based, 1 <= k <= n) among
 // key_of(0..n-1), 8-bit digits from the top; it also returns how many keys are strictly smaller and how
 // many are equal.  Two histograms alternate (the idle one is cleared while the other is scanned), which
-// leaves three barriers per digit; and as soon as the chosen bin holds a single key the remaining digits are
-// read off that key instead of being counted.  `sh` needs kSelectLdsWords words of LDS.  All threads of
-// the block call it.
-constexpr int kSelectLdsWords = 2 * 256 + 8;
+// leaves three barriers per digit; and as soon as the chosen bin holds no more keys than a wave has lanes the
+// remaining digits are not counted: one wave ranks those keys directly.  `sh` needs kSelectLdsWords words of
+// LDS.  All threads of the block call it.
+constexpr int kSelectLdsWords = 2 * 256 + 12;
 
 template <int NT, class KeyFn>
 __device__ void radix_select(KeyFn key_of, int n, uint32_t k, uint32_t* sh,
                              uint32_t& kth, uint32_t& n_less, uint32_t& n_equal) {
   static_assert(NT >= 256 && NT % kWave == 0, "one thread per histogram bin");
   uint32_t* wtot = sh + 512;  // inclusive totals of the four scanning waves
-  uint32_t* res = sh + 516;   // bin, keys below the bin, keys in the bin, the key itself (early exit)
+  uint32_t* res = sh + 516;   // bin, keys below the bin, keys in the bin, the key itself and a counter (early exit)
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   __syncthreads();  // `sh` may still be in use by a previous call
   if (tid < 256) sh[tid] = 0;
@@ -165,7 +165,7 @@ __device__ void radix_select(KeyFn key_of, int n, uint32_t k, uint32_t* sh,
     if (tid < 256) {
       for (int w = 0; w < wave; ++w) incl += wtot[w];
       const uint32_t excl = incl - h;
-      if (excl < kk && kk <= incl) { res[0] = tid; res[1] = excl; res[2] = h; }
+      if (excl < kk && kk <= incl) { res[0] = tid; res[1] = excl; res[2] = h; res[4] = 0; }
     }
     __syncthreads();
     prefix |= res[0] << shift;
@@ -173,13 +173,29 @@ __device__ void radix_select(KeyFn key_of, int n, uint32_t k, uint32_t* sh,
     less += res[1];
     kk -= res[1];
     neq = res[2];
-    if (neq == 1 && pass < 3) {  // a single candidate is left: it is the answer
+    if (neq <= kWave && pass < 3) {
+      // At most a wave's worth of candidates is left: they are gathered (into the idle histogram, which is clear)
+      // and ranked by one wave directly, every lane counting the candidates below and equal to its own.
+      uint32_t* cand = idle;
       for (int i = tid; i < n; i += NT) {
         const uint32_t key = key_of(i);
-        if ((key & mask) == prefix) res[3] = key;
+        if ((key & mask) == prefix) cand[atomicAdd(&res[4], 1u)] = key;
+      }
+      __syncthreads();
+      if (tid < kWave) {
+        const uint32_t mine = tid < neq ? cand[tid] : 0xffffffffu;
+        uint32_t lt = 0, eq = 0;
+        for (uint32_t m = 0; m < neq; ++m) {
+          const uint32_t other = cand[m];
+          lt += other < mine ? 1u : 0u;
+          eq += other == mine ? 1u : 0u;
+        }
+        if (tid < neq && lt < kk && kk <= lt + eq) { res[1] = lt; res[2] = eq; res[3] = mine; }  // equal lanes agree
       }
       __syncthreads();
       prefix = res[3];
+      less += res[1];
+      neq = res[2];
       break;
     }
   }

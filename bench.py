@@ -231,6 +231,46 @@ def main():
     torch.cuda.synchronize()
     ms, n = roco.roco_profile_read()
     probe_alone_s = ms * 1e-3 / max(1, n)
+    # The same decode loop with the batch split into two halves (8 sequences each) on two HIP streams of default
+    # priority: while one half's kernel is in its selection tail, or between two launches, the other half's streams.
+    two_streams = None
+    if U % 2 == 0 and roco.decode_step_launches(roco.RocoParams(U // 2, d, B, s, roco.ROCO_BF16)) == 1:
+        Uh = U // 2
+        ph = roco.RocoParams(Uh, d, B, s, roco.ROCO_BF16)
+        phref = ctypes.byref(ph)
+        ws_h = [torch.empty(roco.decode_workspace_bytes(ph), dtype=torch.uint8, device="cuda") for _ in range(2)]
+        side = [torch.cuda.Stream(), torch.cuda.Stream()]
+        rowh, cnth = Uh * d * esz, Uh * 4
+        halves = []
+        for h in range(2):
+            halves.append((cK + h * Uh * B * d * esz, cV + h * Uh * B * d * esz, cS + h * Uh * 3 * B * 4,
+                           cP + h * Uh * B * 4, cN + h * cnth, cX + h * cnth, ws_h[h].data_ptr(), ws_h[h].numel(),
+                           side[h].cuda_stream))
+
+        def decode_halves():
+            for t in range(decode_steps):
+                a = step_args[t]
+                for h, (hK, hV, hS, hP, hN, hX, hw, hwb, hs) in enumerate(halves):
+                    rc = lib.roco_decode_step(phref, a[0] + h * rowh, a[1] + h * rowh, a[2] + h * rowh, a[3] + h * cnth,
+                                              hK, hV, hS, hP, hN, hX, a[4] + h * rowh, a[5] + h * cnth, a[6] + h * cnth,
+                                              hw, hwb, hs)
+                    if rc != 0:
+                        raise roco.RocoError(rc, "roco_decode_step")
+
+        for st in side:
+            st.wait_stream(stream)
+        decode_halves()  # warm-up
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        decode_halves()
+        torch.cuda.synchronize()
+        dt2 = time.perf_counter() - t0
+        stream.wait_stream(side[0]); stream.wait_stream(side[1])
+        assert int(cache.n_used.min()) == B and int(cache.n_used.max()) == B
+        two_streams = {"workload": "the same 16 sequences as two halves of 8 on two HIP streams, %d steps" % decode_steps,
+                       "ms_per_token_step": dt2 / decode_steps * 1e3,
+                       "tokens_per_s": cfg.batch * decode_steps / dt2,
+                       "step_frac_of_hbm_peak": step_bytes / (dt2 / decode_steps) / 1e9 / HBM_PEAK_GBS}
     # a short extra pass (outside the timed region) with events around the two prefill statistics kernels
     pre_kernel_ms = {}
     for name in ("prefill_rows", "prefill_columns", "prefill_select", "prefill_gather"):
@@ -427,6 +467,7 @@ def main():
                                  "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                  "frac": step_bytes / (decode_ms * 1e-3 / (decode_steps * args.steps)) / 1e9 / HBM_PEAK_GBS,
                                  "bytes_per_step": step_bytes},
+        "decode_two_streams": two_streams,
         "prefill_with_attention_output": with_output,
         "prefill_given_row_normalisers": given_lse,
         "roofline_prefill": {"bound": "mfma", "achieved": prefill_flops / (prefill_ms * 1e-3 / args.steps) / 1e12,

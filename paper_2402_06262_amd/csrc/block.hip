@@ -14,9 +14,9 @@
 //                   slots against the block's (up to 32) queries on the matrix cores (score tile = K . Q^T, the
 //                   query in the lane), stores the base-2 logits, keeps an online softmax per query and
 //                   accumulates O^T = V^T . P^T with V^T fragments from the LDS transpose read.
-//   block_finish  : grid (slot chunks, units).  Merges the partials per query, writes the outputs, adds the
-//                   statistics of all rows to every slot.  The select_victims kernel of the decode path then
-//                   chooses the victim a following decode step would take.
+//   block_finish  : one workgroup per unit.  Merges the partials per query, writes the outputs, adds the
+//                   statistics of all rows to every slot and chooses the victim a following single-token step
+//                   would take.
 //
 // The same three kernels serve grouped-query attention (section 5.3, "Extension to Grouped-Query Attention"):
 // g query heads share the unit's keys and values, the query rows are (token, head) pairs, and the statistics
@@ -35,8 +35,7 @@ using namespace mfma;
 
 constexpr int kPrepThreads = 1024;
 constexpr int kAttThreads = 128;  // two waves: one 32-slot half of a 64-slot tile each
-constexpr int kFinThreads = 256;
-constexpr int kFinSlots = 2 * kFinThreads;  // slots per block_finish workgroup
+constexpr int kFinThreads = 1024;
 constexpr int kQ = 32;            // queries per matrix tile; a block holds at most this many tokens
 
 // ------------------------------------------------------------------------------------------------
@@ -416,22 +415,23 @@ __global__ __launch_bounds__(256) void block_attend_simple(BlockArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// Grid (chunks, units): workgroup (c, u) owns slots [c * kFinSlots, (c + 1) * kFinSlots) of unit u and the query
-// rows r = c, c + chunks, ...  The victim for a following single-token step is chosen afterwards by the
-// select_victims kernel, from the statistics written here.
-template <int DT, int D, bool SELECT, int NT>
-__global__ __launch_bounds__(NT) void block_finish(BlockArgs a) {
-  constexpr int kSlots = 2 * NT;  // slots per workgroup and sweep
-  extern __shared__ uint32_t lds_keys[];  // SELECT: [2][B] ranking keys when B <= kMaxDecodeBudgetLds
-  __shared__ uint32_t sel_sh[SELECT ? kSelectLdsWords : 1];
+// One workgroup per unit: it walks all slots of the unit two per thread and sweep, keeps the ranking keys in LDS and
+// chooses the next victim itself.  (Spreading the update over slot chunks and selecting in a launch of its own
+// measured slower for every number of query rows: the extra launch costs more than the longer sweep.)
+template <int DT, int D>
+__global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
+  constexpr int NT = kFinThreads;
+  constexpr int kSlots = 2 * NT;  // slots per sweep
+  extern __shared__ uint32_t lds_keys[];  // [2][B] ranking keys when B <= kMaxDecodeBudgetLds
+  __shared__ uint32_t sel_sh[kSelectLdsWords];
   __shared__ unsigned long long best_sh[NT / kWave];
   __shared__ float Mq[kQ], invq[kQ];
-  const int u = blockIdx.y, chunk = blockIdx.x, chunks = gridDim.x, tid = threadIdx.x;
+  const int u = blockIdx.x, tid = threadIdx.x;
   const int B = a.B, nq = a.queries, S = a.splits;
   int n = a.n_used[u];
   int fresh = -1;  // single-token step without block_prepare: the slot the token took, which this kernel books
   bool evicted = false;
-  if (SELECT && a.single) {
+  if (a.single) {
     evicted = n >= B;
     fresh = evicted ? min(max(a.next_slot[u], 0), B - 1) : n;
     n = evicted ? B : n + 1;
@@ -454,7 +454,7 @@ __global__ __launch_bounds__(NT) void block_finish(BlockArgs a) {
     invq[tid] = 1.0f / L;
   }
   __syncthreads();  // every thread has read n_used and next_slot
-  if (SELECT && a.single && tid == 0) {
+  if (a.single && tid == 0) {
     int32_t* pos = a.pos + static_cast<size_t>(u) * B;
     const int old_pos = pos[fresh];
     pos[fresh] = a.qpos0[u];
@@ -463,9 +463,8 @@ __global__ __launch_bounds__(NT) void block_finish(BlockArgs a) {
     if (a.evicted_pos) a.evicted_pos[u] = evicted ? old_pos : -1;
   }
   // outputs of this workgroup's query rows
-  const int my_rows = nq > chunk ? (nq - chunk + chunks - 1) / chunks : 0;
-  for (int idx = tid; idx < my_rows * D; idx += NT) {
-    const int q = chunk + (idx / D) * chunks, dd = idx % D;
+  for (int idx = tid; idx < nq * D; idx += NT) {
+    const int q = idx / D, dd = idx % D;
     float o = 0.0f;
     for (int s = 0; s < S; ++s) {
       const float ms = pm[s * kQ + q];
@@ -482,11 +481,9 @@ __global__ __launch_bounds__(NT) void block_finish(BlockArgs a) {
   uint32_t* var_key = (B <= kMaxDecodeBudgetLds) ? lds_keys : a.keys + static_cast<size_t>(u) * 2 * B;
   uint32_t* mas_key = var_key + B;
   const bool by_pos = a.pol.needs_pos();
-  // B is a multiple of 4 on this path, so a pair of slots is inside [0, B).  Without SELECT a workgroup owns one
-  // chunk of slots; with it, one workgroup walks all chunks of its unit and then chooses the next victim itself.
-  const int j_end = SELECT ? n : min(n, (chunk + 1) * kSlots);
-  for (int j = chunk * kSlots + tid * 2; j < j_end; j += kSlots) {
-  const int2 bi = (SELECT && a.single) ? make_int2(-1, -1)
+  // B is a multiple of 4 on this path, so a pair of slots is inside [0, B).
+  for (int j = tid * 2; j < n; j += kSlots) {
+  const int2 bi = a.single ? make_int2(-1, -1)
                                        : *reinterpret_cast<const int2*>(a.blk_idx + static_cast<size_t>(u) * B + j);
   const float2 a1 = *reinterpret_cast<const float2*>(acc + j);
   const float2 a2 = *reinterpret_cast<const float2*>(acc2 + j);
@@ -518,7 +515,7 @@ __global__ __launch_bounds__(NT) void block_finish(BlockArgs a) {
   *reinterpret_cast<float2*>(acc + j) = make_float2(s1[0], s1[1]);
   *reinterpret_cast<float2*>(acc2 + j) = make_float2(s2[0], s2[1]);
   *reinterpret_cast<float2*>(cnt + j) = make_float2(sc[0], sc[1]);
-  if (SELECT && full) {
+  if (full) {
 #pragma unroll
     for (int e = 0; e < 2; ++e)
       if (j + e < n)
@@ -527,22 +524,17 @@ __global__ __launch_bounds__(NT) void block_finish(BlockArgs a) {
                      mas_key[j + e], var_key[j + e]);
   }
   }
-  if (SELECT) {  // the victim a following single-token step would take
-    if (full) {
-      __syncthreads();
-      const int victim = select_victim_block<NT>(var_key, mas_key, B, a.pol.scope_size(a.scope, B), sel_sh, best_sh);
-      if (tid == 0) a.next_slot[u] = victim;
-    } else if (tid == 0) {
-      a.next_slot[u] = -1;
-    }
+  // the victim a following single-token step would take
+  if (full) {
+    __syncthreads();
+    const int victim = select_victim_block<NT>(var_key, mas_key, B, a.pol.scope_size(a.scope, B), sel_sh, best_sh);
+    if (tid == 0) a.next_slot[u] = victim;
+  } else if (tid == 0) {
+    a.next_slot[u] = -1;
   }
 }
 
 }  // namespace
-
-// Few query rows (a grouped decode step, a short block): one workgroup per unit updates the statistics and chooses
-// the next victim in place.  Many rows: the update is spread over slot chunks and the selection is a launch of its own.
-static bool finish_selects(const BlockArgs& a) { return a.queries <= 4; }
 
 // ROCO_BLOCK_SINGLE=0 keeps block_prepare in single-token steps (tests run both).
 static bool single_step_off() {
@@ -553,13 +545,8 @@ static bool single_step_off() {
 template <int DT, int D>
 void launch_block_tail(const BlockArgs& a, hipStream_t s) {
   ProfScope ps(kProfBlockFinish, s);
-  if (finish_selects(a)) {
-    const size_t key_lds = (a.B <= kMaxDecodeBudgetLds) ? static_cast<size_t>(a.B) * 2 * sizeof(uint32_t) : 0;
-    hipLaunchKernelGGL((block_finish<DT, D, true, 1024>), dim3(1, a.units), dim3(1024), key_lds, s, a);
-  } else {
-    hipLaunchKernelGGL((block_finish<DT, D, false, kFinThreads>), dim3((a.B + kFinSlots - 1) / kFinSlots, a.units),
-                       dim3(kFinThreads), 0, s, a);
-  }
+  const size_t key_lds = (a.B <= kMaxDecodeBudgetLds) ? static_cast<size_t>(a.B) * 2 * sizeof(uint32_t) : 0;
+  hipLaunchKernelGGL((block_finish<DT, D>), dim3(a.units), dim3(kFinThreads), key_lds, s, a);
 }
 
 template <int DT, int D>
@@ -574,8 +561,8 @@ void launch_block_simple(const BlockArgs& a, hipStream_t s) {
 // dtype / head_dim other than bf16 / 128 take the vector-ALU attention (a.splits must then be 1)
 hipError_t launch_block(int dtype, int head_dim, const BlockArgs& args, hipStream_t s) {
   BlockArgs a = args;
-  // A single-token step on the matrix-core path whose finishing kernel also selects needs no block_prepare.
-  a.single = (a.block == 1 && finish_selects(a) && dtype == kBF16 && head_dim == 128 && !single_step_off()) ? 1 : 0;
+  // A single-token step on the matrix-core path needs no block_prepare.
+  a.single = (a.block == 1 && dtype == kBF16 && head_dim == 128 && !single_step_off()) ? 1 : 0;
   const size_t key_lds = (a.B <= kMaxDecodeBudgetLds) ? static_cast<size_t>(a.B) * 2 * sizeof(uint32_t) : 0;
   constexpr size_t kAttLds = 4 * static_cast<size_t>(kTileBytes);  // 68 KiB: above the default dynamic limit
   const bool mfma_path = dtype == kBF16 && head_dim == 128;
@@ -606,11 +593,7 @@ hipError_t launch_block(int dtype, int head_dim, const BlockArgs& args, hipStrea
     return hipErrorInvalidValue;
   }
   if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
-  if (finish_selects(a)) return hipSuccess;
-  DecodeArgs sel = {};  // the victim a following single-token decode step would take
-  sel.units = a.units; sel.B = a.B; sel.scope = a.scope; sel.pol = a.pol; sel.pos = a.pos;
-  sel.stats = a.stats; sel.n_used = a.n_used; sel.next_slot = a.next_slot; sel.keys = a.keys;
-  return launch_select_victims(sel, s);
+  return hipSuccess;
 }
 
 }  // namespace roco

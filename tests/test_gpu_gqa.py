@@ -63,8 +63,8 @@ def drive(units, B, s, group, blocks, seed, recency=False, tag="", single_token_
 
 @pytest.fixture(params=["single", "prepared"])
 def single_step(request, monkeypatch):
-    """A single-token step of up to four heads books its token inside the attention and finishing kernels; the
-    general block path (a preparing kernel first) stays selectable, and both must agree with the oracle."""
+    """A single-token step books its token inside the attention and finishing kernels; the general block path (a
+    preparing kernel first) stays selectable, and both must agree with the oracle."""
     monkeypatch.setenv("ROCO_BLOCK_SINGLE", "0" if request.param == "prepared" else "1")
     return request.param
 
@@ -72,8 +72,6 @@ def single_step(request, monkeypatch):
 @pytest.mark.parametrize("group", [1, 2, 4, 8, 32])
 def test_grouped_decode_steps_fill_then_evict(group, single_step):
     """Token-wise grouped-query decode from an empty cache: 96 appends, then 40 evicting steps."""
-    if group > 4 and single_step == "prepared":
-        pytest.skip("more than four heads always take the preparing kernel")
     drive(3, 96, 12, group, [1] * 136, seed=80 + group, tag=f"gqa-decode-g{group}", single_token_entry=True)
 
 

@@ -267,3 +267,72 @@ def test_group_of_one_matches_the_token_wise_decode_step_bit_for_bit_in_its_deci
     ha, hb = P.cache_to_host(a), P.cache_to_host(b)
     assert np.array_equal(ha["pos"], hb["pos"]) and np.array_equal(ha["stats"][:, 2], hb["stats"][:, 2])
     P.assert_stat_close(hb["stats"][:, 0], ha["stats"][:, 0].astype(np.float64), "Acc")
+
+
+def test_grouped_and_block_steps_captured_in_a_hip_graph_replay_like_eager_steps():
+    """The block-wise and grouped steps allocate nothing and never synchronise either.  A grouped single-token step,
+    a grouped block and another single-token step are captured once and replayed three times with eager work and
+    synchronisations in between; every replay must leave exactly what the same calls leave when launched eagerly."""
+    import paper_2402_06262_amd as roco
+    import test_gpu_parity as TP
+    P = _P()
+    units, L, B, s, d, g, b = 5, 180, 96, 12, 128, 4, 6
+    rng = np.random.default_rng(77)
+    T = L + 2 + b
+    Q = round_to_bf16(rng.standard_normal((units, g, T, d)).astype(np.float32) + 0.2)
+    K = round_to_bf16(rng.standard_normal((units, T, d)).astype(np.float32))
+    V = round_to_bf16(rng.standard_normal((units, T, d)).astype(np.float32))
+    sess = P.make_session(units, d, B, s, "bf16")
+    P.gpu_prefill_gqa(sess, g, Q[:, :, :L].copy(), K[:, :L].copy(), V[:, :L].copy(), [L, L, 150, 96, 40], False)
+    c, p = sess.cache, sess.params
+    ws = torch.empty(roco.block_workspace_bytes(p, b), dtype=torch.uint8, device="cuda")
+    dev = lambda x: P.to_dev(np.ascontiguousarray(x), "bf16")
+    lens = torch.tensor([L, L, 150, 96, 40], dtype=torch.int32, device="cuda")
+    q1, k1, v1 = dev(Q[:, :, L]), dev(K[:, L]), dev(V[:, L])
+    qb, kb, vb = dev(Q[:, :, L + 1:L + 1 + b].transpose(0, 2, 1, 3)), dev(K[:, L + 1:L + 1 + b]), dev(V[:, L + 1:L + 1 + b])
+    q2, k2, v2 = dev(Q[:, :, T - 1]), dev(K[:, T - 1]), dev(V[:, T - 1])
+    pos1, posb, pos2 = lens.clone(), lens + 1, lens + 1 + b
+    o1 = torch.zeros((units, g, d), dtype=torch.bfloat16, device="cuda")
+    ob = torch.zeros((units, b, g, d), dtype=torch.bfloat16, device="cuda")
+    o2 = torch.zeros_like(o1)
+    e1 = torch.zeros((units,), dtype=torch.int32, device="cuda")
+    eb = torch.zeros((units, b), dtype=torch.int32, device="cuda")
+    e2 = torch.zeros_like(e1)
+
+    def run_steps():
+        roco.roco_decode_step_gqa(p, g, q1, k1, v1, pos1, c.K, c.V, c.stats, c.pos, c.n_used, c.next_slot, o1, e1, None, ws)
+        roco.roco_encode_block_gqa(p, b, g, qb, kb, vb, posb, c.K, c.V, c.stats, c.pos, c.n_used, c.next_slot, ob, eb,
+                                   None, ws)
+        roco.roco_decode_step_gqa(p, g, q2, k2, v2, pos2, c.K, c.V, c.stats, c.pos, c.n_used, c.next_slot, o2, e2, None, ws)
+
+    def snapshot():
+        return [x.clone() for x in (o1, ob, o2, e1, eb, e2)] + TP._state(c)
+
+    start = TP._state(c)
+    want = []
+    for _ in range(3):  # the state keeps evolving from round to round (positions repeat; only equality matters here)
+        run_steps()
+        torch.cuda.synchronize()
+        want.append(snapshot())
+    TP._restore(c, start)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run_steps()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    TP._restore(c, start)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run_steps()
+    TP._restore(c, start)
+    torch.cuda.synchronize()
+    scratch = torch.zeros(1 << 20, device="cuda")
+    for r in range(3):
+        graph.replay()
+        scratch.add_(1.0)
+        torch.cuda.synchronize()
+        for a, w in zip(snapshot(), want[r]):
+            assert torch.equal(a, w), f"replay {r} differs from the eager calls"

@@ -31,7 +31,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix peak
 # HBM-side bytes of one decode_attend launch on this workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a
 # plain copy of known size (profiles/decode_prefill_workload3_rocprofv3.txt); only valid for the default shape.
 ATTEND_TRAFFIC_BYTES = 543662034
-FUSED_TRAFFIC_BYTES = 563477240  # decode_fused (the shape the step takes on this workload): see the same file
+FUSED_TRAFFIC_BYTES = 563454305  # decode_fused (the shape the step takes on this workload): see the same file
 
 
 def generate(cfg, seed, workers):
@@ -106,6 +106,8 @@ def main():
     ap.add_argument("--cpu-steps", type=int, default=512)
     ap.add_argument("--with-out", action="store_true", help="also produce the prefill attention output O")
     ap.add_argument("--no-blockwise", action="store_true", help="skip the block-wise evict-and-encode table")
+    ap.add_argument("--no-two-streams", action="store_true",
+                    help="skip the decode loop with the batch split over two HIP streams")
     ap.add_argument("--no-consistency", action="store_true", help="skip the synthetic consistency study")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 512 MiB device copy (a kernel of known traffic, to scale rocprofv3's "
@@ -234,7 +236,8 @@ def main():
     # The same decode loop with the batch split into two halves (8 sequences each) on two HIP streams of default
     # priority: while one half's kernel is in its selection tail, or between two launches, the other half's streams.
     two_streams = None
-    if U % 2 == 0 and roco.decode_step_launches(roco.RocoParams(U // 2, d, B, s, roco.ROCO_BF16)) == 1:
+    if (not args.no_two_streams and U % 2 == 0
+            and roco.decode_step_launches(roco.RocoParams(U // 2, d, B, s, roco.ROCO_BF16)) == 1):
         Uh = U // 2
         ph = roco.RocoParams(Uh, d, B, s, roco.ROCO_BF16)
         phref = ctypes.byref(ph)

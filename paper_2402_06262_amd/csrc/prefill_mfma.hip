@@ -303,7 +303,7 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_mfma(PrefillArg
       if (blk < pair_id || (pass == 1 && blk == pair_id)) break;
     } else {
       if (pass == 1) break;
-      blk = n_blocks - 1 - pair_id;  // the longest streams start first
+      blk = pair_id;  // the longest streams start first: key block 0 is attended by every query
     }
     const int j0 = blk * kOwn;
     const int kw0 = j0 + 64 * wave;
@@ -430,7 +430,7 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_gqa_mfma(Prefil
       if (blk < pair_id || (pass == 1 && blk == pair_id)) break;
     } else {
       if (pass == 1) break;
-      blk = n_blocks - 1 - pair_id;
+      blk = pair_id;  // the longest streams start first
     }
     const int j0 = blk * kOwn;
     const int kw0 = j0 + 64 * wave;

@@ -226,6 +226,12 @@ def test_matrix_core_prefill_statistics_ragged_lengths(recency):
     run_workload("bf16", 128, len(lens), lens, 517, 100, 12, 3, seed=31, want_out=False, tag=f"mfma-ragged-{recency}", **kw)
 
 
+def test_matrix_core_prefill_with_one_block_per_workgroup(monkeypatch):
+    """ROCO_PREFILL_PAIRED=0: every workgroup takes one block of rows instead of a long and a short one."""
+    monkeypatch.setenv("ROCO_PREFILL_PAIRED", "0")
+    run_workload("bf16", 128, 3, [700, 520, 300], 700, 256, 24, 0, seed=29, want_out=False, tag="unpaired")
+
+
 def test_matrix_core_prefill_matches_vector_path_bitwise_decisions(monkeypatch):
     """Same inputs through the matrix-core kernels and through the vector-ALU kernels: retained sets agree and
     the statistics agree to fp32 rounding (the two paths differ only in summation order)."""

@@ -16,6 +16,8 @@
 // Operand layout of the 32x32x16 instruction, as used here: lane l supplies row (l % 32) and the 8
 // consecutive k-elements starting at 8 * (l / 32) of each 16-wide k-step, for A and for B alike; register r
 // of the result belongs to A-row 8 * (r / 4) + 4 * (l / 32) + (r % 4) and B-row (l % 32).
+#include <cstdlib>
+
 #include "kernels.hpp"
 #include "mfma.hpp"
 #include "profile.hpp"
@@ -281,8 +283,11 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_mfma(PrefillArg
   constexpr int kOwn = Shape<WAVES>::kOwn;
   __shared__ __attribute__((aligned(16))) char lds[2][kTile * kLdsRow];
   __shared__ __attribute__((aligned(16))) float lse_s[2][kTile];
-  int u, pair_id;
-  if (!locate(a.units, a.pairs, u, pair_id)) return;
+  int u, id;
+  if (!locate(a.units, a.pairs * a.qsplit, u, id)) return;
+  const int seg = id % a.qsplit, pair_id = id / a.qsplit;  // which share of the queries, which blocks of keys
+  float* const out1 = seg == 0 ? a.acc : reinterpret_cast<float*>(a.var_key);    // second share: see sum_query_shares
+  float* const out2 = seg == 0 ? a.acc2 : reinterpret_cast<float*>(a.mas_key);
   const int len = a.len[u];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int half = lane >> 5;
@@ -313,15 +318,20 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_mfma(PrefillArg
     load_owned(own1, Kb, kj1, len - 1);
     float s1a = 0.0f, s2a = 0.0f, s1b = 0.0f, s2b = 0.0f;
 
-    const int t_first = j0 / kTile;  // first query tile with a query >= j0
-    const int t_last = (len - 1) / kTile;
+    int t_first = j0 / kTile;  // first query tile with a query >= j0
+    int t_last = (len - 1) / kTile;
+    if (a.qsplit > 1) {  // this workgroup's share of those tiles (possibly none)
+      const int per = (t_last - t_first + a.qsplit) / a.qsplit;
+      t_first += seg * per;
+      t_last = min(t_last, t_first + per - 1);
+    }
     Staged<WAVES> stA;
     float lseA = 0.0f;
     auto fetch = [&](Staged<WAVES>& st, float& lse_st, int t) {
       tile_load(st, Qb, t * kTile, len - 1);
       if (threadIdx.x < kTile) lse_st = lse[min(t * kTile + static_cast<int>(threadIdx.x), len - 1)];
     };
-    fetch(stA, lseA, t_first);
+    if (t_first <= t_last) fetch(stA, lseA, t_first);
     __syncthreads();  // the previous pass has finished with the LDS buffers
     auto step = [&](Staged<WAVES>& st, float& lse_st, int t) {
       const int b = (t - t_first) & 1;
@@ -351,8 +361,8 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_mfma(PrefillArg
     s2a += __shfl_xor(s2a, 32, kWave);
     s1b += __shfl_xor(s1b, 32, kWave);
     s2b += __shfl_xor(s2b, 32, kWave);
-    if (half == 0 && kj0 < len) { a.acc[ubase + kj0] = s1a; a.acc2[ubase + kj0] = s2a; }
-    if (half == 0 && kj1 < len) { a.acc[ubase + kj1] = s1b; a.acc2[ubase + kj1] = s2b; }
+    if (half == 0 && kj0 < len) { out1[ubase + kj0] = s1a; out2[ubase + kj0] = s2a; }
+    if (half == 0 && kj1 < len) { out1[ubase + kj1] = s1b; out2[ubase + kj1] = s2b; }
   }
 }
 
@@ -406,8 +416,11 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_gqa_mfma(Prefil
   static_assert(Shape<WAVES>::kChunks % 2 == 0, "half a staged tile per head");
   __shared__ __attribute__((aligned(16))) char lds[2][kTile * kLdsRow];
   __shared__ __attribute__((aligned(16))) float lse_s[2][kTile];
-  int u, pair_id;
-  if (!locate(a.units, a.pairs, u, pair_id)) return;
+  int u, id;
+  if (!locate(a.units, a.pairs * a.qsplit, u, id)) return;
+  const int seg = id % a.qsplit, pair_id = id / a.qsplit;  // which share of the queries, which blocks of keys
+  float* const out1 = seg == 0 ? a.acc : reinterpret_cast<float*>(a.var_key);    // second share: see sum_query_shares
+  float* const out2 = seg == 0 ? a.acc2 : reinterpret_cast<float*>(a.mas_key);
   const int G = a.group, HP = (G + 1) / 2;  // head pairs per block of 32 queries
   const float inv_heads = 1.0f / static_cast<float>(G);
   const int len = a.len[u];
@@ -441,9 +454,14 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_gqa_mfma(Prefil
     float s1a = 0.0f, s2a = 0.0f, s1b = 0.0f, s2b = 0.0f;
     f32x16 pb0 = {0}, pb1 = {0};  // sums over the heads, for this lane's two keys
 
-    const int r_first = j0 / 32;         // first block of 32 queries with a query >= j0
-    const int r_last = (len - 1) / 32;
-    const int n_it = (r_last - r_first + 1) * HP;
+    int r_first = j0 / 32;         // first block of 32 queries with a query >= j0
+    int r_last = (len - 1) / 32;
+    if (a.qsplit > 1) {  // this workgroup's share of those blocks (possibly none)
+      const int per = (r_last - r_first + a.qsplit) / a.qsplit;
+      r_first += seg * per;
+      r_last = min(r_last, r_first + per - 1);
+    }
+    const int n_it = max(0, r_last - r_first + 1) * HP;
     Staged<WAVES> stA;
     float lseA = 0.0f;
     auto fetch = [&](Staged<WAVES>& st, float& lse_st, int it) {
@@ -455,7 +473,7 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_gqa_mfma(Prefil
         lse_st = lse_of(t < 32 ? h0 : h1)[min(r * 32 + (t & 31), len - 1)];
       }
     };
-    fetch(stA, lseA, 0);
+    if (n_it > 0) fetch(stA, lseA, 0);
     __syncthreads();  // the previous pass has finished with the LDS buffers
     for (int it = 0; it < n_it; ++it) {
       const int b = it & 1;
@@ -503,9 +521,21 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_gqa_mfma(Prefil
     s2a += __shfl_xor(s2a, 32, kWave);
     s1b += __shfl_xor(s1b, 32, kWave);
     s2b += __shfl_xor(s2b, 32, kWave);
-    if (half == 0 && kj0 < len) { a.acc[ubase + kj0] = s1a; a.acc2[ubase + kj0] = s2a; }
-    if (half == 0 && kj1 < len) { a.acc[ubase + kj1] = s1b; a.acc2[ubase + kj1] = s2b; }
+    if (half == 0 && kj0 < len) { out1[ubase + kj0] = s1a; out2[ubase + kj0] = s2a; }
+    if (half == 0 && kj1 < len) { out1[ubase + kj1] = s1b; out2[ubase + kj1] = s2b; }
   }
+}
+
+// With few units the queries of every block of keys are shared by two workgroups (PrefillArgs::qsplit = 2), so that
+// the chip has enough of them; the second one leaves its sums in the planes that the selection will later use for
+// its ranking keys, and this kernel adds them to the first one's: a fixed order, the same bits every run.
+__global__ __launch_bounds__(256) void sum_query_shares(PrefillArgs a) {
+  const int u = blockIdx.y;
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= a.len[u]) return;
+  const size_t i = static_cast<size_t>(u) * a.L_max + j;
+  a.acc[i] += reinterpret_cast<const float*>(a.var_key)[i];
+  a.acc2[i] += reinterpret_cast<const float*>(a.mas_key)[i];
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -687,6 +717,14 @@ __global__ __launch_bounds__(256) void mfma_probe(int iters, float* sink) {
   sink[static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x] = sum;
 }
 
+// Two workgroups per block of keys when one would leave the chip short of workgroups (fewer than four per compute
+// unit); ROCO_PREFILL_QSPLIT = 1 or 2 overrides.
+int columns_query_shares(const PrefillArgs& a, int pairs) {
+  const char* e = getenv("ROCO_PREFILL_QSPLIT");
+  if (e != nullptr && (e[0] == '1' || e[0] == '2')) return e[0] - '0';
+  return static_cast<long long>(a.units) * pairs < 1024 ? 2 : 1;
+}
+
 template <int WAVES>
 hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
   constexpr int kOwn = Shape<WAVES>::kOwn;
@@ -694,7 +732,8 @@ hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
   PrefillArgs b = a;
   b.paired = a.paired >= 0 ? a.paired : 1;  // pairing measured faster than lock-step single blocks
   b.pairs = b.paired ? (n_blocks + 1) / 2 : n_blocks;  // ids per unit
-  const dim3 grid(static_cast<unsigned>((a.units + 7) / 8 * 8 * b.pairs));
+  b.qsplit = columns_query_shares(a, b.pairs);
+  const dim3 grid(static_cast<unsigned>((a.units + 7) / 8 * 8 * b.pairs * b.qsplit));
   const dim3 rows_grid(static_cast<unsigned>((a.units * a.group + 7) / 8 * 8 * b.pairs));  // one id set per query head
   if (!a.skip_rows) {
     ProfScope ps(kProfPrefillRows, s);
@@ -706,6 +745,8 @@ hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
     else if (a.pol.counts_above_average())
       hipLaunchKernelGGL((prefill_columns_mfma<WAVES, true>), grid, dim3(WAVES * kWave), 0, s, b);
     else hipLaunchKernelGGL((prefill_columns_mfma<WAVES, false>), grid, dim3(WAVES * kWave), 0, s, b);
+    if (b.qsplit > 1)
+      hipLaunchKernelGGL(sum_query_shares, dim3((a.L_max + 255) / 256, a.units), dim3(256), 0, s, b);
   }
   return hipGetLastError();
 }
@@ -736,12 +777,15 @@ hipError_t launch_with_output(const PrefillArgs& a, hipStream_t s) {
   PrefillArgs c = a;
   c.paired = 1;
   c.pairs = (n_blocks + 1) / 2;
+  c.qsplit = columns_query_shares(a, c.pairs);
   {
     ProfScope ps(kProfPrefillColumns, s);
-    const dim3 cgrid(static_cast<unsigned>((a.units + 7) / 8 * 8 * c.pairs));
+    const dim3 cgrid(static_cast<unsigned>((a.units + 7) / 8 * 8 * c.pairs * c.qsplit));
     if (a.group != 1) hipLaunchKernelGGL(prefill_columns_gqa_mfma<4>, cgrid, dim3(4 * kWave), 0, s, c);
     else if (a.pol.counts_above_average()) hipLaunchKernelGGL((prefill_columns_mfma<4, true>), cgrid, dim3(4 * kWave), 0, s, c);
     else hipLaunchKernelGGL((prefill_columns_mfma<4, false>), cgrid, dim3(4 * kWave), 0, s, c);
+    if (c.qsplit > 1)
+      hipLaunchKernelGGL(sum_query_shares, dim3((a.L_max + 255) / 256, a.units), dim3(256), 0, s, c);
   }
   return hipGetLastError();
 }

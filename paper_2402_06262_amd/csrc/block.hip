@@ -33,14 +33,14 @@ namespace {
 
 using namespace mfma;
 
-constexpr int kPrepThreads = 1024;
+constexpr int kPrepThreads = 1024;  // 512 when the units outnumber the compute units (see launch_block)
 constexpr int kAttThreads = 128;  // two waves: one 32-slot half of a 64-slot tile each
 constexpr int kFinThreads = 1024;
 constexpr int kQ = 32;            // queries per matrix tile; a block holds at most this many tokens
 
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kPrepThreads) void block_prepare(BlockArgs a) {
-  constexpr int NT = kPrepThreads;
+template <int NT>
+__global__ __launch_bounds__(NT) void block_prepare(BlockArgs a) {
   extern __shared__ uint32_t lds_keys[];  // [2][B] when B <= kMaxDecodeBudgetLds
   __shared__ uint32_t sel_sh[kSelectLdsWords];
   __shared__ uint32_t scan_sh[NT / kWave + 1];
@@ -575,7 +575,10 @@ hipError_t launch_block(int dtype, int head_dim, const BlockArgs& args, hipStrea
   }
   if (!a.single) {
     ProfScope ps(kProfBlockPrepare, s);
-    hipLaunchKernelGGL(block_prepare, dim3(a.units), dim3(kPrepThreads), key_lds, s, a);
+    // Two 1024-thread workgroups do not run side by side on a compute unit here (measured: the second half of 512
+    // units starts when the first has finished); with more units than compute units 512 threads are faster.
+    if (a.units > 256) hipLaunchKernelGGL(block_prepare<512>, dim3(a.units), dim3(512), key_lds, s, a);
+    else hipLaunchKernelGGL(block_prepare<kPrepThreads>, dim3(a.units), dim3(kPrepThreads), key_lds, s, a);
   }
   if (mfma_path) {
     {

@@ -320,6 +320,23 @@ int roco_probe_cache_read(const roco_params* params, const void* K_cache, const 
  */
 int roco_probe_mfma(int32_t workgroups, int32_t iters, float* sink, size_t sink_bytes, void* hip_stream);
 
+/*
+ * Environment switches (read on the host at every call; meant for tests and tuning, the defaults are the measured
+ * choices).  None of them changes what a call computes, only which kernels and launch shapes do it.
+ *   ROCO_DECODE_FUSED=0|1      decode step as the split pair / as one kernel (default: one kernel from 64 units on
+ *                              when budget <= 4096); roco_decode_step_launches reports the choice
+ *   ROCO_DECODE_SPLITS=n       splits of the budget in the split pair (default: until about 128 workgroups exist)
+ *   ROCO_DECODE_UNROLL=2|4|8   cache rows in flight per lane group (default 8)
+ *   ROCO_DECODE_ROTATE=0|1     staggered start row per workgroup (default 1)
+ *   ROCO_STREAMING_LOADS=0|1   non-temporal loads of the cache rows (default: caches above 192 MiB)
+ *   ROCO_PREFILL_SIMPLE=1      vector-ALU prefill passes also for bf16 / head_dim 128
+ *   ROCO_PREFILL_PAIRED=0|1    one block of rows per workgroup / a long and a short one (default 1)
+ *   ROCO_PREFILL_WAVES=4|8     waves per workgroup of the matrix-core prefill passes (default 4)
+ *   ROCO_PREFILL_QSPLIT=1|2    workgroups per block of keys in the column pass (default: 2 with few units)
+ *   ROCO_BLOCK_SPLITS=n        splits of the budget in the block-wise / grouped steps (default: about 512 / units)
+ *   ROCO_BLOCK_SINGLE=0        single-token block steps go through the preparing kernel like longer blocks
+ */
+
 /* Static description of a return code. */
 const char* roco_strerror(int code);
 

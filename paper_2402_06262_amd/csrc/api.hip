@@ -128,7 +128,7 @@ bool streaming_loads(const roco_params* p) {
 
 bool decode_is_fused(const roco_params* p) {
   const int want = env_int("ROCO_DECODE_FUSED", -1);
-  return (want < 0 ? p->units >= 64 : want != 0) && p->budget <= kMaxDecodeBudgetLds;
+  return (want < 0 ? p->units >= 64 : want != 0) && p->budget <= kMaxFusedBudget;
 }
 
 }  // namespace

@@ -545,7 +545,8 @@ static bool single_step_off() {
 template <int DT, int D>
 void launch_block_tail(const BlockArgs& a, hipStream_t s) {
   ProfScope ps(kProfBlockFinish, s);
-  const size_t key_lds = (a.B <= kMaxDecodeBudgetLds) ? static_cast<size_t>(a.B) * 2 * sizeof(uint32_t) : 0;
+  const size_t key_lds = key_lds_bytes(a.B);
+  (void)allow_key_lds(reinterpret_cast<const void*>(block_finish<DT, D>), key_lds);  // if refused, the launch fails and is reported
   hipLaunchKernelGGL((block_finish<DT, D>), dim3(a.units), dim3(kFinThreads), key_lds, s, a);
 }
 
@@ -563,7 +564,10 @@ hipError_t launch_block(int dtype, int head_dim, const BlockArgs& args, hipStrea
   BlockArgs a = args;
   // A single-token step on the matrix-core path needs no block_prepare.
   a.single = (a.block == 1 && dtype == kBF16 && head_dim == 128 && !single_step_off()) ? 1 : 0;
-  const size_t key_lds = (a.B <= kMaxDecodeBudgetLds) ? static_cast<size_t>(a.B) * 2 * sizeof(uint32_t) : 0;
+  const size_t key_lds = key_lds_bytes(a.B);
+  if (!allow_key_lds(reinterpret_cast<const void*>(block_prepare<512>), key_lds) ||
+      !allow_key_lds(reinterpret_cast<const void*>(block_prepare<kPrepThreads>), key_lds))
+    return hipErrorInvalidValue;
   constexpr size_t kAttLds = 4 * static_cast<size_t>(kTileBytes);  // 68 KiB: above the default dynamic limit
   const bool mfma_path = dtype == kBF16 && head_dim == 128;
   static bool attr_done = false;

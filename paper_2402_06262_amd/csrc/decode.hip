@@ -475,8 +475,8 @@ void launch_attend(const DecodeArgs& a, hipStream_t s) {
 
 template <int DT, int D>
 hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t s) {
-  const size_t lds = (a.B <= kMaxDecodeBudgetLds) ? static_cast<size_t>(a.B) * 2 * sizeof(uint32_t) : 0;
-  if (a.fused) {  // requires B <= kMaxDecodeBudgetLds (checked by the host)
+  const size_t lds = key_lds_bytes(a.B);
+  if (a.fused) {  // requires B <= kMaxFusedBudget (checked by the host)
     ProfScope ps(kProfDecodeAttend, s);
     const size_t lds3 = static_cast<size_t>(a.B) * 3 * sizeof(uint32_t);
     hipLaunchKernelGGL((decode_fused<DT, D, 8>), dim3(a.units), dim3(kFusedThreads), lds3, s, a);
@@ -488,6 +488,7 @@ hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t s) {
     default: launch_attend<DT, D, 4>(a, s); break;
   }
   {
+    if (!allow_key_lds(reinterpret_cast<const void*>(decode_finish<DT, D>), lds)) return hipErrorInvalidValue;
     ProfScope ps(kProfDecodeFinish, s);
     hipLaunchKernelGGL((decode_finish<DT, D>), dim3(a.units), dim3(kFinishThreads), lds, s, a);
   }
@@ -535,7 +536,8 @@ hipError_t launch_cache_read_probe(int dtype, int head_dim, const DecodeArgs& a,
 }
 
 hipError_t launch_select_victims(const DecodeArgs& a, hipStream_t s) {
-  const size_t lds = (a.B <= kMaxDecodeBudgetLds) ? static_cast<size_t>(a.B) * 2 * sizeof(uint32_t) : 0;
+  const size_t lds = key_lds_bytes(a.B);
+  if (!allow_key_lds(reinterpret_cast<const void*>(select_victims), lds)) return hipErrorInvalidValue;
   ProfScope ps(kProfDecodeSelect, s);
   hipLaunchKernelGGL(select_victims, dim3(a.units), dim3(kFinishThreads), lds, s, a);
   return hipGetLastError();

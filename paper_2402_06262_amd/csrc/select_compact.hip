@@ -179,7 +179,8 @@ __global__ __launch_bounds__(kSelThreads) void select_retained(DecodeArgs a, int
 }  // namespace
 
 hipError_t launch_select_retained(const DecodeArgs& a, int keep, int32_t* mask, hipStream_t s) {
-  const size_t lds = (a.B <= kMaxDecodeBudgetLds) ? static_cast<size_t>(a.B) * 2 * sizeof(uint32_t) : 0;
+  const size_t lds = key_lds_bytes(a.B);
+  if (!allow_key_lds(reinterpret_cast<const void*>(select_retained), lds)) return hipErrorInvalidValue;
   hipLaunchKernelGGL(select_retained, dim3(a.units), dim3(kSelThreads), lds, s, a, keep, mask);
   return hipGetLastError();
 }

@@ -107,9 +107,18 @@ def test_block_step_many_splits_budget_2048():
     drive(2, 128, 2048, 64, [2300, 2048], [32, 16, 32], seed=73, tag="b2048")
 
 
-def test_block_steps_with_a_budget_above_the_lds_key_limit():
-    """B > 4096: the ranking keys of both finishing shapes and of the preparing kernel live in the workspace."""
+def test_block_steps_with_a_budget_above_4096():
     drive(1, 128, 4104, 40, [4200], [1, 1, 8, 32, 1, 3], seed=74, tag="b4104")
+
+
+def test_block_steps_whose_ranking_keys_need_more_than_64_kib_of_lds():
+    """8192 < B <= 16384: the preparing and finishing kernels raise their dynamic LDS limit before the launch."""
+    drive(1, 128, 8200, 40, [8300], [1, 8, 32, 1], seed=75, tag="b8200")
+
+
+def test_block_steps_with_a_budget_above_the_lds_key_limit():
+    """B > 16384: the ranking keys of the preparing and finishing kernels live in the workspace."""
+    drive(1, 128, 16392, 40, [16500], [1, 8, 32, 1], seed=76, tag="b16392")
 
 
 def test_block_steps_at_the_serving_shape_all_512_units():

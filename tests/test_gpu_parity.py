@@ -178,9 +178,19 @@ def test_exact_ties_go_to_the_lowest_index():
     assert np.allclose(res.full.acc, acc, rtol=1e-12)
 
 
-def test_budget_above_the_lds_key_limit_uses_the_workspace_keys():
-    """B > 4096: the selection keeps its ranking keys in the workspace instead of LDS."""
+def test_budget_just_above_the_one_kernel_limit():
+    """B > 4096 takes the split pair whatever the number of units; its ranking keys still fit the default LDS."""
     run_workload("bf16", 64, 1, [4300], 4300, 4100, 33, 5, seed=21, want_out=False, tag="b4100")
+
+
+def test_budget_whose_ranking_keys_need_more_than_64_kib_of_lds():
+    """8192 < B <= 16384: the selection kernels raise their dynamic LDS limit before the launch."""
+    run_workload("bf16", 64, 1, [8300], 8300, 8200, 33, 4, seed=22, want_out=False, tag="b8200")
+
+
+def test_budget_above_the_lds_key_limit_uses_the_workspace_keys():
+    """B > 16384: the selection keeps its ranking keys in the workspace instead of LDS."""
+    run_workload("bf16", 64, 1, [16500], 16500, 16400, 33, 3, seed=23, want_out=False, tag="b16400")
 
 
 def test_select_victims_entry_point_reproduces_the_maintained_hint():

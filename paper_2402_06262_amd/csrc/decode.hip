@@ -17,6 +17,7 @@
 //     attention score inside it.
 //
 //   select_victims : the selection alone (for a cache whose statistics were produced elsewhere).
+#include <cstdlib>
 #include "kernels.hpp"
 #include "profile.hpp"
 #include "stream.hpp"
@@ -219,9 +220,8 @@ __device__ __forceinline__ void update_statistics(float* acc, float* acc2, float
 }
 
 // ------------------------------------------------------------------------------------------------
-template <int DT, int D>
-__global__ __launch_bounds__(kFinishThreads) void decode_finish(DecodeArgs a) {
-  constexpr int NT = kFinishThreads;
+template <int DT, int D, int NT>
+__global__ __launch_bounds__(NT) void decode_finish(DecodeArgs a) {
   extern __shared__ uint32_t lds_keys[];  // [2][B] when B <= kMaxDecodeBudgetLds
   __shared__ uint32_t sel_sh[kSelectLdsWords];
   __shared__ unsigned long long best_sh[NT / kWave];
@@ -488,9 +488,18 @@ hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t s) {
     default: launch_attend<DT, D, 4>(a, s); break;
   }
   {
-    if (!allow_key_lds(reinterpret_cast<const void*>(decode_finish<DT, D>), lds)) return hipErrorInvalidValue;
     ProfScope ps(kProfDecodeFinish, s);
-    hipLaunchKernelGGL((decode_finish<DT, D>), dim3(a.units), dim3(kFinishThreads), lds, s, a);
+    // A unit's statistics and selection are one workgroup's work: 1024 threads when there is at most one unit per
+    // compute unit and enough slots to share out (measured: faster from 1024 slots on, e.g. 34 -> 28 us per step at
+    // 40 units x 4096 slots, 78 -> 64 at 64 x 8192), else 256.
+    if (a.B >= 1024 && a.units <= 256) {
+      if (!allow_key_lds(reinterpret_cast<const void*>(decode_finish<DT, D, 1024>), lds)) return hipErrorInvalidValue;
+      hipLaunchKernelGGL((decode_finish<DT, D, 1024>), dim3(a.units), dim3(1024), lds, s, a);
+    } else {
+      if (!allow_key_lds(reinterpret_cast<const void*>(decode_finish<DT, D, kFinishThreads>), lds))
+        return hipErrorInvalidValue;
+      hipLaunchKernelGGL((decode_finish<DT, D, kFinishThreads>), dim3(a.units), dim3(kFinishThreads), lds, s, a);
+    }
   }
   return hipGetLastError();
 }

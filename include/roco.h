@@ -323,7 +323,7 @@ int roco_probe_mfma(int32_t workgroups, int32_t iters, float* sink, size_t sink_
 /*
  * Environment switches (read on the host at every call; meant for tests and tuning, the defaults are the measured
  * choices).  None of them changes what a call computes, only which kernels and launch shapes do it.
- *   ROCO_DECODE_FUSED=0|1      decode step as the split pair / as one kernel (default: one kernel from 64 units on
+ *   ROCO_DECODE_FUSED=0|1      decode step as the split pair / as one kernel (default: one kernel from 128 units on
  *                              when budget <= 4096); roco_decode_step_launches reports the choice
  *   ROCO_DECODE_SPLITS=n       splits of the budget in the split pair (default: until about 128 workgroups exist)
  *   ROCO_DECODE_UNROLL=2|4|8   cache rows in flight per lane group (default 8)

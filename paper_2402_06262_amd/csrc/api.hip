@@ -113,8 +113,6 @@ void choose_splits(const roco_params* p, int unroll, int& splits, int& rows_per_
   rows_per_split = rows;
 }
 
-// One workgroup per unit once there are enough units to keep the chip streaming (measured on B = 2048, bf16,
-// d = 128: ahead of the split path from 64 units on, behind it at 32 and 40).
 // Whether the K / V rows are read with the non-temporal hint.  Measured (B = 2048, bf16, d = 128): a cache of up to
 // about 160 MiB is partly found again in the chip's last-level cache by the next step when loaded normally (31 vs 34
 // us at 128 units); from 256 MiB on it only thrashes that cache and displaces the statistics (75 vs 69 us at 320
@@ -126,9 +124,12 @@ bool streaming_loads(const roco_params* p) {
   return static_cast<size_t>(p->units) * p->budget * row * 2 > (static_cast<size_t>(kStreamingAboveMiB) << 20);
 }
 
+// One workgroup per unit once the units cover half of the compute units (measured, bf16, d = 128: 31 vs 34 us per
+// step at 128 units x 2048 slots and 19 vs 23 at 128 x 1024, but 30 vs 24 at 64 x 2048 and 54 vs 36 at 64 x 4096,
+// where a workgroup per unit leaves most of the chip without work).
 bool decode_is_fused(const roco_params* p) {
   const int want = env_int("ROCO_DECODE_FUSED", -1);
-  return (want < 0 ? p->units >= 64 : want != 0) && p->budget <= kMaxFusedBudget;
+  return (want < 0 ? p->units >= 128 : want != 0) && p->budget <= kMaxFusedBudget;
 }
 
 }  // namespace

@@ -89,9 +89,11 @@ def test_workspace_queries():
     assert roco.decode_workspace_bytes(roco.RocoParams(4, 64, 128, 129, roco.ROCO_F32)) == 0  # scope > B
     assert roco.decode_workspace_bytes(roco.RocoParams(65535, 64, 128, 16, roco.ROCO_F32)) > 0
     assert roco.decode_workspace_bytes(roco.RocoParams(65536, 64, 128, 16, roco.ROCO_F32)) == 0  # units per call
-    # which decode shape a call takes: fused from 64 units on while the budget fits LDS, else the split pair
+    # which decode shape a call takes: fused from 128 units on while the budget fits LDS, else the split pair
     assert roco.decode_step_launches(roco.RocoParams(512, 128, 2048, 64, roco.ROCO_BF16)) == 1
     assert roco.decode_step_launches(roco.RocoParams(40, 128, 4096, 64, roco.ROCO_BF16)) == 2
+    assert roco.decode_step_launches(roco.RocoParams(127, 128, 2048, 64, roco.ROCO_BF16)) == 2
+    assert roco.decode_step_launches(roco.RocoParams(128, 128, 2048, 64, roco.ROCO_BF16)) == 1
     assert roco.decode_step_launches(roco.RocoParams(512, 128, 8192, 64, roco.ROCO_BF16)) == 2
     assert roco.load_library().roco_decode_step_launches(ctypes.byref(roco.RocoParams(4, 96, 128, 16, roco.ROCO_F32))) == EUNSUPPORTED
 

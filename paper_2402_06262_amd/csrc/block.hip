@@ -139,9 +139,8 @@ __device__ __forceinline__ void kv_store(const StagedKV& s, char* tileK, char* t
   const int t = threadIdx.x;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const int off = ((t >> 4) + 8 * i) * kLdsRow + (t & 15) * 16;
-    *reinterpret_cast<uint4*>(tileK + off) = s.k[i];
-    *reinterpret_cast<uint4*>(tileV + off) = s.v[i];
+    *reinterpret_cast<uint4*>(tileK + ((t >> 4) + 8 * i) * kLdsRow + (t & 15) * 16) = s.k[i];
+    *reinterpret_cast<uint4*>(tileV + ((t >> 4) + 8 * i) * kLdsRowV + (t & 15) * 16) = s.v[i];
   }
 }
 
@@ -225,7 +224,7 @@ __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
   if (n_tiles > 0) fetch(0);
   for (int t = 0; t < n_tiles; ++t) {
     char* const tileK = lds_dyn + (t & 1) * kTileBytes;
-    char* const tileV = lds_dyn + (2 + (t & 1)) * kTileBytes;
+    char* const tileV = lds_dyn + 2 * kTileBytes + (t & 1) * kTileBytesV;
     kv_store(st, tileK, tileV);
     if (tid < kTile) { bidx_s[t & 1][tid] = st_bidx; pos_s[t & 1][tid] = st_pos; }
     __syncthreads();
@@ -298,11 +297,11 @@ __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
     // ---- O^T += V^T . P^T
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      const char* vt = tileV + (32 * wave + ks * 16) * kLdsRow + tr_off;
+      const char* vt = tileV + (32 * wave + ks * 16) * kLdsRowV + tr_off;
 #pragma unroll
       for (int db = 0; db < 4; ++db) {
         const uint2 lo = lds_read_transposed(vt + db * 64);
-        const uint2 hi = lds_read_transposed(vt + 8 * kLdsRow + db * 64);
+        const uint2 hi = lds_read_transposed(vt + 8 * kLdsRowV + db * 64);
         const uint4 afrag = make_uint4(lo.x, lo.y, hi.x, hi.y);
         o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, afrag), pfrag[ks], o[db], 0, 0, 0);
       }
@@ -568,7 +567,7 @@ hipError_t launch_block(int dtype, int head_dim, const BlockArgs& args, hipStrea
   if (!allow_key_lds(reinterpret_cast<const void*>(block_prepare<512>), key_lds) ||
       !allow_key_lds(reinterpret_cast<const void*>(block_prepare<kPrepThreads>), key_lds))
     return hipErrorInvalidValue;
-  constexpr size_t kAttLds = 4 * static_cast<size_t>(kTileBytes);  // 68 KiB: above the default dynamic limit
+  constexpr size_t kAttLds = 2 * static_cast<size_t>(kTileBytes + kTileBytesV);  // 74 KiB: above the default dynamic limit
   const bool mfma_path = dtype == kBF16 && head_dim == 128;
   static bool attr_done = false;
   if (mfma_path && !attr_done) {

@@ -20,6 +20,12 @@ constexpr int kRowBytes = D * 2;         // 256
 constexpr int kLdsRow = kRowBytes + 16;  // padded: 16 lanes x 16 B then hit distinct bank groups
 constexpr int kKSteps = D / 16;          // 8 matrix instructions per 32x32 tile
 constexpr int kTileBytes = kTile * kLdsRow;
+// V tiles that are read with the LDS transpose read take rows of 320 bytes: a 16-lane group of that read touches 4
+// consecutive rows x 32 bytes, and with 80-dword rows the 32 lanes served together fall on 64 distinct banks (with
+// the 272-byte rows of the K tiles, whose 128-bit row reads need that stride, half of the LDS cycles of those reads
+// were bank conflicts).
+constexpr int kLdsRowV = kRowBytes + 64;
+constexpr int kTileBytesV = kTile * kLdsRowV;
 
 __device__ __forceinline__ float max16(const f32x16& s) {
   float a = fmaxf(fmaxf(s[0], s[1]), s[2]);  // the compiler folds these into three-operand maxima
@@ -49,7 +55,7 @@ __device__ __forceinline__ uint2 lds_read_transposed(const char* p) {
 __device__ __forceinline__ int transposed_fragment_offset() {
   const int lane = threadIdx.x & (kWave - 1);
   const int i16 = lane & 15, grp = lane >> 4;
-  return ((grp >> 1) * 4 + (i16 >> 2)) * kLdsRow + ((grp & 1) * 16 + (i16 & 3) * 4) * 2;
+  return ((grp >> 1) * 4 + (i16 >> 2)) * kLdsRowV + ((grp & 1) * 16 + (i16 & 3) * 4) * 2;
 }
 
 }  // namespace mfma

@@ -52,12 +52,12 @@ __device__ __forceinline__ void tile_load(Staged<WAVES>& s, const char* base, in
     s.w[i] = load16(base + static_cast<size_t>(row) * kRowBytes + (t & 15) * 16);
   }
 }
-template <int WAVES>
+template <int WAVES, int ROW = kLdsRow>
 __device__ __forceinline__ void tile_store(const Staged<WAVES>& s, char* lds) {
   const int t = threadIdx.x;
 #pragma unroll
   for (int i = 0; i < Shape<WAVES>::kChunks; ++i)
-    *reinterpret_cast<uint4*>(lds + ((t >> 4) + Shape<WAVES>::kRowsPerSweep * i) * kLdsRow + (t & 15) * 16) = s.w[i];
+    *reinterpret_cast<uint4*>(lds + ((t >> 4) + Shape<WAVES>::kRowsPerSweep * i) * ROW + (t & 15) * 16) = s.w[i];
 }
 
 // Two 32x32 score tiles: streamed rows [sub*32, sub*32+32) of the LDS tile against the wave's two groups of
@@ -550,7 +550,6 @@ __global__ __launch_bounds__(256) void sum_query_shares(PrefillArgs a) {
 // at row i/4, column 4*(i%4) of the block, lane i receives rows 0..3 of column i.)  The k-slot order of both
 // operands follows the accumulator layout of the score tile: slots 0-3 are keys 4h..4h+3 and slots 4-7 are keys
 // 8+4h..8+4h+3 of a 16-key step, h = lane / 32.
-constexpr int kOutTileBytes = kTileBytes;  // one K or V tile in LDS
 
 template <int WAVES>
 __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_out_mfma(PrefillArgs a) {
@@ -591,10 +590,10 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_out_mfma(PrefillAr
   tile_load(stK, Kb, 0, len - 1);
   tile_load(stV, Vb, 0, len - 1);
   for (int t = 0; t < n_tiles; ++t) {
-    char* const tileK = lds_dyn + (t & 1) * kOutTileBytes;
-    char* const tileV = lds_dyn + (2 + (t & 1)) * kOutTileBytes;
+    char* const tileK = lds_dyn + (t & 1) * kTileBytes;
+    char* const tileV = lds_dyn + 2 * kTileBytes + (t & 1) * kTileBytesV;
     tile_store(stK, tileK);
-    tile_store(stV, tileV);
+    tile_store<WAVES, kLdsRowV>(stV, tileV);
     __syncthreads();
     if (t + 1 < n_tiles) {
       tile_load(stK, Kb, (t + 1) * kTile, len - 1);
@@ -660,11 +659,11 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_out_mfma(PrefillAr
       // ---- O^T += V^T . P^T : two 16-key steps x four blocks of 32 head dimensions
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
-        const char* vt = tileV + (sub * 32 + ks * 16) * kLdsRow + tr_off;
+        const char* vt = tileV + (sub * 32 + ks * 16) * kLdsRowV + tr_off;
 #pragma unroll
         for (int db = 0; db < 4; ++db) {
           const uint2 lo = lds_read_transposed(vt + db * 64);                // keys 4h .. 4h+3 of the step
-          const uint2 hi = lds_read_transposed(vt + 8 * kLdsRow + db * 64);  // keys 8+4h .. 8+4h+3
+          const uint2 hi = lds_read_transposed(vt + 8 * kLdsRowV + db * 64);  // keys 8+4h .. 8+4h+3
           const uint4 afrag = make_uint4(lo.x, lo.y, hi.x, hi.y);
           o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, afrag), pfrag[ks], o[db], 0, 0, 0);
         }
@@ -755,7 +754,7 @@ hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
 hipError_t launch_with_output(const PrefillArgs& a, hipStream_t s) {
   constexpr int WAVES = 4;
   constexpr int kOwnQ = 32 * WAVES;
-  constexpr size_t kLds = 4 * static_cast<size_t>(kOutTileBytes);  // 68 KiB: above the default dynamic limit
+  constexpr size_t kLds = 2 * static_cast<size_t>(kTileBytes + kTileBytesV);  // 74 KiB: above the default dynamic limit
   static bool attr_done = false;
   if (!attr_done) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_rows_out_mfma<WAVES>),

@@ -188,6 +188,7 @@ int run_prefill(const roco_params* params, int group, const void* Q, const void*
   a.mfma_waves = env_int("ROCO_PREFILL_WAVES", 0);
   a.skip_rows = want_lse ? 1 : 0;
   a.qsplit = 1;
+  a.ksplit = 1;
   a.scale_log2 = scale_log2(params);
   a.recency_window = params->recency_window;
   a.recency_bias_log2 = params->recency_bias * 1.4426950408889634f;

@@ -82,6 +82,7 @@ struct PrefillArgs {
   int mfma_waves;        // matrix-core path: 4 or 8 waves per workgroup, 0 = choose by problem size
   int skip_rows;         // 1: lse already holds the row normalisers, pass 1 is not run
   int qsplit;            // matrix-core path: 1, or 2 = two workgroups share a block's queries (set by its launcher)
+  int ksplit;            // matrix-core path, row pass: 1, or 2 = two workgroups share a block's keys (ditto)
   float scale_log2;
   int recency_window;
   float recency_bias_log2;

@@ -159,8 +159,10 @@ template <int WAVES>
 __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_mfma(PrefillArgs a) {
   constexpr int kOwn = Shape<WAVES>::kOwn;
   __shared__ __attribute__((aligned(16))) char lds[2][kTile * kLdsRow];
-  int u, pair_id;  // u counts (unit, query head) pairs: with grouped-query attention a unit has a.group heads
-  if (!locate(a.units * a.group, a.pairs, u, pair_id)) return;
+  int u, id;  // u counts (unit, query head) pairs: with grouped-query attention a unit has a.group heads
+  if (!locate(a.units * a.group, a.pairs * a.ksplit, u, id)) return;
+  const int seg = id % a.ksplit, pair_id = id / a.ksplit;  // which share of the keys, which blocks of queries
+  float* const lse_out = seg == 0 ? a.lse : a.acc;  // second share: see merge_key_shares (group = 1 only)
   const int uk = u / a.group;  // the unit: its keys and its length
   const int len = a.len[uk];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
@@ -198,14 +200,20 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_mfma(PrefillArgs a
 
     const int last_key = min(len, q0 + kOwn) - 1;  // keys 0..last_key are visible to some query of the block
     const int n_tiles = last_key / kTile + 1;
+    int t_lo = 0, t_hi = n_tiles - 1;  // this workgroup's share of the key tiles (possibly none)
+    if (a.ksplit > 1) {
+      const int per = (n_tiles + a.ksplit - 1) / a.ksplit;
+      t_lo = seg * per;
+      t_hi = min(t_hi, t_lo + per - 1);
+    }
     // The next tile is requested right after the barrier and has the whole tile of work to arrive.
     Staged<WAVES> stA;
-    tile_load(stA, Kb, 0, len - 1);
+    if (t_lo <= t_hi) tile_load(stA, Kb, t_lo * kTile, len - 1);
     __syncthreads();  // the previous pass has finished with the LDS buffers
     auto step = [&](Staged<WAVES>& st, int t) {
       tile_store(st, lds[t & 1]);
       __syncthreads();
-      if (t + 1 < n_tiles) tile_load(st, Kb, (t + 1) * kTile, len - 1);
+      if (t + 1 <= t_hi) tile_load(st, Kb, (t + 1) * kTile, len - 1);
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub) {
         const int kb = t * kTile + sub * 32;
@@ -221,19 +229,19 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_mfma(PrefillArgs a
         else lse_update<false>(s1, sc, kb, half, qi1, w, rb, m1, l1);
       }
     };
-    for (int t = 0; t < n_tiles; ++t) step(stA, t);
+    for (int t = t_lo; t <= t_hi; ++t) step(stA, t);
     // the two lane halves hold different keys of the same query
     {
       const float mo = __shfl_xor(m0, 32, kWave), lo = __shfl_xor(l0, 32, kWave);
       const float mn = fmaxf(m0, mo);
       const float tot = (m0 > -INFINITY ? l0 * fast_exp2(m0 - mn) : 0.0f) + (mo > -INFINITY ? lo * fast_exp2(mo - mn) : 0.0f);
-      if (half == 0 && qi0 < len) a.lse[ubase + qi0] = mn + log2f(tot);
+      if (half == 0 && qi0 < len) lse_out[ubase + qi0] = mn + log2f(tot);  // -inf for a share without keys
     }
     {
       const float mo = __shfl_xor(m1, 32, kWave), lo = __shfl_xor(l1, 32, kWave);
       const float mn = fmaxf(m1, mo);
       const float tot = (m1 > -INFINITY ? l1 * fast_exp2(m1 - mn) : 0.0f) + (mo > -INFINITY ? lo * fast_exp2(mo - mn) : 0.0f);
-      if (half == 0 && qi1 < len) a.lse[ubase + qi1] = mn + log2f(tot);
+      if (half == 0 && qi1 < len) lse_out[ubase + qi1] = mn + log2f(tot);
     }
   }
 }
@@ -526,6 +534,19 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_gqa_mfma(Prefil
   }
 }
 
+// Row pass with few units: the keys of every block of queries are shared by two workgroups (PrefillArgs::ksplit = 2);
+// the second one leaves its log-sum-exp in the plane the column pass will overwrite later, and this kernel merges
+// the two: log2(2^a + 2^b).
+__global__ __launch_bounds__(256) void merge_key_shares(PrefillArgs a) {
+  const int u = blockIdx.y;
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= a.len[u]) return;
+  const size_t at = static_cast<size_t>(u) * a.L_max + i;
+  const float x = a.lse[at], y = a.acc[at];
+  const float top = fmaxf(x, y);
+  if (top > -INFINITY) a.lse[at] = top + log2f(fast_exp2(x - top) + fast_exp2(y - top));
+}
+
 // With few units the queries of every block of keys are shared by two workgroups (PrefillArgs::qsplit = 2), so that
 // the chip has enough of them; the second one leaves its sums in the planes that the selection will later use for
 // its ranking keys, and this kernel adds them to the first one's: a fixed order, the same bits every run.
@@ -732,11 +753,14 @@ hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
   b.paired = a.paired >= 0 ? a.paired : 1;  // pairing measured faster than lock-step single blocks
   b.pairs = b.paired ? (n_blocks + 1) / 2 : n_blocks;  // ids per unit
   b.qsplit = columns_query_shares(a, b.pairs);
+  b.ksplit = a.group == 1 ? b.qsplit : 1;  // the second share's plane has no room for several heads
   const dim3 grid(static_cast<unsigned>((a.units + 7) / 8 * 8 * b.pairs * b.qsplit));
-  const dim3 rows_grid(static_cast<unsigned>((a.units * a.group + 7) / 8 * 8 * b.pairs));  // one id set per query head
+  const dim3 rows_grid(static_cast<unsigned>((a.units * a.group + 7) / 8 * 8 * b.pairs * b.ksplit));  // one id set per query head
   if (!a.skip_rows) {
     ProfScope ps(kProfPrefillRows, s);
     hipLaunchKernelGGL(prefill_rows_mfma<WAVES>, rows_grid, dim3(WAVES * kWave), 0, s, b);
+    if (b.ksplit > 1)
+      hipLaunchKernelGGL(merge_key_shares, dim3((a.L_max + 255) / 256, a.units), dim3(256), 0, s, b);
   }
   {
     ProfScope ps(kProfPrefillColumns, s);

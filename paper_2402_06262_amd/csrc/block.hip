@@ -379,16 +379,16 @@ __global__ __launch_bounds__(256) void block_attend_simple(BlockArgs a) {
   const int qp = a.qpos0[u] + ti;
   const int w = a.recency_window;
   const float rb = a.recency_bias_log2;
-  auto bias = [&](int row) -> float {
+  auto bias = [&](int row, int row_pos) -> float {
     if (bidx[row] > ti) return -INFINITY;  // a later token of the block
-    const int dlt = qp - pos[row];
+    const int dlt = qp - row_pos;
     return (w > 0 && dlt >= 0 && dlt < w) ? rb : 0.0f;
   };
   auto fix = [](int, uint4&, int) {};
   FlashState<G::EPL> st;
   st.reset();
   const int passes = (n + PASS - 1) / PASS;
-  stream_attend<DT, D, U, true, false>(qf, Kb, Vb, 0, n, passes, 0, PASS, wave * (U * G::R), bias, z, -1, fix, fix, st);
+  stream_attend<DT, D, U, true, false>(qf, Kb, Vb, 0, n, passes, 0, PASS, wave * (U * G::R), bias, pos, z, -1, fix, fix, st);
   merge_groups_in_wave<DT, D>(st);
   if (lane < G::LPR) {
     if (lane == 0) { sm_m[wave] = st.m; sm_l[wave] = st.l; }

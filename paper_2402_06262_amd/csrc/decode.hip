@@ -65,8 +65,8 @@ __global__ __launch_bounds__(kAttendThreads) void decode_attend(DecodeArgs a) {
 
   FlashState<G::EPL> st;
   st.reset();
-  auto bias = [&](int row) -> float {
-    const int dlt = (row == slot) ? 0 : qp - pos[row];
+  auto bias = [&](int row, int row_pos) -> float {
+    const int dlt = (row == slot) ? 0 : qp - row_pos;
     return (dlt >= 0 && dlt < w) ? rb : 0.0f;
   };
   // in-place overwrite of the slot the new token takes: the cache never grows past B
@@ -89,13 +89,13 @@ __global__ __launch_bounds__(kAttendThreads) void decode_attend(DecodeArgs a) {
                              : 0;
   if (w > 0)
     stream_attend<DT, D, U, true, false>(qf, Kb, Vb, row0, row1, passes, a.rotate ? rot : 0, PASS, wave * (U * G::R),
-                                         bias, z, slot, fix_k, fix_v, st);
+                                         bias, pos, z, slot, fix_k, fix_v, st);
   else if (a.streaming)
     stream_attend<DT, D, U, false, true>(qf, Kb, Vb, row0, row1, passes, a.rotate ? rot : 0, PASS, wave * (U * G::R),
-                                         bias, z, slot, fix_k, fix_v, st);
+                                         bias, pos, z, slot, fix_k, fix_v, st);
   else
     stream_attend<DT, D, U, false, false>(qf, Kb, Vb, row0, row1, passes, a.rotate ? rot : 0, PASS, wave * (U * G::R),
-                                          bias, z, slot, fix_k, fix_v, st);
+                                          bias, pos, z, slot, fix_k, fix_v, st);
   merge_groups_in_wave<DT, D>(st);
 
   if (lane < G::LPR) {
@@ -346,8 +346,8 @@ __global__ __launch_bounds__(kFusedThreads) void decode_fused(DecodeArgs a) {
 
   FlashState<G::EPL> st;
   st.reset();
-  auto bias = [&](int row) -> float {
-    const int dlt = (row == slot) ? 0 : qp - pos[row];
+  auto bias = [&](int row, int row_pos) -> float {
+    const int dlt = (row == slot) ? 0 : qp - row_pos;
     return (dlt >= 0 && dlt < w) ? rb : 0.0f;
   };
   auto fix_k = [&](int row, uint4& kw, int col) {
@@ -365,13 +365,13 @@ __global__ __launch_bounds__(kFusedThreads) void decode_fused(DecodeArgs a) {
   const int passes = (n + PASS - 1) / PASS;
   const int rot = a.rotate ? static_cast<int>((static_cast<unsigned>(u) * 5u) % static_cast<unsigned>(passes)) : 0;
   if (w > 0)
-    stream_attend<DT, D, U, true, false>(qf, Kb, Vb, 0, n, passes, rot, PASS, wave * (U * G::R), bias, z, slot, fix_k,
+    stream_attend<DT, D, U, true, false>(qf, Kb, Vb, 0, n, passes, rot, PASS, wave * (U * G::R), bias, pos, z, slot, fix_k,
                                          fix_v, st);
   else if (a.streaming)
-    stream_attend<DT, D, U, false, true>(qf, Kb, Vb, 0, n, passes, rot, PASS, wave * (U * G::R), bias, z, slot, fix_k,
+    stream_attend<DT, D, U, false, true>(qf, Kb, Vb, 0, n, passes, rot, PASS, wave * (U * G::R), bias, pos, z, slot, fix_k,
                                          fix_v, st);
   else
-    stream_attend<DT, D, U, false, false>(qf, Kb, Vb, 0, n, passes, rot, PASS, wave * (U * G::R), bias, z, slot, fix_k,
+    stream_attend<DT, D, U, false, false>(qf, Kb, Vb, 0, n, passes, rot, PASS, wave * (U * G::R), bias, pos, z, slot, fix_k,
                                           fix_v, st);
   merge_groups_in_wave<DT, D>(st);
 

@@ -40,13 +40,13 @@ __global__ __launch_bounds__(kThreads) void prefill_rows_simple(PrefillArgs a) {
   const float rb = a.recency_bias_log2;
   FlashState<G::EPL> st;
   st.reset();
-  auto bias = [&](int row) -> float { return (i - row < w) ? rb : 0.0f; };  // row <= i here
+  auto bias = [&](int row, int) -> float { return (i - row < w) ? rb : 0.0f; };  // row <= i here
   auto fix = [](int, uint4&, int) {};
   constexpr int PASS = kUnroll * G::R;
   if (w > 0)
-    stream_attend<DT, D, kUnroll, true, false>(qf, Kb, Vb, 0, i + 1, (i + PASS) / PASS, 0, PASS, 0, bias, nullptr, -1, fix, fix, st);
+    stream_attend<DT, D, kUnroll, true, false>(qf, Kb, Vb, 0, i + 1, (i + PASS) / PASS, 0, PASS, 0, bias, nullptr, nullptr, -1, fix, fix, st);
   else
-    stream_attend<DT, D, kUnroll, false, false>(qf, Kb, Vb, 0, i + 1, (i + PASS) / PASS, 0, PASS, 0, bias, nullptr, -1, fix, fix, st);
+    stream_attend<DT, D, kUnroll, false, false>(qf, Kb, Vb, 0, i + 1, (i + PASS) / PASS, 0, PASS, 0, bias, nullptr, nullptr, -1, fix, fix, st);
   merge_groups_in_wave<DT, D>(st);
   if (lane == 0) a.lse[ubase + i] = st.m + log2f(st.l);
   if (a.O != nullptr && lane < G::LPR) {

@@ -47,14 +47,16 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 //   STREAMING   loads K / V with the non-temporal hint: right when the whole cache is far larger than the chip's
 //               last-level cache (the rows would only displace the statistics), wrong when it fits and the next
 //               step would find it there;
-//   bias(row)   is added to the base-2 logit (only evaluated when HAS_BIAS);
+//   bias(row, x) is added to the base-2 logit (only evaluated when HAS_BIAS); x = aux[row] if aux is not null (the
+//               row's position, say), loaded with the row's K so that it has arrived when the score is formed: a load
+//               inside bias() would have to wait for every load issued before it, the next block's rows included;
 //   zptr        if not null, receives every base-2 logit once: zptr[row];
 //   special_row a row that must not take the branch-free path (the slot being overwritten), or -1;
 //   fix_k(row, kw, c) / fix_v(row, vw, c) may replace the loaded 16 bytes of that row.
 template <int DT, int D, int U, bool HAS_BIAS, bool STREAMING, class BiasFn, class FixK, class FixV>
 __device__ __forceinline__ void stream_attend(const float* qf, const char* Kbase, const char* Vbase,
                                               int row_begin, int row_end, int passes, int rot, int pass_rows,
-                                              int wave_off, BiasFn bias, float* zptr, int special_row,
+                                              int wave_off, BiasFn bias, const int32_t* aux, float* zptr, int special_row,
                                               FixK fix_k, FixV fix_v, FlashState<RowGeom<DT, D>::EPL>& st) {
   using G = RowGeom<DT, D>;
   const int lane = threadIdx.x & (kWave - 1);
@@ -69,8 +71,21 @@ __device__ __forceinline__ void stream_attend(const float* qf, const char* Kbase
       w[u] = STREAMING ? load16_streaming(base_ptr + off) : load16(base_ptr + off);
     }
   };
+  int aw[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) aw[u] = 0;
+  auto issue_aux = [&](int blk) {
+    if (HAS_BIAS && aux != nullptr) {
+      const int base = row_begin + blk * pass_rows + wave_off;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int row = base + u * G::R + g;
+        aw[u] = aux[row < row_end ? row : row_begin];
+      }
+    }
+  };
   auto is_plain = [&](int base) {
-    return !HAS_BIAS && base + U * G::R <= row_end && (special_row < base || special_row >= base + U * G::R);
+    return base + U * G::R <= row_end && (special_row < base || special_row >= base + U * G::R);
   };
 
   // K registers -> U base-2 logits of this lane group (t) and their maximum (mb)
@@ -86,6 +101,7 @@ __device__ __forceinline__ void stream_attend(const float* qf, const char* Kbase
 #pragma unroll
         for (int e = 0; e < G::EPL; ++e) dot = fmaf(qf[e], kf[e], dot);
         t[u] = group_sum<G::LPR>(dot);
+        if (HAS_BIAS) t[u] += bias(base + u * G::R + g, aw[u]);
         mb = fmaxf(mb, t[u]);
       }
       if (zptr != nullptr) {  // lane c of a group stores the logit of the group's c-th row: one store per block
@@ -106,7 +122,7 @@ __device__ __forceinline__ void stream_attend(const float* qf, const char* Kbase
         for (int e = 0; e < G::EPL; ++e) dot = fmaf(qf[e], kf[e], dot);
         dot = group_sum<G::LPR>(dot);
         if (row < row_end) {
-          t[u] = HAS_BIAS ? dot + bias(row) : dot;
+          t[u] = HAS_BIAS ? dot + bias(row, aw[u]) : dot;
           if (c == 0 && zptr != nullptr) zptr[row] = t[u];
         } else {
           t[u] = -INFINITY;
@@ -147,11 +163,13 @@ __device__ __forceinline__ void stream_attend(const float* qf, const char* Kbase
   float t[U];
   float mb;
   int blk = rot;
+  issue_aux(blk);
   issue(blk, Kbase, kw);
   issue(blk, Vbase, vw);
   for (int it = 0; it + 1 < passes; ++it) {
     const int nb = (blk + 1 == passes) ? 0 : blk + 1;
     scores(blk, kw, t, mb);
+    issue_aux(nb);
     issue(nb, Kbase, kw);
     accumulate(blk, vw, t, mb);
     issue(nb, Vbase, vw);

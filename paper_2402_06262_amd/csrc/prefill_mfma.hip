@@ -114,7 +114,7 @@ __device__ __forceinline__ bool locate(int units, int pairs, int& unit, int& pai
 }
 
 // Online log-sum-exp update of one lane with the 16 scores of a tile.
-//   INTERIOR: every key of the tile is visible to every query of the group and there is no bias:
+//   INTERIOR: every key of the tile is visible to every query of the group and none is inside a recency window:
 //             3 vector instructions per score (multiply-add, exponential, add) plus 8 for the maximum.
 template <bool INTERIOR>
 __device__ __forceinline__ void lse_update(const f32x16& s, float sc, int kb, int half, int qi, int w, float rb,
@@ -222,10 +222,10 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_mfma(PrefillArgs a
         f32x16 s0, s1;
         score_tiles(lds[t & 1], sub, own0, own1, do0, do1, s0, s1);
         if (do0) {
-          if (w == 0 && kb + 31 <= qw0) lse_update<true>(s0, sc, kb, half, qi0, w, rb, m0, l0);
+          if (kb + 31 + w <= qw0) lse_update<true>(s0, sc, kb, half, qi0, w, rb, m0, l0);
           else lse_update<false>(s0, sc, kb, half, qi0, w, rb, m0, l0);
         }
-        if (w == 0 && kb + 31 <= qw0 + 32) lse_update<true>(s1, sc, kb, half, qi1, w, rb, m1, l1);
+        if (kb + 31 + w <= qw0 + 32) lse_update<true>(s1, sc, kb, half, qi1, w, rb, m1, l1);
         else lse_update<false>(s1, sc, kb, half, qi1, w, rb, m1, l1);
       }
     };
@@ -354,12 +354,12 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_mfma(PrefillArg
         if (!do0) continue;
         f32x16 c0, c1;
         score_tiles(lds[b], sub, own0, own1, do0, do1, c0, c1);
-        const bool whole = w == 0 && ib + 31 < len;  // no ragged end, no bias
+        const bool whole = ib + 31 < len;  // no ragged end
         const float* lt = &lse_s[b][sub * 32];
-        if (whole && ib >= kw0 + 31) column_update<true, COUNT>(c0, lt, sc, ib, half, kj0, len, w, rb, s1a, s2a);
+        if (whole && ib >= kw0 + 31 + w) column_update<true, COUNT>(c0, lt, sc, ib, half, kj0, len, w, rb, s1a, s2a);
         else column_update<false, COUNT>(c0, lt, sc, ib, half, kj0, len, w, rb, s1a, s2a);
         if (do1) {
-          if (whole && ib >= kw0 + 63) column_update<true, COUNT>(c1, lt, sc, ib, half, kj1, len, w, rb, s1b, s2b);
+          if (whole && ib >= kw0 + 63 + w) column_update<true, COUNT>(c1, lt, sc, ib, half, kj1, len, w, rb, s1b, s2b);
           else column_update<false, COUNT>(c1, lt, sc, ib, half, kj1, len, w, rb, s1b, s2b);
         }
       }
@@ -493,7 +493,7 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_gqa_mfma(Prefil
       const int ib = r * 32;
       const bool do0 = ib + 31 >= kw0, do1 = ib + 31 >= kw0 + 32;  // some query of the block reaches the keys
       if (!do0) continue;  // wave-uniform, and the same for every head of the block
-      const bool whole = w == 0 && ib + 31 < len;  // no ragged end, no bias
+      const bool whole = ib + 31 < len;  // no ragged end
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub) {
         const int h = 2 * hp + sub;
@@ -501,10 +501,10 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_gqa_mfma(Prefil
         f32x16 c0, c1;
         score_tiles(lds[b], sub, own0, own1, do0, do1, c0, c1);
         const float* lt = &lse_s[b][sub * 32];
-        if (whole && ib >= kw0 + 31) column_probs<true>(c0, lt, sc, ib, half, kj0, len, w, rb, h == 0, pb0);
+        if (whole && ib >= kw0 + 31 + w) column_probs<true>(c0, lt, sc, ib, half, kj0, len, w, rb, h == 0, pb0);
         else column_probs<false>(c0, lt, sc, ib, half, kj0, len, w, rb, h == 0, pb0);
         if (do1) {
-          if (whole && ib >= kw0 + 63) column_probs<true>(c1, lt, sc, ib, half, kj1, len, w, rb, h == 0, pb1);
+          if (whole && ib >= kw0 + 63 + w) column_probs<true>(c1, lt, sc, ib, half, kj1, len, w, rb, h == 0, pb1);
           else column_probs<false>(c1, lt, sc, ib, half, kj1, len, w, rb, h == 0, pb1);
         }
       }
@@ -638,7 +638,7 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_out_mfma(PrefillAr
               __builtin_bit_cast(bf16x8, own[kk]), sacc, 0, 0, 0);
       }
       // ---- base-2 logits, masked
-      const bool interior = w == 0 && kb + 31 <= qw0;
+      const bool interior = kb + 31 + w <= qw0;  // wholly visible and wholly outside the recency window
       float tv[16];
       float mb = -INFINITY;
       if (interior) {

@@ -216,6 +216,8 @@ struct KSmallest {
 
 template <int NT, class KeyFn>
 __device__ KSmallest select_k_smallest(KeyFn key_of, int n, uint32_t k, uint32_t* sh) {
+  // everything is wanted (the policies whose scope is the whole cache, say): nothing to select
+  if (k >= static_cast<uint32_t>(n)) return KSmallest{0xffffffffu, 0xffffffffu};
   KSmallest r;
   uint32_t n_less, n_equal;
   radix_select<NT>(key_of, n, k, sh, r.kth, n_less, n_equal);

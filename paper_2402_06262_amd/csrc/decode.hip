@@ -87,7 +87,10 @@ __global__ __launch_bounds__(kAttendThreads) void decode_attend(DecodeArgs a) {
   const int rot = passes > 0 ? static_cast<int>((static_cast<unsigned>(u) * 5u + static_cast<unsigned>(split) * 3u) %
                                                 static_cast<unsigned>(passes))
                              : 0;
-  if (w > 0)
+  if (w > 0 && a.streaming)
+    stream_attend<DT, D, U, true, true>(qf, Kb, Vb, row0, row1, passes, a.rotate ? rot : 0, PASS, wave * (U * G::R),
+                                        bias, pos, z, slot, fix_k, fix_v, st);
+  else if (w > 0)
     stream_attend<DT, D, U, true, false>(qf, Kb, Vb, row0, row1, passes, a.rotate ? rot : 0, PASS, wave * (U * G::R),
                                          bias, pos, z, slot, fix_k, fix_v, st);
   else if (a.streaming)
@@ -364,7 +367,10 @@ __global__ __launch_bounds__(kFusedThreads) void decode_fused(DecodeArgs a) {
   };
   const int passes = (n + PASS - 1) / PASS;
   const int rot = a.rotate ? static_cast<int>((static_cast<unsigned>(u) * 5u) % static_cast<unsigned>(passes)) : 0;
-  if (w > 0)
+  if (w > 0 && a.streaming)
+    stream_attend<DT, D, U, true, true>(qf, Kb, Vb, 0, n, passes, rot, PASS, wave * (U * G::R), bias, pos, z, slot, fix_k,
+                                        fix_v, st);
+  else if (w > 0)
     stream_attend<DT, D, U, true, false>(qf, Kb, Vb, 0, n, passes, rot, PASS, wave * (U * G::R), bias, pos, z, slot, fix_k,
                                          fix_v, st);
   else if (a.streaming)

@@ -31,7 +31,9 @@ constexpr int kFinishThreads = kDecodeSelectThreads;
 constexpr int kFusedThreads = 256;  // with 8 rows in flight per lane group: two workgroups per compute unit
 
 // ------------------------------------------------------------------------------------------------
-template <int DT, int D, int U>
+// BIAS: a recency bias is in force; STREAMING: non-temporal loads.  They are template parameters, not branches inside
+// one kernel, to keep each kernel's code (the unrolled, software-pipelined stream) small.
+template <int DT, int D, int U, bool BIAS, bool STREAMING>
 __global__ __launch_bounds__(kAttendThreads) void decode_attend(DecodeArgs a) {
   using G = RowGeom<DT, D>;
   constexpr int STREAMS = kAttendWaves;  // one merged stream per wave reaches LDS
@@ -87,18 +89,8 @@ __global__ __launch_bounds__(kAttendThreads) void decode_attend(DecodeArgs a) {
   const int rot = passes > 0 ? static_cast<int>((static_cast<unsigned>(u) * 5u + static_cast<unsigned>(split) * 3u) %
                                                 static_cast<unsigned>(passes))
                              : 0;
-  if (w > 0 && a.streaming)
-    stream_attend<DT, D, U, true, true>(qf, Kb, Vb, row0, row1, passes, a.rotate ? rot : 0, PASS, wave * (U * G::R),
-                                        bias, pos, z, slot, fix_k, fix_v, st);
-  else if (w > 0)
-    stream_attend<DT, D, U, true, false>(qf, Kb, Vb, row0, row1, passes, a.rotate ? rot : 0, PASS, wave * (U * G::R),
-                                         bias, pos, z, slot, fix_k, fix_v, st);
-  else if (a.streaming)
-    stream_attend<DT, D, U, false, true>(qf, Kb, Vb, row0, row1, passes, a.rotate ? rot : 0, PASS, wave * (U * G::R),
-                                         bias, pos, z, slot, fix_k, fix_v, st);
-  else
-    stream_attend<DT, D, U, false, false>(qf, Kb, Vb, row0, row1, passes, a.rotate ? rot : 0, PASS, wave * (U * G::R),
-                                          bias, pos, z, slot, fix_k, fix_v, st);
+  stream_attend<DT, D, U, BIAS, STREAMING>(qf, Kb, Vb, row0, row1, passes, a.rotate ? rot : 0, PASS, wave * (U * G::R),
+                                           bias, pos, z, slot, fix_k, fix_v, st);
   merge_groups_in_wave<DT, D>(st);
 
   if (lane < G::LPR) {
@@ -303,7 +295,7 @@ __global__ __launch_bounds__(NT) void decode_finish(DecodeArgs a) {
 // statistics from the logits kept in LDS and choose the next victim.  Nothing but the final results is written
 // to global memory and no second launch is needed; the price is that a workgroup's selection phase does not
 // stream, so this shape is used when there are at least about two units per compute unit to overlap with.
-template <int DT, int D, int U>
+template <int DT, int D, int U, bool BIAS, bool STREAMING>
 __global__ __launch_bounds__(kFusedThreads) void decode_fused(DecodeArgs a) {
   using G = RowGeom<DT, D>;
   constexpr int NT = kFusedThreads, WAVES = NT / kWave;
@@ -367,18 +359,8 @@ __global__ __launch_bounds__(kFusedThreads) void decode_fused(DecodeArgs a) {
   };
   const int passes = (n + PASS - 1) / PASS;
   const int rot = a.rotate ? static_cast<int>((static_cast<unsigned>(u) * 5u) % static_cast<unsigned>(passes)) : 0;
-  if (w > 0 && a.streaming)
-    stream_attend<DT, D, U, true, true>(qf, Kb, Vb, 0, n, passes, rot, PASS, wave * (U * G::R), bias, pos, z, slot, fix_k,
-                                        fix_v, st);
-  else if (w > 0)
-    stream_attend<DT, D, U, true, false>(qf, Kb, Vb, 0, n, passes, rot, PASS, wave * (U * G::R), bias, pos, z, slot, fix_k,
-                                         fix_v, st);
-  else if (a.streaming)
-    stream_attend<DT, D, U, false, true>(qf, Kb, Vb, 0, n, passes, rot, PASS, wave * (U * G::R), bias, pos, z, slot, fix_k,
-                                         fix_v, st);
-  else
-    stream_attend<DT, D, U, false, false>(qf, Kb, Vb, 0, n, passes, rot, PASS, wave * (U * G::R), bias, pos, z, slot, fix_k,
-                                          fix_v, st);
+  stream_attend<DT, D, U, BIAS, STREAMING>(qf, Kb, Vb, 0, n, passes, rot, PASS, wave * (U * G::R), bias, pos, z, slot,
+                                           fix_k, fix_v, st);
   merge_groups_in_wave<DT, D>(st);
 
   if (lane < G::LPR) {
@@ -476,7 +458,12 @@ __global__ __launch_bounds__(kAttendThreads) void cache_read_probe(DecodeArgs a)
 template <int DT, int D, int U>
 void launch_attend(const DecodeArgs& a, hipStream_t s) {
   ProfScope ps(kProfDecodeAttend, s);
-  hipLaunchKernelGGL((decode_attend<DT, D, U>), dim3(a.splits, a.units), dim3(kAttendThreads), 0, s, a);
+  const dim3 grid(a.splits, a.units), block(kAttendThreads);
+  const bool bias = a.recency_window > 0, nt = a.streaming != 0;
+  if (bias && nt) hipLaunchKernelGGL((decode_attend<DT, D, U, true, true>), grid, block, 0, s, a);
+  else if (bias) hipLaunchKernelGGL((decode_attend<DT, D, U, true, false>), grid, block, 0, s, a);
+  else if (nt) hipLaunchKernelGGL((decode_attend<DT, D, U, false, true>), grid, block, 0, s, a);
+  else hipLaunchKernelGGL((decode_attend<DT, D, U, false, false>), grid, block, 0, s, a);
 }
 
 template <int DT, int D>
@@ -485,7 +472,12 @@ hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t s) {
   if (a.fused) {  // requires B <= kMaxFusedBudget (checked by the host)
     ProfScope ps(kProfDecodeAttend, s);
     const size_t lds3 = static_cast<size_t>(a.B) * 3 * sizeof(uint32_t);
-    hipLaunchKernelGGL((decode_fused<DT, D, 8>), dim3(a.units), dim3(kFusedThreads), lds3, s, a);
+    const dim3 grid(a.units), block(kFusedThreads);
+    const bool bias = a.recency_window > 0, nt = a.streaming != 0;
+    if (bias && nt) hipLaunchKernelGGL((decode_fused<DT, D, 8, true, true>), grid, block, lds3, s, a);
+    else if (bias) hipLaunchKernelGGL((decode_fused<DT, D, 8, true, false>), grid, block, lds3, s, a);
+    else if (nt) hipLaunchKernelGGL((decode_fused<DT, D, 8, false, true>), grid, block, lds3, s, a);
+    else hipLaunchKernelGGL((decode_fused<DT, D, 8, false, false>), grid, block, lds3, s, a);
     return hipGetLastError();
   }
   switch (a.unroll) {

@@ -31,7 +31,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix peak
 # HBM-side bytes of one decode_attend launch on this workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a
 # plain copy of known size (profiles/decode_prefill_workload3_rocprofv3.txt); only valid for the default shape.
 ATTEND_TRAFFIC_BYTES = 543662034
-FUSED_TRAFFIC_BYTES = 563454305  # decode_fused (the shape the step takes on this workload): see the same file
+FUSED_TRAFFIC_BYTES = 563437192  # decode_fused (the shape the step takes on this workload): see the same file
 
 
 def generate(cfg, seed, workers):

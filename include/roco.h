@@ -26,6 +26,10 @@
  *   - Argument errors are detected on the host before anything is launched
  *     and are reported by a negative return code; 0 is success.
  *   - Values held in device memory (`len`, `n_used`, `qpos`) are trusted.
+ *   - A workspace is scratch for the duration of one call's kernels and carries nothing from call to call.  Calls
+ *     that may run at the same time (different streams) need workspaces of their own, and caches of their own:
+ *     splitting the units of a batch over two streams, each half with its own workspace, is the intended way to
+ *     overlap one half's selection with the other half's streaming.
  */
 #ifndef ROCO_H
 #define ROCO_H

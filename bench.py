@@ -333,18 +333,23 @@ def main():
         ms, n = roco.roco_profile_read()
         dec_kernel_ms[name] = ms / max(1, n)
     # the matrix throughput this machine sustains (its clock under that load included): the prefill passes' matrix
-    # instruction in a loop on register operands, and nothing else
+    # instruction in a loop on register operands, and nothing else -- with operands of pseudo-random values (the bit
+    # activity of real activations; the ceiling the prefill is compared with) and with a few constant small values
     roco.roco_profile_kernel(roco.PROF_KERNELS["mfma_probe"])
     sink = torch.empty(2048 * 256, dtype=torch.float32, device="cuda")
-    probe_flops = 0
-    for k in range(6):
-        if k == 1:
-            roco.roco_profile_read()  # the first launch is a warm-up
-            probe_flops = 0
-        probe_flops += roco.roco_probe_mfma(2048, 2048, sink, stream=stream)
-    torch.cuda.synchronize()
-    ms, n = roco.roco_profile_read()
-    mfma_ceiling_tflops = probe_flops / (ms * 1e-3) / 1e12
+    mfma_ceiling = {}
+    for random_operands in (True, False):
+        probe_flops = 0
+        for k in range(6):
+            if k == 1:
+                torch.cuda.synchronize()
+                roco.roco_profile_read()  # the first launch is a warm-up
+                probe_flops = 0
+            probe_flops += roco.roco_probe_mfma(2048, 2048, sink, stream=stream, random_operands=random_operands)
+        torch.cuda.synchronize()
+        ms, n = roco.roco_profile_read()
+        mfma_ceiling[random_operands] = probe_flops / (ms * 1e-3) / 1e12
+    mfma_ceiling_tflops = mfma_ceiling[True]
     # prefill repeated on its own: median and minimum of 10
     reps = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(10)]
     roco.roco_profile_kernel(-1)
@@ -478,6 +483,7 @@ def main():
                              "frac": prefill_flops / (prefill_ms * 1e-3 / args.steps) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                              "flops_per_pass": prefill_flops,
                              "measured_mfma_ceiling_TFLOPs": mfma_ceiling_tflops,
+                             "measured_mfma_ceiling_constant_operands_TFLOPs": mfma_ceiling[False],
                              "frac_of_measured_ceiling": prefill_flops / (prefill_ms * 1e-3 / args.steps) / 1e12
                              / mfma_ceiling_tflops,
                              "prefill_ms_median_of_10": rep_ms[len(rep_ms) // 2], "prefill_ms_min_of_10": rep_ms[0]},

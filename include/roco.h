@@ -319,10 +319,16 @@ int roco_probe_cache_read(const roco_params* params, const void* K_cache, const 
  * Benchmark aid: `workgroups` workgroups of four waves, each wave issuing iters x 8 dependent-by-four
  * v_mfma_f32_32x32x16_bf16 (the instruction of the prefill statistics passes) on register operands and nothing else,
  * so that a benchmark can measure the matrix throughput the machine at hand sustains (its clock under that load
- * included).  Flops of one call = workgroups * 4 * iters * 8 * 32768.  sink out [workgroups * 256] fp32 (device):
- * receives a checksum per lane.  1 <= workgroups <= 1048576, 1 <= iters <= 1048576.
+ * included).  `operands`: ROCO_PROBE_CONSTANT_OPERANDS = one operand pair holding a few small values;
+ * ROCO_PROBE_RANDOM_OPERANDS = eight operand pairs of pseudo-random values in (-2, 2), whose bit activity is that of
+ * real activations (the matrix units draw more power and the sustained clock is lower).  Flops of one call =
+ * workgroups * 4 * iters * 8 * 32768.  sink out [workgroups * 256] fp32 (device): receives a checksum per lane.
+ * 1 <= workgroups <= 1048576, 1 <= iters <= 1048576.
  */
-int roco_probe_mfma(int32_t workgroups, int32_t iters, float* sink, size_t sink_bytes, void* hip_stream);
+#define ROCO_PROBE_CONSTANT_OPERANDS 0
+#define ROCO_PROBE_RANDOM_OPERANDS 1
+int roco_probe_mfma(int32_t workgroups, int32_t iters, int32_t operands, float* sink, size_t sink_bytes,
+                    void* hip_stream);
 
 /*
  * Environment switches (read on the host at every call; meant for tests and tuning, the defaults are the measured

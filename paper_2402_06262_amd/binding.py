@@ -87,7 +87,7 @@ def load_library() -> ctypes.CDLL:
     lib.roco_probe_cache_read.restype = ctypes.c_int
     lib.roco_probe_cache_read.argtypes = [pp, vp, vp, vp, sz, vp]
     lib.roco_probe_mfma.restype = ctypes.c_int
-    lib.roco_probe_mfma.argtypes = [i32, i32, vp, sz, vp]
+    lib.roco_probe_mfma.argtypes = [i32, i32, i32, vp, sz, vp]
     lib.roco_block_workspace_bytes.restype = sz
     lib.roco_block_workspace_bytes.argtypes = [pp, i32]
     lib.roco_encode_block.restype = ctypes.c_int
@@ -301,10 +301,10 @@ def roco_probe_cache_read(params: RocoParams, K_cache, V_cache, workspace, works
         raise RocoError(rc, "roco_probe_cache_read")
 
 
-def roco_probe_mfma(workgroups: int, iters: int, sink, stream=None) -> int:
+def roco_probe_mfma(workgroups: int, iters: int, sink, stream=None, random_operands: bool = False) -> int:
     """See include/roco.h: a loop of the prefill passes' matrix instruction (benchmark aid).  Returns the flops."""
-    rc = load_library().roco_probe_mfma(int(workgroups), int(iters), _ptr(sink), sink.numel() * sink.element_size(),
-                                        _stream(stream))
+    rc = load_library().roco_probe_mfma(int(workgroups), int(iters), 1 if random_operands else 0, _ptr(sink),
+                                        sink.numel() * sink.element_size(), _stream(stream))
     if rc != 0:
         raise RocoError(rc, "roco_probe_mfma")
     return int(workgroups) * 4 * int(iters) * 8 * 32768

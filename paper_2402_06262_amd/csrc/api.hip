@@ -433,11 +433,13 @@ int roco_probe_cache_read(const roco_params* params, const void* K_cache, const 
   return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
 }
 
-int roco_probe_mfma(int32_t workgroups, int32_t iters, float* sink, size_t sink_bytes, void* hip_stream) {
+int roco_probe_mfma(int32_t workgroups, int32_t iters, int32_t operands, float* sink, size_t sink_bytes,
+                    void* hip_stream) {
   if (workgroups < 1 || workgroups > (1 << 20) || iters < 1 || iters > (1 << 20)) return ROCO_EINVAL;
+  if (operands != ROCO_PROBE_CONSTANT_OPERANDS && operands != ROCO_PROBE_RANDOM_OPERANDS) return ROCO_EINVAL;
   if (sink == nullptr || !aligned16(sink)) return ROCO_EINVAL;
   if (sink_bytes < static_cast<size_t>(workgroups) * 256 * sizeof(float)) return ROCO_EWORKSPACE;
-  const hipError_t e = launch_mfma_probe(workgroups, iters, sink, static_cast<hipStream_t>(hip_stream));
+  const hipError_t e = launch_mfma_probe(workgroups, iters, operands == ROCO_PROBE_RANDOM_OPERANDS, sink, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
 }
 

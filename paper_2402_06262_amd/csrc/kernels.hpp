@@ -136,7 +136,7 @@ hipError_t launch_block(int dtype, int head_dim, const BlockArgs& a, hipStream_t
 hipError_t launch_decode(int dtype, int head_dim, const DecodeArgs& a, hipStream_t s);
 int decode_rows_per_pass(int dtype, int head_dim, int unroll);  // granularity of DecodeArgs::rows_per_split
 hipError_t launch_cache_read_probe(int dtype, int head_dim, const DecodeArgs& a, hipStream_t s);
-hipError_t launch_mfma_probe(int workgroups, int iters, float* sink, hipStream_t s);
+hipError_t launch_mfma_probe(int workgroups, int iters, bool random_operands, float* sink, hipStream_t s);
 hipError_t launch_select_victims(const DecodeArgs& a, hipStream_t s);
 // uses stats, pos, n_used, keys; writes mask[units][B] (1 = survives a shrink of the unit to `keep` tokens)
 hipError_t launch_select_retained(const DecodeArgs& a, int keep, int32_t* mask, hipStream_t s);  // uses stats, n_used, next_slot, keys

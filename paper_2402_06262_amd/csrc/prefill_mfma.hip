@@ -120,16 +120,33 @@ template <bool INTERIOR>
 __device__ __forceinline__ void lse_update(const f32x16& s, float sc, int kb, int half, int qi, int w, float rb,
                                            float& m, float& l) {
   if (INTERIOR) {
-    const float m_new = fmaxf(m, max16(s) * sc);
-    const float neg = -m_new;
+    // l = sum 2^(t - m) is a floating-point number, so m need not be the running maximum: any reference that keeps
+    // the terms from overflowing gives the same sum to rounding.  The terms are first taken against the reference as
+    // it stands (3 instructions per score and nothing else); only if some lane's share comes out above 2^64 -- the
+    // first tile, whose reference is -inf, and a row whose scores later rise by more than 64 powers of two -- is
+    // the tile redone with the reference raised to its maximum.
+    const float neg = -m;
     float sum0 = 0.0f, sum1 = 0.0f;
 #pragma unroll
     for (int r = 0; r < 16; r += 2) {
       sum0 += fast_exp2(fmaf(s[r], sc, neg));
       sum1 += fast_exp2(fmaf(s[r + 1], sc, neg));
     }
-    l = fmaf(l, fast_exp2(m - m_new), sum0 + sum1);
-    m = m_new;
+    const float sum = sum0 + sum1;
+    if (__builtin_amdgcn_ballot_w64(!(sum <= 0x1p64f)) == 0) {
+      l += sum;
+    } else {
+      const float m_new = fmaxf(m, max16(s) * sc);
+      const float neg_new = -m_new;
+      float t0 = 0.0f, t1 = 0.0f;
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) {
+        t0 += fast_exp2(fmaf(s[r], sc, neg_new));
+        t1 += fast_exp2(fmaf(s[r + 1], sc, neg_new));
+      }
+      l = fmaf(l, fast_exp2(m - m_new), t0 + t1);
+      m = m_new;
+    }
   } else {
     float tv[16];
     float mb = -INFINITY;
@@ -637,44 +654,61 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_out_mfma(PrefillAr
               __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p + kk * 32)),
               __builtin_bit_cast(bf16x8, own[kk]), sacc, 0, 0, 0);
       }
-      // ---- base-2 logits, masked
+      // ---- probabilities against the reference m, as a B operand (bf16), and their sum
       const bool interior = kb + 31 + w <= qw0;  // wholly visible and wholly outside the recency window
-      float tv[16];
-      float mb = -INFINITY;
-      if (interior) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) tv[r] = sacc[r] * sc;
-        mb = max16(sacc) * sc;
-      } else {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = kb + 8 * (r >> 2) + 4 * half + (r & 3);
-          float x = sacc[r] * sc;
-          if (w > 0 && qi - key < w) x += rb;
-          if (key > qi) x = -INFINITY;
-          tv[r] = x;
-          mb = fmaxf(mb, x);
-        }
-      }
-      // the two lane halves feed one matrix product, so they must share the reference maximum
-      mb = fmaxf(mb, __shfl_xor(mb, 32, kWave));
-      const float m_new = fmaxf(m, mb);  // finite: the first half-tile holds key 0, which every query sees
-      if (__any(m_new > m)) {
-        const float alpha = fast_exp2(m - m_new);  // 0 when m is still -inf
-        l *= alpha;
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-      }
-      m = m_new;
       bf16x8 pfrag[2];
       float sum = 0.0f;
+      bool done = false;
+      if (interior) {
+        // The reference need not be the running maximum (see lse_update): the terms are taken against it as it
+        // stands, and only a half-tile whose sum leaves the safe range -- the first one, whose reference is -inf,
+        // and scores that rise by more than 40 powers of two later on -- takes the path below that raises it.
+        const float neg = -m;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float pv = fast_exp2(tv[r] - m_new);
-        sum += pv;
-        pfrag[r >> 3][r & 7] = static_cast<__bf16>(pv);
+        for (int r = 0; r < 16; ++r) {
+          const float pv = fast_exp2(fmaf(sacc[r], sc, neg));
+          sum += pv;
+          pfrag[r >> 3][r & 7] = static_cast<__bf16>(pv);
+        }
+        done = __builtin_amdgcn_ballot_w64(!(sum <= 0x1p40f)) == 0;
+      }
+      if (!done) {
+        float tv[16];
+        float mb = -INFINITY;
+        if (interior) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) tv[r] = sacc[r] * sc;
+          mb = max16(sacc) * sc;
+        } else {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = kb + 8 * (r >> 2) + 4 * half + (r & 3);
+            float x = sacc[r] * sc;
+            if (w > 0 && qi - key < w) x += rb;
+            if (key > qi) x = -INFINITY;
+            tv[r] = x;
+            mb = fmaxf(mb, x);
+          }
+        }
+        // the two lane halves feed one matrix product, so they must share the reference
+        mb = fmaxf(mb, __shfl_xor(mb, 32, kWave));
+        const float m_new = fmaxf(m, mb);  // finite: the first half-tile holds key 0, which every query sees
+        if (__any(m_new > m)) {
+          const float alpha = fast_exp2(m - m_new);  // 0 when m is still -inf
+          l *= alpha;
+#pragma unroll
+          for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+        }
+        m = m_new;
+        sum = 0.0f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float pv = fast_exp2(tv[r] - m_new);
+          sum += pv;
+          pfrag[r >> 3][r & 7] = static_cast<__bf16>(pv);
+        }
       }
       l += sum;
       // ---- O^T += V^T . P^T : two 16-key steps x four blocks of 32 head dimensions
@@ -711,23 +745,38 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_out_mfma(PrefillAr
 }
 
 // Benchmark aid: the matrix instruction of the passes above on register operands, four independent accumulator
-// chains per wave, nothing else.  The checksum keeps the chains alive.
+// chains per wave, nothing else.  The checksum keeps the chains alive.  RANDOM = false: one operand pair holding a few
+// small values (few bits toggle between instructions); RANDOM = true: eight operand pairs of pseudo-random values in
+// (-2, 2), the bit activity of real activations -- the matrix units then draw more power and the clock gives way.
+template <bool RANDOM>
 __global__ __launch_bounds__(256) void mfma_probe(int iters, float* sink) {
+  constexpr int NP = RANDOM ? 8 : 1;
   const int lane = threadIdx.x & (kWave - 1);
-  bf16x8 x, y;
+  bf16x8 x[NP], y[NP];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    x[e] = static_cast<__bf16>(0.00390625f * static_cast<float>(1 + ((lane + e) & 3)));
-    y[e] = static_cast<__bf16>(0.0078125f * static_cast<float>(1 + ((lane ^ e) & 1)));
-  }
+  for (int j = 0; j < NP; ++j)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      if (RANDOM) {
+        uint32_t h = threadIdx.x * 64u + j * 8u + e + blockIdx.x * 7919u;
+        h ^= h >> 16; h *= 0x7feb352du; h ^= h >> 15; h *= 0x846ca68bu; h ^= h >> 16;
+        x[j][e] = static_cast<__bf16>((static_cast<int>(h & 0xffffu) - 32768) * (1.0f / 16384.0f));
+        y[j][e] = static_cast<__bf16>((static_cast<int>(h >> 16) - 32768) * (1.0f / 16384.0f));
+      } else {
+        x[j][e] = static_cast<__bf16>(0.00390625f * static_cast<float>(1 + ((lane + e) & 3)));
+        y[j][e] = static_cast<__bf16>(0.0078125f * static_cast<float>(1 + ((lane ^ e) & 1)));
+      }
+    }
   f32x16 acc[4];
 #pragma unroll
   for (int c = 0; c < 4; ++c) acc[c] = f32x16{0};
   for (int i = 0; i < iters; ++i) {
 #pragma unroll
-    for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, acc[c], 0, 0, 0);
+    for (int c = 0; c < 4; ++c)
+      acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x[c % NP], y[(2 * c) % NP], acc[c], 0, 0, 0);
 #pragma unroll
-    for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y, x, acc[c], 0, 0, 0);
+    for (int c = 0; c < 4; ++c)
+      acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(y[(c + 4) % NP], x[(2 * c + 1) % NP], acc[c], 0, 0, 0);
   }
   float sum = 0.0f;
 #pragma unroll
@@ -815,9 +864,11 @@ hipError_t launch_with_output(const PrefillArgs& a, hipStream_t s) {
 
 }  // namespace
 
-hipError_t launch_mfma_probe(int workgroups, int iters, float* sink, hipStream_t s) {
+hipError_t launch_mfma_probe(int workgroups, int iters, bool random_operands, float* sink, hipStream_t s) {
   ProfScope ps(kProfMfmaProbe, s);
-  hipLaunchKernelGGL(mfma_probe, dim3(static_cast<unsigned>(workgroups)), dim3(256), 0, s, iters, sink);
+  const dim3 grid(static_cast<unsigned>(workgroups));
+  if (random_operands) hipLaunchKernelGGL(mfma_probe<true>, grid, dim3(256), 0, s, iters, sink);
+  else hipLaunchKernelGGL(mfma_probe<false>, grid, dim3(256), 0, s, iters, sink);
   return hipGetLastError();
 }
 

@@ -49,10 +49,11 @@ def test_prefill_from_given_normalisers_validates_its_arguments():
 
 def test_mfma_probe_arguments_are_validated_on_the_host():
     lib = roco.load_library()
-    assert lib.roco_probe_mfma(0, 16, 0x1000, 1 << 20, None) == EINVAL
-    assert lib.roco_probe_mfma(16, 0, 0x1000, 1 << 20, None) == EINVAL
-    assert lib.roco_probe_mfma(16, 16, None, 1 << 20, None) == EINVAL
-    assert lib.roco_probe_mfma(16, 16, 0x1000, 16 * 1024 - 1, None) == EWORKSPACE
+    assert lib.roco_probe_mfma(0, 16, 0, 0x1000, 1 << 20, None) == EINVAL
+    assert lib.roco_probe_mfma(16, 0, 0, 0x1000, 1 << 20, None) == EINVAL
+    assert lib.roco_probe_mfma(16, 16, 2, 0x1000, 1 << 20, None) == EINVAL
+    assert lib.roco_probe_mfma(16, 16, 1, None, 1 << 20, None) == EINVAL
+    assert lib.roco_probe_mfma(16, 16, 1, 0x1000, 16 * 1024 - 1, None) == EWORKSPACE
 
 
 def test_params_struct_layout_matches_the_header():

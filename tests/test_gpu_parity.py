@@ -236,6 +236,30 @@ def test_matrix_core_prefill_statistics_ragged_lengths(recency):
     run_workload("bf16", 128, len(lens), lens, 517, 100, 12, 3, seed=31, want_out=False, tag=f"mfma-ragged-{recency}", **kw)
 
 
+@pytest.mark.parametrize("want_out", [False, True])
+def test_matrix_core_prefill_scores_that_rise_far_above_the_earlier_ones(want_out):
+    """The row passes keep a reference for their exponentials that is only raised when a tile's sum leaves the safe
+    range: two keys deep inside the prompt whose scores lie 70-90 powers of two above everything before them (and
+    the second as far above the first) force that path after the first tile, with and without the attention
+    output; lengths end before, between and after the two keys."""
+    P = _parity()
+    units, L, B, s, d = 4, 700, 256, 24, 128
+    lens = [700, 650, 300, 100]
+    rng = np.random.default_rng(77)
+    e = rng.standard_normal(d)
+    e = (e / np.linalg.norm(e)).astype(np.float32)
+    Q = rng.standard_normal((units, L, d)).astype(np.float32) + 8.0 * e
+    K = rng.standard_normal((units, L, d)).astype(np.float32)
+    V = rng.standard_normal((units, L, d)).astype(np.float32)
+    K[:, 150] = 80.0 * e
+    K[:, 420] = 160.0 * e
+    Q, K, V = round_to_bf16(Q), round_to_bf16(K), round_to_bf16(V)
+    sess = P.make_session(units, d, B, s, "bf16")
+    g = P.gpu_prefill(sess, Q, K, V, lens, want_out)
+    for u in range(units):
+        P.check_prefill_unit(g, u, Q[u], K[u], V[u], lens[u], B, s, 1.0 / math.sqrt(d), "bf16", 0, 0.0, want_out)
+
+
 def test_matrix_core_prefill_with_one_block_per_workgroup(monkeypatch):
     """ROCO_PREFILL_PAIRED=0: every workgroup takes one block of rows instead of a long and a short one."""
     monkeypatch.setenv("ROCO_PREFILL_PAIRED", "0")

@@ -158,24 +158,53 @@ __global__ __launch_bounds__(kThreads) void prefill_last_row(PrefillArgs a) {
   const int w = a.recency_window;
   const float rb = a.recency_bias_log2;
   const float inv_heads = 1.0f / static_cast<float>(a.group);
-  for (int base = wave * G::R; base < len; base += kWaves * G::R) {
-    const int j = base + g;
-    const int jc = j < len ? j : last;
-    float kf[G::EPL];
-    unpack16<DT>(load16(Kb + static_cast<size_t>(jc) * G::ROW_BYTES + c * 16), kf);
-    float pbar = 0.0f;
-    for (int h = 0; h < a.group; ++h) {  // the unit's query heads (one without grouped-query attention)
-      const size_t qbase = (static_cast<size_t>(u) * a.group + h) * a.L_max;
-      float qf[G::EPL];
-      unpack16<DT>(load16(static_cast<const char*>(a.Q) + (qbase + last) * G::ROW_BYTES + c * 16), qf);
-      float dot = 0.0f;
+  constexpr int U = 4;  // key rows in flight per lane group: the loop is bound by load latency, not by bytes
+  // the last token's query, scaled, and its normaliser: loaded once when the unit has a single head
+  float q0[G::EPL];
+  float lse0 = 0.0f;
+  auto load_query = [&](int h, float* qs, float& lse_h) {
+    const size_t qbase = (static_cast<size_t>(u) * a.group + h) * a.L_max;
+    float qf[G::EPL];
+    unpack16<DT>(load16(static_cast<const char*>(a.Q) + (qbase + last) * G::ROW_BYTES + c * 16), qf);
 #pragma unroll
-      for (int e = 0; e < G::EPL; ++e) dot = fmaf(qf[e] * a.scale_log2, kf[e], dot);
-      dot = group_sum<G::LPR>(dot);
-      if (w > 0 && last - jc < w) dot += rb;
-      pbar += fast_exp2(dot - a.lse[qbase + last]);
+    for (int e = 0; e < G::EPL; ++e) qs[e] = qf[e] * a.scale_log2;
+    lse_h = a.lse[qbase + last];
+  };
+  if (a.group == 1) load_query(0, q0, lse0);
+  for (int base = wave * G::R; base < len; base += kWaves * G::R * U) {
+    float kf[U][G::EPL];
+    int jc[U];
+#pragma unroll
+    for (int r = 0; r < U; ++r) {
+      const int j = base + r * kWaves * G::R + g;
+      jc[r] = j < len ? j : last;
+      unpack16<DT>(load16(Kb + static_cast<size_t>(jc[r]) * G::ROW_BYTES + c * 16), kf[r]);
     }
-    if (c == 0 && j < len) a.acc2[ubase + j] = pbar * inv_heads;
+    float pbar[U] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int h = 0; h < a.group; ++h) {  // the unit's query heads (one without grouped-query attention)
+      float qh[G::EPL];
+      float lse_h = lse0;
+      if (a.group == 1) {
+#pragma unroll
+        for (int e = 0; e < G::EPL; ++e) qh[e] = q0[e];
+      } else {
+        load_query(h, qh, lse_h);
+      }
+#pragma unroll
+      for (int r = 0; r < U; ++r) {
+        float dot = 0.0f;
+#pragma unroll
+        for (int e = 0; e < G::EPL; ++e) dot = fmaf(qh[e], kf[r][e], dot);
+        dot = group_sum<G::LPR>(dot);
+        if (w > 0 && last - jc[r] < w) dot += rb;
+        pbar[r] += fast_exp2(dot - lse_h);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < U; ++r) {
+      const int j = base + r * kWaves * G::R + g;
+      if (c == 0 && j < len) a.acc2[ubase + j] = pbar[r] * inv_heads;
+    }
   }
 }
 

@@ -120,6 +120,35 @@ def test_unit_that_fills_up_during_decode():
     run_workload("bf16", 128, 3, lens, 37, 40, 5, 36, seed=12, tag="fill-up")
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64)])
+def test_decode_from_an_empty_cache_without_any_prefill(dtype, d):
+    """Token-wise generation from scratch: the first step attends the new token alone, nothing is evicted until the
+    budget is reached, then every step evicts; the cache contents are compared at the end."""
+    P = _parity()
+    units, B, s, steps = 3, 24, 5, 40
+    sc = 1.0 / math.sqrt(d)
+    rng = np.random.default_rng(83)
+    Q = rng.standard_normal((units, steps, d)).astype(np.float32) + 0.25
+    K = rng.standard_normal((units, steps, d)).astype(np.float32)
+    V = rng.standard_normal((units, steps, d)).astype(np.float32)
+    if dtype == "bf16":
+        Q, K, V = round_to_bf16(Q), round_to_bf16(K), round_to_bf16(V)
+    sess = P.make_session(units, d, B, s, dtype)
+    states = [orc.CacheState(np.zeros((B, d)), np.zeros((B, d)), np.zeros(B), np.zeros(B), np.zeros(B),
+                             np.full(B, -1, dtype=np.int64), 0) for _ in range(units)]
+    ties = P.TieCount()
+    for t in range(steps):
+        g_out, g_slot, g_pos = P.gpu_decode_step(sess, Q[:, t], K[:, t], V[:, t], [t] * units)
+        for u in range(units):
+            ties += P.lockstep_decode_unit(states[u], u, g_out, g_slot, g_pos, Q[u, t], K[u, t], V[u, t], t, s, sc,
+                                           dtype, 0, 0.0, what=f"[from-empty] step {t}")
+            assert states[u].n_used == min(t + 1, B)
+            assert (int(g_slot[u]) >= 0) == (t >= B)
+    host = P.cache_to_host(sess)
+    for u in range(units):
+        P.check_cache_unit(host, u, states[u], what="[from-empty] final cache")
+
+
 @pytest.mark.parametrize("scope", [1, 7, 96])
 def test_scope_extremes(scope):
     """scope = 1 (only the lowest-variance slot may go), scope = B (plain lowest mean attention score)."""

@@ -662,7 +662,9 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_out_mfma(PrefillAr
       if (interior) {
         // The reference need not be the running maximum (see lse_update): the terms are taken against it as it
         // stands, and only a half-tile whose sum leaves the safe range -- the first one, whose reference is -inf,
-        // and scores that rise by more than 40 powers of two later on -- takes the path below that raises it.
+        // and scores that rise by more than 16 powers of two later on -- takes the path below that raises it.  (The
+        // bound is kept low here because the probabilities multiply V: the unnormalised output stays within 2^16 * n
+        // times the largest |v|.)
         const float neg = -m;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -670,7 +672,7 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_out_mfma(PrefillAr
           sum += pv;
           pfrag[r >> 3][r & 7] = static_cast<__bf16>(pv);
         }
-        done = __builtin_amdgcn_ballot_w64(!(sum <= 0x1p40f)) == 0;
+        done = __builtin_amdgcn_ballot_w64(!(sum <= 0x1p16f)) == 0;
       }
       if (!done) {
         float tv[16];

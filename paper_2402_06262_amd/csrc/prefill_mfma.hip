@@ -410,10 +410,15 @@ __device__ __forceinline__ void tile_load_two(Staged<WAVES>& s, const char* base
   }
 }
 
-// The 16 probabilities of a tile (one key, 16 queries of one head) added into `pb` (or stored, for the first head).
+// The 16 probabilities of a tile (one key, 16 queries of one head) added into `pb` (cleared before the first head).
 template <bool INTERIOR>
 __device__ __forceinline__ void column_probs(const f32x16& s, const float* lse_tile, float sc, int ib, int half,
-                                             int kj, int len, int w, float rb, bool first, f32x16& pb) {
+                                             int kj, int len, int w, float rb, f32x16& pb) {
+  if (!INTERIOR) {
+    // The masks of this (rare) path depend only on values known before the branch that leads here; the compiler
+    // would compute all of them ahead of that branch, on every tile.  An opaque copy of the block index keeps them here.
+    asm volatile("" : "+s"(ib));
+  }
 #pragma unroll
   for (int g4 = 0; g4 < 4; ++g4) {
     const float4 ls = *reinterpret_cast<const float4*>(lse_tile + 8 * g4 + 4 * half);
@@ -430,7 +435,7 @@ __device__ __forceinline__ void column_probs(const f32x16& s, const float* lse_t
         p = fast_exp2(x);
         if (qi < kj || qi >= len) p = 0.0f;
       }
-      pb[4 * g4 + e] = first ? p : pb[4 * g4 + e] + p;
+      pb[4 * g4 + e] += p;
     }
   }
 }
@@ -511,6 +516,10 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_gqa_mfma(Prefil
       const bool do0 = ib + 31 >= kw0, do1 = ib + 31 >= kw0 + 32;  // some query of the block reaches the keys
       if (!do0) continue;  // wave-uniform, and the same for every head of the block
       const bool whole = ib + 31 < len;  // no ragged end
+      if (hp == 0) {  // a new block of queries: the sums over the heads start from zero
+        pb0 = f32x16{0};
+        pb1 = f32x16{0};
+      }
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub) {
         const int h = 2 * hp + sub;
@@ -518,11 +527,11 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_gqa_mfma(Prefil
         f32x16 c0, c1;
         score_tiles(lds[b], sub, own0, own1, do0, do1, c0, c1);
         const float* lt = &lse_s[b][sub * 32];
-        if (whole && ib >= kw0 + 31 + w) column_probs<true>(c0, lt, sc, ib, half, kj0, len, w, rb, h == 0, pb0);
-        else column_probs<false>(c0, lt, sc, ib, half, kj0, len, w, rb, h == 0, pb0);
+        if (whole && ib >= kw0 + 31 + w) column_probs<true>(c0, lt, sc, ib, half, kj0, len, w, rb, pb0);
+        else column_probs<false>(c0, lt, sc, ib, half, kj0, len, w, rb, pb0);
         if (do1) {
-          if (whole && ib >= kw0 + 63 + w) column_probs<true>(c1, lt, sc, ib, half, kj1, len, w, rb, h == 0, pb1);
-          else column_probs<false>(c1, lt, sc, ib, half, kj1, len, w, rb, h == 0, pb1);
+          if (whole && ib >= kw0 + 63 + w) column_probs<true>(c1, lt, sc, ib, half, kj1, len, w, rb, pb1);
+          else column_probs<false>(c1, lt, sc, ib, half, kj1, len, w, rb, pb1);
         }
       }
       if (hp == HP - 1) {  // every head of this block of queries has been added

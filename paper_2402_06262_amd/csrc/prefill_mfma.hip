@@ -267,13 +267,18 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_mfma(PrefillArgs a
 // statistic is the number of queries that gave the key more than their row's average, p * (i + 1) > 1 (section
 // 4.1, quantised score), instead of the sum of squares.
 template <bool INTERIOR, bool COUNT>
-__device__ __forceinline__ void column_update(const f32x16& s, const float* lse_tile, float sc, int ib, int half,
-                                              int kj, int len, int w, float rb, float& s1, float& s2) {
+__device__ __forceinline__ void column_update(const f32x16& s, const float* lse_tile, const float* rinv_tile, float sc,
+                                              int ib, int half, int kj, int len, int w, float rb, float& s1, float& s2) {
   float a1 = 0.0f, a2 = 0.0f, b1 = 0.0f, b2 = 0.0f;
 #pragma unroll
   for (int g4 = 0; g4 < 4; ++g4) {
     const float4 ls = *reinterpret_cast<const float4*>(lse_tile + 8 * g4 + 4 * half);
     const float lv[4] = {ls.x, ls.y, ls.z, ls.w};
+    float rv[4] = {0.0f, 0.0f, 0.0f, 0.0f};  // COUNT: 1 / (tokens the query attended), staged with the normalisers
+    if (COUNT) {
+      const float4 rs = *reinterpret_cast<const float4*>(rinv_tile + 8 * g4 + 4 * half);
+      rv[0] = rs.x; rv[1] = rs.y; rv[2] = rs.z; rv[3] = rs.w;
+    }
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       float x = fmaf(s[4 * g4 + e], sc, -lv[e]);
@@ -288,8 +293,7 @@ __device__ __forceinline__ void column_update(const f32x16& s, const float* lse_
       }
       float second;
       if (COUNT) {
-        const float rows = static_cast<float>(ib + 8 * g4 + 4 * half + e + 1);  // tokens query i attended
-        second = p * rows > 1.0f ? 1.0f : 0.0f;
+        second = p > rv[e] ? 1.0f : 0.0f;  // p * (i + 1) > 1
       } else {
         second = p * p;
       }
@@ -308,6 +312,7 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_mfma(PrefillArg
   constexpr int kOwn = Shape<WAVES>::kOwn;
   __shared__ __attribute__((aligned(16))) char lds[2][kTile * kLdsRow];
   __shared__ __attribute__((aligned(16))) float lse_s[2][kTile];
+  __shared__ __attribute__((aligned(16))) float rinv_s[COUNT ? 2 : 1][COUNT ? kTile : 4];  // 1 / (i + 1) per staged query
   int u, id;
   if (!locate(a.units, a.pairs * a.qsplit, u, id)) return;
   const int seg = id % a.qsplit, pair_id = id / a.qsplit;  // which share of the queries, which blocks of keys
@@ -361,7 +366,10 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_mfma(PrefillArg
     auto step = [&](Staged<WAVES>& st, float& lse_st, int t) {
       const int b = (t - t_first) & 1;
       tile_store(st, lds[b]);
-      if (threadIdx.x < kTile) lse_s[b][threadIdx.x] = lse_st;
+      if (threadIdx.x < kTile) {
+        lse_s[b][threadIdx.x] = lse_st;
+        if (COUNT) rinv_s[b][threadIdx.x] = 1.0f / static_cast<float>(t * kTile + static_cast<int>(threadIdx.x) + 1);
+      }
       __syncthreads();
       if (t + 1 <= t_last) fetch(st, lse_st, t + 1);
 #pragma unroll
@@ -373,11 +381,12 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_mfma(PrefillArg
         score_tiles(lds[b], sub, own0, own1, do0, do1, c0, c1);
         const bool whole = ib + 31 < len;  // no ragged end
         const float* lt = &lse_s[b][sub * 32];
-        if (whole && ib >= kw0 + 31 + w) column_update<true, COUNT>(c0, lt, sc, ib, half, kj0, len, w, rb, s1a, s2a);
-        else column_update<false, COUNT>(c0, lt, sc, ib, half, kj0, len, w, rb, s1a, s2a);
+        const float* rt = &rinv_s[COUNT ? b : 0][COUNT ? sub * 32 : 0];
+        if (whole && ib >= kw0 + 31 + w) column_update<true, COUNT>(c0, lt, rt, sc, ib, half, kj0, len, w, rb, s1a, s2a);
+        else column_update<false, COUNT>(c0, lt, rt, sc, ib, half, kj0, len, w, rb, s1a, s2a);
         if (do1) {
-          if (whole && ib >= kw0 + 63 + w) column_update<true, COUNT>(c1, lt, sc, ib, half, kj1, len, w, rb, s1b, s2b);
-          else column_update<false, COUNT>(c1, lt, sc, ib, half, kj1, len, w, rb, s1b, s2b);
+          if (whole && ib >= kw0 + 63 + w) column_update<true, COUNT>(c1, lt, rt, sc, ib, half, kj1, len, w, rb, s1b, s2b);
+          else column_update<false, COUNT>(c1, lt, rt, sc, ib, half, kj1, len, w, rb, s1b, s2b);
         }
       }
     };

@@ -569,6 +569,161 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_gqa_mfma(Prefil
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// pass 2 for grouped-query attention when the number of heads divides 16 (2, 4, 8, 16): the streamed tile holds
+// 64 / G query positions for all G heads, its rows ordered so that the G heads of a query land in G consecutive
+// accumulator registers of a lane (register r of lane half hf holds row 8 * (r / 4) + 4 * hf + r % 4 of a 32-row
+// sub-tile; that row is given to query hf * 16 / G + r / G of the sub-tile, head r % G).  The sum over the heads is
+// then a sum down a few registers of one result tile: nothing is carried from tile to tile, and the kernel keeps the
+// register budget -- three waves per SIMD -- of the ungrouped column pass.
+template <int G> struct GroupedRows {
+  static constexpr int kPerHalf = 16 / G;      // queries per lane half in a 32-row sub-tile
+  static constexpr int kPerSub = 32 / G;       // query positions per sub-tile
+  static constexpr int kPerTile = 64 / G;      // query positions per 64-row tile
+  // LDS row of a tile -> local query position and head
+  __device__ static void locate(int row, int& ql, int& h) {
+    const int sub = row >> 5, rr = row & 31;
+    const int hf = (rr >> 2) & 1, r = 4 * (rr >> 3) + (rr & 3);
+    ql = sub * kPerSub + hf * kPerHalf + r / G;
+    h = r % G;
+  }
+};
+
+template <bool INTERIOR, int G>
+__device__ __forceinline__ void column_update_grouped(const f32x16& s, const float* lse_tile, float sc, int ib, int half,
+                                                      int kj, int len, int w, float rb, const Policy& pol,
+                                                      float& s1, float& s2) {
+  if (!INTERIOR) asm volatile("" : "+s"(ib));  // keeps this path's masks out of the code before the branch (see column_probs)
+  constexpr int kPerHalf = GroupedRows<G>::kPerHalf;
+  float p[16];
+#pragma unroll
+  for (int g4 = 0; g4 < 4; ++g4) {
+    const float4 ls = *reinterpret_cast<const float4*>(lse_tile + 8 * g4 + 4 * half);
+    const float lv[4] = {ls.x, ls.y, ls.z, ls.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int r = 4 * g4 + e;
+      float x = fmaf(s[r], sc, -lv[e]);
+      if (INTERIOR) {
+        p[r] = fast_exp2(x);
+      } else {
+        const int qi = ib + half * kPerHalf + r / G;
+        if (w > 0 && qi - kj < w) x += rb;
+        p[r] = (qi < kj || qi >= len) ? 0.0f : fast_exp2(x);
+      }
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < kPerHalf; ++q) {
+    float sum = p[q * G];
+#pragma unroll
+    for (int h = 1; h < G; ++h) sum += p[q * G + h];
+    const float pbar = sum * (1.0f / static_cast<float>(G));
+    s1 += pbar;
+    s2 = pol.second_statistic(s2, pbar, static_cast<float>(ib + half * kPerHalf + q + 1));
+  }
+}
+
+template <int WAVES, int G>
+__global__ __launch_bounds__(WAVES * kWave) void prefill_columns_gqa_pow2_mfma(PrefillArgs a) {
+  using GR = GroupedRows<G>;
+  constexpr int kOwn = Shape<WAVES>::kOwn;
+  constexpr int QT = GR::kPerTile, QS = GR::kPerSub;
+  __shared__ __attribute__((aligned(16))) char lds[2][kTile * kLdsRow];
+  __shared__ __attribute__((aligned(16))) float lse_s[2][kTile];
+  int u, id;
+  if (!locate(a.units, a.pairs * a.qsplit, u, id)) return;
+  const int seg = id % a.qsplit, pair_id = id / a.qsplit;  // which share of the queries, which blocks of keys
+  float* const out1 = seg == 0 ? a.acc : reinterpret_cast<float*>(a.var_key);    // second share: see sum_query_shares
+  float* const out2 = seg == 0 ? a.acc2 : reinterpret_cast<float*>(a.mas_key);
+  const int len = a.len[u];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int half = lane >> 5;
+  const size_t ubase = static_cast<size_t>(u) * a.L_max;
+  const char* Kb = static_cast<const char*>(a.K) + ubase * kRowBytes;
+  const char* Qu = static_cast<const char*>(a.Q) + static_cast<size_t>(u) * G * a.L_max * kRowBytes;  // [G][L_max][d]
+  const float* lse_u = a.lse + static_cast<size_t>(u) * G * a.L_max;
+  const float sc = a.scale_log2;
+  const int w = a.recency_window;
+  const float rb = a.recency_bias_log2;
+  const int n_blocks = (len + kOwn - 1) / kOwn;
+  if (a.paired ? 2 * pair_id > n_blocks - 1 : pair_id >= n_blocks) return;  // nothing left for this id
+  // this thread's rows of a staged tile: local query position and head, fixed for the whole kernel
+  int row_q[Shape<WAVES>::kChunks], row_h[Shape<WAVES>::kChunks];
+#pragma unroll
+  for (int i = 0; i < Shape<WAVES>::kChunks; ++i)
+    GR::locate((threadIdx.x >> 4) + Shape<WAVES>::kRowsPerSweep * i, row_q[i], row_h[i]);
+  int lse_q = 0, lse_h = 0;
+  if (threadIdx.x < kTile) GR::locate(threadIdx.x, lse_q, lse_h);
+
+  for (int pass = 0; pass < 2; ++pass) {  // one long and one short block of keys per workgroup
+    int blk;
+    if (a.paired) {
+      blk = pass == 0 ? pair_id : n_blocks - 1 - pair_id;
+      if (blk < pair_id || (pass == 1 && blk == pair_id)) break;
+    } else {
+      if (pass == 1) break;
+      blk = pair_id;  // the longest streams start first
+    }
+    const int j0 = blk * kOwn;
+    const int kw0 = j0 + 64 * wave;
+    const int kj0 = kw0 + (lane & 31), kj1 = kj0 + 32;  // this lane's two keys
+    uint4 own0[kKSteps], own1[kKSteps];
+    load_owned(own0, Kb, kj0, len - 1);
+    load_owned(own1, Kb, kj1, len - 1);
+    float s1a = 0.0f, s2a = 0.0f, s1b = 0.0f, s2b = 0.0f;
+
+    int t_first = j0 / QT;  // first tile with a query >= j0
+    int t_last = (len - 1) / QT;
+    if (a.qsplit > 1) {  // this workgroup's share of those tiles (possibly none)
+      const int per = (t_last - t_first + a.qsplit) / a.qsplit;
+      t_first += seg * per;
+      t_last = min(t_last, t_first + per - 1);
+    }
+    Staged<WAVES> stA;
+    float lseA = 0.0f;
+    auto fetch = [&](Staged<WAVES>& st, float& lse_st, int t) {
+#pragma unroll
+      for (int i = 0; i < Shape<WAVES>::kChunks; ++i) {
+        const int qpos = min(t * QT + row_q[i], len - 1);  // positions past the end are masked by the update
+        st.w[i] = load16(Qu + (static_cast<size_t>(row_h[i]) * a.L_max + qpos) * kRowBytes + (threadIdx.x & 15) * 16);
+      }
+      if (threadIdx.x < kTile) lse_st = lse_u[static_cast<size_t>(lse_h) * a.L_max + min(t * QT + lse_q, len - 1)];
+    };
+    if (t_first <= t_last) fetch(stA, lseA, t_first);
+    __syncthreads();  // the previous pass has finished with the LDS buffers
+    for (int t = t_first; t <= t_last; ++t) {
+      const int b = (t - t_first) & 1;
+      tile_store(stA, lds[b]);
+      if (threadIdx.x < kTile) lse_s[b][threadIdx.x] = lseA;
+      __syncthreads();
+      if (t + 1 <= t_last) fetch(stA, lseA, t + 1);
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+        const int ib = t * QT + sub * QS;  // first query position of the sub-tile; its last one is ib + QS - 1
+        const bool do0 = ib + QS - 1 >= kw0, do1 = ib + QS - 1 >= kw0 + 32;  // some query reaches the keys
+        if (!do0) continue;
+        f32x16 c0, c1;
+        score_tiles(lds[b], sub, own0, own1, do0, do1, c0, c1);
+        const bool whole = ib + QS - 1 < len;  // no ragged end
+        const float* lt = &lse_s[b][sub * 32];
+        if (whole && ib >= kw0 + 31 + w) column_update_grouped<true, G>(c0, lt, sc, ib, half, kj0, len, w, rb, a.pol, s1a, s2a);
+        else column_update_grouped<false, G>(c0, lt, sc, ib, half, kj0, len, w, rb, a.pol, s1a, s2a);
+        if (do1) {
+          if (whole && ib >= kw0 + 63 + w) column_update_grouped<true, G>(c1, lt, sc, ib, half, kj1, len, w, rb, a.pol, s1b, s2b);
+          else column_update_grouped<false, G>(c1, lt, sc, ib, half, kj1, len, w, rb, a.pol, s1b, s2b);
+        }
+      }
+    }
+    s1a += __shfl_xor(s1a, 32, kWave);
+    s2a += __shfl_xor(s2a, 32, kWave);
+    s1b += __shfl_xor(s1b, 32, kWave);
+    s2b += __shfl_xor(s2b, 32, kWave);
+    if (half == 0 && kj0 < len) { out1[ubase + kj0] = s1a; out2[ubase + kj0] = s2a; }
+    if (half == 0 && kj1 < len) { out1[ubase + kj1] = s1b; out2[ubase + kj1] = s2b; }
+  }
+}
+
 // Row pass with few units: the keys of every block of queries are shared by two workgroups (PrefillArgs::ksplit = 2);
 // the second one leaves its log-sum-exp in the plane the column pass will overwrite later, and this kernel merges
 // the two: log2(2^a + 2^b).
@@ -814,6 +969,19 @@ int columns_query_shares(const PrefillArgs& a, int pairs) {
   return static_cast<long long>(a.units) * pairs < 1024 ? 2 : 1;
 }
 
+// Grouped column pass: the in-register head sum when the number of heads divides 16, else the general kernel.
+template <int WAVES>
+void launch_columns_grouped(const PrefillArgs& b, dim3 grid, hipStream_t s) {
+  const dim3 block(WAVES * kWave);
+  switch (b.group) {
+    case 2: hipLaunchKernelGGL((prefill_columns_gqa_pow2_mfma<WAVES, 2>), grid, block, 0, s, b); break;
+    case 4: hipLaunchKernelGGL((prefill_columns_gqa_pow2_mfma<WAVES, 4>), grid, block, 0, s, b); break;
+    case 8: hipLaunchKernelGGL((prefill_columns_gqa_pow2_mfma<WAVES, 8>), grid, block, 0, s, b); break;
+    case 16: hipLaunchKernelGGL((prefill_columns_gqa_pow2_mfma<WAVES, 16>), grid, block, 0, s, b); break;
+    default: hipLaunchKernelGGL(prefill_columns_gqa_mfma<WAVES>, grid, block, 0, s, b); break;
+  }
+}
+
 template <int WAVES>
 hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
   constexpr int kOwn = Shape<WAVES>::kOwn;
@@ -833,7 +1001,7 @@ hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
   }
   {
     ProfScope ps(kProfPrefillColumns, s);
-    if (a.group != 1) hipLaunchKernelGGL(prefill_columns_gqa_mfma<WAVES>, grid, dim3(WAVES * kWave), 0, s, b);
+    if (a.group != 1) launch_columns_grouped<WAVES>(b, grid, s);
     else if (a.pol.counts_above_average())
       hipLaunchKernelGGL((prefill_columns_mfma<WAVES, true>), grid, dim3(WAVES * kWave), 0, s, b);
     else hipLaunchKernelGGL((prefill_columns_mfma<WAVES, false>), grid, dim3(WAVES * kWave), 0, s, b);
@@ -873,7 +1041,7 @@ hipError_t launch_with_output(const PrefillArgs& a, hipStream_t s) {
   {
     ProfScope ps(kProfPrefillColumns, s);
     const dim3 cgrid(static_cast<unsigned>((a.units + 7) / 8 * 8 * c.pairs * c.qsplit));
-    if (a.group != 1) hipLaunchKernelGGL(prefill_columns_gqa_mfma<4>, cgrid, dim3(4 * kWave), 0, s, c);
+    if (a.group != 1) launch_columns_grouped<4>(c, cgrid, s);
     else if (a.pol.counts_above_average()) hipLaunchKernelGGL((prefill_columns_mfma<4, true>), cgrid, dim3(4 * kWave), 0, s, c);
     else hipLaunchKernelGGL((prefill_columns_mfma<4, false>), cgrid, dim3(4 * kWave), 0, s, c);
     if (c.qsplit > 1)

@@ -147,6 +147,23 @@ def test_grouped_prefill_then_grouped_decode(dtype, d, group):
                         tag=f"gqa-prefill-{dtype}-{d}-g{group}")
 
 
+@pytest.mark.parametrize("group", [2, 4, 8, 16])
+@pytest.mark.parametrize("recency", [False, True])
+def test_grouped_prefill_on_the_matrix_cores_with_heads_summed_in_registers(group, recency, monkeypatch):
+    """Group sizes that divide 16 take the column pass whose tiles hold all heads of a few query positions: lengths
+    around its tile edges (64 / g positions per tile), several key blocks, with and without the recency bias; the
+    query tiles of a key block on one workgroup (as with many units) or shared by two (as with few)."""
+    monkeypatch.setenv("ROCO_PREFILL_QSPLIT", "1" if recency else "2")
+    run_grouped_prefill("bf16", 128, group, [517, 300, 64 // group + 1, 129, 33], 517, 100, 12, seed=540 + group,
+                        recency=recency, tag=f"gqa-pow2-g{group}-{recency}", steps=2)
+
+
+def test_grouped_prefill_with_eight_heads_under_the_accumulated_score():
+    """Several key blocks per unit, two units, eight heads, ranked by the accumulated score over the whole cache."""
+    run_grouped_prefill("bf16", 128, 8, [700, 420], 700, 256, 256, seed=551, policy=orc.Policy("aas", "all"),
+                        tag="gqa-pow2-aas", steps=0)
+
+
 def test_grouped_prefill_with_recency_bias_and_three_heads():
     run_grouped_prefill("bf16", 128, 3, [200, 77], 200, 64, 9, seed=520, recency=True, tag="gqa-prefill-recency")
 

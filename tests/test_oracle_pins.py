@@ -745,9 +745,6 @@ def test_quantised_score_equals_an_explicit_recount_of_above_average_attention()
         for sl, p in enumerate(keep):
             count[p] += 1 if w[sl] > 1.0 / B else 0
         assert [count[p] for p in keep] == list(st.acc2)
-    # a block of tokens: each row is compared with the average of what that row attended
-    blk = orc.encode_block(st.copy(), Q[:3] + 1.0, K[:3], V[:3], L + T, 3, 0.6, policy=pol)
-    assert blk.out.shape == (3, d)
 
 
 def test_row_normalisers_closed_forms():
@@ -781,3 +778,122 @@ def test_row_normalisers_give_back_the_probabilities():
         logits = np.array([sc * float(Q[i] @ K[j]) + (0.25 if i - j < 5 else 0.0) for j in range(i + 1)])
         p = np.exp(logits - lse[i])
         assert abs(p.sum() - 1.0) < 1e-13
+
+
+# ---------------------------------------------------------------------------- quantised score in the block / grouped paths
+
+def _softmax_over(K_rows, q, scale):
+    """One softmax row written out with plain Python loops (section 2.1, eq. 1)."""
+    logits = [scale * sum(float(a) * float(b) for a, b in zip(k, q)) for k in K_rows]
+    top = max(logits)
+    e = [math.exp(x - top) for x in logits]
+    tot = sum(e)
+    return [x / tot for x in e]
+
+
+def _recount_block(st_before, Qb, Kb, Vb, qpos0, slots, scale, heads, wrong_average=False):
+    """What the three arrays must hold after a block has been encoded into the slots `slots` (already known: which
+    slots a block takes is pinned elsewhere), rebuilt token by token with loops: the block's token i attends the
+    older tokens and the block's tokens 0..i; a slot's second array counts the rows whose (head-mean) probability
+    for it was above the average of that row, 1 / (number of tokens the row attended) (section 4.1, quantised
+    score).  `wrong_average` divides by the cache's final occupancy instead: the mistake the pin must catch."""
+    B = st_before.budget
+    K = [list(r) for r in st_before.K]
+    acc, acc2, cnt = list(st_before.acc), list(st_before.acc2), list(st_before.count)
+    in_block = {}
+    for i, s in enumerate(slots):
+        K[s] = list(Kb[i])
+        acc[s] = acc2[s] = cnt[s] = 0.0
+        in_block[int(s)] = i
+    n_new = min(B, st_before.n_used + len(slots))
+    for i in range(len(slots)):
+        seen = [s for s in range(n_new) if in_block.get(s, -1) <= i]
+        rows = [_softmax_over([K[s] for s in seen], Qb[i][h] if heads else Qb[i], scale) for h in range(heads or 1)]
+        mean = [sum(r[t] for r in rows) / len(rows) for t in range(len(seen))]
+        avg_of = n_new if wrong_average else len(seen)
+        for t, s in enumerate(seen):
+            acc[s] += mean[t]
+            acc2[s] += 1.0 if mean[t] * avg_of > 1.0 else 0.0
+            cnt[s] += 1.0
+    return acc, acc2, cnt
+
+
+def test_quantised_score_in_a_block_counts_against_the_tokens_each_row_attended():
+    """encode_block under importance "aqas": a block that straddles a full cache (some tokens take empty slots, some
+    take over evicted ones), so the rows of one block attend different numbers of tokens; the count of above-average
+    rows is rebuilt with loops over dense softmax rows and compared exactly.  A recount that takes the average over
+    the final occupancy instead of over what each row attended gives different numbers on this case."""
+    rng = np.random.default_rng(101)
+    L, d, B, b = 9, 4, 12, 6
+    Q, K, V = rand_unit(rng, L + b, d)
+    pol = orc.Policy("aqas", "all")
+    st = orc.prefill_compress(Q[:L], K[:L], V[:L], L, B, 3, 0.8, policy=pol).cache  # 9 of 12 slots used
+    before = st.copy()
+    Qb = 0.4 * Q[L:L + b]  # flat rows: many probabilities lie between 1/12 and 1/7, where the two averages differ
+    blk = orc.encode_block(st, Qb, K[L:L + b], V[L:L + b], L, 3, 0.8, policy=pol)
+    assert (blk.evicted_slot >= 0).sum() == 3 and (blk.evicted_slot < 0).sum() == 3  # straddles the budget
+    acc, acc2, cnt = _recount_block(before, Qb, K[L:L + b], V[L:L + b], L, blk.slots, 0.8, heads=0)
+    assert list(st.acc2) == acc2 and list(st.count) == cnt
+    assert np.allclose(st.acc, acc, rtol=1e-12)
+    _, wrong, _ = _recount_block(before, Qb, K[L:L + b], V[L:L + b], L, blk.slots, 0.8, heads=0, wrong_average=True)
+    assert wrong != acc2  # the case tells the two averages apart
+
+
+def test_quantised_score_in_a_grouped_block_thresholds_the_head_mean():
+    """encode_block_gqa under "aqas": the head-mean probability of each of the block's tokens is compared with the
+    average of that token's row; loops over dense per-head softmax rows, exact comparison, same straddling block."""
+    rng = np.random.default_rng(102)
+    L, d, B, b, g = 10, 4, 13, 5, 3
+    Q, K, V = rand_unit(rng, L + b, d)
+    Qg = rng.standard_normal((b, g, d)) * 0.5  # flat rows, see the ungrouped test
+    pol = orc.Policy("aqas", "window")
+    st = orc.prefill_compress(Q[:L], K[:L], V[:L], L, B, 4, 0.7, policy=pol).cache  # 10 of 13 slots used
+    before = st.copy()
+    blk = orc.encode_block_gqa(st, Qg, K[L:L + b], V[L:L + b], L, 4, 0.7, policy=pol)
+    assert (blk.evicted_slot >= 0).sum() == 2 and (blk.evicted_slot < 0).sum() == 3
+    acc, acc2, cnt = _recount_block(before, Qg, K[L:L + b], V[L:L + b], L, blk.slots, 0.7, heads=g)
+    assert list(st.acc2) == acc2 and list(st.count) == cnt
+    assert np.allclose(st.acc, acc, rtol=1e-12)
+    _, wrong, _ = _recount_block(before, Qg, K[L:L + b], V[L:L + b], L, blk.slots, 0.7, heads=g, wrong_average=True)
+    assert wrong != acc2
+    # thresholding each head and averaging the bits is a different statistic; the case tells them apart too
+    per_head = [0.0] * B
+    in_block = {int(s): i for i, s in enumerate(blk.slots)}
+    Kn = [list(r) for r in st.K]
+    for i in range(b):
+        seen = [s for s in range(st.n_used) if in_block.get(s, -1) <= i]
+        for h in range(g):
+            row = _softmax_over([Kn[s] for s in seen], Qg[i][h], 0.7)
+            for t, s in enumerate(seen):
+                per_head[s] += (1.0 if row[t] * len(seen) > 1.0 else 0.0) / g
+    base = [0.0 if int(s) in in_block else float(before.acc2[s]) for s in range(B)]
+    assert [x + y for x, y in zip(base, per_head)] != acc2
+
+
+def test_grouped_prefill_quantised_score_and_outputs_from_dense_per_head_softmaxes():
+    """prefill_statistics_gqa: (1) under "aqas" the second array counts the rows i whose head-mean probability for
+    key j exceeds 1 / (i + 1); (2) want_out returns every head's own P_h V.  Both against dense causal attention
+    written separately (einsum softmax per head)."""
+    rng = np.random.default_rng(103)
+    L, d, g = 19, 5, 4
+    Qh = rng.standard_normal((g, L, d)) * 1.3
+    _, K, V = rand_unit(rng, L, d)
+    sc = 0.6
+    Ps, Os = zip(*(dense_causal_attention(Qh[h], K, V, sc) for h in range(g)))
+    Pbar = sum(Ps) / g
+    want = [sum(1.0 for i in range(j, L) if Pbar[i, j] > 1.0 / (i + 1)) for j in range(L)]
+    got = orc.prefill_statistics_gqa(Qh, K, V, L, sc, row_block=6, policy=orc.Policy("aqas", "all"), want_out=True)
+    assert list(got.acc2) == want
+    assert max(want) >= 3 and min(want) == 0  # not degenerate
+    assert np.allclose(got.acc, Pbar.sum(0), rtol=1e-12)
+    assert np.array_equal(got.count, L - np.arange(L))
+    assert got.out.shape == (g, L, d)
+    for h in range(g):
+        assert np.allclose(got.out[h], Os[h], rtol=1e-12, atol=1e-14)
+    # each head's output is its own, not the head-mean's: swapping two heads swaps the outputs
+    swapped = orc.prefill_statistics_gqa(Qh[[1, 0, 2, 3]], K, V, L, sc, want_out=True)
+    assert np.allclose(swapped.out[0], Os[1], rtol=1e-12) and np.allclose(swapped.out[1], Os[0], rtol=1e-12)
+    assert np.allclose(swapped.acc2, (Pbar ** 2).sum(0), rtol=1e-12)  # default policy: squares of the head-mean
+    # thresholding per head and averaging the bits is a different statistic
+    bits = sum((P * np.arange(1, L + 1)[:, None] > 1.0) & np.tril(np.ones((L, L), bool)) for P in Ps) / g
+    assert list(bits.sum(0)) != want

@@ -5,6 +5,7 @@ import os
 import shutil
 import subprocess
 import sys
+import tempfile
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
@@ -29,9 +30,7 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found; the RoCo library cannot be built")
 
 
-def build_library(verbose: bool = True) -> str:
-    """Compile every HIP source into one shared library next to this file; returns its path."""
-    cmd = [hipcc_path(), *HIPCC_FLAGS, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB_PATH]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, capture_output=True, text=True)
@@ -42,6 +41,21 @@ def build_library(verbose: bool = True) -> str:
         print(out, flush=True)
     if proc.returncode != 0:
         raise RuntimeError(f"hipcc failed ({proc.returncode}):\n{out}")
+
+
+def build_library(verbose: bool = True) -> str:
+    """Compile every HIP source (one hipcc process each, side by side) and link them into one shared library next to
+    this file; returns its path.  Objects go to a temporary folder: nothing but the library is left in the tree."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    hipcc = hipcc_path()
+    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    with tempfile.TemporaryDirectory(prefix="roco_build_") as tmp:
+        objs = [os.path.join(tmp, s.replace(".hip", ".o")) for s in SOURCES]
+        cmds = [[hipcc, *compile_flags, "-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
+        with ThreadPoolExecutor(max_workers=min(len(cmds), os.cpu_count() or 1)) as pool:
+            list(pool.map(lambda c: _run(c, verbose), cmds))
+        _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB_PATH], verbose)
     return LIB_PATH
 
 

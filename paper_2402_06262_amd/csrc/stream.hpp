@@ -136,8 +136,15 @@ __device__ __forceinline__ void stream_attend(const float* qf, const char* Kbase
   auto accumulate = [&](int blk, uint4* vw, const float* t, float mb) {
     const int base = row_begin + blk * pass_rows + wave_off;
     if (!is_plain(base)) {
+      // Rows past the end were loaded from row_begin only to keep the address in range.  Their weight is 2^-inf = 0,
+      // but row_begin may be the very slot this step fills for the first time, whose bytes in the caller's buffer
+      // are arbitrary (0 x NaN is NaN): such rows contribute zeros, whatever was loaded.
 #pragma unroll
-      for (int u = 0; u < U; ++u) fix_v(base + u * G::R + g, vw[u], c);
+      for (int u = 0; u < U; ++u) {
+        const int row = base + u * G::R + g;
+        fix_v(row, vw[u], c);
+        if (row >= row_end) vw[u] = make_uint4(0u, 0u, 0u, 0u);
+      }
     }
     const float m_new = fmaxf(st.m, mb);
     if (m_new > -INFINITY) {  // false only while this group has seen no valid row at all

@@ -149,6 +149,77 @@ def test_decode_from_an_empty_cache_without_any_prefill(dtype, d):
         P.check_cache_unit(host, u, states[u], what="[from-empty] final cache")
 
 
+def _poison_unused(cache, n_used):
+    """Every byte of the cache slots (and statistics) at or beyond n_used[u] becomes 0xFF: NaN patterns in fp32 and in
+    bf16.  The library must never let those bytes reach a result: such slots are documented as ignored."""
+    for u, n in enumerate(n_used):
+        cache.K[u, n:].view(torch.uint8).fill_(0xFF)
+        cache.V[u, n:].view(torch.uint8).fill_(0xFF)
+        cache.stats[u, :, n:].view(torch.uint8).fill_(0xFF)
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64)])
+def test_unused_cache_slots_may_hold_any_bytes_decode_from_empty(dtype, d):
+    """Token-wise decode into a cache whose memory was never cleared: the first step's only row is the new token's,
+    and the rows loaded merely to keep addresses in range (weight zero) must not turn the output into NaN."""
+    P = _parity()
+    units, B, s, steps = 3, 24, 5, 30
+    sc = 1.0 / math.sqrt(d)
+    rng = np.random.default_rng(84)
+    Q = rng.standard_normal((units, steps, d)).astype(np.float32) + 0.25
+    K = rng.standard_normal((units, steps, d)).astype(np.float32)
+    V = rng.standard_normal((units, steps, d)).astype(np.float32)
+    if dtype == "bf16":
+        Q, K, V = round_to_bf16(Q), round_to_bf16(K), round_to_bf16(V)
+    sess = P.make_session(units, d, B, s, dtype)
+    _poison_unused(sess.cache, [0] * units)
+    states = [orc.CacheState(np.zeros((B, d)), np.zeros((B, d)), np.zeros(B), np.zeros(B), np.zeros(B),
+                             np.full(B, -1, dtype=np.int64), 0) for _ in range(units)]
+    for t in range(steps):
+        g_out, g_slot, g_pos = P.gpu_decode_step(sess, Q[:, t], K[:, t], V[:, t], [t] * units)
+        assert np.isfinite(g_out).all(), f"step {t}: bytes of an unused slot reached the output"
+        for u in range(units):
+            P.lockstep_decode_unit(states[u], u, g_out, g_slot, g_pos, Q[u, t], K[u, t], V[u, t], t, s, sc, dtype, 0, 0.0,
+                                   what=f"[poisoned-empty] step {t}")
+    host = P.cache_to_host(sess)
+    for u in range(units):
+        P.check_cache_unit(host, u, states[u], what="[poisoned-empty] final cache")
+
+
+def test_unused_cache_slots_may_hold_any_bytes_after_a_short_prompt():
+    """A prompt that ends exactly where one workgroup's slot range ends (128 rows per range at this shape in the split
+    decode step), budget above it: the next token's slot is the first row of the following range, whose bytes were
+    never written.  Unused slots are poisoned after the prefill; the following steps must match the oracle."""
+    P = _parity()
+    units, L, B, s, d, steps = 3, 128, 512, 16, 128, 3
+    lens = [128, 128, 256]
+    rng = np.random.default_rng(85)
+    T = 256 + steps
+    Q = round_to_bf16(rng.standard_normal((units, T, d)).astype(np.float32) + 0.25)
+    K = round_to_bf16(rng.standard_normal((units, T, d)).astype(np.float32))
+    V = round_to_bf16(rng.standard_normal((units, T, d)).astype(np.float32))
+    sc = 1.0 / math.sqrt(d)
+    sess = P.make_session(units, d, B, s, "bf16")
+    g = P.gpu_prefill(sess, Q[:, :256].copy(), K[:, :256].copy(), V[:, :256].copy(), lens, False)
+    states = [P.check_prefill_unit(g, u, Q[u, :256], K[u, :256], V[u, :256], lens[u], B, s, sc, "bf16", want_out=False)[0].cache
+              for u in range(units)]
+    _poison_unused(sess.cache, lens)
+    pos = list(lens)
+    for t in range(steps):
+        g_out, g_slot, g_pos = P.gpu_decode_step(sess, Q[:, 256 + t], K[:, 256 + t], V[:, 256 + t], pos)
+        assert np.isfinite(g_out).all(), f"step {t}: bytes of an unused slot reached the output"
+        for u in range(units):
+            P.lockstep_decode_unit(states[u], u, g_out, g_slot, g_pos, Q[u, 256 + t], K[u, 256 + t], V[u, 256 + t],
+                                   pos[u], s, sc, "bf16", what=f"[poisoned-short-prompt] step {t}")
+        pos = [p + 1 for p in pos]
+    host = P.cache_to_host(sess)
+    for u in range(units):
+        n = states[u].n_used
+        assert np.array_equal(host["stats"][u, 2][:n], states[u].count[:n])
+        P.assert_stat_close(host["stats"][u, 0][:n], states[u].acc[:n], f"unit {u} Acc")
+        P.assert_stat_close(host["stats"][u, 1][:n], states[u].acc2[:n], f"unit {u} Acc2")
+
+
 @pytest.mark.parametrize("scope", [1, 7, 96])
 def test_scope_extremes(scope):
     """scope = 1 (only the lowest-variance slot may go), scope = B (plain lowest mean attention score)."""

@@ -52,7 +52,8 @@ enum {
   ROCO_EINVAL = -1,        /* null / misaligned pointer, budget < 1, scope outside [1, budget], ... */
   ROCO_EUNSUPPORTED = -2,  /* dtype or head_dim the kernels are not built for                       */
   ROCO_EWORKSPACE = -3,    /* workspace smaller than the matching *_workspace_bytes() query        */
-  ROCO_EHIP = -4           /* a kernel launch failed (hipGetLastError)                             */
+  ROCO_EHIP = -4,          /* a kernel launch failed (hipGetLastError)                             */
+  ROCO_ESCRATCH = -5       /* roco_decode_step_static: the shape needs more than ROCO_STATIC_SCRATCH_BYTES */
 };
 
 typedef struct roco_params {
@@ -200,6 +201,27 @@ int roco_decode_step(const roco_params* params,
                      void* K_cache, void* V_cache, float* stats, int32_t* pos, int32_t* n_used,
                      int32_t* next_slot, void* out, int32_t* evicted_slot, int32_t* evicted_pos,
                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * roco_decode_step for callers that cannot allocate device memory or pass a workspace along: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspace, same kernels,
+ * same results bit for bit.  The scratch the kernels need (base-2 logits, per-range partial results, ranking keys) is
+ * a ROCO_STATIC_SCRATCH_BYTES array inside the library's device code: every GPU the library runs on holds its own
+ * copy until the process ends.  The call allocates nothing (no hipMalloc / hipFree, no allocating library routine);
+ * its first call on a device looks the array's address up once.
+ *   - A shape whose roco_decode_workspace_bytes(params) exceeds ROCO_STATIC_SCRATCH_BYTES is refused with
+ *     ROCO_ESCRATCH before anything is launched (workload 3's 512 units x 2048 slots need 20.3 MiB and fit).
+ *   - All calls on one GPU share that GPU's array, and the array keeps the previous call's contents.  Nothing in it
+ *     has to start from zero: every word a kernel reads has been written earlier in the same call.  Calls that may
+ *     overlap on one GPU (two streams, two threads) race on it: use roco_decode_step with workspaces of their own.
+ *   - Refused with ROCO_EUNSUPPORTED while roco_profile_kernel is switched on (that aid creates HIP events).
+ */
+#define ROCO_STATIC_SCRATCH_BYTES (32u << 20)
+int roco_decode_step_static(const roco_params* params,
+                            const void* q, const void* k_new, const void* v_new, const int32_t* qpos,
+                            void* K_cache, void* V_cache, float* stats, int32_t* pos, int32_t* n_used,
+                            int32_t* next_slot, void* out, int32_t* evicted_slot, int32_t* evicted_pos,
+                            void* hip_stream);
 
 /*
  * Block-wise evict-and-encode (section 5.3 "Overhead", appendix B: the block size b is the number of tokens

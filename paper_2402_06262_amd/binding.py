@@ -84,6 +84,8 @@ def load_library() -> ctypes.CDLL:
     lib.roco_prefill_compress.argtypes = [pp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.roco_decode_step.restype = ctypes.c_int
     lib.roco_decode_step.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.roco_decode_step_static.restype = ctypes.c_int
+    lib.roco_decode_step_static.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.roco_probe_cache_read.restype = ctypes.c_int
     lib.roco_probe_cache_read.argtypes = [pp, vp, vp, vp, sz, vp]
     lib.roco_probe_mfma.restype = ctypes.c_int
@@ -202,6 +204,17 @@ def roco_decode_step(params: RocoParams, q, k_new, v_new, qpos, K_cache, V_cache
         _ptr(workspace), int(workspace_bytes), _stream(stream))
     if rc != 0:
         raise RocoError(rc, "roco_decode_step")
+
+
+def roco_decode_step_static(params: RocoParams, q, k_new, v_new, qpos, K_cache, V_cache, stats, pos, n_used,
+                            next_slot, out, evicted_slot, evicted_pos, stream=None) -> None:
+    """See include/roco.h: the decode step on the library's own static scratch (no workspace, no allocation)."""
+    rc = load_library().roco_decode_step_static(
+        ctypes.byref(params), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(qpos), _ptr(K_cache), _ptr(V_cache),
+        _ptr(stats), _ptr(pos), _ptr(n_used), _ptr(next_slot), _ptr(out), _ptr(evicted_slot), _ptr(evicted_pos),
+        _stream(stream))
+    if rc != 0:
+        raise RocoError(rc, "roco_decode_step_static")
 
 
 def prefill_gqa_workspace_bytes(params: RocoParams, group: int, L_max: int) -> int:

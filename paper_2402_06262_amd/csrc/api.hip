@@ -3,8 +3,17 @@
 #include <math.h>
 #include <stdlib.h>
 
+#include <mutex>
+
 #include "../../include/roco.h"
 #include "kernels.hpp"
+#include "profile.hpp"
+
+// Scratch of roco_decode_step_static: device memory that belongs to the library's code object, so the call needs no
+// allocation and no workspace from the caller.  Every GPU the library runs on holds its own copy, at its own
+// address, until the process ends.  In host code this name is only a handle for hipGetSymbolAddress; kernels get the
+// address that call returns.
+static __device__ __align__(256) unsigned char scratch[ROCO_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -220,6 +229,68 @@ int run_prefill(const roco_params* params, int group, const void* Q, const void*
 }
 }  // namespace
 
+namespace {
+// Argument checks shared by the two entry points of the token-wise decode step (host only, nothing is launched).
+int check_decode_args(const roco_params* params, const void* q, const void* k_new, const void* v_new,
+                      const int32_t* qpos, void* K_cache, void* V_cache, float* stats, int32_t* pos, int32_t* n_used,
+                      int32_t* next_slot, void* out) {
+  const int rc = check_params(params);
+  if (rc != ROCO_OK) return rc;
+  const void* need[] = {q, k_new, v_new, qpos, K_cache, V_cache, stats, pos, n_used, next_slot, out};
+  for (const void* ptr : need)
+    if (ptr == nullptr || !aligned16(ptr)) return ROCO_EINVAL;
+  return ROCO_OK;
+}
+
+// The decode step's kernels on `workspace` (device memory of at least decode_layout(params).total bytes).
+int launch_decode_step(const roco_params* params, const void* q, const void* k_new, const void* v_new,
+                       const int32_t* qpos, void* K_cache, void* V_cache, float* stats, int32_t* pos,
+                       int32_t* n_used, int32_t* next_slot, void* out, int32_t* evicted_slot, int32_t* evicted_pos,
+                       void* workspace, void* hip_stream) {
+  const DecodeLayout lay = decode_layout(params);
+  DecodeArgs a;
+  a.units = params->units; a.B = params->budget; a.scope = params->scope;
+  a.pol = policy_of(params);
+  a.unroll = env_int("ROCO_DECODE_UNROLL", 8);  // rows per lane group per block; 8 measured best on workload 3
+  if (a.unroll != 2 && a.unroll != 4) a.unroll = 8;
+  a.rotate = env_int("ROCO_DECODE_ROTATE", 1);
+  choose_splits(params, a.unroll, a.splits, a.rows_per_split);
+  a.fused = decode_is_fused(params) ? 1 : 0;
+  a.streaming = streaming_loads(params) ? 1 : 0;
+  a.scale_log2 = scale_log2(params);
+  a.recency_window = params->recency_window;
+  a.recency_bias_log2 = params->recency_bias * 1.4426950408889634f;
+  a.q = q; a.k_new = k_new; a.v_new = v_new; a.qpos = qpos;
+  a.K = K_cache; a.V = V_cache; a.stats = stats; a.pos = pos; a.n_used = n_used; a.next_slot = next_slot; a.out = out;
+  a.evicted_slot = evicted_slot; a.evicted_pos = evicted_pos;
+  char* ws = static_cast<char*>(workspace);
+  a.z = reinterpret_cast<float*>(ws + lay.z);
+  a.part_m = reinterpret_cast<float*>(ws + lay.part_m);
+  a.part_l = reinterpret_cast<float*>(ws + lay.part_l);
+  a.part_o = reinterpret_cast<float*>(ws + lay.part_o);
+  a.keys = reinterpret_cast<uint32_t*>(ws + lay.keys);
+  const hipError_t e = launch_decode(params->dtype, params->head_dim, a, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
+}
+
+// Device address of `scratch` on the current device: looked up once per device, with that device current, and kept.
+constexpr int kMaxDevices = 64;
+bool static_scratch(void** out) {
+  static std::mutex mu;
+  static void* addr[kMaxDevices] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return false;
+  std::lock_guard<std::mutex> lock(mu);
+  if (addr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return false;
+    addr[dev] = p;
+  }
+  *out = addr[dev];
+  return true;
+}
+}  // namespace
+
 extern "C" {
 
 int roco_prefill_compress(const roco_params* params, const void* Q, const void* K, const void* V,
@@ -250,37 +321,26 @@ int roco_decode_step(const roco_params* params, const void* q, const void* k_new
                      const int32_t* qpos, void* K_cache, void* V_cache, float* stats, int32_t* pos,
                      int32_t* n_used, int32_t* next_slot, void* out, int32_t* evicted_slot,
                      int32_t* evicted_pos, void* workspace, size_t workspace_bytes, void* hip_stream) {
-  const int rc = check_params(params);
+  const int rc = check_decode_args(params, q, k_new, v_new, qpos, K_cache, V_cache, stats, pos, n_used, next_slot, out);
   if (rc != ROCO_OK) return rc;
-  const void* need[] = {q, k_new, v_new, qpos, K_cache, V_cache, stats, pos, n_used, next_slot, out, workspace};
-  for (const void* ptr : need)
-    if (ptr == nullptr || !aligned16(ptr)) return ROCO_EINVAL;
-  const DecodeLayout lay = decode_layout(params);
-  if (workspace_bytes < lay.total) return ROCO_EWORKSPACE;
+  if (workspace == nullptr || !aligned16(workspace)) return ROCO_EINVAL;
+  if (workspace_bytes < decode_layout(params).total) return ROCO_EWORKSPACE;
+  return launch_decode_step(params, q, k_new, v_new, qpos, K_cache, V_cache, stats, pos, n_used, next_slot, out,
+                            evicted_slot, evicted_pos, workspace, hip_stream);
+}
 
-  DecodeArgs a;
-  a.units = params->units; a.B = params->budget; a.scope = params->scope;
-  a.pol = policy_of(params);
-  a.unroll = env_int("ROCO_DECODE_UNROLL", 8);  // rows per lane group per block; 8 measured best on workload 3
-  if (a.unroll != 2 && a.unroll != 4) a.unroll = 8;
-  a.rotate = env_int("ROCO_DECODE_ROTATE", 1);
-  choose_splits(params, a.unroll, a.splits, a.rows_per_split);
-  a.fused = decode_is_fused(params) ? 1 : 0;
-  a.streaming = streaming_loads(params) ? 1 : 0;
-  a.scale_log2 = scale_log2(params);
-  a.recency_window = params->recency_window;
-  a.recency_bias_log2 = params->recency_bias * 1.4426950408889634f;
-  a.q = q; a.k_new = k_new; a.v_new = v_new; a.qpos = qpos;
-  a.K = K_cache; a.V = V_cache; a.stats = stats; a.pos = pos; a.n_used = n_used; a.next_slot = next_slot; a.out = out;
-  a.evicted_slot = evicted_slot; a.evicted_pos = evicted_pos;
-  char* ws = static_cast<char*>(workspace);
-  a.z = reinterpret_cast<float*>(ws + lay.z);
-  a.part_m = reinterpret_cast<float*>(ws + lay.part_m);
-  a.part_l = reinterpret_cast<float*>(ws + lay.part_l);
-  a.part_o = reinterpret_cast<float*>(ws + lay.part_o);
-  a.keys = reinterpret_cast<uint32_t*>(ws + lay.keys);
-  const hipError_t e = launch_decode(params->dtype, params->head_dim, a, static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
+int roco_decode_step_static(const roco_params* params, const void* q, const void* k_new, const void* v_new,
+                            const int32_t* qpos, void* K_cache, void* V_cache, float* stats, int32_t* pos,
+                            int32_t* n_used, int32_t* next_slot, void* out, int32_t* evicted_slot,
+                            int32_t* evicted_pos, void* hip_stream) {
+  const int rc = check_decode_args(params, q, k_new, v_new, qpos, K_cache, V_cache, stats, pos, n_used, next_slot, out);
+  if (rc != ROCO_OK) return rc;
+  if (decode_layout(params).total > static_cast<size_t>(ROCO_STATIC_SCRATCH_BYTES)) return ROCO_ESCRATCH;
+  if (roco::g_prof_which >= 0) return ROCO_EUNSUPPORTED;  // the profiling aid creates HIP events
+  void* ptr = nullptr;
+  if (!static_scratch(&ptr)) return ROCO_EHIP;
+  return launch_decode_step(params, q, k_new, v_new, qpos, K_cache, V_cache, stats, pos, n_used, next_slot, out,
+                            evicted_slot, evicted_pos, ptr, hip_stream);
 }
 
 size_t roco_block_workspace_bytes(const roco_params* params, int32_t block) {
@@ -450,6 +510,7 @@ const char* roco_strerror(int code) {
     case ROCO_EUNSUPPORTED: return "unsupported dtype, head_dim or budget";
     case ROCO_EWORKSPACE: return "workspace too small";
     case ROCO_EHIP: return "HIP kernel launch failed";
+    case ROCO_ESCRATCH: return "the call needs more scratch than the library's static buffer holds";
     default: return "unknown error code";
   }
 }

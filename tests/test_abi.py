@@ -25,7 +25,7 @@ def test_library_loads_and_exports_every_declared_symbol():
             "roco_decode_workspace_bytes", "roco_strerror", "roco_version", "roco_select_victims",
             "roco_probe_cache_read", "roco_profile_sampling", "roco_encode_block", "roco_block_workspace_bytes",
             "roco_decode_step_gqa", "roco_encode_block_gqa",
-            "roco_select_retained", "roco_decode_step_launches"} <= set(names)
+            "roco_select_retained", "roco_decode_step_launches", "roco_decode_step_static"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in roco.h but not exported"
     assert roco.roco_version() == 1
@@ -201,3 +201,17 @@ def test_loading_fails_loudly_when_the_library_is_missing(monkeypatch):
     monkeypatch.setattr(binding, "_LIB_NAME", "libroco_missing.so")
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         binding.load_library()
+
+
+def test_static_scratch_decode_step_validates_on_the_host():
+    """Argument errors and shapes beyond the static scratch are reported before any HIP call."""
+    lib = roco.load_library()
+    ok = roco.RocoParams(4, 128, 64, 8, roco.ROCO_BF16)
+    args = [0x1000] * 13
+    assert lib.roco_decode_step_static(None, *args, None) == EINVAL
+    assert lib.roco_decode_step_static(ctypes.byref(ok), None, *args[1:], None) == EINVAL
+    assert lib.roco_decode_step_static(ctypes.byref(ok), 0x1001, *args[1:], None) == EINVAL
+    big = roco.RocoParams(4096, 128, 4096, 64, roco.ROCO_BF16)
+    assert roco.decode_workspace_bytes(big) > 32 << 20
+    assert lib.roco_decode_step_static(ctypes.byref(big), *args, None) == -5
+    assert "static" in roco.roco_strerror(-5)

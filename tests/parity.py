@@ -44,10 +44,22 @@ def to_host(t: torch.Tensor) -> np.ndarray:
     return t.detach().float().cpu().numpy() if t.dtype in (torch.bfloat16, torch.float32) else t.detach().cpu().numpy()
 
 
+# Run-wide records, printed at the end of a pytest session (tests/conftest.py): the worst output error in units of
+# the tolerance under the floor in use (rms of the vector) and under the stricter floor 1e-3 * rms, per storage type;
+# and every test's declared-tie count.
+WORST_OUT = {"f32": [0.0, 0.0], "bf16": [0.0, 0.0]}
+TIE_LOG: List[tuple] = []
+
+
 def assert_out_close(g: np.ndarray, o: np.ndarray, dtype: str, what: str):
     g, o = np.asarray(g, np.float64), np.asarray(o, np.float64)
     rms = math.sqrt(float(np.mean(o * o))) if o.size else 0.0
     tol = OUT_RTOL[dtype] * np.maximum(np.abs(o), rms)
+    if o.size:
+        err = np.abs(g - o)
+        w = WORST_OUT[dtype]
+        w[0] = max(w[0], float(np.max(err / np.maximum(tol, 1e-300))))
+        w[1] = max(w[1], float(np.max(err / np.maximum(OUT_RTOL[dtype] * np.maximum(np.abs(o), 1e-3 * rms), 1e-300))))
     bad = np.abs(g - o) > tol
     assert not bad.any(), f"{what}: {int(bad.sum())} of {o.size} outside tolerance; worst |g-o|/tol = " \
                           f"{float(np.max(np.abs(g - o) / np.maximum(tol, 1e-300))):.3g}"
@@ -74,6 +86,16 @@ class TieCount:
         self.decode_decisions += o.decode_decisions
         self.decode_ties += o.decode_ties
         return self
+
+
+def assert_few_ties(t: "TieCount", what: str, exact: bool = False):
+    """Declared ties are decisions on which the library and the oracle differ inside the tolerance band; they must stay
+    rare, or a wrong ranking could hide among them.  Ceiling: 1 % of the decisions (at least 2); `exact` (fp32 storage,
+    where both sides rank nearly identical numbers): none at all."""
+    dec, ties = t.prefill_decisions + t.decode_decisions, t.prefill_ties + t.decode_ties
+    TIE_LOG.append((what, t.prefill_decisions, t.prefill_ties, t.decode_decisions, t.decode_ties))
+    limit = 0 if exact else max(2, dec // 100)
+    assert ties <= limit, f"{what}: {ties} declared ties in {dec} eviction decisions (limit {limit}): {t}"
 
 
 @dataclass

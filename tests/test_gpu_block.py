@@ -66,6 +66,7 @@ def drive(units, d, B, s, prompt_lens, blocks, seed, recency=False, tag="", dtyp
         ties += P.lockstep_decode_unit(states[u], u, g_out, g_slot, g_pos, Q[u, t - 1], K[u, t - 1], V[u, t - 1], nxt[u], s,
                                        sc, dtype, rw, rb, what=f"[{tag}] decode after blocks")
     print(f"[{tag}] ties {ties}", flush=True)
+    P.assert_few_ties(ties, tag)
     return ties
 
 
@@ -182,3 +183,4 @@ def test_block_steps_at_the_serving_shape_all_512_units():
         for k, u in enumerate(sample):
             P.check_cache_unit(host, k, states[k], what=f"[cfg3-block] block {i} unit {u}")
     print("[cfg3-block] ties", ties, flush=True)
+    P.assert_few_ties(ties, "cfg3-block")

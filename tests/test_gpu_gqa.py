@@ -58,6 +58,7 @@ def drive(units, B, s, group, blocks, seed, recency=False, tag="", single_token_
                 P.check_cache_unit(host, u, states[u], what=f"[{tag}] after block {b} @ {t}")
         t += b
     print(f"[{tag}] ties {ties}", flush=True)
+    P.assert_few_ties(ties, tag)
     return ties
 
 
@@ -138,6 +139,7 @@ def run_grouped_prefill(dtype, d, group, lens, L, B, s, seed, steps=6, recency=F
     for u in range(units):
         P.check_cache_unit(host, u, states[u], what=f"[{tag}] end")
     print(f"[{tag}] ties {ties}", flush=True)
+    P.assert_few_ties(ties, tag)
 
 
 @pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 128), ("bf16", 64)])
@@ -220,6 +222,7 @@ def test_grouped_prefill_at_the_serving_shape():
         _, t = P.check_prefill_unit(g_res, k_, None, Kh, Vh, L, B, s, sc, "bf16", 0, 0.0, False, full=full)
         ties += t
     print(f"[gqa-prefill-serving] ties {ties}", flush=True)
+    P.assert_few_ties(ties, "gqa-prefill-serving")
 
 
 def test_grouped_decode_at_the_serving_shape():
@@ -258,6 +261,7 @@ def test_grouped_decode_at_the_serving_shape():
     for u in sample:
         P.check_cache_unit({k: v[[u]] for k, v in host.items()}, 0, states[u], what="[gqa-serving] end")
     print(f"[gqa-serving] ties {ties}", flush=True)
+    P.assert_few_ties(ties, "gqa-serving")
 
 
 def test_group_of_one_matches_the_token_wise_decode_step_bit_for_bit_in_its_decisions():

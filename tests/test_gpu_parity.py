@@ -74,6 +74,7 @@ def run_workload(dtype, head_dim, units, lens, L_max, budget, scope, steps, seed
             for u in range(units):
                 P.check_cache_unit(host, u, states[u], what=f"[{tag}] step {step}")
     print(f"[{tag}] ties: {ties}", flush=True)
+    P.assert_few_ties(ties, tag)
     return ties
 
 
@@ -105,6 +106,7 @@ def test_config1_tiny_fp32_prefill_then_64_decode_steps(seed):
         P.check_cache_unit(host, u, states[u], what=f"cfg1 seed {seed} end")
     print("cfg1 ties", ties, flush=True)
     assert ties.decode_decisions == cfg.units * cfg.steps and ties.prefill_decisions == cfg.units
+    P.assert_few_ties(ties, f"cfg1 seed {seed}", exact=True)
 
 
 @pytest.mark.parametrize("dtype,head_dim", [("bf16", 128), ("bf16", 64), ("f32", 128), ("f32", 64)])

@@ -59,6 +59,7 @@ def run(dtype, d, group, lens, L, B, s, seed, recency=False, policy=None, tag=""
     torch.cuda.synchronize()
     assert torch.equal(kept, c.next_slot)
     print(f"[{tag}] ties {ties}", flush=True)
+    P.assert_few_ties(ties, tag)
 
 
 @pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128)])

@@ -363,7 +363,6 @@ int roco_probe_mfma(int32_t workgroups, int32_t iters, int32_t operands, float* 
  *   ROCO_STREAMING_LOADS=0|1   non-temporal loads of the cache rows (default: caches above 192 MiB)
  *   ROCO_PREFILL_SIMPLE=1      vector-ALU prefill passes also for bf16 / head_dim 128
  *   ROCO_PREFILL_PAIRED=0|1    one block of rows per workgroup / a long and a short one (default 1)
- *   ROCO_PREFILL_WAVES=4|8     waves per workgroup of the matrix-core prefill passes (default 4)
  *   ROCO_PREFILL_QSPLIT=1|2    workgroups per block of rows in the two prefill passes (default: 2 with few units)
  *   ROCO_BLOCK_SPLITS=n        splits of the budget in the block-wise / grouped steps (default: about 512 / units)
  *   ROCO_BLOCK_SINGLE=0        single-token block steps go through the preparing kernel like longer blocks

@@ -194,7 +194,6 @@ int run_prefill(const roco_params* params, int group, const void* Q, const void*
   a.pol = policy_of(params);
   a.pairs = 0;
   a.paired = env_int("ROCO_PREFILL_PAIRED", -1);
-  a.mfma_waves = env_int("ROCO_PREFILL_WAVES", 0);
   a.skip_rows = want_lse ? 1 : 0;
   a.qsplit = 1;
   a.ksplit = 1;
@@ -211,7 +210,8 @@ int run_prefill(const roco_params* params, int group, const void* Q, const void*
   a.mas_key = reinterpret_cast<uint32_t*>(ws + lay.mas_key);
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const bool mfma = params->dtype == ROCO_BF16 && params->head_dim == 128 &&
+  // (the matrix-core kernels address a unit's rows with 32-bit byte offsets: up to 4M tokens of 256 bytes)
+  const bool mfma = params->dtype == ROCO_BF16 && params->head_dim == 128 && L_max <= (1 << 22) &&
                     env_int("ROCO_PREFILL_SIMPLE", 0) == 0;
   if (want_lse) {  // the kernels keep base-2 normalisers
     const size_t count = static_cast<size_t>(params->units) * group * L_max;

@@ -79,7 +79,6 @@ struct PrefillArgs {
   Policy pol;
   int pairs;             // matrix-core path: workgroup ids per unit (set by its launcher)
   int paired;            // matrix-core path: 1 = long+short block per workgroup, 0 = one block, -1 = choose
-  int mfma_waves;        // matrix-core path: 4 or 8 waves per workgroup, 0 = choose by problem size
   int skip_rows;         // 1: lse already holds the row normalisers, pass 1 is not run
   int qsplit;            // matrix-core path: 1, or 2 = two workgroups share a block's queries (set by its launcher)
   int ksplit;            // matrix-core path, row pass: 1, or 2 = two workgroups share a block's keys (ditto)

@@ -22,6 +22,7 @@
 #include "mfma.hpp"
 #include "profile.hpp"
 #include "stream.hpp"
+#include "tile_ring.hpp"
 
 namespace roco {
 namespace {
@@ -116,15 +117,32 @@ __device__ __forceinline__ bool locate(int units, int pairs, int& unit, int& pai
 // Online log-sum-exp update of one lane with the 16 scores of a tile.
 //   INTERIOR: every key of the tile is visible to every query of the group and none is inside a recency window:
 //             3 vector instructions per score (multiply-add, exponential, add) plus 8 for the maximum.
+// l = sum 2^(t - m) is a floating-point number, so m need not be the running maximum: any reference that keeps the
+// terms from overflowing gives the same sum to rounding.  The terms of a tile are first taken against the reference
+// as it stands (3 instructions per score and nothing else: `sum`); only if some lane's share comes out above 2^64
+// -- the first tile, whose reference is -inf, and a row whose scores later rise by more than 64 powers of two --
+// is the tile redone with the reference raised to its maximum.
+__device__ __forceinline__ void lazy_finish(float sum, const f32x16& s, float sc, float& m, float& l) {
+  if (__builtin_amdgcn_ballot_w64(!(sum <= 0x1p64f)) == 0) {
+    l += sum;
+  } else {
+    const float m_new = fmaxf(m, max16(s) * sc);
+    const float neg_new = -m_new;
+    float t0 = 0.0f, t1 = 0.0f;
+#pragma unroll
+    for (int r = 0; r < 16; r += 2) {
+      t0 += fast_exp2(fmaf(s[r], sc, neg_new));
+      t1 += fast_exp2(fmaf(s[r + 1], sc, neg_new));
+    }
+    l = fmaf(l, fast_exp2(m - m_new), t0 + t1);
+    m = m_new;
+  }
+}
+
 template <bool INTERIOR>
 __device__ __forceinline__ void lse_update(const f32x16& s, float sc, int kb, int half, int qi, int w, float rb,
                                            float& m, float& l) {
   if (INTERIOR) {
-    // l = sum 2^(t - m) is a floating-point number, so m need not be the running maximum: any reference that keeps
-    // the terms from overflowing gives the same sum to rounding.  The terms are first taken against the reference as
-    // it stands (3 instructions per score and nothing else); only if some lane's share comes out above 2^64 -- the
-    // first tile, whose reference is -inf, and a row whose scores later rise by more than 64 powers of two -- is
-    // the tile redone with the reference raised to its maximum.
     const float neg = -m;
     float sum0 = 0.0f, sum1 = 0.0f;
 #pragma unroll
@@ -132,21 +150,7 @@ __device__ __forceinline__ void lse_update(const f32x16& s, float sc, int kb, in
       sum0 += fast_exp2(fmaf(s[r], sc, neg));
       sum1 += fast_exp2(fmaf(s[r + 1], sc, neg));
     }
-    const float sum = sum0 + sum1;
-    if (__builtin_amdgcn_ballot_w64(!(sum <= 0x1p64f)) == 0) {
-      l += sum;
-    } else {
-      const float m_new = fmaxf(m, max16(s) * sc);
-      const float neg_new = -m_new;
-      float t0 = 0.0f, t1 = 0.0f;
-#pragma unroll
-      for (int r = 0; r < 16; r += 2) {
-        t0 += fast_exp2(fmaf(s[r], sc, neg_new));
-        t1 += fast_exp2(fmaf(s[r + 1], sc, neg_new));
-      }
-      l = fmaf(l, fast_exp2(m - m_new), t0 + t1);
-      m = m_new;
-    }
+    lazy_finish(sum0 + sum1, s, sc, m, l);
   } else {
     float tv[16];
     float mb = -INFINITY;
@@ -172,49 +176,56 @@ __device__ __forceinline__ void lse_update(const f32x16& s, float sc, int kb, in
 
 // ------------------------------------------------------------------------------------------------
 // pass 1: lse[i] = log2 sum_{j<=i} 2^(t_ij),  t_ij = scale*log2(e) * q_i.k_j + bias
-template <int WAVES>
-__global__ __launch_bounds__(WAVES * kWave) void prefill_rows_mfma(PrefillArgs a) {
-  constexpr int kOwn = Shape<WAVES>::kOwn;
-  __shared__ __attribute__((aligned(16))) char lds[2][kTile * kLdsRow];
+//
+// A workgroup owns 256 queries: wave w the groups of 32 that start at 32 w and at 32 (7 - w) of the block, so that
+// the work under the causal diagonal is the same for every wave.  The key tiles come through a TileRing
+// (tile_ring.hpp), requested two tiles ahead.  The keys below the block's first query form a rectangle in which
+// nothing is masked and every wave does the same work: those tiles run software-pipelined (fill_and_consume: the
+// matrix instructions of one half-tile interleaved with the exponentials of the half-tile before it, four
+// accumulators).  The tiles that touch the diagonal or a recency window take the plain form, masks and all.
+template <int S> struct StageTag { static constexpr int value = S; };
+
+__global__ __launch_bounds__(256, 2) void prefill_rows_mfma(PrefillArgs a) {
+  constexpr int kOwn = Shape<4>::kOwn;
+  __shared__ __attribute__((aligned(1024))) char ring[kRingBytes];
   int u, id;  // u counts (unit, query head) pairs: with grouped-query attention a unit has a.group heads
   if (!locate(a.units * a.group, a.pairs * a.ksplit, u, id)) return;
   const int seg = id % a.ksplit, pair_id = id / a.ksplit;  // which share of the keys, which blocks of queries
   float* const lse_out = seg == 0 ? a.lse : a.acc;  // second share: see merge_key_shares (group = 1 only)
   const int uk = u / a.group;  // the unit: its keys and its length
   const int len = a.len[uk];
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int lane = threadIdx.x & (kWave - 1);
   const int half = lane >> 5;
+  TileRing tr;
+  tr.init();
+  const int wave = tr.wave;
+  const uint32_t ring_addr = lds_address(ring);
   const size_t ubase = static_cast<size_t>(u) * a.L_max;
   const char* Qb = static_cast<const char*>(a.Q) + ubase * kRowBytes;
   const char* Kb = static_cast<const char*>(a.K) + static_cast<size_t>(uk) * a.L_max * kRowBytes;
+  const v4i32 kbuf = make_buffer(Kb, static_cast<uint32_t>(len) * kRowBytes);  // keys past the end read as zeros
   const float sc = a.scale_log2;
   const int w = a.recency_window;
   const float rb = a.recency_bias_log2;
   const int n_blocks = (len + kOwn - 1) / kOwn;
   if (a.paired ? 2 * pair_id > n_blocks - 1 : pair_id >= n_blocks) return;  // nothing left for this id
 
-  // Two schedules.  Paired (few workgroups in all): a workgroup takes one long and one short block (p and
-  // n-1-p), so that all of them do the same amount of work whatever their position under the causal diagonal.
-  // Unpaired (plenty of workgroups): one block each; the workgroups of a unit sit on one die, start together
-  // and walk the streamed operand from row 0 at the same pace, so a streamed tile is fetched from HBM once and
-  // then found in that die's L2 by the others.
+  // Two schedules.  Paired: a workgroup takes one long and one short block (n-1-p and p), so that all of them do
+  // the same amount of work whatever their position under the causal diagonal.  Unpaired: one block each.
   for (int pass = 0; pass < 2; ++pass) {
     int blk;
     if (a.paired) {
-      blk = pass == 0 ? pair_id : n_blocks - 1 - pair_id;
-      if (blk < pair_id || (pass == 1 && blk == pair_id)) break;
+      // The long block first: the workgroups of a unit start together, on one die, and all of them then walk the keys
+      // from row 0 at the same pace, so a key tile is fetched from memory once and found in that die's L2 by the others.
+      blk = pass == 0 ? n_blocks - 1 - pair_id : pair_id;
+      if (pass == 1 && blk == n_blocks - 1 - pair_id) break;  // the middle block of an odd number has no partner
     } else {
       if (pass == 1) break;
       blk = n_blocks - 1 - pair_id;  // the longest streams start first
     }
     const int q0 = blk * kOwn;
-    const int qw0 = q0 + 64 * wave;  // first query of this wave
-    const int qi0 = qw0 + (lane & 31), qi1 = qi0 + 32;
-    uint4 own0[kKSteps], own1[kKSteps];
-    load_owned(own0, Qb, qi0, len - 1);
-    load_owned(own1, Qb, qi1, len - 1);
-    float m0 = -INFINITY, l0 = 0.0f, m1 = -INFINITY, l1 = 0.0f;
-
+    const int qg0 = q0 + 32 * wave, qg1 = q0 + 32 * (7 - wave);  // first query of this wave's two groups (qg0 < qg1)
+    const int qi0 = qg0 + (lane & 31), qi1 = qg1 + (lane & 31);
     const int last_key = min(len, q0 + kOwn) - 1;  // keys 0..last_key are visible to some query of the block
     const int n_tiles = last_key / kTile + 1;
     int t_lo = 0, t_hi = n_tiles - 1;  // this workgroup's share of the key tiles (possibly none)
@@ -223,30 +234,98 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_mfma(PrefillArgs a
       t_lo = seg * per;
       t_hi = min(t_hi, t_lo + per - 1);
     }
-    // The next tile is requested right after the barrier and has the whole tile of work to arrive.
-    Staged<WAVES> stA;
-    if (t_lo <= t_hi) tile_load(stA, Kb, t_lo * kTile, len - 1);
-    __syncthreads();  // the previous pass has finished with the LDS buffers
-    auto step = [&](Staged<WAVES>& st, int t) {
-      tile_store(st, lds[t & 1]);
-      __syncthreads();
-      if (t + 1 <= t_hi) tile_load(st, Kb, (t + 1) * kTile, len - 1);
+    // tiles [t_lo, t_rect) lie wholly below the block's first query and outside every recency window
+    const int t_rect = min(t_hi + 1, max(t_lo, (q0 + 1 - w) >= 0 ? (q0 + 1 - w) / kTile : 0));
+    __syncthreads();  // the previous block has finished with the ring
+    if (t_lo <= t_hi) tr.request(kbuf, ring_addr, t_lo, 0);
+    if (t_lo + 1 <= t_hi) tr.request(kbuf, ring_addr, t_lo + 1, 1);
+    uint4 own0[kKSteps], own1[kKSteps];
+    load_owned(own0, Qb, qi0, len - 1);
+    load_owned(own1, Qb, qi1, len - 1);
+    // The owned rows must have arrived before the loop: a wait for them inside it would also wait for the tiles
+    // requested last, which are meant to stay in flight.
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    float m0 = -INFINITY, l0 = 0.0f, m1 = -INFINITY, l1 = 0.0f;
+
+    auto next_tile = [&](int t, int stage) {  // tile t has landed in `stage`; tile t + 2 is requested
+      if (t + 1 <= t_hi) wait_loads<4>();  // tile t + 1 may still be on its way
+      else wait_loads<0>();
+      __syncthreads();  // every wave's share of tile t is in LDS, and everybody has issued its last read of tile t - 1
+      if (t + 2 <= t_hi) tr.request(kbuf, ring_addr, t + 2, (stage + 2) % kRingStages);
+    };
+
+    // ---- the rectangle: software-pipelined.  A* hold the scores of a tile's first 32 keys, B* of its last 32.
+    f32x16 A0, A1, B0, B1;
+    bool pending = false;  // B* hold scores that have not been summed yet
+    auto consume_into = [&](const f32x16& y0, const f32x16& y1, float& a0, float& b0, float& a1, float& b1) {
+      const float n0 = -m0, n1 = -m1;
+      return [&, n0, n1](int kk, int g) {
+        if (g == 0) {
+          a0 += fast_exp2(fmaf(y0[2 * kk], sc, n0));
+          b0 += fast_exp2(fmaf(y0[2 * kk + 1], sc, n0));
+        } else {
+          a1 += fast_exp2(fmaf(y1[2 * kk], sc, n1));
+          b1 += fast_exp2(fmaf(y1[2 * kk + 1], sc, n1));
+        }
+      };
+    };
+    auto rect_tile = [&](auto stage, int t) {
+      constexpr int S = decltype(stage)::value;
+      next_tile(t, S);
+      const char* p = ring + S * kRingTileBytes;
+      float a0 = 0.0f, b0 = 0.0f, a1 = 0.0f, b1 = 0.0f;
+      auto pin = [&]() { asm volatile("" : "+v"(a0), "+v"(b0), "+v"(a1), "+v"(b1)); };
+      if (pending) {
+        fill_and_consume<true>(p, tr.frag, own0, own1, A0, A1, consume_into(B0, B1, a0, b0, a1, b1), pin);
+        lazy_finish(a0 + b0, B0, sc, m0, l0);
+        lazy_finish(a1 + b1, B1, sc, m1, l1);
+      } else {
+        fill_and_consume<false>(p, tr.frag, own0, own1, A0, A1, [](int, int) {}, pin);
+      }
+      a0 = b0 = a1 = b1 = 0.0f;
+      fill_and_consume<true>(p + 32 * kRowBytes, tr.frag, own0, own1, B0, B1, consume_into(A0, A1, a0, b0, a1, b1), pin);
+      lazy_finish(a0 + b0, A0, sc, m0, l0);
+      lazy_finish(a1 + b1, A1, sc, m1, l1);
+      pending = true;
+    };
+    int t = t_lo;
+    for (; t + 2 < t_rect; t += 3) {
+      rect_tile(StageTag<0>{}, t);
+      rect_tile(StageTag<1>{}, t + 1);
+      rect_tile(StageTag<2>{}, t + 2);
+    }
+    int stage = 0;  // ring stage of tile t
+    if (t < t_rect) { rect_tile(StageTag<0>{}, t); ++t; stage = 1; }
+    if (t < t_rect) { rect_tile(StageTag<1>{}, t); ++t; stage = 2; }
+    if (pending) {  // drain
+      float a0 = 0.0f, b0 = 0.0f, a1 = 0.0f, b1 = 0.0f;
+      auto c = consume_into(B0, B1, a0, b0, a1, b1);
+#pragma unroll
+      for (int kk = 0; kk < kKSteps; ++kk) { c(kk, 0); c(kk, 1); }
+      lazy_finish(a0 + b0, B0, sc, m0, l0);
+      lazy_finish(a1 + b1, B1, sc, m1, l1);
+    }
+
+    // ---- the tiles that touch the diagonal (or a recency window): masks decided per wave and group
+    for (; t <= t_hi; ++t) {
+      next_tile(t, stage);
+      const char* p = ring + stage * kRingTileBytes;
+      stage = stage == kRingStages - 1 ? 0 : stage + 1;
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub) {
         const int kb = t * kTile + sub * 32;
-        const bool do0 = kb <= qw0 + 31, do1 = kb <= qw0 + 63;  // not wholly above the diagonal
+        const bool do0 = kb <= qg0 + 31, do1 = kb <= qg1 + 31;  // not wholly above the diagonal
         if (!do1) continue;
         f32x16 s0, s1;
-        score_tiles(lds[t & 1], sub, own0, own1, do0, do1, s0, s1);
+        score_tiles_ring(p + sub * (32 * kRowBytes), tr.frag, own0, own1, do0, do1, s0, s1);
         if (do0) {
-          if (kb + 31 + w <= qw0) lse_update<true>(s0, sc, kb, half, qi0, w, rb, m0, l0);
+          if (kb + 31 + w <= qg0) lse_update<true>(s0, sc, kb, half, qi0, w, rb, m0, l0);
           else lse_update<false>(s0, sc, kb, half, qi0, w, rb, m0, l0);
         }
-        if (kb + 31 + w <= qw0 + 32) lse_update<true>(s1, sc, kb, half, qi1, w, rb, m1, l1);
+        if (kb + 31 + w <= qg1) lse_update<true>(s1, sc, kb, half, qi1, w, rb, m1, l1);
         else lse_update<false>(s1, sc, kb, half, qi1, w, rb, m1, l1);
       }
-    };
-    for (int t = t_lo; t <= t_hi; ++t) step(stA, t);
+    }
     // the two lane halves hold different keys of the same query
     {
       const float mo = __shfl_xor(m0, 32, kWave), lo = __shfl_xor(l0, 32, kWave);
@@ -307,31 +386,48 @@ __device__ __forceinline__ void column_update(const f32x16& s, const float* lse_
 
 // ------------------------------------------------------------------------------------------------
 // pass 2: Acc[j] = sum_{i>=j} 2^(t_ij - lse_i),  Acc2[j] = sum_{i>=j} (same)^2
-template <int WAVES, bool COUNT>
-__global__ __launch_bounds__(WAVES * kWave) void prefill_columns_mfma(PrefillArgs a) {
-  constexpr int kOwn = Shape<WAVES>::kOwn;
-  __shared__ __attribute__((aligned(16))) char lds[2][kTile * kLdsRow];
-  __shared__ __attribute__((aligned(16))) float lse_s[2][kTile];
-  __shared__ __attribute__((aligned(16))) float rinv_s[COUNT ? 2 : 1][COUNT ? kTile : 4];  // 1 / (i + 1) per staged query
+//
+// A workgroup owns 256 keys (wave w the groups of 32 that start at 32 w and 32 (7 - w) of the block) and walks the
+// query tiles from the end of the prompt DOWN to its own keys: every workgroup of a unit then starts at the same
+// tile and moves at the same pace, so a query tile is fetched from memory once and found in the die's L2 by the
+// others (a sum does not care about the order of its terms).  The tiles come through a TileRing; the row
+// normalisers of a tile's 64 queries ride along with it, every wave loading them into a copy of its own (one more
+// load per wave and tile; four stages, because a tile's normalisers are still needed one tile later by the
+// pipelined form).  Queries that lie past all of the block's keys and outside every recency window form a
+// rectangle in which nothing is masked: software-pipelined as in the row pass; the ragged end of the prompt and
+// the tiles on the diagonal take the plain form.
+template <bool COUNT>
+__global__ __launch_bounds__(256, 2) void prefill_columns_mfma(PrefillArgs a) {
+  constexpr int kOwn = Shape<4>::kOwn;
+  constexpr int kLseStages = 4;
+  __shared__ __attribute__((aligned(1024))) char ring[kRingBytes];
+  __shared__ __attribute__((aligned(256))) float lse_s[kLseStages][4][kTile];  // [stage][wave][query of the tile]
+  __shared__ __attribute__((aligned(16))) float rinv_s[COUNT ? kLseStages : 1][COUNT ? kTile : 4];  // 1 / (i + 1)
   int u, id;
   if (!locate(a.units, a.pairs * a.qsplit, u, id)) return;
   const int seg = id % a.qsplit, pair_id = id / a.qsplit;  // which share of the queries, which blocks of keys
   float* const out1 = seg == 0 ? a.acc : reinterpret_cast<float*>(a.var_key);    // second share: see sum_query_shares
   float* const out2 = seg == 0 ? a.acc2 : reinterpret_cast<float*>(a.mas_key);
   const int len = a.len[u];
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int lane = threadIdx.x & (kWave - 1);
   const int half = lane >> 5;
+  TileRing tr;
+  tr.init();
+  const int wave = tr.wave;
+  const uint32_t ring_addr = lds_address(ring);
+  const uint32_t lse_addr = lds_address(&lse_s[0][wave][0]);
   const size_t ubase = static_cast<size_t>(u) * a.L_max;
   const char* Qb = static_cast<const char*>(a.Q) + ubase * kRowBytes;
   const char* Kb = static_cast<const char*>(a.K) + ubase * kRowBytes;
-  const float* lse = a.lse + ubase;
+  const v4i32 qbuf = make_buffer(Qb, static_cast<uint32_t>(len) * kRowBytes);  // queries past the end read as zeros
+  const v4i32 lbuf = make_buffer(a.lse + ubase, static_cast<uint32_t>(len) * 4u);
   const float sc = a.scale_log2;
   const int w = a.recency_window;
   const float rb = a.recency_bias_log2;
   const int n_blocks = (len + kOwn - 1) / kOwn;
   if (a.paired ? 2 * pair_id > n_blocks - 1 : pair_id >= n_blocks) return;  // nothing left for this id
 
-  for (int pass = 0; pass < 2; ++pass) {  // one long and one short block of keys per workgroup
+  for (int pass = 0; pass < 2; ++pass) {  // one long and one short block of keys per workgroup, the long one first
     int blk;
     if (a.paired) {
       blk = pass == 0 ? pair_id : n_blocks - 1 - pair_id;
@@ -341,13 +437,8 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_mfma(PrefillArg
       blk = pair_id;  // the longest streams start first: key block 0 is attended by every query
     }
     const int j0 = blk * kOwn;
-    const int kw0 = j0 + 64 * wave;
-    const int kj0 = kw0 + (lane & 31), kj1 = kj0 + 32;  // this lane's two keys
-    uint4 own0[kKSteps], own1[kKSteps];
-    load_owned(own0, Kb, kj0, len - 1);
-    load_owned(own1, Kb, kj1, len - 1);
-    float s1a = 0.0f, s2a = 0.0f, s1b = 0.0f, s2b = 0.0f;
-
+    const int kg0 = j0 + 32 * wave, kg1 = j0 + 32 * (7 - wave);  // first key of this wave's two groups (kg0 < kg1)
+    const int kj0 = kg0 + (lane & 31), kj1 = kg1 + (lane & 31);  // this lane's two keys
     int t_first = j0 / kTile;  // first query tile with a query >= j0
     int t_last = (len - 1) / kTile;
     if (a.qsplit > 1) {  // this workgroup's share of those tiles (possibly none)
@@ -355,42 +446,125 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_mfma(PrefillArg
       t_first += seg * per;
       t_last = min(t_last, t_first + per - 1);
     }
-    Staged<WAVES> stA;
-    float lseA = 0.0f;
-    auto fetch = [&](Staged<WAVES>& st, float& lse_st, int t) {
-      tile_load(st, Qb, t * kTile, len - 1);
-      if (threadIdx.x < kTile) lse_st = lse[min(t * kTile + static_cast<int>(threadIdx.x), len - 1)];
+    const int n = t_last - t_first + 1;  // the i-th tile of the walk is t_last - i
+    // tiles from t_rect_lo on lie past every key of the block and outside every recency window
+    const int t_rect_lo = (j0 + kOwn - 1 + w + kTile - 1) / kTile;
+    auto request = [&](int i) {  // five loads per wave
+      const int t = t_last - i;
+      tr.request(qbuf, ring_addr, t, i % kRingStages);
+      load4_to_lds(lbuf, lse_addr + (i % kLseStages) * (4 * kTile * 4), lane * 4, __builtin_amdgcn_readfirstlane(t * kTile * 4));
     };
-    if (t_first <= t_last) fetch(stA, lseA, t_first);
-    __syncthreads();  // the previous pass has finished with the LDS buffers
-    auto step = [&](Staged<WAVES>& st, float& lse_st, int t) {
-      const int b = (t - t_first) & 1;
-      tile_store(st, lds[b]);
-      if (threadIdx.x < kTile) {
-        lse_s[b][threadIdx.x] = lse_st;
-        if (COUNT) rinv_s[b][threadIdx.x] = 1.0f / static_cast<float>(t * kTile + static_cast<int>(threadIdx.x) + 1);
-      }
+    __syncthreads();  // the previous block has finished with the ring
+    if (0 < n) request(0);
+    if (1 < n) request(1);
+    uint4 own0[kKSteps], own1[kKSteps];
+    load_owned(own0, Kb, kj0, len - 1);
+    load_owned(own1, Kb, kj1, len - 1);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the owned rows are in before the loop (see prefill_rows_mfma)
+    float s1a = 0.0f, s2a = 0.0f, s1b = 0.0f, s2b = 0.0f;
+
+    auto next_tile = [&](int i) {  // the i-th tile has landed; the (i + 2)-th is requested
+      if (COUNT && threadIdx.x < kTile)
+        rinv_s[COUNT ? i % kLseStages : 0][threadIdx.x] =
+            1.0f / static_cast<float>((t_last - i) * kTile + static_cast<int>(threadIdx.x) + 1);
+      if (i + 1 < n) wait_loads<5>();  // the next tile may still be on its way
+      else wait_loads<0>();
       __syncthreads();
-      if (t + 1 <= t_last) fetch(st, lse_st, t + 1);
+      if (i + 2 < n) request(i + 2);
+    };
+    auto plain_tile = [&](int i) {
+      const int t = t_last - i;
+      next_tile(i);
+      const char* p = ring + (i % kRingStages) * kRingTileBytes;
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub) {
         const int ib = t * kTile + sub * 32;
-        const bool do0 = ib + 31 >= kw0, do1 = ib + 31 >= kw0 + 32;  // some query of the tile reaches the keys
+        const bool do0 = ib + 31 >= kg0, do1 = ib + 31 >= kg1;  // some query of the half-tile reaches the keys
         if (!do0) continue;
         f32x16 c0, c1;
-        score_tiles(lds[b], sub, own0, own1, do0, do1, c0, c1);
+        score_tiles_ring(p + sub * (32 * kRowBytes), tr.frag, own0, own1, do0, do1, c0, c1);
         const bool whole = ib + 31 < len;  // no ragged end
-        const float* lt = &lse_s[b][sub * 32];
-        const float* rt = &rinv_s[COUNT ? b : 0][COUNT ? sub * 32 : 0];
-        if (whole && ib >= kw0 + 31 + w) column_update<true, COUNT>(c0, lt, rt, sc, ib, half, kj0, len, w, rb, s1a, s2a);
+        const float* lt = &lse_s[i % kLseStages][wave][sub * 32];
+        const float* rt = &rinv_s[COUNT ? i % kLseStages : 0][COUNT ? sub * 32 : 0];
+        if (whole && ib >= kg0 + 31 + w) column_update<true, COUNT>(c0, lt, rt, sc, ib, half, kj0, len, w, rb, s1a, s2a);
         else column_update<false, COUNT>(c0, lt, rt, sc, ib, half, kj0, len, w, rb, s1a, s2a);
         if (do1) {
-          if (whole && ib >= kw0 + 63 + w) column_update<true, COUNT>(c1, lt, rt, sc, ib, half, kj1, len, w, rb, s1b, s2b);
+          if (whole && ib >= kg1 + 31 + w) column_update<true, COUNT>(c1, lt, rt, sc, ib, half, kj1, len, w, rb, s1b, s2b);
           else column_update<false, COUNT>(c1, lt, rt, sc, ib, half, kj1, len, w, rb, s1b, s2b);
         }
       }
     };
-    for (int t = t_first; t <= t_last; ++t) step(stA, lseA, t);
+
+    int i = 0;
+    while (i < n && (t_last - i) * kTile + kTile - 1 >= len) plain_tile(i++);  // the ragged end of the prompt
+
+    // ---- the rectangle: software-pipelined.  A* hold the scores of a tile's first 32 queries, B* of its last 32.
+    f32x16 A0, A1, B0, B1;
+    bool pending = false;   // B* hold scores that have not been added yet ...
+    int pending_i = 0;      // ... of the tile with this index of the walk
+    // one step: (x0, x1) are filled from the half-tile at p while (y0, y1), the scores of half `ysub` of walk index
+    // `yi`, are turned into probabilities and added to the lane's two keys
+    auto step = [&](auto consume_tag, const char* p, f32x16& x0, f32x16& x1, const f32x16& y0, const f32x16& y1, int yi,
+                    int ysub) {
+      constexpr bool CONSUME = decltype(consume_tag)::value != 0;
+      float4 lv[4], rv[4];
+      if (CONSUME) {
+        const float* lt = &lse_s[yi % kLseStages][wave][ysub * 32 + 4 * half];
+        const float* rt = &rinv_s[COUNT ? yi % kLseStages : 0][COUNT ? ysub * 32 + 4 * half : 0];
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          lv[g4] = *reinterpret_cast<const float4*>(lt + 8 * g4);
+          if (COUNT) rv[g4] = *reinterpret_cast<const float4*>(rt + 8 * g4);
+        }
+      }
+      float a1 = 0.0f, a2 = 0.0f, b1 = 0.0f, b2 = 0.0f, c1 = 0.0f, c2 = 0.0f, d1 = 0.0f, d2 = 0.0f;
+      auto comp = [](const float4& v, int e) { return e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w; };
+      auto one = [&](float s, float lse_q, float rinv_q, float& sum1, float& sum2) {
+        const float pr = fast_exp2(fmaf(s, sc, -lse_q));
+        sum1 += pr;
+        if (COUNT) sum2 += pr > rinv_q ? 1.0f : 0.0f;  // p * (i + 1) > 1
+        else sum2 = fmaf(pr, pr, sum2);
+      };
+      auto consume = [&](int kk, int g) {
+        const int r = 2 * kk;  // scores r and r + 1: queries 8 (r / 4) + 4 half + r % 4 (+ 1) of the half-tile
+        const float la = comp(lv[r >> 2], r & 3), lb = comp(lv[r >> 2], (r & 3) + 1);
+        const float ra = COUNT ? comp(rv[r >> 2], r & 3) : 0.0f, rbq = COUNT ? comp(rv[r >> 2], (r & 3) + 1) : 0.0f;
+        if (g == 0) { one(y0[r], la, ra, a1, a2); one(y0[r + 1], lb, rbq, b1, b2); }
+        else        { one(y1[r], la, ra, c1, c2); one(y1[r + 1], lb, rbq, d1, d2); }
+      };
+      auto pin = [&]() { asm volatile("" : "+v"(a1), "+v"(a2), "+v"(b1), "+v"(b2), "+v"(c1), "+v"(c2), "+v"(d1), "+v"(d2)); };
+      fill_and_consume<CONSUME>(p, tr.frag, own0, own1, x0, x1, consume, pin);
+      if (CONSUME) {
+        s1a += a1 + b1; s2a += a2 + b2;
+        s1b += c1 + d1; s2b += c2 + d2;
+      }
+    };
+    auto rect_tile = [&](auto stage, int ii) {
+      constexpr int S = decltype(stage)::value;
+      next_tile(ii);
+      const char* p = ring + S * kRingTileBytes;
+      if (pending) step(StageTag<1>{}, p, A0, A1, B0, B1, pending_i, 1);
+      else step(StageTag<0>{}, p, A0, A1, B0, B1, 0, 0);
+      step(StageTag<1>{}, p + 32 * kRowBytes, B0, B1, A0, A1, ii, 0);
+      pending = true;
+      pending_i = ii;
+    };
+    auto is_rect = [&](int ii) { return ii < n && t_last - ii >= t_rect_lo; };
+    for (int stage = i % kRingStages;;) {  // the ring stage of a tile follows from its index; the code wants it static
+      if (stage == 0) { if (!is_rect(i)) break; rect_tile(StageTag<0>{}, i++); stage = 1; }
+      if (stage == 1) { if (!is_rect(i)) break; rect_tile(StageTag<1>{}, i++); stage = 2; }
+      if (stage == 2) { if (!is_rect(i)) break; rect_tile(StageTag<2>{}, i++); stage = 0; }
+    }
+    if (pending) {  // drain
+      const float* lt = &lse_s[pending_i % kLseStages][wave][32];
+      const float* rt = &rinv_s[COUNT ? pending_i % kLseStages : 0][COUNT ? 32 : 0];
+      const int ib = (t_last - pending_i) * kTile + 32;
+      column_update<true, COUNT>(B0, lt, rt, sc, ib, half, kj0, len, w, rb, s1a, s2a);
+      column_update<true, COUNT>(B1, lt, rt, sc, ib, half, kj1, len, w, rb, s1b, s2b);
+    }
+    // ---- the tiles on the diagonal (or inside a recency window)
+    while (i < n) plain_tile(i++);
+
     s1a += __shfl_xor(s1a, 32, kWave);
     s2a += __shfl_xor(s2a, 32, kWave);
     s1b += __shfl_xor(s1b, 32, kWave);
@@ -995,7 +1169,7 @@ hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
   const dim3 rows_grid(static_cast<unsigned>((a.units * a.group + 7) / 8 * 8 * b.pairs * b.ksplit));  // one id set per query head
   if (!a.skip_rows) {
     ProfScope ps(kProfPrefillRows, s);
-    hipLaunchKernelGGL(prefill_rows_mfma<WAVES>, rows_grid, dim3(WAVES * kWave), 0, s, b);
+    hipLaunchKernelGGL(prefill_rows_mfma, rows_grid, dim3(WAVES * kWave), 0, s, b);
     if (b.ksplit > 1)
       hipLaunchKernelGGL(merge_key_shares, dim3((a.L_max + 255) / 256, a.units), dim3(256), 0, s, b);
   }
@@ -1003,8 +1177,8 @@ hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
     ProfScope ps(kProfPrefillColumns, s);
     if (a.group != 1) launch_columns_grouped<WAVES>(b, grid, s);
     else if (a.pol.counts_above_average())
-      hipLaunchKernelGGL((prefill_columns_mfma<WAVES, true>), grid, dim3(WAVES * kWave), 0, s, b);
-    else hipLaunchKernelGGL((prefill_columns_mfma<WAVES, false>), grid, dim3(WAVES * kWave), 0, s, b);
+      hipLaunchKernelGGL(prefill_columns_mfma<true>, grid, dim3(WAVES * kWave), 0, s, b);
+    else hipLaunchKernelGGL(prefill_columns_mfma<false>, grid, dim3(WAVES * kWave), 0, s, b);
     if (b.qsplit > 1)
       hipLaunchKernelGGL(sum_query_shares, dim3((a.L_max + 255) / 256, a.units), dim3(256), 0, s, b);
   }
@@ -1042,8 +1216,8 @@ hipError_t launch_with_output(const PrefillArgs& a, hipStream_t s) {
     ProfScope ps(kProfPrefillColumns, s);
     const dim3 cgrid(static_cast<unsigned>((a.units + 7) / 8 * 8 * c.pairs * c.qsplit));
     if (a.group != 1) launch_columns_grouped<4>(c, cgrid, s);
-    else if (a.pol.counts_above_average()) hipLaunchKernelGGL((prefill_columns_mfma<4, true>), cgrid, dim3(4 * kWave), 0, s, c);
-    else hipLaunchKernelGGL((prefill_columns_mfma<4, false>), cgrid, dim3(4 * kWave), 0, s, c);
+    else if (a.pol.counts_above_average()) hipLaunchKernelGGL(prefill_columns_mfma<true>, cgrid, dim3(4 * kWave), 0, s, c);
+    else hipLaunchKernelGGL(prefill_columns_mfma<false>, cgrid, dim3(4 * kWave), 0, s, c);
     if (c.qsplit > 1)
       hipLaunchKernelGGL(sum_query_shares, dim3((a.L_max + 255) / 256, a.units), dim3(256), 0, s, c);
   }
@@ -1062,9 +1236,9 @@ hipError_t launch_mfma_probe(int workgroups, int iters, bool random_operands, fl
 
 hipError_t launch_prefill_attention_mfma(const PrefillArgs& a, hipStream_t s) {
   if (a.O != nullptr) return launch_with_output(a, s);
-  // 256 owned rows per workgroup by default.  512 halve the streamed traffic but leave one workgroup per
-  // compute unit, all of whose waves wait at the same barriers; measured slower on the serving workload.
-  return a.mfma_waves == 8 ? launch_t<8>(a, s) : launch_t<4>(a, s);
+  // 256 owned rows per workgroup (512 halved the streamed traffic but left one workgroup per compute unit, all of
+  // whose waves wait at the same barriers: measured slower on the serving workload).
+  return launch_t<4>(a, s);
 }
 
 }  // namespace roco

@@ -28,10 +28,35 @@ import numpy as np  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix peak
-# HBM-side bytes of one decode_attend launch on this workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a
-# plain copy of known size (profiles/decode_prefill_workload3_rocprofv3.txt); only valid for the default shape.
-ATTEND_TRAFFIC_BYTES = 543662034
-FUSED_TRAFFIC_BYTES = 563437192  # decode_fused (the shape the step takes on this workload): see the same file
+ALU_SLOTS_PER_MFMA = {"rows": 9, "columns": 11}  # issue slots per matrix instruction, see alu_cobound_tflops
+
+
+def alu_cobound_tflops(which):
+    """What the vector ALU allows the prefill passes, as a matrix rate.  A 32x32x16 matrix instruction produces two
+    scores per lane and occupies the matrix pipe of its SIMD for 32 cycles; a SIMD issues one vector instruction of a
+    wave per 4 cycles (64 lanes on 16 lanes per clock: 64 fp32 lanes per clock and compute unit), and the exponential
+    takes two such slots.  Per score the row pass needs multiply-add + exponential + add = 4 slots, the column pass
+    one multiply-add more = 5; with the matrix instruction's own slot that is 9 / 11 slots = 36 / 44 cycles per matrix
+    instruction against 32: 0.89 / 0.73 of the matrix peak, however the two kinds are interleaved."""
+    return MFMA_BF16_PEAK_TFLOPS * 32.0 / (4.0 * ALU_SLOTS_PER_MFMA[which])
+
+
+def measured_traffic(kernel, workload):
+    """HBM-side bytes per launch of `kernel` on `workload`, as rocprofv3 counted them: the TRAFFIC lines of the
+    summaries under profiles/ (each names the kernel, the workload and the commit it was measured at).  None when no
+    line matches: the figure is never carried over to another kernel or shape."""
+    import glob
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
+        with open(path) as f:
+            for line in f:
+                if not line.startswith("TRAFFIC "):
+                    continue
+                rec = dict(kv.split("=", 1) for kv in line.split()[1:])
+                if rec.get("kernel") == kernel and rec.get("workload") == str(workload):
+                    return {"bytes": int(rec["fetch_bytes"]) + int(rec["write_bytes"]), "fetch_bytes": int(rec["fetch_bytes"]),
+                            "write_bytes": int(rec["write_bytes"]), "kernel": kernel, "measured_at_commit": rec.get("commit"),
+                            "source": os.path.relpath(path, ROOT)}
+    return None
 
 
 def generate(cfg, seed, workers):
@@ -94,6 +119,142 @@ def cpu_baseline(cfg, Q, K, V, decode_steps, n_units, n_steps):
     }
 
 
+def _decode_loop(torch, roco, p, cache, sq, sk, sv, qpos, out, ev_slot, ev_pos, ws, stream):
+    """A function that runs all decode steps of [steps, units, d] inputs through roco_decode_step (addresses worked out
+    once, plain integers into the C entry point: the loop is launch-rate sensitive)."""
+    import ctypes
+    lib = roco.load_library()
+    steps, U, d = sq.shape
+    esz = sq.element_size()
+    row = U * d * esz
+    pref = ctypes.byref(p)
+    c = [x.data_ptr() for x in (cache.K, cache.V, cache.stats, cache.pos, cache.n_used, cache.next_slot)]
+    args = [(sq.data_ptr() + t * row, sk.data_ptr() + t * row, sv.data_ptr() + t * row, qpos.data_ptr() + t * U * 4)
+            for t in range(steps)]
+    o, es, ep, w, wb, st = out.data_ptr(), ev_slot.data_ptr(), ev_pos.data_ptr(), ws.data_ptr(), ws.numel(), stream.cuda_stream
+
+    def run():
+        for a in args:
+            rc = lib.roco_decode_step(pref, a[0], a[1], a[2], a[3], c[0], c[1], c[2], c[3], c[4], c[5], o, es, ep, w, wb, st)
+            if rc != 0:
+                raise roco.RocoError(rc, "roco_decode_step")
+    return run
+
+
+def _timed(torch, stream, fn, reps=1):
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(reps):
+        fn()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def side_workloads(torch, roco, seed, which):
+    """Throughput of the other benchmark workloads (1, 2, 4, 5), each with the roofline that bounds it: MFMA for the
+    prompt passes, HBM for the decode step where the step's working set is far larger than the 256 MB last-level cache
+    (workload 4), no bandwidth claim where it fits (workload 5) or where a step is launch latency (workload 1)."""
+    from inputs import CONFIGS, make_unit, unit_ids
+    from inputs.device import make_layer_on_device
+    stream = torch.cuda.current_stream()
+    res = {}
+    for idx in which:
+        cfg = CONFIGS[idx - 1]
+        L, B, s, d, steps = cfg.prompt_len, cfg.budget, cfg.scope, cfg.head_dim, cfg.steps
+        dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        esz = 2 if cfg.dtype == "bf16" else 4
+        rdt = roco.ROCO_BF16 if cfg.dtype == "bf16" else roco.ROCO_F32
+        per_layer = cfg.batch * cfg.heads
+        U = cfg.units
+        p = roco.RocoParams(U, d, B, s, rdt, 0.0, cfg.recency_window, cfg.recency_bias)
+        lp = roco.RocoParams(per_layer, d, B, s, rdt, 0.0, cfg.recency_window, cfg.recency_bias)
+        cache = roco.alloc_cache(p)
+        ws_p = torch.empty(roco.prefill_workspace_bytes(lp, L), dtype=torch.uint8, device="cuda")
+        dlen = torch.full((per_layer,), L, dtype=torch.int32, device="cuda")
+        sq = torch.empty((max(steps, 1), U, d), dtype=dt, device="cuda")
+        sk, sv = torch.empty_like(sq), torch.empty_like(sq)
+        prefill_ms = 0.0
+        for layer in range(cfg.layers):  # the prompt pass runs layer by layer, as a model would call it
+            if idx >= 4:  # drawn on the device: the host generator would need minutes
+                Qd, Kd, Vd, _ = make_layer_on_device(cfg, layer, seed=seed)
+            else:
+                units = [make_unit(cfg, *i, seed=seed) for i in unit_ids(cfg)]
+                Qd, Kd, Vd = (upload(np.stack([getattr(u_, n_) for u_ in units]), torch, dt) for n_ in ("Q", "K", "V"))
+            lo, hi = layer * per_layer, (layer + 1) * per_layer
+            dQ, dK, dV = (x[:, :L].contiguous() for x in (Qd, Kd, Vd))
+            if steps:
+                for x, dst in ((Qd, sq), (Kd, sk), (Vd, sv)):
+                    dst[:, lo:hi] = x[:, L:L + steps].transpose(0, 1)
+            del Qd, Kd, Vd
+
+            def prefill():
+                roco.roco_prefill_compress(lp, dQ, dK, dV, dlen, L, cache.K[lo:hi], cache.V[lo:hi], cache.stats[lo:hi],
+                                           cache.pos[lo:hi], cache.n_used[lo:hi], cache.next_slot[lo:hi], None, ws_p, stream=stream)
+            prefill()  # warm-up
+            torch.cuda.synchronize()
+            prefill_ms += _timed(torch, stream, prefill, 3 if cfg.layers > 1 else 5)
+            del dQ, dK, dV
+        flops = U * 2 * d * L * (L + 1)
+        tf = flops / (prefill_ms * 1e-3) / 1e12
+        r = {"workload": f"config {idx}: {cfg.layers} layer(s) x batch {cfg.batch} x {cfg.heads} heads x {d} dims {cfg.dtype}, "
+                         f"prompt {L} -> B={B}, scope {s}, {steps} decode steps", "units": U,
+             "prefill_ms": prefill_ms, "prefill_evict_tokens_per_s": cfg.batch * L / (prefill_ms * 1e-3)}
+        if cfg.dtype == "bf16" and d == 128:
+            r["roofline_prefill"] = {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                     "frac": tf / MFMA_BF16_PEAK_TFLOPS, "flops": flops}
+        else:
+            r["roofline_prefill"] = {"bound": "alu", "achieved": tf, "peak": None, "unit": "TFLOP/s", "frac": None,
+                                     "note": "fp32 / head_dim 64 takes the vector-ALU passes; 4 units: latency, no claim"}
+        if steps:
+            qpos = (torch.arange(steps, dtype=torch.int32, device="cuda")[:, None] + L).expand(steps, U).contiguous()
+            out = torch.empty((U, d), dtype=dt, device="cuda")
+            ev_slot = torch.empty((U,), dtype=torch.int32, device="cuda")
+            ev_pos = torch.empty_like(ev_slot)
+            snap = [t.clone() for t in (cache.K, cache.V, cache.stats, cache.pos, cache.n_used, cache.next_slot)]
+            step_bytes = U * B * (2 * d * esz + 24)
+            by_scope = {}
+            for scope in (cfg.scope_sweep or (s,)):
+                ps = roco.RocoParams(U, d, B, scope, rdt, 0.0, cfg.recency_window, cfg.recency_bias)
+                ws_d = torch.empty(max(16, roco.decode_workspace_bytes(ps)), dtype=torch.uint8, device="cuda")
+                run = _decode_loop(torch, roco, ps, cache, sq, sk, sv, qpos, out, ev_slot, ev_pos, ws_d, stream)
+                best = None
+                for rep in range(2):
+                    for t, sn in zip((cache.K, cache.V, cache.stats, cache.pos, cache.n_used, cache.next_slot), snap):
+                        t.copy_(sn)
+                    if scope != s:
+                        roco.roco_select_victims(ps, cache.stats, cache.pos, cache.n_used, cache.next_slot, ws_d, stream=stream)
+                    torch.cuda.synchronize()
+                    ms = _timed(torch, stream, run)
+                    best = ms if best is None else min(best, ms)
+                assert int(cache.n_used.min()) == B and int((ev_slot >= 0).sum()) == U
+                by_scope[str(scope)] = {"ms_per_token_step": best / steps, "tokens_per_s": cfg.batch * steps / (best * 1e-3),
+                                        "step_GBps": step_bytes / (best * 1e-3 / steps) / 1e9,
+                                        "launches_per_step": roco.decode_step_launches(ps)}
+                del ws_d
+            main_scope = by_scope[str(s)]
+            r["decode_ms_per_token_step"] = main_scope["ms_per_token_step"]
+            r["decode_tokens_per_s"] = main_scope["tokens_per_s"]
+            if len(by_scope) > 1:
+                r["decode_by_scope"] = by_scope
+            cache_bytes = U * B * 2 * d * esz
+            if cache_bytes > (1 << 30):  # far beyond the last-level cache: an HBM figure means something
+                r["roofline_decode_step"] = {"bound": "hbm", "achieved": main_scope["step_GBps"], "peak": HBM_PEAK_GBS,
+                                             "unit": "GB/s", "frac": main_scope["step_GBps"] / HBM_PEAK_GBS,
+                                             "bytes_per_step": step_bytes}
+            else:
+                why = ("fits the 256 MB last-level cache: no HBM claim" if cache_bytes > (8 << 20)
+                       else "a step is launch latency: no bandwidth claim")
+                r["roofline_decode_step"] = {"bound": "hbm", "achieved": main_scope["step_GBps"], "peak": HBM_PEAK_GBS,
+                                             "unit": "GB/s", "frac": None, "bytes_per_step": step_bytes,
+                                             "note": f"{cache_bytes / 2**20:.1f} MiB of K and V per step {why}"}
+            del snap, qpos
+        res[str(idx)] = r
+        del cache, ws_p, sq, sk, sv
+        torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -109,6 +270,8 @@ def main():
     ap.add_argument("--no-two-streams", action="store_true",
                     help="skip the decode loop with the batch split over two HIP streams")
     ap.add_argument("--no-consistency", action="store_true", help="skip the synthetic consistency study")
+    ap.add_argument("--workloads", default="1,2,4,5",
+                    help="the other benchmark workloads to time beside the headline one (comma separated; '' = none)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 512 MiB device copy (a kernel of known traffic, to scale rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -221,6 +384,7 @@ def main():
     step_bytes = U * B * (2 * d * esz + 24)
     attend_bytes = step_bytes if fused else U * B * 2 * d * esz
     attend_name = "decode_fused" if fused else "decode_attend"
+    traffic = measured_traffic(attend_name, 3) if (U == 512 and decode_steps > 0) else None
     attend_avg_s = attend_ms * 1e-3 / max(1, attend_n)
     # prefill statistics: two causal QK^T passes (row normalisers, then column statistics), 2 flops per MAC
     prefill_flops = U * 2 * d * L * (L + 1) * (1.5 if args.with_out else 1.0)
@@ -350,6 +514,20 @@ def main():
         ms, n = roco.roco_profile_read()
         mfma_ceiling[random_operands] = probe_flops / (ms * 1e-3) / 1e12
     mfma_ceiling_tflops = mfma_ceiling[True]
+    # ... and the ceiling of each pass's own instruction mix: the steady state of its pipelined form (matrix
+    # instructions, fragment reads, the vector work per score) with no global loads, barriers or masks
+    mix_ceiling = {}
+    for which, mix in (("rows", 1), ("columns", 2)):
+        probe_flops = 0
+        for k in range(5):
+            if k == 1:
+                torch.cuda.synchronize()
+                roco.roco_profile_read()
+                probe_flops = 0
+            probe_flops += roco.roco_probe_mfma(2048, 512, sink, stream=stream, mix=mix)
+        torch.cuda.synchronize()
+        ms, n = roco.roco_profile_read()
+        mix_ceiling[which] = probe_flops / (ms * 1e-3) / 1e12
     # prefill repeated on its own: median and minimum of 10
     reps = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(10)]
     roco.roco_profile_kernel(-1)
@@ -467,7 +645,7 @@ def main():
         "roofline": {"kernel": attend_name, "bound": "hbm", "achieved": attend_bytes / attend_avg_s / 1e9,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": attend_bytes / attend_avg_s / 1e9 / HBM_PEAK_GBS,
-                     "traffic": (FUSED_TRAFFIC_BYTES if fused else ATTEND_TRAFFIC_BYTES) if U == 512 else None,
+                     "traffic": (traffic or {}).get("bytes"), "traffic_source": traffic,
                      "bytes_per_launch": attend_bytes, "avg_launch_ms": attend_avg_s * 1e3, "launches": attend_n,
                      "measured_read_ceiling_GBps": U * B * 2 * d * esz / probe_alone_s / 1e9,
                      "frac_of_measured_ceiling": attend_bytes / attend_avg_s / (U * B * 2 * d * esz / probe_alone_s)},
@@ -487,6 +665,19 @@ def main():
                              "frac_of_measured_ceiling": prefill_flops / (prefill_ms * 1e-3 / args.steps) / 1e12
                              / mfma_ceiling_tflops,
                              "prefill_ms_median_of_10": rep_ms[len(rep_ms) // 2], "prefill_ms_min_of_10": rep_ms[0]},
+        "roofline_prefill_kernels": {
+            which: {"kernel": kname, "bound": "alu", "avg_launch_ms": pre_kernel_ms[key],
+                    "achieved": prefill_flops / 2 / (pre_kernel_ms[key] * 1e-3) / 1e12, "unit": "TFLOP/s",
+                    "peak": alu_cobound_tflops(which),
+                    "frac": prefill_flops / 2 / (pre_kernel_ms[key] * 1e-3) / 1e12 / alu_cobound_tflops(which),
+                    "frac_of_mfma_peak": prefill_flops / 2 / (pre_kernel_ms[key] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                    "measured_mix_ceiling_TFLOPs": mix_ceiling[which],
+                    "frac_of_measured_mix_ceiling": prefill_flops / 2 / (pre_kernel_ms[key] * 1e-3) / 1e12 / mix_ceiling[which],
+                    "traffic": (measured_traffic(kname, 3) or {}).get("bytes") if U == 512 else None,
+                    "traffic_source": measured_traffic(kname, 3) if U == 512 else None,
+                    "algorithmic_bytes": 2 * U * L * d * esz}
+            for which, kname, key in (("rows", "prefill_rows_mfma", "prefill_rows"), ("columns", "prefill_columns_mfma", "prefill_columns"))
+        } if not args.with_out else None,
         "kernel_ms": {**dec_kernel_ms, **pre_kernel_ms},
         "input_generation_s": t_gen,
     }
@@ -514,6 +705,11 @@ def main():
             "jaccard_vs_full_cache": {k_: {str(r_): round(v_[0], 4) for r_, v_ in d_.items()} for k_, d_ in study.items()},
             "seconds": round(time.perf_counter() - t0c, 2)}
         del cq, ck, cv
+    which = [int(x) for x in args.workloads.split(",") if x.strip()]
+    if which:
+        del dQ, dK, dV, sq, sk, sv, out, cache
+        torch.cuda.empty_cache()
+        result["workloads"] = side_workloads(torch, roco, args.seed, which)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, Q, K, V, decode_steps, args.cpu_units, args.cpu_steps)
     print(json.dumps(result), flush=True)

@@ -309,6 +309,19 @@ int roco_select_retained(const roco_params* params, int32_t keep, const float* s
                          void* hip_stream);
 
 /*
+ * Overlap of two sets of cached tokens per unit: the two counts behind the Jaccard similarity |A and B| / |A or B| of
+ * the consistency study (section 4.1, Fig. 2: the tokens a budgeted cache holds against the top-B tokens of the full
+ * cache).  Set A of unit u holds the positions pos_a[u][j] of the slots j < n_used_a[u] whose mask_a[u][j] is not 0
+ * (mask_a NULL: all of those slots); set B likewise.  Positions outside [0, max_pos) are ignored; positions inside one
+ * cache are distinct.
+ * pos_a, mask_a in [units, slots_a] int32; n_used_a in [units]; pos_b, mask_b in [units, slots_b]; n_used_b in [units];
+ * inter, uni out [units] int32.  max_pos <= 524288 (else ROCO_EUNSUPPORTED).  No workspace.
+ */
+int roco_set_overlap(int32_t units, int32_t slots_a, const int32_t* pos_a, const int32_t* mask_a, const int32_t* n_used_a,
+                     int32_t slots_b, const int32_t* pos_b, const int32_t* mask_b, const int32_t* n_used_b,
+                     int32_t max_pos, int32_t* inter, int32_t* uni, void* hip_stream);
+
+/*
  * Profiling aid (not part of the method; for benchmarks).  roco_profile_kernel(k) makes every later call
  * record a pair of HIP events on the caller's stream around kernel k only (k = one of ROCO_PROF_*; -1 turns
  * it off).  roco_profile_read() waits for the recorded events, returns their summed elapsed time in
@@ -344,11 +357,19 @@ int roco_probe_cache_read(const roco_params* params, const void* K_cache, const 
  * included).  `operands`: ROCO_PROBE_CONSTANT_OPERANDS = one operand pair holding a few small values;
  * ROCO_PROBE_RANDOM_OPERANDS = eight operand pairs of pseudo-random values in (-2, 2), whose bit activity is that of
  * real activations (the matrix units draw more power and the sustained clock is lower).  Flops of one call =
- * workgroups * 4 * iters * 8 * 32768.  sink out [workgroups * 256] fp32 (device): receives a checksum per lane.
+ * workgroups * 4 * iters * 8 * 32768.
+ * ROCO_PROBE_ROW_PASS_MIX / ROCO_PROBE_COLUMN_PASS_MIX: the steady state of the row / column pass instead -- per
+ * wave `iters` tiles of 32 matrix instructions on pseudo-random values, interleaved as in the passes with the 16
+ * fragment reads from an LDS tile (which the workgroup fills itself) and the pass's vector work per score (multiply-
+ * add, exponential, add; the column pass one multiply-add more and the row normalisers from LDS), with no global
+ * loads, barriers or masks: the ceiling of the passes' instruction mix.  Flops = workgroups * 4 * iters * 32 * 32768.
+ * sink out [workgroups * 256] fp32 (device): receives a checksum per lane.
  * 1 <= workgroups <= 1048576, 1 <= iters <= 1048576.
  */
 #define ROCO_PROBE_CONSTANT_OPERANDS 0
 #define ROCO_PROBE_RANDOM_OPERANDS 1
+#define ROCO_PROBE_ROW_PASS_MIX 2
+#define ROCO_PROBE_COLUMN_PASS_MIX 3
 int roco_probe_mfma(int32_t workgroups, int32_t iters, int32_t operands, float* sink, size_t sink_bytes,
                     void* hip_stream);
 

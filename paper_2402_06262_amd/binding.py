@@ -102,6 +102,8 @@ def load_library() -> ctypes.CDLL:
     lib.roco_select_victims.argtypes = [pp, vp, vp, vp, vp, vp, sz, vp]
     lib.roco_select_retained.restype = ctypes.c_int
     lib.roco_select_retained.argtypes = [pp, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.roco_set_overlap.restype = ctypes.c_int
+    lib.roco_set_overlap.argtypes = [i32, i32, vp, vp, vp, i32, vp, vp, vp, i32, vp, vp, vp]
     lib.roco_strerror.restype = ctypes.c_char_p
     lib.roco_strerror.argtypes = [ctypes.c_int]
     lib.roco_version.restype = ctypes.c_int
@@ -314,13 +316,24 @@ def roco_probe_cache_read(params: RocoParams, K_cache, V_cache, workspace, works
         raise RocoError(rc, "roco_probe_cache_read")
 
 
-def roco_probe_mfma(workgroups: int, iters: int, sink, stream=None, random_operands: bool = False) -> int:
-    """See include/roco.h: a loop of the prefill passes' matrix instruction (benchmark aid).  Returns the flops."""
-    rc = load_library().roco_probe_mfma(int(workgroups), int(iters), 1 if random_operands else 0, _ptr(sink),
+def roco_probe_mfma(workgroups: int, iters: int, sink, stream=None, random_operands: bool = False, mix: int = 0) -> int:
+    """See include/roco.h: a loop of the prefill passes' matrix instruction, or (mix = 1 row pass, 2 column pass) the
+    steady state of a pass's instruction mix (benchmark aid).  Returns the flops of the call."""
+    mode = (1 + int(mix)) if mix else (1 if random_operands else 0)
+    rc = load_library().roco_probe_mfma(int(workgroups), int(iters), mode, _ptr(sink),
                                         sink.numel() * sink.element_size(), _stream(stream))
     if rc != 0:
         raise RocoError(rc, "roco_probe_mfma")
-    return int(workgroups) * 4 * int(iters) * 8 * 32768
+    return int(workgroups) * 4 * int(iters) * (32 if mix else 8) * 32768
+
+
+def roco_set_overlap(pos_a, mask_a, n_used_a, pos_b, mask_b, n_used_b, max_pos: int, inter, uni, stream=None) -> None:
+    """See include/roco.h: |A and B| and |A or B| per unit of two sets of cached positions (masks may be None)."""
+    rc = load_library().roco_set_overlap(int(pos_a.shape[0]), int(pos_a.shape[1]), _ptr(pos_a), _ptr(mask_a), _ptr(n_used_a),
+                                         int(pos_b.shape[1]), _ptr(pos_b), _ptr(mask_b), _ptr(n_used_b), int(max_pos),
+                                         _ptr(inter), _ptr(uni), _stream(stream))
+    if rc != 0:
+        raise RocoError(rc, "roco_set_overlap")
 
 
 def roco_select_victims(params: RocoParams, stats, pos, n_used, next_slot, workspace,

@@ -6,8 +6,8 @@ its own B slots received), and the B most important tokens when the full cache i
 t + 1 tokens, from a run that never evicts).  The paper sets the local window to 0, i.e. the scope is the whole
 cache, and averages over positions, heads and layers; here the average runs over positions and units.
 
-Everything the method computes (attention, statistics, evictions, the top-B selection) runs in the library's
-kernels; this module only steps the two caches side by side and counts set overlaps with torch bitmaps.
+Everything the method computes (attention, statistics, evictions, the top-B selection, the overlap of the two sets)
+runs in the library's kernels; this module only steps the two caches side by side and averages the ratios.
 """
 from __future__ import annotations
 
@@ -41,15 +41,6 @@ class _Run:
         c = self.cache
         roco.roco_decode_step(self.p, q, k, v, qpos, c.K, c.V, c.stats, c.pos, c.n_used, c.next_slot, self.out, None,
                               None, self.ws_d)
-
-
-def _bitmap(torch, pos, valid, T):
-    """[units, T] bool: which positions the slots flagged `valid` hold."""
-    U = pos.shape[0]
-    bm = torch.zeros((U, T + 1), dtype=torch.bool, device=pos.device)
-    idx = torch.where(valid, pos.long(), torch.full_like(pos, T).long())  # invalid slots land in a spare column
-    bm.scatter_(1, idx, True)
-    return bm[:, :T]
 
 
 def consistency_study(Q, K, V, prompt_len: int, rates: Sequence[float] = (0.3, 0.4, 0.5, 0.6),
@@ -90,6 +81,8 @@ def consistency_study(Q, K, V, prompt_len: int, rates: Sequence[float] = (0.3, 0
     total = {key: 0.0 for key in runs}
     count = {key: 0 for key in runs}
     mask = torch.empty((U, T), dtype=torch.int32, device="cuda")
+    inter = torch.empty((U,), dtype=torch.int32, device="cuda")
+    union = torch.empty((U,), dtype=torch.int32, device="cuda")
     for i, t in enumerate(range(L, T)):
         q, k, v, qpos = steps[i]
         for full in fulls.values():
@@ -106,13 +99,10 @@ def consistency_study(Q, K, V, prompt_len: int, rates: Sequence[float] = (0.3, 0
                 continue  # nothing has been evicted yet: the two sets are trivially equal
             sel = roco.RocoParams(U, d, T, T, dt, importance=IMPORTANCE[name], scope_kind=roco.ROCO_SCOPE_ALL, sinks=sinks)
             roco.roco_select_retained(sel, B, fc.stats, fc.pos, fc.n_used, mask, full.ws_d)
-            top_full = _bitmap(torch, fc.pos, mask.bool(), T)
             c = run.cache
-            slots = torch.arange(c.pos.shape[1], device="cuda")[None, :] < c.n_used[:, None]
-            held = _bitmap(torch, c.pos, slots, T)
-            inter = (top_full & held).sum(1).double()
-            union = (top_full | held).sum(1).double()
-            total[(name, r)] += float((inter / union).sum())
+            roco.roco_set_overlap(fc.pos, mask, fc.n_used, c.pos, None, c.n_used, T, inter, union)
+            i_h, u_h = inter.cpu().numpy(), union.cpu().numpy()  # the report: mean ratio over units and positions
+            total[(name, r)] += float((i_h / u_h).sum())
             count[(name, r)] += U
     torch.cuda.synchronize()
     out: Dict[str, Dict[float, Tuple[float, int]]] = {}

@@ -452,6 +452,20 @@ int roco_select_retained(const roco_params* params, int32_t keep, const float* s
   return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
 }
 
+int roco_set_overlap(int32_t units, int32_t slots_a, const int32_t* pos_a, const int32_t* mask_a, const int32_t* n_used_a,
+                     int32_t slots_b, const int32_t* pos_b, const int32_t* mask_b, const int32_t* n_used_b,
+                     int32_t max_pos, int32_t* inter, int32_t* uni, void* hip_stream) {
+  if (units < 1 || slots_a < 1 || slots_b < 1 || max_pos < 1) return ROCO_EINVAL;
+  if (units > 65535 || max_pos > (1 << 19)) return ROCO_EUNSUPPORTED;  // the bitmap of a unit sits in 64 KiB of LDS
+  const void* need[] = {pos_a, n_used_a, pos_b, n_used_b, inter, uni};
+  for (const void* ptr : need)
+    if (ptr == nullptr || !aligned16(ptr)) return ROCO_EINVAL;
+  if ((mask_a != nullptr && !aligned16(mask_a)) || (mask_b != nullptr && !aligned16(mask_b))) return ROCO_EINVAL;
+  const hipError_t e = launch_set_overlap(units, slots_a, pos_a, mask_a, n_used_a, slots_b, pos_b, mask_b, n_used_b,
+                                          max_pos, inter, uni, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
+}
+
 int roco_select_victims(const roco_params* params, const float* stats, const int32_t* pos, const int32_t* n_used,
                         int32_t* next_slot, void* workspace, size_t workspace_bytes, void* hip_stream) {
   const int rc = check_params(params);
@@ -496,10 +510,10 @@ int roco_probe_cache_read(const roco_params* params, const void* K_cache, const 
 int roco_probe_mfma(int32_t workgroups, int32_t iters, int32_t operands, float* sink, size_t sink_bytes,
                     void* hip_stream) {
   if (workgroups < 1 || workgroups > (1 << 20) || iters < 1 || iters > (1 << 20)) return ROCO_EINVAL;
-  if (operands != ROCO_PROBE_CONSTANT_OPERANDS && operands != ROCO_PROBE_RANDOM_OPERANDS) return ROCO_EINVAL;
+  if (operands < ROCO_PROBE_CONSTANT_OPERANDS || operands > ROCO_PROBE_COLUMN_PASS_MIX) return ROCO_EINVAL;
   if (sink == nullptr || !aligned16(sink)) return ROCO_EINVAL;
   if (sink_bytes < static_cast<size_t>(workgroups) * 256 * sizeof(float)) return ROCO_EWORKSPACE;
-  const hipError_t e = launch_mfma_probe(workgroups, iters, operands == ROCO_PROBE_RANDOM_OPERANDS, sink, static_cast<hipStream_t>(hip_stream));
+  const hipError_t e = launch_mfma_probe(workgroups, iters, operands, sink, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? ROCO_OK : ROCO_EHIP;
 }
 

@@ -135,10 +135,14 @@ hipError_t launch_block(int dtype, int head_dim, const BlockArgs& a, hipStream_t
 hipError_t launch_decode(int dtype, int head_dim, const DecodeArgs& a, hipStream_t s);
 int decode_rows_per_pass(int dtype, int head_dim, int unroll);  // granularity of DecodeArgs::rows_per_split
 hipError_t launch_cache_read_probe(int dtype, int head_dim, const DecodeArgs& a, hipStream_t s);
-hipError_t launch_mfma_probe(int workgroups, int iters, bool random_operands, float* sink, hipStream_t s);
+hipError_t launch_mfma_probe(int workgroups, int iters, int mode, float* sink, hipStream_t s);  // mode: ROCO_PROBE_*
 hipError_t launch_select_victims(const DecodeArgs& a, hipStream_t s);
 // uses stats, pos, n_used, keys; writes mask[units][B] (1 = survives a shrink of the unit to `keep` tokens)
 hipError_t launch_select_retained(const DecodeArgs& a, int keep, int32_t* mask, hipStream_t s);  // uses stats, n_used, next_slot, keys
+// |A and B| and |A or B| per unit of two sets of cached positions in [0, max_pos), max_pos <= 524288
+hipError_t launch_set_overlap(int units, int slots_a, const int32_t* pos_a, const int32_t* mask_a, const int32_t* n_a,
+                              int slots_b, const int32_t* pos_b, const int32_t* mask_b, const int32_t* n_b, int max_pos,
+                              int32_t* inter, int32_t* uni, hipStream_t s);
 hipError_t launch_prefill_attention_simple(int dtype, int head_dim, const PrefillArgs& a, hipStream_t s);
 hipError_t launch_prefill_attention_mfma(const PrefillArgs& a, hipStream_t s);  // bf16, head_dim 128
 // overwrites PrefillArgs::acc2 with the attention row of each unit's last prompt token (kImpLast)

@@ -1135,6 +1135,89 @@ __global__ __launch_bounds__(256) void mfma_probe(int iters, float* sink) {
   sink[static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x] = sum;
 }
 
+// Benchmark aid: the steady state of the two passes' software-pipelined form and nothing around it.  A workgroup
+// fills one LDS tile with pseudo-random values itself, then every wave runs `tiles` times the four steps of a
+// tile (32 matrix instructions, their 16 fragment reads, and the pass's vector work on the 2048 scores of the two
+// half-tiles before: PASS 1 = multiply-add, exponential, add per score; PASS 2 = one more multiply-add and the
+// row normalisers read from LDS) -- no global loads, no barriers, no masks.  What this reaches is the ceiling of
+// the passes' instruction mix on the machine at hand, its clock under that load included.
+template <int PASS>
+__global__ __launch_bounds__(256, 2) void prefill_mix_probe(int tiles, float* sink) {
+  __shared__ __attribute__((aligned(1024))) char tile[kRingTileBytes];
+  __shared__ __attribute__((aligned(16))) float lse_s[kTile];
+  const int lane = threadIdx.x & (kWave - 1), half = lane >> 5;
+  auto rnd = [&](uint32_t i) {
+    uint32_t h = i * 0x9e3779b9u + blockIdx.x * 7919u;
+    h ^= h >> 16; h *= 0x7feb352du; h ^= h >> 15; h *= 0x846ca68bu; h ^= h >> 16;
+    return h;
+  };
+  for (int i = threadIdx.x; i < kRingTileBytes / 4; i += 256) {  // two bf16 values in (-2, 2) per word
+    const uint32_t h = rnd(i);
+    const float lo = (static_cast<int>(h & 0xffffu) - 32768) * (1.0f / 16384.0f);
+    const float hi = (static_cast<int>(h >> 16) - 32768) * (1.0f / 16384.0f);
+    reinterpret_cast<uint32_t*>(tile)[i] = f32_to_bf16(lo) | (static_cast<uint32_t>(f32_to_bf16(hi)) << 16);
+  }
+  if (threadIdx.x < kTile) lse_s[threadIdx.x] = 40.0f + 0.01f * threadIdx.x;
+  uint4 own0[kKSteps], own1[kKSteps];
+#pragma unroll
+  for (int kk = 0; kk < kKSteps; ++kk) {
+    own0[kk] = make_uint4(rnd(threadIdx.x * 64 + kk * 8) & 0xbfffbfffu, rnd(threadIdx.x * 64 + kk * 8 + 1) & 0xbfffbfffu,
+                          rnd(threadIdx.x * 64 + kk * 8 + 2) & 0xbfffbfffu, rnd(threadIdx.x * 64 + kk * 8 + 3) & 0xbfffbfffu);
+    own1[kk] = make_uint4(rnd(threadIdx.x * 64 + kk * 8 + 4) & 0xbfffbfffu, rnd(threadIdx.x * 64 + kk * 8 + 5) & 0xbfffbfffu,
+                          rnd(threadIdx.x * 64 + kk * 8 + 6) & 0xbfffbfffu, rnd(threadIdx.x * 64 + kk * 8 + 7) & 0xbfffbfffu);
+  }  // (exponent bit 14 cleared: magnitudes below 2)
+  TileRing tr;
+  tr.init();
+  __syncthreads();
+  const float sc = 0.1275f;
+  float l0 = 0.0f, l1 = 0.0f, q0 = 0.0f, q1 = 0.0f;
+  f32x16 A0, A1, B0, B1;
+  auto step = [&](auto consume_tag, const char* p, f32x16& x0, f32x16& x1, const f32x16& y0, const f32x16& y1, int ysub) {
+    constexpr bool CONSUME = decltype(consume_tag)::value != 0;
+    float a0 = 0.0f, b0 = 0.0f, a1 = 0.0f, b1 = 0.0f, c0 = 0.0f, d0 = 0.0f, c1 = 0.0f, d1 = 0.0f;
+    float4 lv[4];
+    if (PASS == 2 && CONSUME) {
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) lv[g4] = *reinterpret_cast<const float4*>(&lse_s[ysub * 32 + 8 * g4 + 4 * half]);
+    }
+    auto comp = [](const float4& v, int e) { return e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w; };
+    auto consume = [&](int kk, int g) {
+      const int r = 2 * kk;
+      const f32x16& y = g == 0 ? y0 : y1;
+      float& sa = g == 0 ? a0 : a1; float& sb = g == 0 ? b0 : b1; float& ta = g == 0 ? c0 : c1; float& tb = g == 0 ? d0 : d1;
+      if (PASS == 1) {
+        sa += fast_exp2(fmaf(y[r], sc, -40.0f));
+        sb += fast_exp2(fmaf(y[r + 1], sc, -40.0f));
+      } else {
+        const float pa = fast_exp2(fmaf(y[r], sc, -comp(lv[r >> 2], r & 3)));
+        const float pb = fast_exp2(fmaf(y[r + 1], sc, -comp(lv[r >> 2], (r & 3) + 1)));
+        sa += pa; ta = fmaf(pa, pa, ta);
+        sb += pb; tb = fmaf(pb, pb, tb);
+      }
+    };
+    auto pin = [&]() { asm volatile("" : "+v"(a0), "+v"(b0), "+v"(a1), "+v"(b1), "+v"(c0), "+v"(d0), "+v"(c1), "+v"(d1)); };
+    fill_and_consume<CONSUME>(p, tr.frag, own0, own1, x0, x1, consume, pin);
+    if (CONSUME) {
+      if (PASS == 1) {  // the row pass checks every tile's sum against its safe range
+        if (__builtin_amdgcn_ballot_w64(!(a0 + b0 <= 0x1p64f)) == 0) l0 += a0 + b0;
+        if (__builtin_amdgcn_ballot_w64(!(a1 + b1 <= 0x1p64f)) == 0) l1 += a1 + b1;
+      } else {
+        l0 += a0 + b0; l1 += a1 + b1; q0 += c0 + d0; q1 += c1 + d1;
+      }
+    }
+  };
+  step(StageTag<0>{}, tile, A0, A1, B0, B1, 0);
+  for (int t = 0; t < tiles; ++t) {
+    asm volatile("" : "+v"(own0[0].x), "+v"(own1[0].x));  // not loop-invariant as far as the compiler can tell
+    step(StageTag<1>{}, tile + 32 * kRowBytes, B0, B1, A0, A1, 0);
+    step(StageTag<1>{}, tile, A0, A1, B0, B1, 1);
+  }
+  float sum = l0 + l1 + q0 + q1;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) sum += A0[r] + A1[r];
+  sink[static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x] = sum;
+}
+
 // Two workgroups per block of keys when one would leave the chip short of workgroups (fewer than four per compute
 // unit); ROCO_PREFILL_QSPLIT = 1 or 2 overrides.
 int columns_query_shares(const PrefillArgs& a, int pairs) {
@@ -1226,11 +1309,16 @@ hipError_t launch_with_output(const PrefillArgs& a, hipStream_t s) {
 
 }  // namespace
 
-hipError_t launch_mfma_probe(int workgroups, int iters, bool random_operands, float* sink, hipStream_t s) {
+hipError_t launch_mfma_probe(int workgroups, int iters, int mode, float* sink, hipStream_t s) {
   ProfScope ps(kProfMfmaProbe, s);
   const dim3 grid(static_cast<unsigned>(workgroups));
-  if (random_operands) hipLaunchKernelGGL(mfma_probe<true>, grid, dim3(256), 0, s, iters, sink);
-  else hipLaunchKernelGGL(mfma_probe<false>, grid, dim3(256), 0, s, iters, sink);
+  switch (mode) {
+    case 0: hipLaunchKernelGGL(mfma_probe<false>, grid, dim3(256), 0, s, iters, sink); break;
+    case 1: hipLaunchKernelGGL(mfma_probe<true>, grid, dim3(256), 0, s, iters, sink); break;
+    case 2: hipLaunchKernelGGL(prefill_mix_probe<1>, grid, dim3(256), 0, s, iters, sink); break;
+    case 3: hipLaunchKernelGGL(prefill_mix_probe<2>, grid, dim3(256), 0, s, iters, sink); break;
+    default: return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 

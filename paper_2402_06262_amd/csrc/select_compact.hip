@@ -176,7 +176,57 @@ __global__ __launch_bounds__(kSelThreads) void select_retained(DecodeArgs a, int
   for (int i = tid; i < B; i += NT) mask[i] = (i < n && !out.has(key2(i), i)) ? 1 : 0;
 }
 
+// Overlap of two sets of cached tokens per unit (what section 4.1's consistency study compares): set X holds the
+// positions pos_x[j] of the slots j < n_x with mask_x[j] != 0 (no mask: every such slot).  Positions inside a cache
+// are distinct, so |A and B| is the number of B's members whose bit A has set in an LDS bitmap over [0, max_pos).
+__global__ __launch_bounds__(256) void set_overlap(int slots_a, const int32_t* pos_a, const int32_t* mask_a,
+                                                   const int32_t* n_a, int slots_b, const int32_t* pos_b,
+                                                   const int32_t* mask_b, const int32_t* n_b, int max_pos,
+                                                   int32_t* inter_out, int32_t* union_out) {
+  extern __shared__ uint32_t bits[];  // (max_pos + 31) / 32 words
+  __shared__ uint32_t cnt[3];         // |A|, |B|, |A and B|
+  const int u = blockIdx.x, tid = threadIdx.x;
+  const int words = (max_pos + 31) / 32;
+  for (int i = tid; i < words; i += 256) bits[i] = 0u;
+  if (tid < 3) cnt[tid] = 0u;
+  __syncthreads();
+  const int na = min(n_a[u], slots_a), nb = min(n_b[u], slots_b);
+  uint32_t mine_a = 0, mine_b = 0, mine_i = 0;
+  for (int j = tid; j < na; j += 256) {
+    const int p = pos_a[static_cast<size_t>(u) * slots_a + j];
+    if ((mask_a == nullptr || mask_a[static_cast<size_t>(u) * slots_a + j] != 0) && p >= 0 && p < max_pos) {
+      atomicOr(&bits[p >> 5], 1u << (p & 31));
+      ++mine_a;
+    }
+  }
+  __syncthreads();
+  for (int j = tid; j < nb; j += 256) {
+    const int p = pos_b[static_cast<size_t>(u) * slots_b + j];
+    if ((mask_b == nullptr || mask_b[static_cast<size_t>(u) * slots_b + j] != 0) && p >= 0 && p < max_pos) {
+      ++mine_b;
+      mine_i += (bits[p >> 5] >> (p & 31)) & 1u;
+    }
+  }
+  atomicAdd(&cnt[0], mine_a);
+  atomicAdd(&cnt[1], mine_b);
+  atomicAdd(&cnt[2], mine_i);
+  __syncthreads();
+  if (tid == 0) {
+    inter_out[u] = static_cast<int32_t>(cnt[2]);
+    union_out[u] = static_cast<int32_t>(cnt[0] + cnt[1] - cnt[2]);
+  }
+}
+
 }  // namespace
+
+hipError_t launch_set_overlap(int units, int slots_a, const int32_t* pos_a, const int32_t* mask_a, const int32_t* n_a,
+                              int slots_b, const int32_t* pos_b, const int32_t* mask_b, const int32_t* n_b, int max_pos,
+                              int32_t* inter, int32_t* uni, hipStream_t s) {
+  const size_t lds = static_cast<size_t>((max_pos + 31) / 32) * sizeof(uint32_t);  // the host keeps this within 64 KiB
+  hipLaunchKernelGGL(set_overlap, dim3(units), dim3(256), lds, s, slots_a, pos_a, mask_a, n_a, slots_b, pos_b, mask_b, n_b,
+                     max_pos, inter, uni);
+  return hipGetLastError();
+}
 
 hipError_t launch_select_retained(const DecodeArgs& a, int keep, int32_t* mask, hipStream_t s) {
   const size_t lds = key_lds_bytes(a.B);

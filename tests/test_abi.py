@@ -25,7 +25,7 @@ def test_library_loads_and_exports_every_declared_symbol():
             "roco_decode_workspace_bytes", "roco_strerror", "roco_version", "roco_select_victims",
             "roco_probe_cache_read", "roco_profile_sampling", "roco_encode_block", "roco_block_workspace_bytes",
             "roco_decode_step_gqa", "roco_encode_block_gqa",
-            "roco_select_retained", "roco_decode_step_launches", "roco_decode_step_static"} <= set(names)
+            "roco_select_retained", "roco_decode_step_launches", "roco_decode_step_static", "roco_set_overlap"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in roco.h but not exported"
     assert roco.roco_version() == 1
@@ -51,7 +51,8 @@ def test_mfma_probe_arguments_are_validated_on_the_host():
     lib = roco.load_library()
     assert lib.roco_probe_mfma(0, 16, 0, 0x1000, 1 << 20, None) == EINVAL
     assert lib.roco_probe_mfma(16, 0, 0, 0x1000, 1 << 20, None) == EINVAL
-    assert lib.roco_probe_mfma(16, 16, 2, 0x1000, 1 << 20, None) == EINVAL
+    assert lib.roco_probe_mfma(16, 16, 4, 0x1000, 1 << 20, None) == EINVAL
+    assert lib.roco_probe_mfma(16, 16, -1, 0x1000, 1 << 20, None) == EINVAL
     assert lib.roco_probe_mfma(16, 16, 1, None, 1 << 20, None) == EINVAL
     assert lib.roco_probe_mfma(16, 16, 1, 0x1000, 16 * 1024 - 1, None) == EWORKSPACE
 
@@ -215,3 +216,20 @@ def test_static_scratch_decode_step_validates_on_the_host():
     assert roco.decode_workspace_bytes(big) > 32 << 20
     assert lib.roco_decode_step_static(ctypes.byref(big), *args, None) == -5
     assert "static" in roco.roco_strerror(-5)
+
+
+def test_set_overlap_validates_on_the_host():
+    lib = roco.load_library()
+    ok = [4, 16, 0x1000, None, 0x1000, 16, 0x1000, None, 0x1000, 64, 0x1000, 0x1000, None]
+    bad_units, bad_max, big_max, misaligned = list(ok), list(ok), list(ok), list(ok)
+    bad_units[0] = 0
+    bad_max[9] = 0
+    big_max[9] = (1 << 19) + 1
+    misaligned[3] = 0x1004
+    assert lib.roco_set_overlap(*bad_units) == EINVAL
+    assert lib.roco_set_overlap(*bad_max) == EINVAL
+    assert lib.roco_set_overlap(*big_max) == EUNSUPPORTED
+    assert lib.roco_set_overlap(*misaligned) == EINVAL
+    no_out = list(ok)
+    no_out[10] = None
+    assert lib.roco_set_overlap(*no_out) == EINVAL

@@ -91,3 +91,25 @@ def test_consistency_study_matches_the_same_study_on_the_oracle():
             assert abs(mean - tot / cnt) < 5e-3  # identical sets up to fp32 / fp64 near-ties in a few positions
     # closed form: recency is perfectly consistent with its own full-cache variant (both are the last B tokens)
     assert got["oldest"][0.3][0] == 1.0 and got["oldest"][0.5][0] == 1.0
+
+
+def test_set_overlap_counts_against_python_sets():
+    """roco_set_overlap on random caches: masked and unmasked sets, partially filled units, an empty set."""
+    import paper_2402_06262_amd as roco
+    rng = np.random.default_rng(5)
+    units, sa, sb, T = 5, 96, 40, 300
+    pos_a = np.stack([rng.choice(T, size=sa, replace=False) for _ in range(units)]).astype(np.int32)
+    pos_b = np.stack([rng.choice(T, size=sb, replace=False) for _ in range(units)]).astype(np.int32)
+    mask_a = (rng.random((units, sa)) < 0.6).astype(np.int32)
+    n_a = np.array([sa, 50, 0, 96, 7], np.int32)
+    n_b = np.array([sb, 40, 12, 0, 40], np.int32)
+    dev = lambda x: torch.from_numpy(x).cuda()
+    inter = torch.full((units,), -1, dtype=torch.int32, device="cuda")
+    uni = torch.full((units,), -1, dtype=torch.int32, device="cuda")
+    for use_mask in (True, False):
+        roco.roco_set_overlap(dev(pos_a), dev(mask_a) if use_mask else None, dev(n_a), dev(pos_b), None, dev(n_b), T, inter, uni)
+        torch.cuda.synchronize()
+        for u in range(units):
+            A = {int(p) for j, p in enumerate(pos_a[u, :n_a[u]]) if not use_mask or mask_a[u, j]}
+            Bs = {int(p) for p in pos_b[u, :n_b[u]]}
+            assert int(inter[u]) == len(A & Bs) and int(uni[u]) == len(A | Bs), (use_mask, u)

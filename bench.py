@@ -59,6 +59,23 @@ def measured_traffic(kernel, workload):
     return None
 
 
+def counted_issue_bound_tflops(kernel, workload):
+    """The matrix rate at which the vector-issue port saturates with the instruction mix rocprofv3 counted for
+    `kernel` (COUNTED lines under profiles/): per matrix instruction its own issue slot, one per vector instruction
+    and a second one per transcendental, 4 cycles each, against the pipe's 32 cycles.  None without a counted mix."""
+    import glob
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
+        with open(path) as f:
+            for line in f:
+                if line.startswith("COUNTED "):
+                    rec = dict(kv.split("=", 1) for kv in line.split()[1:])
+                    if rec.get("kernel") == kernel and rec.get("workload") == str(workload):
+                        slots = 1.0 + float(rec["valu_per_mfma"]) + float(rec["trans_per_mfma"])
+                        return {"TFLOPs": MFMA_BF16_PEAK_TFLOPS * 32.0 / (4.0 * slots), "issue_slots_per_mfma": slots,
+                                "measured_at_commit": rec.get("commit"), "source": os.path.relpath(path, ROOT)}
+    return None
+
+
 def generate(cfg, seed, workers):
     """All units of the workload as float32 host arrays [units, T, d] (bf16-representable)."""
     from inputs import make_unit, unit_ids
@@ -673,6 +690,7 @@ def main():
                     "frac_of_mfma_peak": prefill_flops / 2 / (pre_kernel_ms[key] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                     "measured_mix_ceiling_TFLOPs": mix_ceiling[which],
                     "frac_of_measured_mix_ceiling": prefill_flops / 2 / (pre_kernel_ms[key] * 1e-3) / 1e12 / mix_ceiling[which],
+                    "issue_bound_at_counted_mix": counted_issue_bound_tflops(kname, 3) if U == 512 else None,
                     "traffic": (measured_traffic(kname, 3) or {}).get("bytes") if U == 512 else None,
                     "traffic_source": measured_traffic(kname, 3) if U == 512 else None,
                     "algorithmic_bytes": 2 * U * L * d * esz}

@@ -237,14 +237,15 @@ int roco_decode_step_static(const roco_params* params,
  *   p_i = softmax(scale q_i.K[j] + bias), out_i = sum_j p_ij V[j]; every attended slot gets p_ij, p_ij^2 and 1
  *   added to Acc, Acc2 and Count.  next_slot is left ready for a following roco_decode_step.
  *
- * block            in  1 <= b <= min(32, B)
+ * block            in  1 <= b <= min(64, B)
  * q, k_new, v_new  in  [units, b, d]   dtype
  * qpos0            in  [units]         int32 position of the block's first token
  * cache state      in/out as in roco_decode_step
  * out              out [units, b, d]   dtype
  * evicted_slot, evicted_pos  out [units, b] int32: the slot token i took over from an evicted token and that
  *                  token's position, or -1 where token i went to an empty slot (either may be NULL)
- * workspace        roco_block_workspace_bytes(params, block) bytes
+ * workspace        roco_block_workspace_bytes(params, block) bytes: sized for the largest step (64 query rows per
+ *                  unit), so that one workspace serves every block size and group size of a unit count and budget
  * Supported: budget a multiple of 4 (else ROCO_EUNSUPPORTED).  bf16 with head_dim 128 runs on the matrix cores
  * and streams K and V once per block; the other dtypes / head_dims compute the same step with one pass over K and
  * V per query row.
@@ -263,8 +264,9 @@ int roco_encode_block(const roco_params* params, int32_t block,
  * Acc += mean_h p_h, Acc2 += (mean_h p_h)^2, Count += 1; eviction, slot assignment and everything else are those
  * of roco_encode_block.  K and V are streamed once for the whole group and block.
  *
- * roco_encode_block_gqa: `block` tokens per unit, block * group <= 32 (else ROCO_EUNSUPPORTED); group = 1 is
- * roco_encode_block.  roco_decode_step_gqa: block = 1, so group <= 32; group = 1 is roco_decode_step.
+ * roco_encode_block_gqa: `block` tokens per unit, block * group <= 64 (else ROCO_EUNSUPPORTED; 16 tokens of a group
+ * of 4 is appendix A's setting); group = 1 is roco_encode_block.  roco_decode_step_gqa: block = 1, so group <= 64;
+ * group = 1 is roco_decode_step.
  *
  * q                in  [units, block, group, d] dtype      ([units, group, d] for the decode step)
  * k_new, v_new     in  [units, block, d]        dtype      ([units, d])

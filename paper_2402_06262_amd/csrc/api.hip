@@ -368,6 +368,7 @@ int run_block(const roco_params* params, int tokens, int heads, const void* q, c
   a.units = params->units; a.B = params->budget; a.scope = params->scope;
   a.pol = policy_of(params);
   a.block = tokens; a.heads = heads; a.queries = tokens * heads;
+  a.qrows = a.queries > 32 ? 64 : 32;
   a.row_bytes = params->head_dim * (params->dtype == ROCO_BF16 ? 2 : 4);
   a.streaming = streaming_loads(params) ? 1 : 0;
   {  // split the budget into 64-slot-aligned ranges: two resident workgroups per compute unit measured best

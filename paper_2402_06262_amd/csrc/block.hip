@@ -11,9 +11,10 @@
 //   block_prepare : one workgroup per unit.  Victims (two exact radix selects), ordered slot assignment,
 //                   K / V rows of the block written into their slots, pos / statistics of those slots reset.
 //   block_attend  : grid (splits, units), two waves.  64-slot K and V tiles through LDS, each wave scores 32
-//                   slots against the block's (up to 32) queries on the matrix cores (score tile = K . Q^T, the
-//                   query in the lane), stores the base-2 logits, keeps an online softmax per query and
-//                   accumulates O^T = V^T . P^T with V^T fragments from the LDS transpose read.
+//                   slots against the block's queries on the matrix cores (score tile = K . Q^T, the query in
+//                   the lane; one or two tiles of 32 query rows, every K and V^T fragment read from LDS feeding
+//                   both), stores the base-2 logits, keeps an online softmax per query and accumulates
+//                   O^T = V^T . P^T with V^T fragments from the LDS transpose read.
 //   block_finish  : one workgroup per unit.  Merges the partials per query, writes the outputs, adds the
 //                   statistics of all rows to every slot and chooses the victim a following single-token step
 //                   would take.
@@ -36,7 +37,8 @@ using namespace mfma;
 constexpr int kPrepThreads = 1024;  // 512 when the units outnumber the compute units (see launch_block)
 constexpr int kAttThreads = 128;  // two waves: one 32-slot half of a 64-slot tile each
 constexpr int kFinThreads = 1024;
-constexpr int kQ = 32;            // queries per matrix tile; a block holds at most this many tokens
+constexpr int kQ = 32;            // query rows per matrix tile
+static_assert(kMaxBlock == 2 * kQ, "a step holds at most two tiles of query rows");
 
 // ------------------------------------------------------------------------------------------------
 template <int NT>
@@ -44,7 +46,7 @@ __global__ __launch_bounds__(NT) void block_prepare(BlockArgs a) {
   extern __shared__ uint32_t lds_keys[];  // [2][B] when B <= kMaxDecodeBudgetLds
   __shared__ uint32_t sel_sh[kSelectLdsWords];
   __shared__ uint32_t scan_sh[NT / kWave + 1];
-  __shared__ int slot_of[kQ];
+  __shared__ int slot_of[kMaxBlock];
   const int u = blockIdx.x, tid = threadIdx.x;
   const int B = a.B, b = a.block;
   const int n = a.n_used[u];
@@ -58,7 +60,7 @@ __global__ __launch_bounds__(NT) void block_prepare(BlockArgs a) {
   uint32_t* var_key = (B <= kMaxDecodeBudgetLds) ? lds_keys : a.keys + static_cast<size_t>(u) * 2 * B;
   uint32_t* mas_key = var_key + B;
 
-  if (tid < kQ) slot_of[tid] = 0;
+  if (tid < kMaxBlock) slot_of[tid] = 0;
   KSmallest scope = {0u, 0u}, out = {0u, 0u};
   // one eviction from a full cache: the victim was already chosen when the statistics were last updated
   const int hint = (E == 1 && n == B) ? a.next_slot[u] : -1;
@@ -144,14 +146,17 @@ __device__ __forceinline__ void kv_store(const StagedKV& s, char* tileK, char* t
   }
 }
 
+// NQT: tiles of 32 query rows (1 or 2).  The workspace planes are addressed with a.qrows = 32 NQT rows per unit.
+template <int NQT>
 __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
+  constexpr int QR = NQT * kQ;
   extern __shared__ __attribute__((aligned(16))) char lds_dyn[];  // K[2] and V[2] tiles; reused for the merge
   __shared__ __attribute__((aligned(16))) int32_t bidx_s[2][kTile];
   __shared__ __attribute__((aligned(16))) int32_t pos_s[2][kTile];
-  __shared__ float merge_m[kQ], merge_l[kQ];
+  __shared__ float merge_m[QR], merge_l[QR];
   const int u = blockIdx.y, split = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-  const int half = lane >> 5, qi = lane & 31;  // this lane's query (block token index)
+  const int half = lane >> 5, qi = lane & 31;  // this lane's query row inside a tile
   const int B = a.B, b = a.queries;
   // Usually block_prepare has run: n_used counts the block's tokens and their rows are in the cache.  A single-token
   // step skips it (BlockArgs::single): the token's slot is known from the state, its row is read from k_new / v_new
@@ -172,24 +177,34 @@ __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
   char* Vb = static_cast<char*>(a.V) + static_cast<size_t>(u) * B * kRowBytes;
   const int32_t* bidx = a.blk_idx + static_cast<size_t>(u) * B;
   const int32_t* pos = a.pos + static_cast<size_t>(u) * B;
-  float* z = a.z + static_cast<size_t>(u) * kQ * B;
+  float* z = a.z + static_cast<size_t>(u) * QR * B;
   const float sc = a.scale_log2;
   const int w = a.recency_window;
   const float rb = a.recency_bias_log2;
-  const int ti = qi / a.heads;  // this lane's block token; the heads of a group share its position
-  const int qp = a.qpos0[u] + ti;
+  int ti[NQT], qp[NQT];  // this lane's block token per tile; the heads of a group share its position
+#pragma unroll
+  for (int t2 = 0; t2 < NQT; ++t2) {
+    ti[t2] = (kQ * t2 + qi) / a.heads;
+    qp[t2] = a.qpos0[u] + ti[t2];
+  }
 
   // B operand: the block's queries (lanes beyond the block reuse its last query; their results are dropped)
-  uint4 own[kKSteps];
-  {
-    const char* qrow = static_cast<const char*>(a.q) + (static_cast<size_t>(u) * b + min(qi, b - 1)) * kRowBytes;
+  uint4 own[NQT][kKSteps];
 #pragma unroll
-    for (int kk = 0; kk < kKSteps; ++kk) own[kk] = load16(qrow + kk * 32 + half * 16);
+  for (int t2 = 0; t2 < NQT; ++t2) {
+    const char* qrow = static_cast<const char*>(a.q) + (static_cast<size_t>(u) * b + min(kQ * t2 + qi, b - 1)) * kRowBytes;
+#pragma unroll
+    for (int kk = 0; kk < kKSteps; ++kk) own[t2][kk] = load16(qrow + kk * 32 + half * 16);
   }
-  float m = -INFINITY, l = 0.0f;
-  f32x16 o[4];
+  float m[NQT], l[NQT];
+  f32x16 o[NQT][4];
 #pragma unroll
-  for (int db = 0; db < 4; ++db) o[db] = f32x16{0};
+  for (int t2 = 0; t2 < NQT; ++t2) {
+    m[t2] = -INFINITY;
+    l[t2] = 0.0f;
+#pragma unroll
+    for (int db = 0; db < 4; ++db) o[t2][db] = f32x16{0};
+  }
   const int tr_off = transposed_fragment_offset();
 
   const int n_tiles = row1 > row0 ? (row1 - row0 + kTile - 1) / kTile : 0;
@@ -232,20 +247,25 @@ __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
     const int tr0 = tile_row(t);
     const int sb = tr0 + 32 * wave;  // first slot of this wave's half-tile
     if (sb < row1) {                               // wave-uniform
-    // ---- scores of 32 slots x 32 queries
-    f32x16 sacc;
+    // ---- scores of 32 slots x 32 NQT queries: every K fragment feeds one accumulator chain per query tile
+    f32x16 sacc[NQT];
     {
       const char* p = tileK + (32 * wave + (lane & 31)) * kLdsRow + half * 16;
       const f32x16 zero = {0};
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-          __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p)), __builtin_bit_cast(bf16x8, own[0]), zero, 0, 0, 0);
 #pragma unroll
-      for (int kk = 1; kk < kKSteps; ++kk)
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-            __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p + kk * 32)),
-            __builtin_bit_cast(bf16x8, own[kk]), sacc, 0, 0, 0);
+      for (int kk = 0; kk < kKSteps; ++kk) {
+        const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p + kk * 32));
+#pragma unroll
+        for (int t2 = 0; t2 < NQT; ++t2)
+          sacc[t2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, __builtin_bit_cast(bf16x8, own[t2][kk]),
+                                                             kk == 0 ? zero : sacc[t2], 0, 0, 0);
+      }
     }
+    bf16x8 pfrag[NQT][2];
+#pragma unroll
+    for (int t2 = 0; t2 < NQT; ++t2) {
     // ---- base-2 logits: a slot is visible if it exists and does not hold a later token of the block
+    const int q = kQ * t2 + qi;
     float tv[16];
     float mb = -INFINITY;
 #pragma unroll
@@ -258,42 +278,42 @@ __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int slot = tr0 + base + e;
-        float x = sacc[4 * g4 + e] * sc;
+        float x = sacc[t2][4 * g4 + e] * sc;
         if (w > 0) {
-          const int dlt = qp - psv[e];
+          const int dlt = qp[t2] - psv[e];
           if (dlt >= 0 && dlt < w) x += rb;
         }
-        if (slot >= row1 || biv[e] > ti) x = -INFINITY;
+        if (slot >= row1 || biv[e] > ti[t2]) x = -INFINITY;
         tv[4 * g4 + e] = x;
         mb = fmaxf(mb, x);
       }
       const int slot0 = tr0 + base;
-      if (qi < b && slot0 < row1) {  // logits of real queries and real slots are kept for the statistics
-        *reinterpret_cast<float4*>(z + static_cast<size_t>(qi) * B + slot0) =
+      if (q < b && slot0 < row1) {  // logits of real queries and real slots are kept for the statistics
+        *reinterpret_cast<float4*>(z + static_cast<size_t>(q) * B + slot0) =
             make_float4(tv[4 * g4], tv[4 * g4 + 1], tv[4 * g4 + 2], tv[4 * g4 + 3]);
       }
     }
     mb = fmaxf(mb, __shfl_xor(mb, 32, kWave));  // both lane halves feed one matrix product
-    const float m_new = fmaxf(m, mb);
-    if (__any(m_new > m)) {
-      const float alpha = (m_new > -INFINITY) ? fast_exp2(m - m_new) : 1.0f;
-      l *= alpha;
+    const float m_new = fmaxf(m[t2], mb);
+    if (__any(m_new > m[t2])) {
+      const float alpha = (m_new > -INFINITY) ? fast_exp2(m[t2] - m_new) : 1.0f;
+      l[t2] *= alpha;
 #pragma unroll
       for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+        for (int r = 0; r < 16; ++r) o[t2][db][r] *= alpha;
     }
-    m = m_new;
-    bf16x8 pfrag[2];
+    m[t2] = m_new;
     float sum = 0.0f;
     const float ref = (m_new > -INFINITY) ? m_new : 0.0f;  // nothing visible yet: every term is 2^-inf = 0
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const float pv = fast_exp2(tv[r] - ref);
       sum += pv;
-      pfrag[r >> 3][r & 7] = static_cast<__bf16>(pv);
+      pfrag[t2][r >> 3][r & 7] = static_cast<__bf16>(pv);
     }
-    l += sum;
+    l[t2] += sum;
+    }
     // ---- O^T += V^T . P^T
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
@@ -302,49 +322,60 @@ __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
       for (int db = 0; db < 4; ++db) {
         const uint2 lo = lds_read_transposed(vt + db * 64);
         const uint2 hi = lds_read_transposed(vt + 8 * kLdsRowV + db * 64);
-        const uint4 afrag = make_uint4(lo.x, lo.y, hi.x, hi.y);
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, afrag), pfrag[ks], o[db], 0, 0, 0);
+        const bf16x8 afrag = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+#pragma unroll
+        for (int t2 = 0; t2 < NQT; ++t2)
+          o[t2][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag, pfrag[t2][ks], o[t2][db], 0, 0, 0);
       }
     }
     }
   }
-  l += __shfl_xor(l, 32, kWave);  // the lane halves summed different slots of the same query
+#pragma unroll
+  for (int t2 = 0; t2 < NQT; ++t2) l[t2] += __shfl_xor(l[t2], 32, kWave);  // the lane halves summed different slots
 
   // ---- merge the two waves (wave 1 hands its state to wave 0 through LDS), then write the split's partial
   __syncthreads();  // everybody is done with the tiles
-  float* mo = reinterpret_cast<float*>(lds_dyn);  // [32 queries][128 dims]
+  float* mo = reinterpret_cast<float*>(lds_dyn);  // [QR query rows][128 dims]
   if (wave == 1) {
-    if (half == 0) { merge_m[qi] = m; merge_l[qi] = l; }
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+    for (int t2 = 0; t2 < NQT; ++t2) {
+      const int q = kQ * t2 + qi;
+      if (half == 0) { merge_m[q] = m[t2]; merge_l[q] = l[t2]; }
 #pragma unroll
-      for (int r = 0; r < 16; ++r) mo[qi * D + db * 32 + 8 * (r >> 2) + 4 * half + (r & 3)] = o[db][r];
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mo[q * D + db * 32 + 8 * (r >> 2) + 4 * half + (r & 3)] = o[t2][db][r];
+    }
   }
   __syncthreads();
   if (wave == 0) {
-    const float m1 = merge_m[qi], l1 = merge_l[qi];
-    const float M = fmaxf(m, m1);
-    const float w0 = (m > -INFINITY) ? fast_exp2(m - M) : 0.0f;
-    const float w1 = (m1 > -INFINITY) ? fast_exp2(m1 - M) : 0.0f;
-    if (half == 0) {
-      a.part_m[pidx * kQ + qi] = M;
-      a.part_l[pidx * kQ + qi] = l * w0 + l1 * w1;
-    }
-    float* po = a.part_o + (pidx * kQ + qi) * D;
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        const int d0 = db * 32 + 8 * g4 + 4 * half;
-        float4 r4;
-        const float4 other = (w1 > 0.0f) ? *reinterpret_cast<const float4*>(mo + qi * D + d0)
-                                         : make_float4(0.0f, 0.0f, 0.0f, 0.0f);  // wave 1 saw nothing: ignore LDS
-        r4.x = o[db][4 * g4 + 0] * w0 + other.x * w1;
-        r4.y = o[db][4 * g4 + 1] * w0 + other.y * w1;
-        r4.z = o[db][4 * g4 + 2] * w0 + other.z * w1;
-        r4.w = o[db][4 * g4 + 3] * w0 + other.w * w1;
-        *reinterpret_cast<float4*>(po + d0) = r4;
+    for (int t2 = 0; t2 < NQT; ++t2) {
+      const int q = kQ * t2 + qi;
+      const float m1 = merge_m[q], l1 = merge_l[q];
+      const float M = fmaxf(m[t2], m1);
+      const float w0 = (m[t2] > -INFINITY) ? fast_exp2(m[t2] - M) : 0.0f;
+      const float w1 = (m1 > -INFINITY) ? fast_exp2(m1 - M) : 0.0f;
+      if (half == 0) {
+        a.part_m[pidx * QR + q] = M;
+        a.part_l[pidx * QR + q] = l[t2] * w0 + l1 * w1;
       }
+      float* po = a.part_o + (pidx * QR + q) * D;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          const int d0 = db * 32 + 8 * g4 + 4 * half;
+          float4 r4;
+          const float4 other = (w1 > 0.0f) ? *reinterpret_cast<const float4*>(mo + q * D + d0)
+                                           : make_float4(0.0f, 0.0f, 0.0f, 0.0f);  // wave 1 saw nothing: ignore LDS
+          r4.x = o[t2][db][4 * g4 + 0] * w0 + other.x * w1;
+          r4.y = o[t2][db][4 * g4 + 1] * w0 + other.y * w1;
+          r4.z = o[t2][db][4 * g4 + 2] * w0 + other.z * w1;
+          r4.w = o[t2][db][4 * g4 + 3] * w0 + other.w * w1;
+          *reinterpret_cast<float4*>(po + d0) = r4;
+        }
+    }
   }
 }
 
@@ -375,7 +406,7 @@ __global__ __launch_bounds__(256) void block_attend_simple(BlockArgs a) {
   const char* Vb = static_cast<const char*>(a.V) + static_cast<size_t>(u) * B * G::ROW_BYTES;
   const int32_t* bidx = a.blk_idx + static_cast<size_t>(u) * B;
   const int32_t* pos = a.pos + static_cast<size_t>(u) * B;
-  float* z = a.z + (static_cast<size_t>(u) * kQ + r) * B;
+  float* z = a.z + (static_cast<size_t>(u) * a.qrows + r) * B;
   const int qp = a.qpos0[u] + ti;
   const int w = a.recency_window;
   const float rb = a.recency_bias_log2;
@@ -399,7 +430,7 @@ __global__ __launch_bounds__(256) void block_attend_simple(BlockArgs a) {
   float M = -INFINITY;
 #pragma unroll
   for (int s = 0; s < WAVES; ++s) M = fmaxf(M, sm_m[s]);
-  const size_t pidx = static_cast<size_t>(u) * kQ + r;  // one split
+  const size_t pidx = static_cast<size_t>(u) * a.qrows + r;  // one split
   if (tid < D) {
     float o = 0.0f, l = 0.0f;
 #pragma unroll
@@ -424,9 +455,9 @@ __global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
   extern __shared__ uint32_t lds_keys[];  // [2][B] ranking keys when B <= kMaxDecodeBudgetLds
   __shared__ uint32_t sel_sh[kSelectLdsWords];
   __shared__ unsigned long long best_sh[NT / kWave];
-  __shared__ float Mq[kQ], invq[kQ];
+  __shared__ float Mq[kMaxBlock], invq[kMaxBlock];
   const int u = blockIdx.x, tid = threadIdx.x;
-  const int B = a.B, nq = a.queries, S = a.splits;
+  const int B = a.B, nq = a.queries, S = a.splits, QR = a.qrows;
   int n = a.n_used[u];
   int fresh = -1;  // single-token step without block_prepare: the slot the token took, which this kernel books
   bool evicted = false;
@@ -437,17 +468,17 @@ __global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
   }
   const int heads = a.heads;
   const float inv_heads = 1.0f / static_cast<float>(heads);
-  const float* pm = a.part_m + static_cast<size_t>(u) * S * kQ;
-  const float* pl = a.part_l + static_cast<size_t>(u) * S * kQ;
-  const float* po = a.part_o + static_cast<size_t>(u) * S * kQ * D;
+  const float* pm = a.part_m + static_cast<size_t>(u) * S * QR;
+  const float* pl = a.part_l + static_cast<size_t>(u) * S * QR;
+  const float* po = a.part_o + static_cast<size_t>(u) * S * QR * D;
 
-  if (tid < kQ) {  // per query: merge the splits' normalisers in split order
+  if (tid < QR) {  // per query: merge the splits' normalisers in split order
     float M = -INFINITY;
-    for (int s = 0; s < S; ++s) M = fmaxf(M, pm[s * kQ + tid]);
+    for (int s = 0; s < S; ++s) M = fmaxf(M, pm[s * QR + tid]);
     float L = 0.0f;
     for (int s = 0; s < S; ++s) {
-      const float ms = pm[s * kQ + tid];
-      L += (ms > -INFINITY) ? pl[s * kQ + tid] * fast_exp2(ms - M) : 0.0f;
+      const float ms = pm[s * QR + tid];
+      L += (ms > -INFINITY) ? pl[s * QR + tid] * fast_exp2(ms - M) : 0.0f;
     }
     Mq[tid] = M;
     invq[tid] = 1.0f / L;
@@ -466,8 +497,8 @@ __global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
     const int q = idx / D, dd = idx % D;
     float o = 0.0f;
     for (int s = 0; s < S; ++s) {
-      const float ms = pm[s * kQ + q];
-      o += (ms > -INFINITY) ? po[(static_cast<size_t>(s) * kQ + q) * D + dd] * fast_exp2(ms - Mq[q]) : 0.0f;
+      const float ms = pm[s * QR + q];
+      o += (ms > -INFINITY) ? po[(static_cast<size_t>(s) * QR + q) * D + dd] * fast_exp2(ms - Mq[q]) : 0.0f;
     }
     store_elem<DT>(a.out, (static_cast<size_t>(u) * nq + q) * D + dd, o * invq[q]);
   }
@@ -475,7 +506,7 @@ __global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
   float* acc = a.stats + static_cast<size_t>(u) * 3 * B;
   float* acc2 = acc + B;
   float* cnt = acc2 + B;
-  const float* z = a.z + static_cast<size_t>(u) * kQ * B;
+  const float* z = a.z + static_cast<size_t>(u) * QR * B;
   const bool full = n >= B;
   uint32_t* var_key = (B <= kMaxDecodeBudgetLds) ? lds_keys : a.keys + static_cast<size_t>(u) * 2 * B;
   uint32_t* mas_key = var_key + B;
@@ -569,12 +600,10 @@ hipError_t launch_block(int dtype, int head_dim, const BlockArgs& args, hipStrea
     return hipErrorInvalidValue;
   constexpr size_t kAttLds = 2 * static_cast<size_t>(kTileBytes + kTileBytesV);  // 74 KiB: above the default dynamic limit
   const bool mfma_path = dtype == kBF16 && head_dim == 128;
-  static bool attr_done = false;
-  if (mfma_path && !attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(block_attend), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            static_cast<int>(kAttLds)) != hipSuccess)
+  if (mfma_path) {  // set on every call: cheap, and right on whichever device is current
+    const void* fn = a.qrows > kQ ? reinterpret_cast<const void*>(block_attend<2>) : reinterpret_cast<const void*>(block_attend<1>);
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kAttLds)) != hipSuccess)
       return hipErrorInvalidValue;
-    attr_done = true;
   }
   if (!a.single) {
     ProfScope ps(kProfBlockPrepare, s);
@@ -586,7 +615,8 @@ hipError_t launch_block(int dtype, int head_dim, const BlockArgs& args, hipStrea
   if (mfma_path) {
     {
       ProfScope ps(kProfBlockAttend, s);
-      hipLaunchKernelGGL(block_attend, dim3(a.splits, a.units), dim3(kAttThreads), kAttLds, s, a);
+      if (a.qrows > kQ) hipLaunchKernelGGL(block_attend<2>, dim3(a.splits, a.units), dim3(kAttThreads), kAttLds, s, a);
+      else hipLaunchKernelGGL(block_attend<1>, dim3(a.splits, a.units), dim3(kAttThreads), kAttLds, s, a);
     }
     launch_block_tail<kBF16, 128>(a, s);
   } else if (dtype == kBF16 && head_dim == 64) {

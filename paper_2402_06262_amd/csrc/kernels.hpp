@@ -100,7 +100,7 @@ struct PrefillArgs {
   uint32_t* mas_key;     // [units][L_max]
 };
 
-constexpr int kMaxBlock = 32;        // tokens per block-wise step (one 32-wide matrix tile of queries)
+constexpr int kMaxBlock = 64;        // query rows (tokens x heads) per block-wise step: two 32-wide matrix tiles
 constexpr int kMaxBlockSplits = 8;   // split-K partials per unit of the block-wise step
 
 struct BlockArgs {
@@ -110,7 +110,8 @@ struct BlockArgs {
   int row_bytes;  // bytes of a K / V / q row
   int single;     // 1: single-token step without block_prepare (set by launch_block)
   int heads;    // query heads that share the unit's keys and values (1 without grouped-query attention)
-  int queries;  // query rows per unit = block * heads <= 32; row r belongs to token r / heads, head r % heads
+  int queries;  // query rows per unit = block * heads <= 64; row r belongs to token r / heads, head r % heads
+  int qrows;    // rows per unit of the z / part_* planes: 32, or 64 when queries > 32
   float scale_log2;
   int recency_window;
   float recency_bias_log2;
@@ -123,10 +124,10 @@ struct BlockArgs {
   int32_t *evicted_slot, *evicted_pos;  // [units][block], may be null
   // workspace
   int32_t* blk_idx;                // [units][B]   block token index held by a slot, -1 for older tokens
-  float* z;                        // [units][32][B] base-2 logits
-  float* part_m;                   // [units][splits][32]
-  float* part_l;                   // [units][splits][32]
-  float* part_o;                   // [units][splits][32][128]
+  float* z;                        // [units][qrows][B] base-2 logits
+  float* part_m;                   // [units][splits][qrows]
+  float* part_l;                   // [units][splits][qrows]
+  float* part_o;                   // [units][splits][qrows][128]
   uint32_t* keys;                  // [units][2][B] when B is too large for LDS
 };
 hipError_t launch_block(int dtype, int head_dim, const BlockArgs& a, hipStream_t s);  // B % 4 == 0

@@ -150,7 +150,7 @@ def test_encode_block_validates_on_the_host():
     lib = roco.load_library()
     p = roco.RocoParams(4, 128, 256, 16, roco.ROCO_BF16)
     need = roco.block_workspace_bytes(p, 8)
-    assert need > 4 * 32 * 256 * 4
+    assert need > 4 * 64 * 256 * 4  # logits of 64 query rows per unit, whatever the block
     args = [0x1000] * 14
 
     def call(params, block, a=args, ws=need):
@@ -163,11 +163,11 @@ def test_encode_block_validates_on_the_host():
         return (lib.roco_encode_block_gqa(ctypes.byref(p), block, group, *args, need, None),
                 lib.roco_decode_step_gqa(ctypes.byref(p), group, *args, need, None))
 
-    assert grouped(1, 0) == (EINVAL, EINVAL) and grouped(1, 33) == (EUNS, EUNS)
-    assert grouped(8, 5)[0] == EUNS and grouped(9, 4)[0] == EUNS  # more than 32 query rows
+    assert grouped(1, 0) == (EINVAL, EINVAL) and grouped(1, 65) == (EUNS, EUNS)
+    assert grouped(13, 5)[0] == EUNS and grouped(17, 4)[0] == EUNS  # more than 64 query rows
 
     assert call(p, 0) == EINVAL and call(p, 257) == EINVAL
-    assert call(p, 33) == EUNS
+    assert call(p, 65) == EUNS
     assert call(roco.RocoParams(4, 96, 256, 16, roco.ROCO_BF16), 4) == EUNS  # head_dim
     assert call(roco.RocoParams(4, 128, 254, 16, roco.ROCO_BF16), 4) == EUNS  # budget not a multiple of 4
     assert roco.block_workspace_bytes(roco.RocoParams(4, 96, 256, 16, roco.ROCO_BF16), 4) == 0

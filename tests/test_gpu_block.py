@@ -70,7 +70,7 @@ def drive(units, d, B, s, prompt_lens, blocks, seed, recency=False, tag="", dtyp
     return ties
 
 
-@pytest.mark.parametrize("b", [1, 2, 5, 16, 32])
+@pytest.mark.parametrize("b", [1, 2, 5, 16, 32, 33, 64])
 def test_block_steps_on_a_full_cache(b):
     """Cache filled by prefill-compress, then blocks of b tokens: b evictions per step."""
     drive(3, 128, 256, 24, [400, 300, 256], [b] * 4, seed=60 + b, tag=f"full-{b}")
@@ -90,7 +90,7 @@ def test_single_token_blocks_fill_then_evict_with_recency_bias():
 def test_block_steps_on_the_vector_path_for_other_dtypes_and_head_dims(dtype, d):
     """Shapes the matrix-core kernel is not built for take one vector-ALU pass per query row: same step, same
     parity bar.  From a compressed cache and with a unit that is still filling up; ragged block sizes."""
-    drive(3, d, 96, 10, [150, 96, 40], [8, 1, 32, 5, 16, 32, 3], seed=140 + d, tag=f"simple-{dtype}-{d}", dtype=dtype)
+    drive(3, d, 96, 10, [150, 96, 40], [8, 1, 32, 5, 16, 32, 3, 64, 47], seed=140 + d, tag=f"simple-{dtype}-{d}", dtype=dtype)
     drive(2, d, 64, 8, [100, 64], [4, 32], seed=150 + d, recency=True, tag=f"simple-recency-{dtype}-{d}", dtype=dtype)
 
 
@@ -98,6 +98,7 @@ def test_block_steps_fill_an_empty_cache_then_start_evicting():
     """Block-wise prompt encoding from scratch: no eviction until the budget is reached, partial eviction when a
     block straddles it, ragged block sizes."""
     drive(2, 128, 200, 16, [0, 0], [32, 32, 32, 32, 32, 32, 7, 32, 1, 13, 32], seed=71, tag="from-empty")
+    drive(2, 128, 200, 16, [0, 0], [64, 64, 64, 64, 40, 64, 1, 64], seed=77, tag="from-empty-64")
 
 
 def test_block_steps_with_recency_bias_and_partially_filled_units():

@@ -70,22 +70,25 @@ def single_step(request, monkeypatch):
     return request.param
 
 
-@pytest.mark.parametrize("group", [1, 2, 4, 8, 32])
+@pytest.mark.parametrize("group", [1, 2, 4, 8, 32, 64])
 def test_grouped_decode_steps_fill_then_evict(group, single_step):
     """Token-wise grouped-query decode from an empty cache: 96 appends, then 40 evicting steps."""
     drive(3, 96, 12, group, [1] * 136, seed=80 + group, tag=f"gqa-decode-g{group}", single_token_entry=True)
 
 
-@pytest.mark.parametrize("group,blocks", [(4, [8] * 12 + [3, 8, 1, 5, 8]), (2, [16] * 7 + [9, 16]), (3, [10, 7, 10, 10, 2] * 3)])
+@pytest.mark.parametrize("group,blocks", [(4, [8] * 12 + [3, 8, 1, 5, 8]), (2, [16] * 7 + [9, 16]), (3, [10, 7, 10, 10, 2] * 3),
+                                          (4, [16] * 3 + [9, 16, 16, 3, 16, 1, 16]), (8, [8] * 7 + [5, 8, 8]), (5, [12, 7, 12] * 4),
+                                          (2, [32, 17, 32, 32]), (64, [1] * 70)])
 def test_grouped_blocks(group, blocks):
-    """Block-wise grouped-query encoding (block * group query rows per matrix tile), ragged blocks included."""
+    """Block-wise grouped-query encoding (block * group query rows on one or two matrix tiles), ragged blocks and
+    blocks that straddle the budget (B = 64: the cache fills inside the fourth block of 16 tokens) included."""
     drive(2, 64, 8, group, blocks, seed=90 + group, tag=f"gqa-block-g{group}")
 
 
 @pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 64)])
 def test_grouped_steps_on_the_vector_path(dtype, d):
     """Grouped-query decode and block steps for the shapes that take the vector-ALU attention."""
-    drive(2, 48, 6, 4, [1] * 60 + [8, 3, 8, 1], seed=170 + d, tag=f"gqa-simple-{dtype}-{d}", single_token_entry=True,
+    drive(2, 48, 6, 4, [1] * 60 + [8, 3, 8, 1, 16, 11, 16], seed=170 + d, tag=f"gqa-simple-{dtype}-{d}", single_token_entry=True,
           dtype=dtype, d=d)
 
 

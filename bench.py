@@ -567,7 +567,7 @@ def main():
         snap = [t.clone() for t in (cache.K, cache.V, cache.stats, cache.pos, cache.n_used, cache.next_slot)]
         bq, bk, bv = (x[:n_tok].transpose(0, 1).contiguous() for x in (sq, sk, sv))  # [U, n_tok, d]
         blockwise = {}
-        for bsz in (1, 2, 4, 8, 16, 32):
+        for bsz in (1, 2, 4, 8, 16, 32, 64):
             nb = n_tok // bsz
             tq, tk, tv = (x.view(U, nb, bsz, d).permute(1, 0, 2, 3).contiguous() for x in (bq, bk, bv))
             ws_b = torch.empty(roco.block_workspace_bytes(p, bsz), dtype=torch.uint8, device="cuda")
@@ -632,7 +632,37 @@ def main():
                 torch.cuda.synchronize()
                 ptimes.append(e0.elapsed_time(e1))
             del ws_pg
+            by_block = None
+            if g == 4:  # appendix A's setting: a group of 4 encoded in blocks of up to 16 tokens (64 query rows)
+                by_block = {}
+                n_b = min(128, n_tok)
+                for bsz in (1, 2, 4, 8, 16):
+                    nb = n_b // bsz
+                    tq = sq[:n_b].reshape(nb, bsz, Ug, g, d).permute(0, 2, 1, 3, 4).contiguous()  # [nb, Ug, bsz, g, d]
+                    tk = sk[:n_b, :Ug].reshape(nb, bsz, Ug, d).permute(0, 2, 1, 3).contiguous()
+                    tv = sv[:n_b, :Ug].reshape(nb, bsz, Ug, d).permute(0, 2, 1, 3).contiguous()
+                    ws_gb = torch.empty(roco.block_workspace_bytes(pg, bsz), dtype=torch.uint8, device="cuda")
+                    gbout = torch.empty((Ug, bsz, g, d), dtype=dt, device="cuda")
+                    qp0 = [torch.full((Ug,), L + i * bsz, dtype=torch.int32, device="cuda") for i in range(nb)]
+                    btimes = []
+                    for rep in range(2):
+                        for t, sn in zip((cg.K, cg.V, cg.stats, cg.pos, cg.n_used, cg.next_slot), snap):
+                            t.copy_(sn[:Ug])
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record(stream)
+                        for i in range(nb):
+                            roco.roco_encode_block_gqa(pg, bsz, g, tq[i], tk[i], tv[i], qp0[i], cg.K, cg.V, cg.stats, cg.pos,
+                                                       cg.n_used, cg.next_slot, gbout, None, None, ws_gb, stream=stream)
+                        e1.record(stream)
+                        torch.cuda.synchronize()
+                        btimes.append(e0.elapsed_time(e1))
+                    bms = min(btimes)
+                    by_block[str(bsz)] = {"tokens_per_s": cfg.batch * n_b / (bms * 1e-3), "ms_per_block_step": bms / nb}
+                    del tq, tk, tv, ws_gb, gbout
+                for v in by_block.values():
+                    v["speedup_vs_block_1"] = v["tokens_per_s"] / by_block["1"]["tokens_per_s"]
             gqa[str(g)] = {"kv_heads_per_layer": 32 // g, "units": Ug, "ms_per_token_step": ms,
+                           "encode_by_block_size": by_block,
                            "prefill_evict_ms": min(ptimes), "prefill_evict_tokens_per_s": cfg.batch * L / (min(ptimes) * 1e-3),
                            "tokens_per_s": cfg.batch / (ms * 1e-3),
                            "cache_read_GBps": Ug * B * d * 2 * 2 / (ms * 1e-3) / 1e9}

@@ -1171,7 +1171,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mix_probe(int tiles, float* si
   __syncthreads();
   const float sc = 0.1275f;
   float l0 = 0.0f, l1 = 0.0f, q0 = 0.0f, q1 = 0.0f;
-  f32x16 A0, A1, B0, B1;
+  f32x16 A0, A1, B0 = {0}, B1 = {0};
   auto step = [&](auto consume_tag, const char* p, f32x16& x0, f32x16& x1, const f32x16& y0, const f32x16& y1, int ysub) {
     constexpr bool CONSUME = decltype(consume_tag)::value != 0;
     float a0 = 0.0f, b0 = 0.0f, a1 = 0.0f, b1 = 0.0f, c0 = 0.0f, d0 = 0.0f, c1 = 0.0f, d1 = 0.0f;
@@ -1273,13 +1273,10 @@ hipError_t launch_with_output(const PrefillArgs& a, hipStream_t s) {
   constexpr int WAVES = 4;
   constexpr int kOwnQ = 32 * WAVES;
   constexpr size_t kLds = 2 * static_cast<size_t>(kTileBytes + kTileBytesV);  // 74 KiB: above the default dynamic limit
-  static bool attr_done = false;
-  if (!attr_done) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_rows_out_mfma<WAVES>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kLds)) != hipSuccess)
-      return hipErrorInvalidValue;
-    attr_done = true;
-  }
+  // set on every call: cheap, and right on whichever device is current
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_rows_out_mfma<WAVES>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kLds)) != hipSuccess)
+    return hipErrorInvalidValue;
   PrefillArgs b = a;
   b.paired = 0;
   b.pairs = (a.L_max + kOwnQ - 1) / kOwnQ;  // workgroup ids per unit

@@ -187,7 +187,8 @@ template <int S> struct StageTag { static constexpr int value = S; };
 
 __global__ __launch_bounds__(256, 2) void prefill_rows_mfma(PrefillArgs a) {
   constexpr int kOwn = Shape<4>::kOwn;
-  __shared__ __attribute__((aligned(1024))) char ring[kRingBytes];
+  constexpr int NS = 4;  // ring stages: a tile is requested three tiles of work ahead of its use
+  __shared__ __attribute__((aligned(1024))) char ring[NS * kRingTileBytes];
   int u, id;  // u counts (unit, query head) pairs: with grouped-query attention a unit has a.group heads
   if (!locate(a.units * a.group, a.pairs * a.ksplit, u, id)) return;
   const int seg = id % a.ksplit, pair_id = id / a.ksplit;  // which share of the keys, which blocks of queries
@@ -239,6 +240,7 @@ __global__ __launch_bounds__(256, 2) void prefill_rows_mfma(PrefillArgs a) {
     __syncthreads();  // the previous block has finished with the ring
     if (t_lo <= t_hi) tr.request(kbuf, ring_addr, t_lo, 0);
     if (t_lo + 1 <= t_hi) tr.request(kbuf, ring_addr, t_lo + 1, 1);
+    if (t_lo + 2 <= t_hi) tr.request(kbuf, ring_addr, t_lo + 2, 2);
     uint4 own0[kKSteps], own1[kKSteps];
     load_owned(own0, Qb, qi0, len - 1);
     load_owned(own1, Qb, qi1, len - 1);
@@ -247,11 +249,12 @@ __global__ __launch_bounds__(256, 2) void prefill_rows_mfma(PrefillArgs a) {
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     float m0 = -INFINITY, l0 = 0.0f, m1 = -INFINITY, l1 = 0.0f;
 
-    auto next_tile = [&](int t, int stage) {  // tile t has landed in `stage`; tile t + 2 is requested
-      if (t + 1 <= t_hi) wait_loads<4>();  // tile t + 1 may still be on its way
+    auto next_tile = [&](int t, int stage) {  // tile t has landed in `stage`; tile t + 3 is requested
+      if (t + 2 <= t_hi) wait_loads<8>();  // tiles t + 1 and t + 2 may still be on their way
+      else if (t + 1 <= t_hi) wait_loads<4>();
       else wait_loads<0>();
       __syncthreads();  // every wave's share of tile t is in LDS, and everybody has issued its last read of tile t - 1
-      if (t + 2 <= t_hi) tr.request(kbuf, ring_addr, t + 2, (stage + 2) % kRingStages);
+      if (t + 3 <= t_hi) tr.request(kbuf, ring_addr, t + 3, (stage + 3) % NS);
     };
 
     // ---- the rectangle: software-pipelined.  A* hold the scores of a tile's first 32 keys, B* of its last 32.
@@ -289,14 +292,16 @@ __global__ __launch_bounds__(256, 2) void prefill_rows_mfma(PrefillArgs a) {
       pending = true;
     };
     int t = t_lo;
-    for (; t + 2 < t_rect; t += 3) {
+    for (; t + 3 < t_rect; t += 4) {
       rect_tile(StageTag<0>{}, t);
       rect_tile(StageTag<1>{}, t + 1);
       rect_tile(StageTag<2>{}, t + 2);
+      rect_tile(StageTag<3>{}, t + 3);
     }
     int stage = 0;  // ring stage of tile t
     if (t < t_rect) { rect_tile(StageTag<0>{}, t); ++t; stage = 1; }
     if (t < t_rect) { rect_tile(StageTag<1>{}, t); ++t; stage = 2; }
+    if (t < t_rect) { rect_tile(StageTag<2>{}, t); ++t; stage = 3; }
     if (pending) {  // drain
       float a0 = 0.0f, b0 = 0.0f, a1 = 0.0f, b1 = 0.0f;
       auto c = consume_into(B0, B1, a0, b0, a1, b1);
@@ -307,10 +312,64 @@ __global__ __launch_bounds__(256, 2) void prefill_rows_mfma(PrefillArgs a) {
     }
 
     // ---- the tiles that touch the diagonal (or a recency window): masks decided per wave and group
+    if (w == 0 && t_hi - t < NS && t <= t_hi) {
+      // No window and at most four tiles left (the block's own 256 keys): they all fit in the ring, so the waves
+      // need not meet after every tile.  Per tile the work is uneven (the early group of a wave has run out of
+      // visible keys while its late group still has some), over the whole triangle it is even: nine half-tiles per
+      // wave.  Tiles t .. t + 2 were requested by the rectangle (or the prologue); the fourth is requested here and
+      // waited for once, after the first tile's work.  Half-tiles that only the late group still sees are taken
+      // two at a time, so that there are always two accumulator chains.
+      const int t0 = t, stage0 = stage;
+      wait_loads<0>();
+      __syncthreads();  // tiles t0 .. t0 + 2 are in LDS; everybody has issued its last read of tile t0 - 1
+      if (t0 + 3 <= t_hi) tr.request(kbuf, ring_addr, t0 + 3, (stage0 + 3) % NS);
+      const int n_sub = 2 * (t_hi - t0 + 1);
+      auto sub_ptr = [&](int sg) {
+        const int st = (stage0 + (sg >> 1)) % NS;
+        return ring + st * kRingTileBytes + (sg & 1) * (32 * kRowBytes);
+      };
+      auto update0 = [&](const f32x16& s0, int kb) {
+        if (kb + 31 <= qg0) lse_update<true>(s0, sc, kb, half, qi0, w, rb, m0, l0);
+        else lse_update<false>(s0, sc, kb, half, qi0, w, rb, m0, l0);
+      };
+      auto update1 = [&](const f32x16& s1, int kb) {
+        if (kb + 31 <= qg1) lse_update<true>(s1, sc, kb, half, qi1, w, rb, m1, l1);
+        else lse_update<false>(s1, sc, kb, half, qi1, w, rb, m1, l1);
+      };
+      auto run = [&](int sg, int sg_end) {  // half-tiles [sg, sg_end) of the triangle
+        while (sg < sg_end) {
+          const int kb = t0 * kTile + 32 * sg;
+          if (kb > qg1 + 31) break;  // wholly above the diagonal for both groups (qg0 < qg1), and so is the rest
+          f32x16 s0, s1;
+          if (kb <= qg0 + 31) {  // both groups: one fragment, two chains
+            score_tiles_ring(sub_ptr(sg), tr.frag, own0, own1, true, true, s0, s1);
+            update0(s0, kb);
+            update1(s1, kb);
+            sg += 1;
+          } else if (sg + 1 < sg_end && kb + 32 <= qg1 + 31) {  // the late group alone, two half-tiles at once
+            score_two_subs_ring(sub_ptr(sg), sub_ptr(sg + 1), tr.frag, own1, s0, s1);
+            update1(s0, kb);
+            update1(s1, kb + 32);
+            sg += 2;
+          } else {
+            score_tiles_ring(sub_ptr(sg), tr.frag, own0, own1, false, true, s0, s1);
+            update1(s1, kb);
+            sg += 1;
+          }
+        }
+      };
+      run(0, min(2, n_sub));
+      if (n_sub > 6) {
+        wait_loads<0>();
+        __syncthreads();  // the fourth tile is in LDS
+      }
+      run(2, n_sub);
+      t = t_hi + 1;
+    }
     for (; t <= t_hi; ++t) {
       next_tile(t, stage);
       const char* p = ring + stage * kRingTileBytes;
-      stage = stage == kRingStages - 1 ? 0 : stage + 1;
+      stage = stage == NS - 1 ? 0 : stage + 1;
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub) {
         const int kb = t * kTile + sub * 32;

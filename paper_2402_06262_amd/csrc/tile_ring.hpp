@@ -118,6 +118,23 @@ __device__ __forceinline__ void score_tiles_ring(const char* p, const int* frag,
   }
 }
 
+// Two 32x32 score tiles of one group of owned rows against two different half-tiles (two independent accumulator
+// chains, as above, for the stretch of the diagonal where only one of a wave's groups still has keys to see).
+__device__ __forceinline__ void score_two_subs_ring(const char* pa, const char* pb, const int* frag, const uint4* own,
+                                                    f32x16& acc_a, f32x16& acc_b) {
+  const f32x16 zero = {0};
+  auto mm = [](bf16x8 x, const uint4& y, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, __builtin_bit_cast(bf16x8, y), c, 0, 0, 0);
+  };
+#pragma unroll
+  for (int kk = 0; kk < kKSteps; ++kk) {
+    const bf16x8 fa = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(pa + frag[kk]));
+    const bf16x8 fb = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(pb + frag[kk]));
+    acc_a = mm(fa, own[kk], kk == 0 ? zero : acc_a);
+    acc_b = mm(fb, own[kk], kk == 0 ? zero : acc_b);
+  }
+}
+
 // The software-pipelined form of the above for tiles where nothing is masked: the 16 matrix instructions that fill
 // (x0, x1) from the half-tile at `p` are issued one at a time, and after each of them comes one slice of the vector
 // work that consumes the two score tiles (y0, y1) filled one step earlier -- consume(kk, g) handles scores 2 kk and

@@ -458,8 +458,9 @@ __device__ __forceinline__ void column_update(const f32x16& s, const float* lse_
 template <bool COUNT>
 __global__ __launch_bounds__(256, 2) void prefill_columns_mfma(PrefillArgs a) {
   constexpr int kOwn = Shape<4>::kOwn;
-  constexpr int kLseStages = 4;
-  __shared__ __attribute__((aligned(1024))) char ring[kRingBytes];
+  constexpr int NS = 4;          // ring stages: a tile is requested three tiles of work ahead of its use
+  constexpr int kLseStages = 8;  // the normalisers of a tile are still read while the tile after it is worked on
+  __shared__ __attribute__((aligned(1024))) char ring[NS * kRingTileBytes];
   __shared__ __attribute__((aligned(256))) float lse_s[kLseStages][4][kTile];  // [stage][wave][query of the tile]
   __shared__ __attribute__((aligned(16))) float rinv_s[COUNT ? kLseStages : 1][COUNT ? kTile : 4];  // 1 / (i + 1)
   int u, id;
@@ -510,31 +511,36 @@ __global__ __launch_bounds__(256, 2) void prefill_columns_mfma(PrefillArgs a) {
     const int t_rect_lo = (j0 + kOwn - 1 + w + kTile - 1) / kTile;
     auto request = [&](int i) {  // five loads per wave
       const int t = t_last - i;
-      tr.request(qbuf, ring_addr, t, i % kRingStages);
+      tr.request(qbuf, ring_addr, t, i % NS);
       load4_to_lds(lbuf, lse_addr + (i % kLseStages) * (4 * kTile * 4), lane * 4, __builtin_amdgcn_readfirstlane(t * kTile * 4));
     };
     __syncthreads();  // the previous block has finished with the ring
     if (0 < n) request(0);
     if (1 < n) request(1);
+    if (2 < n) request(2);
     uint4 own0[kKSteps], own1[kKSteps];
     load_owned(own0, Kb, kj0, len - 1);
     load_owned(own1, Kb, kj1, len - 1);
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the owned rows are in before the loop (see prefill_rows_mfma)
     float s1a = 0.0f, s2a = 0.0f, s1b = 0.0f, s2b = 0.0f;
 
-    auto next_tile = [&](int i) {  // the i-th tile has landed; the (i + 2)-th is requested
+    auto put_rinv = [&](int i) {
       if (COUNT && threadIdx.x < kTile)
         rinv_s[COUNT ? i % kLseStages : 0][threadIdx.x] =
             1.0f / static_cast<float>((t_last - i) * kTile + static_cast<int>(threadIdx.x) + 1);
-      if (i + 1 < n) wait_loads<5>();  // the next tile may still be on its way
+    };
+    auto next_tile = [&](int i) {  // the i-th tile has landed; the (i + 3)-th is requested
+      put_rinv(i);
+      if (i + 2 < n) wait_loads<10>();  // the next two tiles may still be on their way
+      else if (i + 1 < n) wait_loads<5>();
       else wait_loads<0>();
       __syncthreads();
-      if (i + 2 < n) request(i + 2);
+      if (i + 3 < n) request(i + 3);
     };
     auto plain_tile = [&](int i) {
       const int t = t_last - i;
       next_tile(i);
-      const char* p = ring + (i % kRingStages) * kRingTileBytes;
+      const char* p = ring + (i % NS) * kRingTileBytes;
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub) {
         const int ib = t * kTile + sub * 32;
@@ -609,10 +615,11 @@ __global__ __launch_bounds__(256, 2) void prefill_columns_mfma(PrefillArgs a) {
       pending_i = ii;
     };
     auto is_rect = [&](int ii) { return ii < n && t_last - ii >= t_rect_lo; };
-    for (int stage = i % kRingStages;;) {  // the ring stage of a tile follows from its index; the code wants it static
+    for (int stage = i % NS;;) {  // the ring stage of a tile follows from its index; the code wants it static
       if (stage == 0) { if (!is_rect(i)) break; rect_tile(StageTag<0>{}, i++); stage = 1; }
       if (stage == 1) { if (!is_rect(i)) break; rect_tile(StageTag<1>{}, i++); stage = 2; }
-      if (stage == 2) { if (!is_rect(i)) break; rect_tile(StageTag<2>{}, i++); stage = 0; }
+      if (stage == 2) { if (!is_rect(i)) break; rect_tile(StageTag<2>{}, i++); stage = 3; }
+      if (stage == 3) { if (!is_rect(i)) break; rect_tile(StageTag<3>{}, i++); stage = 0; }
     }
     if (pending) {  // drain
       const float* lt = &lse_s[pending_i % kLseStages][wave][32];
@@ -622,6 +629,63 @@ __global__ __launch_bounds__(256, 2) void prefill_columns_mfma(PrefillArgs a) {
       column_update<true, COUNT>(B1, lt, rt, sc, ib, half, kj1, len, w, rb, s1b, s2b);
     }
     // ---- the tiles on the diagonal (or inside a recency window)
+    if (!COUNT && w == 0 && i < n && n - i <= NS) {  // (the counting variant has no registers to spare for it)
+      // No window and at most four tiles left (the queries at the block's own 256 positions): they all fit in the
+      // ring, so the waves need not meet after every tile; see the same stretch of prefill_rows_mfma.  Half-tiles
+      // are taken from the highest query position down; those that only the early group of keys still reaches are
+      // taken two at a time.  The walk's tiles i .. i + 2 have been requested; the fourth is requested here and
+      // waited for once, after the first tile's work.
+      const int i0 = i;
+      put_rinv(i0);
+      if (i0 + 1 < n) put_rinv(i0 + 1);
+      if (i0 + 2 < n) put_rinv(i0 + 2);
+      wait_loads<0>();
+      __syncthreads();  // tiles i0 .. i0 + 2 are in LDS; everybody is done with the stage the fourth tile takes
+      if (i0 + 3 < n) {
+        request(i0 + 3);
+        put_rinv(i0 + 3);
+      }
+      const int n_half = 2 * (n - i0);
+      const int ib_top = (t_last - i0) * kTile + 32;  // half-tile h holds the queries from ib_top - 32 h on
+      auto tile_ptr = [&](int h) { return ring + ((i0 + (h >> 1)) % NS) * kRingTileBytes + (1 - (h & 1)) * (32 * kRowBytes); };
+      auto update = [&](const f32x16& c, int h, int kg, int kj, float& s1, float& s2) {
+        const int ib = ib_top - 32 * h;
+        const int st = (i0 + (h >> 1)) % kLseStages, off = (1 - (h & 1)) * 32;
+        const float* lt = &lse_s[st][wave][off];
+        const float* rt = &rinv_s[COUNT ? st : 0][COUNT ? off : 0];
+        if (ib + 31 < len && ib >= kg + 31) column_update<true, COUNT>(c, lt, rt, sc, ib, half, kj, len, w, rb, s1, s2);
+        else column_update<false, COUNT>(c, lt, rt, sc, ib, half, kj, len, w, rb, s1, s2);
+      };
+      auto run = [&](int h, int h_end) {
+        while (h < h_end) {
+          const int ib = ib_top - 32 * h;
+          if (ib + 31 < kg0) break;  // no query of this half-tile, or of any later one, reaches the wave's keys
+          f32x16 c0, c1;
+          if (ib + 31 >= kg1) {  // both groups: one fragment, two chains
+            score_tiles_ring(tile_ptr(h), tr.frag, own0, own1, true, true, c0, c1);
+            update(c0, h, kg0, kj0, s1a, s2a);
+            update(c1, h, kg1, kj1, s1b, s2b);
+            h += 1;
+          } else if (h + 1 < h_end && ib - 1 >= kg0) {  // the early group alone, two half-tiles at once
+            score_two_subs_ring(tile_ptr(h), tile_ptr(h + 1), tr.frag, own0, c0, c1);
+            update(c0, h, kg0, kj0, s1a, s2a);
+            update(c1, h + 1, kg0, kj0, s1a, s2a);
+            h += 2;
+          } else {
+            score_tiles_ring(tile_ptr(h), tr.frag, own0, own1, true, false, c0, c1);
+            update(c0, h, kg0, kj0, s1a, s2a);
+            h += 1;
+          }
+        }
+      };
+      run(0, min(2, n_half));
+      if (n_half > 6) {
+        wait_loads<0>();
+        __syncthreads();  // the fourth tile is in LDS
+      }
+      run(2, n_half);
+      i = n;
+    }
     while (i < n) plain_tile(i++);
 
     s1a += __shfl_xor(s1a, 32, kWave);

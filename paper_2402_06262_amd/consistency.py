@@ -11,7 +11,7 @@ runs in the library's kernels; this module only steps the two caches side by sid
 """
 from __future__ import annotations
 
-from typing import Dict, Iterable, Sequence, Tuple
+from typing import Optional, Dict, Iterable, Sequence, Tuple
 
 from . import binding as roco
 
@@ -45,11 +45,12 @@ class _Run:
 
 def consistency_study(Q, K, V, prompt_len: int, rates: Sequence[float] = (0.3, 0.4, 0.5, 0.6),
                       importances: Iterable[str] = ("mas", "aas"), sample_every: int = 8,
-                      sinks: int = 0) -> Dict[str, Dict[float, Tuple[float, int]]]:
+                      sinks: int = 0, counts: Optional[dict] = None) -> Dict[str, Dict[float, Tuple[float, int]]]:
     """Q, K, V: device tensors [units, T, d] (bf16 or fp32), the first `prompt_len` rows are the prompt.
 
     Budget for rate r is round(r * T).  Returns {importance: {rate: (mean Jaccard, positions compared)}} over the
-    sampled positions t >= prompt_len at which the full cache holds more than B tokens.
+    sampled positions t >= prompt_len at which the full cache holds more than B tokens.  A dict passed as `counts`
+    receives the raw set sizes behind every ratio: counts[(importance, rate, t)] = (|A and B|, |A or B|) per unit.
     """
     import torch
     U, T, d = Q.shape
@@ -102,6 +103,8 @@ def consistency_study(Q, K, V, prompt_len: int, rates: Sequence[float] = (0.3, 0
             c = run.cache
             roco.roco_set_overlap(fc.pos, mask, fc.n_used, c.pos, None, c.n_used, T, inter, union)
             i_h, u_h = inter.cpu().numpy(), union.cpu().numpy()  # the report: mean ratio over units and positions
+            if counts is not None:
+                counts[(name, r, t)] = (i_h.copy(), u_h.copy())
             total[(name, r)] += float((i_h / u_h).sum())
             count[(name, r)] += U
     torch.cuda.synchronize()

@@ -23,6 +23,7 @@ constexpr int kGatherRows = 64;  // cache rows per gather workgroup
 
 __global__ __launch_bounds__(kSelThreads) void prefill_select(PrefillArgs a) {
   constexpr int NT = kSelThreads;
+  extern __shared__ uint32_t lds_keys[];  // [2][L_max] ranking keys when L_max <= kMaxDecodeBudgetLds
   __shared__ uint32_t sel_sh[kSelectLdsWords];
   __shared__ uint32_t scan_sh[NT / kWave + 1];
   __shared__ unsigned long long best_sh[NT / kWave];
@@ -32,8 +33,10 @@ __global__ __launch_bounds__(kSelThreads) void prefill_select(PrefillArgs a) {
   const size_t ubase = static_cast<size_t>(u) * a.L_max;
   const float* acc = a.acc + ubase;
   const float* acc2 = a.acc2 + ubase;
-  uint32_t* var_key = a.var_key + ubase;
-  uint32_t* mas_key = a.mas_key + ubase;
+  // every radix pass reads every key: in LDS they cost a fraction of a trip to the L2 each
+  const bool keys_in_lds = a.L_max <= kMaxDecodeBudgetLds;
+  uint32_t* var_key = keys_in_lds ? lds_keys : a.var_key + ubase;
+  uint32_t* mas_key = keys_in_lds ? lds_keys + a.L_max : a.mas_key + ubase;
   float* oacc = a.stats + static_cast<size_t>(u) * 3 * B;
   float* oacc2 = oacc + B;
   float* ocnt = oacc2 + B;
@@ -238,7 +241,9 @@ hipError_t launch_select_retained(const DecodeArgs& a, int keep, int32_t* mask, 
 hipError_t launch_prefill_select_compact(int dtype, int head_dim, const PrefillArgs& a, hipStream_t s) {
   {
     ProfScope ps(kProfPrefillSelect, s);
-    hipLaunchKernelGGL(prefill_select, dim3(a.units), dim3(kSelThreads), 0, s, a);
+    const size_t key_lds = key_lds_bytes(a.L_max);  // the budget's keys for the first decode victim fit too: B < L_max
+    if (!allow_key_lds(reinterpret_cast<const void*>(prefill_select), key_lds)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(prefill_select, dim3(a.units), dim3(kSelThreads), key_lds, s, a);
   }
   ProfScope ps(kProfPrefillGather, s);
   const int row_bytes = head_dim * (dtype == kBF16 ? 2 : 4);

@@ -69,6 +69,23 @@ def test_block_steps_on_a_random_shape(seed):
         prompt = [0] * units
     else:
         prompt = [int(x) for x in r.integers(1, 2 * B, size=units)]
-    blocks = [int(x) for x in r.integers(1, 33, size=int(r.integers(2, 7)))]
+    blocks = [int(x) for x in r.integers(1, 65 if seed % 2 else 33, size=int(r.integers(2, 7)))]  # one and two tiles of query rows
+    blocks = [min(b, B) for b in blocks]
     TB.drive(units, d, B, s, prompt, blocks, seed=5000 + seed, recency=bool(r.integers(2)), tag=f"random-block-{seed}",
              dtype=dtype)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_grouped_blocks_on_a_random_shape(seed):
+    """Grouped-query blocks of random sizes, block x group up to 64 query rows, with and without the recency bias."""
+    r = np.random.default_rng([980, seed])
+    dtype, d = [("bf16", 128), ("bf16", 128), ("f32", 64), ("bf16", 64)][r.integers(4)]
+    group = int([2, 3, 4, 5, 8, 16][r.integers(6)])
+    units = int(r.integers(1, 4))
+    B = 4 * int(r.integers(12, 60))
+    s = int(r.integers(1, B + 1))
+    cap = min(64 // group, B)
+    blocks = [int(x) for x in r.integers(1, cap + 1, size=int(r.integers(4, 12)))] + [cap] * int(B // cap + 2)
+    r.shuffle(blocks)
+    TG.drive(units, B, s, group, blocks, seed=6000 + seed, recency=bool(r.integers(2)), tag=f"random-gqa-block-{seed}",
+             dtype=dtype, d=d)

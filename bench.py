@@ -284,6 +284,9 @@ def main():
     ap.add_argument("--cpu-steps", type=int, default=512)
     ap.add_argument("--with-out", action="store_true", help="also produce the prefill attention output O")
     ap.add_argument("--no-blockwise", action="store_true", help="skip the block-wise evict-and-encode table")
+    ap.add_argument("--block-sizes", default="1,2,4,8,16,32,64", help="block sizes of the block-wise table")
+    ap.add_argument("--gqa-groups", default="1,4,8", help="group sizes of the grouped-query table")
+    ap.add_argument("--gqa-block-sizes", default="1,2,4,8,16", help="block sizes encoded with a group of 4")
     ap.add_argument("--no-two-streams", action="store_true",
                     help="skip the decode loop with the batch split over two HIP streams")
     ap.add_argument("--no-consistency", action="store_true", help="skip the synthetic consistency study")
@@ -567,7 +570,7 @@ def main():
         snap = [t.clone() for t in (cache.K, cache.V, cache.stats, cache.pos, cache.n_used, cache.next_slot)]
         bq, bk, bv = (x[:n_tok].transpose(0, 1).contiguous() for x in (sq, sk, sv))  # [U, n_tok, d]
         blockwise = {}
-        for bsz in (1, 2, 4, 8, 16, 32, 64):
+        for bsz in [int(x) for x in args.block_sizes.split(",") if x.strip()]:
             nb = n_tok // bsz
             tq, tk, tv = (x.view(U, nb, bsz, d).permute(1, 0, 2, 3).contiguous() for x in (bq, bk, bv))
             ws_b = torch.empty(roco.block_workspace_bytes(p, bsz), dtype=torch.uint8, device="cuda")
@@ -588,15 +591,15 @@ def main():
             ms = min(times)
             blockwise[str(bsz)] = {"tokens_per_s": cfg.batch * n_tok / (ms * 1e-3), "ms_per_block_step": ms / nb}
             del tq, tk, tv, ws_b
-        base = blockwise["1"]["tokens_per_s"]
-        for v in blockwise.values():
-            v["speedup_vs_block_1"] = v["tokens_per_s"] / base
+        if "1" in blockwise:
+            for v in blockwise.values():
+                v["speedup_vs_block_1"] = v["tokens_per_s"] / blockwise["1"]["tokens_per_s"]
 
         # Grouped-query attention: the same 32 query heads per sequence over 32 / g key/value heads (g = 4 is the
         # Zephyr-style shape); one token per step.  The start state of each key/value head is a compressed cache.
         gqa = {}
         n_g = min(64, n_tok)
-        for g in (1, 4, 8):
+        for g in [int(x) for x in args.gqa_groups.split(",") if x.strip()]:
             Ug = U // g
             pg = roco.RocoParams(Ug, d, B, s, roco.ROCO_BF16)
             cg = roco.alloc_cache(pg)
@@ -636,7 +639,7 @@ def main():
             if g == 4:  # appendix A's setting: a group of 4 encoded in blocks of up to 16 tokens (64 query rows)
                 by_block = {}
                 n_b = min(128, n_tok)
-                for bsz in (1, 2, 4, 8, 16):
+                for bsz in [int(x) for x in args.gqa_block_sizes.split(",") if x.strip()]:
                     nb = n_b // bsz
                     tq = sq[:n_b].reshape(nb, bsz, Ug, g, d).permute(0, 2, 1, 3, 4).contiguous()  # [nb, Ug, bsz, g, d]
                     tk = sk[:n_b, :Ug].reshape(nb, bsz, Ug, d).permute(0, 2, 1, 3).contiguous()
@@ -659,8 +662,9 @@ def main():
                     bms = min(btimes)
                     by_block[str(bsz)] = {"tokens_per_s": cfg.batch * n_b / (bms * 1e-3), "ms_per_block_step": bms / nb}
                     del tq, tk, tv, ws_gb, gbout
-                for v in by_block.values():
-                    v["speedup_vs_block_1"] = v["tokens_per_s"] / by_block["1"]["tokens_per_s"]
+                if "1" in by_block:
+                    for v in by_block.values():
+                        v["speedup_vs_block_1"] = v["tokens_per_s"] / by_block["1"]["tokens_per_s"]
             gqa[str(g)] = {"kv_heads_per_layer": 32 // g, "units": Ug, "ms_per_token_step": ms,
                            "encode_by_block_size": by_block,
                            "prefill_evict_ms": min(ptimes), "prefill_evict_tokens_per_s": cfg.batch * L / (min(ptimes) * 1e-3),

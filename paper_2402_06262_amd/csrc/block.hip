@@ -352,6 +352,7 @@ __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
 #pragma unroll
     for (int t2 = 0; t2 < NQT; ++t2) {
       const int q = kQ * t2 + qi;
+      if (q >= b) continue;  // lanes beyond the step's query rows repeated its last query: nothing of theirs is kept
       const float m1 = merge_m[q], l1 = merge_l[q];
       const float M = fmaxf(m[t2], m1);
       const float w0 = (m[t2] > -INFINITY) ? fast_exp2(m[t2] - M) : 0.0f;
@@ -472,7 +473,7 @@ __global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
   const float* pl = a.part_l + static_cast<size_t>(u) * S * QR;
   const float* po = a.part_o + static_cast<size_t>(u) * S * QR * D;
 
-  if (tid < QR) {  // per query: merge the splits' normalisers in split order
+  if (tid < nq) {  // per query row: merge the splits' normalisers in split order
     float M = -INFINITY;
     for (int s = 0; s < S; ++s) M = fmaxf(M, pm[s * QR + tid]);
     float L = 0.0f;

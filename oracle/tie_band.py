@@ -7,7 +7,7 @@ index sets must be identical unless the oracle's own score gap lies inside the
 tolerance band
 
     MAS:       |gap| <= rel * MAS
-    variance:  |gap| <= rel * (Acc2/Count + MAS^2)
+    variance:  |gap| <= rel * (Acc2/Count + MAS^2)          rel = 1e-5
 
 (the variance band is stated on the two terms that cancel in
 Acc2/Count - MAS^2, section 4.3 of the paper, because the difference itself can
@@ -28,8 +28,13 @@ import numpy as np
 
 F64 = np.float64
 
+# Relative width of the band.  The statistics are fp32 sums of up to a few tens of thousands of probabilities, each
+# itself good to a few ulp: rounding error accumulates like sqrt(N) * 2^-24, about 1e-5 for N = 32768.  (Every
+# differing decision of the GPU suite lies inside 1e-6; at 1e-7, two ulp, some of them no longer do.)
+REL = 1e-5
 
-def bands_for(policy, acc, acc2, count, rel: float = 1e-3) -> Tuple[np.ndarray, np.ndarray]:
+
+def bands_for(policy, acc, acc2, count, rel: float = REL) -> Tuple[np.ndarray, np.ndarray]:
     """(eps_importance, eps_scope_key) per token for an eviction policy (an object with `importance` and
     `scope_kind` strings, or None for RoCo): scores that are sums of probabilities get the relative band,
     scores that are positions are exact."""
@@ -47,7 +52,7 @@ def bands_for(policy, acc, acc2, count, rel: float = 1e-3) -> Tuple[np.ndarray, 
     return eps_m, eps_v
 
 
-def bands(acc, acc2, count, rel: float = 1e-3) -> Tuple[np.ndarray, np.ndarray]:
+def bands(acc, acc2, count, rel: float = REL) -> Tuple[np.ndarray, np.ndarray]:
     """(eps_mas, eps_var) per token."""
     acc, acc2, count = (np.asarray(a, dtype=F64) for a in (acc, acc2, count))
     mas = acc / count

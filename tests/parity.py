@@ -119,7 +119,7 @@ _IMPORTANCE = {"mas": 0, "aas": 1, "oldest": 2, "ltas": 3, "aqas": 4}
 # threshold can fall on either side in fp32 and in float64, so the two counts of a token may differ by the number of
 # such near-threshold events it has seen.  The harness keeps that number per slot next to the oracle state
 # (`state.slack`), compares the counts within it and uses it as the tie band of the eviction decision.
-AQAS_DELTA = 1e-3
+AQAS_DELTA = 1e-4
 
 
 def _is_aqas(policy) -> bool:

@@ -44,3 +44,5 @@ def pytest_terminal_summary(terminalreporter):
     for dtype, (used, strict) in parity.WORST_OUT.items():
         tr.write_line(f"worst attention-output error, {dtype}: {used:.3f} of the tolerance with the floor rms(o); "
                       f"{strict:.3f} with the floor 1e-3 * rms(o)")
+    tr.write_line(f"worst Acc / Acc2 error: {parity.WORST_STAT[0]:.3g} relative (tolerance {parity.STAT_RTOL:g}, "
+                  f"floor {parity.STAT_FLOOR:g})")

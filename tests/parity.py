@@ -3,7 +3,7 @@
 Tolerances:
   * attention outputs: |g - o| <= tol * max(|o|, rms(o)) per vector, tol = 1e-3 (fp32 storage) or 2e-2
     (bf16 storage, whose rounding alone is 2^-9 relative);
-  * Acc, Acc2:        |g - o| <= 1e-3 * max(|o|, 1e-6);  Count, pos, n_used, copied K/V rows: exact;
+  * Acc, Acc2:        |g - o| <= 1e-4 * max(|o|, 1e-6);  Count, pos, n_used, copied K/V rows: exact;
   * eviction decisions: identical index sets, unless the oracle's own gap lies inside the tie band
     (oracle/tie_band.py); such declared ties are counted, and the oracle adopts the library's choice so
     that later steps stay comparable.
@@ -21,7 +21,7 @@ import paper_2402_06262_amd as roco
 from oracle import roco_oracle as orc
 from oracle import tie_band
 
-STAT_RTOL = 1e-3
+STAT_RTOL = 1e-4  # fp32 sums of probabilities against float64: the worst of a full GPU run is 1.1e-5
 STAT_FLOOR = 1e-6
 OUT_RTOL = {"f32": 1e-3, "bf16": 2e-2}
 
@@ -65,9 +65,14 @@ def assert_out_close(g: np.ndarray, o: np.ndarray, dtype: str, what: str):
                           f"{float(np.max(np.abs(g - o) / np.maximum(tol, 1e-300))):.3g}"
 
 
+WORST_STAT = [0.0]  # largest |g - o| / max(|o|, STAT_FLOOR) of a run, printed at the end of a GPU run
+
+
 def assert_stat_close(g: np.ndarray, o: np.ndarray, what: str):
     g, o = np.asarray(g, np.float64), np.asarray(o, np.float64)
     tol = STAT_RTOL * np.maximum(np.abs(o), STAT_FLOOR)
+    if o.size:
+        WORST_STAT[0] = max(WORST_STAT[0], float(np.max(np.abs(g - o) / np.maximum(np.abs(o), STAT_FLOOR))))
     bad = np.abs(g - o) > tol
     assert not bad.any(), f"{what}: {int(bad.sum())} of {o.size} outside tolerance; worst rel = " \
                           f"{float(np.max(np.abs(g - o) / np.maximum(np.abs(o), STAT_FLOOR))):.3g}"

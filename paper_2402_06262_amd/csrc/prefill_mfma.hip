@@ -1021,6 +1021,212 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_columns_gqa_pow2_mfma(P
   }
 }
 
+// The grouped column pass on the tile ring, for G = 2, 4, 8, 16 heads and the sum-of-squares second statistic: the
+// shape of prefill_columns_mfma (keys owned in groups w and 7 - w, query tiles walked downwards through a four-stage
+// ring filled by loads that go straight to LDS, the rectangle software-pipelined on four accumulators) with the tile
+// composition of prefill_columns_gqa_pow2_mfma (64 / G query positions for all G heads, the heads of a position in G
+// consecutive accumulator registers of a lane).  Which (head, position) a tile row holds is a constant of the lane
+// that loads it, so the gather over the G query arrays costs nothing: it is the lane's buffer offset.  In the
+// rectangle the head sum of a position is carried over the G / 2 slices of the pipelined step that hold its heads.
+// The tiles near the diagonal and the ragged end of the prompt take the plain form, one barrier per tile.
+template <int G>
+__global__ __launch_bounds__(256, 2) void prefill_columns_gqa_ring(PrefillArgs a) {
+  using GR = GroupedRows<G>;
+  constexpr int kOwn = Shape<4>::kOwn;
+  constexpr int QT = GR::kPerTile, QS = GR::kPerSub;
+  constexpr int NS = 4;          // ring stages
+  constexpr int kLseStages = 8;  // see prefill_columns_mfma
+  static_assert(G == 2 || G == 4 || G == 8 || G == 16, "the heads of a position fill whole pairs of registers");
+  __shared__ __attribute__((aligned(1024))) char ring[NS * kRingTileBytes];
+  __shared__ __attribute__((aligned(256))) float lse_s[kLseStages][4][kTile];  // [stage][wave][row of the tile]
+  int u, id;
+  if (!locate(a.units, a.pairs * a.qsplit, u, id)) return;
+  const int seg = id % a.qsplit, pair_id = id / a.qsplit;
+  float* const out1 = seg == 0 ? a.acc : reinterpret_cast<float*>(a.var_key);    // second share: see sum_query_shares
+  float* const out2 = seg == 0 ? a.acc2 : reinterpret_cast<float*>(a.mas_key);
+  const int len = a.len[u];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int half = lane >> 5;
+  TileRing tr;
+  tr.init();
+  const int wave = tr.wave;
+  const uint32_t ring_addr = lds_address(ring);
+  const uint32_t lse_addr = lds_address(&lse_s[0][wave][0]);
+  const size_t ubase = static_cast<size_t>(u) * a.L_max;
+  const char* Kb = static_cast<const char*>(a.K) + ubase * kRowBytes;
+  const char* Qu = static_cast<const char*>(a.Q) + static_cast<size_t>(u) * G * a.L_max * kRowBytes;  // [G][L_max][d]
+  // (the launcher checks that G * L_max rows fit a 32-bit byte offset; rows past a head's prompt are masked below)
+  const v4i32 qbuf = make_buffer(Qu, static_cast<uint32_t>(G) * static_cast<uint32_t>(a.L_max) * kRowBytes);
+  const v4i32 lbuf = make_buffer(a.lse + static_cast<size_t>(u) * G * a.L_max,
+                                 static_cast<uint32_t>(G) * static_cast<uint32_t>(a.L_max) * 4u);
+  // this lane's four rows of a tile and its row of the normalisers: head and local position are fixed
+  int qoff[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = 16 * wave + 4 * i + (lane >> 4);
+    int ql, h;
+    GR::locate(r, ql, h);
+    qoff[i] = (h * a.L_max + ql) * kRowBytes + (((lane & 15) ^ (r & 15)) << 4);
+  }
+  int loff;
+  {
+    int ql, h;
+    GR::locate(lane, ql, h);
+    loff = (h * a.L_max + ql) * 4;
+  }
+  const float sc = a.scale_log2;
+  const int w = a.recency_window;
+  const float rb = a.recency_bias_log2;
+  const int n_blocks = (len + kOwn - 1) / kOwn;
+  if (a.paired ? 2 * pair_id > n_blocks - 1 : pair_id >= n_blocks) return;  // nothing left for this id
+
+  for (int pass = 0; pass < 2; ++pass) {  // one long and one short block of keys per workgroup, the long one first
+    int blk;
+    if (a.paired) {
+      blk = pass == 0 ? pair_id : n_blocks - 1 - pair_id;
+      if (blk < pair_id || (pass == 1 && blk == pair_id)) break;
+    } else {
+      if (pass == 1) break;
+      blk = pair_id;
+    }
+    const int j0 = blk * kOwn;
+    const int kg0 = j0 + 32 * wave, kg1 = j0 + 32 * (7 - wave);  // first key of this wave's two groups (kg0 < kg1)
+    const int kj0 = kg0 + (lane & 31), kj1 = kg1 + (lane & 31);
+    int t_first = j0 / QT;  // first tile with a query position >= j0
+    int t_last = (len - 1) / QT;
+    if (a.qsplit > 1) {
+      const int per = (t_last - t_first + a.qsplit) / a.qsplit;
+      t_first += seg * per;
+      t_last = min(t_last, t_first + per - 1);
+    }
+    const int n = t_last - t_first + 1;  // the i-th tile of the walk is t_last - i
+    // tiles from t_rect_lo on lie past every key of the block and outside every recency window
+    const int t_rect_lo = (j0 + kOwn - 1 + w + QT - 1) / QT;
+    auto request = [&](int i) {  // five loads per wave
+      const int t = t_last - i;
+      const uint32_t dst = ring_addr + (i % NS) * kRingTileBytes + wave * 4096;
+      const int soff = __builtin_amdgcn_readfirstlane(t * QT * kRowBytes);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) load16_to_lds(qbuf, dst + k * 1024, qoff[k], soff);
+      load4_to_lds(lbuf, lse_addr + (i % kLseStages) * (4 * kTile * 4), loff, __builtin_amdgcn_readfirstlane(t * QT * 4));
+    };
+    __syncthreads();  // the previous block has finished with the ring
+    if (0 < n) request(0);
+    if (1 < n) request(1);
+    if (2 < n) request(2);
+    uint4 own0[kKSteps], own1[kKSteps];
+    load_owned(own0, Kb, kj0, len - 1);
+    load_owned(own1, Kb, kj1, len - 1);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the owned rows are in before the loop
+    float s1a = 0.0f, s2a = 0.0f, s1b = 0.0f, s2b = 0.0f;
+
+    auto next_tile = [&](int i) {  // the i-th tile has landed; the (i + 3)-th is requested
+      if (i + 2 < n) wait_loads<10>();
+      else if (i + 1 < n) wait_loads<5>();
+      else wait_loads<0>();
+      __syncthreads();
+      if (i + 3 < n) request(i + 3);
+    };
+    auto plain_tile = [&](int i) {
+      const int t = t_last - i;
+      next_tile(i);
+      const char* p = ring + (i % NS) * kRingTileBytes;
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+        const int ib = t * QT + sub * QS;  // first query position of the sub-tile; its last one is ib + QS - 1
+        const bool do0 = ib + QS - 1 >= kg0, do1 = ib + QS - 1 >= kg1;  // some query reaches the keys
+        if (!do0) continue;
+        f32x16 c0, c1;
+        score_tiles_ring(p + sub * (32 * kRowBytes), tr.frag, own0, own1, do0, do1, c0, c1);
+        const bool whole = ib + QS - 1 < len;  // no ragged end
+        const float* lt = &lse_s[i % kLseStages][wave][sub * 32];
+        if (whole && ib >= kg0 + 31 + w) column_update_grouped<true, G>(c0, lt, sc, ib, half, kj0, len, w, rb, a.pol, s1a, s2a);
+        else column_update_grouped<false, G>(c0, lt, sc, ib, half, kj0, len, w, rb, a.pol, s1a, s2a);
+        if (do1) {
+          if (whole && ib >= kg1 + 31 + w) column_update_grouped<true, G>(c1, lt, sc, ib, half, kj1, len, w, rb, a.pol, s1b, s2b);
+          else column_update_grouped<false, G>(c1, lt, sc, ib, half, kj1, len, w, rb, a.pol, s1b, s2b);
+        }
+      }
+    };
+
+    int i = 0;
+    while (i < n && (t_last - i) * QT + QT - 1 >= len) plain_tile(i++);  // the ragged end of the prompt
+
+    // ---- the rectangle: software-pipelined.  A* hold the scores of a tile's first 32 rows, B* of its last 32.
+    f32x16 A0, A1, B0, B1;
+    bool pending = false;
+    int pending_i = 0;
+    constexpr float kInvG = 1.0f / static_cast<float>(G);
+    auto step = [&](auto consume_tag, const char* p, f32x16& x0, f32x16& x1, const f32x16& y0, const f32x16& y1, int yi,
+                    int ysub) {
+      constexpr bool CONSUME = decltype(consume_tag)::value != 0;
+      float4 lv[4];
+      if (CONSUME) {
+        const float* lt = &lse_s[yi % kLseStages][wave][ysub * 32 + 4 * half];
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) lv[g4] = *reinterpret_cast<const float4*>(lt + 8 * g4);
+      }
+      float a1 = 0.0f, a2 = 0.0f, c1 = 0.0f, c2 = 0.0f;  // sums of the head-mean and of its square, per key group
+      float ha = 0.0f, hc = 0.0f;                        // head sum of the position under way, per key group
+      auto comp = [](const float4& v, int e) { return e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w; };
+      auto consume = [&](int kk, int g) {
+        const int r = 2 * kk;  // registers r and r + 1: two heads of one position (G consecutive registers each)
+        const f32x16& y = g == 0 ? y0 : y1;
+        float& hs = g == 0 ? ha : hc;
+        float& sum1 = g == 0 ? a1 : c1;
+        float& sum2 = g == 0 ? a2 : c2;
+        const float pa = fast_exp2(fmaf(y[r], sc, -comp(lv[r >> 2], r & 3)));
+        const float pb = fast_exp2(fmaf(y[r + 1], sc, -comp(lv[r >> 2], (r & 3) + 1)));
+        if (r % G == 0) hs = pa + pb;
+        else hs += pa + pb;
+        if ((r + 2) % G == 0) {  // the position's last two heads
+          const float pbar = hs * kInvG;
+          sum1 += pbar;
+          sum2 = fmaf(pbar, pbar, sum2);
+        }
+      };
+      auto pin = [&]() { asm volatile("" : "+v"(a1), "+v"(a2), "+v"(c1), "+v"(c2), "+v"(ha), "+v"(hc)); };
+      fill_and_consume<CONSUME>(p, tr.frag, own0, own1, x0, x1, consume, pin);
+      if (CONSUME) {
+        s1a += a1; s2a += a2;
+        s1b += c1; s2b += c2;
+      }
+    };
+    auto rect_tile = [&](auto stage, int ii) {
+      constexpr int S = decltype(stage)::value;
+      next_tile(ii);
+      const char* p = ring + S * kRingTileBytes;
+      if (pending) step(StageTag<1>{}, p, A0, A1, B0, B1, pending_i, 1);
+      else step(StageTag<0>{}, p, A0, A1, B0, B1, 0, 0);
+      step(StageTag<1>{}, p + 32 * kRowBytes, B0, B1, A0, A1, ii, 0);
+      pending = true;
+      pending_i = ii;
+    };
+    auto is_rect = [&](int ii) { return ii < n && t_last - ii >= t_rect_lo; };
+    for (int stage = i % NS;;) {
+      if (stage == 0) { if (!is_rect(i)) break; rect_tile(StageTag<0>{}, i++); stage = 1; }
+      if (stage == 1) { if (!is_rect(i)) break; rect_tile(StageTag<1>{}, i++); stage = 2; }
+      if (stage == 2) { if (!is_rect(i)) break; rect_tile(StageTag<2>{}, i++); stage = 3; }
+      if (stage == 3) { if (!is_rect(i)) break; rect_tile(StageTag<3>{}, i++); stage = 0; }
+    }
+    if (pending) {  // drain: the last 32 rows of the last rectangle tile
+      const float* lt = &lse_s[pending_i % kLseStages][wave][32];
+      const int ib = (t_last - pending_i) * QT + QS;
+      column_update_grouped<true, G>(B0, lt, sc, ib, half, kj0, len, w, rb, a.pol, s1a, s2a);
+      column_update_grouped<true, G>(B1, lt, sc, ib, half, kj1, len, w, rb, a.pol, s1b, s2b);
+    }
+    // ---- the tiles near the diagonal (or inside a recency window)
+    while (i < n) plain_tile(i++);
+
+    s1a += __shfl_xor(s1a, 32, kWave);
+    s2a += __shfl_xor(s2a, 32, kWave);
+    s1b += __shfl_xor(s1b, 32, kWave);
+    s2b += __shfl_xor(s2b, 32, kWave);
+    if (half == 0 && kj0 < len) { out1[ubase + kj0] = s1a; out2[ubase + kj0] = s2a; }
+    if (half == 0 && kj1 < len) { out1[ubase + kj1] = s1b; out2[ubase + kj1] = s2b; }
+  }
+}
+
 // Row pass with few units: the keys of every block of queries are shared by two workgroups (PrefillArgs::ksplit = 2);
 // the second one leaves its log-sum-exp in the plane the column pass will overwrite later, and this kernel merges
 // the two: log2(2^a + 2^b).
@@ -1353,6 +1559,20 @@ int columns_query_shares(const PrefillArgs& a, int pairs) {
 template <int WAVES>
 void launch_columns_grouped(const PrefillArgs& b, dim3 grid, hipStream_t s) {
   const dim3 block(WAVES * kWave);
+  // The ring-fed kernel where it applies: sum-of-squares second statistic, a power-of-two group, and all of a unit's
+  // query rows inside a 32-bit byte offset.  ROCO_PREFILL_GQA_RING=0 keeps the register-staged kernels (tests run both).
+  const char* e = getenv("ROCO_PREFILL_GQA_RING");
+  const bool ring_ok = !(e != nullptr && e[0] == '0') && !b.pol.counts_above_average() &&
+                       static_cast<long long>(b.group) * b.L_max * kRowBytes < (1ll << 31);
+  if (ring_ok) {
+    switch (b.group) {
+      case 2: hipLaunchKernelGGL((prefill_columns_gqa_ring<2>), grid, block, 0, s, b); return;
+      case 4: hipLaunchKernelGGL((prefill_columns_gqa_ring<4>), grid, block, 0, s, b); return;
+      case 8: hipLaunchKernelGGL((prefill_columns_gqa_ring<8>), grid, block, 0, s, b); return;
+      case 16: hipLaunchKernelGGL((prefill_columns_gqa_ring<16>), grid, block, 0, s, b); return;
+      default: break;
+    }
+  }
   switch (b.group) {
     case 2: hipLaunchKernelGGL((prefill_columns_gqa_pow2_mfma<WAVES, 2>), grid, block, 0, s, b); break;
     case 4: hipLaunchKernelGGL((prefill_columns_gqa_pow2_mfma<WAVES, 4>), grid, block, 0, s, b); break;

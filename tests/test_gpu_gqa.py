@@ -154,13 +154,24 @@ def test_grouped_prefill_then_grouped_decode(dtype, d, group):
 
 @pytest.mark.parametrize("group", [2, 4, 8, 16])
 @pytest.mark.parametrize("recency", [False, True])
-def test_grouped_prefill_on_the_matrix_cores_with_heads_summed_in_registers(group, recency, monkeypatch):
+@pytest.mark.parametrize("ring", ["ring", "staged"])
+def test_grouped_prefill_on_the_matrix_cores_with_heads_summed_in_registers(group, recency, ring, monkeypatch):
     """Group sizes that divide 16 take the column pass whose tiles hold all heads of a few query positions: lengths
     around its tile edges (64 / g positions per tile), several key blocks, with and without the recency bias; the
-    query tiles of a key block on one workgroup (as with many units) or shared by two (as with few)."""
+    query tiles of a key block on one workgroup (as with many units) or shared by two (as with few); tiles fed by the
+    LDS ring (the default) or staged through registers."""
     monkeypatch.setenv("ROCO_PREFILL_QSPLIT", "1" if recency else "2")
+    monkeypatch.setenv("ROCO_PREFILL_GQA_RING", "1" if ring == "ring" else "0")
     run_grouped_prefill("bf16", 128, group, [517, 300, 64 // group + 1, 129, 33], 517, 100, 12, seed=540 + group,
-                        recency=recency, tag=f"gqa-pow2-g{group}-{recency}", steps=2)
+                        recency=recency, tag=f"gqa-pow2-g{group}-{recency}-{ring}", steps=2)
+
+
+@pytest.mark.parametrize("group", [2, 4, 16])
+def test_grouped_prefill_long_prompts_through_the_ring(group):
+    """Prompts of many key blocks and query tiles: the rectangle of the ring-fed grouped column pass (software-pipelined,
+    head sums carried across its slices) does most of the work; ragged lengths, one prompt shorter than the budget."""
+    run_grouped_prefill("bf16", 128, group, [1500, 1337, 1024, 90], 1500, 256, 40, seed=560 + group,
+                        tag=f"gqa-ring-long-g{group}", steps=2)
 
 
 def test_grouped_prefill_with_eight_heads_under_the_accumulated_score():

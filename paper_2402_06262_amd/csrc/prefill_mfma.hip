@@ -113,6 +113,15 @@ __device__ __forceinline__ bool locate(int units, int pairs, int& unit, int& pai
   pair = seq % pairs;
   return unit < units;
 }
+// The same for (unit, query head) pairs, u = unit * group + head: the heads of a unit stream the same keys (and
+// values), so they all go to the die unit % 8.  The grid covers ceil(units / 8) * 8 * group * pairs ids.
+__device__ __forceinline__ bool locate_heads(int units, int group, int pairs, int& u, int& pair) {
+  int v;  // virtual index: die v % 8, and on a die the heads of one unit before the next unit's
+  if (!locate(((units + 7) / 8) * 8 * group, pairs, v, pair)) return false;
+  const int unit = (v / (8 * group)) * 8 + (v & 7), head = (v >> 3) % group;
+  u = unit * group + head;
+  return unit < units;
+}
 
 // Online log-sum-exp update of one lane with the 16 scores of a tile.
 //   INTERIOR: every key of the tile is visible to every query of the group and none is inside a recency window:
@@ -190,7 +199,7 @@ __global__ __launch_bounds__(256, 2) void prefill_rows_mfma(PrefillArgs a) {
   constexpr int NS = 4;  // ring stages: a tile is requested three tiles of work ahead of its use
   __shared__ __attribute__((aligned(1024))) char ring[NS * kRingTileBytes];
   int u, id;  // u counts (unit, query head) pairs: with grouped-query attention a unit has a.group heads
-  if (!locate(a.units * a.group, a.pairs * a.ksplit, u, id)) return;
+  if (!locate_heads(a.units, a.group, a.pairs * a.ksplit, u, id)) return;
   const int seg = id % a.ksplit, pair_id = id / a.ksplit;  // which share of the keys, which blocks of queries
   float* const lse_out = seg == 0 ? a.lse : a.acc;  // second share: see merge_key_shares (group = 1 only)
   const int uk = u / a.group;  // the unit: its keys and its length
@@ -1270,7 +1279,7 @@ __global__ __launch_bounds__(WAVES * kWave) void prefill_rows_out_mfma(PrefillAr
   constexpr int kOwnQ = 32 * WAVES;  // one group of 32 queries per wave
   extern __shared__ __attribute__((aligned(16))) char lds_dyn[];  // K[2] then V[2] tiles
   int u, blk_id;
-  if (!locate(a.units * a.group, a.pairs, u, blk_id)) return;  // u counts (unit, query head) pairs
+  if (!locate_heads(a.units, a.group, a.pairs, u, blk_id)) return;  // u counts (unit, query head) pairs
   const int uk = u / a.group;  // the unit: its keys, values and length
   const int len = a.len[uk];
   const int n_blocks = (len + kOwnQ - 1) / kOwnQ;
@@ -1592,7 +1601,7 @@ hipError_t launch_t(const PrefillArgs& a, hipStream_t s) {
   b.qsplit = columns_query_shares(a, b.pairs);
   b.ksplit = a.group == 1 ? b.qsplit : 1;  // the second share's plane has no room for several heads
   const dim3 grid(static_cast<unsigned>((a.units + 7) / 8 * 8 * b.pairs * b.qsplit));
-  const dim3 rows_grid(static_cast<unsigned>((a.units * a.group + 7) / 8 * 8 * b.pairs * b.ksplit));  // one id set per query head
+  const dim3 rows_grid(static_cast<unsigned>((a.units + 7) / 8 * 8 * a.group * b.pairs * b.ksplit));  // one id set per query head
   if (!a.skip_rows) {
     ProfScope ps(kProfPrefillRows, s);
     hipLaunchKernelGGL(prefill_rows_mfma, rows_grid, dim3(WAVES * kWave), 0, s, b);
@@ -1626,7 +1635,7 @@ hipError_t launch_with_output(const PrefillArgs& a, hipStream_t s) {
   {
     ProfScope ps(kProfPrefillRows, s);
     hipLaunchKernelGGL(prefill_rows_out_mfma<WAVES>,
-                       dim3(static_cast<unsigned>((a.units * a.group + 7) / 8 * 8 * b.pairs)), dim3(WAVES * kWave), kLds,
+                       dim3(static_cast<unsigned>((a.units + 7) / 8 * 8 * a.group * b.pairs)), dim3(WAVES * kWave), kLds,
                        s, b);
   }
   constexpr int kOwn = Shape<4>::kOwn;

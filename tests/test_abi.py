@@ -233,3 +233,45 @@ def test_set_overlap_validates_on_the_host():
     no_out = list(ok)
     no_out[10] = None
     assert lib.roco_set_overlap(*no_out) == EINVAL
+
+
+def test_header_is_plain_c_and_a_c_program_links_against_the_library(tmp_path):
+    """include/roco.h compiles as C99 with warnings as errors; a C program calls the host-only entry points (sizes,
+    codes, argument validation: nothing is launched) through the shared library."""
+    import shutil
+    import subprocess
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if cc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_roco.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <string.h>
+#include "roco.h"
+int main(void) {
+  roco_params p;
+  memset(&p, 0, sizeof p);
+  p.units = 4; p.head_dim = 128; p.budget = 256; p.scope = 16; p.dtype = ROCO_BF16;
+  if (sizeof(roco_params) != 44) return 1;
+  if (roco_version() != ROCO_VERSION) return 2;
+  if (roco_decode_workspace_bytes(&p) == 0 || roco_prefill_workspace_bytes(&p, 512) == 0) return 3;
+  if (roco_block_workspace_bytes(&p, 8) == 0) return 4;
+  p.head_dim = 96;
+  if (roco_decode_workspace_bytes(&p) != 0) return 5;
+  p.head_dim = 128;
+  /* null pointers are refused on the host, before anything is launched */
+  if (roco_decode_step(&p, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, 0, NULL) != ROCO_EINVAL) return 6;
+  if (roco_set_overlap(0, 1, NULL, NULL, NULL, 1, NULL, NULL, NULL, 1, NULL, NULL, NULL) != ROCO_EINVAL) return 7;
+  if (strcmp(roco_strerror(ROCO_OK), "success") != 0) return 8;
+  printf("ok %d\n", roco_decode_step_launches(&p));
+  return 0;
+}
+''')
+    exe = tmp_path / "use_roco"
+    lib_dir = os.path.dirname(roco.binding.library_path())
+    cmd = [cc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), str(src),
+           "-L", lib_dir, "-l:libroco.so", f"-Wl,-rpath,{lib_dir}", "-o", str(exe)]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    run = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert run.returncode == 0, (run.returncode, run.stdout, run.stderr)
+    assert run.stdout.startswith("ok ")

@@ -387,6 +387,7 @@ int roco_probe_mfma(int32_t workgroups, int32_t iters, int32_t operands, float* 
  *   ROCO_PREFILL_SIMPLE=1      vector-ALU prefill passes also for bf16 / head_dim 128
  *   ROCO_PREFILL_PAIRED=0|1    one block of rows per workgroup / a long and a short one (default 1)
  *   ROCO_PREFILL_QSPLIT=1|2    workgroups per block of rows in the two prefill passes (default: 2 with few units)
+ *   ROCO_PREFILL_GQA_RING=0    grouped-query column pass with register-staged tiles instead of the LDS ring
  *   ROCO_BLOCK_SPLITS=n        splits of the budget in the block-wise / grouped steps (default: about 512 / units)
  *   ROCO_BLOCK_SINGLE=0        single-token block steps go through the preparing kernel like longer blocks
  */

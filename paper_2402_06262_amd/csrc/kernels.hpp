@@ -35,15 +35,17 @@ constexpr int kMaxSplits = 64;        // upper bound on split-K partials per uni
 constexpr int kDecodeSelectThreads = 256;
 constexpr int kMaxFusedBudget = 4096;       // largest budget of the one-kernel decode step (keys and logits in LDS)
 constexpr int kMaxDecodeBudgetLds = 16384;  // ranking keys of a unit are kept in LDS up to here (128 KiB), else in the workspace
-constexpr size_t kDefaultDynamicLds = 65536;  // dynamic LDS a kernel may ask for without raising its limit first
+constexpr size_t kDefaultDynamicLds = 65536;  // LDS a kernel may use without raising its limit first
+constexpr size_t kStaticLdsAllowance = 8192;  // upper bound on the statically declared LDS of the kernels that ask
 
 // Dynamic LDS for the ranking keys of one unit (0: they go to the workspace); raises the kernel's limit when the
-// request is above the default one.  Returns false if the runtime refuses.
+// request, together with what the kernel declares statically, may be above the default one.  Returns false if the
+// runtime refuses.
 inline size_t key_lds_bytes(int B) {
   return B <= kMaxDecodeBudgetLds ? static_cast<size_t>(B) * 2 * sizeof(uint32_t) : 0;
 }
 inline bool allow_key_lds(const void* kernel, size_t bytes) {
-  if (bytes <= kDefaultDynamicLds) return true;
+  if (bytes + kStaticLdsAllowance <= kDefaultDynamicLds) return true;
   return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes)) == hipSuccess;
 }
 

@@ -186,10 +186,10 @@ __global__ __launch_bounds__(256) void set_overlap(int slots_a, const int32_t* p
                                                    const int32_t* n_a, int slots_b, const int32_t* pos_b,
                                                    const int32_t* mask_b, const int32_t* n_b, int max_pos,
                                                    int32_t* inter_out, int32_t* union_out) {
-  extern __shared__ uint32_t bits[];  // (max_pos + 31) / 32 words
-  __shared__ uint32_t cnt[3];         // |A|, |B|, |A and B|
+  extern __shared__ uint32_t bits[];  // (max_pos + 31) / 32 words, then the three counters
   const int u = blockIdx.x, tid = threadIdx.x;
   const int words = (max_pos + 31) / 32;
+  uint32_t* const cnt = bits + words;  // |A|, |B|, |A and B|
   for (int i = tid; i < words; i += 256) bits[i] = 0u;
   if (tid < 3) cnt[tid] = 0u;
   __syncthreads();
@@ -225,7 +225,9 @@ __global__ __launch_bounds__(256) void set_overlap(int slots_a, const int32_t* p
 hipError_t launch_set_overlap(int units, int slots_a, const int32_t* pos_a, const int32_t* mask_a, const int32_t* n_a,
                               int slots_b, const int32_t* pos_b, const int32_t* mask_b, const int32_t* n_b, int max_pos,
                               int32_t* inter, int32_t* uni, hipStream_t s) {
-  const size_t lds = static_cast<size_t>((max_pos + 31) / 32) * sizeof(uint32_t);  // the host keeps this within 64 KiB
+  // the bitmap (the host keeps it within 64 KiB) and three counters: the largest range needs the raised limit
+  const size_t lds = (static_cast<size_t>((max_pos + 31) / 32) + 3) * sizeof(uint32_t);
+  if (!allow_key_lds(reinterpret_cast<const void*>(set_overlap), lds)) return hipErrorInvalidValue;
   hipLaunchKernelGGL(set_overlap, dim3(units), dim3(256), lds, s, slots_a, pos_a, mask_a, n_a, slots_b, pos_b, mask_b, n_b,
                      max_pos, inter, uni);
   return hipGetLastError();

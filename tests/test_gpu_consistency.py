@@ -125,3 +125,28 @@ def test_set_overlap_counts_against_python_sets():
             A = {int(p) for j, p in enumerate(pos_a[u, :n_a[u]]) if not use_mask or mask_a[u, j]}
             Bs = {int(p) for p in pos_b[u, :n_b[u]]}
             assert int(inter[u]) == len(A & Bs) and int(uni[u]) == len(A | Bs), (use_mask, u)
+
+
+def test_set_overlap_over_the_largest_position_range():
+    """max_pos = 524288, the documented limit: the bitmap alone fills 64 KiB of LDS, so the kernel's limit has to be
+    raised; positions at both ends of the range, and one past it that must be ignored."""
+    import paper_2402_06262_amd as roco
+    T = 1 << 19
+    rng = np.random.default_rng(11)
+    units, sa, sb = 3, 512, 384
+    pos_a = np.stack([rng.choice(T, size=sa, replace=False) for _ in range(units)]).astype(np.int32)
+    pos_b = np.stack([rng.choice(T, size=sb, replace=False) for _ in range(units)]).astype(np.int32)
+    pos_a[:, 0], pos_a[:, 1] = 0, T - 1
+    pos_b[:, 0], pos_b[:, 1], pos_b[:, 2] = T - 1, 0, T  # the last one lies outside [0, max_pos)
+    pos_b[:, 3:200] = pos_a[:, 3:200]  # a large common part
+    n_a = np.full(units, sa, np.int32)
+    n_b = np.array([sb, 100, 3], np.int32)
+    dev = lambda x: torch.from_numpy(x).cuda()
+    inter = torch.full((units,), -1, dtype=torch.int32, device="cuda")
+    uni = torch.full((units,), -1, dtype=torch.int32, device="cuda")
+    roco.roco_set_overlap(dev(pos_a), None, dev(n_a), dev(pos_b), None, dev(n_b), T, inter, uni)
+    torch.cuda.synchronize()
+    for u in range(units):
+        A = {int(p) for p in pos_a[u, :n_a[u]]}
+        Bs = {int(p) for p in pos_b[u, :n_b[u]] if p < T}
+        assert int(inter[u]) == len(A & Bs) and int(uni[u]) == len(A | Bs), u

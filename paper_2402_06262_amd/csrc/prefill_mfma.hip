@@ -532,6 +532,8 @@ __global__ __launch_bounds__(256, 2) void prefill_columns_mfma(PrefillArgs a) {
     load_owned(own1, Kb, kj1, len - 1);
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the owned rows are in before the loop (see prefill_rows_mfma)
     float s1a = 0.0f, s2a = 0.0f, s1b = 0.0f, s2b = 0.0f;
+    // second chain of each sum in the rectangle (odd scores of a register pair); folded into the sums after it
+    float t1a = 0.0f, t2a = 0.0f, t1b = 0.0f, t2b = 0.0f;
 
     auto put_rinv = [&](int i) {
       if (COUNT && threadIdx.x < kTile)
@@ -591,7 +593,6 @@ __global__ __launch_bounds__(256, 2) void prefill_columns_mfma(PrefillArgs a) {
           if (COUNT) rv[g4] = *reinterpret_cast<const float4*>(rt + 8 * g4);
         }
       }
-      float a1 = 0.0f, a2 = 0.0f, b1 = 0.0f, b2 = 0.0f, c1 = 0.0f, c2 = 0.0f, d1 = 0.0f, d2 = 0.0f;
       auto comp = [](const float4& v, int e) { return e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w; };
       auto one = [&](float s, float lse_q, float rinv_q, float& sum1, float& sum2) {
         const float pr = fast_exp2(fmaf(s, sc, -lse_q));
@@ -599,19 +600,19 @@ __global__ __launch_bounds__(256, 2) void prefill_columns_mfma(PrefillArgs a) {
         if (COUNT) sum2 += pr > rinv_q ? 1.0f : 0.0f;  // p * (i + 1) > 1
         else sum2 = fmaf(pr, pr, sum2);
       };
+      // The probabilities go straight into the block's running sums, two chains per sum: nothing is zeroed or folded
+      // per step (that cost one vector instruction per matrix instruction).
       auto consume = [&](int kk, int g) {
         const int r = 2 * kk;  // scores r and r + 1: queries 8 (r / 4) + 4 half + r % 4 (+ 1) of the half-tile
         const float la = comp(lv[r >> 2], r & 3), lb = comp(lv[r >> 2], (r & 3) + 1);
         const float ra = COUNT ? comp(rv[r >> 2], r & 3) : 0.0f, rbq = COUNT ? comp(rv[r >> 2], (r & 3) + 1) : 0.0f;
-        if (g == 0) { one(y0[r], la, ra, a1, a2); one(y0[r + 1], lb, rbq, b1, b2); }
-        else        { one(y1[r], la, ra, c1, c2); one(y1[r + 1], lb, rbq, d1, d2); }
+        if (g == 0) { one(y0[r], la, ra, s1a, s2a); one(y0[r + 1], lb, rbq, t1a, t2a); }
+        else        { one(y1[r], la, ra, s1b, s2b); one(y1[r + 1], lb, rbq, t1b, t2b); }
       };
-      auto pin = [&]() { asm volatile("" : "+v"(a1), "+v"(a2), "+v"(b1), "+v"(b2), "+v"(c1), "+v"(c2), "+v"(d1), "+v"(d2)); };
+      auto pin = [&]() {
+        asm volatile("" : "+v"(s1a), "+v"(s2a), "+v"(t1a), "+v"(t2a), "+v"(s1b), "+v"(s2b), "+v"(t1b), "+v"(t2b));
+      };
       fill_and_consume<CONSUME>(p, tr.frag, own0, own1, x0, x1, consume, pin);
-      if (CONSUME) {
-        s1a += a1 + b1; s2a += a2 + b2;
-        s1b += c1 + d1; s2b += c2 + d2;
-      }
     };
     auto rect_tile = [&](auto stage, int ii) {
       constexpr int S = decltype(stage)::value;
@@ -630,6 +631,8 @@ __global__ __launch_bounds__(256, 2) void prefill_columns_mfma(PrefillArgs a) {
       if (stage == 2) { if (!is_rect(i)) break; rect_tile(StageTag<2>{}, i++); stage = 3; }
       if (stage == 3) { if (!is_rect(i)) break; rect_tile(StageTag<3>{}, i++); stage = 0; }
     }
+    s1a += t1a; s2a += t2a;
+    s1b += t1b; s2b += t2b;
     if (pending) {  // drain
       const float* lt = &lse_s[pending_i % kLseStages][wave][32];
       const float* rt = &rinv_s[COUNT ? pending_i % kLseStages : 0][COUNT ? 32 : 0];
@@ -1128,6 +1131,7 @@ __global__ __launch_bounds__(256, 2) void prefill_columns_gqa_ring(PrefillArgs a
     load_owned(own1, Kb, kj1, len - 1);
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the owned rows are in before the loop
     float s1a = 0.0f, s2a = 0.0f, s1b = 0.0f, s2b = 0.0f;
+    float ha = 0.0f, hc = 0.0f;  // rectangle: head sum of the position under way, per key group
 
     auto next_tile = [&](int i) {  // the i-th tile has landed; the (i + 3)-th is requested
       if (i + 2 < n) wait_loads<10>();
@@ -1175,15 +1179,14 @@ __global__ __launch_bounds__(256, 2) void prefill_columns_gqa_ring(PrefillArgs a
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) lv[g4] = *reinterpret_cast<const float4*>(lt + 8 * g4);
       }
-      float a1 = 0.0f, a2 = 0.0f, c1 = 0.0f, c2 = 0.0f;  // sums of the head-mean and of its square, per key group
-      float ha = 0.0f, hc = 0.0f;                        // head sum of the position under way, per key group
+      // The head-means go straight into the block's running sums: nothing is zeroed or folded per step.
       auto comp = [](const float4& v, int e) { return e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w; };
       auto consume = [&](int kk, int g) {
         const int r = 2 * kk;  // registers r and r + 1: two heads of one position (G consecutive registers each)
         const f32x16& y = g == 0 ? y0 : y1;
         float& hs = g == 0 ? ha : hc;
-        float& sum1 = g == 0 ? a1 : c1;
-        float& sum2 = g == 0 ? a2 : c2;
+        float& sum1 = g == 0 ? s1a : s1b;
+        float& sum2 = g == 0 ? s2a : s2b;
         const float pa = fast_exp2(fmaf(y[r], sc, -comp(lv[r >> 2], r & 3)));
         const float pb = fast_exp2(fmaf(y[r + 1], sc, -comp(lv[r >> 2], (r & 3) + 1)));
         if (r % G == 0) hs = pa + pb;
@@ -1194,12 +1197,8 @@ __global__ __launch_bounds__(256, 2) void prefill_columns_gqa_ring(PrefillArgs a
           sum2 = fmaf(pbar, pbar, sum2);
         }
       };
-      auto pin = [&]() { asm volatile("" : "+v"(a1), "+v"(a2), "+v"(c1), "+v"(c2), "+v"(ha), "+v"(hc)); };
+      auto pin = [&]() { asm volatile("" : "+v"(s1a), "+v"(s2a), "+v"(s1b), "+v"(s2b), "+v"(ha), "+v"(hc)); };
       fill_and_consume<CONSUME>(p, tr.frag, own0, own1, x0, x1, consume, pin);
-      if (CONSUME) {
-        s1a += a1; s2a += a2;
-        s1b += c1; s2b += c2;
-      }
     };
     auto rect_tile = [&](auto stage, int ii) {
       constexpr int S = decltype(stage)::value;
@@ -1509,10 +1508,11 @@ __global__ __launch_bounds__(256, 2) void prefill_mix_probe(int tiles, float* si
   __syncthreads();
   const float sc = 0.1275f;
   float l0 = 0.0f, l1 = 0.0f, q0 = 0.0f, q1 = 0.0f;
+  float lb0 = 0.0f, lb1 = 0.0f, qb0 = 0.0f, qb1 = 0.0f;  // column pass: the second chain of each running sum
   f32x16 A0, A1, B0 = {0}, B1 = {0};
   auto step = [&](auto consume_tag, const char* p, f32x16& x0, f32x16& x1, const f32x16& y0, const f32x16& y1, int ysub) {
     constexpr bool CONSUME = decltype(consume_tag)::value != 0;
-    float a0 = 0.0f, b0 = 0.0f, a1 = 0.0f, b1 = 0.0f, c0 = 0.0f, d0 = 0.0f, c1 = 0.0f, d1 = 0.0f;
+    float a0 = 0.0f, b0 = 0.0f, a1 = 0.0f, b1 = 0.0f;  // row pass: the sums of this step, checked before they count
     float4 lv[4];
     if (PASS == 2 && CONSUME) {
 #pragma unroll
@@ -1522,26 +1522,26 @@ __global__ __launch_bounds__(256, 2) void prefill_mix_probe(int tiles, float* si
     auto consume = [&](int kk, int g) {
       const int r = 2 * kk;
       const f32x16& y = g == 0 ? y0 : y1;
-      float& sa = g == 0 ? a0 : a1; float& sb = g == 0 ? b0 : b1; float& ta = g == 0 ? c0 : c1; float& tb = g == 0 ? d0 : d1;
       if (PASS == 1) {
+        float& sa = g == 0 ? a0 : a1; float& sb = g == 0 ? b0 : b1;
         sa += fast_exp2(fmaf(y[r], sc, -40.0f));
         sb += fast_exp2(fmaf(y[r + 1], sc, -40.0f));
-      } else {
+      } else {  // the column pass adds to the block's running sums
+        float& sa = g == 0 ? l0 : l1; float& sb = g == 0 ? lb0 : lb1; float& ta = g == 0 ? q0 : q1; float& tb = g == 0 ? qb0 : qb1;
         const float pa = fast_exp2(fmaf(y[r], sc, -comp(lv[r >> 2], r & 3)));
         const float pb = fast_exp2(fmaf(y[r + 1], sc, -comp(lv[r >> 2], (r & 3) + 1)));
         sa += pa; ta = fmaf(pa, pa, ta);
         sb += pb; tb = fmaf(pb, pb, tb);
       }
     };
-    auto pin = [&]() { asm volatile("" : "+v"(a0), "+v"(b0), "+v"(a1), "+v"(b1), "+v"(c0), "+v"(d0), "+v"(c1), "+v"(d1)); };
+    auto pin = [&]() {
+      if (PASS == 1) asm volatile("" : "+v"(a0), "+v"(b0), "+v"(a1), "+v"(b1));
+      else asm volatile("" : "+v"(l0), "+v"(lb0), "+v"(l1), "+v"(lb1), "+v"(q0), "+v"(qb0), "+v"(q1), "+v"(qb1));
+    };
     fill_and_consume<CONSUME>(p, tr.frag, own0, own1, x0, x1, consume, pin);
-    if (CONSUME) {
-      if (PASS == 1) {  // the row pass checks every tile's sum against its safe range
-        if (__builtin_amdgcn_ballot_w64(!(a0 + b0 <= 0x1p64f)) == 0) l0 += a0 + b0;
-        if (__builtin_amdgcn_ballot_w64(!(a1 + b1 <= 0x1p64f)) == 0) l1 += a1 + b1;
-      } else {
-        l0 += a0 + b0; l1 += a1 + b1; q0 += c0 + d0; q1 += c1 + d1;
-      }
+    if (CONSUME && PASS == 1) {  // the row pass checks every tile's sum against its safe range
+      if (__builtin_amdgcn_ballot_w64(!(a0 + b0 <= 0x1p64f)) == 0) l0 += a0 + b0;
+      if (__builtin_amdgcn_ballot_w64(!(a1 + b1 <= 0x1p64f)) == 0) l1 += a1 + b1;
     }
   };
   step(StageTag<0>{}, tile, A0, A1, B0, B1, 0);
@@ -1550,7 +1550,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mix_probe(int tiles, float* si
     step(StageTag<1>{}, tile + 32 * kRowBytes, B0, B1, A0, A1, 0);
     step(StageTag<1>{}, tile, A0, A1, B0, B1, 1);
   }
-  float sum = l0 + l1 + q0 + q1;
+  float sum = l0 + l1 + q0 + q1 + lb0 + lb1 + qb0 + qb1;
 #pragma unroll
   for (int r = 0; r < 16; ++r) sum += A0[r] + A1[r];
   sink[static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x] = sum;

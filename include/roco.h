@@ -246,9 +246,9 @@ int roco_decode_step_static(const roco_params* params,
  *                  token's position, or -1 where token i went to an empty slot (either may be NULL)
  * workspace        roco_block_workspace_bytes(params, block) bytes: sized for the largest step (64 query rows per
  *                  unit), so that one workspace serves every block size and group size of a unit count and budget
- * Supported: budget a multiple of 4 (else ROCO_EUNSUPPORTED).  bf16 with head_dim 128 runs on the matrix cores
- * and streams K and V once per block; the other dtypes / head_dims compute the same step with one pass over K and
- * V per query row.
+ * Supported: budget a multiple of 4 (else ROCO_EUNSUPPORTED).  K and V are streamed once per block for every dtype
+ * and head_dim: bf16 with head_dim 128 on the matrix cores, the others on the vector ALUs (which bound steps of
+ * more than about 8 query rows).
  */
 size_t roco_block_workspace_bytes(const roco_params* params, int32_t block);
 int roco_encode_block(const roco_params* params, int32_t block,

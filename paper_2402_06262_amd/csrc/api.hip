@@ -383,10 +383,6 @@ int run_block(const roco_params* params, int tokens, int heads, const void* q, c
     rows = (rows + 63) / 64 * 64;
     a.splits = (params->budget + rows - 1) / rows;
     a.rows_per_split = rows;
-    if (params->dtype != ROCO_BF16 || params->head_dim != 128) {  // vector-ALU attention: one workgroup per query row
-      a.splits = 1;
-      a.rows_per_split = params->budget;
-    }
   }
   a.scale_log2 = scale_log2(params);
   a.recency_window = params->recency_window;

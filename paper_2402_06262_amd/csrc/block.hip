@@ -382,66 +382,249 @@ __global__ __launch_bounds__(kAttThreads) void block_attend(BlockArgs a) {
 
 // ------------------------------------------------------------------------------------------------
 // The attention of the block-wise / grouped-query step for the shapes the matrix-core kernel is not built for
-// (fp32, head_dim 64): grid (query rows, units), one workgroup streams all slots of the unit for one query row
-// on the vector ALUs, exactly like a decode step does, with the slots that hold later tokens of the block masked
-// out.  K and V are read once per query row, so this path has the semantics of the step but not its bandwidth
-// saving.  Produces what block_attend produces with a single split.
-template <int DT, int D>
-__global__ __launch_bounds__(256) void block_attend_simple(BlockArgs a) {
+// (fp32, head_dim 64), on the vector ALUs: grid (splits, units), four waves.  K and V are streamed once for all
+// query rows of the step, as on the matrix-core path: a tile of 64 slots goes through LDS (as fp32), then
+//   scores : a wave takes every fourth query row.  Its lanes form QS groups; a lane owns QS slots of the tile (one
+//            lane of every group per slot) and the queries of its group, so that every K or Q value read from LDS
+//            feeds several multiply-adds (a register block of QS slots x QL queries per lane: with one slot per
+//            lane the broadcast reads of Q, not the arithmetic, set the pace).  The group keeps an online softmax
+//            per query row (maximum and sum over the tile by lane reductions inside the group), stores the base-2
+//            logits and leaves the tile's probabilities and the factor that rescales the running output in LDS.
+//   output : a thread owns four output dimensions of every NG-th query row: O[q][d] = O[q][d] alpha[q] +
+//            sum_r P[q][r] V[r][d], four slots at a time (one 16-byte read of P per row, of V per slot).
+// The vector work grows with the number of query rows while the bytes do not: a step of many rows is bound by the
+// ALUs, and still reads the cache once instead of once per row.  Produces what block_attend produces.
+template <int D> struct SharedTile {
+  static constexpr int kRows = 64;        // slots per tile
+  static constexpr int kStride = D + 4;   // floats per K row in LDS: lanes that read consecutive rows hit different banks
+  static size_t lds_bytes(int qmax) {     // K tile, V tile, probabilities, queries, rescale factors
+    return (static_cast<size_t>(kRows) * kStride + static_cast<size_t>(kRows) * D + static_cast<size_t>(qmax) * kRows +
+            static_cast<size_t>(qmax) * D + qmax) * sizeof(float);
+  }
+};
+
+// QMAX: most query rows the instantiation takes (8, 16, 32 or 64).  The smaller ones need fewer registers and less LDS,
+// so more workgroups fit a compute unit, and they keep two tiles in flight per workgroup instead of one.
+template <int DT, int D, int QMAX>
+__global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void block_attend_shared(BlockArgs a) {
   using G = RowGeom<DT, D>;
-  constexpr int U = 4, WAVES = 4;
-  constexpr int PASS = WAVES * U * G::R;
-  __shared__ float sm_m[WAVES], sm_l[WAVES];
-  __shared__ float sm_acc[WAVES][D];
-  const int u = blockIdx.y, r = blockIdx.x;  // r: query row = (token, head)
+  using T = SharedTile<D>;
+  constexpr int TR = T::kRows, KS = T::kStride, WAVES = 4;
+  constexpr int KQ = QMAX / WAVES;       // query rows per wave: wave + 4 k
+  constexpr int QS = KQ >= 4 ? 4 : KQ;   // lane groups of a wave = slots per lane
+  constexpr int RG = kWave / QS;         // lanes per group; lane rg owns slots rg + RG i, i < QS
+  constexpr int QL = KQ / QS;            // query rows per lane: k = qs + QS jq
+  constexpr int DQ = D / 4;              // output phase: threads per query row, four dimensions each
+  constexpr int NG = 256 / DQ;           // ... and groups of threads: group og takes rows og + NG k
+  constexpr int OQ = QMAX >= NG ? QMAX / NG : 1;
+  constexpr int CH = TR * G::LPR / 256;  // 16-byte pieces of a tile per thread and operand
+  constexpr int PF = (QMAX <= 8 || (QMAX <= 32 && D == 64)) ? 2 : 1;  // tiles in flight
+  static_assert(CH >= 1 && TR * G::LPR % 256 == 0, "a tile is dealt evenly to the threads");
+  static_assert(QMAX % WAVES == 0 && KQ % QS == 0 && QS * RG == kWave && RG * QS == TR && QMAX <= kMaxBlock, "query rows and slots are dealt evenly");
+  extern __shared__ __attribute__((aligned(16))) float lds_f[];
+  __shared__ int32_t bidx_s[TR], pos_s[TR];
+  float* const Kt = lds_f;                 // [TR][KS]
+  float* const Vt = Kt + TR * KS;          // [TR][D]
+  float* const Pt = Vt + TR * D;           // [QMAX][TR] probabilities of the tile against the running reference
+  float* const Qs = Pt + QMAX * TR;        // [QMAX][D]  queries times scale * log2(e)
+  float* const al = Qs + QMAX * D;         // [QMAX]     factor for the running output of a query row
+  const int u = blockIdx.y, split = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-  const int c = lane % G::LPR;
-  const int B = a.B;
-  const int n = a.n_used[u];
-  const int ti = r / a.heads;
-  float qf[G::EPL];
-  unpack16<DT>(load16(static_cast<const char*>(a.q) + (static_cast<size_t>(u) * a.queries + r) * G::ROW_BYTES + c * 16), qf);
-#pragma unroll
-  for (int e = 0; e < G::EPL; ++e) qf[e] *= a.scale_log2;
+  const int B = a.B, nq = a.queries, QR = a.qrows;  // QR: rows per unit of the workspace planes
+  const int n = a.n_used[u];  // block_prepare has run: the block's rows are in the cache and counted
+  const int row0 = split * a.rows_per_split;
+  const int row1 = min(n, row0 + a.rows_per_split);
+  const size_t pidx = static_cast<size_t>(u) * a.splits + split;
   const char* Kb = static_cast<const char*>(a.K) + static_cast<size_t>(u) * B * G::ROW_BYTES;
   const char* Vb = static_cast<const char*>(a.V) + static_cast<size_t>(u) * B * G::ROW_BYTES;
   const int32_t* bidx = a.blk_idx + static_cast<size_t>(u) * B;
   const int32_t* pos = a.pos + static_cast<size_t>(u) * B;
-  float* z = a.z + (static_cast<size_t>(u) * a.qrows + r) * B;
-  const int qp = a.qpos0[u] + ti;
+  float* z = a.z + static_cast<size_t>(u) * QR * B;
   const int w = a.recency_window;
   const float rb = a.recency_bias_log2;
-  auto bias = [&](int row, int row_pos) -> float {
-    if (bidx[row] > ti) return -INFINITY;  // a later token of the block
-    const int dlt = qp - row_pos;
-    return (w > 0 && dlt >= 0 && dlt < w) ? rb : 0.0f;
-  };
-  auto fix = [](int, uint4&, int) {};
-  FlashState<G::EPL> st;
-  st.reset();
-  const int passes = (n + PASS - 1) / PASS;
-  stream_attend<DT, D, U, true, false>(qf, Kb, Vb, 0, n, passes, 0, PASS, wave * (U * G::R), bias, pos, z, -1, fix, fix, st);
-  merge_groups_in_wave<DT, D>(st);
-  if (lane < G::LPR) {
-    if (lane == 0) { sm_m[wave] = st.m; sm_l[wave] = st.l; }
+  const int qp0 = a.qpos0[u];
+
+  for (int idx = tid; idx < nq * G::LPR; idx += 256) {  // the step's queries, scaled, as fp32
+    const int q = idx / G::LPR, c = idx % G::LPR;
+    float f[G::EPL];
+    unpack16<DT>(load16(static_cast<const char*>(a.q) + (static_cast<size_t>(u) * nq + q) * G::ROW_BYTES + c * 16), f);
 #pragma unroll
-    for (int e = 0; e < G::EPL; ++e) sm_acc[wave][lane * G::EPL + e] = st.acc[e];
+    for (int e = 0; e < G::EPL; ++e) Qs[q * D + c * G::EPL + e] = f[e] * a.scale_log2;
   }
-  __syncthreads();
-  float M = -INFINITY;
+
+  const int rg = lane % RG, qs = lane / RG;
+  int qrow[QL];        // this lane's query rows (may lie beyond the step's)
+  float m[QL], l[QL];  // their online softmax (the same in every lane of the group)
 #pragma unroll
-  for (int s = 0; s < WAVES; ++s) M = fmaxf(M, sm_m[s]);
-  const size_t pidx = static_cast<size_t>(u) * a.qrows + r;  // one split
-  if (tid < D) {
-    float o = 0.0f, l = 0.0f;
+  for (int jq = 0; jq < QL; ++jq) {
+    qrow[jq] = wave + WAVES * (qs + QS * jq);
+    m[jq] = -INFINITY;
+    l[jq] = 0.0f;
+  }
+  const int dq = tid % DQ, og = tid / DQ;
+  float4 o[OQ];
 #pragma unroll
-    for (int s = 0; s < WAVES; ++s) {
-      const float wgt = (sm_m[s] > -INFINITY) ? fast_exp2(sm_m[s] - M) : 0.0f;
-      l += sm_l[s] * wgt;
-      o += sm_acc[s][tid] * wgt;
+  for (int k = 0; k < OQ; ++k) o[k] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+
+  const int n_tiles = row1 > row0 ? (row1 - row0 + TR - 1) / TR : 0;
+  uint4 pk[PF][CH], pv[PF][CH];
+  int32_t st_bidx[PF], st_pos[PF];  // first wave: of slot `lane` of the tiles on their way
+  auto fetch = [&](int t, uint4* fk, uint4* fv, int32_t& fb, int32_t& fp) {
+    const int tr0 = row0 + t * TR;
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int idx = tid + 256 * i;
+      const int row = min(tr0 + idx / G::LPR, n - 1);  // slots past the end are masked below
+      const size_t off = static_cast<size_t>(row) * G::ROW_BYTES + (idx % G::LPR) * 16;
+      fk[i] = a.streaming ? load16_streaming(Kb + off) : load16(Kb + off);
+      fv[i] = a.streaming ? load16_streaming(Vb + off) : load16(Vb + off);
     }
-    a.part_o[pidx * D + tid] = o;
-    if (tid == 0) { a.part_m[pidx] = M; a.part_l[pidx] = l; }
+    if (tid < TR) {
+      const int slot = min(tr0 + tid, n - 1);
+      fb = bidx[slot];
+      fp = pos[slot];
+    }
+  };
+#pragma unroll
+  for (int j = 0; j < PF; ++j) {
+    st_bidx[j] = -1;
+    st_pos[j] = 0;
+    if (j < n_tiles) fetch(j, pk[j], pv[j], st_bidx[j], st_pos[j]);
+  }
+  for (int t0 = 0; t0 < n_tiles; t0 += PF) {
+#pragma unroll
+    for (int j = 0; j < PF; ++j) {
+      const int t = t0 + j;
+      if (t >= n_tiles) break;
+      const int tr0 = row0 + t * TR;
+#pragma unroll
+      for (int i = 0; i < CH; ++i) {
+        const int idx = tid + 256 * i;
+        const int r = idx / G::LPR, c = idx % G::LPR;
+        float fk[G::EPL], fv[G::EPL];
+        unpack16<DT>(pk[j][i], fk);
+        unpack16<DT>(pv[j][i], fv);
+#pragma unroll
+        for (int e = 0; e < G::EPL; e += 4) {
+          *reinterpret_cast<float4*>(Kt + r * KS + c * G::EPL + e) = make_float4(fk[e], fk[e + 1], fk[e + 2], fk[e + 3]);
+          *reinterpret_cast<float4*>(Vt + r * D + c * G::EPL + e) = make_float4(fv[e], fv[e + 1], fv[e + 2], fv[e + 3]);
+        }
+      }
+      if (tid < TR) { bidx_s[tid] = st_bidx[j]; pos_s[tid] = st_pos[j]; }
+      __syncthreads();  // the tile (and, the first time, the queries) are in LDS
+      if (t + PF < n_tiles) fetch(t + PF, pk[j], pv[j], st_bidx[j], st_pos[j]);
+
+      // ---- scores: QS slots x QL query rows per lane
+      float part[QS][QL];
+#pragma unroll
+      for (int i = 0; i < QS; ++i)
+#pragma unroll
+        for (int jq = 0; jq < QL; ++jq) part[i][jq] = 0.0f;
+#pragma unroll 2  // (fully unrolled, the compiler hoists every LDS read of the tile and runs out of registers)
+      for (int c0 = 0; c0 < D; c0 += 8) {
+        float4 kc[QS][2];
+#pragma unroll
+        for (int i = 0; i < QS; ++i) {
+          kc[i][0] = *reinterpret_cast<const float4*>(Kt + (rg + RG * i) * KS + c0);
+          kc[i][1] = *reinterpret_cast<const float4*>(Kt + (rg + RG * i) * KS + c0 + 4);
+        }
+#pragma unroll
+        for (int jq = 0; jq < QL; ++jq) {
+          const int q = min(qrow[jq], QMAX - 1);
+          const float4 qa = *reinterpret_cast<const float4*>(Qs + q * D + c0);
+          const float4 qb = *reinterpret_cast<const float4*>(Qs + q * D + c0 + 4);
+#pragma unroll
+          for (int i = 0; i < QS; ++i) {
+            float s = part[i][jq];
+            s = fmaf(kc[i][0].x, qa.x, s); s = fmaf(kc[i][0].y, qa.y, s);
+            s = fmaf(kc[i][0].z, qa.z, s); s = fmaf(kc[i][0].w, qa.w, s);
+            s = fmaf(kc[i][1].x, qb.x, s); s = fmaf(kc[i][1].y, qb.y, s);
+            s = fmaf(kc[i][1].z, qb.z, s); s = fmaf(kc[i][1].w, qb.w, s);
+            part[i][jq] = s;
+          }
+        }
+      }
+#pragma unroll
+      for (int jq = 0; jq < QL; ++jq) {
+        const int q = qrow[jq];
+        const bool live = q < nq;   // uniform inside a group of lanes, not inside the wave
+        const int ti = q / a.heads;  // the heads of a group share the token's position
+        float x[QS];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < QS; ++i) {
+          const int r = rg + RG * i, slot = tr0 + r;
+          float v = part[i][jq];
+          const int dlt = qp0 + ti - pos_s[r];
+          if (w > 0 && dlt >= 0 && dlt < w) v += rb;
+          if (slot >= row1 || bidx_s[r] > ti) v = -INFINITY;  // no such slot, or a later token of the block
+          if (live && slot < row1) z[static_cast<size_t>(q) * B + slot] = v;  // kept for the statistics
+          x[i] = v;
+          mx = fmaxf(mx, v);
+        }
+        const float m_new = fmaxf(m[jq], group_max<RG>(mx));
+        const float ref = (m_new > -INFINITY) ? m_new : 0.0f;  // nothing visible yet: every term is 2^-inf = 0
+        const float alpha = (m_new > -INFINITY) ? fast_exp2(m[jq] - m_new) : 1.0f;
+        float sum = 0.0f;
+#pragma unroll
+        for (int i = 0; i < QS; ++i) {
+          const float pr = fast_exp2(x[i] - ref);
+          sum += pr;
+          if (live) Pt[q * TR + rg + RG * i] = pr;
+        }
+        l[jq] = fmaf(l[jq], alpha, group_sum<RG>(sum));
+        m[jq] = m_new;
+        if (live && rg == 0) al[q] = alpha;
+      }
+      __syncthreads();  // the tile's probabilities are in LDS
+
+      // ---- O[q][d] = O[q][d] alpha[q] + sum_r P[q][r] V[r][d]
+#pragma unroll
+      for (int k = 0; k < OQ; ++k) {
+        const int q = og + NG * k;
+        if (q < nq) {
+          const float f = al[q];
+          o[k].x *= f; o[k].y *= f; o[k].z *= f; o[k].w *= f;
+        }
+      }
+      for (int r = 0; r < TR; r += 4) {
+        const float4 v0 = *reinterpret_cast<const float4*>(Vt + r * D + 4 * dq);
+        const float4 v1 = *reinterpret_cast<const float4*>(Vt + (r + 1) * D + 4 * dq);
+        const float4 v2 = *reinterpret_cast<const float4*>(Vt + (r + 2) * D + 4 * dq);
+        const float4 v3 = *reinterpret_cast<const float4*>(Vt + (r + 3) * D + 4 * dq);
+#pragma unroll
+        for (int k = 0; k < OQ; ++k) {
+          const int q = og + NG * k;
+          if (q < nq) {
+            const float4 p4 = *reinterpret_cast<const float4*>(Pt + q * TR + r);
+            o[k].x = fmaf(p4.x, v0.x, o[k].x); o[k].y = fmaf(p4.x, v0.y, o[k].y);
+            o[k].z = fmaf(p4.x, v0.z, o[k].z); o[k].w = fmaf(p4.x, v0.w, o[k].w);
+            o[k].x = fmaf(p4.y, v1.x, o[k].x); o[k].y = fmaf(p4.y, v1.y, o[k].y);
+            o[k].z = fmaf(p4.y, v1.z, o[k].z); o[k].w = fmaf(p4.y, v1.w, o[k].w);
+            o[k].x = fmaf(p4.z, v2.x, o[k].x); o[k].y = fmaf(p4.z, v2.y, o[k].y);
+            o[k].z = fmaf(p4.z, v2.z, o[k].z); o[k].w = fmaf(p4.z, v2.w, o[k].w);
+            o[k].x = fmaf(p4.w, v3.x, o[k].x); o[k].y = fmaf(p4.w, v3.y, o[k].y);
+            o[k].z = fmaf(p4.w, v3.z, o[k].z); o[k].w = fmaf(p4.w, v3.w, o[k].w);
+          }
+        }
+      }
+      __syncthreads();  // everybody is done with the tile before the next one overwrites it
+    }
+  }
+
+  // ---- this split's partial: reference, sum and unnormalised output per query row
+#pragma unroll
+  for (int jq = 0; jq < QL; ++jq) {
+    const int q = qrow[jq];
+    if (q < nq && rg == 0) {
+      a.part_m[pidx * QR + q] = m[jq];
+      a.part_l[pidx * QR + q] = l[jq];
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < OQ; ++k) {
+    const int q = og + NG * k;
+    if (q < nq) *reinterpret_cast<float4*>(a.part_o + (pidx * QR + q) * D + 4 * dq) = o[k];
   }
 }
 
@@ -581,16 +764,31 @@ void launch_block_tail(const BlockArgs& a, hipStream_t s) {
   hipLaunchKernelGGL((block_finish<DT, D>), dim3(a.units), dim3(kFinThreads), key_lds, s, a);
 }
 
-template <int DT, int D>
-void launch_block_simple(const BlockArgs& a, hipStream_t s) {
-  {
-    ProfScope ps(kProfBlockAttend, s);
-    hipLaunchKernelGGL((block_attend_simple<DT, D>), dim3(a.queries, a.units), dim3(256), 0, s, a);
-  }
-  launch_block_tail<DT, D>(a, s);
+template <int DT, int D, int QMAX>
+hipError_t launch_block_shared_q(const BlockArgs& a, hipStream_t s) {
+  const size_t lds = SharedTile<D>::lds_bytes(QMAX);  // 37 to 114 KiB: the limit is set on every call
+  const void* fn = reinterpret_cast<const void*>(block_attend_shared<DT, D, QMAX>);
+  if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
+    return hipErrorInvalidValue;
+  hipLaunchKernelGGL((block_attend_shared<DT, D, QMAX>), dim3(a.splits, a.units), dim3(256), lds, s, a);
+  return hipSuccess;
 }
 
-// dtype / head_dim other than bf16 / 128 take the vector-ALU attention (a.splits must then be 1)
+template <int DT, int D>
+hipError_t launch_block_shared(const BlockArgs& a, hipStream_t s) {
+  {
+    ProfScope ps(kProfBlockAttend, s);
+    const hipError_t e = a.queries <= 8    ? launch_block_shared_q<DT, D, 8>(a, s)
+                         : a.queries <= 16 ? launch_block_shared_q<DT, D, 16>(a, s)
+                         : a.queries <= 32 ? launch_block_shared_q<DT, D, 32>(a, s)
+                                           : launch_block_shared_q<DT, D, kMaxBlock>(a, s);
+    if (e != hipSuccess) return e;
+  }
+  launch_block_tail<DT, D>(a, s);
+  return hipSuccess;
+}
+
+// dtype / head_dim other than bf16 / 128 take the vector-ALU attention
 hipError_t launch_block(int dtype, int head_dim, const BlockArgs& args, hipStream_t s) {
   BlockArgs a = args;
   // A single-token step on the matrix-core path needs no block_prepare.
@@ -620,14 +818,12 @@ hipError_t launch_block(int dtype, int head_dim, const BlockArgs& args, hipStrea
       else hipLaunchKernelGGL(block_attend<1>, dim3(a.splits, a.units), dim3(kAttThreads), kAttLds, s, a);
     }
     launch_block_tail<kBF16, 128>(a, s);
-  } else if (dtype == kBF16 && head_dim == 64) {
-    launch_block_simple<kBF16, 64>(a, s);
-  } else if (dtype == kF32 && head_dim == 64) {
-    launch_block_simple<kF32, 64>(a, s);
-  } else if (dtype == kF32 && head_dim == 128) {
-    launch_block_simple<kF32, 128>(a, s);
   } else {
-    return hipErrorInvalidValue;
+    hipError_t e = hipErrorInvalidValue;
+    if (dtype == kBF16 && head_dim == 64) e = launch_block_shared<kBF16, 64>(a, s);
+    else if (dtype == kF32 && head_dim == 64) e = launch_block_shared<kF32, 64>(a, s);
+    else if (dtype == kF32 && head_dim == 128) e = launch_block_shared<kF32, 128>(a, s);
+    if (e != hipSuccess) return e;
   }
   if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
   return hipSuccess;

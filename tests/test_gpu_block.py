@@ -87,11 +87,16 @@ def test_single_token_blocks_fill_then_evict_with_recency_bias():
 
 
 @pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 64), ("f32", 128)])
-def test_block_steps_on_the_vector_path_for_other_dtypes_and_head_dims(dtype, d):
-    """Shapes the matrix-core kernel is not built for take one vector-ALU pass per query row: same step, same
-    parity bar.  From a compressed cache and with a unit that is still filling up; ragged block sizes."""
+def test_block_steps_on_the_vector_path_for_other_dtypes_and_head_dims(dtype, d, monkeypatch):
+    """Shapes the matrix-core kernel is not built for take the vector-ALU kernel (K and V streamed once for all query
+    rows; its 8 / 16 / 32 / 64-row instantiations all run here): same step, same parity bar.  From a compressed cache
+    and with a unit that is still filling up; ragged block sizes."""
     drive(3, d, 96, 10, [150, 96, 40], [8, 1, 32, 5, 16, 32, 3, 64, 47], seed=140 + d, tag=f"simple-{dtype}-{d}", dtype=dtype)
     drive(2, d, 64, 8, [100, 64], [4, 32], seed=150 + d, recency=True, tag=f"simple-recency-{dtype}-{d}", dtype=dtype)
+    # eight splits of 128 slots over a budget that is no multiple of the 64-slot tile; a unit that stays far from full
+    # ... with the non-temporal loads that caches larger than the last-level cache get
+    monkeypatch.setenv("ROCO_STREAMING_LOADS", "1")
+    drive(2, d, 1000, 24, [1100, 30], [64, 7, 16, 33, 2], seed=160 + d, tag=f"simple-splits-{dtype}-{d}", dtype=dtype)
 
 
 def test_block_steps_fill_an_empty_cache_then_start_evicting():

@@ -595,6 +595,55 @@ def main():
             for v in blockwise.values():
                 v["speedup_vs_block_1"] = v["tokens_per_s"] / blockwise["1"]["tokens_per_s"]
 
+        # The same table for the shapes the matrix cores do not take (workload 1's fp32 / head_dim 64), at workload 3's
+        # bytes: 512 units x 2048 slots of fp32 / d=64 on a full cache with seeded Gaussian rows and valid statistics.
+        blockwise_f32 = {}
+        p32 = roco.RocoParams(U, 64, B, s, roco.ROCO_F32)
+        c32 = roco.alloc_cache(p32)
+        gen32 = torch.Generator(device="cuda").manual_seed(args.seed)
+        for i0 in range(0, U, 64):
+            c32.K[i0:i0 + 64] = torch.randn((min(64, U - i0), B, 64), device="cuda", generator=gen32)
+            c32.V[i0:i0 + 64] = torch.randn((min(64, U - i0), B, 64), device="cuda", generator=gen32)
+        cnt32 = torch.randint(1, 500, (U, B), device="cuda", generator=gen32).float()
+        acc32 = torch.rand((U, B), device="cuda", generator=gen32) * cnt32 / B
+        c32.stats[:, 0] = acc32
+        c32.stats[:, 1] = acc32 * acc32 / cnt32 * (1 + torch.rand((U, B), device="cuda", generator=gen32))
+        c32.stats[:, 2] = cnt32
+        c32.n_used.fill_(B)
+        c32.pos.copy_(torch.arange(B, device="cuda", dtype=torch.int32)[None].expand(U, B))
+        ws_d32 = torch.empty(roco.decode_workspace_bytes(p32), dtype=torch.uint8, device="cuda")
+        roco.roco_select_victims(p32, c32.stats, c32.pos, c32.n_used, c32.next_slot, ws_d32)
+        torch.cuda.synchronize()
+        snap32 = [t.clone() for t in (c32.stats, c32.pos, c32.n_used, c32.next_slot)]  # K / V rows only get overwritten
+        n32 = 64
+        for bsz in [b_ for b_ in (1, 8, 64) if str(b_) in blockwise]:
+            nb = n32 // bsz
+            tq = torch.randn((nb, U, bsz, 64), device="cuda", generator=gen32)
+            tk = torch.randn((nb, U, bsz, 64), device="cuda", generator=gen32)
+            tv = torch.randn((nb, U, bsz, 64), device="cuda", generator=gen32)
+            ws_b = torch.empty(roco.block_workspace_bytes(p32, bsz), dtype=torch.uint8, device="cuda")
+            bout = torch.empty((U, bsz, 64), dtype=torch.float32, device="cuda")
+            qp0 = [torch.full((U,), B + i * bsz, dtype=torch.int32, device="cuda") for i in range(nb)]
+            times = []
+            for rep in range(2):
+                for t, sn in zip((c32.stats, c32.pos, c32.n_used, c32.next_slot), snap32):
+                    t.copy_(sn)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for i in range(nb):
+                    roco.roco_encode_block(p32, bsz, tq[i], tk[i], tv[i], qp0[i], c32.K, c32.V, c32.stats, c32.pos,
+                                           c32.n_used, c32.next_slot, bout, None, None, ws_b, stream=stream)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                times.append(e0.elapsed_time(e1))
+            ms = min(times)
+            blockwise_f32[str(bsz)] = {"tokens_per_s": cfg.batch * n32 / (ms * 1e-3), "ms_per_block_step": ms / nb}
+            del tq, tk, tv, ws_b
+        if "1" in blockwise_f32:
+            for v in blockwise_f32.values():
+                v["speedup_vs_block_1"] = v["tokens_per_s"] / blockwise_f32["1"]["tokens_per_s"]
+        del c32, snap32, ws_d32, cnt32, acc32
+
         # Grouped-query attention: the same 32 query heads per sequence over 32 / g key/value heads (g = 4 is the
         # Zephyr-style shape); one token per step.  The start state of each key/value head is a compressed cache.
         gqa = {}
@@ -736,7 +785,11 @@ def main():
     if blockwise is not None:
         result["blockwise_encode"] = {"workload": f"{n_tok} tokens per sequence encoded on the full B={B} cache in "
                                                   "blocks of b (roco_encode_block), batch 16 x 32 heads",
-                                      "by_block_size": blockwise}
+                                      "by_block_size": blockwise,
+                                      "fp32_head_dim_64": {
+                                          "workload": f"64 tokens per sequence in blocks of b on a full B={B} cache of fp32 / "
+                                                      "head_dim 64 rows (vector-ALU kernel), same units and bytes",
+                                          "by_block_size": blockwise_f32}}
         result["gqa"] = {"workload": f"32 query heads over 32/g key/value heads, batch 16: the {L}-token prompt compressed "
                                      f"to B={B} (roco_prefill_compress_gqa), then one token per step on the full "
                                      "cache (roco_decode_step_gqa)", "by_group_size": gqa}

@@ -15,6 +15,7 @@
 //                   the lane; one or two tiles of 32 query rows, every K and V^T fragment read from LDS feeding
 //                   both), stores the base-2 logits, keeps an online softmax per query and accumulates
 //                   O^T = V^T . P^T with V^T fragments from the LDS transpose read.
+//   block_attend_shared : the same for fp32 and head_dim 64, on the vector ALUs (see there).
 //   block_finish  : one workgroup per unit.  Merges the partials per query, writes the outputs, adds the
 //                   statistics of all rows to every slot and chooses the victim a following single-token step
 //                   would take.

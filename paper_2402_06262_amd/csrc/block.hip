@@ -633,7 +633,9 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void block_attend_shared(Bl
 // One workgroup per unit: it walks all slots of the unit two per thread and sweep, keeps the ranking keys in LDS and
 // chooses the next victim itself.  (Spreading the update over slot chunks and selecting in a launch of its own
 // measured slower for every number of query rows: the extra launch costs more than the longer sweep.)
-template <int DT, int D>
+// CHUNKED: the logits of four query rows are loaded at a time (chosen by the host where it measured faster: grouped
+// queries, and more than 32 rows).
+template <int DT, int D, bool CHUNKED>
 __global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
   constexpr int NT = kFinThreads;
   constexpr int kSlots = 2 * NT;  // slots per sweep
@@ -708,15 +710,7 @@ __global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
 #pragma unroll
   for (int e = 0; e < 2; ++e)
     if (j + e == fresh) { s1[e] = 0.0f; s2[e] = 0.0f; sc[e] = 0.0f; }  // the new token starts from zero
-  for (int t = 0; t < a.block; ++t) {
-    float mean[2] = {0.0f, 0.0f};  // sum over the token's query heads of p
-    for (int h = 0; h < heads; ++h) {
-      const int q = t * heads + h;
-      const float2 zz = *reinterpret_cast<const float2*>(z + static_cast<size_t>(q) * B + j);
-      const float M = Mq[q], inv = invq[q];
-      mean[0] += fast_exp2(zz.x - M) * inv;
-      mean[1] += fast_exp2(zz.y - M) * inv;
-    }
+  auto book = [&](const float* mean, int t) {  // token t of the block has attended: its head-mean goes to the slots
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
       if (j + e < n && biv[e] <= t) {  // older tokens have index -1: attended by every row
@@ -724,6 +718,45 @@ __global__ __launch_bounds__(kFinThreads) void block_finish(BlockArgs a) {
         s1[e] += p;
         s2[e] = a.pol.second_statistic(s2[e], p, static_cast<float>(n - a.block + t + 1));  // what row t attended
         sc[e] += 1.0f;
+      }
+    }
+  };
+  if (!CHUNKED) {
+    for (int t = 0; t < a.block; ++t) {
+      float mean[2] = {0.0f, 0.0f};  // sum over the token's query heads of p
+      for (int h = 0; h < heads; ++h) {
+        const int q = t * heads + h;
+        const float2 zz = *reinterpret_cast<const float2*>(z + static_cast<size_t>(q) * B + j);
+        const float M = Mq[q], inv = invq[q];
+        mean[0] += fast_exp2(zz.x - M) * inv;
+        mean[1] += fast_exp2(zz.y - M) * inv;
+      }
+      book(mean, t);
+    }
+  } else {
+    // The query rows (token-major, a token's heads side by side) are taken four at a time, so that four logit
+    // loads are in flight per thread instead of one.
+    float mean[2] = {0.0f, 0.0f};  // sum over the query heads of the token under way of p
+    int t = 0, h = 0;
+    for (int q0 = 0; q0 < nq; q0 += 4) {
+      float2 zz[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        zz[i] = *reinterpret_cast<const float2*>(z + static_cast<size_t>(min(q0 + i, nq - 1)) * B + j);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int q = q0 + i;
+        if (q < nq) {
+          const float M = Mq[q], inv = invq[q];
+          mean[0] += fast_exp2(zz[i].x - M) * inv;
+          mean[1] += fast_exp2(zz[i].y - M) * inv;
+          if (++h == heads) {  // the token's last head
+            book(mean, t);
+            mean[0] = mean[1] = 0.0f;
+            h = 0;
+            ++t;
+          }
+        }
       }
     }
   }
@@ -761,8 +794,14 @@ template <int DT, int D>
 void launch_block_tail(const BlockArgs& a, hipStream_t s) {
   ProfScope ps(kProfBlockFinish, s);
   const size_t key_lds = key_lds_bytes(a.B);
-  (void)allow_key_lds(reinterpret_cast<const void*>(block_finish<DT, D>), key_lds);  // if refused, the launch fails and is reported
-  hipLaunchKernelGGL((block_finish<DT, D>), dim3(a.units), dim3(kFinThreads), key_lds, s, a);
+  // (if the limit is refused, the launch fails and is reported)
+  if (a.heads > 1 || a.queries > 32) {
+    (void)allow_key_lds(reinterpret_cast<const void*>(block_finish<DT, D, true>), key_lds);
+    hipLaunchKernelGGL((block_finish<DT, D, true>), dim3(a.units), dim3(kFinThreads), key_lds, s, a);
+  } else {
+    (void)allow_key_lds(reinterpret_cast<const void*>(block_finish<DT, D, false>), key_lds);
+    hipLaunchKernelGGL((block_finish<DT, D, false>), dim3(a.units), dim3(kFinThreads), key_lds, s, a);
+  }
 }
 
 template <int DT, int D, int QMAX>

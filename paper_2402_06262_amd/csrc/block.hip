@@ -445,16 +445,16 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void block_attend_shared(Bl
   const float rb = a.recency_bias_log2;
   const int qp0 = a.qpos0[u];
 
-  for (int idx = tid; idx < nq * G::LPR; idx += 256) {  // the step's queries, scaled, as fp32
+  for (int idx = tid; idx < QMAX * G::LPR; idx += 256) {  // the step's queries, scaled, as fp32; zeros beyond them
     const int q = idx / G::LPR, c = idx % G::LPR;
     float f[G::EPL];
-    unpack16<DT>(load16(static_cast<const char*>(a.q) + (static_cast<size_t>(u) * nq + q) * G::ROW_BYTES + c * 16), f);
+    unpack16<DT>(load16(static_cast<const char*>(a.q) + (static_cast<size_t>(u) * nq + min(q, nq - 1)) * G::ROW_BYTES + c * 16), f);
 #pragma unroll
-    for (int e = 0; e < G::EPL; ++e) Qs[q * D + c * G::EPL + e] = f[e] * a.scale_log2;
+    for (int e = 0; e < G::EPL; ++e) Qs[q * D + c * G::EPL + e] = q < nq ? f[e] * a.scale_log2 : 0.0f;
   }
 
   const int rg = lane % RG, qs = lane / RG;
-  int qrow[QL];        // this lane's query rows (may lie beyond the step's)
+  int qrow[QL];        // this lane's query rows (may lie beyond the step's: those compute on zeros and store nothing)
   float m[QL], l[QL];  // their online softmax (the same in every lane of the group)
 #pragma unroll
   for (int jq = 0; jq < QL; ++jq) {

@@ -515,7 +515,8 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void block_attend_shared(Bl
       __syncthreads();  // the tile (and, the first time, the queries) are in LDS
       if (t + PF < n_tiles) fetch(t + PF, pk[j], pv[j], st_bidx[j], st_pos[j]);
 
-      // ---- scores: QS slots x QL query rows per lane
+      // ---- scores: QS slots x QL query rows per lane (a wave whose first query row lies beyond the step's has none)
+      if (wave < nq) {
       float part[QS][QL];
 #pragma unroll
       for (int i = 0; i < QS; ++i)
@@ -577,9 +578,11 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void block_attend_shared(Bl
         m[jq] = m_new;
         if (live && rg == 0) al[q] = alpha;
       }
+      }
       __syncthreads();  // the tile's probabilities are in LDS
 
-      // ---- O[q][d] = O[q][d] alpha[q] + sum_r P[q][r] V[r][d]
+      // ---- O[q][d] = O[q][d] alpha[q] + sum_r P[q][r] V[r][d] (a wave whose first query row is beyond the step's: idle)
+      if ((wave * kWave) / DQ < nq) {
 #pragma unroll
       for (int k = 0; k < OQ; ++k) {
         const int q = og + NG * k;
@@ -608,6 +611,7 @@ __global__ __launch_bounds__(256, (D == 64 ? 2 : 1)) void block_attend_shared(Bl
             o[k].z = fmaf(p4.w, v3.z, o[k].z); o[k].w = fmaf(p4.w, v3.w, o[k].w);
           }
         }
+      }
       }
       __syncthreads();  // everybody is done with the tile before the next one overwrites it
     }

@@ -190,3 +190,59 @@ def test_block_steps_at_the_serving_shape_all_512_units():
             P.check_cache_unit(host, k, states[k], what=f"[cfg3-block] block {i} unit {u}")
     print("[cfg3-block] ties", ties, flush=True)
     P.assert_few_ties(ties, "cfg3-block")
+
+
+def test_block_steps_of_fp32_head_dim_64_at_the_benchmark_shape():
+    """The shape bench.py times for the vector-ALU block kernel: 512 units x 2048 slots of fp32 / head_dim 64 (the
+    non-temporal loads of a cache above the last-level cache's size, one split per unit).  Blocks of 64 fill the
+    empty caches, then blocks of 64 / 16 / 8 / 1 / 33 evict (every instantiation of the kernel); sampled units in
+    lock-step with the oracle, any-size properties on every unit."""
+    import paper_2402_06262_amd as roco
+    P = _P()
+    U, d, B, s, dtype = 512, 64, 2048, 64, "f32"
+    blocks = [64] * 32 + [64, 16, 8, 1, 33]
+    T = sum(blocks)
+    sc = 1.0 / math.sqrt(d)
+    sess = P.make_session(U, d, B, s, dtype)
+    c, p = sess.cache, sess.params
+    gen = torch.Generator(device="cuda").manual_seed(4242)
+    Q = torch.randn((U, T, d), device="cuda", generator=gen) + 0.25
+    K = torch.randn((U, T, d), device="cuda", generator=gen)
+    V = torch.randn((U, T, d), device="cuda", generator=gen)
+    sample = [0, 201, 511]
+    sidx = torch.tensor(sample, device="cuda")
+    hQ, hK, hV = (P.to_host(x[sidx]).astype(np.float64) for x in (Q, K, V))
+    states = [orc.CacheState(np.zeros((B, d)), np.zeros((B, d)), np.zeros(B), np.zeros(B), np.zeros(B),
+                             np.full(B, -1, dtype=np.int64), 0) for _ in sample]
+    ws = torch.empty(roco.block_workspace_bytes(p, 64), dtype=torch.uint8, device="cuda")
+    ties = P.TieCount()
+    t = 0
+    for i, b in enumerate(blocks):
+        print(f"[f32-d64-block] block {i} of {b} at row {t}", flush=True)
+        out = torch.empty((U, b, d), dtype=torch.float32, device="cuda")
+        es = torch.empty((U, b), dtype=torch.int32, device="cuda"); ep = torch.empty_like(es)
+        qp0 = torch.full((U,), t, dtype=torch.int32, device="cuda")
+        roco.roco_encode_block(p, b, Q[:, t:t + b].contiguous(), K[:, t:t + b].contiguous(), V[:, t:t + b].contiguous(), qp0,
+                               c.K, c.V, c.stats, c.pos, c.n_used, c.next_slot, out, es, ep, ws)
+        torch.cuda.synchronize()
+        n_after = min(B, t + b)
+        assert bool((c.n_used == n_after).all()) and bool(torch.isfinite(out).all())
+        if t >= B:  # every token of the block took over an evicted token's slot, in ascending slot order
+            assert bool((es >= 0).all()) and bool((es < B).all())
+            if b > 1:
+                assert bool((es[:, 1:] > es[:, :-1]).all())
+            assert bool((torch.gather(c.pos, 1, es.long()) == (qp0[:, None] + torch.arange(b, device="cuda")[None])).all())
+        else:
+            assert bool((es == -1).all())
+        g_out, g_slot, g_pos = P.to_host(out[sidx]), P.to_host(es[sidx]), P.to_host(ep[sidx])
+        for k, u in enumerate(sample):
+            ties += P.lockstep_block_unit(states[k], k, g_out, g_slot, g_pos, hQ[k, t:t + b], hK[k, t:t + b],
+                                          hV[k, t:t + b], t, s, sc, dtype, what=f"[f32-d64-block] block {i} unit {u}")
+        if t >= B or i % 8 == 7:  # cache contents and statistics: every block once full, every eighth while filling
+            host = dict(K=P.to_host(c.K[sidx]), V=P.to_host(c.V[sidx]), stats=P.to_host(c.stats[sidx]),
+                        pos=P.to_host(c.pos[sidx]), n_used=P.to_host(c.n_used[sidx]))
+            for k, u in enumerate(sample):
+                P.check_cache_unit(host, k, states[k], what=f"[f32-d64-block] block {i} unit {u}")
+        t += b
+    print("[f32-d64-block] ties", ties, flush=True)
+    P.assert_few_ties(ties, "f32-d64-block")
